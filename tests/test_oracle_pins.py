@@ -1,0 +1,743 @@
+"""Pins of the CPU oracle against things other than itself: published
+known answers, closed forms, invariants, brute force, library routines.
+None of these tests needs a GPU."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2104_06272_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny(kind, hidden=(4, 4), B=4, T=5, **kw):
+    if kind == "catch":
+        env = dict(kind="catch", rows=kw.get("rows", 4), cols=kw.get("cols", 3), max_steps=0)
+        cfg = W.get("catch_small")
+    elif kind == "pendulum":
+        env = dict(kind="pendulum", rows=0, cols=0, max_steps=kw.get("max_steps", 200))
+        cfg = W.get("pendulum_8192")
+    else:
+        env = dict(kind="maze", rows=kw.get("rows", 16), cols=kw.get("cols", 16),
+                   max_steps=kw.get("max_steps", 256), p_wall=kw.get("p_wall", 0.2))
+        cfg = W.get("maze_16384")
+    cfg["env"] = env
+    cfg["net"]["hidden"] = list(hidden)
+    cfg["net"]["dtype"] = kw.get("dtype", "fp32")
+    if "lam" in kw:
+        cfg["net"]["lambda"] = kw["lam"]
+    cfg["B"], cfg["T"] = B, T
+    return cfg
+
+
+# --------------------------------------------------------------------------- RNG
+def test_philox_known_answers(orc):
+    rows = [l.split() for l in open(os.path.join(GOLD, "philox4x32_10_kat.txt")) if not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        assert list(orc.philox(v[0:4], v[4:6])) == v[6:10]
+
+
+def test_uniform_and_bounded_statistics(orc):
+    L = orc.lib()
+    words = np.concatenate([orc.draw(7, i, 0, 0) for i in range(5000)])
+    u = np.array([L.orc_u01(int(w)) for w in words])
+    assert u.min() >= 0.0 and u.max() < 1.0
+    assert abs(u.mean() - 0.5) < 4 * math.sqrt(1 / 12 / u.size)
+    assert abs(u.var() - 1 / 12) < 0.003
+    assert L.orc_u01(0xFFFFFFFF) == 1.0 - 2.0 ** -24 and L.orc_u01(0) == 0.0
+    assert L.orc_u01_plus(0xFFFFFFFF) == 1.0 and L.orc_u01_plus(0) == 2.0 ** -24
+    k = np.array([L.orc_bounded(int(w), 5) for w in words])
+    assert k.min() == 0 and k.max() == 4
+    cnt = np.bincount(k, minlength=5)
+    chi2 = ((cnt - k.size / 5) ** 2 / (k.size / 5)).sum()
+    assert chi2 < 18.5          # chi-square, 4 dof, p = 0.001
+    assert L.orc_bounded(0xFFFFFFFF, 5) == 4 and L.orc_bounded(0, 5) == 0
+
+
+def test_counter_draws_are_independent_of_batch(orc):
+    # same (seed, env, t) gives the same draw whatever else exists
+    a = orc.Oracle(tiny("catch", B=3), seed=11)
+    b = orc.Oracle(tiny("catch", B=9), seed=11)
+    assert np.array_equal(a.state_i, b.state_i[:3])
+
+
+# ----------------------------------------------------------------------- detmath
+def _rel(a, b):
+    return np.abs(a.astype(np.float64) - b) / np.maximum(np.abs(b), 1e-300)
+
+
+def test_det_exp(orc):
+    x = np.linspace(-86.9, 87.9, 200001).astype(np.float32)
+    y = orc.f32fun("orc_exp")(x)
+    assert _rel(y, np.exp(x.astype(np.float64))).max() < 3e-7
+    f = orc.lib().orc_exp
+    assert f(0.0) == 1.0
+    assert f(-200.0) == f(-87.0) and f(-87.0) > 0.0
+    # monotone on a fine grid near zero (softmax ordering)
+    z = orc.f32fun("orc_exp")(np.linspace(-1, 0, 5001).astype(np.float32))
+    assert np.all(np.diff(z.astype(np.float64)) >= 0)
+
+
+def test_det_log(orc):
+    x = np.concatenate([np.linspace(2.0 ** -24, 1.0, 100001), np.logspace(-30, 30, 20001)]).astype(np.float32)
+    y = orc.f32fun("orc_log")(x).astype(np.float64)
+    ref = np.log(x.astype(np.float64))
+    err = np.abs(y - ref)
+    assert np.all(err <= 3e-7 * np.abs(ref) + 1e-7)
+    assert orc.lib().orc_log(1.0) == 0.0
+
+
+def test_det_sin_cos(orc):
+    pi_f = float(np.float32(math.pi))
+    x = np.linspace(-pi_f, pi_f, 200001).astype(np.float32)
+    s = orc.f32fun("orc_sin")(x).astype(np.float64)
+    c = orc.f32fun("orc_cos")(x).astype(np.float64)
+    xd = x.astype(np.float64)
+    assert np.abs(s - np.sin(xd)).max() < 2e-7
+    assert np.abs(c - np.cos(xd)).max() < 2e-7
+    big = np.abs(np.sin(xd)) > 1e-2
+    assert _rel(s[big], np.sin(xd)[big]).max() < 4e-7
+    L = orc.lib()
+    assert L.orc_sin(0.0) == 0.0 and L.orc_cos(0.0) == 1.0
+    xs = x[::97]
+    assert np.array_equal(orc.f32fun("orc_sin")(-xs), -orc.f32fun("orc_sin")(xs))
+    assert np.array_equal(orc.f32fun("orc_cos")(-xs), orc.f32fun("orc_cos")(xs))
+
+
+def test_det_cos2pi(orc):
+    u = (np.arange(0, 1 << 24, 257, dtype=np.int64) * 2.0 ** -24).astype(np.float32)
+    y = orc.f32fun("orc_cos2pi")(u).astype(np.float64)
+    assert np.abs(y - np.cos(2 * np.pi * u.astype(np.float64))).max() < 3e-7
+    L = orc.lib()
+    assert L.orc_cos2pi(0.0) == 1.0 and L.orc_cos2pi(0.5) == -1.0
+    assert L.orc_cos2pi(0.25) == 0.0 and L.orc_cos2pi(0.75) == 0.0
+
+
+def test_det_tanh(orc):
+    x = np.concatenate([np.linspace(-12, 12, 100001), np.linspace(-0.3, 0.3, 50001),
+                        np.logspace(-20, -1, 2001)]).astype(np.float32)
+    y = orc.f32fun("orc_tanh")(x)
+    ref = np.tanh(x.astype(np.float64))
+    nz = x != 0
+    assert _rel(y[nz], ref[nz]).max() < 4e-7
+    assert np.abs(y.astype(np.float64)).max() <= 1.0
+    assert orc.lib().orc_tanh(0.0) == 0.0
+    assert np.array_equal(orc.f32fun("orc_tanh")(-x), -y)
+
+
+def test_bf16_round(orc):
+    import torch
+    x = np.random.default_rng(0).standard_normal(20000).astype(np.float32) * 37
+    x = np.concatenate([x, np.array([1.0, 1.00390625, 1.005859375, 1.001953125, 0.0], np.float32)])
+    mine = orc.f32fun("orc_bf16_round")(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()   # library rounding
+    assert np.array_equal(mine, ref)
+
+
+# -------------------------------------------------------------------------- Catch
+def test_catch_episodes_and_returns(orc):
+    cfg = W.get("catch_small", B=200, T=45)
+    o = orc.Oracle(cfg, seed=3)
+    o.rollout()
+    done, rew = o.tr_done, o.tr_reward
+    # every episode lasts rows-1 = 9 steps: dones exactly at t = 8, 17, 26, ...
+    t_idx = np.arange(45)[:, None]
+    assert np.array_equal(done.astype(bool), np.broadcast_to(t_idx % 9 == 8, done.shape))
+    # reward is +-1 exactly when done and exactly 0 otherwise
+    assert np.all(np.isin(rew[done == 1], (-1.0, 1.0)))
+    assert np.all(rew[done == 0] == 0.0)
+    ep_ret = rew.reshape(5, 9, -1).sum(1)
+    assert np.all(np.isin(ep_ret, (-1.0, 1.0)))
+    # observed states: ball row = t mod 9 (never the bottom row), ball column fixed within an episode
+    by = o.tr_state_i[:45, :, 1]
+    assert np.array_equal(by, np.broadcast_to(t_idx % 9, by.shape))
+    bx = o.tr_state_i[:45, :, 0].reshape(5, 9, -1)
+    assert np.all(bx == bx[:, :1])
+    # paddle moves by a-1 with clamping; it restarts in the middle column
+    px = o.tr_state_i[:, :, 2]
+    a = o.tr_action
+    for t in range(45):
+        want = np.clip(px[t] + a[t] - 1, 0, 4)
+        if t % 9 == 8:
+            want = np.full_like(want, 2)
+        assert np.array_equal(px[t + 1], want)
+    # reward sign: caught iff the paddle ends under the ball
+    for t in range(8, 45, 9):
+        final_px = np.clip(px[t] + a[t] - 1, 0, 4)
+        assert np.array_equal(rew[t] > 0, final_px == o.tr_state_i[t, :, 0])
+
+
+def test_catch_observation(orc):
+    o = orc.Oracle(W.get("catch_small", B=50, T=20), seed=5)
+    o.rollout()
+    for b in range(50):
+        x = o.observe(b).reshape(10, 5)
+        bx, by, px, _ = o.state_i[b]
+        want = np.zeros((10, 5), np.float32)
+        want[by, bx] = 1
+        want[9, px] = 1
+        assert np.array_equal(x, want) and x.sum() == 2
+
+
+def test_catch_scripted_policies(orc):
+    # always "stay": caught iff the ball column is the middle one; ball column uniform
+    B = 4000
+    o = orc.Oracle(W.get("catch_small", B=B, T=9), seed=8)
+    bx0 = o.state_i[:, 0].copy()
+    rets = np.zeros(B)
+    for b in range(B):
+        for t in range(9):
+            r, d = o.env_step(b, action=1, t=t)
+            rets[b] += r
+            assert d == (t == 8)
+    assert np.array_equal(rets > 0, bx0 == 2)
+    cnt = np.bincount(bx0, minlength=5)
+    assert ((cnt - B / 5) ** 2 / (B / 5)).sum() < 18.5
+    # zero weights -> uniform policy: P(catch) = 1/5 exactly in law, mean return -> -0.6,
+    # and the paddle's final column follows the 9-step clamped random walk from column 2
+    cfg = W.get("catch_small", B=B, T=9)
+    o = orc.Oracle(cfg, seed=9)
+    o.theta[:] = 0
+    o.rollout()
+    rets = o.tr_reward.sum(0)
+    se = math.sqrt(0.2 * 0.8 * 4 / B)
+    assert abs(rets.mean() + 0.6) < 4 * se
+    law = [Fraction(0)] * 5
+    law[2] = Fraction(1)
+    for _ in range(9):
+        nxt = [Fraction(0)] * 5
+        for c, p in enumerate(law):
+            for mv in (-1, 0, 1):
+                nxt[min(4, max(0, c + mv))] += p / 3
+        law = nxt
+    assert law[0] == Fraction(1304, 6561) and law[1] == Fraction(3946, 19683) and law[2] == Fraction(3967, 19683)
+    final_px = np.clip(o.tr_state_i[8, :, 2] + o.tr_action[8] - 1, 0, 4)
+    cnt = np.bincount(final_px, minlength=5)
+    exp = np.array([float(p) for p in law]) * B
+    assert ((cnt - exp) ** 2 / exp).sum() < 18.5
+
+
+# ----------------------------------------------------------------------- Pendulum
+def _pend_ref(th, thd, a):
+    """closed-form semi-implicit Euler update in float64 with libm"""
+    u = min(2.0, max(-2.0, 2.0 * a))
+    r = -(th * th + 0.1 * thd * thd + 0.001 * u * u)
+    nthd = thd + (15.0 * math.sin(th) + 3.0 * u) * 0.05
+    nthd = min(8.0, max(-8.0, nthd))
+    nth = th + nthd * 0.05
+    nth = (nth + math.pi) % (2 * math.pi) - math.pi
+    return nth, nthd, r
+
+
+def test_pendulum_step_vs_closed_form(orc):
+    o = orc.Oracle(tiny("pendulum", B=1, T=4), seed=1)
+    rng = np.random.default_rng(4)
+    for _ in range(3000):
+        th = np.float32(rng.uniform(-math.pi, math.pi))
+        thd = np.float32(rng.uniform(-8, 8))
+        a = np.float32(rng.uniform(-1, 1))
+        o.state_f[0] = (th, thd)
+        o.state_i[0, 0] = 0
+        r, d = o.env_step(0, action_f=float(a))
+        nth, nthd, rr = _pend_ref(float(th), float(thd), float(a))
+        dth = (float(o.state_f[0, 0]) - nth + math.pi) % (2 * math.pi) - math.pi
+        assert abs(dth) < 1e-5 and abs(float(o.state_f[0, 1]) - nthd) < 1e-5 and abs(r - rr) < 1e-5
+        assert d == 0
+        assert -float(np.float32(math.pi)) <= o.state_f[0, 0] < float(np.float32(math.pi))
+        assert abs(o.state_f[0, 1]) <= 8.0
+        assert r <= 0 and r >= -(math.pi ** 2 + 6.4 + 0.004) - 1e-4
+
+
+def test_pendulum_fixed_point_and_episode_length(orc):
+    o = orc.Oracle(tiny("pendulum", B=2, T=4, max_steps=200), seed=2)
+    o.state_f[0] = (0.0, 0.0)
+    for t in range(199):
+        r, d = o.env_step(0, action_f=0.0, t=t)
+        assert r == 0.0 and d == 0 and tuple(o.state_f[0]) == (0.0, 0.0)
+    r, d = o.env_step(0, action_f=0.0, t=199)
+    assert d == 1 and o.state_i[0, 0] == 0            # 200th step ends the episode and resets
+    th, thd = o.state_f[0]
+    assert -math.pi - 1e-6 <= th <= math.pi + 1e-6 and -1 <= thd < 1
+
+
+def test_pendulum_init_distribution_and_obs(orc):
+    B = 4000
+    o = orc.Oracle(tiny("pendulum", B=B, T=2), seed=6)
+    th, thd = o.state_f[:, 0].astype(np.float64), o.state_f[:, 1].astype(np.float64)
+    assert th.min() >= -math.pi - 1e-6 and th.max() <= math.pi + 1e-6
+    assert abs(th.mean()) < 4 * (2 * math.pi / math.sqrt(12)) / math.sqrt(B)
+    assert abs(th.var() - (2 * math.pi) ** 2 / 12) < 0.25
+    assert thd.min() >= -1 and thd.max() < 1 and abs(thd.mean()) < 4 * (2 / math.sqrt(12)) / math.sqrt(B)
+    for b in range(0, B, 131):
+        x = o.observe(b).astype(np.float64)
+        assert abs(x[0] - math.cos(th[b])) < 3e-7 and abs(x[1] - math.sin(th[b])) < 3e-7 and x[2] == thd[b]
+
+
+def test_pendulum_energy_drift_without_torque(orc):
+    # with u = 0 and no clipping, E = thd^2/2 + 15 cos(th) is conserved by the flow; the
+    # symplectic Euler map keeps it within O(dt) of its initial value
+    o = orc.Oracle(tiny("pendulum", B=1, T=2, max_steps=100000), seed=1)
+    o.state_f[0] = (2.0, 0.5)
+    e0 = 0.5 * 0.5 ** 2 / 2 * 2 + 15 * math.cos(2.0)
+    worst = 0.0
+    for t in range(2000):
+        o.env_step(0, action_f=0.0, t=t)
+        th, thd = (float(v) for v in o.state_f[0])
+        worst = max(worst, abs(0.5 * thd * thd + 15 * math.cos(th) - e0))
+    assert worst < 0.05 * 15 * 3          # O(dt) band, dt = 0.05
+
+
+# --------------------------------------------------------------------------- Maze
+def _flood(walls, n=16):
+    free = ~walls
+    seen = np.zeros_like(free)
+    seen[0, 0] = True
+    while True:
+        grow = seen.copy()
+        grow[1:] |= seen[:-1]; grow[:-1] |= seen[1:]; grow[:, 1:] |= seen[:, :-1]; grow[:, :-1] |= seen[:, 1:]
+        grow &= free
+        if np.array_equal(grow, seen):
+            return seen
+        seen = grow
+
+
+def _walls(o, b, n=16):
+    bits = np.unpackbits(o.walls[b].view(np.uint8), bitorder="little")[: n * n]
+    return bits.reshape(n, n).astype(bool)
+
+
+def test_maze_generation(orc):
+    B = 300
+    o = orc.Oracle(tiny("maze", hidden=(8,), B=B, T=2), seed=4)
+    dens = []
+    for b in range(B):
+        w = _walls(o, b)
+        assert not w[0, 0] and not w[15, 15]
+        assert _flood(w)[15, 15]                     # independent flood fill reaches the goal
+        dens.append(w.mean())
+    # accepted mazes are a connected subset, so density sits at or a little below 0.2*254/256
+    assert 0.15 < np.mean(dens) < 0.2 * 254 / 256 + 0.005
+    # unconditioned wall law: threshold floor(0.2 * 2^32) on raw words
+    words = np.concatenate([orc.draw(4, b, (blk << 32) | 0, 4) for b in range(40) for blk in range(64)])
+    p = (words < 0x33333333).mean()
+    assert abs(p - 0.2) < 4 * math.sqrt(0.16 / words.size)
+    # a rejected first attempt really is disconnected: rebuild attempt 0 by hand and compare
+    rejected = 0
+    for b in range(B):
+        w0 = np.array([orc.draw(4, b, (blk << 32) | 0, 4) for blk in range(64)]).reshape(-1) < 0x33333333
+        w0 = w0.reshape(16, 16).copy(); w0[0, 0] = False; w0[15, 15] = False
+        if _flood(w0)[15, 15]:
+            assert np.array_equal(w0, _walls(o, b))
+        else:
+            rejected += 1
+            assert not np.array_equal(w0, _walls(o, b))
+    assert 0 < rejected < B // 2
+
+
+def _bfs_path(w):
+    from collections import deque
+    n = w.shape[0]
+    prev = {(0, 0): None}
+    q = deque([(0, 0)])
+    moves = [(-1, 0, 0), (0, 1, 1), (1, 0, 2), (0, -1, 3)]
+    while q:
+        r, c = q.popleft()
+        if (r, c) == (n - 1, n - 1):
+            break
+        for dr, dc, a in moves:
+            rr, cc = r + dr, c + dc
+            if 0 <= rr < n and 0 <= cc < n and not w[rr, cc] and (rr, cc) not in prev:
+                prev[(rr, cc)] = ((r, c), a)
+                q.append((rr, cc))
+    acts, cur = [], (n - 1, n - 1)
+    while prev[cur] is not None:
+        cur, a = prev[cur]
+        acts.append(a)
+    return acts[::-1]
+
+
+def test_maze_shortest_path_return_and_walls(orc):
+    o = orc.Oracle(tiny("maze", hidden=(8,), B=20, T=2), seed=12)
+    for b in range(20):
+        w = _walls(o, b)
+        acts = _bfs_path(w)
+        d = len(acts)
+        total = np.float32(0)
+        for i, a in enumerate(acts):
+            r, done = o.env_step(b, action=a, t=i)
+            total = np.float32(total + np.float32(r))
+            assert done == (i == d - 1)
+            if not done:
+                cell = o.state_i[b, 0]
+                assert not w[cell // 16, cell % 16]
+        assert abs(float(total) - (1 - 0.01 * (d - 1))) < 1e-5
+        assert tuple(o.state_i[b, :2]) == (0, 0)
+        # bumping into the border or a wall leaves the agent in place; the step cap ends the episode
+        for i in range(256):
+            r, done = o.env_step(b, action=0 if i % 2 == 0 else 3, t=i)
+            assert o.state_i[b, 0] == 0
+            assert abs(r + 0.01) < 1e-9 and done == (i == 255)
+        x = o.observe(b).reshape(3, 16, 16)
+        assert np.array_equal(x[0].astype(bool), w) and x[1].sum() == 1 and x[1, 0, 0] == 1
+        assert x[2].sum() == 1 and x[2, 15, 15] == 1
+
+
+# ------------------------------------------------------------------------ Network
+def _unpack(o, theta=None):
+    th = o.theta if theta is None else theta
+    dims = [o.D] + list(o.cfg["net"]["hidden"])
+    Ws, bs, off = [], [], 0
+    for l in range(len(dims) - 1):
+        Ws.append(th[off:off + dims[l] * dims[l + 1]].reshape(dims[l], dims[l + 1])); off += dims[l] * dims[l + 1]
+        bs.append(th[off:off + dims[l + 1]]); off += dims[l + 1]
+    Wh = th[off:off + dims[-1] * o.NH].reshape(dims[-1], o.NH); off += dims[-1] * o.NH
+    bh = th[off:off + o.NH]; off += o.NH
+    assert off == th.size
+    return Ws, bs, Wh, bh
+
+
+def test_glorot_init(orc):
+    o = orc.Oracle(W.get("catch_4096", B=2, T=2), seed=0)
+    assert o.P == 79876
+    Ws, bs, Wh, bh = _unpack(o)
+    for Wm in Ws:
+        a = math.sqrt(6.0 / sum(Wm.shape))
+        assert np.abs(Wm).max() <= a * (1 + 1e-6)
+        assert abs(Wm.astype(np.float64).var() / (a * a / 3) - 1) < 0.05
+        assert abs(Wm.mean()) < 4 * a / math.sqrt(3 * Wm.size)
+    for b in bs + [bh]:
+        assert np.all(b == 0)
+    for cols, fo in ((slice(0, 3), 3), (slice(3, 4), 1)):
+        a = math.sqrt(6.0 / (256 + fo))
+        blk = Wh[:, cols]
+        assert np.abs(blk).max() <= a * (1 + 1e-6) and np.abs(blk).max() > 0.9 * a
+    # different seeds and different layers give different numbers
+    o2 = orc.Oracle(W.get("catch_4096", B=2, T=2), seed=1)
+    assert not np.array_equal(o.theta, o2.theta)
+    assert o.P == sum(x.size for x in Ws + bs) + Wh.size + bh.size
+
+
+@pytest.mark.parametrize("name", ["catch_small", "pendulum_8192"])
+def test_forward_vs_float64(orc, name):
+    o = orc.Oracle(W.get(name, B=6, T=3), seed=2)
+    rng = np.random.default_rng(1)
+    o.theta[:] += rng.standard_normal(o.P).astype(np.float32) * 0.05     # non-zero biases too
+    Ws, bs, Wh, bh = _unpack(o)
+    for b in range(6):
+        x = o.observe(b)
+        head, acts = o.forward(x, want_acts=True)
+        hcur = x.astype(np.float64)
+        ref_acts = []
+        for Wm, bv in zip(Ws, bs):
+            hcur = np.maximum(hcur @ Wm.astype(np.float64) + bv, 0)
+            ref_acts.append(hcur)
+        ref = hcur @ Wh.astype(np.float64) + bh
+        assert np.allclose(head, ref, rtol=1e-5, atol=1e-6)
+        assert np.allclose(acts, np.concatenate(ref_acts), rtol=1e-5, atol=1e-6)
+
+
+def test_forward_zero_weights_gives_biases(orc):
+    o = orc.Oracle(W.get("catch_small", B=2, T=2), seed=2)
+    o.theta[:] = 0
+    o.theta[-4:] = (0.25, -1.5, 3.0, 0.125)
+    assert np.array_equal(o.forward(o.observe(0)), np.array([0.25, -1.5, 3.0, 0.125], np.float32))
+
+
+def test_forward_bf16_rounding_points(orc):
+    import torch
+    o = orc.Oracle(tiny("maze", hidden=(32, 16), B=3, T=2, dtype="bf16"), seed=5)
+    bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+    Ws, bs, Wh, bh = _unpack(o)
+    for b in range(3):
+        x = o.observe(b)
+        head, acts = o.forward(x, want_acts=True)
+        hcur = bf(x).astype(np.float64)
+        ref_acts = []
+        for Wm, bv in zip(Ws, bs):
+            z = hcur @ bf(Wm).astype(np.float64) + bv
+            hcur = bf(np.maximum(z, 0).astype(np.float32)).astype(np.float64)
+            ref_acts.append(hcur)
+        ref = hcur @ bf(Wh).astype(np.float64) + bh
+        # hidden activations may differ by one bf16 step where fp32 and fp64 sums straddle a tie
+        assert np.allclose(acts, np.concatenate(ref_acts), rtol=2 ** -7, atol=1e-6)
+        assert np.mean(acts == np.concatenate(ref_acts)) > 0.95
+        assert np.allclose(head, ref, rtol=2e-2, atol=2e-3)
+        assert np.array_equal(acts, bf(acts))          # stored activations are bf16 values
+
+
+# ----------------------------------------------------------------------- Sampling
+def test_categorical_sampler(orc):
+    L = orc.lib()
+    us = (np.arange(0, 1 << 24, 4099) * 2.0 ** -24).astype(np.float32)
+    # equal logits: action = floor(3u) up to the rounding of the running sums
+    a = np.array([orc.sample_categorical([0.7, 0.7, 0.7], u) for u in us])
+    assert np.mean(a == np.floor(3 * us.astype(np.float64))) > 0.9995
+    assert np.all(np.diff(a) >= 0) and set(a) == {0, 1, 2}
+    # a dominant logit wins wherever it sits (the others have mass e^-40, below the grid's smallest u > 0)
+    for i in range(3):
+        lg = [0.0, 0.0, 0.0]; lg[i] = 40.0
+        assert all(orc.sample_categorical(lg, u) == i for u in us[1::50])
+    # frequencies follow softmax
+    lg = np.array([0.3, -1.2, 0.9, 0.1], np.float32)
+    p = np.exp(lg.astype(np.float64)); p /= p.sum()
+    words = np.concatenate([orc.draw(3, i, 5, 0) for i in range(6000)])
+    acts = np.array([orc.sample_categorical(lg, L.orc_u01(int(w))) for w in words])
+    cnt = np.bincount(acts, minlength=4)
+    assert ((cnt - p * acts.size) ** 2 / (p * acts.size)).sum() < 16.3     # 3 dof, p = 0.001
+    # monotone in u: inverse-CDF property
+    a = np.array([orc.sample_categorical(lg, u) for u in us])
+    assert np.all(np.diff(a) >= 0)
+    cdf = np.cumsum(p)
+    assert np.mean(a == np.searchsorted(cdf, us.astype(np.float64), side="right").clip(0, 3)) > 0.9995
+
+
+def test_gaussian_sampler(orc):
+    n = 20000
+    ws = np.array([orc.draw(5, i, 0, 0) for i in range(n)])
+    out = np.array([orc.sample_gaussian(0.3, -0.5, w[0], w[1]) for w in ws], np.float64)
+    eps, z, act = out[:, 0], out[:, 1], out[:, 2]
+    assert abs(eps.mean()) < 4 / math.sqrt(n) and abs(eps.var() - 1) < 0.05
+    kurt = ((eps - eps.mean()) ** 4).mean() / eps.var() ** 2
+    assert abs(kurt - 3) < 0.25
+    sigma = math.exp(-0.5)
+    assert np.allclose(z, 0.3 + sigma * eps, rtol=1e-6, atol=1e-6)
+    assert np.allclose(act, np.tanh(z), rtol=1e-6, atol=1e-7)
+    # Box-Muller against the textbook formula in float64
+    L = orc.lib()
+    u0 = np.array([L.orc_u01_plus(int(w[0])) for w in ws[:2000]], np.float64)
+    u1 = np.array([L.orc_u01(int(w[1])) for w in ws[:2000]], np.float64)
+    assert np.allclose(eps[:2000], np.sqrt(-2 * np.log(u0)) * np.cos(2 * np.pi * u1), rtol=2e-5, atol=2e-6)
+    # clamp of log_sigma
+    e1, z1, _ = orc.sample_gaussian(0.0, 7.0, ws[0][0], ws[0][1])
+    assert abs(z1 - math.exp(2.0) * e1) < 1e-5 * abs(z1) + 1e-6
+    e2, z2, _ = orc.sample_gaussian(0.0, -9.0, ws[0][0], ws[0][1])
+    assert abs(z2 - math.exp(-5.0) * e2) < 1e-5 * abs(z2) + 1e-9
+
+
+# ------------------------------------------------------------------------ Returns
+def _brute_lambda_returns(rew, done, val, gamma, lam):
+    """Mixture definition: G^lam_t = (1-lam) sum_{n<N} lam^(n-1) G^(n)_t + lam^(N-1) G^(N)_t, where
+    G^(n)_t is the n-step return with explicit discount products, and N is the number of steps up
+    to the end of the unroll or of the episode, whichever comes first."""
+    T, B = rew.shape
+    G = np.zeros((T, B))
+    for b in range(B):
+        for t in range(T):
+            N = T - t
+            for n in range(1, T - t + 1):
+                if done[t + n - 1, b]:
+                    N = n
+                    break
+            nstep = []
+            for n in range(1, N + 1):
+                g, disc = 0.0, 1.0
+                for i in range(n):
+                    g += disc * float(rew[t + i, b])
+                    disc *= 0.0 if done[t + i, b] else gamma
+                g += disc * float(val[t + n, b])
+                nstep.append(g)
+            G[t, b] = (1 - lam) * sum(lam ** (n - 1) * nstep[n - 1] for n in range(1, N)) + lam ** (N - 1) * nstep[N - 1]
+    return G
+
+
+@pytest.mark.parametrize("lam", [1.0, 0.95, 0.0, 0.5])
+def test_returns_vs_bruteforce_and_gae(orc, lam):
+    rng = np.random.default_rng(10)
+    T, B, gamma = 13, 7, 0.99
+    rew = rng.standard_normal((T, B)).astype(np.float32)
+    done = (rng.random((T, B)) < 0.2).astype(np.uint8)
+    val = rng.standard_normal((T + 1, B)).astype(np.float32)
+    ret, adv = orc.returns(rew, done, val, gamma, lam)
+    assert np.allclose(ret, _brute_lambda_returns(rew, done, val, gamma, lam), rtol=1e-12, atol=1e-12)
+    # GAE form
+    A = np.zeros((T + 1, B))
+    for t in range(T - 1, -1, -1):
+        disc = np.where(done[t] == 1, 0.0, gamma)
+        delta = rew[t] + disc * val[t + 1] - val[t]
+        A[t] = delta + disc * lam * A[t + 1]
+    assert np.allclose(adv, A[:T], rtol=1e-12, atol=1e-12)
+    assert np.allclose(adv, ret - val[:T], rtol=0, atol=1e-14)
+    if lam == 0.0:
+        assert np.allclose(ret, rew + np.where(done == 1, 0, gamma) * val[1:], atol=1e-14)
+
+
+def test_returns_closed_forms(orc):
+    for line in open(os.path.join(GOLD, "returns_closed_form.txt")):
+        if line.startswith("#"):
+            continue
+        T, gamma, lam, r, v, what, value = line.split()
+        T = int(T); gamma, lam, r, v, value = map(float, (gamma, lam, r, v, value))
+        rew = np.full((T, 2), r, np.float32); done = np.zeros((T, 2), np.uint8)
+        val = np.full((T + 1, 2), v, np.float32)
+        ret, adv = orc.returns(rew, done, val, gamma, lam)
+        got = ret[0, 0] if what == "G0" else adv[0, 0]
+        assert abs(got - value) < 5e-9
+        n = np.arange(T, 0, -1)
+        if lam == 1.0:
+            assert np.allclose(ret[:, 0], r * (1 - gamma ** n) / (1 - gamma) + gamma ** n * v, rtol=1e-12)
+        assert np.allclose(adv[:, 0], (r + gamma * v - v) * (1 - (gamma * lam) ** n) / (1 - gamma * lam), rtol=1e-10)
+    # an episode end at every step: G_t = r_{t+1}
+    rew = np.arange(12, dtype=np.float32).reshape(6, 2)
+    ret, _ = orc.returns(rew, np.ones((6, 2), np.uint8), np.full((7, 2), 9.0, np.float32), 0.99, 0.95)
+    assert np.array_equal(ret, rew.astype(np.float64))
+
+
+# ------------------------------------------------------------- Objective, gradient
+def _np_surrogate(o, theta, obs, kind):
+    """Independent float64 statement of the objective for fixed samples (a, z), A and G."""
+    Ws, bs, Wh, bh = _unpack(o, theta.astype(np.float64))
+    h = obs
+    for Wm, bv in zip(Ws, bs):
+        h = np.maximum(h @ Wm + bv, 0)
+    head = h @ Wh + bh
+    A, G = o.adv.reshape(-1), o.ret.reshape(-1)
+    beta, cv = o.cfg["net"]["entropy_coef"], o.cfg["net"]["value_coef"]
+    V = head[:, -1]
+    if kind == "categorical":
+        lg = head[:, :-1]
+        lp = lg - lg.max(1, keepdims=True)
+        lp = lp - np.log(np.exp(lp).sum(1, keepdims=True))
+        H = -(np.exp(lp) * lp).sum(1)
+        lpa = lp[np.arange(lp.shape[0]), o.tr_action.reshape(-1)]
+    else:
+        mu, ls = head[:, 0], np.clip(head[:, 1], -5, 2)
+        z = o.tr_z.reshape(-1).astype(np.float64)
+        lpa = -0.5 * ((z - mu) / np.exp(ls)) ** 2 - ls - 0.5 * math.log(2 * math.pi)
+        H = ls + 0.5 * math.log(2 * math.pi * math.e)
+    per = -A * lpa + cv * (G - V) ** 2 - beta * H
+    return per.mean(), (-A * lpa).mean(), (cv * (G - V) ** 2).mean(), (-beta * H).mean()
+
+
+@pytest.mark.parametrize("kind", ["catch", "pendulum", "maze"])
+def test_gradient_vs_finite_differences(orc, kind):
+    cfg = tiny(kind, hidden=(5, 4), B=3, T=5, rows=4, cols=4 if kind == "maze" else 3, max_steps=3, p_wall=0.1)
+    o = orc.Oracle(cfg, seed=13)
+    rng = np.random.default_rng(3)
+    o.theta[:] += rng.standard_normal(o.P).astype(np.float32) * 0.3
+    o.rollout()
+    ret, adv = orc.returns(o.tr_reward, o.tr_done, o.tr_value, cfg["net"]["gamma"], cfg["net"]["lambda"])
+    o.ret[:] = ret; o.adv[:] = adv + rng.standard_normal(adv.shape)     # any constants will do
+    o.loss_and_grad()
+    # observations rebuilt from the stored states by the test itself
+    T, B = o.T, o.B
+    obs = np.zeros((T * B, o.D))
+    for t in range(T):
+        for b in range(B):
+            si, sf = o.tr_state_i[t, b], o.tr_state_f[t, b]
+            if kind == "catch":
+                x = np.zeros((4, 3)); x[si[1], si[0]] = 1; x[3, si[2]] = 1
+            elif kind == "pendulum":
+                x = np.array([math.cos(sf[0]), math.sin(sf[0]), sf[1]])
+            else:
+                n = 16
+                wb = np.unpackbits(o.walls[b].view(np.uint8), bitorder="little")[:n].astype(float)
+                ag = np.zeros(n); ag[si[0]] = 1
+                gl = np.zeros(n); gl[n - 1] = 1
+                x = np.concatenate([wb, ag, gl])
+            obs[t * B + b] = np.ravel(x)
+    pol = "categorical" if kind != "pendulum" else "gauss"
+    th0 = o.theta.astype(np.float64)
+    l0 = _np_surrogate(o, th0, obs, pol)
+    assert np.allclose(o.loss, l0, rtol=1e-6, atol=1e-7)
+    h = 1e-5
+    fd = np.zeros(o.P)
+    for i in range(o.P):
+        tp, tm = th0.copy(), th0.copy()
+        tp[i] += h; tm[i] -= h
+        fd[i] = (_np_surrogate(o, tp, obs, pol)[0] - _np_surrogate(o, tm, obs, pol)[0]) / (2 * h)
+    g = o.grad.astype(np.float64)
+    assert np.linalg.norm(g) > 1e-3
+    assert np.linalg.norm(g - fd) / np.linalg.norm(fd) < 1e-5
+    assert np.abs(g - fd).max() < 1e-5 * np.abs(fd).max() + 1e-7
+
+
+def test_head_gradient_identities(orc):
+    cfg = tiny("catch", hidden=(4,), B=4, T=3)
+    o = orc.Oracle(cfg, seed=3)
+    # all-zero parameters: uniform policy, H = log 3, entropy gradient 0
+    o.theta[:] = 0
+    o.rollout()
+    o.ret[:] = 0; o.adv[:] = 0
+    o.loss_and_grad()
+    assert abs(o.loss[3] + float(np.float32(0.01)) * math.log(3)) < 1e-12 and abs(math.log(3) - 1.0986123) < 1e-7
+    assert np.abs(o.grad).max() < 1e-15             # A = 0, G = V = 0, uniform policy
+    # bias gradient of the logits sums to zero for any A (softmax shift invariance)
+    rng = np.random.default_rng(0)
+    o.theta[:] = rng.standard_normal(o.P).astype(np.float32) * 0.5
+    o.rollout()
+    o.adv[:] = rng.standard_normal(o.adv.shape); o.ret[:] = rng.standard_normal(o.ret.shape)
+    o.loss_and_grad()
+    assert abs(o.grad[-4:-1].astype(np.float64).sum()) < 1e-7
+    # mean over copies: duplicating every sample leaves loss and gradient unchanged
+    g1, l1 = o.grad.copy(), o.loss.copy()
+    cfg2 = tiny("catch", hidden=(4,), B=8, T=3)
+    o2 = orc.Oracle(cfg2, seed=3)
+    o2.theta[:] = o.theta
+    for arr in ("tr_state_i", "tr_state_f", "tr_action", "tr_reward", "tr_done", "tr_value"):
+        getattr(o2, arr)[:] = np.concatenate([getattr(o, arr)] * 2, axis=1)
+    o2.adv[:] = np.concatenate([o.adv] * 2, axis=1); o2.ret[:] = np.concatenate([o.ret] * 2, axis=1)
+    o2.loss_and_grad()
+    assert np.allclose(o2.grad, g1, rtol=1e-6, atol=1e-9) and np.allclose(o2.loss, l1, rtol=1e-12)
+
+
+# --------------------------------------------------------------------------- Adam
+def test_adam_closed_forms(orc):
+    g = np.array([0.5, -2.0, 0.0, 1e-3, -7e-6], np.float32)
+    th = np.ones(5, np.float32); m = np.zeros(5); v = np.zeros(5)
+    orc.adam(th, g, m, v, 1, 3e-4, 0.9, 0.999, 1e-8)
+    want = 1 - 3e-4 * g.astype(np.float64) / (np.abs(g) + 1e-8)
+    assert np.allclose(th, want, rtol=0, atol=1e-7) and th[2] == 1.0
+    # constant gradient for t steps: theta_t = theta_0 - t lr g/(|g|+eps)
+    th = np.zeros(5, np.float32); m = np.zeros(5); v = np.zeros(5)
+    for t in range(1, 51):
+        orc.adam(th, g, m, v, t, 3e-4, 0.9, 0.999, 1e-8)
+    assert np.allclose(th, -50 * 3e-4 * g.astype(np.float64) / (np.abs(g) + 1e-8), rtol=1e-5, atol=1e-7)
+
+
+def test_adam_vs_library(orc):
+    import torch
+    rng = np.random.default_rng(2)
+    n = 300
+    p = torch.nn.Parameter(torch.from_numpy(rng.standard_normal(n)).double())
+    opt = torch.optim.Adam([p], lr=3e-4, betas=(0.9, 0.999), eps=1e-8)
+    th = p.detach().numpy().astype(np.float32).copy(); m = np.zeros(n); v = np.zeros(n)
+    p.data = torch.from_numpy(th.astype(np.float64))
+    for t in range(1, 21):
+        g = (rng.standard_normal(n) * 10 ** rng.uniform(-4, 1)).astype(np.float32)
+        p.grad = torch.from_numpy(g.astype(np.float64))
+        opt.step()
+        orc.adam(th, g, m, v, t, 3e-4, 0.9, 0.999, 1e-8)
+    assert np.abs(th - p.detach().numpy()).max() < 1e-6
+
+
+# --------------------------------------------------------------- whole-agent checks
+def test_unroll_continues_across_calls(orc):
+    # two unrolls of 10 equal one of 20 when parameters do not change (state stays resident)
+    a = orc.Oracle(W.get("catch_small", B=16, T=10), seed=21)
+    b = orc.Oracle(W.get("catch_small", B=16, T=20), seed=21)
+    a.rollout(); first = (a.tr_action.copy(), a.tr_reward.copy())
+    a.rollout()
+    b.rollout()
+    assert np.array_equal(np.concatenate([first[0], a.tr_action]), b.tr_action)
+    assert np.array_equal(np.concatenate([first[1], a.tr_reward]), b.tr_reward)
+    assert a.global_step == b.global_step == 20
+
+
+def test_catch_learning_sanity(orc):
+    # not a parity criterion: the mean episode return should rise from about -0.6
+    cfg = W.get("catch_small", B=64, T=20)
+    cfg["net"]["lr"] = 3e-3
+    o = orc.Oracle(cfg, seed=0)
+    first = last = 0.0
+    for i in range(150):
+        o.rollout()
+        r = o.tr_reward.sum() / max(1, o.tr_done.sum())
+        if i < 10: first += r / 10
+        if i >= 140: last += r / 10
+        o.learn()
+    assert last > first + 0.3
