@@ -1,0 +1,159 @@
+/*
+ * anakin.h -- C ABI of the MI355X-native Anakin actor-learner step.
+ *
+ * Anakin (paper section 3.1, "Online Learning with Anakin", and figure 2 top):
+ * the environments live on the accelerator next to the agent; one unit of work
+ * is T agent-environment interactions (observation -> action -> reward, paper
+ * section 2.1) for a batch of B environments, followed by one parameter update
+ * that reuses the policy's forward pass.  The host only schedules (section
+ * 3.1); state stays in device memory between calls (section 2.3).
+ *
+ * All functions return 0 (ANAKIN_OK) or a negative ANAKIN_E_* code; nothing
+ * throws across this boundary.  Unless a parameter says "host", pointers named
+ * d_* are device pointers and h_* are host pointers.  A handle is not
+ * thread-safe; distinct handles are independent.
+ *
+ * Memory ownership: the caller owns the device workspace and the stream.  The
+ * library never allocates device memory; it carves the workspace (256-byte
+ * alignment) and owns only the small host-side handle.
+ */
+#ifndef ANAKIN_H
+#define ANAKIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ANAKIN_OK = 0,
+    ANAKIN_E_INVALID_ARG = -1,         /* null pointer, wrong length */
+    ANAKIN_E_BAD_CONFIG = -2,          /* unsupported env / net / B / T */
+    ANAKIN_E_WORKSPACE_TOO_SMALL = -3,
+    ANAKIN_E_MISALIGNED = -4,          /* workspace not 256-byte aligned */
+    ANAKIN_E_HIP = -5,                 /* a HIP runtime call failed; see anakin_last_error */
+    ANAKIN_E_NONFINITE = -6,
+    ANAKIN_E_STATE = -7                /* e.g. learn without a stored trajectory */
+};
+
+enum { ANAKIN_ENV_CATCH = 0, ANAKIN_ENV_PENDULUM = 1, ANAKIN_ENV_MAZE = 2 };
+enum { ANAKIN_POLICY_CATEGORICAL = 0, ANAKIN_POLICY_TANH_GAUSSIAN = 1 };
+enum { ANAKIN_DTYPE_FP32 = 0, ANAKIN_DTYPE_BF16 = 1 };
+
+/* anakin_set_mode flags */
+enum {
+    ANAKIN_MODE_VALU_GEMM = 1,         /* learn-phase GEMMs on vector ALUs instead of matrix cores */
+    ANAKIN_MODE_CANONICAL_ACTING = 2   /* bf16 nets: act with the sequential fp32 chain instead of matrix cores */
+};
+
+/* Environment (paper section 3.1: initial_state + step on explicit state).
+ * kind CATCH: rows x cols board (max_steps ignored, episodes last rows-1 steps);
+ * PENDULUM: rows/cols ignored, max_steps = episode length;
+ * MAZE: rows x cols <= 256 cells, p_wall = wall probability, max_steps = step cap. */
+typedef struct {
+    int32_t kind, rows, cols, max_steps;
+    float p_wall;
+} anakin_env_cfg;
+
+/* Network, objective and optimiser.  hidden[i] in {32,...,1024}, powers of two.
+ * policy CATEGORICAL goes with CATCH and MAZE, TANH_GAUSSIAN with PENDULUM.
+ * dtype BF16: bfloat16 weights and activations, fp32 accumulation and fp32
+ * master weights.  lambda_ = 1 gives bootstrapped n-step returns. */
+typedef struct {
+    int32_t n_hidden;
+    int32_t hidden[4];
+    int32_t policy;
+    int32_t dtype;
+    float gamma, lambda_, entropy_coef, value_coef, lr, beta1, beta2, eps;
+} anakin_net_cfg;
+
+typedef struct anakin anakin_t;
+
+/* Device pointers into the caller's workspace (valid for the handle's life)
+ * and their byte offsets from the workspace base.  Time-major: index [t][b].
+ * state_* hold the state observed at t (t = 0..T); the rest t = 0..T-1 except
+ * value and head (t = 0..T, the last row being the bootstrap evaluation). */
+typedef struct {
+    int32_t B, T, num_heads, head_stride, n_hidden;
+    int32_t hidden[4];
+    int32_t act_is_bf16;              /* element type of act[]: 0 fp32, 1 bf16 */
+    void* state_s0;  size_t off_state_s0;   /* uint32 [T+1][B] packed state word */
+    void* state_f0;  size_t off_state_f0;   /* float  [T+1][B] (pendulum theta) */
+    void* state_f1;  size_t off_state_f1;   /* float  [T+1][B] (pendulum theta_dot) */
+    void* action;    size_t off_action;     /* uint8  [T][B] categorical action */
+    void* eps;       size_t off_eps;        /* float  [T][B] gaussian noise */
+    void* action_f;  size_t off_action_f;   /* float  [T][B] squashed gaussian action */
+    void* reward;    size_t off_reward;     /* float  [T][B] */
+    void* done;      size_t off_done;       /* uint8  [T][B] */
+    void* value;     size_t off_value;      /* float  [T+1][B] */
+    void* head;      size_t off_head;       /* float  [T+1][B][head_stride] raw head outputs */
+    void* adv;       size_t off_adv;        /* float  [T][B] advantages (after learn) */
+    void* ret;       size_t off_ret;        /* float  [T][B] returns (after learn) */
+    void* act[4];    size_t off_act[4];     /* [T*B][hidden[l]] hidden activations */
+} anakin_traj_view;
+
+/* Sums over the last unroll / update.  Filled after synchronising the stream. */
+typedef struct {
+    double loss, policy_loss, value_loss, entropy_loss;   /* means over B*T (last learn) */
+    double reward_sum;                                    /* over the last unroll */
+    int64_t episodes;                                     /* episode ends in the last unroll */
+    int32_t nonfinite;                                    /* 1 if any of the above is not finite */
+} anakin_metrics;
+
+/* Bytes of device workspace needed for this configuration (0 if it is invalid). */
+size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin_net_cfg* net, int32_t B, int32_t T);
+
+/* Create an agent: B environments in their initial states (drawn from the
+ * seed), Glorot-initialised parameters, zero optimiser state -- all written
+ * into d_workspace on hip_stream (a hipStream_t, may be null for the default
+ * stream).  B must be a multiple of 16.  Synchronises the stream before
+ * returning.  On error *out is null and nothing is enqueued. */
+int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, const anakin_net_cfg* net,
+                      int32_t B, int32_t T, uint64_t seed,
+                      void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* T interactions per env, each: observe, policy/value forward, sample, env
+ * step (paper section 2.1 loop; figure 2 top), then the value of the final
+ * state.  Fills the trajectory; env state carries over to the next call.
+ * Asynchronous: enqueues on the stream and returns. */
+int32_t anakin_rollout(anakin_t* h);
+
+/* One update on the stored trajectory: returns/advantages, actor-critic loss,
+ * backward pass, Adam (paper section 3.1: "parameter update" reusing the
+ * forward pass).  ANAKIN_E_STATE without a preceding rollout.  Asynchronous. */
+int32_t anakin_learn(anakin_t* h);
+
+/* anakin_rollout followed by anakin_learn: the timed unit. */
+int32_t anakin_step(anakin_t* h);
+
+/* Frees the host-side handle (never the workspace).  Synchronises the stream. */
+int32_t anakin_destroy(anakin_t* h);
+
+/* ---- introspection for parity tests and measurement (all synchronise) ---- */
+int32_t anakin_param_count(const anakin_t* h, int64_t* out);
+int32_t anakin_get_params(anakin_t* h, float* h_dst, size_t n);          /* n must equal the count */
+int32_t anakin_set_params(anakin_t* h, const float* h_src, size_t n);    /* also refreshes bf16 copies */
+int32_t anakin_get_grads(anakin_t* h, float* h_dst, size_t n);           /* gradient of the last learn */
+int32_t anakin_get_opt_state(anakin_t* h, float* h_m, float* h_v, int32_t* h_step, size_t n);
+int32_t anakin_set_opt_state(anakin_t* h, const float* h_m, const float* h_v, int32_t step, size_t n);
+/* env state as [B][4] int32 + [B][2] float rows:
+ * catch (ball_x, ball_y, paddle_x, 0); pendulum (steps,0,0,0) + (theta, theta_dot); maze (cell, steps,0,0) */
+int32_t anakin_get_env_state(anakin_t* h, int32_t* h_si, float* h_sf);
+int32_t anakin_set_env_state(anakin_t* h, const int32_t* h_si, const float* h_sf);
+int32_t anakin_get_walls(anakin_t* h, uint32_t* h_walls);                /* [B][8], maze only */
+int32_t anakin_get_global_step(const anakin_t* h, uint64_t* out);
+int32_t anakin_set_global_step(anakin_t* h, uint64_t g);
+int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* out);
+int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out);
+int32_t anakin_set_mode(anakin_t* h, int32_t flags);
+
+/* Handle-owned message for the last error on this handle (valid until the next
+ * call on it); for a null handle, the message of the last failed create. */
+const char* anakin_last_error(const anakin_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANAKIN_H */

@@ -693,11 +693,15 @@ void orc_env_step(orc_t* h, int b, int action, float action_f, uint64_t t, float
 /* a CPU cannot mirror (matrix-core bf16); sampling and env stepping are      */
 /* still the oracle's own.                                                    */
 /* ------------------------------------------------------------------------- */
-void orc_rollout(orc_t* h, const float* forced_head)
+/* sel (optional): roll out only the n_sel listed envs -- envs are independent  */
+/* and every draw is keyed by (env, step), so any subset replays exactly.      */
+void orc_rollout_sel(orc_t* h, const float* forced_head, const int32_t* sel, int n_sel)
 {
     int B = h->B, T = h->T, NH = h->NH;
     float x[1024], head[16];
-    for (int b = 0; b < B; ++b) {
+    int count = sel ? n_sel : B;
+    for (int ib = 0; ib < count; ++ib) {
+        int b = sel ? sel[ib] : ib;
         int32_t* si = h->si + (size_t)b * 4;
         float* sf = h->sf + (size_t)b * 2;
         for (int t = 0; t <= T; ++t) {
@@ -730,8 +734,9 @@ void orc_rollout(orc_t* h, const float* forced_head)
         }
     }
     h->gstep += (uint64_t)T;
-    h->have_traj = 1;
+    h->have_traj = sel ? 0 : 1;
 }
+void orc_rollout(orc_t* h, const float* forced_head) { orc_rollout_sel(h, forced_head, NULL, 0); }
 
 /* ------------------------------------------------------------------------- */
 /* Returns and advantages (binary64).  With disc = gamma (1 - done):          */
@@ -820,7 +825,7 @@ void orc_loss_and_grad(orc_t* h)
             int A = h->A, a = h->tr_act[tb];
             double mx = head[0];
             for (int i = 1; i < A; ++i) if (head[i] > mx) mx = head[i];
-            double Z = 0, p[16], lp[16], H = 0;
+            double Z = 0, p[16] = {0}, lp[16] = {0}, H = 0;
             for (int i = 0; i < A; ++i) Z += exp(head[i] - mx);
             for (int i = 0; i < A; ++i) { lp[i] = head[i] - mx - log(Z); p[i] = exp(lp[i]); H -= p[i] * lp[i]; }
             Lp += -A_ * lp[a];

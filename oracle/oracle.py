@@ -78,6 +78,7 @@ def lib():
         L.orc_env_step.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_uint64, f32p, i32p]
         L.orc_env_step.restype = None
         L.orc_rollout.argtypes = [C.c_void_p, f32p]; L.orc_rollout.restype = None
+        L.orc_rollout_sel.argtypes = [C.c_void_p, f32p, i32p, C.c_int]; L.orc_rollout_sel.restype = None
         L.orc_returns.argtypes = [C.c_int, C.c_int, f32p, u8p, f32p, C.c_double, C.c_double, f64p, f64p]
         L.orc_returns.restype = None
         L.orc_loss_and_grad.argtypes = [C.c_void_p]; L.orc_loss_and_grad.restype = None
@@ -243,13 +244,19 @@ class Oracle:
         self.L.orc_env_step(self.h, b, int(action), float(action_f), int(t), C.byref(r), C.byref(d))
         return r.value, d.value
 
-    def rollout(self, forced_head=None):
+    def rollout(self, forced_head=None, sel=None):
+        """forced_head: [T+1][B][NH] head outputs to sample from instead of the oracle's own forward.
+        sel: env indices to roll out (others untouched; learn is then unavailable)."""
+        fh = None
         if forced_head is not None:
             fh = np.ascontiguousarray(forced_head, np.float32)
             assert fh.shape == (self.T + 1, self.B, self.NH)
-            self.L.orc_rollout(self.h, _ptr(fh, C.c_float))
+        fhp = _ptr(fh, C.c_float) if fh is not None else None
+        if sel is not None:
+            ids = np.ascontiguousarray(sel, np.int32)
+            self.L.orc_rollout_sel(self.h, fhp, _ptr(ids, C.c_int32), ids.size)
         else:
-            self.L.orc_rollout(self.h, None)
+            self.L.orc_rollout(self.h, fhp)
 
     def learn(self):
         rc = self.L.orc_learn(self.h)

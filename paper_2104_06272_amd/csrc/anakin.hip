@@ -1,0 +1,504 @@
+// Host side of libanakin: the C ABI, configuration checks, workspace layout,
+// one-time initialisation (parameters, env states, mazes) and the step
+// scheduler.  The host only enqueues a fixed kernel sequence on one stream
+// (paper section 3.1: the host "is exclusively used to schedule"); all state
+// stays in the caller's device workspace between calls (section 2.3).
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+#include <vector>
+#include "internal.h"
+
+using namespace ank;
+
+static thread_local std::string g_create_error;
+
+namespace ank { void fill_rollout_args(anakin* h, RolloutArgs& a); }
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static bool is_pow2_in(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
+
+// ---- configuration -------------------------------------------------------
+static int build_shapes(const anakin_env_cfg* env, const anakin_net_cfg* net, int B, int T,
+                        EnvDims& ed, NetShape& ns, std::string& err)
+{
+    if (!env || !net) { err = "null configuration"; return ANAKIN_E_INVALID_ARG; }
+    if (B <= 0 || T <= 0 || B % 16 != 0) { err = "B must be a positive multiple of 16 and T positive"; return ANAKIN_E_BAD_CONFIG; }
+    if ((long long)B * (T + 1) >= (1ll << 30)) { err = "B*(T+1) too large"; return ANAKIN_E_BAD_CONFIG; }
+    ed.kind = env->kind; ed.rows = env->rows; ed.cols = env->cols; ed.max_steps = env->max_steps;
+    memset(&ns, 0, sizeof ns);
+    if (env->kind == ANAKIN_ENV_CATCH) {
+        if (env->rows < 2 || env->cols < 1 || env->rows > 255 || env->cols > 255) { err = "catch: rows in 2..255, cols in 1..255"; return ANAKIN_E_BAD_CONFIG; }
+        ns.D = env->rows * env->cols; ns.A = 3;
+    } else if (env->kind == ANAKIN_ENV_PENDULUM) {
+        if (env->max_steps < 1) { err = "pendulum: max_steps >= 1"; return ANAKIN_E_BAD_CONFIG; }
+        ns.D = 3; ns.A = 1;
+    } else if (env->kind == ANAKIN_ENV_MAZE) {
+        if (env->rows < 2 || env->cols < 2 || env->rows * env->cols > 256 || env->max_steps < 1 || env->max_steps > 65535 ||
+            !(env->p_wall >= 0.0f && env->p_wall < 1.0f)) { err = "maze: 4..256 cells, max_steps in 1..65535, p_wall in [0,1)"; return ANAKIN_E_BAD_CONFIG; }
+        ns.D = 3 * env->rows * env->cols; ns.A = 4;
+    } else { err = "unknown env kind"; return ANAKIN_E_BAD_CONFIG; }
+    if (net->policy != ANAKIN_POLICY_CATEGORICAL && net->policy != ANAKIN_POLICY_TANH_GAUSSIAN) { err = "unknown policy"; return ANAKIN_E_BAD_CONFIG; }
+    if ((net->policy == ANAKIN_POLICY_TANH_GAUSSIAN) != (env->kind == ANAKIN_ENV_PENDULUM)) { err = "tanh-gaussian policy goes with the pendulum, categorical with catch and maze"; return ANAKIN_E_BAD_CONFIG; }
+    if (net->dtype != ANAKIN_DTYPE_FP32 && net->dtype != ANAKIN_DTYPE_BF16) { err = "unknown dtype"; return ANAKIN_E_BAD_CONFIG; }
+    if (net->n_hidden < 1 || net->n_hidden > MAX_LAYERS) { err = "n_hidden in 1..4"; return ANAKIN_E_BAD_CONFIG; }
+    ns.L = net->n_hidden; ns.policy = net->policy; ns.bf16 = net->dtype == ANAKIN_DTYPE_BF16;
+    ns.NH = net->policy == ANAKIN_POLICY_CATEGORICAL ? ns.A + 1 : 3;
+    ns.NHP = ns.NH <= 4 ? 4 : 8;
+    ns.dims[0] = ns.D;
+    for (int l = 0; l < ns.L; ++l) {
+        if (!is_pow2_in(net->hidden[l], 32, 1024)) { err = "hidden widths must be powers of two in 32..1024"; return ANAKIN_E_BAD_CONFIG; }
+        ns.dims[l + 1] = net->hidden[l];
+    }
+    long long off = 0;
+    for (int l = 0; l < ns.L; ++l) {
+        ns.w_off[l] = (int)off; off += (long long)ns.dims[l] * ns.dims[l + 1];
+        ns.b_off[l] = (int)off; off += ns.dims[l + 1];
+    }
+    ns.wh_off = (int)off; off += (long long)ns.dims[ns.L] * ns.NH;
+    ns.bh_off = (int)off; off += ns.NH;
+    ns.P = (int)off;
+    if (!(net->gamma >= 0.0f && net->gamma <= 1.0f) || !(net->lambda_ >= 0.0f && net->lambda_ <= 1.0f) ||
+        !(net->lr > 0.0f) || !(net->beta1 >= 0.0f && net->beta1 < 1.0f) || !(net->beta2 >= 0.0f && net->beta2 < 1.0f) ||
+        !(net->eps > 0.0f)) { err = "hyper-parameters out of range"; return ANAKIN_E_BAD_CONFIG; }
+    if (rollout_pick_tile(ns, B) == 0) { err = "no rollout tile fits B and the hidden widths"; return ANAKIN_E_BAD_CONFIG; }
+    return ANAKIN_OK;
+}
+
+// split-K factor for a reduction over M samples feeding `tiles` output tiles:
+// chunks are multiples of 16 rows; aim for about 2048 workgroups, at most 256 splits
+static int pick_splits(int M, int tiles, int max_splits)
+{
+    int cap = 2048 / (tiles > 0 ? tiles : 1);
+    if (cap > max_splits) cap = max_splits;
+    if (cap < 1) cap = 1;
+    int s = M / 16;
+    while (s > cap && s % 2 == 0) s /= 2;
+    return s;
+}
+
+static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* splits, int loss_blocks, Layout& L)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    const size_t P = (size_t)ns.P, n = (size_t)B, tn = (size_t)T * B, t1n = (size_t)(T + 1) * B;
+    L.theta = take(P * 4); L.grad = take(P * 4); L.m = take(P * 4); L.v = take(P * 4);
+    L.w_bf16 = take(ns.bf16 ? P * 2 : 0); L.wt_bf16 = take(ns.bf16 ? P * 2 : 0);
+    L.s0 = take(n * 4); L.f0 = take(n * 4); L.f1 = take(n * 4); L.walls = take(n * 8 * 4);
+    L.tr_s0 = take(t1n * 4); L.tr_f0 = take(t1n * 4); L.tr_f1 = take(t1n * 4);
+    L.tr_act = take(tn); L.tr_eps = take(tn * 4); L.tr_actf = take(tn * 4);
+    L.tr_rew = take(tn * 4); L.tr_done = take(tn);
+    L.tr_val = take(t1n * 4); L.tr_head = take(t1n * ns.NHP * 4);
+    L.adv = take(tn * 4); L.ret = take(tn * 4); L.dhead = take(tn * ns.NHP * 4);
+    for (int l = 0; l < MAX_LAYERS; ++l) {
+        const size_t w = l < ns.L ? (size_t)ns.dims[l + 1] : 0;
+        L.act[l] = take(tn * w * 4);
+        L.dz[l] = take(tn * w * 4);
+    }
+    for (int l = 0; l < MAX_REGIONS; ++l) {
+        size_t cnt = 0;
+        if (l < ns.L) cnt = (size_t)ns.dims[l] * ns.dims[l + 1] + ns.dims[l + 1];
+        else if (l == ns.L) cnt = (size_t)ns.dims[ns.L] * ns.NH + ns.NH;
+        L.part[l] = take(cnt * 4 * (size_t)(l <= ns.L ? splits[l] : 0));
+    }
+    L.loss_part = take((size_t)loss_blocks * 8 * 4);
+    L.total = off;
+}
+
+static void plan(const NetShape& ns, int B, int T, int* splits, int* loss_blocks)
+{
+    const int M = B * T;
+    for (int l = 0; l < MAX_REGIONS; ++l) splits[l] = 0;
+    for (int l = 0; l < ns.L; ++l) {
+        const int tiles = ((ns.dims[l] + 63) / 64) * ((ns.dims[l + 1] + 63) / 64);
+        splits[l] = pick_splits(M, tiles, 256);
+    }
+    splits[ns.L] = pick_splits(M, 2, 1024);
+    *loss_blocks = (M + WG - 1) / WG;
+}
+
+extern "C" size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin_net_cfg* net, int32_t B, int32_t T)
+{
+    EnvDims ed; NetShape ns; std::string err;
+    if (build_shapes(env, net, B, T, ed, ns, err) != ANAKIN_OK) return 0;
+    int splits[MAX_REGIONS], lb;
+    plan(ns, B, T, splits, &lb);
+    Layout L;
+    carve(ed, ns, B, T, splits, lb, L);
+    return L.total;
+}
+
+// ---- one-time initialisation on the host ----------------------------------
+// Glorot-uniform weights: W = a (2u - 1), a = sqrt(6 / (fan_in + fan_out)); each head
+// group (logits / value / mu / log_sigma) has its own fan_out and its own group id;
+// element e of a group takes word e % 4 of the draw with index e / 4.
+static void init_group(uint64_t seed, uint32_t gid, float* W, int ld, int col0, int fan_in, int fan_out)
+{
+    const float a = (float)sqrt(6.0 / (double)(fan_in + fan_out));
+    for (int i = 0; i < fan_in; ++i)
+        for (int j = 0; j < fan_out; ++j) {
+            const uint32_t e = (uint32_t)(i * fan_out + j);
+            const u32x4 w = philox(seed, e >> 2, gid, DOM_PARAM);
+            const uint32_t word = (e & 3) == 0 ? w.x : (e & 3) == 1 ? w.y : (e & 3) == 2 ? w.z : w.w;
+            W[(size_t)i * ld + col0 + j] = a * fmaf(2.0f, u01(word), -1.0f);
+        }
+}
+
+static void init_params_host(const NetShape& ns, uint64_t seed, std::vector<float>& th)
+{
+    th.assign((size_t)ns.P, 0.0f);
+    uint32_t gid = 0;
+    for (int l = 0; l < ns.L; ++l) init_group(seed, gid++, th.data() + ns.w_off[l], ns.dims[l + 1], 0, ns.dims[l], ns.dims[l + 1]);
+    float* Wh = th.data() + ns.wh_off;
+    const int HL = ns.dims[ns.L];
+    if (ns.policy == POLICY_CATEGORICAL) {
+        init_group(seed, gid++, Wh, ns.NH, 0, HL, ns.A);
+        init_group(seed, gid++, Wh, ns.NH, ns.A, HL, 1);
+    } else {
+        for (int c = 0; c < 3; ++c) init_group(seed, gid++, Wh, ns.NH, c, HL, 1);
+    }
+}
+
+// maze walls for one env: redraw until the goal is reachable from the start
+static void make_maze(const EnvDims& ed, float p_wall, uint64_t seed, int env, uint32_t w[8])
+{
+    const int R = ed.rows, C = ed.cols, n = R * C;
+    const uint32_t thr = (uint32_t)floor((double)p_wall * 4294967296.0);
+    std::vector<int> frontier;
+    std::vector<char> seen((size_t)n);
+    for (uint32_t attempt = 0;; ++attempt) {
+        for (int i = 0; i < 8; ++i) w[i] = 0;
+        for (int blk = 0; blk * 4 < n; ++blk) {
+            const u32x4 d = philox(seed, (uint32_t)env, (uint64_t)attempt | ((uint64_t)blk << 32), DOM_MAZE);
+            const uint32_t ws[4] = {d.x, d.y, d.z, d.w};
+            for (int i = 0; i < 4 && blk * 4 + i < n; ++i)
+                if (ws[i] < thr) w[(blk * 4 + i) >> 5] |= 1u << ((blk * 4 + i) & 31);
+        }
+        w[0] &= ~1u;
+        w[(n - 1) >> 5] &= ~(1u << ((n - 1) & 31));
+        // depth-first reachability from the start cell
+        std::fill(seen.begin(), seen.end(), 0);
+        frontier.clear();
+        frontier.push_back(0); seen[0] = 1;
+        bool ok = false;
+        while (!frontier.empty()) {
+            const int c = frontier.back(); frontier.pop_back();
+            if (c == n - 1) { ok = true; break; }
+            const int r = c / C, col = c % C;
+            const int cand[4] = {r > 0 ? c - C : -1, col + 1 < C ? c + 1 : -1, r + 1 < R ? c + C : -1, col > 0 ? c - 1 : -1};
+            for (int d : cand)
+                if (d >= 0 && !seen[d] && !((w[d >> 5] >> (d & 31)) & 1u)) { seen[d] = 1; frontier.push_back(d); }
+        }
+        if (ok) return;
+    }
+}
+
+#define HIPCHK(h, call)                                                                   \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) {                                                           \
+            (h)->err = std::string(#call) + ": " + hipGetErrorString(e_);                 \
+            return ANAKIN_E_HIP;                                                          \
+        }                                                                                 \
+    } while (0)
+
+static int upload(anakin* h, size_t off, const void* src, size_t bytes)
+{
+    if (bytes == 0) return ANAKIN_OK;
+    HIPCHK(h, hipMemcpyAsync(h->ws + off, src, bytes, hipMemcpyHostToDevice, h->stream));
+    HIPCHK(h, hipStreamSynchronize(h->stream));
+    return ANAKIN_OK;
+}
+static int download(anakin* h, void* dst, size_t off, size_t bytes)
+{
+    if (bytes == 0) return ANAKIN_OK;
+    HIPCHK(h, hipMemcpyAsync(dst, h->ws + off, bytes, hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(h, hipStreamSynchronize(h->stream));
+    return ANAKIN_OK;
+}
+
+// packed <-> row form of the env state
+static void pack_state(const EnvDims& ed, const int32_t* si, const float* sf, uint32_t& s0, float& f0, float& f1)
+{
+    f0 = 0.0f; f1 = 0.0f;
+    if (ed.kind == ENV_CATCH) s0 = catch_pack(si[0], si[1], si[2]);
+    else if (ed.kind == ENV_PENDULUM) { s0 = (uint32_t)si[0]; f0 = sf[0]; f1 = sf[1]; }
+    else s0 = (uint32_t)si[0] | ((uint32_t)si[1] << 16);
+}
+static void unpack_state(const EnvDims& ed, uint32_t s0, float f0, float f1, int32_t* si, float* sf)
+{
+    si[0] = si[1] = si[2] = si[3] = 0; sf[0] = sf[1] = 0.0f;
+    if (ed.kind == ENV_CATCH) { si[0] = (int32_t)(s0 & 0xff); si[1] = (int32_t)((s0 >> 8) & 0xff); si[2] = (int32_t)((s0 >> 16) & 0xff); }
+    else if (ed.kind == ENV_PENDULUM) { si[0] = (int32_t)s0; sf[0] = f0; sf[1] = f1; }
+    else { si[0] = (int32_t)(s0 & 0xffff); si[1] = (int32_t)(s0 >> 16); }
+}
+
+extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, const anakin_net_cfg* net,
+                                 int32_t B, int32_t T, uint64_t seed, void* d_workspace, size_t workspace_bytes,
+                                 void* hip_stream)
+{
+    if (!out) { g_create_error = "null output pointer"; return ANAKIN_E_INVALID_ARG; }
+    *out = nullptr;
+    EnvDims ed; NetShape ns;
+    int rc = build_shapes(env, net, B, T, ed, ns, g_create_error);
+    if (rc != ANAKIN_OK) return rc;
+    if (!d_workspace) { g_create_error = "null workspace"; return ANAKIN_E_INVALID_ARG; }
+    if (((uintptr_t)d_workspace & 255u) != 0) { g_create_error = "workspace must be 256-byte aligned"; return ANAKIN_E_MISALIGNED; }
+    anakin* h = new (std::nothrow) anakin();
+    if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
+    h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
+    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0;
+    h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
+    h->stream = static_cast<hipStream_t>(hip_stream);
+    plan(ns, B, T, h->splits, &h->loss_blocks);
+    carve(ed, ns, B, T, h->splits, h->loss_blocks, h->lay);
+    if (h->lay.total > workspace_bytes) {
+        g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";
+        delete h; return ANAKIN_E_WORKSPACE_TOO_SMALL;
+    }
+    h->TM = rollout_pick_tile(ns, B);
+
+    auto fail = [&](int code) { g_create_error = h->err; delete h; return code; };
+    // parameters and optimiser state
+    std::vector<float> th;
+    init_params_host(ns, seed, th);
+    if ((rc = upload(h, h->lay.theta, th.data(), th.size() * 4)) != ANAKIN_OK) return fail(rc);
+    hipError_t e = hipMemsetAsync(h->ws + h->lay.grad, 0, (size_t)ns.P * 4, h->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.m, 0, (size_t)ns.P * 4, h->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.v, 0, (size_t)ns.P * 4, h->stream);
+    if (e != hipSuccess) { h->err = std::string("hipMemsetAsync: ") + hipGetErrorString(e); return fail(ANAKIN_E_HIP); }
+    // initial env states
+    std::vector<uint32_t> s0((size_t)B), walls(ed.kind == ENV_MAZE ? (size_t)B * 8 : 0);
+    std::vector<float> f0((size_t)B, 0.0f), f1((size_t)B, 0.0f);
+    for (int b = 0; b < B; ++b) {
+        const u32x4 w = philox(seed, (uint32_t)b, 0, DOM_INIT);
+        if (ed.kind == ENV_CATCH) s0[b] = catch_reset(ed, w.x);
+        else if (ed.kind == ENV_PENDULUM) { EnvState st; pendulum_reset(st, w.x, w.y); s0[b] = st.s0; f0[b] = st.f0; f1[b] = st.f1; }
+        else {
+            uint32_t wl[8];
+            make_maze(ed, env->p_wall, seed, b, wl);
+            for (int k = 0; k < 8; ++k) walls[(size_t)k * B + b] = wl[k];      // word-major [8][B]
+            s0[b] = 0;
+        }
+    }
+    if ((rc = upload(h, h->lay.s0, s0.data(), (size_t)B * 4)) != ANAKIN_OK) return fail(rc);
+    if ((rc = upload(h, h->lay.f0, f0.data(), (size_t)B * 4)) != ANAKIN_OK) return fail(rc);
+    if ((rc = upload(h, h->lay.f1, f1.data(), (size_t)B * 4)) != ANAKIN_OK) return fail(rc);
+    if ((rc = upload(h, h->lay.walls, walls.data(), walls.size() * 4)) != ANAKIN_OK) return fail(rc);
+    e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) { h->err = std::string("hipStreamSynchronize: ") + hipGetErrorString(e); return fail(ANAKIN_E_HIP); }
+    *out = h;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_destroy(anakin_t* h)
+{
+    if (!h) return ANAKIN_E_INVALID_ARG;
+    (void)hipStreamSynchronize(h->stream);
+    delete h;
+    return ANAKIN_OK;
+}
+
+namespace ank {
+void fill_rollout_args(anakin* h, RolloutArgs& a)
+{
+    const Layout& L = h->lay;
+    a.env = h->env; a.net = h->net; a.theta = at<const float>(h, L.theta);
+    a.B = h->B; a.T = h->T; a.seed = h->seed; a.gstep = h->gstep;
+    rollout_lds_bytes(h->net, h->env, h->TM, &a.ldx);
+    TrajPtrs& t = a.tp;
+    t.s0 = at<uint32_t>(h, L.s0); t.f0 = at<float>(h, L.f0); t.f1 = at<float>(h, L.f1); t.walls = at<const uint32_t>(h, L.walls);
+    t.tr_s0 = at<uint32_t>(h, L.tr_s0); t.tr_f0 = at<float>(h, L.tr_f0); t.tr_f1 = at<float>(h, L.tr_f1);
+    t.tr_act = at<uint8_t>(h, L.tr_act); t.tr_eps = at<float>(h, L.tr_eps); t.tr_actf = at<float>(h, L.tr_actf);
+    t.tr_rew = at<float>(h, L.tr_rew); t.tr_done = at<uint8_t>(h, L.tr_done);
+    t.tr_val = at<float>(h, L.tr_val); t.tr_head = at<float>(h, L.tr_head);
+    for (int l = 0; l < MAX_LAYERS; ++l) t.act[l] = at<float>(h, L.act[l]);
+}
+}  // namespace ank
+
+#define NEED(h) do { if (!(h)) return ANAKIN_E_INVALID_ARG; } while (0)
+
+extern "C" int32_t anakin_rollout(anakin_t* h)
+{
+    NEED(h);
+    HIPCHK(h, launch_rollout(h));
+    h->gstep += (uint64_t)h->T;
+    h->have_traj = 1;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_learn(anakin_t* h)
+{
+    NEED(h);
+    if (!h->have_traj) { h->err = "learn needs a stored trajectory: call anakin_rollout first"; return ANAKIN_E_STATE; }
+    HIPCHK(h, launch_returns(h));
+    HIPCHK(h, launch_head_grad(h));
+    HIPCHK(h, launch_backward(h));
+    HIPCHK(h, launch_adam(h));
+    h->have_traj = 0;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_step(anakin_t* h)
+{
+    int32_t rc = anakin_rollout(h);
+    if (rc != ANAKIN_OK) return rc;
+    return anakin_learn(h);
+}
+
+// ---- introspection ----------------------------------------------------------
+extern "C" int32_t anakin_param_count(const anakin_t* h, int64_t* out)
+{
+    if (!h || !out) return ANAKIN_E_INVALID_ARG;
+    *out = h->net.P;
+    return ANAKIN_OK;
+}
+
+static int check_n(anakin* h, const void* p, size_t n)
+{
+    if (!p) { h->err = "null pointer"; return ANAKIN_E_INVALID_ARG; }
+    if (n != (size_t)h->net.P) { h->err = "length must equal the parameter count"; return ANAKIN_E_INVALID_ARG; }
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_get_params(anakin_t* h, float* dst, size_t n)
+{
+    NEED(h); int rc = check_n(h, dst, n); if (rc) return rc;
+    return download(h, dst, h->lay.theta, n * 4);
+}
+extern "C" int32_t anakin_set_params(anakin_t* h, const float* src, size_t n)
+{
+    NEED(h); int rc = check_n(h, src, n); if (rc) return rc;
+    return upload(h, h->lay.theta, src, n * 4);
+}
+extern "C" int32_t anakin_get_grads(anakin_t* h, float* dst, size_t n)
+{
+    NEED(h); int rc = check_n(h, dst, n); if (rc) return rc;
+    return download(h, dst, h->lay.grad, n * 4);
+}
+extern "C" int32_t anakin_get_opt_state(anakin_t* h, float* m, float* v, int32_t* step, size_t n)
+{
+    NEED(h); int rc = check_n(h, m, n); if (rc) return rc;
+    rc = check_n(h, v, n); if (rc) return rc;
+    if (!step) return ANAKIN_E_INVALID_ARG;
+    if ((rc = download(h, m, h->lay.m, n * 4)) != ANAKIN_OK) return rc;
+    if ((rc = download(h, v, h->lay.v, n * 4)) != ANAKIN_OK) return rc;
+    *step = h->adam_t;
+    return ANAKIN_OK;
+}
+extern "C" int32_t anakin_set_opt_state(anakin_t* h, const float* m, const float* v, int32_t step, size_t n)
+{
+    NEED(h); int rc = check_n(h, m, n); if (rc) return rc;
+    rc = check_n(h, v, n); if (rc) return rc;
+    if (step < 0) { h->err = "negative step"; return ANAKIN_E_INVALID_ARG; }
+    if ((rc = upload(h, h->lay.m, m, n * 4)) != ANAKIN_OK) return rc;
+    if ((rc = upload(h, h->lay.v, v, n * 4)) != ANAKIN_OK) return rc;
+    h->adam_t = step;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_get_env_state(anakin_t* h, int32_t* si, float* sf)
+{
+    NEED(h);
+    if (!si || !sf) return ANAKIN_E_INVALID_ARG;
+    const size_t B = (size_t)h->B;
+    std::vector<uint32_t> s0(B); std::vector<float> f0(B), f1(B);
+    int rc;
+    if ((rc = download(h, s0.data(), h->lay.s0, B * 4)) != ANAKIN_OK) return rc;
+    if ((rc = download(h, f0.data(), h->lay.f0, B * 4)) != ANAKIN_OK) return rc;
+    if ((rc = download(h, f1.data(), h->lay.f1, B * 4)) != ANAKIN_OK) return rc;
+    for (size_t b = 0; b < B; ++b) unpack_state(h->env, s0[b], f0[b], f1[b], si + b * 4, sf + b * 2);
+    return ANAKIN_OK;
+}
+extern "C" int32_t anakin_set_env_state(anakin_t* h, const int32_t* si, const float* sf)
+{
+    NEED(h);
+    if (!si || !sf) return ANAKIN_E_INVALID_ARG;
+    const size_t B = (size_t)h->B;
+    std::vector<uint32_t> s0(B); std::vector<float> f0(B), f1(B);
+    for (size_t b = 0; b < B; ++b) {
+        const int32_t* s = si + b * 4;
+        bool ok = true;
+        if (h->env.kind == ENV_CATCH) ok = s[0] >= 0 && s[0] < h->env.cols && s[1] >= 0 && s[1] < h->env.rows - 1 && s[2] >= 0 && s[2] < h->env.cols;
+        else if (h->env.kind == ENV_PENDULUM) ok = s[0] >= 0 && s[0] < h->env.max_steps;
+        else ok = s[0] >= 0 && s[0] < h->env.rows * h->env.cols && s[1] >= 0 && s[1] < h->env.max_steps;
+        if (!ok) { h->err = "env state out of range"; return ANAKIN_E_INVALID_ARG; }
+        pack_state(h->env, s, sf + b * 2, s0[b], f0[b], f1[b]);
+    }
+    int rc;
+    if ((rc = upload(h, h->lay.s0, s0.data(), B * 4)) != ANAKIN_OK) return rc;
+    if ((rc = upload(h, h->lay.f0, f0.data(), B * 4)) != ANAKIN_OK) return rc;
+    return upload(h, h->lay.f1, f1.data(), B * 4);
+}
+extern "C" int32_t anakin_get_walls(anakin_t* h, uint32_t* out)
+{
+    NEED(h);
+    if (!out) return ANAKIN_E_INVALID_ARG;
+    if (h->env.kind != ENV_MAZE) { h->err = "walls exist for the maze only"; return ANAKIN_E_STATE; }
+    const size_t B = (size_t)h->B;
+    std::vector<uint32_t> w(B * 8);
+    int rc = download(h, w.data(), h->lay.walls, B * 8 * 4);
+    if (rc) return rc;
+    for (size_t b = 0; b < B; ++b) for (int k = 0; k < 8; ++k) out[b * 8 + k] = w[(size_t)k * B + b];
+    return ANAKIN_OK;
+}
+extern "C" int32_t anakin_get_global_step(const anakin_t* h, uint64_t* out)
+{
+    if (!h || !out) return ANAKIN_E_INVALID_ARG;
+    *out = h->gstep;
+    return ANAKIN_OK;
+}
+extern "C" int32_t anakin_set_global_step(anakin_t* h, uint64_t g) { NEED(h); h->gstep = g; return ANAKIN_OK; }
+
+extern "C" int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* v)
+{
+    NEED(h);
+    if (!v) return ANAKIN_E_INVALID_ARG;
+    HIPCHK(h, hipStreamSynchronize(h->stream));
+    const Layout& L = h->lay;
+    memset(v, 0, sizeof *v);
+    v->B = h->B; v->T = h->T; v->num_heads = h->net.NH; v->head_stride = h->net.NHP; v->n_hidden = h->net.L;
+    for (int l = 0; l < h->net.L; ++l) v->hidden[l] = h->net.dims[l + 1];
+    v->act_is_bf16 = 0;
+#define SETP(field, off) v->field = h->ws + (off); v->off_##field = (off)
+    SETP(state_s0, L.tr_s0); SETP(state_f0, L.tr_f0); SETP(state_f1, L.tr_f1);
+    SETP(action, L.tr_act); SETP(eps, L.tr_eps); SETP(action_f, L.tr_actf);
+    SETP(reward, L.tr_rew); SETP(done, L.tr_done); SETP(value, L.tr_val); SETP(head, L.tr_head);
+    SETP(adv, L.adv); SETP(ret, L.ret);
+#undef SETP
+    for (int l = 0; l < h->net.L; ++l) { v->act[l] = h->ws + L.act[l]; v->off_act[l] = L.act[l]; }
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out)
+{
+    NEED(h);
+    if (!out) return ANAKIN_E_INVALID_ARG;
+    std::vector<float> part((size_t)h->loss_blocks * 8);
+    int rc = download(h, part.data(), h->lay.loss_part, part.size() * 4);
+    if (rc) return rc;
+    double s[5] = {0, 0, 0, 0, 0};
+    for (int b = 0; b < h->loss_blocks; ++b) for (int k = 0; k < 5; ++k) s[k] += (double)part[(size_t)b * 8 + k];
+    const double M = (double)h->B * h->T;
+    out->policy_loss = s[0] / M; out->value_loss = s[1] / M; out->entropy_loss = s[2] / M;
+    out->loss = out->policy_loss + out->value_loss + out->entropy_loss;
+    out->reward_sum = s[3];
+    out->episodes = (int64_t)llround(s[4]);
+    out->nonfinite = !(isfinite(out->loss) && isfinite(out->reward_sum));
+    return out->nonfinite ? ANAKIN_E_NONFINITE : ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_set_mode(anakin_t* h, int32_t flags)
+{
+    NEED(h);
+    if (flags & ~(ANAKIN_MODE_VALU_GEMM | ANAKIN_MODE_CANONICAL_ACTING)) { h->err = "unknown mode flag"; return ANAKIN_E_INVALID_ARG; }
+    h->mode = flags;
+    return ANAKIN_OK;
+}
+
+extern "C" const char* anakin_last_error(const anakin_t* h)
+{
+    return h ? h->err.c_str() : g_create_error.c_str();
+}

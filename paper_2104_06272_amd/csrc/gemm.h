@@ -1,0 +1,37 @@
+// Argument blocks of the dense-layer backward kernels (vector-ALU and
+// matrix-core versions take the same ones).
+#pragma once
+#include "internal.h"
+
+namespace ank {
+
+// where the first layer's input comes from: the compact state snapshots
+struct ObsSrc {
+    int kind, B;
+    EnvDims env;
+    const uint32_t* s0; const float* f0; const float* f1;   // [T+1][B], row m = t*B + b
+    const uint32_t* walls;                                   // [8][B]
+};
+
+// dX[m][i] = (x[m][i] > 0) * sum_j dY[m][j] W[i][j];  W is [K][N] row-major (K = inputs, N = outputs)
+struct GemmNtArgs {
+    int M, K, N, bf16;
+    const float* dy;      // [M][N]
+    const float* w;       // [K][N]
+    const float* x;       // [M][K] forward activations (relu mask)
+    float* dx;            // [M][K]
+};
+
+// partial[s][i][j] = sum over rows of chunk s of x[m][i] dY[m][j]; partial[s][K*N + j] = column sums of dY
+struct GemmTnArgs {
+    int M, K, N, bf16, splits, rows, tiles_i, use_obs;
+    const float* x;       // [M][K], unused when use_obs
+    const float* dy;      // [M][N]
+    float* partial;       // [splits][K*N + N]
+    ObsSrc obs;
+};
+
+hipError_t launch_gemm_nt_valu(const GemmNtArgs& a, hipStream_t s);
+hipError_t launch_gemm_tn_valu(GemmTnArgs a, hipStream_t s);
+
+}  // namespace ank

@@ -1,0 +1,105 @@
+// Host-side handle, device workspace layout and kernel argument blocks shared by
+// the translation units of libanakin.  Nothing here is part of the public ABI.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <hip/hip_runtime.h>
+#include "env.cuh"
+#include "../../include/anakin.h"
+
+namespace ank {
+
+constexpr int MAX_LAYERS = 4;
+constexpr int MAX_REGIONS = MAX_LAYERS + 1;      // one (W,b) pair per hidden layer + the heads
+constexpr int WG = 256;                          // threads per workgroup everywhere
+
+// network shape and parameter offsets (elements into theta)
+struct NetShape {
+    int D, A, NH, NHP, L;
+    int dims[MAX_LAYERS + 2];                    // D, H1..HL
+    int w_off[MAX_LAYERS], b_off[MAX_LAYERS], wh_off, bh_off;
+    int P;
+    int policy, bf16;
+};
+
+// trajectory and env-state pointers (device)
+struct TrajPtrs {
+    uint32_t* s0; float* f0; float* f1; const uint32_t* walls;        // current env state; walls [8][B]
+    uint32_t* tr_s0; float* tr_f0; float* tr_f1;                       // [T+1][B] state observed at t
+    uint8_t* tr_act; float* tr_eps; float* tr_actf;                    // [T][B]
+    float* tr_rew; uint8_t* tr_done;                                   // [T][B]
+    float* tr_val;                                                     // [T+1][B]
+    float* tr_head;                                                    // [T+1][B][NHP]
+    float* act[MAX_LAYERS];                                            // [T*B][H_l] hidden activations
+};
+
+struct RolloutArgs {
+    EnvDims env;
+    NetShape net;
+    TrajPtrs tp;
+    const float* theta;
+    int B, T, ldx;
+    uint64_t seed, gstep;
+};
+
+// split-K partial sums of one parameter region (W_l followed by b_l, or Wh followed by bh)
+struct Region { int start, count, splits; const float* partial; };
+
+struct AdamArgs {
+    Region reg[MAX_REGIONS];
+    int n_regions, P;
+    float* theta; float* grad; float* m; float* v;
+    uint16_t* w_bf16;            // bf16 copy of theta (same indexing), or null
+    uint16_t* wt_bf16;           // bf16 copy with every weight matrix transposed, or null
+    NetShape net;
+    float lr, beta1, beta2, eps, bc1, bc2;
+};
+
+struct Layout {
+    size_t theta, grad, m, v, w_bf16, wt_bf16;
+    size_t s0, f0, f1, walls;
+    size_t tr_s0, tr_f0, tr_f1, tr_act, tr_eps, tr_actf, tr_rew, tr_done, tr_val, tr_head;
+    size_t adv, ret, dhead;
+    size_t act[MAX_LAYERS], dz[MAX_LAYERS];
+    size_t part[MAX_REGIONS];
+    size_t loss_part;
+    size_t total;
+};
+
+}  // namespace ank
+
+struct anakin {
+    anakin_env_cfg env_cfg;
+    anakin_net_cfg net_cfg;
+    ank::EnvDims env;
+    ank::NetShape net;
+    int B, T;
+    uint64_t seed, gstep;
+    int adam_t;
+    int have_traj;
+    int mode;
+    char* ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+    ank::Layout lay;
+    int TM;                       // envs per workgroup in the rollout kernel
+    int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
+    int loss_blocks;
+    std::string err;
+};
+
+namespace ank {
+
+template <class T> inline T* at(const anakin* h, size_t off) { return reinterpret_cast<T*>(h->ws + off); }
+
+// kernel launchers (each enqueues on h->stream and returns the HIP status)
+hipError_t launch_rollout(anakin* h);
+hipError_t launch_returns(anakin* h);
+hipError_t launch_head_grad(anakin* h);
+hipError_t launch_backward(anakin* h);
+hipError_t launch_adam(anakin* h);
+int rollout_pick_tile(const NetShape& net, int B);
+size_t rollout_lds_bytes(const NetShape& net, const EnvDims& env, int TM, int* ldx);
+
+}  // namespace ank

@@ -1,0 +1,305 @@
+// The update on a stored unroll (paper section 3.1: the parameter update that
+// follows the T interactions and reuses the policy's forward pass):
+//   returns_scan   reverse scan over t of the lambda-return recursion
+//   head_grad      actor-critic loss terms and the gradient w.r.t. head outputs
+//   head_backward  gradient of the head matrix, and of the last hidden layer
+//   adam_reduce    fixed-order sum of split-K partials fused with Adam
+// Hidden-layer GEMMs live in gemm.hip.  No floating-point atomics anywhere:
+// every reduction has a fixed order, so runs are reproducible bit for bit.
+#include "internal.h"
+
+namespace ank {
+
+// ---------------------------------------------------------------------------
+// G_T = V(s_T);  G_t = r + disc ((1-lambda) V_{t+1} + lambda G_{t+1});  A_t = G_t - V_t
+// with disc = 0 after an episode end, gamma otherwise.  One lane per env walks
+// its column backwards; consecutive lanes touch consecutive addresses of the
+// time-major arrays, so every load and store is fully coalesced.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(WG) void returns_scan(int B, int T, const float* __restrict__ rew,
+                                                   const uint8_t* __restrict__ done, const float* __restrict__ val,
+                                                   float gamma, float lambda, float* __restrict__ adv,
+                                                   float* __restrict__ ret)
+{
+    const int b = blockIdx.x * WG + threadIdx.x;
+    if (b >= B) return;
+    const float oml = 1.0f - lambda;
+    float G = val[(size_t)T * B + b];
+    float vnext = G;
+#pragma unroll 4
+    for (int t = T - 1; t >= 0; --t) {
+        const size_t i = (size_t)t * B + b;
+        const float r = rew[i], v = val[i];
+        const float disc = done[i] ? 0.0f : gamma;
+        const float mix = fmaf(lambda, G, oml * vnext);
+        G = fmaf(disc, mix, r);
+        ret[i] = G;
+        adv[i] = G - v;
+        vnext = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per sample: l = -A log pi(a|s) + c_v (G - V)^2 - beta H, and d l / d head / M.
+// Categorical: d/dlogit_i = -A (1[i=a] - p_i) + beta p_i (log p_i + H).
+// Gaussian (score function at the stored noise, log_sigma clamped to [-5,2]):
+// d/dmu = -A eps / sigma, d/dlog_sigma = -A (eps^2 - 1) - beta (0 when clamped).
+// Also block sums of the loss terms, rewards and episode ends for the metrics.
+// ---------------------------------------------------------------------------
+struct HeadGradArgs {
+    int M, A, NH, NHP, policy;
+    const float* head; const uint8_t* act; const float* eps; const float* adv; const float* ret;
+    const float* rew; const uint8_t* done;
+    float* dhead; float* loss_part;        // [blocks][8]
+    float beta, cv, inv_m;
+};
+
+__global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
+{
+    __shared__ float red[WG / 64][8];
+    const int i = blockIdx.x * WG + threadIdx.x;
+    float lp_term = 0.0f, v_term = 0.0f, e_term = 0.0f, rsum = 0.0f, dcount = 0.0f;
+    if (i < a.M) {
+        const float* h = a.head + (size_t)i * a.NHP;
+        float hv[8];
+        const float4 h0 = *reinterpret_cast<const float4*>(h);
+        hv[0] = h0.x; hv[1] = h0.y; hv[2] = h0.z; hv[3] = h0.w;
+        if (a.NHP == 8) {
+            const float4 h1 = *reinterpret_cast<const float4*>(h + 4);
+            hv[4] = h1.x; hv[5] = h1.y; hv[6] = h1.z; hv[7] = h1.w;
+        } else { hv[4] = hv[5] = hv[6] = hv[7] = 0.0f; }
+        const float A_ = a.adv[i], G_ = a.ret[i];
+        float V = hv[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) if (j == a.NH - 1) V = hv[j];
+        float d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        const float dv = G_ - V;
+        v_term = a.cv * dv * dv;
+        const float gV = -2.0f * a.cv * dv * a.inv_m;
+        if (a.policy == POLICY_CATEGORICAL) {
+            const int act = a.act[i];
+            float mx = hv[0];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) if (j < a.A) mx = fmaxf(mx, hv[j]);
+            float e[8], Z = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { e[j] = (j < a.A) ? det_exp(hv[j] - mx) : 0.0f; Z += e[j]; }
+            const float logZ = det_log(Z), invZ = 1.0f / Z;
+            float H = 0.0f, lpa = 0.0f, p[8], lp[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                lp[j] = hv[j] - mx - logZ;
+                p[j] = e[j] * invZ;
+                if (j < a.A) H -= p[j] * lp[j];
+                if (j == act) lpa = lp[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < a.A) d[j] = (-A_ * ((j == act ? 1.0f : 0.0f) - p[j]) + a.beta * p[j] * (lp[j] + H)) * a.inv_m;
+            lp_term = -A_ * lpa;
+            e_term = -a.beta * H;
+        } else {
+            const float ls = hv[1];
+            const bool clamped = ls < -5.0f || ls > 2.0f;
+            const float lsc = fminf(fmaxf(ls, -5.0f), 2.0f);
+            const float sigma = det_exp(lsc), ep = a.eps[i];
+            d[0] = (-A_ * ep / sigma) * a.inv_m;
+            d[1] = clamped ? 0.0f : (-A_ * (ep * ep - 1.0f) - a.beta) * a.inv_m;
+            lp_term = -A_ * (-0.5f * ep * ep - lsc - 0x1.d67f1cp-1f);
+            e_term = -a.beta * (lsc + 0x1.6b3f8ep+0f);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) if (j == a.NH - 1) d[j] = gV;
+        float* o = a.dhead + (size_t)i * a.NHP;
+        *reinterpret_cast<float4*>(o) = make_float4(d[0], d[1], d[2], d[3]);
+        if (a.NHP == 8) *reinterpret_cast<float4*>(o + 4) = make_float4(d[4], d[5], d[6], d[7]);
+        rsum = a.rew[i];
+        dcount = a.done[i] ? 1.0f : 0.0f;
+    }
+    // fixed-order block reduction: butterfly inside a wave, then waves in order
+    float vals[5] = {lp_term, v_term, e_term, rsum, dcount};
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+        for (int off = 32; off > 0; off >>= 1) vals[k] += __shfl_xor(vals[k], off, 64);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0)
+        for (int k = 0; k < 5; ++k) red[wave][k] = vals[k];
+    __syncthreads();
+    if (threadIdx.x < 8) {
+        float s = 0.0f;
+        if (threadIdx.x < 5)
+            for (int w = 0; w < WG / 64; ++w) s += red[w][threadIdx.x];
+        a.loss_part[(size_t)blockIdx.x * 8 + threadIdx.x] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Heads: dWh[j][a] = sum_m h[m][j] dhead[m][a], dbh[a] = sum_m dhead[m][a] (per
+// row chunk, as split-K partials) and dZ[m][j] = (h[m][j] > 0) sum_a Wh[j][a]
+// dhead[m][a].  K = NH <= 5 is no matrix-core shape: plain vector FMAs, one
+// pass over h (read) and dZ (write), both coalesced.
+// A workgroup handles `rows` consecutive samples; when the hidden width is
+// below 256 several rows are processed side by side and their partial sums are
+// combined through LDS in a fixed order.
+// ---------------------------------------------------------------------------
+struct HeadBwdArgs {
+    int M, H, NH, NHP, rows;
+    const float* h; const float* dhead; const float* wh;   // wh: theta + wh_off, [H][NH]
+    float* dz; float* partial;                             // partial: [splits][H*NH + NH]
+    int bf16;
+};
+
+__global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
+{
+    extern __shared__ float lds[];                          // [groups][H*NH + NH] for the final combine
+    const int H = a.H, NH = a.NH, NHP = a.NHP;
+    const int jblocks = (H + WG - 1) / WG;                  // 1 unless H > 256
+    const int hw = H < WG ? H : WG;                         // threads across the hidden dimension
+    const int groups = WG / hw;                             // rows processed side by side
+    const int g = threadIdx.x / hw, jl = threadIdx.x % hw;
+    const int split = blockIdx.x / jblocks, jb = blockIdx.x % jblocks;
+    const int j = jb * WG + jl;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    float w[8], dw[8], db[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float x = (k < NH) ? a.wh[(size_t)j * NH + k] : 0.0f;
+        if (a.bf16) x = bf16_to_f(bf16_bits(x));
+        w[k] = x; dw[k] = 0.0f; db[k] = 0.0f;
+    }
+    for (int m = m_begin + g; m < m_end; m += groups) {
+        const float* dh = a.dhead + (size_t)m * NHP;
+        float d[8];
+        const float4 d0 = *reinterpret_cast<const float4*>(dh);
+        d[0] = d0.x; d[1] = d0.y; d[2] = d0.z; d[3] = d0.w;
+        if (NHP == 8) {
+            const float4 d1 = *reinterpret_cast<const float4*>(dh + 4);
+            d[4] = d1.x; d[5] = d1.y; d[6] = d1.z; d[7] = d1.w;
+        } else { d[4] = d[5] = d[6] = d[7] = 0.0f; }
+        const float hv = a.h[(size_t)m * H + j];
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (k < NH) {
+                s = fmaf(w[k], d[k], s);
+                dw[k] = fmaf(hv, d[k], dw[k]);
+                db[k] += d[k];
+            }
+        }
+        a.dz[(size_t)m * H + j] = hv > 0.0f ? s : 0.0f;
+    }
+    // combine the row groups in ascending group order
+    const int stride = H * NH + NH;
+    float* out = a.partial + (size_t)split * stride;
+    if (groups == 1) {
+        for (int k = 0; k < NH; ++k) out[(size_t)j * NH + k] = dw[k];
+        if (j == 0) for (int k = 0; k < NH; ++k) out[(size_t)H * NH + k] = db[k];
+        return;
+    }
+    float* mine = lds + (size_t)g * stride;
+    for (int k = 0; k < NH; ++k) mine[j * NH + k] = dw[k];
+    if (jl == 0) for (int k = 0; k < NH; ++k) mine[H * NH + k] = db[k];
+    __syncthreads();
+    for (int i = threadIdx.x; i < stride; i += WG) {
+        float s = 0.0f;
+        for (int gg = 0; gg < groups; ++gg) s += lds[(size_t)gg * stride + i];
+        out[i] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Adam with the gradient reduction fused in: g = sum over split-K partials in
+// ascending split order, then m, v, theta.  Streams theta, m, v once in and
+// once out (28 bytes per parameter besides the partials).  For bf16 networks
+// the rounded copies the matrix-core kernels read are refreshed here too.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(WG) void adam_reduce(const AdamArgs a)
+{
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i >= a.P) return;
+    int r = 0;
+#pragma unroll
+    for (int k = 1; k < MAX_REGIONS; ++k) if (k < a.n_regions && i >= a.reg[k].start) r = k;
+    const Region rg = a.reg[r];
+    const float* p = rg.partial + (i - rg.start);
+    float g = 0.0f;
+    for (int s = 0; s < rg.splits; ++s) g += p[(size_t)s * rg.count];
+    const float m = a.beta1 * a.m[i] + (1.0f - a.beta1) * g;
+    const float v = a.beta2 * a.v[i] + (1.0f - a.beta2) * g * g;
+    const float mh = m / a.bc1, vh = v / a.bc2;
+    const float th = a.theta[i] - a.lr * mh / (sqrtf(vh) + a.eps);
+    a.grad[i] = g;
+    a.m[i] = m;
+    a.v[i] = v;
+    a.theta[i] = th;
+    if (a.w_bf16) a.w_bf16[i] = bf16_bits(th);
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+hipError_t launch_returns(anakin* h)
+{
+    const Layout& L = h->lay;
+    hipLaunchKernelGGL(returns_scan, dim3((h->B + WG - 1) / WG), dim3(WG), 0, h->stream, h->B, h->T,
+                       at<const float>(h, L.tr_rew), at<const uint8_t>(h, L.tr_done), at<const float>(h, L.tr_val),
+                       h->net_cfg.gamma, h->net_cfg.lambda_, at<float>(h, L.adv), at<float>(h, L.ret));
+    return hipGetLastError();
+}
+
+hipError_t launch_head_grad(anakin* h)
+{
+    const Layout& L = h->lay;
+    HeadGradArgs a;
+    a.M = h->B * h->T; a.A = h->net.A; a.NH = h->net.NH; a.NHP = h->net.NHP; a.policy = h->net.policy;
+    a.head = at<const float>(h, L.tr_head); a.act = at<const uint8_t>(h, L.tr_act); a.eps = at<const float>(h, L.tr_eps);
+    a.adv = at<const float>(h, L.adv); a.ret = at<const float>(h, L.ret);
+    a.rew = at<const float>(h, L.tr_rew); a.done = at<const uint8_t>(h, L.tr_done);
+    a.dhead = at<float>(h, L.dhead); a.loss_part = at<float>(h, L.loss_part);
+    a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef; a.inv_m = (float)(1.0 / (double)a.M);
+    hipLaunchKernelGGL(head_grad, dim3(h->loss_blocks), dim3(WG), 0, h->stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_head_backward(anakin* h)
+{
+    const Layout& L = h->lay;
+    const NetShape& n = h->net;
+    HeadBwdArgs a;
+    a.M = h->B * h->T; a.H = n.dims[n.L]; a.NH = n.NH; a.NHP = n.NHP;
+    const int splits = h->splits[n.L];
+    a.rows = a.M / splits;
+    a.h = at<const float>(h, L.act[n.L - 1]); a.dhead = at<const float>(h, L.dhead);
+    a.wh = at<const float>(h, L.theta) + n.wh_off;
+    a.dz = at<float>(h, L.dz[n.L - 1]); a.partial = at<float>(h, L.part[n.L]);
+    a.bf16 = n.bf16;
+    const int jblocks = (a.H + WG - 1) / WG;
+    const int hw = a.H < WG ? a.H : WG;
+    const int groups = WG / hw;
+    const size_t lds = groups > 1 ? (size_t)groups * (a.H * a.NH + a.NH) * sizeof(float) : 0;
+    hipLaunchKernelGGL(head_backward, dim3(splits * jblocks), dim3(WG), lds, h->stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_adam(anakin* h)
+{
+    const Layout& L = h->lay;
+    const NetShape& n = h->net;
+    AdamArgs a;
+    a.n_regions = n.L + 1; a.P = n.P;
+    for (int l = 0; l < n.L; ++l)
+        a.reg[l] = Region{n.w_off[l], n.dims[l] * n.dims[l + 1] + n.dims[l + 1], h->splits[l], at<const float>(h, L.part[l])};
+    a.reg[n.L] = Region{n.wh_off, n.dims[n.L] * n.NH + n.NH, h->splits[n.L], at<const float>(h, L.part[n.L])};
+    for (int l = n.L + 1; l < MAX_REGIONS; ++l) a.reg[l] = Region{0x7fffffff, 0, 0, nullptr};
+    a.theta = at<float>(h, L.theta); a.grad = at<float>(h, L.grad); a.m = at<float>(h, L.m); a.v = at<float>(h, L.v);
+    a.w_bf16 = nullptr; a.wt_bf16 = nullptr;
+    a.net = n;
+    h->adam_t += 1;
+    a.lr = h->net_cfg.lr; a.beta1 = h->net_cfg.beta1; a.beta2 = h->net_cfg.beta2; a.eps = h->net_cfg.eps;
+    a.bc1 = (float)(1.0 - pow((double)h->net_cfg.beta1, (double)h->adam_t));
+    a.bc2 = (float)(1.0 - pow((double)h->net_cfg.beta2, (double)h->adam_t));
+    hipLaunchKernelGGL(adam_reduce, dim3((n.P + WG - 1) / WG), dim3(WG), 0, h->stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace ank
