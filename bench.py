@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Throughput of the Anakin actor-learner step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload catch_4096]
+
+A step is one pass of the whole hot path (unroll of T interactions for B envs,
+then one update) through the C ABI.  Prints ONE JSON line: env-steps/s over K
+steps, the roofline of the dominant kernel (per-kernel durations from HIP
+events recorded on the launch stream in a second, instrumented pass of the
+same K steps), and the CPU oracle timed on a bounded sample of the workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT,):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+# published MI355X peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_FP32_TFLOPS = 157.3      # fp32 vector (packed) = fp32 matrix-core peak
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def kernel_models(cfg, P):
+    """Algorithmic work per launch of each kernel: (bound, amount, unit-peak, unit)."""
+    B, T = cfg["B"], cfg["T"]
+    M = B * T
+    kind = cfg["env"]["kind"]
+    hid = cfg["net"]["hidden"]
+    D = {"catch": 50, "pendulum": 3, "maze": 768}[kind]
+    NH = 3 if kind == "pendulum" else ({"catch": 3, "maze": 4}[kind] + 1)
+    dims = [D] + hid
+    # effective input count of the first layer: a one-hot board adds only its set rows
+    first_rows = {"catch": 2, "pendulum": 3, "maze": 53}[kind]
+    w_act = first_rows * dims[1] + sum(dims[i] * dims[i + 1] for i in range(1, len(dims) - 1)) + dims[-1] * NH
+    bf16 = cfg["net"].get("dtype") == "bf16"
+    mfma_peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    snap = {"catch": 4, "pendulum": 8, "maze": 2}[kind]
+    models = {
+        # acting: fp32 FMAs of the canonical forward, (T+1) evaluations per env
+        "rollout": ("alu", 2.0 * w_act * B * (T + 1) / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"),
+        # 17 B per (t,b): read r 4 + done 1 + V 4, write A 4 + G 4
+        "returns_scan": ("hbm", 17.0 * M / 1e9, PEAK_HBM_GBS, "GB/s"),
+        # 28 B per parameter: read theta,g,m,v, write theta,m,v
+        "adam_reduce": ("hbm", 28.0 * P / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "head_grad": ("hbm", (NH * 4 + 1 + 8 + NH * 4) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "head_backward": ("hbm", (8.0 * dims[-1] + 4 * NH) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
+    }
+    tn = sum(2.0 * dims[i] * dims[i + 1] * M for i in range(1, len(dims) - 1))
+    nt = tn
+    models["gemm_tn"] = ("mfma", tn / 1e12, mfma_peak, "TFLOP/s")
+    models["gemm_nt_mask"] = ("mfma", nt / 1e12, mfma_peak, "TFLOP/s")
+    models["gemm_tn_obs"] = ("mfma", 2.0 * dims[0] * dims[1] * M / 1e12, mfma_peak, "TFLOP/s")
+    return models, snap
+
+
+def cpu_baseline(cfg, budget_s=20.0):
+    """The oracle as it stands, single-threaded, on a bounded sample: the same network, T and
+    hyper-parameters with B cut so that one full step takes roughly the budget."""
+    from oracle import oracle as O
+    from paper_2104_06272_amd import workloads as W
+    probe_B = 16
+    c = dict(cfg); c["B"] = probe_B
+    o = O.Oracle(c, seed=0)
+    t0 = time.perf_counter(); o.step(); dt = time.perf_counter() - t0
+    per_env = max(dt / probe_B, 1e-9)
+    B = int(max(16, min(cfg["B"], (budget_s / per_env) // 16 * 16)))
+    c["B"] = B
+    o = O.Oracle(c, seed=0)
+    t0 = time.perf_counter(); o.step(); dt = time.perf_counter() - t0
+    return {"value": B * cfg["T"] / dt, "unit": "env steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"1 full step (rollout + update) at B={B} of {cfg['B']} envs, T={cfg['T']}, same network; "
+                      f"{dt:.1f} s single-threaded"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="catch_4096")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--valu-gemm", action="store_true", help="learn-phase GEMMs on vector ALUs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2104_06272_amd import binding, workloads as W
+    cfg = W.get(args.workload)
+    torch.cuda.set_device(0)
+    g = binding.Anakin(cfg, seed=0, device="cuda:0")
+    if args.valu_gemm:
+        g.set_mode(binding.MODE_VALU_GEMM)
+    for _ in range(max(args.warmup, 1)):
+        g.step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(g.stream)
+    for _ in range(args.steps):
+        g.step()
+    e1.record(g.stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1)
+    ms_per_step = ms / args.steps
+    value = cfg["B"] * cfg["T"] * args.steps / (ms / 1e3)
+    metrics = g.metrics()
+
+    # instrumented pass: the same K steps with two events around every kernel launch
+    g.profile(True)
+    for _ in range(args.steps):
+        g.step()
+    times = g.kernel_times()
+    g.profile(False)
+    models, _ = kernel_models(cfg, g.P)
+    per_kernel = {}
+    for name, (calls, total) in times.items():
+        launches_per_step = calls / args.steps
+        avg_us = total / calls * 1e3
+        entry = {"calls_per_step": launches_per_step, "avg_us": round(avg_us, 2),
+                 "us_per_step": round(total / args.steps * 1e3, 2)}
+        if name in models:
+            bound, amount, peak, unit = models[name]
+            per_launch = amount / launches_per_step
+            ach = per_launch / (avg_us * 1e-6) * (1.0 if unit == "TFLOP/s" else 1.0)
+            entry.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit,
+                          "frac": round(ach / peak, 4)})
+        per_kernel[name] = entry
+    dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
+    d = per_kernel[dominant]
+    roofline = {"kernel": dominant, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
+                "unit": d.get("unit"), "frac": d.get("frac"), "traffic": None,
+                "avg_launch_us": d["avg_us"]}
+    out = {
+        "metric": "env steps/sec (rollout+learn) on 1 MI355X", "value": value, "unit": "env steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["net"].get("dtype") == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "env": cfg["env"]["kind"], "B": cfg["B"], "T": cfg["T"],
+                   "hidden": cfg["net"]["hidden"], "params": g.P},
+        "roofline": roofline,
+        "kernels": per_kernel,
+        "wall_s": round(wall, 3),
+        "loss": metrics["loss"], "mean_episode_return": metrics["reward_sum"] / max(1, metrics["episodes"]),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    g.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

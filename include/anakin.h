@@ -149,6 +149,20 @@ int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* out);
 int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out);
 int32_t anakin_set_mode(anakin_t* h, int32_t flags);
 
+/* Per-kernel timing for measurement.  While enabled, every kernel launch is
+ * bracketed by two events recorded on the handle's stream (this adds a few
+ * microseconds per launch, so throughput is timed with profiling off).
+ * anakin_profile(h, 1) clears the totals and starts; anakin_profile(h, 0)
+ * stops.  anakin_kernel_times synchronises the stream and writes up to cap
+ * entries; *n receives the number of distinct kernels seen. */
+typedef struct {
+    char name[48];
+    int64_t calls;
+    double total_ms;
+} anakin_kernel_time;
+int32_t anakin_profile(anakin_t* h, int32_t enable);
+int32_t anakin_kernel_times(anakin_t* h, anakin_kernel_time* out, int32_t cap, int32_t* n);
+
 /* Handle-owned message for the last error on this handle (valid until the next
  * call on it); for a null handle, the message of the last failed create. */
 const char* anakin_last_error(const anakin_t* h);

@@ -51,11 +51,15 @@ class Metrics(C.Structure):
                 ("nonfinite", C.c_int32)]
 
 
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("calls", C.c_int64), ("total_ms", C.c_double)]
+
+
 EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_step",
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
-           "anakin_get_metrics", "anakin_set_mode", "anakin_last_error"]
+           "anakin_get_metrics", "anakin_set_mode", "anakin_profile", "anakin_kernel_times", "anakin_last_error"]
 
 _lib = None
 
@@ -73,6 +77,7 @@ def load():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2104_06272_amd.build` first")
+    import torch  # noqa: F401  -- loads the HIP runtime this process will share with the library
     L = C.CDLL(LIB_PATH)
     vp, f32p, i32p, u32p = C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_uint32)
     L.anakin_workspace_bytes.argtypes = [C.POINTER(EnvCfg), C.POINTER(NetCfg), C.c_int32, C.c_int32]
@@ -95,6 +100,8 @@ def load():
     L.anakin_get_trajectory.argtypes = [vp, C.POINTER(TrajView)]
     L.anakin_get_metrics.argtypes = [vp, C.POINTER(Metrics)]
     L.anakin_set_mode.argtypes = [vp, C.c_int32]
+    L.anakin_profile.argtypes = [vp, C.c_int32]
+    L.anakin_kernel_times.argtypes = [vp, C.POINTER(KernelTime), C.c_int32, C.POINTER(C.c_int32)]
     L.anakin_last_error.argtypes = [vp]
     L.anakin_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -274,6 +281,16 @@ class Anakin:
             acts.append(a.reshape(T, B, H))
         out["act"] = acts
         return out
+
+    def profile(self, enable):
+        self._chk(self.L.anakin_profile(self.h, 1 if enable else 0))
+
+    def kernel_times(self):
+        """{kernel name: (calls, total_ms)} since profiling was switched on; synchronises."""
+        buf = (KernelTime * 32)()
+        n = C.c_int32()
+        self._chk(self.L.anakin_kernel_times(self.h, buf, 32, C.byref(n)))
+        return {buf[i].name.decode(): (buf[i].calls, buf[i].total_ms) for i in range(min(n.value, 32))}
 
     def synchronize(self):
         self.stream.synchronize()

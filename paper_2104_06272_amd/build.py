@@ -20,6 +20,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
 
 
+def torch_lib_dir():
+    try:
+        import importlib.util
+        spec = importlib.util.find_spec("torch")
+        return os.path.join(os.path.dirname(spec.origin), "lib") if spec and spec.origin else None
+    except Exception:
+        return None
+
+
 def build(verbose=True, jobs=8):
     objs = []
     procs = []
@@ -41,7 +50,14 @@ def build(verbose=True, jobs=8):
         failed |= p.returncode != 0
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    # One HIP runtime per process: PyTorch ships its own libamdhip64.so, and a second copy loaded
+    # from /opt/rocm would see no device.  Link against the copy PyTorch loads (falling back to the
+    # system one by rpath when PyTorch's directory is absent).
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-no-hip-rt", "-o", LIB, *objs]
+    tl = torch_lib_dir()
+    if tl and os.path.exists(os.path.join(tl, "libamdhip64.so")):
+        cmd += ["-L" + tl, "-Wl,-rpath," + tl]
+    cmd += ["-L/opt/rocm/lib", "-Wl,-rpath,/opt/rocm/lib", "-lamdhip64"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

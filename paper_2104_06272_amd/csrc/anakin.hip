@@ -249,7 +249,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     anakin* h = new (std::nothrow) anakin();
     if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
-    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0;
+    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ns, B, T, h->splits, &h->loss_blocks);
@@ -296,7 +296,8 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
 extern "C" int32_t anakin_destroy(anakin_t* h)
 {
     if (!h) return ANAKIN_E_INVALID_ARG;
-    (void)hipStreamSynchronize(h->stream);
+    (void)prof_resolve(h);
+    for (hipEvent_t e : h->prof_pool) (void)hipEventDestroy(e);
     delete h;
     return ANAKIN_OK;
 }
@@ -319,6 +320,72 @@ void fill_rollout_args(anakin* h, RolloutArgs& a)
 }  // namespace ank
 
 #define NEED(h) do { if (!(h)) return ANAKIN_E_INVALID_ARG; } while (0)
+
+// ---- per-kernel timing ----------------------------------------------------------
+namespace ank {
+static hipEvent_t prof_event(anakin* h)
+{
+    if (!h->prof_pool.empty()) { hipEvent_t e = h->prof_pool.back(); h->prof_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+ProfScope::ProfScope(anakin* h_, const char* name) : h(h_), idx(-1)
+{
+    if (!h->prof_on) return;
+    int id = -1;
+    for (size_t i = 0; i < h->prof_totals.size(); ++i) if (h->prof_totals[i].name == name) { id = (int)i; break; }
+    if (id < 0) { h->prof_totals.push_back({name, 0, 0.0}); id = (int)h->prof_totals.size() - 1; }
+    anakin::ProfPending p{id, prof_event(h), prof_event(h)};
+    if (!p.start || !p.stop) return;
+    (void)hipEventRecord(p.start, h->stream);
+    h->prof_pending.push_back(p);
+    idx = (int)h->prof_pending.size() - 1;
+}
+ProfScope::~ProfScope()
+{
+    if (idx >= 0) (void)hipEventRecord(h->prof_pending[(size_t)idx].stop, h->stream);
+}
+hipError_t prof_resolve(anakin* h)
+{
+    hipError_t e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return e;
+    for (const auto& p : h->prof_pending) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, p.start, p.stop) == hipSuccess) {
+            h->prof_totals[(size_t)p.name].calls += 1;
+            h->prof_totals[(size_t)p.name].ms += (double)ms;
+        }
+        h->prof_pool.push_back(p.start); h->prof_pool.push_back(p.stop);
+    }
+    h->prof_pending.clear();
+    return hipSuccess;
+}
+}  // namespace ank
+
+extern "C" int32_t anakin_profile(anakin_t* h, int32_t enable)
+{
+    NEED(h);
+    HIPCHK(h, prof_resolve(h));
+    if (enable) h->prof_totals.clear();
+    h->prof_on = enable ? 1 : 0;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_kernel_times(anakin_t* h, anakin_kernel_time* out, int32_t cap, int32_t* n)
+{
+    NEED(h);
+    if (!n || (cap > 0 && !out)) return ANAKIN_E_INVALID_ARG;
+    HIPCHK(h, prof_resolve(h));
+    *n = (int32_t)h->prof_totals.size();
+    for (int32_t i = 0; i < *n && i < cap; ++i) {
+        memset(&out[i], 0, sizeof out[i]);
+        strncpy(out[i].name, h->prof_totals[(size_t)i].name.c_str(), sizeof(out[i].name) - 1);
+        out[i].calls = h->prof_totals[(size_t)i].calls;
+        out[i].total_ms = h->prof_totals[(size_t)i].ms;
+    }
+    return ANAKIN_OK;
+}
 
 extern "C" int32_t anakin_rollout(anakin_t* h)
 {
@@ -343,6 +410,7 @@ extern "C" int32_t anakin_learn(anakin_t* h)
 
 extern "C" int32_t anakin_step(anakin_t* h)
 {
+    if (h && h->prof_pending.size() > 8192) HIPCHK(h, prof_resolve(h));
     int32_t rc = anakin_rollout(h);
     if (rc != ANAKIN_OK) return rc;
     return anakin_learn(h);

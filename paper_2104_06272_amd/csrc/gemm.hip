@@ -180,7 +180,10 @@ hipError_t launch_backward(anakin* h)
         t.obs.s0 = at<const uint32_t>(h, L.tr_s0); t.obs.f0 = at<const float>(h, L.tr_f0);
         t.obs.f1 = at<const float>(h, L.tr_f1); t.obs.walls = at<const uint32_t>(h, L.walls);
         t.bf16 = n.bf16; t.tiles_i = 0;
-        e = launch_gemm_tn_valu(t, h->stream);
+        {
+            ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
+            e = launch_gemm_tn_valu(t, h->stream);
+        }
         if (e != hipSuccess) return e;
         if (l > 0) {
             GemmNtArgs g;
@@ -190,7 +193,10 @@ hipError_t launch_backward(anakin* h)
             g.x = at<const float>(h, L.act[l - 1]);
             g.dx = at<float>(h, L.dz[l - 1]);
             g.bf16 = n.bf16;
-            e = launch_gemm_nt_valu(g, h->stream);
+            {
+                ProfScope prof(h, "gemm_nt_mask");
+                e = launch_gemm_nt_valu(g, h->stream);
+            }
             if (e != hipSuccess) return e;
         }
     }

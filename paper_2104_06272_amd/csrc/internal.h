@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string>
+#include <vector>
 #include <hip/hip_runtime.h>
 #include "env.cuh"
 #include "../../include/anakin.h"
@@ -87,11 +88,26 @@ struct anakin {
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
     std::string err;
+    // optional per-kernel timing with events on the launch stream
+    int prof_on;
+    struct ProfPending { int name; hipEvent_t start, stop; };
+    struct ProfTotal { std::string name; long long calls; double ms; };
+    std::vector<ProfPending> prof_pending;
+    std::vector<hipEvent_t> prof_pool;
+    std::vector<ProfTotal> prof_totals;
 };
 
 namespace ank {
 
 template <class T> inline T* at(const anakin* h, size_t off) { return reinterpret_cast<T*>(h->ws + off); }
+
+// per-kernel timing: brackets one launch with two events when profiling is on
+struct ProfScope {
+    anakin* h; int idx;
+    ProfScope(anakin* h_, const char* name);
+    ~ProfScope();
+};
+hipError_t prof_resolve(anakin* h);
 
 // kernel launchers (each enqueues on h->stream and returns the HIP status)
 hipError_t launch_rollout(anakin* h);

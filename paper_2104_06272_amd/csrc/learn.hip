@@ -241,6 +241,7 @@ __global__ __launch_bounds__(WG) void adam_reduce(const AdamArgs a)
 hipError_t launch_returns(anakin* h)
 {
     const Layout& L = h->lay;
+    ProfScope prof(h, "returns_scan");
     hipLaunchKernelGGL(returns_scan, dim3((h->B + WG - 1) / WG), dim3(WG), 0, h->stream, h->B, h->T,
                        at<const float>(h, L.tr_rew), at<const uint8_t>(h, L.tr_done), at<const float>(h, L.tr_val),
                        h->net_cfg.gamma, h->net_cfg.lambda_, at<float>(h, L.adv), at<float>(h, L.ret));
@@ -257,6 +258,7 @@ hipError_t launch_head_grad(anakin* h)
     a.rew = at<const float>(h, L.tr_rew); a.done = at<const uint8_t>(h, L.tr_done);
     a.dhead = at<float>(h, L.dhead); a.loss_part = at<float>(h, L.loss_part);
     a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef; a.inv_m = (float)(1.0 / (double)a.M);
+    ProfScope prof(h, "head_grad");
     hipLaunchKernelGGL(head_grad, dim3(h->loss_blocks), dim3(WG), 0, h->stream, a);
     return hipGetLastError();
 }
@@ -277,6 +279,7 @@ hipError_t launch_head_backward(anakin* h)
     const int hw = a.H < WG ? a.H : WG;
     const int groups = WG / hw;
     const size_t lds = groups > 1 ? (size_t)groups * (a.H * a.NH + a.NH) * sizeof(float) : 0;
+    ProfScope prof(h, "head_backward");
     hipLaunchKernelGGL(head_backward, dim3(splits * jblocks), dim3(WG), lds, h->stream, a);
     return hipGetLastError();
 }
@@ -298,6 +301,7 @@ hipError_t launch_adam(anakin* h)
     a.lr = h->net_cfg.lr; a.beta1 = h->net_cfg.beta1; a.beta2 = h->net_cfg.beta2; a.eps = h->net_cfg.eps;
     a.bc1 = (float)(1.0 - pow((double)h->net_cfg.beta1, (double)h->adam_t));
     a.bc2 = (float)(1.0 - pow((double)h->net_cfg.beta2, (double)h->adam_t));
+    ProfScope prof(h, "adam_reduce");
     hipLaunchKernelGGL(adam_reduce, dim3((n.P + WG - 1) / WG), dim3(WG), 0, h->stream, a);
     return hipGetLastError();
 }

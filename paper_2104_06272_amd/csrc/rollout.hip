@@ -343,6 +343,7 @@ static hipError_t launch_one(anakin* h, const RolloutArgs& a, size_t lds)
     auto kern = rollout_kernel<ENV, BF>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    ProfScope prof(h, "rollout");
     hipLaunchKernelGGL(kern, dim3(h->B / h->TM), dim3(WG), lds, h->stream, a, h->TM);
     return hipGetLastError();
 }

@@ -50,6 +50,7 @@ LOCKSTEP_CASES = {
     "pendulum_B128": (variant("pendulum_8192", B=128), 0, 2, TOL_F32),
     "pendulum_short_episodes": (variant("pendulum_8192", hidden=[64, 64], B=64, T=32, max_steps=25), 2, 3, TOL_F32),
     "maze_fp32_small": (variant("maze_16384", hidden=[64, 64], B=64, T=32, dtype="fp32", max_steps=20), 1, 3, TOL_F32),
+    "maze_bf16_canonical": (variant("maze_16384", hidden=[64, 64, 32], B=64, T=16, max_steps=40), 3, 2, TOL_BF16),
     "maze_fp32_8x8": (variant("maze_16384", hidden=[32], B=32, T=24, dtype="fp32", rows=8, cols=8, max_steps=30), 0, 2, TOL_F32),
 }
 
