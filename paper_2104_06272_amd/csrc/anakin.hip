@@ -68,10 +68,10 @@ static int build_shapes(const anakin_env_cfg* env, const anakin_net_cfg* net, in
 }
 
 // split-K factor for a reduction over M samples feeding `tiles` output tiles:
-// chunks are multiples of 16 rows; aim for about 2048 workgroups, at most 256 splits
+// chunks are multiples of 16 rows; aim for about 1024 workgroups, at most max_splits splits
 static int pick_splits(int M, int tiles, int max_splits)
 {
-    int cap = 2048 / (tiles > 0 ? tiles : 1);
+    int cap = 1024 / (tiles > 0 ? tiles : 1);
     if (cap > max_splits) cap = max_splits;
     if (cap < 1) cap = 1;
     int s = M / 16;
@@ -112,10 +112,10 @@ static void plan(const NetShape& ns, int B, int T, int* splits, int* loss_blocks
     const int M = B * T;
     for (int l = 0; l < MAX_REGIONS; ++l) splits[l] = 0;
     for (int l = 0; l < ns.L; ++l) {
-        const int tiles = ((ns.dims[l] + 63) / 64) * ((ns.dims[l + 1] + 63) / 64);
+        const int tiles = ((ns.dims[l] + 127) / 128) * ((ns.dims[l + 1] + 127) / 128);
         splits[l] = pick_splits(M, tiles, 256);
     }
-    splits[ns.L] = pick_splits(M, 2, 1024);
+    splits[ns.L] = pick_splits(M, 2, 512);
     *loss_blocks = (M + WG - 1) / WG;
 }
 

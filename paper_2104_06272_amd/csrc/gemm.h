@@ -33,5 +33,7 @@ struct GemmTnArgs {
 
 hipError_t launch_gemm_nt_valu(const GemmNtArgs& a, hipStream_t s);
 hipError_t launch_gemm_tn_valu(GemmTnArgs a, hipStream_t s);
+hipError_t launch_gemm_nt_mfma(const GemmNtArgs& a, hipStream_t s);
+hipError_t launch_gemm_tn_mfma(GemmTnArgs a, hipStream_t s);
 
 }  // namespace ank

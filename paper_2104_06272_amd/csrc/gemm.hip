@@ -180,9 +180,10 @@ hipError_t launch_backward(anakin* h)
         t.obs.s0 = at<const uint32_t>(h, L.tr_s0); t.obs.f0 = at<const float>(h, L.tr_f0);
         t.obs.f1 = at<const float>(h, L.tr_f1); t.obs.walls = at<const uint32_t>(h, L.walls);
         t.bf16 = n.bf16; t.tiles_i = 0;
+        const bool mfma = !(h->mode & ANAKIN_MODE_VALU_GEMM) && !n.bf16;
         {
             ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
-            e = launch_gemm_tn_valu(t, h->stream);
+            e = mfma ? launch_gemm_tn_mfma(t, h->stream) : launch_gemm_tn_valu(t, h->stream);
         }
         if (e != hipSuccess) return e;
         if (l > 0) {
@@ -195,7 +196,7 @@ hipError_t launch_backward(anakin* h)
             g.bf16 = n.bf16;
             {
                 ProfScope prof(h, "gemm_nt_mask");
-                e = launch_gemm_nt_valu(g, h->stream);
+                e = mfma ? launch_gemm_nt_mfma(g, h->stream) : launch_gemm_nt_valu(g, h->stream);
             }
             if (e != hipSuccess) return e;
         }

@@ -149,24 +149,29 @@ struct HeadBwdArgs {
     int bf16;
 };
 
+// Each lane owns four consecutive hidden units (16-byte loads and stores), H/4 lanes
+// cover a row, and 256/(H/4) rows are processed side by side by one workgroup.
 __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
 {
     extern __shared__ float lds[];                          // [groups][H*NH + NH] for the final combine
     const int H = a.H, NH = a.NH, NHP = a.NHP;
-    const int jblocks = (H + WG - 1) / WG;                  // 1 unless H > 256
-    const int hw = H < WG ? H : WG;                         // threads across the hidden dimension
+    const int hw = H >> 2;                                  // lanes across the hidden dimension (<= 256)
     const int groups = WG / hw;                             // rows processed side by side
-    const int g = threadIdx.x / hw, jl = threadIdx.x % hw;
-    const int split = blockIdx.x / jblocks, jb = blockIdx.x % jblocks;
-    const int j = jb * WG + jl;
+    const int g = threadIdx.x / hw, j = (threadIdx.x % hw) << 2;
+    const int split = blockIdx.x;
     const int m_begin = split * a.rows, m_end = m_begin + a.rows;
-    float w[8], dw[8], db[8];
+    float w[4][8], dw[4][8], db[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        float x = (k < NH) ? a.wh[(size_t)j * NH + k] : 0.0f;
-        if (a.bf16) x = bf16_to_f(bf16_bits(x));
-        w[k] = x; dw[k] = 0.0f; db[k] = 0.0f;
-    }
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float x = (k < NH) ? a.wh[(size_t)(j + c) * NH + k] : 0.0f;
+            if (a.bf16) x = bf16_to_f(bf16_bits(x));
+            w[c][k] = x; dw[c][k] = 0.0f;
+        }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) db[k] = 0.0f;
+#pragma unroll 2
     for (int m = m_begin + g; m < m_end; m += groups) {
         const float* dh = a.dhead + (size_t)m * NHP;
         float d[8];
@@ -176,29 +181,33 @@ __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
             const float4 d1 = *reinterpret_cast<const float4*>(dh + 4);
             d[4] = d1.x; d[5] = d1.y; d[6] = d1.z; d[7] = d1.w;
         } else { d[4] = d[5] = d[6] = d[7] = 0.0f; }
-        const float hv = a.h[(size_t)m * H + j];
-        float s = 0.0f;
+        const float4 hv4 = *reinterpret_cast<const float4*>(a.h + (size_t)m * H + j);
+        const float hv[4] = {hv4.x, hv4.y, hv4.z, hv4.w};
+        float o[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            if (k < NH) {
-                s = fmaf(w[k], d[k], s);
-                dw[k] = fmaf(hv, d[k], dw[k]);
-                db[k] += d[k];
+        for (int c = 0; c < 4; ++c) {
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (k < NH) {
+                    s = fmaf(w[c][k], d[k], s);
+                    dw[c][k] = fmaf(hv[c], d[k], dw[c][k]);
+                }
             }
+            o[c] = hv[c] > 0.0f ? s : 0.0f;
         }
-        a.dz[(size_t)m * H + j] = hv > 0.0f ? s : 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) if (k < NH) db[k] += d[k];
+        *reinterpret_cast<float4*>(a.dz + (size_t)m * H + j) = make_float4(o[0], o[1], o[2], o[3]);
     }
     // combine the row groups in ascending group order
     const int stride = H * NH + NH;
     float* out = a.partial + (size_t)split * stride;
-    if (groups == 1) {
-        for (int k = 0; k < NH; ++k) out[(size_t)j * NH + k] = dw[k];
-        if (j == 0) for (int k = 0; k < NH; ++k) out[(size_t)H * NH + k] = db[k];
-        return;
-    }
     float* mine = lds + (size_t)g * stride;
-    for (int k = 0; k < NH; ++k) mine[j * NH + k] = dw[k];
-    if (jl == 0) for (int k = 0; k < NH; ++k) mine[H * NH + k] = db[k];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        for (int k = 0; k < NH; ++k) mine[(j + c) * NH + k] = dw[c][k];
+    if (j == 0) for (int k = 0; k < NH; ++k) mine[H * NH + k] = db[k];
     __syncthreads();
     for (int i = threadIdx.x; i < stride; i += WG) {
         float s = 0.0f;
@@ -213,17 +222,31 @@ __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
 // once out (28 bytes per parameter besides the partials).  For bf16 networks
 // the rounded copies the matrix-core kernels read are refreshed here too.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(WG) void adam_reduce(const AdamArgs a)
+constexpr int ADAM_WAVES = 16;
+__global__ __launch_bounds__(ADAM_WAVES * 64) void adam_reduce(const AdamArgs a)
 {
-    const int i = blockIdx.x * WG + threadIdx.x;
-    if (i >= a.P) return;
-    int r = 0;
-#pragma unroll
-    for (int k = 1; k < MAX_REGIONS; ++k) if (k < a.n_regions && i >= a.reg[k].start) r = k;
-    const Region rg = a.reg[r];
-    const float* p = rg.partial + (i - rg.start);
+    // 64 consecutive parameters per workgroup; each of the 16 wavefronts adds its share of the
+    // split-K partials (splits w, w+16, w+32, ...), then the 16 sums are combined in wave order
+    __shared__ float red[ADAM_WAVES][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + lane;
+    const bool ok = i < a.P;
     float g = 0.0f;
-    for (int s = 0; s < rg.splits; ++s) g += p[(size_t)s * rg.count];
+    if (ok) {
+        int r = 0;
+#pragma unroll
+        for (int k = 1; k < MAX_REGIONS; ++k) if (k < a.n_regions && i >= a.reg[k].start) r = k;
+        const Region rg = a.reg[r];
+        const float* p = rg.partial + (i - rg.start);
+#pragma unroll 4
+        for (int s = wave; s < rg.splits; s += ADAM_WAVES) g += p[(size_t)s * rg.count];
+    }
+    red[wave][lane] = g;
+    __syncthreads();
+    if (wave != 0 || !ok) return;
+    g = red[0][lane];
+#pragma unroll
+    for (int w = 1; w < ADAM_WAVES; ++w) g += red[w][lane];
     const float m = a.beta1 * a.m[i] + (1.0f - a.beta1) * g;
     const float v = a.beta2 * a.v[i] + (1.0f - a.beta2) * g * g;
     const float mh = m / a.bc1, vh = v / a.bc2;
@@ -275,12 +298,10 @@ hipError_t launch_head_backward(anakin* h)
     a.wh = at<const float>(h, L.theta) + n.wh_off;
     a.dz = at<float>(h, L.dz[n.L - 1]); a.partial = at<float>(h, L.part[n.L]);
     a.bf16 = n.bf16;
-    const int jblocks = (a.H + WG - 1) / WG;
-    const int hw = a.H < WG ? a.H : WG;
-    const int groups = WG / hw;
-    const size_t lds = groups > 1 ? (size_t)groups * (a.H * a.NH + a.NH) * sizeof(float) : 0;
+    const int groups = WG / (a.H >> 2);
+    const size_t lds = (size_t)groups * (a.H * a.NH + a.NH) * sizeof(float);
     ProfScope prof(h, "head_backward");
-    hipLaunchKernelGGL(head_backward, dim3(splits * jblocks), dim3(WG), lds, h->stream, a);
+    hipLaunchKernelGGL(head_backward, dim3(splits), dim3(WG), lds, h->stream, a);
     return hipGetLastError();
 }
 
@@ -302,7 +323,7 @@ hipError_t launch_adam(anakin* h)
     a.bc1 = (float)(1.0 - pow((double)h->net_cfg.beta1, (double)h->adam_t));
     a.bc2 = (float)(1.0 - pow((double)h->net_cfg.beta2, (double)h->adam_t));
     ProfScope prof(h, "adam_reduce");
-    hipLaunchKernelGGL(adam_reduce, dim3((n.P + WG - 1) / WG), dim3(WG), 0, h->stream, a);
+    hipLaunchKernelGGL(adam_reduce, dim3((n.P + 63) / 64), dim3(ADAM_WAVES * 64), 0, h->stream, a);
     return hipGetLastError();
 }
 
