@@ -45,7 +45,8 @@ enum { ANAKIN_DTYPE_FP32 = 0, ANAKIN_DTYPE_BF16 = 1 };
 /* anakin_set_mode flags */
 enum {
     ANAKIN_MODE_VALU_GEMM = 1,         /* learn-phase GEMMs on vector ALUs instead of matrix cores */
-    ANAKIN_MODE_CANONICAL_ACTING = 2   /* bf16 nets: act with the sequential fp32 chain instead of matrix cores */
+    ANAKIN_MODE_CANONICAL_ACTING = 2,  /* act with the sequential fp32 FMA chain on vector ALUs instead of matrix cores */
+    ANAKIN_MODE_STREAM_WEIGHTS = 4     /* acting: stream hidden-layer weights from L2 even when they fit on chip */
 };
 
 /* Environment (paper section 3.1: initial_state + step on explicit state).

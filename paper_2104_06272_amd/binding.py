@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libanakin.so")
 
 OK = 0
 E_INVALID_ARG, E_BAD_CONFIG, E_WORKSPACE_TOO_SMALL, E_MISALIGNED, E_HIP, E_NONFINITE, E_STATE = -1, -2, -3, -4, -5, -6, -7
-MODE_VALU_GEMM, MODE_CANONICAL_ACTING = 1, 2
+MODE_VALU_GEMM, MODE_CANONICAL_ACTING, MODE_STREAM_WEIGHTS = 1, 2, 4
 
 ENV_KINDS = {"catch": 0, "pendulum": 1, "maze": 2}
 POLICIES = {"categorical": 0, "tanh_gaussian": 1}

@@ -259,6 +259,8 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
         delete h; return ANAKIN_E_WORKSPACE_TOO_SMALL;
     }
     h->TM = rollout_pick_tile(ns, B);
+    h->TM_mfma = rollout_pick_tile_mfma(ns, B);
+    h->TM_res = rollout_resident_tile(ns, B);
 
     auto fail = [&](int code) { g_create_error = h->err; delete h; return code; };
     // parameters and optimiser state
@@ -561,7 +563,7 @@ extern "C" int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out)
 extern "C" int32_t anakin_set_mode(anakin_t* h, int32_t flags)
 {
     NEED(h);
-    if (flags & ~(ANAKIN_MODE_VALU_GEMM | ANAKIN_MODE_CANONICAL_ACTING)) { h->err = "unknown mode flag"; return ANAKIN_E_INVALID_ARG; }
+    if (flags & ~(ANAKIN_MODE_VALU_GEMM | ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS)) { h->err = "unknown mode flag"; return ANAKIN_E_INVALID_ARG; }
     h->mode = flags;
     return ANAKIN_OK;
 }

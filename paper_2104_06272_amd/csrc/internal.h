@@ -84,7 +84,9 @@ struct anakin {
     size_t ws_bytes;
     hipStream_t stream;
     ank::Layout lay;
-    int TM;                       // envs per workgroup in the rollout kernel
+    int TM;                       // envs per workgroup in the vector-ALU rollout kernel
+    int TM_mfma;                  // envs per workgroup in the matrix-core rollout kernel (0: not applicable)
+    int TM_res;                   // envs per workgroup in the weights-resident rollout kernel (0: not applicable)
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
     std::string err;
@@ -116,6 +118,8 @@ hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);
 hipError_t launch_adam(anakin* h);
 int rollout_pick_tile(const NetShape& net, int B);
+int rollout_pick_tile_mfma(const NetShape& net, int B);
+int rollout_resident_tile(const NetShape& net, int B);
 size_t rollout_lds_bytes(const NetShape& net, const EnvDims& env, int TM, int* ldx);
 
 }  // namespace ank

@@ -86,11 +86,12 @@ constexpr int OBS_WORDS = 12;
 // first layer: gather-sum for the one-hot boards, three fmas for the pendulum
 template <int ENV, int RM, bool BF>
 __device__ __forceinline__ void first_layer(const RolloutArgs& a, const uint32_t* __restrict__ obs,
-                                            float* __restrict__ Y, int ldx, int tid, float* __restrict__ gout)
+                                            float* __restrict__ Y, int ldx, int tid, float* __restrict__ gout,
+                                            const float* w1)
 {
     const int N = a.net.dims[1];
     const int CG = N >> 2, tn = tid % CG, m0 = (tid / CG) * RM, c0 = tn << 2;
-    const float* wp = a.theta + a.net.w_off[0] + c0;
+    const float* wp = w1 + c0;
     float acc[RM][4];
     const float4 b = ld4(a.theta + a.net.b_off[0] + c0);
 #pragma unroll
@@ -144,15 +145,16 @@ __device__ __forceinline__ void first_layer(const RolloutArgs& a, const uint32_t
 }
 
 template <int ENV, bool BF>
-__device__ __forceinline__ void run_first_layer(const RolloutArgs& a, int TM, const uint32_t* obs, float* Y, int tid, float* gout)
+__device__ __forceinline__ void run_first_layer(const RolloutArgs& a, int TM, const uint32_t* obs, float* Y, int tid, float* gout,
+                                                const float* w1)
 {
     const int RM = TM * a.net.dims[1] / 1024;
     switch (RM) {
-        case 1: first_layer<ENV, 1, BF>(a, obs, Y, a.ldx, tid, gout); break;
-        case 2: first_layer<ENV, 2, BF>(a, obs, Y, a.ldx, tid, gout); break;
-        case 4: first_layer<ENV, 4, BF>(a, obs, Y, a.ldx, tid, gout); break;
-        case 8: first_layer<ENV, 8, BF>(a, obs, Y, a.ldx, tid, gout); break;
-        default: first_layer<ENV, 16, BF>(a, obs, Y, a.ldx, tid, gout); break;
+        case 1: first_layer<ENV, 1, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
+        case 2: first_layer<ENV, 2, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
+        case 4: first_layer<ENV, 4, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
+        case 8: first_layer<ENV, 8, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
+        default: first_layer<ENV, 16, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
     }
 }
 
@@ -172,7 +174,238 @@ __device__ __forceinline__ void run_dense_layer(const RolloutArgs& a, int TM, in
     }
 }
 
-template <int ENV, bool BF>
+
+// ---------------------------------------------------------------------------
+// Hidden layers on the matrix cores.  On gfx950 the fp32 MFMA instructions add
+// their products one k at a time with a fused multiply-add, ascending in k, and
+// chain through the accumulator operand -- measured bit-identical to the
+// sequential fmaf chain on random, wide-range and integer inputs -- so starting
+// the accumulator from the bias and feeding k in ascending order reproduces
+// the canonical order exactly while running at matrix-core rate.
+//
+// Wavefront w owns output columns [w N/4, (w+1) N/4); lane l feeds column
+// w N/4 + NT (l % 16|32) + t of tile t, so one vector load of NT consecutive
+// weights per k serves all of the lane's tiles and the epilogue stores NT
+// consecutive outputs.  The weights of the next block of k are fetched from L2
+// into registers while the current block is multiplied.
+// ---------------------------------------------------------------------------
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+template <int NT>
+__device__ __forceinline__ void load_nt(const float* __restrict__ p, float (&b)[NT])
+{
+    if (NT == 1) { b[0] = p[0]; }
+    else if (NT == 2) { const float2 v = *reinterpret_cast<const float2*>(p); b[0] = v.x; b[1] = v.y; }
+    else {
+#pragma unroll
+        for (int q = 0; q < NT / 4; ++q) {
+            const float4 v = *reinterpret_cast<const float4*>(p + 4 * q);
+            b[4 * q + 0] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
+        }
+    }
+}
+template <int NT>
+__device__ __forceinline__ void store_nt(float* __restrict__ p, const float (&b)[NT])
+{
+    if (NT == 1) { p[0] = b[0]; }
+    else if (NT == 2) { *reinterpret_cast<float2*>(p) = make_float2(b[0], b[1]); }
+    else {
+#pragma unroll
+        for (int q = 0; q < NT / 4; ++q)
+            *reinterpret_cast<float4*>(p + 4 * q) = make_float4(b[4 * q + 0], b[4 * q + 1], b[4 * q + 2], b[4 * q + 3]);
+    }
+}
+
+// 16 envs per workgroup: v_mfma_f32_16x16x4_f32.  Lane l feeds A[row l%16][k l/16] and
+// B[k l/16][col l%16]; accumulator register r of lane l is D[row 4*(l/16) + r][col l%16].
+template <int NT>
+__device__ __forceinline__ void mfma_layer_m16(const float* __restrict__ X, float* __restrict__ Y, int ldx,
+                                               const float* __restrict__ W, const float* __restrict__ bias,
+                                               int K, int N, int tid, float* __restrict__ gout)
+{
+    constexpr int U = NT <= 4 ? 8 : (NT == 8 ? 4 : 2);          // k-steps (of 4) per prefetch block
+    const int lane = tid & 63, wave = tid >> 6;
+    const int col0 = wave * (N >> 2) + NT * (lane & 15), kq = lane >> 4;
+    f4v acc[NT];
+    {
+        float bv[NT];
+        load_nt<NT>(bias + col0, bv);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) { acc[t][0] = bv[t]; acc[t][1] = bv[t]; acc[t][2] = bv[t]; acc[t][3] = bv[t]; }
+    }
+    const float* wp = W + (size_t)kq * N + col0;
+    const float* xp = X + (lane & 15) * ldx + kq;
+    float bc[U][NT], bn[U][NT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_nt<NT>(wp + (size_t)(4 * u) * N, bc[u]);
+    for (int k0 = 0; k0 < K; k0 += 4 * U) {
+        if (k0 + 4 * U < K) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) load_nt<NT>(wp + (size_t)(k0 + 4 * U + 4 * u) * N, bn[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float av = xp[k0 + 4 * u];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bc[u][t], acc[t], 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bc[u][t] = bn[u][t];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * kq + r;
+        float o[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) o[t] = acc[t][r] > 0.0f ? acc[t][r] : 0.0f;
+        store_nt<NT>(Y + row * ldx + col0, o);
+        if (gout) store_nt<NT>(gout + (size_t)row * N + col0, o);
+    }
+}
+
+// 32*MT envs per workgroup: v_mfma_f32_32x32x2_f32.  Lane l feeds A[row l%32][k l/32] and
+// B[k l/32][col l%32]; accumulator register r is D[row 8*(r/4) + 4*(l/32) + r%4][col l%32].
+template <int MT, int NT>
+__device__ __forceinline__ void mfma_layer_m32(const float* __restrict__ X, float* __restrict__ Y, int ldx,
+                                               const float* __restrict__ W, const float* __restrict__ bias,
+                                               int K, int N, int tid, float* __restrict__ gout)
+{
+    constexpr int U = NT <= 2 ? 8 : (NT == 4 ? 4 : 2);          // k-steps (of 2) per prefetch block
+    const int lane = tid & 63, wave = tid >> 6;
+    const int col0 = wave * (N >> 2) + NT * (lane & 31), kq = lane >> 5;
+    f16v acc[MT][NT];
+    {
+        float bv[NT];
+        load_nt<NT>(bias + col0, bv);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mt][t][r] = bv[t];
+    }
+    const float* wp = W + (size_t)kq * N + col0;
+    const float* xp = X + (lane & 31) * ldx + kq;
+    float bc[U][NT], bn[U][NT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_nt<NT>(wp + (size_t)(2 * u) * N, bc[u]);
+    for (int k0 = 0; k0 < K; k0 += 2 * U) {
+        if (k0 + 2 * U < K) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) load_nt<NT>(wp + (size_t)(k0 + 2 * U + 2 * u) * N, bn[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const float av = xp[mt * 32 * ldx + k0 + 2 * u];
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bc[u][t], acc[mt][t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bc[u][t] = bn[u][t];
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = mt * 32 + 8 * (r >> 2) + 4 * kq + (r & 3);
+            float o[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) o[t] = acc[mt][t][r] > 0.0f ? acc[mt][t][r] : 0.0f;
+            store_nt<NT>(Y + row * ldx + col0, o);
+            if (gout) store_nt<NT>(gout + (size_t)row * N + col0, o);
+        }
+}
+
+__device__ __forceinline__ void run_mfma_layer(const RolloutArgs& a, int TM, int l, const float* X, float* Y, int tid, float* gout)
+{
+    const int K = a.net.dims[l], N = a.net.dims[l + 1];
+    const float* W = a.theta + a.net.w_off[l];
+    const float* bias = a.theta + a.net.b_off[l];
+    if (TM == 16) {
+        switch (N >> 6) {                                   // tiles per wavefront: N / 4 / 16
+            case 1: mfma_layer_m16<1>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            case 2: mfma_layer_m16<2>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            case 4: mfma_layer_m16<4>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            case 8: mfma_layer_m16<8>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            default: mfma_layer_m16<16>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+        }
+    } else if (TM == 32) {
+        switch (N >> 7) {                                   // N / 4 / 32
+            case 1: mfma_layer_m32<1, 1>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            case 2: mfma_layer_m32<1, 2>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            case 4: mfma_layer_m32<1, 4>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            default: mfma_layer_m32<1, 8>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+        }
+    } else {
+        switch (N >> 7) {
+            case 1: mfma_layer_m32<2, 1>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            case 2: mfma_layer_m32<2, 2>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+            default: mfma_layer_m32<2, 4>(X, Y, a.ldx, W, bias, K, N, tid, gout); break;
+        }
+    }
+}
+
+// Heads: out[m][j] = bh[j] + sum_k X[m][k] Wh[k][j], one sequential fused multiply-add chain
+// per (env, head) as the canonical order demands.  The chain is latency-bound, so what matters
+// is that its operands are already in registers: lane (m, j) streams row m of X and row j of
+// the transposed head matrix (both k-contiguous in LDS, 16-byte reads), 32 k at a time, with
+// the next block in flight while the current one is consumed.
+// whT: [NH][ldw] in LDS (ldw = HL + 4).
+template <int U>
+__device__ __forceinline__ void heads_load(const float* __restrict__ x, const float* __restrict__ w, float4 (&xv)[U], float4 (&wv)[U])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) { xv[u] = *reinterpret_cast<const float4*>(x + 4 * u); wv[u] = *reinterpret_cast<const float4*>(w + 4 * u); }
+}
+template <int U>
+__device__ __forceinline__ float heads_fma(const float4 (&xv)[U], const float4 (&wv)[U], float acc)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        acc = fmaf(xv[u].x, wv[u].x, acc);
+        acc = fmaf(xv[u].y, wv[u].y, acc);
+        acc = fmaf(xv[u].z, wv[u].z, acc);
+        acc = fmaf(xv[u].w, wv[u].w, acc);
+    }
+    return acc;
+}
+// U: float4 per register block (a block covers 4U values of k; HL is a multiple of 4U)
+template <int U>
+__device__ __forceinline__ void heads_chain(const float* __restrict__ X, int ldx, const float* __restrict__ whT, int ldw,
+                                            const float* __restrict__ bhs, float* __restrict__ heads,
+                                            int HL, int NH, int NHP, int TM, int tid)
+{
+    constexpr int KB = 4 * U;
+    for (int idx = tid; idx < TM * NH; idx += WG) {
+        const int m = idx % TM, j = idx / TM;
+        float acc = bhs[j];
+        const float* x = X + m * ldx;
+        const float* w = whT + j * ldw;
+        float4 xa[U], wa[U], xb[U], wb[U];                      // two register blocks, used alternately
+        heads_load<U>(x, w, xa, wa);
+        for (int k0 = 0; k0 < HL; k0 += 2 * KB) {
+            const bool more = k0 + KB < HL;
+            if (more) heads_load<U>(x + k0 + KB, w + k0 + KB, xb, wb);
+            acc = heads_fma<U>(xa, wa, acc);
+            if (more) {
+                if (k0 + 2 * KB < HL) heads_load<U>(x + k0 + 2 * KB, w + k0 + 2 * KB, xa, wa);
+                acc = heads_fma<U>(xb, wb, acc);
+            }
+        }
+        heads[m * NHP + j] = acc;
+    }
+}
+
+template <int ENV, bool BF, bool MF>
 __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const int TM)
 {
     extern __shared__ float4 smem4[];
@@ -180,22 +413,24 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
     const int ldx = a.ldx, NH = a.net.NH, NHP = a.net.NHP, L = a.net.L, HL = a.net.dims[a.net.L];
     float* bufA = smem;
     float* bufB = bufA + TM * ldx;
-    float* whs = bufB + TM * ldx;                 // [HL][NHP] head weights
-    float* bhs = whs + HL * NHP;                  // [8] head biases
+    float* whs = bufB + TM * ldx;                 // [8][HL + 4] head weights, transposed
+    float* bhs = whs + 8 * (HL + 4);              // [8] head biases
     float* heads = bhs + 8;                       // [TM][NHP]
     uint32_t* obs = reinterpret_cast<uint32_t*>(heads + TM * NHP);   // [TM][OBS_WORDS]
+    uint32_t* rng = obs + TM * OBS_WORDS;                            // [TM][4] draws of the current step
 
     const int tid = threadIdx.x;
     const int b0 = blockIdx.x * TM;
     const int B = a.B, T = a.T;
     const TrajPtrs& tp = a.tp;
 
-    // head weights into LDS once
-    for (int i = tid; i < HL * NHP; i += WG) {
-        const int k = i / NHP, j = i - k * NHP;
-        float w = 0.0f;
-        if (j < NH) { w = a.theta[a.net.wh_off + k * NH + j]; if (BF) w = bfr(w); }
-        whs[i] = w;
+    // head weights into LDS once, transposed: whs[j][k], row stride HL + 4
+    const int ldw = HL + 4;
+    for (int i = tid; i < HL * NH; i += WG) {
+        const int k = i / NH, j = i - k * NH;
+        float w = a.theta[a.net.wh_off + i];
+        if (BF) w = bfr(w);
+        whs[j * ldw + k] = w;
     }
     if (tid < 8) bhs[tid] = tid < NH ? a.theta[a.net.bh_off + tid] : 0.0f;
 
@@ -237,28 +472,27 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         // ---- forward -------------------------------------------------------
         const bool keep = t < T;                 // the bootstrap evaluation keeps no activations
         float* g0 = keep ? tp.act[0] + ((size_t)t * B + b0) * a.net.dims[1] : nullptr;
-        run_first_layer<ENV, BF>(a, TM, obs, bufA, tid, g0);
+        run_first_layer<ENV, BF>(a, TM, obs, bufA, tid, g0, a.theta + a.net.w_off[0]);
         __syncthreads();
         float* cur = bufA;
         float* nxt = bufB;
         for (int l = 1; l < L; ++l) {
             float* gl = keep ? tp.act[l] + ((size_t)t * B + b0) * a.net.dims[l + 1] : nullptr;
-            run_dense_layer<BF>(a, TM, l, cur, nxt, tid, gl);
+            if (MF) run_mfma_layer(a, TM, l, cur, nxt, tid, gl);
+            else run_dense_layer<BF>(a, TM, l, cur, nxt, tid, gl);
             __syncthreads();
             float* tmp = cur; cur = nxt; nxt = tmp;
         }
-        for (int idx = tid; idx < TM * NH; idx += WG) {
-            const int m = idx % TM, j = idx / TM;
-            float acc = bhs[j];
-            const float* x = cur + m * ldx;
-            for (int k0 = 0; k0 < HL; k0 += 4) {
-                const float4 xv = ld4(x + k0);
-                acc = fmaf(xv.x, whs[(k0 + 0) * NHP + j], acc);
-                acc = fmaf(xv.y, whs[(k0 + 1) * NHP + j], acc);
-                acc = fmaf(xv.z, whs[(k0 + 2) * NHP + j], acc);
-                acc = fmaf(xv.w, whs[(k0 + 3) * NHP + j], acc);
+        heads_chain<8>(cur, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
+        // the step's random draws do not depend on the network: the last lanes of the workgroup,
+        // idle during the head chains, produce them now
+        if (t < T) {
+            for (int idx = WG - 1 - tid; idx < 2 * TM; idx += WG) {
+                const int e = idx % TM, which = idx / TM;
+                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, which == 0 ? DOM_ACTION : DOM_RESET);
+                rng[e * 4 + 2 * which] = w.x;
+                rng[e * 4 + 2 * which + 1] = w.y;
             }
-            heads[m * NHP + j] = acc;
         }
         __syncthreads();
         // ---- sample, step, record -------------------------------------------
@@ -274,22 +508,19 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
             if (t < T) {
-                const uint64_t gt = a.gstep + (uint64_t)t;
-                const u32x4 wa = philox(a.seed, (uint32_t)b, gt, DOM_ACTION);
+                const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);   // action words 0,1; reset words 0,1
                 float r; int done;
                 if (ENV == ENV_PENDULUM) {
                     float eps, act;
-                    sample_gaussian(hv[0], hv[1], wa.x, wa.y, eps, act);
+                    sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
                     tp.tr_eps[tb] = eps;
                     tp.tr_actf[tb] = act;
-                    const u32x4 wr = philox(a.seed, (uint32_t)b, gt, DOM_RESET);
-                    pendulum_step(a.env, st, act, wr.x, wr.y, r, done);
+                    pendulum_step(a.env, st, act, dr.z, dr.w, r, done);
                 } else {
-                    const int act = sample_categorical<8>(hv, a.net.A, u01(wa.x));
+                    const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
                     if (ENV == ENV_CATCH) {
-                        const u32x4 wr = philox(a.seed, (uint32_t)b, gt, DOM_RESET);
-                        catch_step(a.env, st, act, wr.x, r, done);
+                        catch_step(a.env, st, act, dr.z, r, done);
                     } else {
                         const uint32_t* wl = obs + tid * OBS_WORDS;
                         maze_step(a.env, st, act, [wl](int c) { return ((wl[c >> 5] >> (c & 31)) & 1u) != 0u; }, r, done);
@@ -306,6 +537,289 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
     }
+}
+
+
+// ---------------------------------------------------------------------------
+// Weights resident on chip.  For two-layer nets up to 256 x 256 the whole
+// hidden-to-hidden matrix fits the register file of one compute unit: a CU has
+// 4 SIMDs x 512 registers x 64 lanes x 4 B = 512 KB, W2 (256 x 256 fp32) is
+// 256 KB, i.e. 256 registers per lane at one wavefront per SIMD.  Each lane
+// loads, once per launch, exactly the B-operand values it will feed to the
+// matrix cores -- W2[k][its columns] for its k phase -- and reuses them for all
+// T+1 forward passes, so the acting loop reads no hidden-layer weight from
+// memory at all.  The first layer's matrix (gathered by row) and the head
+// matrix sit in LDS.  Everything else is as in rollout_kernel, and the
+// accumulation order is the same canonical one.
+// ---------------------------------------------------------------------------
+template <int KS, int NT>
+__device__ __forceinline__ void resident_m16(const float (&wreg)[KS][NT], const float* __restrict__ X, float* __restrict__ Y,
+                                             int ldx, const float* __restrict__ bias, int N, int tid, float* __restrict__ gout)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int col0 = wave * (N >> 2) + NT * (lane & 15), kq = lane >> 4;
+    f4v acc[NT];
+    {
+        float bv[NT];
+        load_nt<NT>(bias + col0, bv);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) { acc[t][0] = bv[t]; acc[t][1] = bv[t]; acc[t][2] = bv[t]; acc[t][3] = bv[t]; }
+    }
+    const float* xp = X + (lane & 15) * ldx + kq;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const float av = xp[4 * s];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wreg[s][t], acc[t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * kq + r;
+        float o[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) o[t] = acc[t][r] > 0.0f ? acc[t][r] : 0.0f;
+        store_nt<NT>(Y + row * ldx + col0, o);
+        if (gout) store_nt<NT>(gout + (size_t)row * N + col0, o);
+    }
+}
+
+template <int KS, int NT>
+__device__ __forceinline__ void resident_m32(const float (&wreg)[KS][NT], const float* __restrict__ X, float* __restrict__ Y,
+                                             int ldx, const float* __restrict__ bias, int N, int tid, float* __restrict__ gout)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int col0 = wave * (N >> 2) + NT * (lane & 31), kq = lane >> 5;
+    f16v acc[NT];
+    {
+        float bv[NT];
+        load_nt<NT>(bias + col0, bv);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = bv[t];
+    }
+    const float* xp = X + (lane & 31) * ldx + kq;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const float av = xp[2 * s];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, wreg[s][t], acc[t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * kq + (r & 3);
+        float o[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) o[t] = acc[t][r] > 0.0f ? acc[t][r] : 0.0f;
+        store_nt<NT>(Y + row * ldx + col0, o);
+        if (gout) store_nt<NT>(gout + (size_t)row * N + col0, o);
+    }
+}
+
+
+// RK x RN: shape of the resident hidden-to-hidden layer; M32: 32 envs per workgroup, else 16
+template <int ENV, bool M32, int RK, int RN>
+__global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs a)
+{
+    constexpr int TM = M32 ? 32 : 16;
+    constexpr int KS = M32 ? RK / 2 : RK / 4;                      // MFMA k-steps per forward pass
+    constexpr int NT = M32 ? RN / 128 : RN / 64;                   // MFMA tiles per wavefront
+    constexpr bool W1_IN_LDS = ENV != ENV_MAZE;
+    extern __shared__ float4 smem4[];
+    float* smem = reinterpret_cast<float*>(smem4);
+    constexpr int HL = RN;
+    const int ldx = a.ldx, NH = a.net.NH, NHP = a.net.NHP, D = a.net.dims[0];
+    float* bufA = smem;
+    float* bufB = bufA + TM * ldx;
+    float* whs = bufB + TM * ldx;                 // [8][HL + 4] head weights, transposed
+    float* bhs = whs + 8 * (HL + 4);              // [8] head biases
+    float* heads = bhs + 8;                       // [TM][NHP]
+    uint32_t* obs = reinterpret_cast<uint32_t*>(heads + TM * NHP);   // [TM][OBS_WORDS]
+    uint32_t* rng = obs + TM * OBS_WORDS;                            // [TM][4] draws of the current step
+    float* w1s = reinterpret_cast<float*>(rng + TM * 4);             // [D][RK] first-layer weights
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b0 = blockIdx.x * TM;
+    const int B = a.B, T = a.T;
+    const TrajPtrs& tp = a.tp;
+
+    constexpr int ldw = HL + 4;
+    for (int i = tid; i < HL * NH; i += WG) {
+        const int k = i / NH, j = i - k * NH;
+        whs[j * ldw + k] = a.theta[a.net.wh_off + i];
+    }
+    if (tid < 8) bhs[tid] = tid < NH ? a.theta[a.net.bh_off + tid] : 0.0f;
+    if (W1_IN_LDS) {
+        const float4* src = reinterpret_cast<const float4*>(a.theta + a.net.w_off[0]);
+        float4* dst = reinterpret_cast<float4*>(w1s);
+        for (int i = tid; i < D * RK / 4; i += WG) dst[i] = src[i];
+    }
+    const float* w1 = W1_IN_LDS ? w1s : a.theta + a.net.w_off[0];
+
+    // this lane's share of W2, in matrix-core operand order
+    float wreg[KS][NT];
+    {
+        const float* W2 = a.theta + a.net.w_off[1];
+        const int col0 = wave * (RN >> 2) + NT * (M32 ? (lane & 31) : (lane & 15));
+        const int kq = M32 ? (lane >> 5) : (lane >> 4);
+        constexpr int kstep = M32 ? 2 : 4;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) load_nt<NT>(W2 + (size_t)(kstep * s + kq) * RN + col0, wreg[s]);
+    }
+    const float* bias2 = a.theta + a.net.b_off[1];
+
+    EnvState st{0u, 0.0f, 0.0f};
+    const bool owner = tid < TM;
+    const int b = b0 + tid;
+    if (owner) {
+        st.s0 = tp.s0[b];
+        if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        if (ENV == ENV_MAZE) {
+            for (int w = 0; w < 8; ++w) obs[tid * OBS_WORDS + w] = tp.walls[(size_t)w * B + b];
+        }
+    }
+
+#ifdef ANK_PHASE_TIMING
+    long long ph[6] = {0, 0, 0, 0, 0, 0}, c0, c1;
+#define PH(i) do { c1 = clock64(); ph[i] += c1 - c0; c0 = c1; } while (0)
+    c0 = clock64();
+#else
+#define PH(i) do { } while (0)
+#endif
+    for (int t = 0; t <= T; ++t) {
+        const size_t tb = (size_t)t * B + b;
+        if (owner) {
+            tp.tr_s0[tb] = st.s0;
+            if (ENV == ENV_CATCH) {
+                int bc, pc;
+                catch_obs_cells(a.env, st.s0, bc, pc);
+                obs[tid * OBS_WORDS + 0] = (uint32_t)bc;
+                obs[tid * OBS_WORDS + 1] = (uint32_t)pc;
+            } else if (ENV == ENV_PENDULUM) {
+                tp.tr_f0[tb] = st.f0;
+                tp.tr_f1[tb] = st.f1;
+                float sn, cs;
+                det_sincos(st.f0, sn, cs);
+                obs[tid * OBS_WORDS + 0] = bits_from_f(cs);
+                obs[tid * OBS_WORDS + 1] = bits_from_f(sn);
+                obs[tid * OBS_WORDS + 2] = bits_from_f(st.f1);
+            } else {
+                obs[tid * OBS_WORDS + 8] = st.s0 & 0xffffu;
+            }
+        }
+        __syncthreads();
+        PH(0);
+        const bool keep = t < T;
+        float* g0 = keep ? tp.act[0] + ((size_t)t * B + b0) * RK : nullptr;
+        first_layer<ENV, TM * RK / 1024, false>(a, obs, bufA, ldx, tid, g0, w1);
+        __syncthreads();
+        PH(1);
+        float* g1 = keep ? tp.act[1] + ((size_t)t * B + b0) * RN : nullptr;
+        if (M32) resident_m32<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
+        else resident_m16<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
+        __syncthreads();
+        PH(2);
+        heads_chain<(RK * RN >= 256 * 256 ? 2 : 8)>(bufB, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
+        // the step's random draws do not depend on the network: the last lanes of the workgroup,
+        // idle during the head chains, produce them now
+        if (t < T) {
+            for (int idx = WG - 1 - tid; idx < 2 * TM; idx += WG) {
+                const int e = idx % TM, which = idx / TM;
+                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, which == 0 ? DOM_ACTION : DOM_RESET);
+                rng[e * 4 + 2 * which] = w.x;
+                rng[e * 4 + 2 * which + 1] = w.y;
+            }
+        }
+        __syncthreads();
+        PH(3);
+        if (owner) {
+            const float4 h0 = ld4(heads + tid * NHP);
+            const float4 h1 = NHP == 8 ? ld4(heads + tid * NHP + 4) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+            float* hd = tp.tr_head + tb * NHP;
+            *reinterpret_cast<float4*>(hd) = h0;
+            if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = h1;
+            float val = hv[0];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
+            tp.tr_val[tb] = val;
+            if (t < T) {
+                const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);   // action words 0,1; reset words 0,1
+                float r; int done;
+                if (ENV == ENV_PENDULUM) {
+                    float eps, act;
+                    sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
+                    tp.tr_eps[tb] = eps;
+                    tp.tr_actf[tb] = act;
+                    pendulum_step(a.env, st, act, dr.z, dr.w, r, done);
+                } else {
+                    const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
+                    tp.tr_act[tb] = (uint8_t)act;
+                    if (ENV == ENV_CATCH) {
+                        catch_step(a.env, st, act, dr.z, r, done);
+                    } else {
+                        const uint32_t* wl = obs + tid * OBS_WORDS;
+                        maze_step(a.env, st, act, [wl](int c) { return ((wl[c >> 5] >> (c & 31)) & 1u) != 0u; }, r, done);
+                    }
+                }
+                tp.tr_rew[tb] = r;
+                tp.tr_done[tb] = (uint8_t)done;
+            }
+        }
+        PH(4);
+    }
+#ifdef ANK_PHASE_TIMING
+    if (tid == 0 && (blockIdx.x == 0 || blockIdx.x == 100))
+        printf("block %d phases (cycles/step): observe %lld first %lld mfma %lld heads %lld sample %lld\n", (int)blockIdx.x,
+               ph[0] / (T + 1), ph[1] / (T + 1), ph[2] / (T + 1), ph[3] / (T + 1), ph[4] / (T + 1));
+#endif
+#undef PH
+    if (owner) {
+        tp.s0[b] = st.s0;
+        if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
+    }
+}
+
+// which resident shape (if any) fits this net: 0 none, else the width (64, 128, 256)
+int rollout_resident_width(const NetShape& net)
+{
+    if (net.bf16 || net.L != 2 || net.dims[1] != net.dims[2]) return 0;
+    const int w = net.dims[1];
+    return (w == 64 || w == 128 || w == 256) ? w : 0;
+}
+int rollout_resident_tile(const NetShape& net, int B)
+{
+    const int w = rollout_resident_width(net);
+    if (!w) return 0;
+    if (w >= 128 && B % 32 == 0 && B / 32 >= 256) return 32;
+    return 16;
+}
+
+// can the hidden-to-hidden layers run on the matrix cores with TM envs per workgroup?
+static bool mfma_tile_ok(const NetShape& net, int TM)
+{
+    if (net.bf16 || net.L < 2) return false;
+    if (TM != 16 && TM != 32 && TM != 64) return false;
+    if (TM * net.dims[1] > 16 * 1024) return false;                 // first-layer register tile
+    for (int l = 2; l <= net.L; ++l) {
+        const int N = net.dims[l];
+        if (TM == 16 ? N < 64 : N < 128) return false;              // at least one MFMA tile per wavefront
+        if (TM == 64 && N > 512) return false;                      // accumulator budget
+    }
+    int hmax = 0;
+    for (int l = 1; l <= net.L; ++l) hmax = net.dims[l] > hmax ? net.dims[l] : hmax;
+    return (size_t)2 * TM * (hmax + 4) * 4 <= 128 * 1024;           // two activation buffers in LDS
+}
+
+int rollout_pick_tile_mfma(const NetShape& net, int B)
+{
+    int best = 0;
+    for (int tm = 16; tm <= 64; tm *= 2) {
+        if (B % tm || !mfma_tile_ok(net, tm)) continue;
+        if (!best) best = tm;
+        if (B / tm >= 256) best = tm;
+    }
+    return best;
 }
 
 int rollout_pick_tile(const NetShape& net, int B)
@@ -333,33 +847,71 @@ size_t rollout_lds_bytes(const NetShape& net, const EnvDims&, int TM, int* ldx_o
     for (int l = 1; l <= net.L; ++l) hmax = net.dims[l] > hmax ? net.dims[l] : hmax;
     const int ldx = hmax + 4;
     if (ldx_out) *ldx_out = ldx;
-    size_t words = (size_t)2 * TM * ldx + (size_t)net.dims[net.L] * net.NHP + 8 + (size_t)TM * net.NHP + (size_t)TM * OBS_WORDS;
+    size_t words = (size_t)2 * TM * ldx + (size_t)8 * (net.dims[net.L] + 4) + 8 + (size_t)TM * net.NHP + (size_t)TM * (OBS_WORDS + 4);
     return words * 4;
 }
 
-template <int ENV, bool BF>
-static hipError_t launch_one(anakin* h, const RolloutArgs& a, size_t lds)
+template <int ENV, bool BF, bool MF>
+static hipError_t launch_one(anakin* h, const RolloutArgs& a, int TM)
 {
-    auto kern = rollout_kernel<ENV, BF>;
+    const size_t lds = rollout_lds_bytes(h->net, h->env, TM, nullptr);
+    auto kern = rollout_kernel<ENV, BF, MF>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     ProfScope prof(h, "rollout");
-    hipLaunchKernelGGL(kern, dim3(h->B / h->TM), dim3(WG), lds, h->stream, a, h->TM);
+    hipLaunchKernelGGL(kern, dim3(h->B / TM), dim3(WG), lds, h->stream, a, TM);
     return hipGetLastError();
 }
 
 void fill_rollout_args(anakin* h, RolloutArgs& a);
 
+template <int ENV, bool M32, int RW>
+static hipError_t launch_resident(anakin* h, const RolloutArgs& a)
+{
+    constexpr int TM = M32 ? 32 : 16;
+    size_t lds = rollout_lds_bytes(h->net, h->env, TM, nullptr);
+    if (ENV != ENV_MAZE) lds += (size_t)h->net.dims[0] * RW * 4;
+    auto kern = rollout_resident_kernel<ENV, M32, RW, RW>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ProfScope prof(h, "rollout");
+    hipLaunchKernelGGL(kern, dim3(h->B / TM), dim3(WG), lds, h->stream, a);
+    return hipGetLastError();
+}
+
+template <int ENV>
+static hipError_t launch_resident_env(anakin* h, const RolloutArgs& a, int width, int tm)
+{
+    if (width == 256) return tm == 32 ? launch_resident<ENV, true, 256>(h, a) : launch_resident<ENV, false, 256>(h, a);
+    if (width == 128) return tm == 32 ? launch_resident<ENV, true, 128>(h, a) : launch_resident<ENV, false, 128>(h, a);
+    return launch_resident<ENV, false, 64>(h, a);
+}
+
 hipError_t launch_rollout(anakin* h)
 {
     RolloutArgs a;
     fill_rollout_args(h, a);
-    const size_t lds = rollout_lds_bytes(h->net, h->env, h->TM, nullptr);
     const bool bf = h->net.bf16 != 0;
+    if (h->TM_res > 0 && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS))) {
+        const int w = rollout_resident_width(h->net);
+        switch (h->env.kind) {
+            case ENV_CATCH:    return launch_resident_env<ENV_CATCH>(h, a, w, h->TM_res);
+            case ENV_PENDULUM: return launch_resident_env<ENV_PENDULUM>(h, a, w, h->TM_res);
+            default:           return launch_resident_env<ENV_MAZE>(h, a, w, h->TM_res);
+        }
+    }
+    const bool mf = h->TM_mfma > 0 && !(h->mode & ANAKIN_MODE_CANONICAL_ACTING);
+    if (mf) {
+        switch (h->env.kind) {
+            case ENV_CATCH:    return launch_one<ENV_CATCH, false, true>(h, a, h->TM_mfma);
+            case ENV_PENDULUM: return launch_one<ENV_PENDULUM, false, true>(h, a, h->TM_mfma);
+            default:           return launch_one<ENV_MAZE, false, true>(h, a, h->TM_mfma);
+        }
+    }
     switch (h->env.kind) {
-        case ENV_CATCH:    return bf ? launch_one<ENV_CATCH, true>(h, a, lds) : launch_one<ENV_CATCH, false>(h, a, lds);
-        case ENV_PENDULUM: return bf ? launch_one<ENV_PENDULUM, true>(h, a, lds) : launch_one<ENV_PENDULUM, false>(h, a, lds);
-        default:           return bf ? launch_one<ENV_MAZE, true>(h, a, lds) : launch_one<ENV_MAZE, false>(h, a, lds);
+        case ENV_CATCH:    return bf ? launch_one<ENV_CATCH, true, false>(h, a, h->TM) : launch_one<ENV_CATCH, false, false>(h, a, h->TM);
+        case ENV_PENDULUM: return bf ? launch_one<ENV_PENDULUM, true, false>(h, a, h->TM) : launch_one<ENV_PENDULUM, false, false>(h, a, h->TM);
+        default:           return bf ? launch_one<ENV_MAZE, true, false>(h, a, h->TM) : launch_one<ENV_MAZE, false, false>(h, a, h->TM);
     }
 }
 
