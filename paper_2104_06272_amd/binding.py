@@ -11,7 +11,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libanakin.so")
+LIB_PATH = os.environ.get("ANAKIN_LIB", os.path.join(_HERE, "libanakin.so"))
 
 OK = 0
 E_INVALID_ARG, E_BAD_CONFIG, E_WORKSPACE_TOO_SMALL, E_MISALIGNED, E_HIP, E_NONFINITE, E_STATE = -1, -2, -3, -4, -5, -6, -7

@@ -12,7 +12,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libanakin.so")
+LIB = os.environ.get("ANAKIN_OUT", os.path.join(HERE, "libanakin.so"))
 SOURCES = ["anakin.hip", "rollout.hip", "learn.hip", "gemm.hip", "gemm_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -33,7 +33,7 @@ def torch_lib_dir():
 def build(verbose=True, jobs=8):
     objs = []
     procs = []
-    bdir = os.path.join(HERE, "_build")
+    bdir = os.environ.get("ANAKIN_BUILD_DIR", os.path.join(HERE, "_build"))
     os.makedirs(bdir, exist_ok=True)
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))

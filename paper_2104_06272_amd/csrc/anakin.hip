@@ -107,7 +107,7 @@ static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* s
     L.total = off;
 }
 
-static void plan(const NetShape& ns, int B, int T, int* splits, int* loss_blocks)
+static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* splits, int* loss_blocks)
 {
     const int M = B * T;
     for (int l = 0; l < MAX_REGIONS; ++l) splits[l] = 0;
@@ -115,7 +115,8 @@ static void plan(const NetShape& ns, int B, int T, int* splits, int* loss_blocks
         const int tiles = ((ns.dims[l] + 127) / 128) * ((ns.dims[l + 1] + 127) / 128);
         splits[l] = pick_splits(M, tiles, 256);
     }
-    splits[ns.L] = pick_splits(M, 2, 512);
+    splits[ns.L] = pick_splits(M, 1, 1024);
+    if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
     *loss_blocks = (M + WG - 1) / WG;
 }
 
@@ -124,7 +125,7 @@ extern "C" size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin
     EnvDims ed; NetShape ns; std::string err;
     if (build_shapes(env, net, B, T, ed, ns, err) != ANAKIN_OK) return 0;
     int splits[MAX_REGIONS], lb;
-    plan(ns, B, T, splits, &lb);
+    plan(ed, ns, B, T, splits, &lb);
     Layout L;
     carve(ed, ns, B, T, splits, lb, L);
     return L.total;
@@ -252,7 +253,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
-    plan(ns, B, T, h->splits, &h->loss_blocks);
+    plan(ed, ns, B, T, h->splits, &h->loss_blocks);
     carve(ed, ns, B, T, h->splits, h->loss_blocks, h->lay);
     if (h->lay.total > workspace_bytes) {
         g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";

@@ -169,6 +169,12 @@ hipError_t launch_backward(anakin* h)
     const NetShape& n = h->net;
     const int M = h->B * h->T;
     for (int l = n.L - 1; l >= 0; --l) {
+        // one-hot boards (Catch) and the 3-feature pendulum need no GEMM for the first layer
+        if (l == 0 && h->env.kind != ENV_MAZE && !(h->mode & ANAKIN_MODE_VALU_GEMM) && (size_t)WG * n.dims[0] * 4 <= 96 * 1024) {
+            e = launch_first_layer_grad(h);
+            if (e != hipSuccess) return e;
+            continue;
+        }
         GemmTnArgs t;
         t.M = M; t.K = n.dims[l]; t.N = n.dims[l + 1];
         t.splits = h->splits[l]; t.rows = M / t.splits;

@@ -30,25 +30,35 @@ __device__ __forceinline__ f16v mfma32(float a, float b, f16v c)
 
 // ---------------------------------------------------------------------------
 // dX = (dY W^T) masked by relu'(x).  Both operands are contiguous along the
-// reduction index j, so tiles are stored [row][j] in LDS with an odd row stride
-// (conflict-free operand reads: 32 lanes walk 32 rows).
+// reduction index j, so tiles are stored [row][j] in LDS and every lane fetches
+// four consecutive j with one 16-byte read, feeding four MFMA steps (the order
+// of the reduction is free here, so step s of a group takes j = 8g + 4 (l/32) + s).
+// Row stride 36 floats: eight consecutive rows cover all 32 banks.
 // ---------------------------------------------------------------------------
+constexpr int NT_BK = 32;
+constexpr int NT_LD = NT_BK + 4;
+
 __global__ __launch_bounds__(WG) void gemm_nt_mask_mfma(const GemmNtArgs a)
 {
-    constexpr int LD = BK + 1;
-    __shared__ float As[BT * LD];        // dY tile [m][j]
-    __shared__ float Bs[BT * LD];        // W tile  [i][j]
+    __shared__ __attribute__((aligned(16))) float As[BT * NT_LD];        // dY tile [m][j]
+    __shared__ __attribute__((aligned(16))) float Bs[BT * NT_LD];        // W tile  [i][j]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.x * BT, i0 = blockIdx.y * BT;
-    const int lrow = tid >> 1, lk = (tid & 1) * 8;                 // loader: one row, 8 consecutive j
+    const int lrow = tid >> 1, lk = (tid & 1) * 16;                // loader: one row, 16 consecutive j
     const bool a_ok = m0 + lrow < a.M, b_ok = i0 + lrow < a.K;
     const float* ap = a.dy + (size_t)(m0 + lrow) * a.N + lk;
     const float* bp = a.w + (size_t)(i0 + lrow) * a.N + lk;
     const float4 zero = make_float4(0, 0, 0, 0);
-    float4 ra0 = zero, ra1 = zero, rb0 = zero, rb1 = zero;
-    if (a_ok) { ra0 = *reinterpret_cast<const float4*>(ap); ra1 = *reinterpret_cast<const float4*>(ap + 4); }
-    if (b_ok) { rb0 = *reinterpret_cast<const float4*>(bp); rb1 = *reinterpret_cast<const float4*>(bp + 4); }
+    float4 ra[4] = {zero, zero, zero, zero}, rb[4] = {zero, zero, zero, zero};
+    auto fetch = [&](int j0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (a_ok) ra[q] = *reinterpret_cast<const float4*>(ap + j0 + 4 * q);
+            if (b_ok) rb[q] = *reinterpret_cast<const float4*>(bp + j0 + 4 * q);
+        }
+    };
+    fetch(0);
     f16v acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -57,25 +67,46 @@ __global__ __launch_bounds__(WG) void gemm_nt_mask_mfma(const GemmNtArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     const int l32 = lane & 31, lhi = lane >> 5;
-    for (int j0 = 0; j0 < a.N; j0 += BK) {
-        float* as = As + lrow * LD + lk;
-        float* bs = Bs + lrow * LD + lk;
-        as[0] = ra0.x; as[1] = ra0.y; as[2] = ra0.z; as[3] = ra0.w; as[4] = ra1.x; as[5] = ra1.y; as[6] = ra1.z; as[7] = ra1.w;
-        bs[0] = rb0.x; bs[1] = rb0.y; bs[2] = rb0.z; bs[3] = rb0.w; bs[4] = rb1.x; bs[5] = rb1.y; bs[6] = rb1.z; bs[7] = rb1.w;
+    const float* __restrict__ xin = a.x;
+    float* __restrict__ dxo = a.dx;
+    float xm[4][16];                                               // relu mask source, fetched during the last chunk
+    const float* a_rd = As + (wm * 64 + l32) * NT_LD + 4 * lhi;
+    const float* b_rd = Bs + (wn * 64 + l32) * NT_LD + 4 * lhi;
+    for (int j0 = 0; j0 < a.N; j0 += NT_BK) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            *reinterpret_cast<float4*>(&As[lrow * NT_LD + lk + 4 * q]) = ra[q];
+            *reinterpret_cast<float4*>(&Bs[lrow * NT_LD + lk + 4 * q]) = rb[q];
+        }
         __syncthreads();
-        if (j0 + BK < a.N) {                                       // prefetch the next chunk
-            if (a_ok) { ra0 = *reinterpret_cast<const float4*>(ap + j0 + BK); ra1 = *reinterpret_cast<const float4*>(ap + j0 + BK + 4); }
-            if (b_ok) { rb0 = *reinterpret_cast<const float4*>(bp + j0 + BK); rb1 = *reinterpret_cast<const float4*>(bp + j0 + BK + 4); }
+        if (j0 + NT_BK < a.N) fetch(j0 + NT_BK);                  // next chunk in flight during the MFMAs
+        else {                                                     // last chunk: fetch the relu mask under the MFMAs
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                const int i = i0 + wn * 64 + (t4 & 1) * 32 + l32;
+                const int mb = m0 + wm * 64 + (t4 >> 1) * 32 + 4 * lhi;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = mb + 8 * (r >> 2) + (r & 3);
+                    xm[t4][r] = (m < a.M && i < a.K) ? xin[(size_t)m * a.K + i] : 0.0f;
+                }
+            }
         }
 #pragma unroll
-        for (int ks = 0; ks < BK; ks += 2) {
-            const int k = ks + lhi;
-            const float a0 = As[(wm * 64 + l32) * LD + k], a1 = As[(wm * 64 + 32 + l32) * LD + k];
-            const float b0 = Bs[(wn * 64 + l32) * LD + k], b1 = Bs[(wn * 64 + 32 + l32) * LD + k];
-            acc[0][0] = mfma32(a0, b0, acc[0][0]);
-            acc[0][1] = mfma32(a0, b1, acc[0][1]);
-            acc[1][0] = mfma32(a1, b0, acc[1][0]);
-            acc[1][1] = mfma32(a1, b1, acc[1][1]);
+        for (int g = 0; g < NT_BK / 8; ++g) {
+            const float4 a0 = *reinterpret_cast<const float4*>(a_rd + 8 * g);
+            const float4 a1 = *reinterpret_cast<const float4*>(a_rd + 32 * NT_LD + 8 * g);
+            const float4 b0 = *reinterpret_cast<const float4*>(b_rd + 8 * g);
+            const float4 b1 = *reinterpret_cast<const float4*>(b_rd + 32 * NT_LD + 8 * g);
+            const float a0s[4] = {a0.x, a0.y, a0.z, a0.w}, a1s[4] = {a1.x, a1.y, a1.z, a1.w};
+            const float b0s[4] = {b0.x, b0.y, b0.z, b0.w}, b1s[4] = {b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                acc[0][0] = mfma32(a0s[st], b0s[st], acc[0][0]);
+                acc[0][1] = mfma32(a0s[st], b1s[st], acc[0][1]);
+                acc[1][0] = mfma32(a1s[st], b0s[st], acc[1][0]);
+                acc[1][1] = mfma32(a1s[st], b1s[st], acc[1][1]);
+            }
         }
         __syncthreads();
     }
@@ -84,13 +115,11 @@ __global__ __launch_bounds__(WG) void gemm_nt_mask_mfma(const GemmNtArgs a)
 #pragma unroll
         for (int tc = 0; tc < 2; ++tc) {
             const int i = i0 + wn * 64 + tc * 32 + l32;
+            const int mb = m0 + wm * 64 + tr * 32 + 4 * lhi;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * 64 + tr * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
-                if (m < a.M && i < a.K) {
-                    const size_t o = (size_t)m * a.K + i;
-                    a.dx[o] = a.x[o] > 0.0f ? acc[tr][tc][r] : 0.0f;
-                }
+                const int m = mb + 8 * (r >> 2) + (r & 3);
+                if (m < a.M && i < a.K) dxo[(size_t)m * a.K + i] = xm[tr * 2 + tc][r] > 0.0f ? acc[tr][tc][r] : 0.0f;
             }
         }
 }

@@ -44,6 +44,9 @@ struct RolloutArgs {
     uint64_t seed, gstep;
 };
 
+// state snapshots the first layer's input is rebuilt from (row m = t*B + b of the trajectory)
+struct ObsLite { EnvDims env; const uint32_t* s0; const float* f0; const float* f1; };
+
 // split-K partial sums of one parameter region (W_l followed by b_l, or Wh followed by bh)
 struct Region { int start, count, splits; const float* partial; };
 
@@ -117,6 +120,7 @@ hipError_t launch_returns(anakin* h);
 hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);
 hipError_t launch_adam(anakin* h);
+hipError_t launch_first_layer_grad(anakin* h);
 int rollout_pick_tile(const NetShape& net, int B);
 int rollout_pick_tile_mfma(const NetShape& net, int B);
 int rollout_resident_tile(const NetShape& net, int B);

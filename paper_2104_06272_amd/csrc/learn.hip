@@ -171,34 +171,43 @@ __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
         }
 #pragma unroll
     for (int k = 0; k < 8; ++k) db[k] = 0.0f;
-#pragma unroll 2
-    for (int m = m_begin + g; m < m_end; m += groups) {
-        const float* dh = a.dhead + (size_t)m * NHP;
-        float d[8];
-        const float4 d0 = *reinterpret_cast<const float4*>(dh);
-        d[0] = d0.x; d[1] = d0.y; d[2] = d0.z; d[3] = d0.w;
-        if (NHP == 8) {
-            const float4 d1 = *reinterpret_cast<const float4*>(dh + 4);
-            d[4] = d1.x; d[5] = d1.y; d[6] = d1.z; d[7] = d1.w;
-        } else { d[4] = d[5] = d[6] = d[7] = 0.0f; }
-        const float4 hv4 = *reinterpret_cast<const float4*>(a.h + (size_t)m * H + j);
-        const float hv[4] = {hv4.x, hv4.y, hv4.z, hv4.w};
-        float o[4];
+    const float* __restrict__ hin = a.h;
+    const float* __restrict__ dhin = a.dhead;
+    float* __restrict__ dzo = a.dz;
+    constexpr int RB = 4;                                   // rows in flight per lane
+    for (int mb = m_begin + g; mb < m_end; mb += RB * groups) {
+        float4 hv4[RB], d0[RB], d1[RB];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            float s = 0.0f;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (k < NH) {
-                    s = fmaf(w[c][k], d[k], s);
-                    dw[c][k] = fmaf(hv[c], d[k], dw[c][k]);
-                }
-            }
-            o[c] = hv[c] > 0.0f ? s : 0.0f;
+        for (int u = 0; u < RB; ++u) {
+            const int m = mb + u * groups;
+            const bool ok = m < m_end;
+            hv4[u] = ok ? *reinterpret_cast<const float4*>(hin + (size_t)m * H + j) : make_float4(0, 0, 0, 0);
+            d0[u] = ok ? *reinterpret_cast<const float4*>(dhin + (size_t)m * NHP) : make_float4(0, 0, 0, 0);
+            d1[u] = (ok && NHP == 8) ? *reinterpret_cast<const float4*>(dhin + (size_t)m * NHP + 4) : make_float4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) if (k < NH) db[k] += d[k];
-        *reinterpret_cast<float4*>(a.dz + (size_t)m * H + j) = make_float4(o[0], o[1], o[2], o[3]);
+        for (int u = 0; u < RB; ++u) {
+            const int m = mb + u * groups;
+            if (m >= m_end) break;
+            const float d[8] = {d0[u].x, d0[u].y, d0[u].z, d0[u].w, d1[u].x, d1[u].y, d1[u].z, d1[u].w};
+            const float hv[4] = {hv4[u].x, hv4[u].y, hv4[u].z, hv4[u].w};
+            float o[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float sacc = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (k < NH) {
+                        sacc = fmaf(w[c][k], d[k], sacc);
+                        dw[c][k] = fmaf(hv[c], d[k], dw[c][k]);
+                    }
+                }
+                o[c] = hv[c] > 0.0f ? sacc : 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) if (k < NH) db[k] += d[k];
+            *reinterpret_cast<float4*>(dzo + (size_t)m * H + j) = make_float4(o[0], o[1], o[2], o[3]);
+        }
     }
     // combine the row groups in ascending group order
     const int stride = H * NH + NH;
@@ -214,6 +223,107 @@ __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
         for (int gg = 0; gg < groups; ++gg) s += lds[(size_t)gg * stride + i];
         out[i] = s;
     }
+}
+
+// ---------------------------------------------------------------------------
+// First-layer gradient without a GEMM.  The Catch observation is a 0/1 board
+// with exactly two cells set, so dW1 = X^T dZ1 is a scatter: every sample adds
+// its dZ1 row into the two weight rows its board selects.  Lane j owns column j
+// of an LDS accumulator [cells][columns]; rows of the chunk are visited in
+// order, so the sum is deterministic and needs no atomics.  The pendulum's
+// three-feature observation is handled by the same kernel with three register
+// accumulators per lane.  Column sums (the bias gradient) come for free.
+// ---------------------------------------------------------------------------
+struct FirstGradArgs {
+    int M, K, N, rows;
+    const float* dy;          // [M][N] gradient w.r.t. the first layer's pre-activations
+    float* partial;           // [splits][K*N + N]
+    ObsLite obs;
+};
+
+template <int ENV>
+__global__ __launch_bounds__(WG) void first_layer_grad(const FirstGradArgs a)
+{
+    extern __shared__ float accs[];                          // [groups][K][cw]
+    const int N = a.N, K = a.K;
+    const int cw = N < WG ? N : WG, groups = WG / cw;
+    const int g = threadIdx.x / cw, jl = threadIdx.x % cw;
+    const int j = blockIdx.y * WG + jl;
+    const int split = blockIdx.x;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    float* mine = accs + (size_t)g * K * cw + jl;            // this lane's column, stride cw between cells
+    if (ENV == ENV_CATCH) for (int k = 0; k < K; ++k) mine[k * cw] = 0.0f;
+    float bsum = 0.0f, r0 = 0.0f, r1 = 0.0f, r2 = 0.0f;
+    const float* __restrict__ dyin = a.dy;
+    constexpr int RB = 16;                                   // rows in flight per lane
+    for (int mb = m_begin + g; mb < m_end; mb += RB * groups) {
+        float d[RB], f0[RB], f1[RB];
+        uint32_t sw[RB];
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const int m = mb + u * groups;
+            const bool ok = m < m_end;
+            d[u] = ok ? dyin[(size_t)m * N + j] : 0.0f;
+            if (ENV == ENV_CATCH) sw[u] = ok ? a.obs.s0[m] : 0u;
+            else { f0[u] = ok ? a.obs.f0[m] : 0.0f; f1[u] = ok ? a.obs.f1[m] : 0.0f; }
+        }
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            if (mb + u * groups >= m_end) break;
+            bsum += d[u];
+            if (ENV == ENV_CATCH) {
+                int bc, pc;
+                catch_obs_cells(a.obs.env, sw[u], bc, pc);
+                mine[bc * cw] += d[u];
+                mine[pc * cw] += d[u];
+            } else {
+                float sn, cs;
+                det_sincos(f0[u], sn, cs);
+                r0 = fmaf(cs, d[u], r0); r1 = fmaf(sn, d[u], r1); r2 = fmaf(f1[u], d[u], r2);
+            }
+        }
+    }
+    float* out = a.partial + (size_t)split * ((size_t)K * N + N);
+    if (ENV != ENV_CATCH) { mine[0] = r0; mine[cw] = r1; mine[2 * cw] = r2; }
+    __shared__ float bred[WG];
+    bred[threadIdx.x] = bsum;
+    __syncthreads();
+    // combine the row groups in ascending order
+    for (int i = threadIdx.x; i < K * cw; i += WG) {
+        const int k = i / cw, c = i % cw;
+        float s = 0.0f;
+        for (int gg = 0; gg < groups; ++gg) s += accs[((size_t)gg * K + k) * cw + c];
+        out[(size_t)k * N + blockIdx.y * WG + c] = s;
+    }
+    if (threadIdx.x < cw) {
+        float s = 0.0f;
+        for (int gg = 0; gg < groups; ++gg) s += bred[gg * cw + threadIdx.x];
+        out[(size_t)K * N + blockIdx.y * WG + threadIdx.x] = s;
+    }
+}
+
+hipError_t launch_first_layer_grad(anakin* h)
+{
+    const Layout& L = h->lay;
+    const NetShape& n = h->net;
+    FirstGradArgs a;
+    a.M = h->B * h->T; a.K = n.dims[0]; a.N = n.dims[1];
+    a.rows = a.M / h->splits[0];
+    a.dy = at<const float>(h, L.dz[0]); a.partial = at<float>(h, L.part[0]);
+    a.obs.env = h->env; a.obs.s0 = at<const uint32_t>(h, L.tr_s0);
+    a.obs.f0 = at<const float>(h, L.tr_f0); a.obs.f1 = at<const float>(h, L.tr_f1);
+    const size_t lds = (size_t)WG * a.K * sizeof(float);
+    const dim3 grid(h->splits[0], (a.N + WG - 1) / WG);
+    ProfScope prof(h, "first_layer_grad");
+    if (h->env.kind == ENV_CATCH) {
+        auto kern = first_layer_grad<ENV_CATCH>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, dim3(WG), lds, h->stream, a);
+    } else {
+        hipLaunchKernelGGL(first_layer_grad<ENV_PENDULUM>, grid, dim3(WG), lds, h->stream, a);
+    }
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
