@@ -79,7 +79,7 @@ static int pick_splits(int M, int tiles, int max_splits)
     return s;
 }
 
-static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* splits, int loss_blocks, Layout& L)
+static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* splits, int head_fan, int loss_blocks, Layout& L)
 {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
@@ -103,11 +103,12 @@ static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* s
         else if (l == ns.L) cnt = (size_t)ns.dims[ns.L] * ns.NH + ns.NH;
         L.part[l] = take(cnt * 4 * (size_t)(l <= ns.L ? splits[l] : 0));
     }
+    L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
     L.loss_part = take((size_t)loss_blocks * 8 * 4);
     L.total = off;
 }
 
-static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* splits, int* loss_blocks)
+static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* splits, int* head_fan, int* loss_blocks)
 {
     const int M = B * T;
     for (int l = 0; l < MAX_REGIONS; ++l) splits[l] = 0;
@@ -115,8 +116,12 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         const int tiles = ((ns.dims[l] + 127) / 128) * ((ns.dims[l + 1] + 127) / 128);
         splits[l] = pick_splits(M, tiles, 256);
     }
-    splits[ns.L] = pick_splits(M, 1, 1024);
+    splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256);
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
+    // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
+    int fan = 1;
+    while (fan < 16 && (M / 16) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 32) fan *= 2;
+    *head_fan = fan;
     *loss_blocks = (M + WG - 1) / WG;
 }
 
@@ -124,10 +129,10 @@ extern "C" size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin
 {
     EnvDims ed; NetShape ns; std::string err;
     if (build_shapes(env, net, B, T, ed, ns, err) != ANAKIN_OK) return 0;
-    int splits[MAX_REGIONS], lb;
-    plan(ed, ns, B, T, splits, &lb);
+    int splits[MAX_REGIONS], lb, fan;
+    plan(ed, ns, B, T, splits, &fan, &lb);
     Layout L;
-    carve(ed, ns, B, T, splits, lb, L);
+    carve(ed, ns, B, T, splits, fan, lb, L);
     return L.total;
 }
 
@@ -253,8 +258,8 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
-    plan(ed, ns, B, T, h->splits, &h->loss_blocks);
-    carve(ed, ns, B, T, h->splits, h->loss_blocks, h->lay);
+    plan(ed, ns, B, T, h->splits, &h->head_fan, &h->loss_blocks);
+    carve(ed, ns, B, T, h->splits, h->head_fan, h->loss_blocks, h->lay);
     if (h->lay.total > workspace_bytes) {
         g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";
         delete h; return ANAKIN_E_WORKSPACE_TOO_SMALL;

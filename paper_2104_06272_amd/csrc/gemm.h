@@ -24,7 +24,7 @@ struct GemmNtArgs {
 
 // partial[s][i][j] = sum over rows of chunk s of x[m][i] dY[m][j]; partial[s][K*N + j] = column sums of dY
 struct GemmTnArgs {
-    int M, K, N, bf16, splits, rows, tiles_i, use_obs;
+    int M, K, N, ldy, bf16, splits, rows, tiles_i, use_obs;   // ldy: row stride of dy (>= N)
     const float* x;       // [M][K], unused when use_obs
     const float* dy;      // [M][N]
     float* partial;       // [splits][K*N + N]

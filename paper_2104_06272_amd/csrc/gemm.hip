@@ -112,7 +112,7 @@ __global__ __launch_bounds__(WG) void gemm_tn_splitk_valu(const GemmTnArgs a)
         } else if (i0 + lc < a.K) {
             vx = *reinterpret_cast<const float4*>(a.x + (size_t)m * a.K + i0 + lc);
         }
-        if (j0 + lc < a.N) vy = *reinterpret_cast<const float4*>(a.dy + (size_t)m * a.N + j0 + lc);
+        if (j0 + lc < a.ldy) vy = *reinterpret_cast<const float4*>(a.dy + (size_t)m * a.ldy + j0 + lc);
         *reinterpret_cast<float4*>(&Xs[lr][lc]) = vx;
         *reinterpret_cast<float4*>(&Ys[lr][lc]) = vy;
         __syncthreads();
@@ -163,11 +163,12 @@ hipError_t launch_head_backward(anakin* h);
 
 hipError_t launch_backward(anakin* h)
 {
-    hipError_t e = launch_head_backward(h);
-    if (e != hipSuccess) return e;
     const Layout& L = h->lay;
     const NetShape& n = h->net;
     const int M = h->B * h->T;
+    hipError_t e;
+    e = launch_head_backward(h);
+    if (e != hipSuccess) return e;
     for (int l = n.L - 1; l >= 0; --l) {
         // one-hot boards (Catch) and the 3-feature pendulum need no GEMM for the first layer
         if (l == 0 && h->env.kind != ENV_MAZE && !(h->mode & ANAKIN_MODE_VALU_GEMM) && (size_t)WG * n.dims[0] * 4 <= 96 * 1024) {
@@ -176,7 +177,7 @@ hipError_t launch_backward(anakin* h)
             continue;
         }
         GemmTnArgs t;
-        t.M = M; t.K = n.dims[l]; t.N = n.dims[l + 1];
+        t.M = M; t.K = n.dims[l]; t.N = n.dims[l + 1]; t.ldy = t.N;
         t.splits = h->splits[l]; t.rows = M / t.splits;
         t.dy = at<const float>(h, L.dz[l]);
         t.partial = at<float>(h, L.part[l]);

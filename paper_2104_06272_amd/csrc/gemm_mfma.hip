@@ -173,7 +173,7 @@ __global__ __launch_bounds__(WG) void gemm_tn_splitk_mfma(const GemmTnArgs a)
     const int split = blockIdx.y;
     const int m_begin = split * a.rows, m_end = m_begin + a.rows;
     const int lrow = tid >> 4, lc = (tid & 15) * 8;                // loader: one sample row, 8 consecutive columns
-    const bool x_ok = i0 + lc < a.K, y_ok = j0 + lc < a.N;        // K, N are multiples of 8 on the dense path
+    const bool x_ok = i0 + lc < a.K, y_ok = j0 + lc < a.ldy;      // K is a multiple of 8 on the dense path, ldy of 4
     const float4 zero = make_float4(0, 0, 0, 0);
     float4 rx0 = zero, rx1 = zero, ry0 = zero, ry1 = zero;
     auto fetch = [&](int mb) {
@@ -187,8 +187,9 @@ __global__ __launch_bounds__(WG) void gemm_tn_splitk_mfma(const GemmTnArgs a)
             rx0 = *reinterpret_cast<const float4*>(p); rx1 = *reinterpret_cast<const float4*>(p + 4);
         }
         if (y_ok) {
-            const float* p = a.dy + (size_t)m * a.N + j0 + lc;
-            ry0 = *reinterpret_cast<const float4*>(p); ry1 = *reinterpret_cast<const float4*>(p + 4);
+            const float* p = a.dy + (size_t)m * a.ldy + j0 + lc;
+            ry0 = *reinterpret_cast<const float4*>(p);
+            if (j0 + lc + 4 < a.ldy) ry1 = *reinterpret_cast<const float4*>(p + 4);
         }
     };
     fetch(m_begin);

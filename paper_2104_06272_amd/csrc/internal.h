@@ -67,6 +67,7 @@ struct Layout {
     size_t adv, ret, dhead;
     size_t act[MAX_LAYERS], dz[MAX_LAYERS];
     size_t part[MAX_REGIONS];
+    size_t head_stage;           // first-stage partials of the head gradient
     size_t loss_part;
     size_t total;
 };
@@ -92,6 +93,7 @@ struct anakin {
     int TM_res;                   // envs per workgroup in the weights-resident rollout kernel (0: not applicable)
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
+    int head_fan;                 // first-stage workgroups per split of the head-gradient pass
     std::string err;
     // optional per-kernel timing with events on the launch stream
     int prof_on;

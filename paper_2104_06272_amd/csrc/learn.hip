@@ -226,6 +226,22 @@ __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// Second stage of a two-level split-K sum: dst[s][i] = sum_{f < fan} src[s*fan + f][i],
+// in ascending f.  Lets a bandwidth-bound producer use many small workgroups while the
+// Adam kernel still sees few partials.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(WG) void partial_reduce(const float* __restrict__ src, float* __restrict__ dst, int count, int fan)
+{
+    const int i = blockIdx.x * WG + threadIdx.x, s = blockIdx.y;
+    if (i >= count) return;
+    const float* p = src + (size_t)s * fan * count + i;
+    float acc = 0.0f;
+#pragma unroll 4
+    for (int f = 0; f < fan; ++f) acc += p[(size_t)f * count];
+    dst[(size_t)s * count + i] = acc;
+}
+
+// ---------------------------------------------------------------------------
 // First-layer gradient without a GEMM.  The Catch observation is a 0/1 board
 // with exactly two cells set, so dW1 = X^T dZ1 is a scatter: every sample adds
 // its dZ1 row into the two weight rows its board selects.  Lane j owns column j
@@ -402,16 +418,26 @@ hipError_t launch_head_backward(anakin* h)
     const NetShape& n = h->net;
     HeadBwdArgs a;
     a.M = h->B * h->T; a.H = n.dims[n.L]; a.NH = n.NH; a.NHP = n.NHP;
-    const int splits = h->splits[n.L];
-    a.rows = a.M / splits;
+    const int splits = h->splits[n.L], fan = h->head_fan;
+    const int stage1 = splits * fan;                        // workgroups of the streaming pass
+    a.rows = a.M / stage1;
     a.h = at<const float>(h, L.act[n.L - 1]); a.dhead = at<const float>(h, L.dhead);
     a.wh = at<const float>(h, L.theta) + n.wh_off;
-    a.dz = at<float>(h, L.dz[n.L - 1]); a.partial = at<float>(h, L.part[n.L]);
+    a.dz = at<float>(h, L.dz[n.L - 1]);
+    a.partial = fan > 1 ? at<float>(h, L.head_stage) : at<float>(h, L.part[n.L]);
     a.bf16 = n.bf16;
     const int groups = WG / (a.H >> 2);
-    const size_t lds = (size_t)groups * (a.H * a.NH + a.NH) * sizeof(float);
-    ProfScope prof(h, "head_backward");
-    hipLaunchKernelGGL(head_backward, dim3(splits), dim3(WG), lds, h->stream, a);
+    const int stride = a.H * a.NH + a.NH;
+    const size_t lds = (size_t)groups * stride * sizeof(float);
+    {
+        ProfScope prof(h, "head_backward");
+        hipLaunchKernelGGL(head_backward, dim3(stage1), dim3(WG), lds, h->stream, a);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || fan == 1) return e;
+    ProfScope prof(h, "partial_reduce");
+    hipLaunchKernelGGL(partial_reduce, dim3((stride + WG - 1) / WG, splits), dim3(WG), 0, h->stream,
+                       at<const float>(h, L.head_stage), at<float>(h, L.part[n.L]), stride, fan);
     return hipGetLastError();
 }
 
