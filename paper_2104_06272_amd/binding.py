@@ -275,7 +275,8 @@ class Anakin:
         for l in range(v.n_hidden):
             H = v.hidden[l]
             if v.act_is_bf16:
-                a = self.ws[v.off_act[l]:v.off_act[l] + T * B * H * 2].view(torch.bfloat16).float().cpu().numpy()
+                a = self.ws[v.off_act[l]:v.off_act[l] + T * B * H * 2].view(torch.bfloat16).float()
+                a = a.view(T * B // 8, H, 8).permute(0, 2, 1).contiguous().cpu().numpy()
             else:
                 a = grab(v.off_act[l], T * B * H, torch.float32)
             acts.append(a.reshape(T, B, H))

@@ -69,12 +69,12 @@ static int build_shapes(const anakin_env_cfg* env, const anakin_net_cfg* net, in
 
 // split-K factor for a reduction over M samples feeding `tiles` output tiles:
 // chunks are multiples of 16 rows; aim for about 1024 workgroups, at most max_splits splits
-static int pick_splits(int M, int tiles, int max_splits)
+static int pick_splits(int M, int tiles, int max_splits, int quantum = 16)
 {
     int cap = 1024 / (tiles > 0 ? tiles : 1);
     if (cap > max_splits) cap = max_splits;
     if (cap < 1) cap = 1;
-    int s = M / 16;
+    int s = M / quantum;
     while (s > cap && s % 2 == 0) s /= 2;
     return s;
 }
@@ -104,6 +104,7 @@ static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* s
         L.part[l] = take(cnt * 4 * (size_t)(l <= ns.L ? splits[l] : 0));
     }
     L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
+    L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
     L.loss_part = take((size_t)loss_blocks * 8 * 4);
     L.total = off;
 }
@@ -119,8 +120,11 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256);
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
+    const bool bfp = rollout_bf16_ok(ns, B);
+    const int hq = bfp ? 64 : 16;                       // row quantum of the head pass
+    if (bfp) splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256, 64);
     int fan = 1;
-    while (fan < 16 && (M / 16) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 32) fan *= 2;
+    while (fan < 16 && (M / hq) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 2 * hq) fan *= 2;
     *head_fan = fan;
     *loss_blocks = (M + WG - 1) / WG;
 }
@@ -255,7 +259,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     anakin* h = new (std::nothrow) anakin();
     if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
-    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0;
+    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ed, ns, B, T, h->splits, &h->head_fan, &h->loss_blocks);
@@ -267,6 +271,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->TM = rollout_pick_tile(ns, B);
     h->TM_mfma = rollout_pick_tile_mfma(ns, B);
     h->TM_res = rollout_resident_tile(ns, B);
+    h->bf16_path = rollout_bf16_ok(ns, B) ? 1 : 0;
 
     auto fail = [&](int code) { g_create_error = h->err; delete h; return code; };
     // parameters and optimiser state
@@ -277,6 +282,10 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.m, 0, (size_t)ns.P * 4, h->stream);
     if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.v, 0, (size_t)ns.P * 4, h->stream);
     if (e != hipSuccess) { h->err = std::string("hipMemsetAsync: ") + hipGetErrorString(e); return fail(ANAKIN_E_HIP); }
+    if (ns.bf16) {
+        e = launch_refresh_bf16(h);
+        if (e != hipSuccess) { h->err = std::string("refresh_bf16: ") + hipGetErrorString(e); return fail(ANAKIN_E_HIP); }
+    }
     // initial env states
     std::vector<uint32_t> s0((size_t)B), walls(ed.kind == ENV_MAZE ? (size_t)B * 8 : 0);
     std::vector<float> f0((size_t)B, 0.0f), f1((size_t)B, 0.0f);
@@ -398,7 +407,9 @@ extern "C" int32_t anakin_kernel_times(anakin_t* h, anakin_kernel_time* out, int
 extern "C" int32_t anakin_rollout(anakin_t* h)
 {
     NEED(h);
-    HIPCHK(h, launch_rollout(h));
+    if (bf16_mfma(h)) HIPCHK(h, launch_rollout_bf16(h));
+    else HIPCHK(h, launch_rollout(h));
+    h->traj_packed = bf16_mfma(h) ? 1 : 0;
     h->gstep += (uint64_t)h->T;
     h->have_traj = 1;
     return ANAKIN_OK;
@@ -410,7 +421,9 @@ extern "C" int32_t anakin_learn(anakin_t* h)
     if (!h->have_traj) { h->err = "learn needs a stored trajectory: call anakin_rollout first"; return ANAKIN_E_STATE; }
     HIPCHK(h, launch_returns(h));
     HIPCHK(h, launch_head_grad(h));
-    HIPCHK(h, launch_backward(h));
+    if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
+    if (h->traj_packed) HIPCHK(h, launch_backward_bf16(h));
+    else HIPCHK(h, launch_backward(h));
     HIPCHK(h, launch_adam(h));
     h->have_traj = 0;
     return ANAKIN_OK;
@@ -447,7 +460,12 @@ extern "C" int32_t anakin_get_params(anakin_t* h, float* dst, size_t n)
 extern "C" int32_t anakin_set_params(anakin_t* h, const float* src, size_t n)
 {
     NEED(h); int rc = check_n(h, src, n); if (rc) return rc;
-    return upload(h, h->lay.theta, src, n * 4);
+    if ((rc = upload(h, h->lay.theta, src, n * 4)) != ANAKIN_OK) return rc;
+    if (h->net.bf16) {
+        HIPCHK(h, launch_refresh_bf16(h));
+        HIPCHK(h, hipStreamSynchronize(h->stream));
+    }
+    return ANAKIN_OK;
 }
 extern "C" int32_t anakin_get_grads(anakin_t* h, float* dst, size_t n)
 {
@@ -537,7 +555,7 @@ extern "C" int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* v)
     memset(v, 0, sizeof *v);
     v->B = h->B; v->T = h->T; v->num_heads = h->net.NH; v->head_stride = h->net.NHP; v->n_hidden = h->net.L;
     for (int l = 0; l < h->net.L; ++l) v->hidden[l] = h->net.dims[l + 1];
-    v->act_is_bf16 = 0;
+    v->act_is_bf16 = h->traj_packed ? 2 : 0;
 #define SETP(field, off) v->field = h->ws + (off); v->off_##field = (off)
     SETP(state_s0, L.tr_s0); SETP(state_f0, L.tr_f0); SETP(state_f1, L.tr_f1);
     SETP(action, L.tr_act); SETP(eps, L.tr_eps); SETP(action_f, L.tr_actf);
@@ -570,6 +588,11 @@ extern "C" int32_t anakin_set_mode(anakin_t* h, int32_t flags)
 {
     NEED(h);
     if (flags & ~(ANAKIN_MODE_VALU_GEMM | ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS)) { h->err = "unknown mode flag"; return ANAKIN_E_INVALID_ARG; }
+    const int ref = ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_VALU_GEMM;
+    if (h->net.bf16 && h->bf16_path && (flags & ref) != 0 && (flags & ref) != ref) {
+        h->err = "bf16 networks: the two reference-path flags go together (activation storage differs between the paths)";
+        return ANAKIN_E_INVALID_ARG;
+    }
     h->mode = flags;
     return ANAKIN_OK;
 }

@@ -44,6 +44,19 @@ struct RolloutArgs {
     uint64_t seed, gstep;
 };
 
+// position of parameter i in the copy that stores every weight matrix transposed
+// (layers [N][K], heads [NH][HL]); biases keep their place
+ANK_HD int transposed_index(const NetShape& n, int i)
+{
+    for (int l = 0; l < n.L; ++l) {
+        const int K = n.dims[l], N = n.dims[l + 1], off = i - n.w_off[l];
+        if (off >= 0 && off < K * N) return n.w_off[l] + (off % N) * K + off / N;
+    }
+    const int off = i - n.wh_off, HL = n.dims[n.L];
+    if (off >= 0 && off < HL * n.NH) return n.wh_off + (off % n.NH) * HL + off / n.NH;
+    return i;
+}
+
 // state snapshots the first layer's input is rebuilt from (row m = t*B + b of the trajectory)
 struct ObsLite { EnvDims env; const uint32_t* s0; const float* f0; const float* f1; };
 
@@ -68,6 +81,7 @@ struct Layout {
     size_t act[MAX_LAYERS], dz[MAX_LAYERS];
     size_t part[MAX_REGIONS];
     size_t head_stage;           // first-stage partials of the head gradient
+    size_t prefix;               // bf16 acting: per-env first-layer prefix [B][H1] fp32
     size_t loss_part;
     size_t total;
 };
@@ -94,6 +108,8 @@ struct anakin {
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
     int head_fan;                 // first-stage workgroups per split of the head-gradient pass
+    int bf16_path;                // the bf16 matrix-core kernels support this net
+    int traj_packed;              // the stored unroll holds packed bf16 activations
     std::string err;
     // optional per-kernel timing with events on the launch stream
     int prof_on;
@@ -123,6 +139,13 @@ hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);
 hipError_t launch_adam(anakin* h);
 hipError_t launch_first_layer_grad(anakin* h);
+hipError_t launch_partial_reduce(const float* src, float* dst, int count, int fan, int splits, hipStream_t s);
+hipError_t launch_rollout_bf16(anakin* h);
+hipError_t launch_backward_bf16(anakin* h);
+hipError_t launch_refresh_bf16(anakin* h);
+bool rollout_bf16_ok(const NetShape& net, int B);
+// bf16 network running on the matrix-core path (packed bf16 activations) rather than the fp32 reference path
+inline bool bf16_mfma(const anakin* h) { return h->bf16_path && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_VALU_GEMM)); }
 int rollout_pick_tile(const NetShape& net, int B);
 int rollout_pick_tile_mfma(const NetShape& net, int B);
 int rollout_resident_tile(const NetShape& net, int B);

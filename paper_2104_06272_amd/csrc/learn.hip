@@ -381,7 +381,11 @@ __global__ __launch_bounds__(ADAM_WAVES * 64) void adam_reduce(const AdamArgs a)
     a.m[i] = m;
     a.v[i] = v;
     a.theta[i] = th;
-    if (a.w_bf16) a.w_bf16[i] = bf16_bits(th);
+    if (a.w_bf16) {
+        const uint16_t hb = bf16_bits(th);
+        a.w_bf16[i] = hb;
+        a.wt_bf16[transposed_index(a.net, i)] = hb;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -409,6 +413,12 @@ hipError_t launch_head_grad(anakin* h)
     a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef; a.inv_m = (float)(1.0 / (double)a.M);
     ProfScope prof(h, "head_grad");
     hipLaunchKernelGGL(head_grad, dim3(h->loss_blocks), dim3(WG), 0, h->stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_partial_reduce(const float* src, float* dst, int count, int fan, int splits, hipStream_t s)
+{
+    hipLaunchKernelGGL(partial_reduce, dim3((count + WG - 1) / WG, splits), dim3(WG), 0, s, src, dst, count, fan);
     return hipGetLastError();
 }
 
@@ -452,7 +462,8 @@ hipError_t launch_adam(anakin* h)
     a.reg[n.L] = Region{n.wh_off, n.dims[n.L] * n.NH + n.NH, h->splits[n.L], at<const float>(h, L.part[n.L])};
     for (int l = n.L + 1; l < MAX_REGIONS; ++l) a.reg[l] = Region{0x7fffffff, 0, 0, nullptr};
     a.theta = at<float>(h, L.theta); a.grad = at<float>(h, L.grad); a.m = at<float>(h, L.m); a.v = at<float>(h, L.v);
-    a.w_bf16 = nullptr; a.wt_bf16 = nullptr;
+    a.w_bf16 = n.bf16 ? at<uint16_t>(h, L.w_bf16) : nullptr;
+    a.wt_bf16 = n.bf16 ? at<uint16_t>(h, L.wt_bf16) : nullptr;
     a.net = n;
     h->adam_t += 1;
     a.lr = h->net_cfg.lr; a.beta1 = h->net_cfg.beta1; a.beta2 = h->net_cfg.beta2; a.eps = h->net_cfg.eps;

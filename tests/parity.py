@@ -56,6 +56,7 @@ def assert_rollout_equal(g, o, kind, sel=None, head_tol=None):
         assert np.array_equal(tr["value"][:, cols], o.tr_value[:, cols]), "values differ"
     else:
         assert np.array_equal(tr["value"][:, cols], o.tr_value[:, cols])      # forced: both hold the GPU's
+        assert np.array_equal(tr["head"][:, cols], o.tr_head[:, cols])
     return tr
 
 

@@ -164,6 +164,92 @@ def test_full_size_rollout_sampled_envs(gpu, orc, name):
     g.close()
 
 
+# --------------------------------------------------------------------------- bf16 on the matrix cores
+BF16_CASES = {
+    "maze_bf16_128": (variant("maze_16384", hidden=[128, 128, 128], B=64, T=16, max_steps=40), 3, 2),
+    "maze_bf16_256_512": (variant("maze_16384", hidden=[256, 512], B=128, T=8, rows=8, cols=8, max_steps=20), 1, 2),
+    "catch_bf16_128": (variant("catch_4096", hidden=[128, 128], B=64, T=12, dtype="bf16"), 0, 2),
+    "pendulum_bf16_128": (variant("pendulum_8192", hidden=[128, 128], B=64, T=10, dtype="bf16", max_steps=7), 2, 2),
+}
+
+
+def _forced_lockstep(gpu, orc, cfg, seed, updates, sel=None, learn=True):
+    """Logit-forced protocol for the bf16 matrix-core acting path: the accumulation order inside the bf16
+    MFMA is the hardware's, so (1) the GPU's head outputs are checked against the oracle's own sequential
+    forward within the bf16 tolerance, (2) the oracle samples from the GPU's head outputs with its own
+    sampler and RNG and steps its own envs -- actions, rewards, dones and states must then match bit for
+    bit, (3) both learn on the identical unroll and gradients / parameters agree within 2e-2."""
+    kind = cfg["env"]["kind"]
+    g = gpu.Anakin(cfg, seed=seed); o = orc.Oracle(cfg, seed=seed)
+    PT.assert_same_init(g, o, kind)
+    for u in range(updates):
+        PT.sync_oracle_from_gpu(g, o)
+        keep_i, keep_f = o.state_i.copy(), o.state_f.copy()
+        g.rollout()
+        tr = g.trajectory()
+        o.rollout(forced_head=tr["head"], sel=sel)
+        PT.assert_rollout_equal(g, o, kind, sel=sel, head_tol=TOL_BF16)
+        PT.assert_final_state_equal(g, o, kind, sel=sel)
+        # (1) head outputs and stored activations against the oracle's own forward on the same states
+        scale = max(1e-3, float(np.abs(tr["head"]).max()))
+        cols = range(g.B) if sel is None else list(sel)
+        worst = 0.0
+        for (t, b) in [(0, cols[0]), (g.T - 1, cols[-1]), (g.T // 2, cols[len(cols) // 2]), (g.T, cols[1])]:
+            save = (o.state_i[b].copy(), o.state_f[b].copy())
+            o.state_i[b] = o.tr_state_i[t, b]; o.state_f[b] = o.tr_state_f[t, b]
+            x = o.observe(b)
+            o.state_i[b], o.state_f[b] = save
+            head, acts = o.forward(x, want_acts=True)
+            worst = max(worst, float(np.abs(head - tr["head"][t, b]).max()) / scale)
+            if t < g.T:
+                got = np.concatenate([a[t, b] for a in tr["act"]])
+                assert np.abs(got - acts).max() <= 2 ** -6 * max(1.0, float(np.abs(acts).max())), "activations differ"
+        assert worst <= TOL_BF16, f"head outputs differ by {worst:.3e} of their scale"
+        if learn:
+            g.learn(); o.learn()
+            e_g, e_p = PT.assert_learn_close(g, o, TOL_BF16)
+            say(f"  update {u}: head err {worst:.2e}, grad rel {e_g:.2e}, param rel {e_p:.2e}")
+        else:
+            g.learn()
+            assert g.metrics()["nonfinite"] == 0
+            say(f"  unroll {u}: head err {worst:.2e}")
+    g.close()
+
+
+@pytest.mark.parametrize("case", list(BF16_CASES))
+def test_bf16_matrix_core_path(gpu, orc, case):
+    cfg, seed, updates = BF16_CASES[case]
+    say(f"[bf16] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+    _forced_lockstep(gpu, orc, cfg, seed, updates)
+
+
+def test_bf16_reference_mode_is_exact(gpu, orc):
+    """The same bf16 net on the sequential fp32-chain reference path matches the oracle bit for bit."""
+    cfg, seed, _ = BF16_CASES["maze_bf16_128"]
+    g = gpu.Anakin(cfg, seed=seed); o = orc.Oracle(cfg, seed=seed)
+    g.set_mode(gpu.MODE_CANONICAL_ACTING | gpu.MODE_VALU_GEMM)
+    with pytest.raises(gpu.AnakinError):
+        g.set_mode(gpu.MODE_VALU_GEMM)
+    g.set_mode(gpu.MODE_CANONICAL_ACTING | gpu.MODE_VALU_GEMM)
+    PT.sync_oracle_from_gpu(g, o)
+    g.rollout(); o.rollout()
+    PT.assert_rollout_equal(g, o, "maze")
+    g.learn(); o.learn()
+    PT.assert_learn_close(g, o, TOL_BF16)
+    g.close()
+
+
+def test_full_size_maze_bf16_sampled_envs(gpu, orc):
+    """The maze workload at full size (B=16384, 768-512-512-512 bf16) in the benchmark's launch shape:
+    logit-forced replay of a seeded sample of envs, plus properties that hold at any size."""
+    cfg = W.get("maze_16384")
+    B = cfg["B"]
+    rng = np.random.default_rng(4)
+    sel = np.unique(np.concatenate([[0, 1, 63, 64, B - 1, B - 64, B // 2], rng.integers(0, B, 9)])).astype(np.int32)
+    say(f"[full size] maze_16384 envs={sel.tolist()}")
+    _forced_lockstep(gpu, orc, cfg, 0, 2, sel=sel, learn=False)
+
+
 def test_determinism_and_resume(gpu):
     """Same seed twice gives the same bytes; a byte copy of the workspace plus the two host counters
     resumes bit-exactly (explicit, device-resident state; counter-based RNG)."""
