@@ -25,6 +25,18 @@ PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3      # fp32 vector (packed) = fp32 matrix-core peak
 PEAK_BF16_TFLOPS = 2500.0
 
+# HBM bytes per launch (MB) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# copy-kernel calibration; source: profiles/catch_4096_hbm_traffic.md.  Reported as roofline.traffic
+# when the dominant kernel of the benchmarked workload is listed.
+MEASURED_TRAFFIC_MB = {
+    ("catch_4096", "rollout"): 173.3,
+    ("catch_4096", "gemm_nt_mask"): 341.7,
+    ("catch_4096", "gemm_tn"): 377.8,
+    ("catch_4096", "head_backward"): 180.0,
+    ("catch_4096", "first_layer_grad"): 101.0,
+    ("catch_4096", "adam_reduce"): 62.1,
+}
+
 
 def kernel_models(cfg, P):
     """Algorithmic work per launch of each kernel: (bound, amount, unit-peak, unit)."""
@@ -41,15 +53,20 @@ def kernel_models(cfg, P):
     bf16 = cfg["net"].get("dtype") == "bf16"
     mfma_peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     snap = {"catch": 4, "pendulum": 8, "maze": 2}[kind]
+    dense_act = sum(dims[i] * dims[i + 1] for i in range(1, len(dims) - 1))
     models = {
-        # acting: fp32 FMAs of the canonical forward, (T+1) evaluations per env
-        "rollout": ("alu", 2.0 * w_act * B * (T + 1) / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s"),
+        # acting: (T+1) forward passes per env; hidden-to-hidden layers run on the matrix cores, the one-hot
+        # first layer and the heads on vector ALUs -- all counted as 2 flop per weight actually touched
+        "rollout": ("mfma" if dense_act else "alu", 2.0 * w_act * B * (T + 1) / 1e12, mfma_peak if dense_act else PEAK_FP32_TFLOPS, "TFLOP/s"),
         # 17 B per (t,b): read r 4 + done 1 + V 4, write A 4 + G 4
         "returns_scan": ("hbm", 17.0 * M / 1e9, PEAK_HBM_GBS, "GB/s"),
         # 28 B per parameter: read theta,g,m,v, write theta,m,v
         "adam_reduce": ("hbm", 28.0 * P / 1e9, PEAK_HBM_GBS, "GB/s"),
         "head_grad": ("hbm", (NH * 4 + 1 + 8 + NH * 4) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "head_backward": ("hbm", (8.0 * dims[-1] + 4 * NH) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
+        # read h_L, write dZ_L (bf16: written in two layouts)
+        "head_backward": ("hbm", ((6.0 if bf16 else 8.0) * dims[-1] + 4 * NH) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
+        # scatter of dZ1 rows into the selected weight rows: one read of dZ1
+        "first_layer_grad": ("hbm", 4.0 * dims[1] * M / 1e9, PEAK_HBM_GBS, "GB/s"),
     }
     tn = sum(2.0 * dims[i] * dims[i + 1] * M for i in range(1, len(dims) - 1))
     nt = tn
@@ -86,12 +103,24 @@ def main():
     ap.add_argument("--workload", default="catch_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--valu-gemm", action="store_true", help="learn-phase GEMMs on vector ALUs")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run a plain device copy of this many MiB 20 times "
+                         "(calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
+    if args.copy_probe:
+        n = args.copy_probe * 1024 * 1024 // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_MiB": args.copy_probe, "copies": 20}))
+        return
     from paper_2104_06272_amd import binding, workloads as W
     cfg = W.get(args.workload)
     torch.cuda.set_device(0)
@@ -137,7 +166,8 @@ def main():
     dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
     d = per_kernel[dominant]
     roofline = {"kernel": dominant, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
-                "unit": d.get("unit"), "frac": d.get("frac"), "traffic": None,
+                "unit": d.get("unit"), "frac": d.get("frac"),
+                "traffic": MEASURED_TRAFFIC_MB.get((args.workload, dominant)), "traffic_unit": "MB per launch",
                 "avg_launch_us": d["avg_us"]}
     out = {
         "metric": "env steps/sec (rollout+learn) on 1 MI355X", "value": value, "unit": "env steps/s",
