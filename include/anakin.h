@@ -79,7 +79,8 @@ typedef struct anakin anakin_t;
 typedef struct {
     int32_t B, T, num_heads, head_stride, n_hidden;
     int32_t hidden[4];
-    int32_t act_is_bf16;              /* act[]: 0 fp32 [T*B][H]; 2 bf16 packed [T*B/8][H][8] (8 consecutive samples per feature) */
+    int32_t act_is_bf16;              /* act[]: 0 fp32 [T*B][H]; 2 bf16 packed [T*B/8][H][8] (8 consecutive samples per
+                                         feature); -1 not stored (one-layer nets: the update rebuilds the layer) */
     void* state_s0;  size_t off_state_s0;   /* uint32 [T+1][B] packed state word */
     void* state_f0;  size_t off_state_f0;   /* float  [T+1][B] (pendulum theta) */
     void* state_f1;  size_t off_state_f1;   /* float  [T+1][B] (pendulum theta_dot) */

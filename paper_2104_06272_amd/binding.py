@@ -272,7 +272,7 @@ class Anakin:
             "ret": grab(v.off_ret, T * B, torch.float32).reshape(T, B),
         }
         acts = []
-        for l in range(v.n_hidden):
+        for l in range(v.n_hidden if v.act_is_bf16 >= 0 else 0):
             H = v.hidden[l]
             if v.act_is_bf16:
                 a = self.ws[v.off_act[l]:v.off_act[l] + T * B * H * 2].view(torch.bfloat16).float()

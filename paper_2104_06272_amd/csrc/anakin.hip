@@ -119,6 +119,7 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     }
     splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256);
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
+    if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
     const bool bfp = rollout_bf16_ok(ns, B);
     const int hq = bfp ? 64 : 16;                       // row quantum of the head pass
@@ -259,7 +260,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     anakin* h = new (std::nothrow) anakin();
     if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
-    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0;
+    h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0; h->traj_no_acts = 0;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ed, ns, B, T, h->splits, &h->head_fan, &h->loss_blocks);
@@ -325,6 +326,7 @@ void fill_rollout_args(anakin* h, RolloutArgs& a)
     const Layout& L = h->lay;
     a.env = h->env; a.net = h->net; a.theta = at<const float>(h, L.theta);
     a.B = h->B; a.T = h->T; a.seed = h->seed; a.gstep = h->gstep;
+    a.keep_acts = one_layer_fused(h) ? 0 : 1;
     rollout_lds_bytes(h->net, h->env, h->TM, &a.ldx);
     TrajPtrs& t = a.tp;
     t.s0 = at<uint32_t>(h, L.s0); t.f0 = at<float>(h, L.f0); t.f1 = at<float>(h, L.f1); t.walls = at<const uint32_t>(h, L.walls);
@@ -410,6 +412,7 @@ extern "C" int32_t anakin_rollout(anakin_t* h)
     if (bf16_mfma(h)) HIPCHK(h, launch_rollout_bf16(h));
     else HIPCHK(h, launch_rollout(h));
     h->traj_packed = bf16_mfma(h) ? 1 : 0;
+    h->traj_no_acts = one_layer_fused(h) ? 1 : 0;
     h->gstep += (uint64_t)h->T;
     h->have_traj = 1;
     return ANAKIN_OK;
@@ -422,7 +425,9 @@ extern "C" int32_t anakin_learn(anakin_t* h)
     HIPCHK(h, launch_returns(h));
     HIPCHK(h, launch_head_grad(h));
     if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
+    if (h->traj_no_acts != (one_layer_fused(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     if (h->traj_packed) HIPCHK(h, launch_backward_bf16(h));
+    else if (h->traj_no_acts) HIPCHK(h, launch_learn_one_layer(h));
     else HIPCHK(h, launch_backward(h));
     HIPCHK(h, launch_adam(h));
     h->have_traj = 0;
@@ -555,7 +560,7 @@ extern "C" int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* v)
     memset(v, 0, sizeof *v);
     v->B = h->B; v->T = h->T; v->num_heads = h->net.NH; v->head_stride = h->net.NHP; v->n_hidden = h->net.L;
     for (int l = 0; l < h->net.L; ++l) v->hidden[l] = h->net.dims[l + 1];
-    v->act_is_bf16 = h->traj_packed ? 2 : 0;
+    v->act_is_bf16 = h->traj_packed ? 2 : (h->traj_no_acts ? -1 : 0);
 #define SETP(field, off) v->field = h->ws + (off); v->off_##field = (off)
     SETP(state_s0, L.tr_s0); SETP(state_f0, L.tr_f0); SETP(state_f1, L.tr_f1);
     SETP(action, L.tr_act); SETP(eps, L.tr_eps); SETP(action_f, L.tr_actf);

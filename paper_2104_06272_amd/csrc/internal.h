@@ -41,6 +41,7 @@ struct RolloutArgs {
     TrajPtrs tp;
     const float* theta;
     int B, T, ldx;
+    int keep_acts;               // store hidden activations for the update (0: the update rebuilds them)
     uint64_t seed, gstep;
 };
 
@@ -110,6 +111,7 @@ struct anakin {
     int head_fan;                 // first-stage workgroups per split of the head-gradient pass
     int bf16_path;                // the bf16 matrix-core kernels support this net
     int traj_packed;              // the stored unroll holds packed bf16 activations
+    int traj_no_acts;             // the stored unroll holds no hidden activations (one-layer nets)
     std::string err;
     // optional per-kernel timing with events on the launch stream
     int prof_on;
@@ -139,6 +141,9 @@ hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);
 hipError_t launch_adam(anakin* h);
 hipError_t launch_first_layer_grad(anakin* h);
+hipError_t launch_learn_one_layer(anakin* h);
+// single hidden layer on a one-hot or 3-feature observation: the update rebuilds the layer from the state
+inline bool one_layer_fused(const anakin* h) { return h->net.L == 1 && h->env.kind != ENV_MAZE && !h->net.bf16 && !(h->mode & ANAKIN_MODE_VALU_GEMM) && h->net.dims[1] <= 128 && (size_t)128 * h->net.dims[0] * 4 + (size_t)h->net.dims[0] * h->net.dims[1] * 4 <= 64 * 1024; }
 hipError_t launch_partial_reduce(const float* src, float* dst, int count, int fan, int splits, hipStream_t s);
 hipError_t launch_rollout_bf16(anakin* h);
 hipError_t launch_backward_bf16(anakin* h);

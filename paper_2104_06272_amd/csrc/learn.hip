@@ -343,6 +343,149 @@ hipError_t launch_first_layer_grad(anakin* h)
 }
 
 // ---------------------------------------------------------------------------
+// Whole backward pass of a one-hidden-layer net in one kernel.  Nothing of the
+// forward pass is read from HBM: the hidden layer h = relu(b1 + W1[ball] +
+// W1[paddle]) (or three fmas for the pendulum) is rebuilt from the 4-byte state
+// snapshot with W1 in LDS -- in the acting order, so the bits equal the acting
+// ones -- then dZ1 = relu'(h) (Wh dhead), the head-matrix gradient, and the
+// scatter of dZ1 into the two selected rows of dW1.  Per sample the kernel
+// reads the state word and the dhead row (20 B) and writes nothing; per chunk
+// it writes one partial of each parameter region.  Lane j owns hidden unit j.
+// ---------------------------------------------------------------------------
+struct OneLayerArgs {
+    int M, D, H, NH, NHP, rows;
+    const float* theta; int w1_off, b1_off, wh_off;
+    const float* dhead;
+    float* partial0;          // [splits][D*H + H]
+    float* partial1;          // [splits][H*NH + NH]
+    ObsLite obs;
+};
+
+// OLW threads per workgroup: small workgroups keep the LDS accumulators small, so more of them fit a CU
+constexpr int OLW = 128;
+// NH (number of head outputs) is a template parameter: the per-sample inner loops are the whole cost here
+template <int ENV, int NH>
+__global__ __launch_bounds__(OLW) void learn_one_layer(const OneLayerArgs a)
+{
+    extern __shared__ float lds[];
+    const int H = a.H, D = a.D;
+    constexpr int NHP = NH <= 4 ? 4 : 8;
+    const int cw = H < OLW ? H : OLW, groups = OLW / cw;
+    float* w1s = lds;                                         // [D][H]
+    float* accs = w1s + D * H;                                // [groups][D][cw]
+    const int g = threadIdx.x / cw, jl = threadIdx.x % cw;
+    const int j = blockIdx.y * OLW + jl;
+    for (int i = threadIdx.x; i < D * H; i += OLW) w1s[i] = a.theta[a.w1_off + i];
+    float* mine = accs + (size_t)g * D * cw + jl;
+    if (ENV == ENV_CATCH) for (int k = 0; k < D; ++k) mine[k * cw] = 0.0f;
+    float wh[NH], dwh[NH], dbh[NH];
+#pragma unroll
+    for (int k = 0; k < NH; ++k) { wh[k] = a.theta[a.wh_off + j * NH + k]; dwh[k] = 0.0f; dbh[k] = 0.0f; }
+    const float b1 = a.theta[a.b1_off + j];
+    float db1 = 0.0f, r0 = 0.0f, r1 = 0.0f, r2 = 0.0f;
+    __syncthreads();
+    const int m_begin = blockIdx.x * a.rows, m_end = m_begin + a.rows;
+    const float* w1c = w1s + j;
+    constexpr int RB = 8;
+    for (int mb = m_begin + g; mb < m_end; mb += RB * groups) {
+        float4 d0[RB], d1[RB];
+        uint32_t sw[RB];
+        float f0[RB], f1[RB];
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const int m = mb + u * groups;
+            const bool ok = m < m_end;
+            d0[u] = ok ? *reinterpret_cast<const float4*>(a.dhead + (size_t)m * NHP) : make_float4(0, 0, 0, 0);
+            d1[u] = (ok && NHP == 8) ? *reinterpret_cast<const float4*>(a.dhead + (size_t)m * NHP + 4) : make_float4(0, 0, 0, 0);
+            if (ENV == ENV_CATCH) sw[u] = ok ? a.obs.s0[m] : 0u;
+            else { f0[u] = ok ? a.obs.f0[m] : 0.0f; f1[u] = ok ? a.obs.f1[m] : 0.0f; }
+        }
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            if (mb + u * groups >= m_end) break;
+            const float d[8] = {d0[u].x, d0[u].y, d0[u].z, d0[u].w, d1[u].x, d1[u].y, d1[u].z, d1[u].w};
+            float hv, x0 = 0.0f, x1 = 0.0f, x2 = 0.0f;
+            int bc = 0, pc = 0;
+            if (ENV == ENV_CATCH) {
+                catch_obs_cells(a.obs.env, sw[u], bc, pc);
+                hv = (b1 + w1c[bc * H]) + w1c[pc * H];
+            } else {
+                float sn, cs;
+                det_sincos(f0[u], sn, cs);
+                x0 = cs; x1 = sn; x2 = f1[u];
+                hv = fmaf(x2, w1c[2 * H], fmaf(x1, w1c[H], fmaf(x0, w1c[0], b1)));
+            }
+            hv = hv > 0.0f ? hv : 0.0f;
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < NH; ++k) { s = fmaf(wh[k], d[k], s); dwh[k] = fmaf(hv, d[k], dwh[k]); dbh[k] += d[k]; }
+            const float dz = hv > 0.0f ? s : 0.0f;
+            db1 += dz;
+            if (ENV == ENV_CATCH) { mine[bc * cw] += dz; mine[pc * cw] += dz; }
+            else { r0 = fmaf(x0, dz, r0); r1 = fmaf(x1, dz, r1); r2 = fmaf(x2, dz, r2); }
+        }
+    }
+    if (ENV != ENV_CATCH) { mine[0] = r0; mine[cw] = r1; mine[2 * cw] = r2; }
+    // per-lane sums of the other regions go through LDS too, then everything is combined group by group
+    __shared__ float red[OLW * 10];                            // [10][OLW]: dwh[0..7], db1, (dbh of lane 0 handled below)
+#pragma unroll
+    for (int k = 0; k < NH; ++k) red[k * OLW + threadIdx.x] = dwh[k];
+    red[8 * OLW + threadIdx.x] = db1;
+    red[9 * OLW + threadIdx.x] = 0.0f;
+    __shared__ float bh_red[8 * 8];                           // [groups <= 8][8]
+    if (jl == 0 && blockIdx.y == 0) for (int k = 0; k < NH; ++k) bh_red[g * 8 + k] = dbh[k];
+    __syncthreads();
+    float* out0 = a.partial0 + (size_t)blockIdx.x * ((size_t)D * H + H);
+    float* out1 = a.partial1 + (size_t)blockIdx.x * ((size_t)H * NH + NH);
+    for (int i = threadIdx.x; i < D * cw; i += OLW) {
+        const int k = i / cw, c = i % cw;
+        float s = 0.0f;
+        for (int gg = 0; gg < groups; ++gg) s += accs[((size_t)gg * D + k) * cw + c];
+        out0[(size_t)k * H + blockIdx.y * OLW + c] = s;
+    }
+    if (threadIdx.x < cw) {
+        const int c = threadIdx.x, col = blockIdx.y * OLW + c;
+        float s = 0.0f;
+        for (int gg = 0; gg < groups; ++gg) s += red[8 * OLW + gg * cw + c];
+        out0[(size_t)D * H + col] = s;
+        for (int k = 0; k < NH; ++k) {
+            float t = 0.0f;
+            for (int gg = 0; gg < groups; ++gg) t += red[k * OLW + gg * cw + c];
+            out1[(size_t)col * NH + k] = t;
+        }
+    }
+    if (threadIdx.x < NH && blockIdx.y == 0) {
+        float t = 0.0f;
+        for (int gg = 0; gg < groups; ++gg) t += bh_red[gg * 8 + threadIdx.x];
+        out1[(size_t)H * NH + threadIdx.x] = t;
+    }
+}
+
+hipError_t launch_learn_one_layer(anakin* h)
+{
+    const Layout& L = h->lay;
+    const NetShape& n = h->net;
+    OneLayerArgs a;
+    a.M = h->B * h->T; a.D = n.dims[0]; a.H = n.dims[1]; a.NH = n.NH; a.NHP = n.NHP;
+    a.rows = a.M / h->splits[0];
+    a.theta = at<const float>(h, L.theta); a.w1_off = n.w_off[0]; a.b1_off = n.b_off[0]; a.wh_off = n.wh_off;
+    a.dhead = at<const float>(h, L.dhead);
+    a.partial0 = at<float>(h, L.part[0]); a.partial1 = at<float>(h, L.part[1]);
+    a.obs.env = h->env; a.obs.s0 = at<const uint32_t>(h, L.tr_s0);
+    a.obs.f0 = at<const float>(h, L.tr_f0); a.obs.f1 = at<const float>(h, L.tr_f1);
+    const size_t lds = ((size_t)a.D * a.H + (size_t)OLW * a.D) * sizeof(float);
+    const dim3 grid(h->splits[0], (a.H + OLW - 1) / OLW);
+    auto go = [&](auto kern) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        ProfScope prof(h, "learn_one_layer");
+        hipLaunchKernelGGL(kern, grid, dim3(OLW), lds, h->stream, a);
+        return hipGetLastError();
+    };
+    return h->env.kind == ENV_CATCH ? go(learn_one_layer<ENV_CATCH, 4>) : go(learn_one_layer<ENV_PENDULUM, 3>);
+}
+
+// ---------------------------------------------------------------------------
 // Adam with the gradient reduction fused in: g = sum over split-K partials in
 // ascending split order, then m, v, theta.  Streams theta, m, v once in and
 // once out (28 bytes per parameter besides the partials).  For bf16 networks

@@ -470,7 +470,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         }
         __syncthreads();
         // ---- forward -------------------------------------------------------
-        const bool keep = t < T;                 // the bootstrap evaluation keeps no activations
+        const bool keep = t < T && a.keep_acts;  // the bootstrap evaluation keeps no activations
         float* g0 = keep ? tp.act[0] + ((size_t)t * B + b0) * a.net.dims[1] : nullptr;
         run_first_layer<ENV, BF>(a, TM, obs, bufA, tid, g0, a.theta + a.net.w_off[0]);
         __syncthreads();
@@ -709,7 +709,7 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         }
         __syncthreads();
         PH(0);
-        const bool keep = t < T;
+        const bool keep = t < T && a.keep_acts;
         float* g0 = keep ? tp.act[0] + ((size_t)t * B + b0) * RK : nullptr;
         first_layer<ENV, TM * RK / 1024, false>(a, obs, bufA, ldx, tid, g0, w1);
         __syncthreads();
