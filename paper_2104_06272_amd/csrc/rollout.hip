@@ -487,11 +487,10 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
         if (t < T) {
-            for (int idx = WG - 1 - tid; idx < 2 * TM; idx += WG) {
-                const int e = idx % TM, which = idx / TM;
-                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, which == 0 ? DOM_ACTION : DOM_RESET);
-                rng[e * 4 + 2 * which] = w.x;
-                rng[e * 4 + 2 * which + 1] = w.y;
+            for (int e = WG - 1 - tid; e < TM; e += WG) {
+                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
+                rng[e * 4] = w.x;
+                rng[e * 4 + 1] = w.y;
             }
         }
         __syncthreads();
@@ -508,19 +507,29 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
             if (t < T) {
-                const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);   // action words 0,1; reset words 0,1
+                const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);   // action draw, words 0 and 1
                 float r; int done;
+                // the reset draw is only needed where an episode ends: the step runs with a placeholder
+                // and the few lanes that finished an episode draw and reset afterwards
                 if (ENV == ENV_PENDULUM) {
                     float eps, act;
                     sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
                     tp.tr_eps[tb] = eps;
                     tp.tr_actf[tb] = act;
-                    pendulum_step(a.env, st, act, dr.z, dr.w, r, done);
+                    pendulum_step(a.env, st, act, 0u, 0u, r, done);
+                    if (done) {
+                        const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                        pendulum_reset(st, wr.x, wr.y);
+                    }
                 } else {
                     const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
                     if (ENV == ENV_CATCH) {
-                        catch_step(a.env, st, act, dr.z, r, done);
+                        catch_step(a.env, st, act, 0u, r, done);
+                        if (done) {
+                            const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                            st.s0 = catch_reset(a.env, wr.x);
+                        }
                     } else {
                         const uint32_t* wl = obs + tid * OBS_WORDS;
                         maze_step(a.env, st, act, [wl](int c) { return ((wl[c >> 5] >> (c & 31)) & 1u) != 0u; }, r, done);
@@ -723,11 +732,10 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
         if (t < T) {
-            for (int idx = WG - 1 - tid; idx < 2 * TM; idx += WG) {
-                const int e = idx % TM, which = idx / TM;
-                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, which == 0 ? DOM_ACTION : DOM_RESET);
-                rng[e * 4 + 2 * which] = w.x;
-                rng[e * 4 + 2 * which + 1] = w.y;
+            for (int e = WG - 1 - tid; e < TM; e += WG) {
+                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
+                rng[e * 4] = w.x;
+                rng[e * 4 + 1] = w.y;
             }
         }
         __syncthreads();
@@ -744,19 +752,29 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
             if (t < T) {
-                const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);   // action words 0,1; reset words 0,1
+                const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);   // action draw, words 0 and 1
                 float r; int done;
+                // the reset draw is only needed where an episode ends: the step runs with a placeholder
+                // and the few lanes that finished an episode draw and reset afterwards
                 if (ENV == ENV_PENDULUM) {
                     float eps, act;
                     sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
                     tp.tr_eps[tb] = eps;
                     tp.tr_actf[tb] = act;
-                    pendulum_step(a.env, st, act, dr.z, dr.w, r, done);
+                    pendulum_step(a.env, st, act, 0u, 0u, r, done);
+                    if (done) {
+                        const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                        pendulum_reset(st, wr.x, wr.y);
+                    }
                 } else {
                     const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
                     if (ENV == ENV_CATCH) {
-                        catch_step(a.env, st, act, dr.z, r, done);
+                        catch_step(a.env, st, act, 0u, r, done);
+                        if (done) {
+                            const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                            st.s0 = catch_reset(a.env, wr.x);
+                        }
                     } else {
                         const uint32_t* wl = obs + tid * OBS_WORDS;
                         maze_step(a.env, st, act, [wl](int c) { return ((wl[c >> 5] >> (c & 31)) & 1u) != 0u; }, r, done);
@@ -836,7 +854,11 @@ int rollout_pick_tile(const NetShape& net, int B)
     for (int tm = 16; tm <= 256; tm *= 2) {
         if (tm < lo || tm > hi || B % tm) continue;
         if (!best) best = tm;                            // smallest valid tile
-        if (B / tm >= 256) best = tm;                    // largest tile that still fills the chip
+        if (B / tm >= 2048) best = tm;                   // largest tile that still leaves eight workgroups per CU
+    }
+    if (best && B / best < 256) {                        // small batches: fill the chip first
+        for (int tm = 16; tm <= 256; tm *= 2)
+            if (tm >= lo && tm <= hi && B % tm == 0 && B / tm >= 256) best = tm;
     }
     return best;
 }

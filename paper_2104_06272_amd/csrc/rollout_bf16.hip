@@ -292,11 +292,10 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
             }
         } else if (t < T) {
             // the other two wavefronts produce this step's random draws meanwhile
-            for (int idx = tid - 2 * 64; idx < 2 * BTM; idx += 2 * 64) {
-                const int e = idx % BTM, which = idx / BTM;
-                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, which == 0 ? DOM_ACTION : DOM_RESET);
-                rng[e * 4 + 2 * which] = w.x;
-                rng[e * 4 + 2 * which + 1] = w.y;
+            for (int e = tid - 2 * 64; e < BTM; e += 2 * 64) {
+                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
+                rng[e * 4] = w.x;
+                rng[e * 4 + 1] = w.y;
             }
         }
         __syncthreads();
@@ -312,18 +311,27 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
             if (t < T) {
-                const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);
+                const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);
                 float r; int done;
                 if (ENV == ENV_PENDULUM) {
                     float eps, act;
                     sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
                     tp.tr_eps[tb] = eps; tp.tr_actf[tb] = act;
-                    pendulum_step(a.env, st, act, dr.z, dr.w, r, done);
+                    pendulum_step(a.env, st, act, 0u, 0u, r, done);
+                    if (done) {
+                        const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                        pendulum_reset(st, wr.x, wr.y);
+                    }
                 } else {
                     const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
-                    if (ENV == ENV_CATCH) catch_step(a.env, st, act, dr.z, r, done);
-                    else {
+                    if (ENV == ENV_CATCH) {
+                        catch_step(a.env, st, act, 0u, r, done);
+                        if (done) {
+                            const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                            st.s0 = catch_reset(a.env, wr.x);
+                        }
+                    } else {
                         const uint32_t* wl = obs + tid * BOBS;
                         maze_step(a.env, st, act, [wl](int c) { return ((wl[c >> 5] >> (c & 31)) & 1u) != 0u; }, r, done);
                     }
