@@ -121,7 +121,7 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
-    const bool bfp = rollout_bf16_ok(ns, B);
+    const bool bfp = rollout_bf16_ok(ns, ed, B);
     const int hq = bfp ? 64 : 16;                       // row quantum of the head pass
     if (bfp) splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256, 64);
     int fan = 1;
@@ -272,7 +272,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->TM = rollout_pick_tile(ns, B);
     h->TM_mfma = rollout_pick_tile_mfma(ns, B);
     h->TM_res = rollout_resident_tile(ns, B);
-    h->bf16_path = rollout_bf16_ok(ns, B) ? 1 : 0;
+    h->bf16_path = rollout_bf16_ok(ns, ed, B) ? 1 : 0;
 
     auto fail = [&](int code) { g_create_error = h->err; delete h; return code; };
     // parameters and optimiser state

@@ -47,11 +47,23 @@ struct RolloutArgs {
 
 // position of parameter i in the copy that stores every weight matrix transposed
 // (layers [N][K], heads [NH][HL]); biases keep their place
+// Layout of the second bf16 copy of the parameters, the one the acting kernel feeds to
+// v_mfma_f32_32x32x16_bf16 as the B operand.  A weight matrix W[K][N] with K % 16 == 0 and
+// N % 32 == 0 is stored in operand tiles: for every block of 32 output columns and every
+// step of 16 inputs, the 64 lanes' 16-byte pieces are adjacent (lane = 32*((k%16)/8) + n%32
+// holds k%8 = 0..7), so one wavefront load is one contiguous KiB.  Other layer matrices are
+// stored transposed ([N][K]); the head matrix as [NH][HL].
+ANK_HD bool mfma_tiled(int K, int N) { return K % 16 == 0 && N % 32 == 0; }
+ANK_HD int tiled_offset(int K, int k, int n)
+{
+    return (((n >> 5) * (K >> 4) + (k >> 4)) << 9) + (((((k & 15) >> 3) << 5) + (n & 31)) << 3) + (k & 7);
+}
 ANK_HD int transposed_index(const NetShape& n, int i)
 {
     for (int l = 0; l < n.L; ++l) {
         const int K = n.dims[l], N = n.dims[l + 1], off = i - n.w_off[l];
-        if (off >= 0 && off < K * N) return n.w_off[l] + (off % N) * K + off / N;
+        if (off >= 0 && off < K * N)
+            return n.w_off[l] + (mfma_tiled(K, N) ? tiled_offset(K, off / N, off % N) : (off % N) * K + off / N);
     }
     const int off = i - n.wh_off, HL = n.dims[n.L];
     if (off >= 0 && off < HL * n.NH) return n.wh_off + (off % n.NH) * HL + off / n.NH;
@@ -148,7 +160,7 @@ hipError_t launch_partial_reduce(const float* src, float* dst, int count, int fa
 hipError_t launch_rollout_bf16(anakin* h);
 hipError_t launch_backward_bf16(anakin* h);
 hipError_t launch_refresh_bf16(anakin* h);
-bool rollout_bf16_ok(const NetShape& net, int B);
+bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B);
 // bf16 network running on the matrix-core path (packed bf16 activations) rather than the fp32 reference path
 inline bool bf16_mfma(const anakin* h) { return h->bf16_path && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_VALU_GEMM)); }
 int rollout_pick_tile(const NetShape& net, int B);

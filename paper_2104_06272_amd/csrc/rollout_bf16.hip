@@ -1,7 +1,7 @@
 // Acting for bf16 networks on the matrix cores (paper figure 2 top; section 2.1
-// loop).  Same persistent structure as the fp32 kernels: a workgroup owns 64
-// environments for the whole unroll, env state in registers, activations in
-// LDS (bf16), trajectory and hidden activations to HBM.
+// loop).  Same persistent structure as the fp32 kernels: a workgroup of eight
+// wavefronts owns 64 environments for the whole unroll, env state in registers,
+// activations in LDS (bf16), trajectory and hidden activations to HBM.
 //
 // Numerics (bf16 workload): weights and layer inputs are bfloat16, products are
 // exact in fp32, accumulation is fp32 inside v_mfma_f32_32x32x16_bf16, bias and
@@ -12,10 +12,16 @@
 // head outputs the kernel stores.
 //
 // The first layer is a gather-sum over the 0/1 observation in fp32.  For the
-// maze the wall plane never changes, so its contribution (bias + wall rows) is
-// computed once per launch, on the matrix cores, into a per-env prefix; each
-// step adds the agent row and the goal row.  Hidden activations are written
-// to HBM sample-packed (see learn_bf16.hip).
+// maze the wall plane and the goal never change, so their contribution (bias +
+// wall rows + goal row) is computed once per launch, on the matrix cores, and
+// then lives in registers for the whole unroll; each step adds the agent row.
+// Hidden activations go to HBM sample-packed (see learn_bf16.hip) straight
+// from registers: the accumulator layout of the MFMA holds four consecutive
+// samples of one column, half of a packed group.
+//
+// Weights of the hidden layers are read from L2 in operand tiles (one KiB per
+// wavefront load, see internal.h), prefetched four 16-input steps ahead into a
+// double register buffer; two wavefronts per SIMD cover the rest of the latency.
 //
 // Operand layout of v_mfma_f32_32x32x16_bf16 (verified on gfx950): lane l feeds
 // A[row l%32][k 8*(l/32) .. +7] and B[k 8*(l/32) .. +7][col l%32]; accumulator
@@ -28,9 +34,22 @@ typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int BTM = 64;                 // envs per workgroup
+constexpr int BWG = 512;                // threads per workgroup: two wavefronts per SIMD
 constexpr int BOBS = 12;                // observation words per env (as in the fp32 kernels)
 
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32v2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32v4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ float bf2f(uint16_t h) { return bf16_to_f(h); }
+// two floats rounded to bfloat16 (round to nearest even), low half first
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    bf2 v;
+    v[0] = (__bf16)lo; v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float relu(float x) { return x > 0.0f ? x : 0.0f; }
 
 struct RolloutBf16Args {
     EnvDims env;
@@ -38,20 +57,23 @@ struct RolloutBf16Args {
     TrajPtrs tp;                         // tp.act[] point to bf16 buffers here
     const float* theta;                  // fp32 master (biases are read from here)
     const uint16_t* w;                   // bf16 copy of theta, same indexing
-    const uint16_t* wt;                  // bf16 copy with every weight matrix transposed ([N][K])
-    float* prefix;                       // [B][H1] first-layer prefix (bias + wall rows)
+    const uint16_t* wt;                  // bf16 copy in matrix-core operand tiles (heads: [NH][HL])
+    float* prefix;                       // [B][H1] first-layer prefix (bias + wall rows + goal row), maze only
     int B, T, ldx;                       // ldx: LDS row stride in bf16 elements
     uint64_t seed, gstep;
 };
 
-// hidden layer on the matrix cores: Y[64][N] = relu(X[64][K] W + b), X and Y bf16 in LDS
+// Hidden layer on the matrix cores: Y[64][N] = relu(X[64][K] W + b), X and Y bf16 in LDS.
+// Wavefront w computes columns [32*NT*w, 32*NT*(w+1)); wavefronts past N stay idle.
+// gP: sample-packed copy of Y in HBM (null: not kept), g8: first sample group of this tile.
 template <int NT>
 __device__ __forceinline__ void bf16_layer(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int ldx,
                                            const uint16_t* __restrict__ Wt, const float* __restrict__ bias,
-                                           int K, int N, int tid)
+                                           int K, int N, int wave, int lane, uint16_t* __restrict__ gP, size_t g8)
 {
-    const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
-    const int n0 = wave * (N >> 2);
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int n0 = wave * 32 * NT;
+    if (n0 >= N) return;
     f16v acc[2][NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -60,85 +82,81 @@ __device__ __forceinline__ void bf16_layer(const uint16_t* __restrict__ X, uint1
         for (int r = 0; r < 16; ++r) { acc[0][t][r] = b; acc[1][t][r] = b; }
     }
     const uint16_t* xa = X + l32 * ldx + 8 * kg;
-    const uint16_t* wb = Wt + (size_t)(n0 + l32) * K + 8 * kg;
-    constexpr int U = 2;                                        // k-steps per prefetch block
-    bf8 bc[U][NT], bn[U][NT];
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) bc[u][t] = *reinterpret_cast<const bf8*>(wb + (size_t)(32 * t) * K + 16 * u);
-    for (int k0 = 0; k0 < K; k0 += 16 * U) {
-        if (k0 + 16 * U < K) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    bn[u][t] = *reinterpret_cast<const bf8*>(wb + (size_t)(32 * t) * K + k0 + 16 * U + 16 * u);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bf8 a0 = *reinterpret_cast<const bf8*>(xa + k0 + 16 * u);
-            const bf8 a1 = *reinterpret_cast<const bf8*>(xa + 32 * ldx + k0 + 16 * u);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bc[u][t], acc[0][t], 0, 0, 0);
-                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bc[u][t], acc[1][t], 0, 0, 0);
-            }
-        }
+    const int KS = K >> 4;                                       // 16-input steps: 8, 16 or 32
+    const uint16_t* wb = Wt + ((size_t)(n0 >> 5) * KS << 9) + lane * 8;
+    constexpr int U = 4;                                         // steps per prefetch block
+    bf8 w0[U][NT], w1[U][NT];
+    auto load = [&](bf8 (&d)[U][NT], int s) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) bc[u][t] = bn[u][t];
+            for (int t = 0; t < NT; ++t) d[u][t] = *reinterpret_cast<const bf8*>(wb + ((size_t)(t * KS + s + u) << 9));
+    };
+    auto compute = [&](const bf8 (&d)[U][NT], int s) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bf8 a0 = *reinterpret_cast<const bf8*>(xa + 16 * (s + u));
+            const bf8 a1 = *reinterpret_cast<const bf8*>(xa + 32 * ldx + 16 * (s + u));
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, d[u][t], acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, d[u][t], acc[1][t], 0, 0, 0);
+            }
+        }
+    };
+    // the scheduling barriers keep every block of loads ahead of the MFMAs of the block before it
+    load(w0, 0);
+    for (int s = 0; s < KS; s += 2 * U) {
+        load(w1, s + U);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(w0, s);
+        if (s + 2 * U < KS) load(w0, s + 2 * U);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(w1, s + U);
     }
+    // register group r/4 of lane (l32, kg) holds rows 8*(r/4) + 4*kg + 0..3 of column l32
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int t = 0; t < NT; ++t) {
+            const int col = n0 + 32 * t + l32;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
-                const float v = acc[mt][t][r] > 0.0f ? acc[mt][t][r] : 0.0f;
-                Y[row * ldx + n0 + 32 * t + l32] = bf16_bits(v);
+            for (int g = 0; g < 4; ++g) {
+                const int row = mt * 32 + 8 * g + 4 * kg;
+                const uint32_t p01 = pack_bf16x2(relu(acc[mt][t][4 * g]), relu(acc[mt][t][4 * g + 1]));
+                const uint32_t p23 = pack_bf16x2(relu(acc[mt][t][4 * g + 2]), relu(acc[mt][t][4 * g + 3]));
+                Y[(row + 0) * ldx + col] = (uint16_t)p01; Y[(row + 1) * ldx + col] = (uint16_t)(p01 >> 16);
+                Y[(row + 2) * ldx + col] = (uint16_t)p23; Y[(row + 3) * ldx + col] = (uint16_t)(p23 >> 16);
+                if (gP) {
+                    // written once, read by the update: streaming stores leave the weights in L2
+                    u32v2 pv; pv[0] = p01; pv[1] = p23;
+                    __builtin_nontemporal_store(pv, reinterpret_cast<u32v2*>(gP + ((g8 + mt * 4 + g) * N + col) * 8 + 4 * kg));
+                }
             }
+        }
 }
 
 __device__ __forceinline__ void run_bf16_layer(const uint16_t* X, uint16_t* Y, int ldx, const uint16_t* Wt, const float* bias,
-                                               int K, int N, int tid)
+                                               int K, int N, int wave, int lane, uint16_t* gP, size_t g8)
 {
-    switch (N >> 7) {                                           // tiles per wavefront: N / 4 / 32
-        case 1: bf16_layer<1>(X, Y, ldx, Wt, bias, K, N, tid); break;
-        case 2: bf16_layer<2>(X, Y, ldx, Wt, bias, K, N, tid); break;
-        default: bf16_layer<4>(X, Y, ldx, Wt, bias, K, N, tid); break;
-    }
+    if (N >= 512) bf16_layer<2>(X, Y, ldx, Wt, bias, K, N, wave, lane, gP, g8);
+    else bf16_layer<1>(X, Y, ldx, Wt, bias, K, N, wave, lane, gP, g8);
 }
 
-// copy of a [64][N] bf16 tile from LDS to the sample-packed activation buffer P8[M/8][N][8]
-// (eight consecutive samples of one feature adjacent): piece (group g, column c) gathers a
-// column of eight rows from LDS and is stored with one 16-byte write, coalesced across c.
-// g: first group of this tile in the buffer.
-__device__ __forceinline__ void store_tile_packed(const uint16_t* __restrict__ Y, int ldx, uint16_t* __restrict__ gP,
-                                                  size_t g, int N, int tid)
-{
-    for (int p = tid; p < 8 * N; p += WG) {
-        const int gi = p / N, c = p - gi * N;
-        const uint16_t* y = Y + (gi * 8) * ldx + c;
-        uint32_t w[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) w[q] = (uint32_t)y[(2 * q) * ldx] | ((uint32_t)y[(2 * q + 1) * ldx] << 16);
-        *reinterpret_cast<uint4*>(gP + ((g + gi) * N + c) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-}
-
-template <int ENV>
-__global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args a)
+// H1: width of the first hidden layer (128, 256 or 512).  Thread (pair of columns cp, env slice eq)
+// owns columns 2*cp, 2*cp+1 of the first layer for EPT = H1/16 consecutive environments.
+template <int ENV, int H1>
+__global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args a)
 {
     extern __shared__ uint4 smem4[];
     uint16_t* bufA = reinterpret_cast<uint16_t*>(smem4);
     const int ldx = a.ldx, NH = a.net.NH, NHP = a.net.NHP, L = a.net.L, HL = a.net.dims[a.net.L];
-    const int H1 = a.net.dims[1], D = a.net.dims[0];
+    const int D = a.net.dims[0];
+    const int ldh = HL + 8;
     uint16_t* bufB = bufA + BTM * ldx;
-    float* heads = reinterpret_cast<float*>(bufB + BTM * ldx);   // [64][NHP]
-    uint32_t* obs = reinterpret_cast<uint32_t*>(heads + BTM * NHP);
+    uint16_t* whs = bufB + BTM * ldx;                            // [8][HL + 8] head weights, rows >= NH zero
+    float* hp = reinterpret_cast<float*>(whs + 8 * ldh);         // [4][64][8] partial head sums per quarter of HL
+    uint32_t* obs = reinterpret_cast<uint32_t*>(hp + 4 * BTM * 8);
     uint32_t* rng = obs + BTM * BOBS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -146,68 +164,98 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
     const int B = a.B, T = a.T;
     const TrajPtrs& tp = a.tp;
     const uint16_t* w1 = a.w + a.net.w_off[0];
+    constexpr int EPT = H1 / 16;
+    const int cp = tid % (H1 / 2), eq = tid / (H1 / 2);
+    const int c = 2 * cp, e0 = eq * EPT;
 
     EnvState st{0u, 0.0f, 0.0f};
     const bool owner = tid < BTM;
     const int b = b0 + tid;
+    float hb[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) hb[j] = j < NH ? a.theta[a.net.bh_off + j] : 0.0f;
     if (owner) {
         st.s0 = tp.s0[b];
         if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
         if (ENV == ENV_MAZE) for (int w = 0; w < 8; ++w) obs[tid * BOBS + w] = tp.walls[(size_t)w * B + b];
     }
+    for (int i = tid; i < 8 * ldh; i += BWG) {
+        const int k = i / ldh, j = i - k * ldh;
+        whs[i] = (k < NH && j < HL) ? a.wt[a.net.wh_off + (size_t)k * HL + j] : (uint16_t)0;
+    }
     __syncthreads();
-    // first-layer prefix per env: the bias, plus -- for the maze -- the contribution of the wall
-    // plane, which never changes: prefix[64][H1] = b1 + Walls[64][cells] W1[cells][H1] on the matrix cores
+    // first-layer constants of this thread: the bias, plus -- for the maze -- the contribution of the wall
+    // plane and of the goal cell, which never change: prefix[64][H1] = b1 + Walls[64][cells] W1[cells][H1]
+    // on the matrix cores, handed over through HBM once per launch
+    float pre[ENV == ENV_MAZE ? EPT : 1][2];
+    const float bias0 = a.theta[a.net.b_off[0] + c], bias1 = a.theta[a.net.b_off[0] + c + 1];
     if (ENV == ENV_MAZE) {
         const int n = a.env.rows * a.env.cols;
         const int l32 = lane & 31, kg = lane >> 5;
-        const int n0 = wave * (H1 >> 2);
-        const int NT1 = H1 >> 7;                                 // 32-column tiles per wavefront (1, 2 or 4)
-        f16v acc[2][4];
+        constexpr int NT1 = H1 >= 512 ? 2 : 1;
+        const int n0 = wave * 32 * NT1;
+        if (n0 < H1) {
+            f16v acc[2][NT1];
 #pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) {
-            const float bb = t4 < NT1 ? a.theta[a.net.b_off[0] + n0 + 32 * t4 + l32] : 0.0f;
+            for (int t4 = 0; t4 < NT1; ++t4) {
+                const float bb = a.theta[a.net.b_off[0] + n0 + 32 * t4 + l32];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { acc[0][t4][r] = bb; acc[1][t4][r] = bb; }
-        }
-        const uint16_t* wb = a.wt + a.net.w_off[0] + (size_t)(n0 + l32) * D + 8 * kg;     // W1^T: [H1][D]
-        for (int k0 = 0; k0 < n; k0 += 16) {
-            bf8 av[2];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                const int cell = k0 + 8 * kg;
-                const uint32_t bits = (obs[(mt * 32 + l32) * BOBS + (cell >> 5)] >> (cell & 31)) & 0xffu;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) av[mt][q] = ((bits >> q) & 1u) ? (__bf16)1.0f : (__bf16)0.0f;
+                for (int r = 0; r < 16; ++r) { acc[0][t4][r] = bb; acc[1][t4][r] = bb; }
             }
+            const int KS = D >> 4;
+            const uint16_t* wb = a.wt + a.net.w_off[0] + ((size_t)(n0 >> 5) * KS << 9) + lane * 8;   // operand tiles of W1
+            for (int k0 = 0; k0 < n; k0 += 16) {
+                bf8 av[2];
 #pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) {
-                if (t4 < NT1) {
-                    const bf8 bv = *reinterpret_cast<const bf8*>(wb + (size_t)(32 * t4) * D + k0);
+                for (int mt = 0; mt < 2; ++mt) {
+                    const int cell = k0 + 8 * kg;
+                    const uint32_t bits = (obs[(mt * 32 + l32) * BOBS + (cell >> 5)] >> (cell & 31)) & 0xffu;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) av[mt][q] = ((bits >> q) & 1u) ? (__bf16)1.0f : (__bf16)0.0f;
+                }
+#pragma unroll
+                for (int t4 = 0; t4 < NT1; ++t4) {
+                    const bf8 bv = *reinterpret_cast<const bf8*>(wb + ((size_t)(t4 * KS + (k0 >> 4)) << 9));
                     acc[0][t4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0], bv, acc[0][t4], 0, 0, 0);
                     acc[1][t4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[1], bv, acc[1][t4], 0, 0, 0);
                 }
             }
-        }
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4)
-                if (t4 < NT1) {
+                for (int t4 = 0; t4 < NT1; ++t4)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int row = mt * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
                         a.prefix[(size_t)(b0 + row) * H1 + n0 + 32 * t4 + l32] = acc[mt][t4][r];
                     }
-                }
-    } else {
-        for (int c = tid; c < H1; c += WG) {
-            const float bb = a.theta[a.net.b_off[0] + c];
-            for (int m = 0; m < BTM; ++m) a.prefix[(size_t)(b0 + m) * H1 + c] = bb;
+        }
+        __syncthreads();
+        const uint32_t goal = *reinterpret_cast<const uint32_t*>(w1 + (size_t)(3 * n - 1) * H1 + c);
+        const float g0 = bf2f((uint16_t)(goal & 0xffffu)), g1 = bf2f((uint16_t)(goal >> 16));
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            const float2 p = *reinterpret_cast<const float2*>(a.prefix + (size_t)(b0 + e0 + m) * H1 + c);
+            pre[ENV == ENV_MAZE ? m : 0][0] = p.x + g0;
+            pre[ENV == ENV_MAZE ? m : 0][1] = p.y + g1;
         }
     }
-    __syncthreads();
+    float wp[3][2] = {{0, 0}, {0, 0}, {0, 0}};                   // pendulum: the three rows of W1
+    if (ENV == ENV_PENDULUM) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const uint32_t ww = *reinterpret_cast<const uint32_t*>(w1 + (size_t)k * H1 + c);
+            wp[k][0] = bf2f((uint16_t)(ww & 0xffffu)); wp[k][1] = bf2f((uint16_t)(ww >> 16));
+        }
+    }
 
+#ifdef ANK_PHASE_TIMING
+    long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, c0, c1;
+#define PH(i) do { c1 = clock64(); ph[i] += c1 - c0; c0 = c1; } while (0)
+    c0 = clock64();
+#else
+#define PH(i) do { } while (0)
+#endif
     for (int t = 0; t <= T; ++t) {
         const size_t tb = (size_t)t * B + b;
         if (owner) {
@@ -228,58 +276,98 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
             }
         }
         __syncthreads();
+        PH(0);
         const bool keep = t < T;
+        const size_t g8 = ((size_t)t * B + b0) >> 3;             // first sample group of this tile
+        // the last wavefront draws this step's random numbers while it waits for its weight rows
+        if (wave == 7 && keep) {
+            const u32x4 w = philox(a.seed, (uint32_t)(b0 + lane), a.gstep + (uint64_t)t, DOM_ACTION);
+            rng[lane * 2] = w.x;
+            rng[lane * 2 + 1] = w.y;
+        }
         // ---- first layer: fp32 gather-sum / three fmas, rounded to bf16 ----------
-        for (int c = 2 * tid; c < H1; c += 2 * WG) {
-#pragma unroll 8
-            for (int m = 0; m < BTM; ++m) {
-                const float2 p = *reinterpret_cast<const float2*>(a.prefix + (size_t)(b0 + m) * H1 + c);
-                float vx = p.x, vy = p.y;
-                if (ENV == ENV_PENDULUM) {
+        {
+            const int n = a.env.rows * a.env.cols;
+            uint32_t r0[ENV == ENV_PENDULUM ? 1 : EPT], r1[ENV == ENV_CATCH ? EPT : 1];
+            if (ENV != ENV_PENDULUM) {
+                // all weight-row loads of this thread in flight before the first is used
 #pragma unroll
-                    for (int k = 0; k < 3; ++k) {
-                        const float x = f_from_bits(obs[m * BOBS + k]);
-                        const uint32_t ww = *reinterpret_cast<const uint32_t*>(w1 + (size_t)k * H1 + c);
-                        vx = fmaf(x, bf2f((uint16_t)(ww & 0xffffu)), vx); vy = fmaf(x, bf2f((uint16_t)(ww >> 16)), vy);
-                    }
-                } else {
-                    const int n = a.env.rows * a.env.cols;
-                    const int r0 = ENV == ENV_CATCH ? (int)obs[m * BOBS + 0] : n + (int)obs[m * BOBS + 8];
-                    const int r1 = ENV == ENV_CATCH ? (int)obs[m * BOBS + 1] : 3 * n - 1;
-                    const uint32_t w0 = *reinterpret_cast<const uint32_t*>(w1 + (size_t)r0 * H1 + c);
-                    const uint32_t w1v = *reinterpret_cast<const uint32_t*>(w1 + (size_t)r1 * H1 + c);
-                    vx += bf2f((uint16_t)(w0 & 0xffffu)); vy += bf2f((uint16_t)(w0 >> 16));
-                    vx += bf2f((uint16_t)(w1v & 0xffffu)); vy += bf2f((uint16_t)(w1v >> 16));
+                for (int m = 0; m < EPT; ++m) {
+                    const int row0 = ENV == ENV_CATCH ? (int)obs[(e0 + m) * BOBS + 0] : n + (int)obs[(e0 + m) * BOBS + 8];
+                    r0[ENV == ENV_PENDULUM ? 0 : m] = *reinterpret_cast<const uint32_t*>(w1 + (size_t)row0 * H1 + c);
+                    if (ENV == ENV_CATCH)
+                        r1[ENV == ENV_CATCH ? m : 0] = *reinterpret_cast<const uint32_t*>(w1 + (size_t)obs[(e0 + m) * BOBS + 1] * H1 + c);
                 }
-                vx = vx > 0.0f ? vx : 0.0f; vy = vy > 0.0f ? vy : 0.0f;
-                *reinterpret_cast<uint32_t*>(bufA + m * ldx + c) = (uint32_t)bf16_bits(vx) | ((uint32_t)bf16_bits(vy) << 16);
+            }
+            uint16_t* actP = keep ? reinterpret_cast<uint16_t*>(tp.act[0]) : nullptr;
+#pragma unroll
+            for (int m0 = 0; m0 < EPT; m0 += 8) {
+                float v[8][2];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int m = m0 + q;
+                    float vx = ENV == ENV_MAZE ? pre[ENV == ENV_MAZE ? m : 0][0] : bias0;
+                    float vy = ENV == ENV_MAZE ? pre[ENV == ENV_MAZE ? m : 0][1] : bias1;
+                    if (ENV == ENV_PENDULUM) {
+#pragma unroll
+                        for (int k = 0; k < 3; ++k) {
+                            const float x = f_from_bits(obs[(e0 + m) * BOBS + k]);
+                            vx = fmaf(x, wp[k][0], vx); vy = fmaf(x, wp[k][1], vy);
+                        }
+                    } else {
+                        const uint32_t g = r0[ENV == ENV_PENDULUM ? 0 : m];
+                        vx += bf2f((uint16_t)(g & 0xffffu)); vy += bf2f((uint16_t)(g >> 16));
+                        if (ENV == ENV_CATCH) {
+                            const uint32_t g1 = r1[ENV == ENV_CATCH ? m : 0];
+                            vx += bf2f((uint16_t)(g1 & 0xffffu)); vy += bf2f((uint16_t)(g1 >> 16));
+                        }
+                    }
+                    v[q][0] = relu(vx); v[q][1] = relu(vy);
+                }
+                uint32_t px[4], py[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    px[q] = pack_bf16x2(v[2 * q][0], v[2 * q + 1][0]);
+                    py[q] = pack_bf16x2(v[2 * q][1], v[2 * q + 1][1]);
+                    // rows m0+2q and m0+2q+1 of the LDS tile, both columns as one 4-byte store
+                    *reinterpret_cast<uint32_t*>(bufA + (e0 + m0 + 2 * q) * ldx + c) = (px[q] & 0xffffu) | (py[q] << 16);
+                    *reinterpret_cast<uint32_t*>(bufA + (e0 + m0 + 2 * q + 1) * ldx + c) = (px[q] >> 16) | (py[q] & 0xffff0000u);
+                }
+                if (actP) {
+                    u32v4* dst = reinterpret_cast<u32v4*>(actP + ((g8 + ((e0 + m0) >> 3)) * H1 + c) * 8);
+                    u32v4 vx4, vy4;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) { vx4[q] = px[q]; vy4[q] = py[q]; }
+                    __builtin_nontemporal_store(vx4, dst);
+                    __builtin_nontemporal_store(vy4, dst + 1);
+                }
             }
         }
         __syncthreads();
-        const size_t g8 = ((size_t)t * B + b0) >> 3;             // first sample group of this tile
-        if (keep) store_tile_packed(bufA, ldx, reinterpret_cast<uint16_t*>(tp.act[0]), g8, H1, tid);
+        PH(1);
         uint16_t* cur = bufA;
         uint16_t* nxt = bufB;
         for (int l = 1; l < L; ++l) {
             const int K = a.net.dims[l], N = a.net.dims[l + 1];
-            run_bf16_layer(cur, nxt, ldx, a.wt + a.net.w_off[l], a.theta + a.net.b_off[l], K, N, tid);
+            run_bf16_layer(cur, nxt, ldx, a.wt + a.net.w_off[l], a.theta + a.net.b_off[l], K, N, wave, lane,
+                           keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8);
             __syncthreads();
-            if (keep) store_tile_packed(nxt, ldx, reinterpret_cast<uint16_t*>(tp.act[l]), g8, N, tid);
             uint16_t* tmp = cur; cur = nxt; nxt = tmp;
         }
-        // ---- heads: two wavefronts, one 32-env tile each, columns >= NH are zero ----
-        if (wave < 2) {
+        PH(3);
+        // ---- heads: wavefront (tile, quarter) sums one quarter of the last layer for 32 envs ----
+        {
             const int l32 = lane & 31, kg = lane >> 5;
-            const bool real = l32 < NH;
-            const float bv = real ? a.theta[a.net.bh_off + l32] : 0.0f;
+            const int tile = wave & 1, kq = wave >> 1, kq_len = HL >> 2;
             f16v acc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = bv;
-            const uint16_t* xa = cur + (wave * 32 + l32) * ldx + 8 * kg;
-            const uint16_t* wb = a.wt + a.net.wh_off + (size_t)(real ? l32 : 0) * HL + 8 * kg;   // heads stored [NH][HL]
-            for (int k0 = 0; k0 < HL; k0 += 16) {
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            const uint16_t* xa = cur + (tile * 32 + l32) * ldx + kq * kq_len + 8 * kg;
+            const uint16_t* wbs = whs + (l32 & 7) * ldh + kq * kq_len + 8 * kg;
+            const bool real = l32 < 8;
+            for (int k0 = 0; k0 < kq_len; k0 += 16) {
                 const bf8 av = *reinterpret_cast<const bf8*>(xa + k0);
-                bf8 bvv = *reinterpret_cast<const bf8*>(wb + k0);
+                bf8 bvv = *reinterpret_cast<const bf8*>(wbs + k0);
                 if (!real) {
 #pragma unroll
                     for (int q = 0; q < 8; ++q) bvv[q] = (__bf16)0.0f;
@@ -288,21 +376,21 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
             }
             if (real) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) heads[(wave * 32 + 8 * (r >> 2) + 4 * kg + (r & 3)) * NHP + l32] = acc[r];
-            }
-        } else if (t < T) {
-            // the other two wavefronts produce this step's random draws meanwhile
-            for (int e = tid - 2 * 64; e < BTM; e += 2 * 64) {
-                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
-                rng[e * 4] = w.x;
-                rng[e * 4 + 1] = w.y;
+                for (int r = 0; r < 16; ++r) hp[(kq * BTM + tile * 32 + 8 * (r >> 2) + 4 * kg + (r & 3)) * 8 + l32] = acc[r];
             }
         }
         __syncthreads();
+        PH(4);
         if (owner) {
             float hv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int j = 0; j < 8; ++j) if (j < NH) hv[j] = heads[tid * NHP + j];
+            for (int j = 0; j < 8; ++j)
+                if (j < NH) {
+                    float s = hb[j];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) s += hp[(q * BTM + tid) * 8 + j];
+                    hv[j] = s;
+                }
             float* hd = tp.tr_head + tb * NHP;
             *reinterpret_cast<float4*>(hd) = make_float4(hv[0], hv[1], hv[2], hv[3]);
             if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = make_float4(hv[4], hv[5], hv[6], hv[7]);
@@ -311,7 +399,7 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
             if (t < T) {
-                const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);
+                const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 2);
                 float r; int done;
                 if (ENV == ENV_PENDULUM) {
                     float eps, act;
@@ -340,7 +428,14 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
                 tp.tr_done[tb] = (uint8_t)done;
             }
         }
+        PH(5);
     }
+#ifdef ANK_PHASE_TIMING
+    if (tid == 0 && (blockIdx.x == 0 || blockIdx.x == 100))
+        printf("block %d phases (cycles/step): observe %lld first %lld layers %lld heads %lld sample %lld\n", (int)blockIdx.x,
+               ph[0] / (T + 1), ph[1] / (T + 1), ph[3] / (T + 1), ph[4] / (T + 1), ph[5] / (T + 1));
+#endif
+#undef PH
     if (owner) {
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
@@ -348,11 +443,14 @@ __global__ __launch_bounds__(WG) void rollout_bf16_kernel(const RolloutBf16Args 
 }
 
 // can this net act on the bf16 matrix-core path?
-bool rollout_bf16_ok(const NetShape& net, int B)
+bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B)
 {
     if (!net.bf16 || B % BTM) return false;
-    for (int l = 1; l <= net.L; ++l) if (net.dims[l] > 512 || net.dims[l] < 128) return false;   // 1..4 tiles of 32 columns per wavefront
-    if (net.dims[net.L] % 16) return false;
+    if (env.kind == ENV_MAZE && (env.rows * env.cols) % 16) return false;   // wall plane in whole 16-cell steps
+    for (int l = 1; l <= net.L; ++l) {
+        const int n = net.dims[l];
+        if (n != 128 && n != 256 && n != 512) return false;     // 1, 2 or 4 tiles of 32 columns per wavefront, 64-input prefetch blocks
+    }
     return true;
 }
 
@@ -370,19 +468,23 @@ hipError_t launch_rollout_bf16(anakin* h)
     int hmax = 0;
     for (int l = 1; l <= h->net.L; ++l) hmax = h->net.dims[l] > hmax ? h->net.dims[l] : hmax;
     a.ldx = hmax + 8;
-    const size_t lds = (size_t)2 * BTM * a.ldx * 2 + (size_t)BTM * h->net.NHP * 4 + (size_t)BTM * (BOBS + 4) * 4;
+    const int HL = h->net.dims[h->net.L], H1 = h->net.dims[1];
+    const size_t lds = (size_t)2 * BTM * a.ldx * 2 + (size_t)8 * (HL + 8) * 2 + (size_t)4 * BTM * 8 * 4 + (size_t)BTM * (BOBS + 2) * 4;
     auto launch = [&](auto kern) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         ProfScope prof(h, "rollout");
-        hipLaunchKernelGGL(kern, dim3(h->B / BTM), dim3(WG), lds, h->stream, a);
+        hipLaunchKernelGGL(kern, dim3(h->B / BTM), dim3(BWG), lds, h->stream, a);
         return hipGetLastError();
     };
+#define ANK_BF16_CASE(ENVK) \
+    (H1 == 128 ? launch(rollout_bf16_kernel<ENVK, 128>) : H1 == 256 ? launch(rollout_bf16_kernel<ENVK, 256>) : launch(rollout_bf16_kernel<ENVK, 512>))
     switch (h->env.kind) {
-        case ENV_CATCH:    return launch(rollout_bf16_kernel<ENV_CATCH>);
-        case ENV_PENDULUM: return launch(rollout_bf16_kernel<ENV_PENDULUM>);
-        default:           return launch(rollout_bf16_kernel<ENV_MAZE>);
+        case ENV_CATCH:    return ANK_BF16_CASE(ENV_CATCH);
+        case ENV_PENDULUM: return ANK_BF16_CASE(ENV_PENDULUM);
+        default:           return ANK_BF16_CASE(ENV_MAZE);
     }
+#undef ANK_BF16_CASE
 }
 
 }  // namespace ank
