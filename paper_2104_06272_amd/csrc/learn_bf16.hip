@@ -27,7 +27,16 @@ __device__ __forceinline__ f16v mfma_bf16(bf8 a, bf8 b, f16v c) { return __built
 __device__ __forceinline__ float bfu(uint16_t h) { return bf16_to_f(h); }
 
 // ---------------------------------------------------------------------------
-// heads: thread j walks sample groups of eight; h is packed, dhead fp32 rows
+// heads.  Both products run on the matrix cores with the fp32 head gradient
+// split into two bfloat16 terms (d = hi + lo, 16 significant bits):
+//   dZ_L[m][j] = relu'(h[m][j]) * sum_k d[m][k] Wh[j][k]   one MFMA per 32x32 tile with the
+//                reduction index running over (hi_0..7, lo_0..7) against (Wh_0..7, Wh_0..7)
+//   dWh[j][k]  = sum_m h[m][j] d[m][k]                      reduction over samples, hi parts in
+//                output columns 0..7 and lo parts in 8..15, added at the end
+// The reduction over samples may visit them in any order as long as both operands agree; the
+// order used here (per lane half kg: samples 4kg..4kg+3 of two consecutive groups of eight) makes
+// the 8-byte pieces of packed h that feed it the same ones that mask dZ_L.
+// A workgroup walks 64 samples at a time for 256 columns; wavefront w owns columns 64w..64w+63.
 // ---------------------------------------------------------------------------
 struct HeadBwdBf16Args {
     int M, H, NH, NHP, rows;                   // rows per workgroup (multiple of 64)
@@ -35,57 +44,157 @@ struct HeadBwdBf16Args {
     uint16_t* dzR; uint16_t* dzP; float* partial;                    // partial: [blocks over rows][H*NH + NH]
 };
 
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
+{
+    bf2v v; v[0] = (__bf16)lo; v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 __global__ __launch_bounds__(WG) void head_backward_bf16(const HeadBwdBf16Args a)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * (WG + 8)];   // [64 samples][256 columns] for the row-major copy
     constexpr int LDT = WG + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * LDT];   // [64 samples][256 columns] for the row-major copy
+    __shared__ uint4 Ahl[2][64];                                       // dZ product, A operand per 32-sample tile
+    __shared__ uint4 Bhl[2][2][64];                                    // dWh product, B operand per 32-sample tile and 16-sample step
     const int H = a.H, NH = a.NH, NHP = a.NHP;
-    const int jb = blockIdx.y * WG, j = jb + threadIdx.x;
-    const bool live = j < H;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int jb = blockIdx.y * WG, jw = jb + wave * 64;
     const int m_begin = blockIdx.x * a.rows, m_end = m_begin + a.rows;
-    float w[8], dw[8], db[8];
+    bf8 wB[2];
+    bool live[2];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { w[k] = (live && k < NH) ? bfu(a.wh16[(size_t)j * NH + k]) : 0.0f; dw[k] = 0.0f; db[k] = 0.0f; }
+    for (int jt = 0; jt < 2; ++jt) {
+        const int j = jw + 32 * jt + l32;
+        live[jt] = j < H;
+        uint16_t w8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w8[k] = (live[jt] && k < NH) ? a.wh16[(size_t)j * NH + k] : (uint16_t)0;
+        const uint4 wv = make_uint4((uint32_t)w8[0] | ((uint32_t)w8[1] << 16), (uint32_t)w8[2] | ((uint32_t)w8[3] << 16),
+                                    (uint32_t)w8[4] | ((uint32_t)w8[5] << 16), (uint32_t)w8[6] | ((uint32_t)w8[7] << 16));
+        wB[jt] = *reinterpret_cast<const bf8*>(&wv);
+    }
+    f16v acc2[2];
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc2[jt][r] = 0.0f;
+    float db[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // output columns 16..31 of the dWh product stay zero
+    reinterpret_cast<uint4*>(Bhl)[tid] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
     for (int m0 = m_begin; m0 < m_end; m0 += 64) {
-#pragma unroll 2
-        for (int g = 0; g < 8; ++g) {
-            const int mg = (m0 >> 3) + g;
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (live) raw = *reinterpret_cast<const uint4*>(a.hP + ((size_t)mg * H + j) * 8);
-            const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-            uint32_t out[4];
+        // packed h of this wavefront's tiles: group g of 32-sample tile mt, samples 4kg..4kg+3
+        uint2 hq[2][2][4];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const float hv = bfu((uint16_t)((rw[q >> 1] >> ((q & 1) * 16)) & 0xffffu));
-                const float* dh = a.dhead + (size_t)(mg * 8 + q) * NHP;
-                float s = 0.0f;
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (k < NH) {
-                        const float d = dh[k];
-                        s = fmaf(w[k], d, s);
-                        dw[k] = fmaf(hv, d, dw[k]);
-                        db[k] += d;
+            for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const size_t G = (size_t)((m0 + 32 * mt) >> 3) + g;
+                    hq[mt][jt][g] = live[jt] ? *reinterpret_cast<const uint2*>(a.hP + (G * H + jw + 32 * jt + l32) * 8 + 4 * kg)
+                                             : make_uint2(0, 0);
+                }
+        if (tid < 64) {
+            const float* dh = a.dhead + (size_t)(m0 + tid) * NHP;
+            float d[8];
+            const float4 d0 = *reinterpret_cast<const float4*>(dh);
+            d[0] = d0.x; d[1] = d0.y; d[2] = d0.z; d[3] = d0.w;
+            if (NHP == 8) { const float4 d1 = *reinterpret_cast<const float4*>(dh + 4); d[4] = d1.x; d[5] = d1.y; d[6] = d1.z; d[7] = d1.w; }
+            else { d[4] = d[5] = d[6] = d[7] = 0.0f; }
+            uint16_t hi[8], lo[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (k >= NH) d[k] = 0.0f;
+                db[k] += d[k];
+                const uint32_t p = cvt_pk_bf16(d[k], 0.0f);
+                hi[k] = (uint16_t)p;
+                lo[k] = (uint16_t)cvt_pk_bf16(d[k] - bfu(hi[k]), 0.0f);
+            }
+            const int mt = tid >> 5, s = tid & 31;
+            Ahl[mt][s] = make_uint4((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16),
+                                    (uint32_t)hi[4] | ((uint32_t)hi[5] << 16), (uint32_t)hi[6] | ((uint32_t)hi[7] << 16));
+            Ahl[mt][32 + s] = make_uint4((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16),
+                                         (uint32_t)lo[4] | ((uint32_t)lo[5] << 16), (uint32_t)lo[6] | ((uint32_t)lo[7] << 16));
+            const int g = s >> 3, r = s & 7, kgs = r >> 2, q = (g & 1) * 4 + (r & 3);
+            uint16_t* Bp = reinterpret_cast<uint16_t*>(&Bhl[mt][g >> 1][0]);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                Bp[(kgs * 32 + k) * 8 + q] = hi[k];
+                Bp[(kgs * 32 + 8 + k) * 8 + q] = lo[k];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const uint4 a1v = Ahl[mt][lane];
+            const bf8 a1 = *reinterpret_cast<const bf8*>(&a1v);
+            const uint4 b20v = Bhl[mt][0][lane], b21v = Bhl[mt][1][lane];
+            const bf8 b20 = *reinterpret_cast<const bf8*>(&b20v), b21 = *reinterpret_cast<const bf8*>(&b21v);
+#pragma unroll
+            for (int jt = 0; jt < 2; ++jt) {
+                const uint4 x0 = make_uint4(hq[mt][jt][0].x, hq[mt][jt][0].y, hq[mt][jt][1].x, hq[mt][jt][1].y);
+                const uint4 x1 = make_uint4(hq[mt][jt][2].x, hq[mt][jt][2].y, hq[mt][jt][3].x, hq[mt][jt][3].y);
+                acc2[jt] = mfma_bf16(*reinterpret_cast<const bf8*>(&x0), b20, acc2[jt]);
+                acc2[jt] = mfma_bf16(*reinterpret_cast<const bf8*>(&x1), b21, acc2[jt]);
+                f16v acc1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+                acc1 = mfma_bf16(a1, wB[jt], acc1);
+                const int col = wave * 64 + 32 * jt + l32;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t mw[2] = {hq[mt][jt][g].x, hq[mt][jt][g].y};
+                    float o[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float hv = bfu((uint16_t)((mw[q >> 1] >> ((q & 1) * 16)) & 0xffffu));
+                        o[q] = hv > 0.0f ? acc1[4 * g + q] : 0.0f;
+                    }
+                    const uint32_t p01 = cvt_pk_bf16(o[0], o[1]), p23 = cvt_pk_bf16(o[2], o[3]);
+                    const int row = 32 * mt + 8 * g + 4 * kg;
+                    tile[(row + 0) * LDT + col] = (uint16_t)p01; tile[(row + 1) * LDT + col] = (uint16_t)(p01 >> 16);
+                    tile[(row + 2) * LDT + col] = (uint16_t)p23; tile[(row + 3) * LDT + col] = (uint16_t)(p23 >> 16);
+                    if (live[jt]) {
+                        const size_t G = (size_t)((m0 + 32 * mt) >> 3) + g;
+                        *reinterpret_cast<uint2*>(a.dzP + (G * H + jw + 32 * jt + l32) * 8 + 4 * kg) = make_uint2(p01, p23);
                     }
                 }
-                const uint16_t o = bf16_bits(hv > 0.0f ? s : 0.0f);
-                tile[(g * 8 + q) * LDT + threadIdx.x] = o;
-                if (q & 1) out[q >> 1] |= (uint32_t)o << 16; else out[q >> 1] = o;
             }
-            if (live) *reinterpret_cast<uint4*>(a.dzP + ((size_t)mg * H + j) * 8) = make_uint4(out[0], out[1], out[2], out[3]);
         }
         __syncthreads();
         // row-major copy: 64 rows x 256 columns, 16-byte pieces
-        for (int i = threadIdx.x; i < 64 * (WG / 8); i += WG) {
+        for (int i = tid; i < 64 * (WG / 8); i += WG) {
             const int row = i / (WG / 8), c = (i % (WG / 8)) * 8;
             if (jb + c < H)
                 *reinterpret_cast<uint4*>(a.dzR + (size_t)(m0 + row) * H + jb + c) = *reinterpret_cast<const uint4*>(&tile[row * LDT + c]);
         }
-        __syncthreads();
     }
+    __syncthreads();
+    // dWh: rows j of the accumulator, columns k (hi parts) and 8+k (lo parts)
+    float* S = reinterpret_cast<float*>(tile);                       // [256 columns j][16]
+    if (l32 < 16) {
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                S[(wave * 64 + 32 * jt + 8 * (r >> 2) + 4 * kg + (r & 3)) * 16 + l32] = acc2[jt][r];
+    }
+    __syncthreads();
     float* out = a.partial + (size_t)blockIdx.x * ((size_t)H * NH + NH);
-    if (live) for (int k = 0; k < NH; ++k) out[(size_t)j * NH + k] = dw[k];
-    if (j == 0) for (int k = 0; k < NH; ++k) out[(size_t)H * NH + k] = db[k];
+    if (jb + tid < H)
+        for (int k = 0; k < NH; ++k) out[(size_t)(jb + tid) * NH + k] = S[tid * 16 + k] + S[tid * 16 + 8 + k];
+    if (blockIdx.y == 0) {
+        __syncthreads();
+        if (tid < 64) for (int k = 0; k < 8; ++k) S[tid * 8 + k] = db[k];
+        __syncthreads();
+        if (tid < NH) {
+            float sum = 0.0f;
+            for (int i = 0; i < 64; ++i) sum += S[i * 8 + tid];
+            out[(size_t)H * NH + tid] = sum;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
