@@ -79,7 +79,7 @@ static int pick_splits(int M, int tiles, int max_splits, int quantum = 16)
     return s;
 }
 
-static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* splits, int head_fan, int loss_blocks, Layout& L)
+static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int* splits, int splits_w, int head_fan, int loss_blocks, Layout& L)
 {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
@@ -101,7 +101,14 @@ static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* s
         size_t cnt = 0;
         if (l < ns.L) cnt = (size_t)ns.dims[l] * ns.dims[l + 1] + ns.dims[l + 1];
         else if (l == ns.L) cnt = (size_t)ns.dims[ns.L] * ns.NH + ns.NH;
-        L.part[l] = take(cnt * 4 * (size_t)(l <= ns.L ? splits[l] : 0));
+        size_t floats = cnt * (size_t)(l <= ns.L ? splits[l] : 0);
+        if (l == 0 && splits_w > 0) {
+            // wall-plane partials, agent-plane partials, column sums (see launch_backward_bf16)
+            const size_t plane = (size_t)ed.rows * ed.cols * ns.dims[1];
+            const size_t pieces = plane * ((size_t)splits_w + splits[0]) + (size_t)ns.dims[1] * splits_w;
+            if (pieces > floats) floats = pieces;
+        }
+        L.part[l] = take(floats * 4);
     }
     L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
     L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
@@ -109,7 +116,7 @@ static void carve(const EnvDims&, const NetShape& ns, int B, int T, const int* s
     L.total = off;
 }
 
-static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* splits, int* head_fan, int* loss_blocks)
+static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* splits, int* splits_w, int* head_fan, int* loss_blocks)
 {
     const int M = B * T;
     for (int l = 0; l < MAX_REGIONS; ++l) splits[l] = 0;
@@ -124,6 +131,19 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     const bool bfp = rollout_bf16_ok(ns, ed, B);
     const int hq = bfp ? 64 : 16;                       // row quantum of the head pass
     if (bfp) splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256, 64);
+    *splits_w = 0;
+    if (bfp) {
+        // 256 x 256 tiles where both sides of a layer are multiples of 256: about one workgroup per CU
+        for (int l = 1; l < ns.L; ++l)
+            if (ns.dims[l] % 256 == 0 && ns.dims[l + 1] % 256 == 0)
+                splits[l] = pick_splits(M, (ns.dims[l] / 256) * (ns.dims[l + 1] / 256), 64, 64);
+        const int cells = ed.rows * ed.cols;
+        if (ed.kind == ENV_MAZE && cells % 256 == 0 && ns.dims[1] % 256 == 0) {
+            const int tiles = (cells / 256) * (ns.dims[1] / 256);
+            splits[0] = pick_splits(M, tiles, 128, 64);            // agent plane: all B*T samples
+            *splits_w = pick_splits(2 * B, tiles, 64, 64);         // wall plane: time-summed, two bf16 terms per env
+        }
+    }
     int fan = 1;
     while (fan < 16 && (M / hq) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 2 * hq) fan *= 2;
     *head_fan = fan;
@@ -134,10 +154,10 @@ extern "C" size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin
 {
     EnvDims ed; NetShape ns; std::string err;
     if (build_shapes(env, net, B, T, ed, ns, err) != ANAKIN_OK) return 0;
-    int splits[MAX_REGIONS], lb, fan;
-    plan(ed, ns, B, T, splits, &fan, &lb);
+    int splits[MAX_REGIONS], sw, lb, fan;
+    plan(ed, ns, B, T, splits, &sw, &fan, &lb);
     Layout L;
-    carve(ed, ns, B, T, splits, fan, lb, L);
+    carve(ed, ns, B, T, splits, sw, fan, lb, L);
     return L.total;
 }
 
@@ -263,8 +283,8 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0; h->traj_no_acts = 0;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
-    plan(ed, ns, B, T, h->splits, &h->head_fan, &h->loss_blocks);
-    carve(ed, ns, B, T, h->splits, h->head_fan, h->loss_blocks, h->lay);
+    plan(ed, ns, B, T, h->splits, &h->splits_w, &h->head_fan, &h->loss_blocks);
+    carve(ed, ns, B, T, h->splits, h->splits_w, h->head_fan, h->loss_blocks, h->lay);
     if (h->lay.total > workspace_bytes) {
         g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";
         delete h; return ANAKIN_E_WORKSPACE_TOO_SMALL;

@@ -13,6 +13,7 @@ namespace ank {
 
 constexpr int MAX_LAYERS = 4;
 constexpr int MAX_REGIONS = MAX_LAYERS + 1;      // one (W,b) pair per hidden layer + the heads
+constexpr int MAX_ADAM_REGIONS = MAX_REGIONS + 4; // the maze first layer of a bf16 net is reduced in five pieces
 constexpr int WG = 256;                          // threads per workgroup everywhere
 
 // network shape and parameter offsets (elements into theta)
@@ -70,6 +71,16 @@ ANK_HD int transposed_index(const NetShape& n, int i)
     return i;
 }
 
+// Workgroup L of a 1-D grid runs on XCD L % 8 (round-robin dispatch) and each XCD has its own L2.
+// Map L to (outer, inner) so that the n_inner workgroups sharing one `outer` (the same operand
+// tile) run back to back on one XCD and the second reader hits in that L2.
+__device__ __forceinline__ void xcd_map(int L, int n_outer, int n_inner, int& outer, int& inner)
+{
+    const int whole = (n_outer >> 3) << 3, full = whole * n_inner;
+    if (L < full) { const int q = L >> 3; inner = q % n_inner; outer = (q / n_inner) * 8 + (L & 7); }
+    else { const int r = L - full; outer = whole + r / n_inner; inner = r % n_inner; }
+}
+
 // state snapshots the first layer's input is rebuilt from (row m = t*B + b of the trajectory)
 struct ObsLite { EnvDims env; const uint32_t* s0; const float* f0; const float* f1; };
 
@@ -77,7 +88,7 @@ struct ObsLite { EnvDims env; const uint32_t* s0; const float* f0; const float* 
 struct Region { int start, count, splits; const float* partial; };
 
 struct AdamArgs {
-    Region reg[MAX_REGIONS];
+    Region reg[MAX_ADAM_REGIONS];
     int n_regions, P;
     float* theta; float* grad; float* m; float* v;
     uint16_t* w_bf16;            // bf16 copy of theta (same indexing), or null
@@ -121,6 +132,8 @@ struct anakin {
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
     int head_fan;                 // first-stage workgroups per split of the head-gradient pass
+    int splits_w;                 // maze first layer of a bf16 net: split count of the wall-plane product (0: one product
+                                  // over all observation rows); splits[0] is then the split count of the agent-plane product
     int bf16_path;                // the bf16 matrix-core kernels support this net
     int traj_packed;              // the stored unroll holds packed bf16 activations
     int traj_no_acts;             // the stored unroll holds no hidden activations (one-layer nets)
@@ -162,6 +175,8 @@ hipError_t launch_backward_bf16(anakin* h);
 hipError_t launch_refresh_bf16(anakin* h);
 bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B);
 // bf16 network running on the matrix-core path (packed bf16 activations) rather than the fp32 reference path
+// the stored unroll was produced by the bf16 matrix-core kernels and the maze first layer is reduced in pieces
+inline bool first_layer_split(const anakin* h) { return h->splits_w > 0 && h->traj_packed; }
 inline bool bf16_mfma(const anakin* h) { return h->bf16_path && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_VALU_GEMM)); }
 int rollout_pick_tile(const NetShape& net, int B);
 int rollout_pick_tile_mfma(const NetShape& net, int B);

@@ -504,7 +504,7 @@ __global__ __launch_bounds__(ADAM_WAVES * 64) void adam_reduce(const AdamArgs a)
     if (ok) {
         int r = 0;
 #pragma unroll
-        for (int k = 1; k < MAX_REGIONS; ++k) if (k < a.n_regions && i >= a.reg[k].start) r = k;
+        for (int k = 1; k < MAX_ADAM_REGIONS; ++k) if (k < a.n_regions && i >= a.reg[k].start) r = k;
         const Region rg = a.reg[r];
         const float* p = rg.partial + (i - rg.start);
 #pragma unroll 4
@@ -599,11 +599,27 @@ hipError_t launch_adam(anakin* h)
     const Layout& L = h->lay;
     const NetShape& n = h->net;
     AdamArgs a;
-    a.n_regions = n.L + 1; a.P = n.P;
-    for (int l = 0; l < n.L; ++l)
-        a.reg[l] = Region{n.w_off[l], n.dims[l] * n.dims[l + 1] + n.dims[l + 1], h->splits[l], at<const float>(h, L.part[l])};
-    a.reg[n.L] = Region{n.wh_off, n.dims[n.L] * n.NH + n.NH, h->splits[n.L], at<const float>(h, L.part[n.L])};
-    for (int l = n.L + 1; l < MAX_REGIONS; ++l) a.reg[l] = Region{0x7fffffff, 0, 0, nullptr};
+    a.P = n.P;
+    int r = 0;
+    for (int l = 0; l < n.L; ++l) {
+        if (l == 0 && first_layer_split(h)) {
+            // wall rows, agent rows, goal rows (zero but the last, which equals the bias gradient), bias
+            const int H1 = n.dims[1], plane = h->env.rows * h->env.cols * H1;
+            const float* pw = at<const float>(h, L.part[0]);
+            const float* pa = pw + (size_t)plane * h->splits_w;
+            const float* pg = pa + (size_t)plane * h->splits[0];
+            a.reg[r++] = Region{n.w_off[0], plane, h->splits_w, pw};
+            a.reg[r++] = Region{n.w_off[0] + plane, plane, h->splits[0], pa};
+            a.reg[r++] = Region{n.w_off[0] + 2 * plane, plane - H1, 0, nullptr};
+            a.reg[r++] = Region{n.w_off[0] + 3 * plane - H1, H1, h->splits_w, pg};
+            a.reg[r++] = Region{n.b_off[0], H1, h->splits_w, pg};
+            continue;
+        }
+        a.reg[r++] = Region{n.w_off[l], n.dims[l] * n.dims[l + 1] + n.dims[l + 1], h->splits[l], at<const float>(h, L.part[l])};
+    }
+    a.reg[r++] = Region{n.wh_off, n.dims[n.L] * n.NH + n.NH, h->splits[n.L], at<const float>(h, L.part[n.L])};
+    a.n_regions = r;
+    for (; r < MAX_ADAM_REGIONS; ++r) a.reg[r] = Region{0x7fffffff, 0, 0, nullptr};
     a.theta = at<float>(h, L.theta); a.grad = at<float>(h, L.grad); a.m = at<float>(h, L.m); a.v = at<float>(h, L.v);
     a.w_bf16 = n.bf16 ? at<uint16_t>(h, L.w_bf16) : nullptr;
     a.wt_bf16 = n.bf16 ? at<uint16_t>(h, L.wt_bf16) : nullptr;

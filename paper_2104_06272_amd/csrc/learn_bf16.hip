@@ -221,7 +221,9 @@ __global__ __launch_bounds__(WG) void gemm_nt_bf16(const GemmNtBf16Args a)
     uint16_t* Bs = As + 128 * NB_LD;                            // [128][NB_LD] W tile
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, kg = lane >> 5;
-    const int m0 = blockIdx.x * 128, i0 = blockIdx.y * 128;
+    int mt_, it_;
+    xcd_map((int)blockIdx.x, (a.M + 127) / 128, (a.K + 127) / 128, mt_, it_);   // the i-tiles of one m-tile share dY
+    const int m0 = mt_ * 128, i0 = it_ * 128;
     // loader: 128 rows x 16 pieces of 16 B = 2048 pieces per matrix, 8 per thread
     uint4 ra[8], rb[8];
     auto fetch = [&](int j0) {
@@ -306,21 +308,25 @@ __global__ __launch_bounds__(WG) void gemm_nt_bf16(const GemmNtBf16Args a)
 // ---------------------------------------------------------------------------
 struct GemmTnBf16Args {
     int M, K, N, splits, rows, tiles_i, use_obs;
+    int obs_row0;             // with use_obs: row i of this product is observation feature obs_row0 + i
     const uint16_t* xP;       // packed [M/8][K][8], unused with use_obs
     const uint16_t* dyP;      // packed [M/8][N][8]
-    float* partial;           // [splits][K*N + N]
+    float* partial;           // [splits][split_stride]: K x N partial of each split
+    size_t split_stride;
+    float* bias_out;          // [splits][bias_stride]: N column sums of each split, or null
+    size_t bias_stride;
     ObsSrc obs;
 };
 
 constexpr int TB_G = 16;      // sample groups (of 8) per LDS stage: 128 samples
 
-__device__ __forceinline__ uint4 obs_piece(const ObsSrc& o, int mg, int i, int K)
+__device__ __forceinline__ uint4 obs_piece(const ObsSrc& o, int mg, int i, bool valid)
 {
     // eight consecutive samples (same time step, consecutive envs) of observation feature i
     uint16_t v[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) v[q] = 0;
-    if (i < K) {
+    if (valid) {
         const int m = mg * 8;
         if (o.kind == ENV_CATCH) {
 #pragma unroll
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(WG) void gemm_tn_bf16(const GemmTnBf16Args a)
         for (int q = 0; q < 8; ++q) {
             const int p = q * WG + tid, g = g0 + (p >> 7), c = p & 127;
             const bool gok = g < g_end;
-            if (OBS) rx[q] = gok ? obs_piece(a.obs, g, i0 + c, a.K) : make_uint4(0, 0, 0, 0);
+            if (OBS) rx[q] = gok ? obs_piece(a.obs, g, a.obs_row0 + i0 + c, i0 + c < a.K) : make_uint4(0, 0, 0, 0);
             else rx[q] = (gok && i0 + c < a.K) ? *reinterpret_cast<const uint4*>(a.xP + ((size_t)g * a.K + i0 + c) * 8) : make_uint4(0, 0, 0, 0);
             ry[q] = (gok && j0 + c < a.N) ? *reinterpret_cast<const uint4*>(a.dyP + ((size_t)g * a.N + j0 + c) * 8) : make_uint4(0, 0, 0, 0);
         }
@@ -424,7 +430,7 @@ __global__ __launch_bounds__(WG) void gemm_tn_bf16(const GemmTnBf16Args a)
         }
         __syncthreads();
     }
-    float* out = a.partial + (size_t)split * ((size_t)a.K * a.N + a.N);
+    float* out = a.partial + (size_t)split * a.split_stride;
     if (live) {
 #pragma unroll
         for (int tr = 0; tr < 2; ++tr)
@@ -438,7 +444,136 @@ __global__ __launch_bounds__(WG) void gemm_tn_bf16(const GemmTnBf16Args a)
                 }
             }
     }
-    if (ti == 0 && tid < 128 && j0 + tid < a.N) out[(size_t)a.K * a.N + j0 + tid] = bsum;
+    if (ti == 0 && a.bias_out && tid < 128 && j0 + tid < a.N) a.bias_out[(size_t)split * a.bias_stride + j0 + tid] = bsum;
+}
+
+// The same product with a 256 x 256 tile and eight wavefronts (two per SIMD, so one's LDS and
+// global traffic overlaps the other's MFMAs): wavefront (wm, wn) owns rows 128*wm.., columns
+// 64*wn.. of the tile, eight 32 x 32 accumulators, and every 16-byte read from LDS feeds 2 or 4
+// MFMAs.  K and N multiples of 256.
+constexpr int BIGWG = 512;
+constexpr int TB_BG = 8;      // sample groups (of 8) per LDS stage: 64 samples
+
+template <bool OBS>
+__global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a)
+{
+    extern __shared__ uint4 smem4[];
+    uint4* Xs = smem4;                       // [TB_BG][256] pieces of 8 samples
+    uint4* Ys = Xs + TB_BG * 256;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, kg = lane >> 5;
+    int split, tile;
+    xcd_map((int)blockIdx.x, a.splits, a.tiles_i * (a.N / 256), split, tile);   // the tiles of one split share its samples
+    const int ti = tile % a.tiles_i, tj = tile / a.tiles_i;
+    const int i0 = ti * 256, j0 = tj * 256;
+    const int g_begin = (split * a.rows) >> 3, g_end = g_begin + (a.rows >> 3);
+    // loader: thread = (column, parity of the sample group), four groups of the stage each
+    const int lc = tid & 255, lg = tid >> 8;
+    uint4 rx[TB_BG / 2], ry[TB_BG / 2];
+    auto fetch = [&](int g0) {
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q) {
+            const int g = g0 + 2 * q + lg;
+            const bool gok = g < g_end;
+            if (OBS) rx[q] = gok ? obs_piece(a.obs, g, a.obs_row0 + i0 + lc, true) : make_uint4(0, 0, 0, 0);
+            else rx[q] = gok ? *reinterpret_cast<const uint4*>(a.xP + ((size_t)g * a.K + i0 + lc) * 8) : make_uint4(0, 0, 0, 0);
+            ry[q] = gok ? *reinterpret_cast<const uint4*>(a.dyP + ((size_t)g * a.N + j0 + lc) * 8) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    fetch(g_begin);
+    f16v acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    float bsum = 0.0f;
+    const bool sums = ti == 0 && a.bias_out != nullptr;
+    for (int g0 = g_begin; g0 < g_end; g0 += TB_BG) {
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q) { Xs[(2 * q + lg) * 256 + lc] = rx[q]; Ys[(2 * q + lg) * 256 + lc] = ry[q]; }
+        __syncthreads();
+        if (sums) {
+#pragma unroll
+            for (int q = 0; q < TB_BG / 2; ++q) {
+                const uint32_t yw[4] = {ry[q].x, ry[q].y, ry[q].z, ry[q].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bsum += bfu((uint16_t)((yw[e >> 1] >> ((e & 1) * 16)) & 0xffffu));
+            }
+        }
+        if (g0 + TB_BG < g_end) fetch(g0 + TB_BG);
+#pragma unroll
+        for (int ks = 0; ks < TB_BG; ks += 2) {                  // one MFMA step = 16 samples = 2 groups
+            bf8 av[4], bv[2];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint4 x = Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32];
+                av[t] = *reinterpret_cast<const bf8*>(&x);
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint4 y = Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32];
+                bv[t] = *reinterpret_cast<const bf8*>(&y);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    float* out = a.partial + (size_t)split * a.split_stride;
+#pragma unroll
+    for (int tr = 0; tr < 4; ++tr)
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc) {
+            const int j = j0 + wn * 64 + tc * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wm * 128 + tr * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+                out[(size_t)i * a.N + j] = acc[tr][tc][r];
+            }
+        }
+    if (sums) {
+        // the two threads of a column (even and odd sample groups) add their sums in a fixed order
+        float* red = reinterpret_cast<float*>(smem4);
+        if (lg == 1) red[lc] = bsum;
+        __syncthreads();
+        if (lg == 0) a.bias_out[(size_t)split * a.bias_stride + j0 + lc] = bsum + red[lc];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Maze first layer.  The observation has three one-hot planes (paper section 2.1 style grid
+// world: walls, agent, goal) and only the agent plane changes within an unroll, so
+//   dW1[wall cell c]  = sum_b walls[b][c] * S[b],   S[b] = sum_t dZ1[t][b]   (B samples, not B*T)
+//   dW1[agent cell c] = sum_m [pos_m == c] dZ1[m]                             (the only full-length product)
+//   dW1[goal cell]    = db1 = sum_b S[b]  for the one goal cell, zero for the others
+// time_sum_bf16 writes S as two bfloat16 terms (hi rows 0..B-1, lo rows B..2B-1 of a packed
+// matrix with 2B samples); the wall product then runs over those 2B samples.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(WG) void time_sum_bf16(const uint16_t* __restrict__ dzP, uint16_t* __restrict__ sP, int B, int T, int H)
+{
+    const size_t idx = (size_t)blockIdx.x * WG + threadIdx.x;          // (env group, column)
+    const size_t n = (size_t)(B >> 3) * H;
+    if (idx >= n) return;
+    float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 8
+    for (int t = 0; t < T; ++t) {
+        const uint4 v = *reinterpret_cast<const uint4*>(dzP + ((size_t)t * n + idx) * 8);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += bfu((uint16_t)((w[e >> 1] >> ((e & 1) * 16)) & 0xffffu));
+    }
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        hi[q] = cvt_pk_bf16(s[2 * q], s[2 * q + 1]);
+        lo[q] = cvt_pk_bf16(s[2 * q] - bfu((uint16_t)hi[q]), s[2 * q + 1] - bfu((uint16_t)(hi[q] >> 16)));
+    }
+    *reinterpret_cast<uint4*>(sP + idx * 8) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    *reinterpret_cast<uint4*>(sP + (n + idx) * 8) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
 }
 
 // ---------------------------------------------------------------------------
@@ -497,29 +632,71 @@ hipError_t launch_backward_bf16(anakin* h)
             if (e != hipSuccess) return e;
         }
     }
-    for (int l = n.L - 1; l >= 0; --l) {
-        GemmTnBf16Args t;
-        t.M = M; t.K = n.dims[l]; t.N = n.dims[l + 1];
-        t.splits = h->splits[l]; t.rows = M / t.splits;
-        t.tiles_i = (t.K + 127) / 128;
-        t.use_obs = (l == 0);
-        t.xP = l > 0 ? actP(l - 1) : nullptr;
-        t.dyP = dzP(l);
-        t.partial = at<float>(h, L.part[l]);
-        t.obs.kind = h->env.kind; t.obs.env = h->env; t.obs.B = h->B;
-        t.obs.s0 = at<const uint32_t>(h, L.tr_s0); t.obs.f0 = at<const float>(h, L.tr_f0);
-        t.obs.f1 = at<const float>(h, L.tr_f1); t.obs.walls = at<const uint32_t>(h, L.walls);
-        const dim3 grid(t.tiles_i * ((t.N + 127) / 128), t.splits);
-        const size_t lds = (size_t)2 * TB_G * 128 * sizeof(uint4);
-        e = t.use_obs ? hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_bf16<true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                      : hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_bf16<false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        {
-            ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
+    auto obs_src = [&]() {
+        ObsSrc o;
+        o.kind = h->env.kind; o.env = h->env; o.B = h->B;
+        o.s0 = at<const uint32_t>(h, L.tr_s0); o.f0 = at<const float>(h, L.tr_f0);
+        o.f1 = at<const float>(h, L.tr_f1); o.walls = at<const uint32_t>(h, L.walls);
+        return o;
+    };
+    // dW partials of one product; big: 256 x 256 tiles
+    auto run_tn = [&](GemmTnBf16Args& t, bool big, const char* name) -> hipError_t {
+        const int tile = big ? 256 : 128;
+        t.tiles_i = (t.K + tile - 1) / tile;
+        const int tiles = t.tiles_i * ((t.N + tile - 1) / tile);
+        const dim3 grid = big ? dim3(tiles * t.splits) : dim3(tiles, t.splits);
+        const size_t lds = (size_t)2 * (big ? TB_BG * 256 : TB_G * 128) * sizeof(uint4);
+        const void* fn = big ? (t.use_obs ? reinterpret_cast<const void*>(gemm_tn_bf16_big<true>) : reinterpret_cast<const void*>(gemm_tn_bf16_big<false>))
+                             : (t.use_obs ? reinterpret_cast<const void*>(gemm_tn_bf16<true>) : reinterpret_cast<const void*>(gemm_tn_bf16<false>));
+        hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e2 != hipSuccess) return e2;
+        ProfScope prof(h, name);
+        if (big) {
+            if (t.use_obs) hipLaunchKernelGGL(gemm_tn_bf16_big<true>, grid, dim3(BIGWG), lds, h->stream, t);
+            else hipLaunchKernelGGL(gemm_tn_bf16_big<false>, grid, dim3(BIGWG), lds, h->stream, t);
+        } else {
             if (t.use_obs) hipLaunchKernelGGL(gemm_tn_bf16<true>, grid, dim3(WG), lds, h->stream, t);
             else hipLaunchKernelGGL(gemm_tn_bf16<false>, grid, dim3(WG), lds, h->stream, t);
         }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        return hipGetLastError();
+    };
+    for (int l = n.L - 1; l >= 0; --l) {
+        if (l == 0 && first_layer_split(h)) {
+            const int H1 = n.dims[1], cells = h->env.rows * h->env.cols, plane = cells * H1;
+            uint16_t* sP = at<uint16_t>(h, L.prefix);                // B x H1 words, free between unrolls
+            float* pw = at<float>(h, L.part[0]);
+            float* pa = pw + (size_t)plane * h->splits_w;
+            float* pg = pa + (size_t)plane * h->splits[0];
+            {
+                ProfScope prof(h, "time_sum");
+                hipLaunchKernelGGL(time_sum_bf16, dim3(((h->B >> 3) * H1 + WG - 1) / WG), dim3(WG), 0, h->stream,
+                                   dzP(0), sP, h->B, h->T, H1);
+            }
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            GemmTnBf16Args t;
+            t.M = 2 * h->B; t.K = cells; t.N = H1; t.splits = h->splits_w; t.rows = t.M / t.splits;
+            t.use_obs = 1; t.obs_row0 = 0; t.xP = nullptr; t.dyP = sP;
+            t.partial = pw; t.split_stride = (size_t)plane; t.bias_out = pg; t.bias_stride = (size_t)H1;
+            t.obs = obs_src();
+            if ((e = run_tn(t, true, "gemm_tn_walls")) != hipSuccess) return e;
+            t.M = M; t.splits = h->splits[0]; t.rows = t.M / t.splits;
+            t.obs_row0 = cells; t.dyP = dzP(0);
+            t.partial = pa; t.bias_out = nullptr; t.bias_stride = 0;
+            if ((e = run_tn(t, true, "gemm_tn_agent")) != hipSuccess) return e;
+            continue;
+        }
+        GemmTnBf16Args t;
+        t.M = M; t.K = n.dims[l]; t.N = n.dims[l + 1];
+        t.splits = h->splits[l]; t.rows = M / t.splits;
+        t.use_obs = (l == 0); t.obs_row0 = 0;
+        t.xP = l > 0 ? actP(l - 1) : nullptr;
+        t.dyP = dzP(l);
+        t.partial = at<float>(h, L.part[l]);
+        t.split_stride = (size_t)t.K * t.N + t.N;
+        t.bias_out = t.partial + (size_t)t.K * t.N; t.bias_stride = t.split_stride;
+        t.obs = obs_src();
+        const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0;
+        if ((e = run_tn(t, big, l == 0 ? "gemm_tn_obs" : "gemm_tn")) != hipSuccess) return e;
         if (l > 0) {
             GemmNtBf16Args g;
             g.M = M; g.K = n.dims[l]; g.N = n.dims[l + 1];
@@ -528,11 +705,10 @@ hipError_t launch_backward_bf16(anakin* h)
             g.hP = actP(l - 1);
             g.dxR = dzR(l - 1); g.dxP = dzP(l - 1);
             const size_t lds2 = (size_t)2 * 128 * NB_LD * sizeof(uint16_t);
-            auto kern = gemm_nt_bf16;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_bf16), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
             if (e != hipSuccess) return e;
             ProfScope prof(h, "gemm_nt_mask");
-            hipLaunchKernelGGL(kern, dim3((g.M + 127) / 128, (g.K + 127) / 128), dim3(WG), lds2, h->stream, g);
+            hipLaunchKernelGGL(gemm_nt_bf16, dim3(((g.M + 127) / 128) * ((g.K + 127) / 128)), dim3(WG), lds2, h->stream, g);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
     }

@@ -169,6 +169,8 @@ def test_full_size_rollout_sampled_envs(gpu, orc, name):
 BF16_CASES = {
     "maze_bf16_128": (variant("maze_16384", hidden=[128, 128, 128], B=64, T=16, max_steps=40), 3, 2),
     "maze_bf16_256_512": (variant("maze_16384", hidden=[256, 512], B=128, T=8, rows=8, cols=8, max_steps=20), 1, 2),
+    # 16x16 maze with 256-wide layers: 256 x 256 GEMM tiles and the first layer reduced plane by plane
+    "maze_bf16_16x16_256": (variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20), 4, 2),
     "catch_bf16_128": (variant("catch_4096", hidden=[128, 128], B=64, T=12, dtype="bf16"), 0, 2),
     "pendulum_bf16_128": (variant("pendulum_8192", hidden=[128, 128], B=64, T=10, dtype="bf16", max_steps=7), 2, 2),
 }
