@@ -79,6 +79,13 @@ static int pick_splits(int M, int tiles, int max_splits, int quantum = 16)
     return s;
 }
 
+// largest split count <= cap whose chunks are whole multiples of `quantum` rows (1 if none)
+static int pick_divisor_splits(int M, int quantum, int cap)
+{
+    for (int s = cap; s > 1; --s) if (M % (s * quantum) == 0) return s;
+    return M % quantum == 0 ? 1 : 0;
+}
+
 static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int* splits, int splits_w, int head_fan, int loss_blocks, Layout& L)
 {
     size_t off = 0;
@@ -126,6 +133,11 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     }
     splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256);
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
+    if (ed.kind == ENV_CATCH && ns.dims[0] < 64 && !ns.bf16) {
+        // matrix-core scatter: 64-sample steps, about two workgroups (of 128 columns) per CU
+        const int s = pick_divisor_splits(M, 64, 512 / ((ns.dims[1] + 127) / 128));
+        if (s > 0) splits[0] = s;
+    }
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
     const bool bfp = rollout_bf16_ok(ns, ed, B);

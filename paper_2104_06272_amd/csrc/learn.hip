@@ -318,6 +318,79 @@ __global__ __launch_bounds__(WG) void first_layer_grad(const FirstGradArgs a)
     }
 }
 
+// The same scatter on the matrix cores for boards of at most 63 cells: dW1 = X^T dZ1 with the 0/1
+// board rebuilt from the state word, v_mfma_f32_32x32x2_f32 taking two samples per step.  Row K of
+// the padded board is all ones, so the column sums (the bias gradient) fall out of the same product
+// and land in the slot after the K weight rows.  The MFMA adds its products in ascending step order,
+// which makes the sum as deterministic as the scatter.  A wavefront owns 32 columns and both
+// 32-row tiles; of each block of 64 samples lane half kg takes samples 32*kg + s at step s, so both
+// halves read whole 128-byte rows of dZ1.
+typedef float f16v_l __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(WG) void first_layer_grad_mfma(const FirstGradArgs a)
+{
+    const int N = a.N, K = a.K;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int j = blockIdx.y * 128 + wave * 32 + l32;
+    const int split = blockIdx.x;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    f16v_l acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc0[r] = 0.0f; acc1[r] = 0.0f; }
+    const float* __restrict__ dy = a.dy + j;
+    // rows per split and N are whole multiples of 64 and 32 here (see the launcher): no guards.
+    // Two register buffers: the loads of the next 64 samples are in flight under the MFMAs of these.
+    auto load = [&](float (&d)[32], uint32_t& lo, uint32_t& hi, int m0) {
+        // lane l holds the padded board of sample m0 + l as a bit mask: its two cells and the ones row K
+        int bc, pc;
+        catch_obs_cells(a.obs.env, a.obs.s0[m0 + lane], bc, pc);
+        const unsigned long long bits = (1ull << bc) | (1ull << pc) | (1ull << K);
+        lo = (uint32_t)bits; hi = (uint32_t)(bits >> 32);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) d[s] = dy[(size_t)(m0 + 32 * kg + s) * N];
+    };
+    auto compute = [&](const float (&d)[32], uint32_t lo, uint32_t hi) {
+        // board operands of all 32 steps first, then an uninterrupted run of MFMAs
+        float x0[32], x1[32];
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {
+            const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readlane((int)lo, s), lo1 = (uint32_t)__builtin_amdgcn_readlane((int)lo, 32 + s);
+            const uint32_t hi0 = (uint32_t)__builtin_amdgcn_readlane((int)hi, s), hi1 = (uint32_t)__builtin_amdgcn_readlane((int)hi, 32 + s);
+            x0[s] = (float)(((kg ? lo1 : lo0) >> l32) & 1u);
+            x1[s] = (float)(((kg ? hi1 : hi0) >> l32) & 1u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[s], d[s], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[s], d[s], acc1, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    float dA[32], dB[32];
+    uint32_t loA, hiA, loB = 0u, hiB = 0u;
+    // every load is unconditional (past the end it re-reads the last block and the result is dropped), so
+    // the wait counters the compiler places before the MFMAs never have to cover the prefetch
+    const int m_last = m_end - 64;
+    load(dA, loA, hiA, m_begin);
+    for (int m0 = m_begin; m0 < m_end; m0 += 128) {
+        load(dB, loB, hiB, m0 + 64 < m_end ? m0 + 64 : m_last);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(dA, loA, hiA);
+        load(dA, loA, hiA, m0 + 128 < m_end ? m0 + 128 : m_last);
+        __builtin_amdgcn_sched_barrier(0);
+        if (m0 + 64 < m_end) compute(dB, loB, hiB);
+    }
+    // rows 0..K-1 are dW1, row K the column sums: row i of the padded product goes to out[i*N + j]
+    float* out = a.partial + (size_t)split * ((size_t)K * N + N);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = 8 * (r >> 2) + 4 * kg + (r & 3);
+        if (i <= K) out[(size_t)i * N + j] = acc0[r];
+        if (i + 32 <= K) out[(size_t)(i + 32) * N + j] = acc1[r];
+    }
+}
+
 hipError_t launch_first_layer_grad(anakin* h)
 {
     const Layout& L = h->lay;
@@ -331,7 +404,9 @@ hipError_t launch_first_layer_grad(anakin* h)
     const size_t lds = (size_t)WG * a.K * sizeof(float);
     const dim3 grid(h->splits[0], (a.N + WG - 1) / WG);
     ProfScope prof(h, "first_layer_grad");
-    if (h->env.kind == ENV_CATCH) {
+    if (h->env.kind == ENV_CATCH && a.K < 64 && a.rows % 64 == 0 && a.N % 128 == 0 && !(h->mode & ANAKIN_MODE_VALU_GEMM)) {
+        hipLaunchKernelGGL(first_layer_grad_mfma, dim3(h->splits[0], a.N / 128), dim3(WG), 0, h->stream, a);
+    } else if (h->env.kind == ENV_CATCH) {
         auto kern = first_layer_grad<ENV_CATCH>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
