@@ -141,7 +141,7 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
     const bool bfp = rollout_bf16_ok(ns, ed, B);
-    const int hq = bfp ? 64 : 16;                       // row quantum of the head pass
+    const int hq = bfp ? 64 : (M % 32 == 0 ? 32 : 16);  // row quantum of the head pass
     if (bfp) splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256, 64);
     *splits_w = 0;
     if (bfp) {

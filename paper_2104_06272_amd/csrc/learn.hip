@@ -225,6 +225,108 @@ __global__ __launch_bounds__(WG) void head_backward(const HeadBwdArgs a)
     }
 }
 
+// The same pass on the matrix cores (v_mfma_f32_32x32x2_f32, whose sum over the reduction index is
+// the same ascending fma chain the vector kernel uses, so dZ_L is unchanged bit for bit):
+//   dZ_L tile [32 samples][32 units] = dhead[32][8] Wh^T[8][32]        4 MFMAs, then the ReLU mask
+//   dWh  tile [32 units][heads]     += h^T[32][2 samples] dhead[2][..]  16 MFMAs per 32 samples
+// The reduction over samples may take them in any order as long as both operands agree; step (g, q)
+// uses sample 8g + 4kg + q for lane half kg, which is the row of the dZ_L accumulator that lane holds,
+// so one load of h serves as operand and as mask.  A workgroup walks its rows 32 at a time;
+// wavefront w owns units 64w..64w+63 of the 256 the workgroup covers.
+typedef float f16v_h __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(WG) void head_backward_mfma(const HeadBwdArgs a)
+{
+    __shared__ float Dl[2][32 * 8];                          // head gradients of the current 32 samples, double buffered
+    __shared__ float red[WG];
+    const int H = a.H, NH = a.NH, NHP = a.NHP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int jw = blockIdx.y * 256 + wave * 64;             // first unit of this wavefront
+    const bool active = jw < H;                              // H is a multiple of 64
+    const int split = blockIdx.x;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    // Wh of this lane's unit in both tiles, as B operand of the dZ product: step i takes heads 2i + kg
+    float wB[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = 2 * i + kg;
+            float x = (active && k < NH) ? a.wh[(size_t)(jw + 32 * t + l32) * NH + k] : 0.0f;
+            if (a.bf16) x = bf16_to_f(bf16_bits(x));
+            wB[t][i] = x;
+        }
+    f16v_h accw[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accw[t][r] = 0.0f;
+    // staging: thread (sample tid / 8, head tid % 8) moves one head gradient per step and keeps its sum
+    const int ss = tid >> 3, sk = tid & 7;
+    float dsum = 0.0f;
+    auto stage = [&](int buf, int m0) {
+        const float v = (sk < NH) ? a.dhead[(size_t)(m0 + ss) * NHP + sk] : 0.0f;
+        Dl[buf][tid] = v;
+        dsum += v;
+    };
+    const float* __restrict__ hin = a.h + jw + l32;
+    float* __restrict__ dzo = a.dz + jw + l32;
+    stage(0, m_begin);
+    __syncthreads();
+    int buf = 0;
+    for (int m0 = m_begin; m0 < m_end; m0 += 32, buf ^= 1) {
+        if (m0 + 32 < m_end) stage(buf ^ 1, m0 + 32);        // visible after the barrier at the end of this step
+        if (active) {
+            float hv[2][16];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    hv[t][r] = hin[(size_t)(m0 + 8 * (r >> 2) + 4 * kg + (r & 3)) * H + 32 * t];
+            // dZ product: A = dhead[sample l32][head 2i + kg]
+            float dA[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dA[i] = Dl[buf][l32 * 8 + 2 * i + kg];
+            // dWh product: B = dhead[sample 8g + 4kg + q][head l32] for l32 < 8, zero columns beyond
+            float dB[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dB[r] = l32 < 8 ? Dl[buf][(8 * (r >> 2) + 4 * kg + (r & 3)) * 8 + l32] : 0.0f;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                f16v_h accz;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accz[r] = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) accz = __builtin_amdgcn_mfma_f32_32x32x2f32(dA[i], wB[t][i], accz, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) accw[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(hv[t][r], dB[r], accw[t], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    dzo[(size_t)(m0 + 8 * (r >> 2) + 4 * kg + (r & 3)) * H + 32 * t] = hv[t][r] > 0.0f ? accz[r] : 0.0f;
+            }
+        }
+        __syncthreads();
+    }
+    // dWh: row = unit 8(r/4) + 4kg + r%4 of the tile, column = head l32
+    float* out = a.partial + (size_t)split * ((size_t)H * NH + NH);
+    if (active && l32 < NH) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                out[(size_t)(jw + 32 * t + 8 * (r >> 2) + 4 * kg + (r & 3)) * NH + l32] = accw[t][r];
+    }
+    if (blockIdx.y == 0) {
+        red[tid] = dsum;
+        __syncthreads();
+        if (tid < NH) {
+            float sum = 0.0f;
+            for (int i = 0; i < 32; ++i) sum += red[i * 8 + tid];
+            out[(size_t)H * NH + tid] = sum;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Second stage of a two-level split-K sum: dst[s][i] = sum_{f < fan} src[s*fan + f][i],
 // in ascending f.  Lets a bandwidth-bound producer use many small workgroups while the
@@ -659,7 +761,10 @@ hipError_t launch_head_backward(anakin* h)
     const size_t lds = (size_t)groups * stride * sizeof(float);
     {
         ProfScope prof(h, "head_backward");
-        hipLaunchKernelGGL(head_backward, dim3(stage1), dim3(WG), lds, h->stream, a);
+        if (a.H % 64 == 0 && a.rows % 32 == 0 && !(h->mode & ANAKIN_MODE_VALU_GEMM))
+            hipLaunchKernelGGL(head_backward_mfma, dim3(stage1, (a.H + 255) / 256), dim3(WG), 0, h->stream, a);
+        else
+            hipLaunchKernelGGL(head_backward, dim3(stage1), dim3(WG), lds, h->stream, a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || fan == 1) return e;
