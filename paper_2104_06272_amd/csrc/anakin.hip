@@ -132,6 +132,13 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         splits[l] = pick_splits(M, tiles, 256);
     }
     splits[ns.L] = pick_splits(M, (ns.dims[ns.L] + 127) / 128, 256);
+    if (!ns.bf16)
+        for (int l = 1; l < ns.L; ++l)
+            if (ns.dims[l] == 256 && ns.dims[l + 1] == 256) {
+                // persistent 256 x 256 dW kernel: one chunk per compute unit, 32-sample steps
+                const int s = pick_divisor_splits(M, 32, 256);
+                if (s > 0) splits[l] = s;
+            }
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
     if (ed.kind == ENV_CATCH && ns.dims[0] < 64 && !ns.bf16) {
         // matrix-core scatter: 64-sample steps, about two workgroups (of 128 columns) per CU

@@ -35,5 +35,10 @@ hipError_t launch_gemm_nt_valu(const GemmNtArgs& a, hipStream_t s);
 hipError_t launch_gemm_tn_valu(GemmTnArgs a, hipStream_t s);
 hipError_t launch_gemm_nt_mfma(const GemmNtArgs& a, hipStream_t s);
 hipError_t launch_gemm_tn_mfma(GemmTnArgs a, hipStream_t s);
+// persistent, operand-resident kernels for 256-wide layers
+bool gemm_nt_res_ok(const GemmNtArgs& a);
+bool gemm_tn_res_ok(const GemmTnArgs& a);
+hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s);
+hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s);
 
 }  // namespace ank

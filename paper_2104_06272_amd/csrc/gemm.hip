@@ -190,7 +190,7 @@ hipError_t launch_backward(anakin* h)
         const bool mfma = !(h->mode & ANAKIN_MODE_VALU_GEMM) && !n.bf16;
         {
             ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
-            e = mfma ? launch_gemm_tn_mfma(t, h->stream) : launch_gemm_tn_valu(t, h->stream);
+            e = !mfma ? launch_gemm_tn_valu(t, h->stream) : gemm_tn_res_ok(t) ? launch_gemm_tn_res(t, h->stream) : launch_gemm_tn_mfma(t, h->stream);
         }
         if (e != hipSuccess) return e;
         if (l > 0) {
@@ -203,7 +203,7 @@ hipError_t launch_backward(anakin* h)
             g.bf16 = n.bf16;
             {
                 ProfScope prof(h, "gemm_nt_mask");
-                e = mfma ? launch_gemm_nt_mfma(g, h->stream) : launch_gemm_nt_valu(g, h->stream);
+                e = !mfma ? launch_gemm_nt_valu(g, h->stream) : gemm_nt_res_ok(g) ? launch_gemm_nt_res(g, h->stream) : launch_gemm_nt_mfma(g, h->stream);
             }
             if (e != hipSuccess) return e;
         }

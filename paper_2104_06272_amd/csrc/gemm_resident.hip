@@ -1,0 +1,227 @@
+// Backward GEMMs of a 256-wide fp32 hidden layer as one persistent workgroup
+// per compute unit (paper section 3.2: the backward pass is the expensive half
+// of the update).  With M = B*T samples and 256 x 256 weights the tiled
+// kernels in gemm_mfma.hip lose time to tile-count quantisation, to a prologue
+// and an epilogue per 128 x 128 tile and to re-reading operands per tile.
+// Here every compute unit takes M/256 consecutive samples and keeps, for the
+// whole launch, the operand that does not depend on the sample in registers:
+//
+//   gemm_nt_res256   dX = (dY W^T) masked: W lives in registers (wavefront w holds
+//                    the 32 output columns 32w.., 128 registers per lane); dY streams
+//                    through LDS 32 rows at a time, double buffered
+//   gemm_tn_res256   dW partial = X^T dY: the whole 256 x 256 accumulator lives in
+//                    registers (eight wavefronts x 128 x 64); X and dY stream through
+//                    LDS 32 samples at a time, double buffered; one partial per unit
+//
+// Eight wavefronts per workgroup, two per SIMD: while one waits at the barrier
+// or for LDS the other feeds the matrix core.  Loads that prefetch past the end
+// re-read the last tile instead of branching, so the wait counters the compiler
+// places in front of the MFMAs never have to cover a conditional prefetch.
+//
+// Operand layout of v_mfma_f32_32x32x2_f32: see gemm_mfma.hip.
+#include "gemm.h"
+
+namespace ank {
+
+typedef float f16v_r __attribute__((ext_vector_type(16)));
+
+constexpr int RWG = 512;
+constexpr int RT = 32;                  // samples per LDS stage
+constexpr int NTR_LD = 256 + 4;         // row stride of the dY stage: eight rows cover all banks for 16-byte reads
+
+__device__ __forceinline__ f16v_r mfma_r(float a, float b, f16v_r c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+
+// ---------------------------------------------------------------------------
+// dX[m][i] = (x[m][i] > 0) * sum_j dY[m][j] W[i][j],  N = 256 (reduction), K a multiple of 256.
+// The order of the reduction is free: step 4p + e of lane half kg takes j = 8p + 4kg + e, so both
+// the resident weights and the LDS operand are fetched 16 bytes at a time.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const int rows_per_block)
+{
+    extern __shared__ float4 smem_r[];
+    float* As0 = reinterpret_cast<float*>(smem_r);
+    float* As1 = As0 + RT * NTR_LD;
+    constexpr int N = 256;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int i = blockIdx.y * 256 + wave * 32 + l32;               // this lane's output column
+    const int m_begin = blockIdx.x * rows_per_block;
+    const int m_end = m_begin + rows_per_block < a.M ? m_begin + rows_per_block : a.M;
+    if (m_begin >= a.M) return;
+    float wreg[128];
+#pragma unroll
+    for (int p = 0; p < 32; ++p) {
+        const float4 v = *reinterpret_cast<const float4*>(a.w + (size_t)i * N + 8 * p + 4 * kg);
+        wreg[4 * p] = v.x; wreg[4 * p + 1] = v.y; wreg[4 * p + 2] = v.z; wreg[4 * p + 3] = v.w;
+    }
+    // loader: 32 rows x 64 pieces of 16 B, four per thread: row 8q + tid/64, piece tid%64
+    const int lrow = tid >> 6, lc = (tid & 63) << 2;
+    const float* __restrict__ dyin = a.dy + lc;
+    const int m_clamp = m_end - 1;
+    float4 st[4];
+    auto fetch = [&](int m0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int m = m0 + 8 * q + lrow;
+            st[q] = *reinterpret_cast<const float4*>(dyin + (size_t)(m < m_end ? m : m_clamp) * N);   // rows past the end are never stored
+        }
+    };
+    auto store = [&](float* buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(buf + (8 * q + lrow) * NTR_LD + lc) = st[q];
+    };
+    fetch(m_begin);
+    store(As0);
+    __syncthreads();
+    const float* __restrict__ xin = a.x + i;
+    float* __restrict__ dxo = a.dx + i;
+    int t = 0;
+    for (int m0 = m_begin; m0 < m_end; m0 += RT, t ^= 1) {
+        const float* cur = t ? As1 : As0;
+        float* nxt = t ? As0 : As1;
+        fetch(m0 + RT < m_end ? m0 + RT : m0);                      // the last step re-reads its own rows
+        float xm[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + 8 * (r >> 2) + 4 * kg + (r & 3);
+            xm[r] = xin[(size_t)(m < m_end ? m : m_clamp) * a.K];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        f16v_r acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const float* a_rd = cur + l32 * NTR_LD + 4 * kg;
+#pragma unroll
+        for (int p = 0; p < 32; ++p) {
+            const float4 av = *reinterpret_cast<const float4*>(a_rd + 8 * p);
+            acc = mfma_r(av.x, wreg[4 * p], acc);
+            acc = mfma_r(av.y, wreg[4 * p + 1], acc);
+            acc = mfma_r(av.z, wreg[4 * p + 2], acc);
+            acc = mfma_r(av.w, wreg[4 * p + 3], acc);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + 8 * (r >> 2) + 4 * kg + (r & 3);
+            if (m < m_end) dxo[(size_t)m * a.K] = xm[r] > 0.0f ? acc[r] : 0.0f;
+        }
+        if (m0 + RT < m_end) store(nxt);
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// partial[s][i][j] = sum over the samples of chunk s of x[m][i] dY[m][j], K = N = 256, plus the
+// column sums of dY.  Wavefront (wm, wn) owns rows 128 wm.., columns 64 wn.. of the product.
+// a.rows is a multiple of 32.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
+{
+    extern __shared__ float4 smem_r[];
+    float* Xs = reinterpret_cast<float*>(smem_r);                    // [2][32][256]
+    float* Ys = Xs + 2 * RT * 256;                                   // [2][32][256]
+    constexpr int K = 256, N = 256;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int split = blockIdx.x;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    const int lrow = tid >> 6, lc = (tid & 63) << 2;
+    const float* __restrict__ xin = a.x + lc;
+    const float* __restrict__ yin = a.dy + lc;
+    float4 sx[4], sy[4];
+    float4 bsum = make_float4(0, 0, 0, 0);
+    auto fetch = [&](int m0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int m = m0 + 8 * q + lrow;
+            sx[q] = *reinterpret_cast<const float4*>(xin + (size_t)m * K);
+            sy[q] = *reinterpret_cast<const float4*>(yin + (size_t)m * a.ldy);
+        }
+    };
+    auto store = [&](int b) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            *reinterpret_cast<float4*>(Xs + (b * RT + 8 * q + lrow) * 256 + lc) = sx[q];
+            *reinterpret_cast<float4*>(Ys + (b * RT + 8 * q + lrow) * 256 + lc) = sy[q];
+            bsum.x += sy[q].x; bsum.y += sy[q].y; bsum.z += sy[q].z; bsum.w += sy[q].w;
+        }
+    };
+    fetch(m_begin);
+    store(0);
+    __syncthreads();
+    f16v_r acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    int t = 0;
+    for (int m0 = m_begin; m0 < m_end; m0 += RT, t ^= 1) {
+        fetch(m0 + RT < m_end ? m0 + RT : m0);                      // the last step re-reads its own rows, unused
+        __builtin_amdgcn_sched_barrier(0);
+        const float* xs = Xs + t * RT * 256 + wm * 128 + l32;
+        const float* ys = Ys + t * RT * 256 + wn * 64 + l32;
+#pragma unroll
+        for (int ks = 0; ks < RT; ks += 2) {
+            const int k = ks + kg;
+            float av[4], bv[2];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) av[q] = xs[k * 256 + 32 * q];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) bv[q] = ys[k * 256 + 32 * q];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_r(av[i], bv[j], acc[i][j]);
+        }
+        if (m0 + RT < m_end) store(t ^ 1);
+        __syncthreads();
+    }
+    float* out = a.partial + (size_t)split * ((size_t)K * N + N);
+#pragma unroll
+    for (int tr = 0; tr < 4; ++tr)
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc) {
+            const int j = wn * 64 + tc * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = wm * 128 + tr * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+                out[(size_t)i * N + j] = acc[tr][tc][r];
+            }
+        }
+    // column sums: the eight loader rows of a column add up in ascending order
+    float* red = Xs;                                                 // [8][256]
+    *reinterpret_cast<float4*>(red + lrow * 256 + lc) = bsum;
+    __syncthreads();
+    if (tid < 256) {
+        float s = 0.0f;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) s += red[g * 256 + tid];
+        out[(size_t)K * N + tid] = s;
+    }
+}
+
+bool gemm_nt_res_ok(const GemmNtArgs& a) { return a.N == 256 && a.K % 256 == 0 && a.M >= 1; }
+bool gemm_tn_res_ok(const GemmTnArgs& a) { return a.K == 256 && a.N == 256 && !a.use_obs && a.rows % RT == 0 && a.ldy % 4 == 0; }
+
+hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s)
+{
+    const int tiles = (a.M + RT - 1) / RT;
+    const int blocks = tiles < 256 ? tiles : 256;
+    const int rows_per_block = ((tiles + blocks - 1) / blocks) * RT;
+    const size_t lds = (size_t)2 * RT * NTR_LD * sizeof(float);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_res256), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gemm_nt_res256, dim3((a.M + rows_per_block - 1) / rows_per_block, a.K / 256), dim3(RWG), lds, s, a, rows_per_block);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s)
+{
+    const size_t lds = (size_t)4 * RT * 256 * sizeof(float);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_res256), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gemm_tn_res256, dim3(a.splits), dim3(RWG), lds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace ank
