@@ -24,6 +24,7 @@
 namespace ank {
 
 typedef float f16v_r __attribute__((ext_vector_type(16)));
+typedef float f4v_r __attribute__((ext_vector_type(4)));
 
 constexpr int RWG = 512;
 constexpr int RT = 32;                  // samples per LDS stage
@@ -54,36 +55,36 @@ __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const 
         wreg[4 * p] = v.x; wreg[4 * p + 1] = v.y; wreg[4 * p + 2] = v.z; wreg[4 * p + 3] = v.w;
     }
     // loader: 32 rows x 64 pieces of 16 B, four per thread: row 8q + tid/64, piece tid%64
-    const int lrow = tid >> 6, lc = (tid & 63) << 2;
-    const float* __restrict__ dyin = a.dy + lc;
+    const int lrow = __builtin_amdgcn_readfirstlane(tid >> 6), lc = (tid & 63) << 2;
     const int m_clamp = m_end - 1;
-    float4 st[4];
+    f4v_r st[4];
     auto fetch = [&](int m0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int m = m0 + 8 * q + lrow;
-            st[q] = *reinterpret_cast<const float4*>(dyin + (size_t)(m < m_end ? m : m_clamp) * N);   // rows past the end are never stored
+            const int m = m0 + 8 * q + lrow;                                                          // uniform in a wavefront
+            st[q] = *reinterpret_cast<const f4v_r*>(a.dy + (size_t)(m < m_end ? m : m_clamp) * N + lc);   // rows past the end are never used
         }
     };
     auto store = [&](float* buf) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(buf + (8 * q + lrow) * NTR_LD + lc) = st[q];
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<f4v_r*>(buf + (8 * q + lrow) * NTR_LD + lc) = st[q];
     };
     fetch(m_begin);
     store(As0);
     __syncthreads();
-    const float* __restrict__ xin = a.x + i;
-    float* __restrict__ dxo = a.dx + i;
+    const uint32_t lane_off = (uint32_t)(4 * kg) * (uint32_t)a.K + (uint32_t)i;
     int t = 0;
     for (int m0 = m_begin; m0 < m_end; m0 += RT, t ^= 1) {
         const float* cur = t ? As1 : As0;
         float* nxt = t ? As0 : As1;
         fetch(m0 + RT < m_end ? m0 + RT : m0);                      // the last step re-reads its own rows
+        // rows come in whole groups of eight (M and the rows per workgroup are multiples of 8), so the row
+        // part of every address and every bounds check is uniform: scalar base + one 32-bit lane offset
         float xm[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int m = m0 + 8 * (r >> 2) + 4 * kg + (r & 3);
-            xm[r] = xin[(size_t)(m < m_end ? m : m_clamp) * a.K];
+            const int mu = m0 + 8 * (r >> 2) + (r & 3);
+            xm[r] = (a.x + (size_t)(mu < m_end ? mu : m_begin) * a.K)[lane_off];
         }
         __builtin_amdgcn_sched_barrier(0);
         f16v_r acc;
@@ -100,8 +101,8 @@ __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const 
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int m = m0 + 8 * (r >> 2) + 4 * kg + (r & 3);
-            if (m < m_end) dxo[(size_t)m * a.K] = xm[r] > 0.0f ? acc[r] : 0.0f;
+            const int mu = m0 + 8 * (r >> 2) + (r & 3);
+            if (mu < m_end) (a.dx + (size_t)mu * a.K)[lane_off] = xm[r] > 0.0f ? acc[r] : 0.0f;
         }
         if (m0 + RT < m_end) store(nxt);
         __syncthreads();
@@ -123,25 +124,23 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
     const int wm = wave >> 2, wn = wave & 3;
     const int split = blockIdx.x;
     const int m_begin = split * a.rows, m_end = m_begin + a.rows;
-    const int lrow = tid >> 6, lc = (tid & 63) << 2;
-    const float* __restrict__ xin = a.x + lc;
-    const float* __restrict__ yin = a.dy + lc;
-    float4 sx[4], sy[4];
-    float4 bsum = make_float4(0, 0, 0, 0);
+    const int lrow = __builtin_amdgcn_readfirstlane(tid >> 6), lc = (tid & 63) << 2;
+    f4v_r sx[4], sy[4];
+    f4v_r bsum = {0.0f, 0.0f, 0.0f, 0.0f};
     auto fetch = [&](int m0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int m = m0 + 8 * q + lrow;
-            sx[q] = *reinterpret_cast<const float4*>(xin + (size_t)m * K);
-            sy[q] = *reinterpret_cast<const float4*>(yin + (size_t)m * a.ldy);
+            const int m = m0 + 8 * q + lrow;                                                          // uniform in a wavefront
+            sx[q] = *reinterpret_cast<const f4v_r*>(a.x + (size_t)m * K + lc);
+            sy[q] = *reinterpret_cast<const f4v_r*>(a.dy + (size_t)m * a.ldy + lc);
         }
     };
     auto store = [&](int b) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            *reinterpret_cast<float4*>(Xs + (b * RT + 8 * q + lrow) * 256 + lc) = sx[q];
-            *reinterpret_cast<float4*>(Ys + (b * RT + 8 * q + lrow) * 256 + lc) = sy[q];
-            bsum.x += sy[q].x; bsum.y += sy[q].y; bsum.z += sy[q].z; bsum.w += sy[q].w;
+            *reinterpret_cast<f4v_r*>(Xs + (b * RT + 8 * q + lrow) * 256 + lc) = sx[q];
+            *reinterpret_cast<f4v_r*>(Ys + (b * RT + 8 * q + lrow) * 256 + lc) = sy[q];
+            bsum += sy[q];
         }
     };
     fetch(m_begin);
@@ -190,7 +189,7 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
         }
     // column sums: the eight loader rows of a column add up in ascending order
     float* red = Xs;                                                 // [8][256]
-    *reinterpret_cast<float4*>(red + lrow * 256 + lc) = bsum;
+    *reinterpret_cast<f4v_r*>(red + lrow * 256 + lc) = bsum;
     __syncthreads();
     if (tid < 256) {
         float s = 0.0f;
@@ -200,7 +199,7 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
     }
 }
 
-bool gemm_nt_res_ok(const GemmNtArgs& a) { return a.N == 256 && a.K % 256 == 0 && a.M >= 1; }
+bool gemm_nt_res_ok(const GemmNtArgs& a) { return a.N == 256 && a.K % 256 == 0 && a.M >= 8 && a.M % 8 == 0; }
 bool gemm_tn_res_ok(const GemmTnArgs& a) { return a.K == 256 && a.N == 256 && !a.use_obs && a.rows % RT == 0 && a.ldy % 4 == 0; }
 
 hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s)
