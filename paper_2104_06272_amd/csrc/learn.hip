@@ -420,6 +420,44 @@ __global__ __launch_bounds__(WG) void first_layer_grad(const FirstGradArgs a)
     }
 }
 
+// Pendulum first layer for widths that are multiples of 256: the three observation features of a
+// row (cos, sin, angular velocity) are computed once per row by one thread and shared through LDS,
+// instead of once per row by every column; lane j then walks the rows in ascending order.
+__global__ __launch_bounds__(WG) void first_layer_grad_pendulum(const FirstGradArgs a)
+{
+    __shared__ float feat[3][WG];
+    const int N = a.N;
+    const int j = blockIdx.y * WG + threadIdx.x;
+    const int split = blockIdx.x;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    float bsum = 0.0f, r0 = 0.0f, r1 = 0.0f, r2 = 0.0f;
+    const float* __restrict__ dy = a.dy + j;
+    for (int mb = m_begin; mb < m_end; mb += WG) {
+        const int m = mb + threadIdx.x;
+        float sn = 0.0f, cs = 0.0f, td = 0.0f;
+        if (m < m_end) { det_sincos(a.obs.f0[m], sn, cs); td = a.obs.f1[m]; }
+        __syncthreads();                                     // the previous batch has been consumed
+        feat[0][threadIdx.x] = cs; feat[1][threadIdx.x] = sn; feat[2][threadIdx.x] = td;
+        __syncthreads();
+        const int n = m_end - mb < WG ? m_end - mb : WG;
+        constexpr int RB = 16;
+        for (int u0 = 0; u0 < n; u0 += RB) {
+            float d[RB];
+#pragma unroll
+            for (int u = 0; u < RB; ++u) d[u] = u0 + u < n ? dy[(size_t)(mb + u0 + u) * N] : 0.0f;
+#pragma unroll
+            for (int u = 0; u < RB; ++u) {
+                if (u0 + u >= n) break;
+                bsum += d[u];
+                r0 = fmaf(feat[0][u0 + u], d[u], r0); r1 = fmaf(feat[1][u0 + u], d[u], r1); r2 = fmaf(feat[2][u0 + u], d[u], r2);
+            }
+        }
+    }
+    float* out = a.partial + (size_t)split * ((size_t)a.K * N + N);
+    out[j] = r0; out[(size_t)N + j] = r1; out[(size_t)2 * N + j] = r2;
+    out[(size_t)a.K * N + j] = bsum;
+}
+
 // The same scatter on the matrix cores for boards of at most 63 cells: dW1 = X^T dZ1 with the 0/1
 // board rebuilt from the state word, v_mfma_f32_32x32x2_f32 taking two samples per step.  Row K of
 // the padded board is all ones, so the column sums (the bias gradient) fall out of the same product
@@ -513,6 +551,8 @@ hipError_t launch_first_layer_grad(anakin* h)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, dim3(WG), lds, h->stream, a);
+    } else if (a.N % WG == 0 && a.K == 3) {
+        hipLaunchKernelGGL(first_layer_grad_pendulum, dim3(h->splits[0], a.N / WG), dim3(WG), 0, h->stream, a);
     } else {
         hipLaunchKernelGGL(first_layer_grad<ENV_PENDULUM>, grid, dim3(WG), lds, h->stream, a);
     }
