@@ -73,6 +73,16 @@ def kernel_models(cfg, P):
     models["gemm_tn"] = ("mfma", tn / 1e12, mfma_peak, "TFLOP/s")
     models["gemm_nt_mask"] = ("mfma", nt / 1e12, mfma_peak, "TFLOP/s")
     models["gemm_tn_obs"] = ("mfma", 2.0 * dims[0] * dims[1] * M / 1e12, mfma_peak, "TFLOP/s")
+    if kind == "maze":
+        cells = cfg["env"]["rows"] * cfg["env"]["cols"]
+        # first layer of a bf16 maze net, reduced plane by plane: time sum of dZ1 (one read, B rows written twice),
+        # wall plane over 2B time-summed samples, agent plane over all samples
+        models["time_sum"] = ("hbm", (2.0 * dims[1] * M + 4.0 * dims[1] * B) / 1e9, PEAK_HBM_GBS, "GB/s")
+        models["gemm_tn_walls"] = ("mfma", 2.0 * cells * dims[1] * 2 * B / 1e12, mfma_peak, "TFLOP/s")
+        models["gemm_tn_agent"] = ("mfma", 2.0 * cells * dims[1] * M / 1e12, mfma_peak, "TFLOP/s")
+    if len(hid) == 1:
+        # fused update of a one-hidden-layer net: reads state, head gradient and returns, rebuilds the layer
+        models["learn_one_layer"] = ("alu", 2.0 * (2 * first_rows * dims[1] + 3 * dims[1] * NH) * M / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s")
     return models, snap
 
 

@@ -302,6 +302,104 @@ __global__ __launch_bounds__(WG) void gemm_nt_bf16(const GemmNtBf16Args a)
 }
 
 // ---------------------------------------------------------------------------
+// The same product as one persistent workgroup per compute unit with the weights in registers:
+// wavefront w of eight keeps the 32 output columns 32w.. of a 256-column block of W (NR/4
+// registers per lane, the B operand of every step), dY streams through LDS 32 rows at a time,
+// double buffered, and nothing but dY, the mask and the result crosses the memory system.  The
+// kernel is HBM-bound by design: about 5 bytes per output element.  NR: reduction length N (256 or
+// 512); K a multiple of 256; M a multiple of 32.
+// ---------------------------------------------------------------------------
+typedef uint32_t u32x4_l __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_l __attribute__((ext_vector_type(2)));
+constexpr int NRES_WG = 512;
+constexpr int NRES_RT = 32;             // rows per stage
+constexpr int NRES_LDT = 256 + 8;       // staging rows of the row-major copy
+
+template <int NR>
+__global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args a, const int rows_per_block)
+{
+    constexpr int LD = NR + 8;                                   // row stride in bf16: eight rows cover all banks
+    constexpr int KS = NR / 16;                                  // MFMA steps
+    constexpr int PPR = NR / 8;                                  // 16-byte pieces per row
+    constexpr int RPP = NRES_WG / PPR;                           // rows per loader pass
+    constexpr int NQ = NRES_RT / RPP;                            // loader passes per stage
+    extern __shared__ uint4 smem4[];
+    uint16_t* As0 = reinterpret_cast<uint16_t*>(smem4);
+    uint16_t* As1 = As0 + NRES_RT * LD;
+    uint16_t* Ts0 = As1 + NRES_RT * LD;
+    uint16_t* Ts1 = Ts0 + NRES_RT * NRES_LDT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    int rb_, cb_;
+    xcd_map((int)blockIdx.x, (a.M + rows_per_block - 1) / rows_per_block, a.K / 256, rb_, cb_);   // column blocks of the same rows share dY in one L2
+    const int i0 = cb_ * 256;
+    const int i = i0 + wave * 32 + l32;                          // this lane's output column
+    const int m_begin = rb_ * rows_per_block;
+    const int m_end = m_begin + rows_per_block < a.M ? m_begin + rows_per_block : a.M;
+    if (m_begin >= a.M) return;
+    bf8 wreg[KS];
+#pragma unroll
+    for (int s2 = 0; s2 < KS; ++s2) wreg[s2] = *reinterpret_cast<const bf8*>(a.w16 + (size_t)i * NR + 16 * s2 + 8 * kg);
+    // loader: row RPP*q + tid/PPR (uniform in a wavefront when PPR >= 64), piece tid%PPR
+    const int lrow = tid / PPR, lc = (tid % PPR) * 8;
+    u32x4_l st[NQ];
+    auto fetch = [&](int m0) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) st[q] = *reinterpret_cast<const u32x4_l*>(a.dyR + (size_t)(m0 + RPP * q + lrow) * NR + lc);
+    };
+    auto store = [&](uint16_t* buf) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) *reinterpret_cast<u32x4_l*>(buf + (RPP * q + lrow) * LD + lc) = st[q];
+    };
+    fetch(m_begin);
+    store(As0);
+    __syncthreads();
+    const uint32_t lane_off = (uint32_t)i * 8u + 4u * kg;        // inside a packed group of eight samples
+    const int cl = wave * 32 + l32;                              // column inside the 256-column block
+    int t = 0;
+    for (int m0 = m_begin; m0 < m_end; m0 += NRES_RT, t ^= 1) {
+        const uint16_t* cur = t ? As1 : As0;
+        uint16_t* nxt = t ? As0 : As1;
+        uint16_t* Ts = t ? Ts1 : Ts0;
+        fetch(m0 + NRES_RT < m_end ? m0 + NRES_RT : m0);        // the last step re-reads its own rows, unused
+        u32x2_l mask[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            mask[g] = *reinterpret_cast<const u32x2_l*>(a.hP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off);
+        __builtin_amdgcn_sched_barrier(0);
+        f16v acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const uint16_t* a_rd = cur + l32 * LD + 8 * kg;
+#pragma unroll
+        for (int s2 = 0; s2 < KS; ++s2) acc = mfma_bf16(*reinterpret_cast<const bf8*>(a_rd + 16 * s2), wreg[s2], acc);
+        // rows 8g + 4kg + q of the stage, column i: half of one packed group per g
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float hv = bfu((uint16_t)((mask[g][q >> 1] >> ((q & 1) * 16)) & 0xffffu));
+                o[q] = hv > 0.0f ? acc[4 * g + q] : 0.0f;
+            }
+            const uint32_t p01 = cvt_pk_bf16(o[0], o[1]), p23 = cvt_pk_bf16(o[2], o[3]);
+            const int rowl = 8 * g + 4 * kg;
+            Ts[(rowl + 0) * NRES_LDT + cl] = (uint16_t)p01; Ts[(rowl + 1) * NRES_LDT + cl] = (uint16_t)(p01 >> 16);
+            Ts[(rowl + 2) * NRES_LDT + cl] = (uint16_t)p23; Ts[(rowl + 3) * NRES_LDT + cl] = (uint16_t)(p23 >> 16);
+            u32x2_l pv; pv[0] = p01; pv[1] = p23;
+            *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
+        }
+        if (m0 + NRES_RT < m_end) store(nxt);
+        __syncthreads();
+        // row-major copy of this stage: 32 rows x 256 columns, two 16-byte pieces per thread
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int p = q * NRES_WG + tid, row = p >> 5, c = (p & 31) << 3;
+            *reinterpret_cast<u32x4_l*>(a.dxR + (size_t)(m0 + row) * a.K + i0 + c) = *reinterpret_cast<const u32x4_l*>(Ts + row * NRES_LDT + c);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // dW partials from packed operands.  LDS tiles [sample group][column][8]; every
 // operand is one 16-byte read.  OBS: the first layer's x comes from the state
 // snapshots (walls bit planes, agent cell, goal cell / Catch cells).
@@ -704,11 +802,25 @@ hipError_t launch_backward_bf16(anakin* h)
             g.w16 = at<const uint16_t>(h, L.w_bf16) + n.w_off[l];
             g.hP = actP(l - 1);
             g.dxR = dzR(l - 1); g.dxP = dzP(l - 1);
-            const size_t lds2 = (size_t)2 * 128 * NB_LD * sizeof(uint16_t);
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_bf16), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-            if (e != hipSuccess) return e;
+            const bool res = (g.N == 256 || g.N == 512) && g.K % 256 == 0 && g.M % NRES_RT == 0;
             ProfScope prof(h, "gemm_nt_mask");
-            hipLaunchKernelGGL(gemm_nt_bf16, dim3(((g.M + 127) / 128) * ((g.K + 127) / 128)), dim3(WG), lds2, h->stream, g);
+            if (res) {
+                const int tiles = g.M / NRES_RT;
+                const int blocks = tiles < 256 ? tiles : 256;
+                const int rows_per_block = ((tiles + blocks - 1) / blocks) * NRES_RT;
+                const size_t lds2 = ((size_t)2 * NRES_RT * (g.N + 8) + (size_t)2 * NRES_RT * NRES_LDT) * sizeof(uint16_t);
+                const void* fn = g.N == 512 ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256>);
+                e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+                if (e != hipSuccess) return e;
+                const dim3 grid(((g.M + rows_per_block - 1) / rows_per_block) * (g.K / 256));
+                if (g.N == 512) hipLaunchKernelGGL(gemm_nt_bf16_res<512>, grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else hipLaunchKernelGGL(gemm_nt_bf16_res<256>, grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+            } else {
+                const size_t lds2 = (size_t)2 * 128 * NB_LD * sizeof(uint16_t);
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_bf16), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(gemm_nt_bf16, dim3(((g.M + 127) / 128) * ((g.K + 127) / 128)), dim3(WG), lds2, h->stream, g);
+            }
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
     }
