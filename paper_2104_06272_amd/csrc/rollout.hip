@@ -379,6 +379,39 @@ __device__ __forceinline__ float heads_fma(const float4 (&xv)[U], const float4 (
     return acc;
 }
 // U: float4 per register block (a block covers 4U values of k; HL is a multiple of 4U)
+// The same chains on the matrix cores for tiles of 16 envs: v_mfma_f32_16x16x4_f32 adds its four
+// products to the accumulator in ascending k, and chained instructions continue the same chain, so
+// 64 of them starting from the bias reproduce acc = fmaf(x_k, w_k, acc), k = 0..255, bit for bit --
+// at four steps per instruction instead of one dependent fma per step.  Lane l feeds
+// A[env l%16][k l/16] and B[k l/16][head l%16]; accumulator register r is D[env 4*(l/16) + r][head l%16].
+// Wavefront w takes envs 16w..16w+15; heads beyond NH are zero columns.
+typedef float f4v_h __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void heads_mfma16(const float* __restrict__ X, int ldx, const float* __restrict__ whT, int ldw,
+                                             const float* __restrict__ bhs, float* __restrict__ heads,
+                                             int HL, int NH, int NHP, int TM, int tid)
+{
+    const int wave = tid >> 6, lane = tid & 63;
+    if (wave * 16 >= TM) return;
+    const int c16 = lane & 15, kq = lane >> 4;
+    const bool real = c16 < NH;
+    const float* x = X + (wave * 16 + c16) * ldx + kq;
+    const float* w = whT + (real ? c16 : 0) * ldw + kq;
+    const float b = real ? bhs[c16] : 0.0f;
+    f4v_h acc = {b, b, b, b};
+    constexpr int UB = 16;                                      // steps per block of operand loads
+    for (int s0 = 0; s0 < HL; s0 += 4 * UB) {
+        float xv[UB], wv[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) { xv[u] = x[s0 + 4 * u]; wv[u] = real ? w[s0 + 4 * u] : 0.0f; }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xv[u], wv[u], acc, 0, 0, 0);
+    }
+    if (real) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) heads[(wave * 16 + 4 * kq + r) * NHP + c16] = acc[r];
+    }
+}
+
 template <int U>
 __device__ __forceinline__ void heads_chain(const float* __restrict__ X, int ldx, const float* __restrict__ whT, int ldw,
                                             const float* __restrict__ bhs, float* __restrict__ heads,
@@ -728,7 +761,8 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         else resident_m16<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
         __syncthreads();
         PH(2);
-        heads_chain<(RK * RN >= 256 * 256 ? 2 : 8)>(bufB, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
+        if (TM % 16 == 0 && HL % 64 == 0) heads_mfma16(bufB, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
+        else heads_chain<(RK * RN >= 256 * 256 ? 2 : 8)>(bufB, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
         if (t < T) {
