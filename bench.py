@@ -26,15 +26,21 @@ PEAK_FP32_TFLOPS = 157.3      # fp32 vector (packed) = fp32 matrix-core peak
 PEAK_BF16_TFLOPS = 2500.0
 
 # HBM bytes per launch (MB) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy-kernel calibration; source: profiles/catch_4096_hbm_traffic.md.  Reported as roofline.traffic
-# when the dominant kernel of the benchmarked workload is listed.
+# copy-kernel calibration; source: profiles/catch_4096_hbm_traffic.md and profiles/maze_16384_hbm_traffic.md.
+# Reported as roofline.traffic when the dominant kernel of the benchmarked workload is listed.
 MEASURED_TRAFFIC_MB = {
     ("catch_4096", "rollout"): 173.3,
-    ("catch_4096", "gemm_nt_mask"): 341.7,
-    ("catch_4096", "gemm_tn"): 377.8,
-    ("catch_4096", "head_backward"): 180.0,
-    ("catch_4096", "first_layer_grad"): 101.0,
-    ("catch_4096", "adam_reduce"): 62.1,
+    ("catch_4096", "gemm_nt_mask"): 254.5,
+    ("catch_4096", "gemm_tn"): 235.3,
+    ("catch_4096", "head_backward"): 174.6,
+    ("catch_4096", "first_layer_grad"): 97.8,
+    ("catch_4096", "adam_reduce"): 84.0,
+    ("maze_16384", "rollout"): 2053.7,
+    ("maze_16384", "gemm_nt_mask"): 2155.9,
+    ("maze_16384", "gemm_tn"): 1257.1,
+    ("maze_16384", "head_backward"): 1687.0,
+    ("maze_16384", "time_sum"): 570.4,
+    ("maze_16384", "adam_reduce"): 268.7,
 }
 
 
