@@ -52,6 +52,9 @@ LOCKSTEP_CASES = {
     "maze_fp32_small": (variant("maze_16384", hidden=[64, 64], B=64, T=32, dtype="fp32", max_steps=20), 1, 3, TOL_F32),
     "maze_bf16_canonical": (variant("maze_16384", hidden=[64, 64, 32], B=64, T=16, max_steps=40), 3, 2, TOL_BF16),
     "maze_fp32_8x8": (variant("maze_16384", hidden=[32], B=32, T=24, dtype="fp32", rows=8, cols=8, max_steps=30), 0, 2, TOL_F32),
+    # 512 -> 256: the weights-resident dX kernel with two column blocks, tiled dW; three 256-wide layers: resident both ways
+    "catch_512x256": (variant("catch_4096", hidden=[512, 256], B=64, T=10), 3, 2, TOL_F32),
+    "catch_256x256x256": (variant("catch_4096", hidden=[256, 256, 256], B=96, T=9), 4, 2, TOL_F32),
 }
 
 
@@ -171,6 +174,8 @@ BF16_CASES = {
     "maze_bf16_256_512": (variant("maze_16384", hidden=[256, 512], B=128, T=8, rows=8, cols=8, max_steps=20), 1, 2),
     # 16x16 maze with 256-wide layers: 256 x 256 GEMM tiles and the first layer reduced plane by plane
     "maze_bf16_16x16_256": (variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20), 4, 2),
+    # the benchmark's layer widths at a size the oracle can follow: every 512-wide update kernel
+    "maze_bf16_16x16_512": (variant("maze_16384", B=64, T=8, max_steps=20), 5, 1),
     "catch_bf16_128": (variant("catch_4096", hidden=[128, 128], B=64, T=12, dtype="bf16"), 0, 2),
     "pendulum_bf16_128": (variant("pendulum_8192", hidden=[128, 128], B=64, T=10, dtype="bf16", max_steps=7), 2, 2),
 }
