@@ -552,12 +552,18 @@ __global__ __launch_bounds__(WG) void gemm_tn_bf16(const GemmTnBf16Args a)
 constexpr int BIGWG = 512;
 constexpr int TB_BG = 8;      // sample groups (of 8) per LDS stage: 64 samples
 
-template <bool OBS>
+// XMODE: where the X operand comes from.  0: packed activations in HBM; 1: the agent plane of the
+// maze observation, a one-hot of the agent cell, built from the stage's 64 cell indices which pass
+// through LDS one stage ahead; 2: any observation rows, rebuilt piece by piece (obs_piece).
+// Two register sets hold the next two stages while the current one is multiplied, so every load
+// has two MFMA phases to arrive.  Chunks are whole stages of 64 samples (a.rows % 64 == 0).
+template <int XMODE>
 __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a)
 {
     extern __shared__ uint4 smem4[];
     uint4* Xs = smem4;                       // [TB_BG][256] pieces of 8 samples
     uint4* Ys = Xs + TB_BG * 256;
+    __shared__ uint32_t posL[2][64];         // XMODE 1: agent cells of the 64 samples of a stage, double buffered
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, kg = lane >> 5;
     int split, tile;
@@ -565,20 +571,51 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
     const int ti = tile % a.tiles_i, tj = tile / a.tiles_i;
     const int i0 = ti * 256, j0 = tj * 256;
     const int g_begin = (split * a.rows) >> 3, g_end = g_begin + (a.rows >> 3);
+    const int g_last = g_end - TB_BG;                            // first group of the last stage
     // loader: thread = (column, parity of the sample group), four groups of the stage each
     const int lc = tid & 255, lg = tid >> 8;
-    uint4 rx[TB_BG / 2], ry[TB_BG / 2];
-    auto fetch = [&](int g0) {
+    struct Set { u32x4_l x[TB_BG / 2]; u32x4_l y[TB_BG / 2]; uint32_t pos; };
+    Set S0, S1;
+    auto fetch = [&](Set& st, int g0) {
+        if (g0 > g_last) g0 = g_last;                            // past the end: re-read the last stage, never used
 #pragma unroll
         for (int q = 0; q < TB_BG / 2; ++q) {
             const int g = g0 + 2 * q + lg;
-            const bool gok = g < g_end;
-            if (OBS) rx[q] = gok ? obs_piece(a.obs, g, a.obs_row0 + i0 + lc, true) : make_uint4(0, 0, 0, 0);
-            else rx[q] = gok ? *reinterpret_cast<const uint4*>(a.xP + ((size_t)g * a.K + i0 + lc) * 8) : make_uint4(0, 0, 0, 0);
-            ry[q] = gok ? *reinterpret_cast<const uint4*>(a.dyP + ((size_t)g * a.N + j0 + lc) * 8) : make_uint4(0, 0, 0, 0);
+            if (XMODE == 0) st.x[q] = *reinterpret_cast<const u32x4_l*>(a.xP + ((size_t)g * a.K + i0 + lc) * 8);
+            st.y[q] = *reinterpret_cast<const u32x4_l*>(a.dyP + ((size_t)g * a.N + j0 + lc) * 8);
+        }
+        if (XMODE == 1) st.pos = a.obs.s0[(size_t)g0 * 8 + (tid & 63)] & 0xffffu;
+    };
+    float bsum = 0.0f;
+    const bool sums = ti == 0 && a.bias_out != nullptr;
+    const int cell = a.obs_row0 + i0 + lc - a.obs.env.rows * a.obs.env.cols;   // XMODE 1: the cell this thread's row stands for
+    // stage -> LDS; pb: parity of the stage (selects the cell buffer)
+    auto store = [&](const Set& st, int g0, int pb) {
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q) {
+            const int gl = 2 * q + lg;
+            u32x4_l x;
+            if (XMODE == 0) x = st.x[q];
+            else if (XMODE == 1) {
+                const u32x4_l p0 = *reinterpret_cast<const u32x4_l*>(&posL[pb][gl * 8]);
+                const u32x4_l p1 = *reinterpret_cast<const u32x4_l*>(&posL[pb][gl * 8 + 4]);
+                const uint32_t one = 0x3f80u;
+                x[0] = ((int)p0[0] == cell ? one : 0u) | ((int)p0[1] == cell ? one << 16 : 0u);
+                x[1] = ((int)p0[2] == cell ? one : 0u) | ((int)p0[3] == cell ? one << 16 : 0u);
+                x[2] = ((int)p1[0] == cell ? one : 0u) | ((int)p1[1] == cell ? one << 16 : 0u);
+                x[3] = ((int)p1[2] == cell ? one : 0u) | ((int)p1[3] == cell ? one << 16 : 0u);
+            } else {
+                const uint4 v = obs_piece(a.obs, g0 + gl, a.obs_row0 + i0 + lc, true);
+                x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+            }
+            *reinterpret_cast<u32x4_l*>(&Xs[gl * 256 + lc]) = x;
+            *reinterpret_cast<u32x4_l*>(&Ys[gl * 256 + lc]) = st.y[q];
+            if (sums) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bsum += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
+            }
         }
     };
-    fetch(g_begin);
     f16v acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -586,40 +623,40 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    float bsum = 0.0f;
-    const bool sums = ti == 0 && a.bias_out != nullptr;
-    for (int g0 = g_begin; g0 < g_end; g0 += TB_BG) {
-#pragma unroll
-        for (int q = 0; q < TB_BG / 2; ++q) { Xs[(2 * q + lg) * 256 + lc] = rx[q]; Ys[(2 * q + lg) * 256 + lc] = ry[q]; }
-        __syncthreads();
-        if (sums) {
-#pragma unroll
-            for (int q = 0; q < TB_BG / 2; ++q) {
-                const uint32_t yw[4] = {ry[q].x, ry[q].y, ry[q].z, ry[q].w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bsum += bfu((uint16_t)((yw[e >> 1] >> ((e & 1) * 16)) & 0xffffu));
-            }
-        }
-        if (g0 + TB_BG < g_end) fetch(g0 + TB_BG);
+    auto compute = [&]() {
 #pragma unroll
         for (int ks = 0; ks < TB_BG; ks += 2) {                  // one MFMA step = 16 samples = 2 groups
             bf8 av[4], bv[2];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const uint4 x = Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32];
-                av[t] = *reinterpret_cast<const bf8*>(&x);
-            }
+            for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const uint4 y = Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32];
-                bv[t] = *reinterpret_cast<const bf8*>(&y);
-            }
+            for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
         }
+    };
+    // one pipeline step: stage g0 (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage
+    // g0 + 2 stages; the cells of stage g0 + 1 stage (held in `nxt`) go to the other cell buffer
+    auto step = [&](Set& cur, const Set& nxt, int g0, int pb) {
+        store(cur, g0, pb);
+        if (XMODE == 1 && tid < 64) posL[pb ^ 1][tid] = nxt.pos;
         __syncthreads();
+        fetch(cur, g0 + 2 * TB_BG);
+        __builtin_amdgcn_sched_barrier(0);
+        compute();
+        __syncthreads();
+    };
+    fetch(S0, g_begin);
+    fetch(S1, g_begin + TB_BG);
+    if (XMODE == 1) {
+        if (tid < 64) posL[0][tid] = S0.pos;
+        __syncthreads();
+    }
+    for (int g0 = g_begin; g0 < g_end; g0 += 2 * TB_BG) {
+        step(S0, S1, g0, 0);
+        if (g0 + TB_BG < g_end) step(S1, S0, g0 + TB_BG, 1);
     }
     float* out = a.partial + (size_t)split * a.split_stride;
 #pragma unroll
@@ -744,14 +781,19 @@ hipError_t launch_backward_bf16(anakin* h)
         const int tiles = t.tiles_i * ((t.N + tile - 1) / tile);
         const dim3 grid = big ? dim3(tiles * t.splits) : dim3(tiles, t.splits);
         const size_t lds = (size_t)2 * (big ? TB_BG * 256 : TB_G * 128) * sizeof(uint4);
-        const void* fn = big ? (t.use_obs ? reinterpret_cast<const void*>(gemm_tn_bf16_big<true>) : reinterpret_cast<const void*>(gemm_tn_bf16_big<false>))
+        // X operand of the 256-tile kernel: packed activations, the agent plane (one-hot of the cell), or generic rows
+        const int cells = h->env.rows * h->env.cols;
+        const int xmode = !t.use_obs ? 0 : (h->env.kind == ENV_MAZE && t.obs_row0 == cells && t.K == cells) ? 1 : 2;
+        const void* fn = big ? (xmode == 0 ? reinterpret_cast<const void*>(gemm_tn_bf16_big<0>) : xmode == 1 ? reinterpret_cast<const void*>(gemm_tn_bf16_big<1>)
+                                                                                                              : reinterpret_cast<const void*>(gemm_tn_bf16_big<2>))
                              : (t.use_obs ? reinterpret_cast<const void*>(gemm_tn_bf16<true>) : reinterpret_cast<const void*>(gemm_tn_bf16<false>));
         hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e2 != hipSuccess) return e2;
         ProfScope prof(h, name);
         if (big) {
-            if (t.use_obs) hipLaunchKernelGGL(gemm_tn_bf16_big<true>, grid, dim3(BIGWG), lds, h->stream, t);
-            else hipLaunchKernelGGL(gemm_tn_bf16_big<false>, grid, dim3(BIGWG), lds, h->stream, t);
+            if (xmode == 0) hipLaunchKernelGGL(gemm_tn_bf16_big<0>, grid, dim3(BIGWG), lds, h->stream, t);
+            else if (xmode == 1) hipLaunchKernelGGL(gemm_tn_bf16_big<1>, grid, dim3(BIGWG), lds, h->stream, t);
+            else hipLaunchKernelGGL(gemm_tn_bf16_big<2>, grid, dim3(BIGWG), lds, h->stream, t);
         } else {
             if (t.use_obs) hipLaunchKernelGGL(gemm_tn_bf16<true>, grid, dim3(WG), lds, h->stream, t);
             else hipLaunchKernelGGL(gemm_tn_bf16<false>, grid, dim3(WG), lds, h->stream, t);
@@ -793,7 +835,7 @@ hipError_t launch_backward_bf16(anakin* h)
         t.split_stride = (size_t)t.K * t.N + t.N;
         t.bias_out = t.partial + (size_t)t.K * t.N; t.bias_stride = t.split_stride;
         t.obs = obs_src();
-        const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0;
+        const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0 && t.rows % 64 == 0;
         if ((e = run_tn(t, big, l == 0 ? "gemm_tn_obs" : "gemm_tn")) != hipSuccess) return e;
         if (l > 0) {
             GemmNtBf16Args g;
