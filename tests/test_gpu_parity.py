@@ -168,6 +168,29 @@ def test_full_size_rollout_sampled_envs(gpu, orc, name):
     g.close()
 
 
+def test_full_size_headline_update(gpu, orc):
+    """The headline workload (Catch, B=4096, T=20, MLP 50-256-256) at full size, one whole step in lockstep:
+    every env of the unroll bit-exact, then loss, gradient, parameters and Adam moments of the update in the
+    launch shape the benchmark times (one persistent workgroup per compute unit in the backward GEMMs).
+    The oracle needs about ten seconds for this step."""
+    cfg = W.get("catch_4096")
+    say("[full size] catch_4096 whole step, all envs")
+    g = gpu.Anakin(cfg, seed=7); o = orc.Oracle(cfg, seed=7)
+    PT.assert_same_init(g, o, "catch")
+    g.step()                                    # one free step first, so the compared update starts from non-initial parameters
+    PT.sync_oracle_from_gpu(g, o)
+    si, sf = g.get_env_state()
+    o.state_i[:] = si
+    o.global_step = g.global_step
+    g.rollout(); o.rollout()
+    PT.assert_rollout_equal(g, o, "catch")
+    PT.assert_final_state_equal(g, o, "catch")
+    g.learn(); o.learn()
+    e_g, e_p = PT.assert_learn_close(g, o, TOL_F32)
+    say(f"  gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
+    g.close()
+
+
 # --------------------------------------------------------------------------- bf16 on the matrix cores
 BF16_CASES = {
     "maze_bf16_128": (variant("maze_16384", hidden=[128, 128, 128], B=64, T=16, max_steps=40), 3, 2),
