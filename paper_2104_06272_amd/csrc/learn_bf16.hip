@@ -207,7 +207,7 @@ struct GemmNtBf16Args {
     const uint16_t* dyR;      // [M][N]
     const uint16_t* w16;      // [K][N]
     const uint16_t* hP;       // packed h_{l-1}: [M/8][K][8]
-    uint16_t* dxR;            // [M][K]
+    uint16_t* dxR;            // [M][K], or null when no product below reads the row-major form
     uint16_t* dxP;            // [M/8][K][8]
 };
 
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(WG) void gemm_nt_bf16(const GemmNtBf16Args a)
     __syncthreads();
     for (int p = tid; p < 128 * 16; p += WG) {
         const int row = p >> 4, c = (p & 15) << 3;
-        if (m0 + row < a.M && i0 + c < a.K)
+        if (a.dxR && m0 + row < a.M && i0 + c < a.K)
             *reinterpret_cast<uint4*>(a.dxR + (size_t)(m0 + row) * a.K + i0 + c) = *reinterpret_cast<const uint4*>(Ts + row * NB_LD + c);
     }
 }
@@ -315,7 +315,7 @@ constexpr int NRES_WG = 512;
 constexpr int NRES_RT = 32;             // rows per stage
 constexpr int NRES_LDT = 256 + 8;       // staging rows of the row-major copy
 
-template <int NR>
+template <int NR, bool ROWMAJOR>
 __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args a, const int rows_per_block)
 {
     constexpr int LD = NR + 8;                                   // row stride in bf16: eight rows cover all banks
@@ -383,8 +383,10 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
             }
             const uint32_t p01 = cvt_pk_bf16(o[0], o[1]), p23 = cvt_pk_bf16(o[2], o[3]);
             const int rowl = 8 * g + 4 * kg;
-            Ts[(rowl + 0) * NRES_LDT + cl] = (uint16_t)p01; Ts[(rowl + 1) * NRES_LDT + cl] = (uint16_t)(p01 >> 16);
-            Ts[(rowl + 2) * NRES_LDT + cl] = (uint16_t)p23; Ts[(rowl + 3) * NRES_LDT + cl] = (uint16_t)(p23 >> 16);
+            if (ROWMAJOR) {
+                Ts[(rowl + 0) * NRES_LDT + cl] = (uint16_t)p01; Ts[(rowl + 1) * NRES_LDT + cl] = (uint16_t)(p01 >> 16);
+                Ts[(rowl + 2) * NRES_LDT + cl] = (uint16_t)p23; Ts[(rowl + 3) * NRES_LDT + cl] = (uint16_t)(p23 >> 16);
+            }
             u32x2_l pv; pv[0] = p01; pv[1] = p23;
             *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
         }
@@ -393,6 +395,7 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
         // row-major copy of this stage: 32 rows x 256 columns, two 16-byte pieces per thread
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
+            if (!ROWMAJOR) break;
             const int p = q * NRES_WG + tid, row = p >> 5, c = (p & 31) << 3;
             *reinterpret_cast<u32x4_l*>(a.dxR + (size_t)(m0 + row) * a.K + i0 + c) = *reinterpret_cast<const u32x4_l*>(Ts + row * NRES_LDT + c);
         }
@@ -843,7 +846,8 @@ hipError_t launch_backward_bf16(anakin* h)
             g.dyR = dzR(l);
             g.w16 = at<const uint16_t>(h, L.w_bf16) + n.w_off[l];
             g.hP = actP(l - 1);
-            g.dxR = dzR(l - 1); g.dxP = dzP(l - 1);
+            g.dxR = l - 1 > 0 ? dzR(l - 1) : nullptr;               // dZ of the first layer feeds only dW products, which read the packed form
+            g.dxP = dzP(l - 1);
             const bool res = (g.N == 256 || g.N == 512) && g.K % 256 == 0 && g.M % NRES_RT == 0;
             ProfScope prof(h, "gemm_nt_mask");
             if (res) {
@@ -851,12 +855,16 @@ hipError_t launch_backward_bf16(anakin* h)
                 const int blocks = tiles < 256 ? tiles : 256;
                 const int rows_per_block = ((tiles + blocks - 1) / blocks) * NRES_RT;
                 const size_t lds2 = ((size_t)2 * NRES_RT * (g.N + 8) + (size_t)2 * NRES_RT * NRES_LDT) * sizeof(uint16_t);
-                const void* fn = g.N == 512 ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256>);
+                const bool rm = g.dxR != nullptr;
+                const void* fn = g.N == 512 ? (rm ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<512, false>))
+                                            : (rm ? reinterpret_cast<const void*>(gemm_nt_bf16_res<256, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256, false>));
                 e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
                 if (e != hipSuccess) return e;
                 const dim3 grid(((g.M + rows_per_block - 1) / rows_per_block) * (g.K / 256));
-                if (g.N == 512) hipLaunchKernelGGL(gemm_nt_bf16_res<512>, grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
-                else hipLaunchKernelGGL(gemm_nt_bf16_res<256>, grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                if (g.N == 512 && rm) hipLaunchKernelGGL((gemm_nt_bf16_res<512, true>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else if (g.N == 512) hipLaunchKernelGGL((gemm_nt_bf16_res<512, false>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else if (rm) hipLaunchKernelGGL((gemm_nt_bf16_res<256, true>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else hipLaunchKernelGGL((gemm_nt_bf16_res<256, false>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
             } else {
                 const size_t lds2 = (size_t)2 * 128 * NB_LD * sizeof(uint16_t);
                 e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_bf16), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
