@@ -142,7 +142,7 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
     if (ed.kind == ENV_CATCH && ns.dims[0] < 64 && !ns.bf16) {
         // matrix-core scatter: 64-sample steps, about two workgroups (of 128 columns) per CU
-        const int s = pick_divisor_splits(M, 64, 512 / ((ns.dims[1] + 127) / 128));
+        const int s = pick_divisor_splits(M, 64, 256);
         if (s > 0) splits[0] = s;
     }
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions

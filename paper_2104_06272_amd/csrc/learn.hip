@@ -462,64 +462,81 @@ __global__ __launch_bounds__(WG) void first_layer_grad_pendulum(const FirstGradA
 // board rebuilt from the state word, v_mfma_f32_32x32x2_f32 taking two samples per step.  Row K of
 // the padded board is all ones, so the column sums (the bias gradient) fall out of the same product
 // and land in the slot after the K weight rows.  The MFMA adds its products in ascending step order,
-// which makes the sum as deterministic as the scatter.  A wavefront owns 32 columns and both
-// 32-row tiles; of each block of 64 samples lane half kg takes samples 32*kg + s at step s, so both
-// halves read whole 128-byte rows of dZ1.
+// which makes the sum as deterministic as the scatter.  A workgroup of eight wavefronts walks its
+// samples 64 at a time and reads whole 1 KiB rows of dZ1; wavefront w owns columns 32w..32w+31 and
+// both 32-row tiles of the board.  Of each block of 64 samples lane half kg takes sample 32*kg + s at
+// step s.  The board operand is the same for all eight wavefronts, so each builds one eighth of it
+// (four steps) and shares it through LDS -- vector-ALU work and MFMAs do not overlap well here, and
+// this keeps the ALU share small.
 typedef float f16v_l __attribute__((ext_vector_type(16)));
+typedef float f4v_l __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(WG) void first_layer_grad_mfma(const FirstGradArgs a)
+__global__ __launch_bounds__(512) void first_layer_grad_mfma(const FirstGradArgs a)
 {
+    __shared__ f4v_l xs[2][2][8][64];                          // [buffer][tile][group of four steps][lane]
     const int N = a.N, K = a.K;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, kg = lane >> 5;
-    const int j = blockIdx.y * 128 + wave * 32 + l32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, kg = lane >> 5;
+    const int j = blockIdx.y * 256 + wave * 32 + l32;
     const int split = blockIdx.x;
-    const int m_begin = split * a.rows, m_end = m_begin + a.rows;
+    const int m_begin = split * a.rows, m_end = m_begin + a.rows;   // a.rows is a multiple of 64, N of 256
     f16v_l acc0, acc1;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc0[r] = 0.0f; acc1[r] = 0.0f; }
-    const float* __restrict__ dy = a.dy + j;
-    // rows per split and N are whole multiples of 64 and 32 here (see the launcher): no guards.
-    // Two register buffers: the loads of the next 64 samples are in flight under the MFMAs of these.
-    auto load = [&](float (&d)[32], uint32_t& lo, uint32_t& hi, int m0) {
-        // lane l holds the padded board of sample m0 + l as a bit mask: its two cells and the ones row K
-        int bc, pc;
-        catch_obs_cells(a.obs.env, a.obs.s0[m0 + lane], bc, pc);
-        const unsigned long long bits = (1ull << bc) | (1ull << pc) | (1ull << K);
-        lo = (uint32_t)bits; hi = (uint32_t)(bits >> 32);
+    const uint32_t lane_off = (uint32_t)(32 * kg) * (uint32_t)N + (uint32_t)j;
+    // loads of one block of 64 samples: this lane's 32 values of dZ1 and the state word of sample m0 + lane
+    auto load = [&](float (&d)[32], uint32_t& sw, int m0) {
+        sw = a.obs.s0[m0 + lane];
 #pragma unroll
-        for (int s = 0; s < 32; ++s) d[s] = dy[(size_t)(m0 + 32 * kg + s) * N];
+        for (int s = 0; s < 32; ++s) d[s] = (a.dy + (size_t)(m0 + s) * N)[lane_off];
     };
-    auto compute = [&](const float (&d)[32], uint32_t lo, uint32_t hi) {
-        // board operands of all 32 steps first, then an uninterrupted run of MFMAs
-        float x0[32], x1[32];
+    // this wavefront's share of the board operand: steps 4w..4w+3, both tiles
+    auto build = [&](uint32_t sw, int buf) {
+        int bc, pc;
+        catch_obs_cells(a.obs.env, sw, bc, pc);
+        const unsigned long long bits = (1ull << bc) | (1ull << pc) | (1ull << K);   // lane l: board of sample l, ones row K
+        const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
+        f4v_l x0, x1;
 #pragma unroll
-        for (int s = 0; s < 32; ++s) {
+        for (int e = 0; e < 4; ++e) {
+            const int s = 4 * wave + e;
             const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readlane((int)lo, s), lo1 = (uint32_t)__builtin_amdgcn_readlane((int)lo, 32 + s);
             const uint32_t hi0 = (uint32_t)__builtin_amdgcn_readlane((int)hi, s), hi1 = (uint32_t)__builtin_amdgcn_readlane((int)hi, 32 + s);
-            x0[s] = (float)(((kg ? lo1 : lo0) >> l32) & 1u);
-            x1[s] = (float)(((kg ? hi1 : hi0) >> l32) & 1u);
+            x0[e] = (float)(((kg ? lo1 : lo0) >> l32) & 1u);
+            x1[e] = (float)(((kg ? hi1 : hi0) >> l32) & 1u);
         }
-        __builtin_amdgcn_sched_barrier(0);
+        xs[buf][0][wave][lane] = x0;
+        xs[buf][1][wave][lane] = x1;
+    };
+    auto compute = [&](const float (&d)[32], int buf) {
 #pragma unroll
-        for (int s = 0; s < 32; ++s) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[s], d[s], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[s], d[s], acc1, 0, 0, 0);
+        for (int g = 0; g < 8; ++g) {
+            const f4v_l x0 = xs[buf][0][g][lane], x1 = xs[buf][1][g][lane];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[e], d[4 * g + e], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[e], d[4 * g + e], acc1, 0, 0, 0);
+            }
         }
-        __builtin_amdgcn_sched_barrier(0);
     };
     float dA[32], dB[32];
-    uint32_t loA, hiA, loB = 0u, hiB = 0u;
+    uint32_t swA, swB;
     // every load is unconditional (past the end it re-reads the last block and the result is dropped), so
     // the wait counters the compiler places before the MFMAs never have to cover the prefetch
     const int m_last = m_end - 64;
-    load(dA, loA, hiA, m_begin);
+    load(dA, swA, m_begin);
+    build(swA, 0);
+    __syncthreads();
     for (int m0 = m_begin; m0 < m_end; m0 += 128) {
-        load(dB, loB, hiB, m0 + 64 < m_end ? m0 + 64 : m_last);
+        load(dB, swB, m0 + 64 < m_end ? m0 + 64 : m_last);
         __builtin_amdgcn_sched_barrier(0);
-        compute(dA, loA, hiA);
-        load(dA, loA, hiA, m0 + 128 < m_end ? m0 + 128 : m_last);
+        compute(dA, 0);
+        build(swB, 1);
+        __syncthreads();
+        load(dA, swA, m0 + 128 < m_end ? m0 + 128 : m_last);
         __builtin_amdgcn_sched_barrier(0);
-        if (m0 + 64 < m_end) compute(dB, loB, hiB);
+        if (m0 + 64 < m_end) compute(dB, 1);
+        build(swA, 0);
+        __syncthreads();
     }
     // rows 0..K-1 are dW1, row K the column sums: row i of the padded product goes to out[i*N + j]
     float* out = a.partial + (size_t)split * ((size_t)K * N + N);
@@ -544,8 +561,8 @@ hipError_t launch_first_layer_grad(anakin* h)
     const size_t lds = (size_t)WG * a.K * sizeof(float);
     const dim3 grid(h->splits[0], (a.N + WG - 1) / WG);
     ProfScope prof(h, "first_layer_grad");
-    if (h->env.kind == ENV_CATCH && a.K < 64 && a.rows % 64 == 0 && a.N % 128 == 0 && !(h->mode & ANAKIN_MODE_VALU_GEMM)) {
-        hipLaunchKernelGGL(first_layer_grad_mfma, dim3(h->splits[0], a.N / 128), dim3(WG), 0, h->stream, a);
+    if (h->env.kind == ENV_CATCH && a.K < 64 && a.rows % 64 == 0 && a.N % 256 == 0 && !(h->mode & ANAKIN_MODE_VALU_GEMM)) {
+        hipLaunchKernelGGL(first_layer_grad_mfma, dim3(h->splits[0], a.N / 256), dim3(512), 0, h->stream, a);
     } else if (h->env.kind == ENV_CATCH) {
         auto kern = first_layer_grad<ENV_CATCH>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
