@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--workload", default="catch_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--valu-gemm", action="store_true", help="learn-phase GEMMs on vector ALUs")
+    ap.add_argument("--peak-probe", action="store_true",
+                    help="instead of the benchmark, measure what this GPU delivers for the rooflines: register-only "
+                         "fp32 and bf16 MFMA loops and a 2 x 1 GiB streaming copy; prints one JSON line")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB 20 times "
                          "(calibrates the HBM byte counters under rocprofv3 --pmc)")
@@ -138,6 +141,25 @@ def main():
         print(json.dumps({"copy_probe_MiB": args.copy_probe, "copies": 20}))
         return
     from paper_2104_06272_amd import binding, workloads as W
+    if args.peak_probe:
+        torch.cuda.set_device(0)
+        scratch = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda:0")
+        stream = torch.cuda.current_stream().cuda_stream
+        out = {}
+        for name, kind, unit, peak in (("mfma_f32", binding.PROBE_MFMA_F32, "TFLOP/s", PEAK_FP32_TFLOPS),
+                                       ("mfma_bf16", binding.PROBE_MFMA_BF16, "TFLOP/s", PEAK_BF16_TFLOPS),
+                                       ("copy", binding.PROBE_COPY, "GB/s", PEAK_HBM_GBS)):
+            best, best_wg = 0.0, 0
+            for wg in ((1024, 4096, 16384, 65536) if name == "copy" else (256, 512, 768, 1024, 2048)):
+                for _ in range(2):
+                    amount, ms = binding.peak_probe(kind, scratch, stream, wg)
+                    rate = amount / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
+                    if rate > best:
+                        best, best_wg = rate, wg
+            out[name] = {"measured": round(best, 1), "published": peak, "unit": unit, "frac": round(best / peak, 3),
+                         "workgroups": best_wg}
+        print(json.dumps({"peak_probe": out}))
+        return
     cfg = W.get(args.workload)
     torch.cuda.set_device(0)
     g = binding.Anakin(cfg, seed=0, device="cuda:0")
@@ -158,6 +180,25 @@ def main():
     ms_per_step = ms / args.steps
     value = cfg["B"] * cfg["T"] * args.steps / (ms / 1e3)
     metrics = g.metrics()
+
+    # the two halves on their own (same K): unrolls only, then the updates of K further steps bracketed by events
+    a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
+    a0.record(g.stream)
+    for _ in range(args.steps):
+        g.rollout()
+    a1.record(g.stream)
+    torch.cuda.synchronize()
+    ms_rollout = a0.elapsed_time(a1) / args.steps
+    pairs = []
+    for _ in range(args.steps):
+        g.rollout()
+        b0 = torch.cuda.Event(enable_timing=True); b1 = torch.cuda.Event(enable_timing=True)
+        b0.record(g.stream)
+        g.learn()
+        b1.record(g.stream)
+        pairs.append((b0, b1))
+    torch.cuda.synchronize()
+    ms_learn = sum(x.elapsed_time(y) for x, y in pairs) / args.steps
 
     # instrumented pass: the same K steps with two events around every kernel launch
     g.profile(True)
@@ -194,6 +235,8 @@ def main():
                    "hidden": cfg["net"]["hidden"], "params": g.P},
         "roofline": roofline,
         "kernels": per_kernel,
+        "rollout_only": {"ms": round(ms_rollout, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_rollout * 1e-3)},
+        "learn_only": {"ms": round(ms_learn, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_learn * 1e-3)},
         "wall_s": round(wall, 3),
         "loss": metrics["loss"], "mean_episode_return": metrics["reward_sum"] / max(1, metrics["episodes"]),
     }

@@ -59,7 +59,8 @@ EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
-           "anakin_get_metrics", "anakin_set_mode", "anakin_profile", "anakin_kernel_times", "anakin_last_error"]
+           "anakin_get_metrics", "anakin_set_mode", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
+           "anakin_last_error"]
 
 _lib = None
 
@@ -104,6 +105,7 @@ def load():
     L.anakin_kernel_times.argtypes = [vp, C.POINTER(KernelTime), C.c_int32, C.POINTER(C.c_int32)]
     L.anakin_last_error.argtypes = [vp]
     L.anakin_last_error.restype = C.c_char_p
+    L.anakin_peak_probe.argtypes = [C.c_int32, C.c_int32, vp, C.c_size_t, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for name in EXPORTS:
         if name not in ("anakin_workspace_bytes", "anakin_last_error"):
             getattr(L, name).restype = C.c_int32
@@ -308,3 +310,17 @@ def unpack_state_word(kind, s0):
     else:
         out[..., 0] = s0 & 0xFFFF; out[..., 1] = s0 >> 16
     return out
+
+
+PROBE_MFMA_F32, PROBE_MFMA_BF16, PROBE_COPY = 0, 1, 2
+
+
+def peak_probe(kind, scratch, stream_ptr, workgroups=0):
+    """(amount, milliseconds) of one peak probe; scratch: a uint8 device tensor the probe may overwrite."""
+    L = load()
+    amount, ms = C.c_double(0.0), C.c_double(0.0)
+    rc = L.anakin_peak_probe(kind, workgroups, C.c_void_p(scratch.data_ptr()), scratch.numel(), C.c_void_p(stream_ptr),
+                             C.byref(amount), C.byref(ms))
+    if rc != 0:
+        raise AnakinError(rc, "peak probe failed")
+    return amount.value, ms.value

@@ -1,0 +1,98 @@
+// Peak probes for the measurement section: what this GPU actually delivers for the two rooflines the
+// kernels are priced against.  A register-only MFMA loop (no memory traffic: every wavefront keeps
+// re-issuing the same instruction on its own accumulators) and a plain streaming copy.  Not part of
+// the hot path; called by `bench.py --peak-probe` only.
+#include "internal.h"
+#include "../../include/anakin.h"
+
+namespace ank {
+
+typedef float pf16v __attribute__((ext_vector_type(16)));
+typedef __bf16 pbf8 __attribute__((ext_vector_type(8)));
+typedef float pf4v __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(WG) void probe_mfma_f32(float* out, int iters, float a0)
+{
+    pf16v acc[4];
+    for (int i = 0; i < 4; ++i) for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    const float a = a0 + (float)threadIdx.x, b = a0 * 0.5f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int i = 0; i < 4; ++i) for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * WG + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(WG) void probe_mfma_bf16(float* out, int iters, float a0)
+{
+    pf16v acc[4];
+    for (int i = 0; i < 4; ++i) for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    pbf8 a, b;
+    for (int q = 0; q < 8; ++q) { a[q] = (__bf16)(a0 + (float)((threadIdx.x + q) & 7)); b[q] = (__bf16)(a0 * (float)q); }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int i = 0; i < 4; ++i) for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * WG + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(WG) void probe_copy(const pf4v* __restrict__ src, pf4v* __restrict__ dst, size_t n4)
+{
+    for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n4; i += (size_t)gridDim.x * WG) dst[i] = src[i];
+}
+
+}  // namespace ank
+
+extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratch, size_t scratch_bytes, void* hip_stream,
+                                     double* amount, double* milliseconds)
+{
+    using namespace ank;
+    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 2 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ANAKIN_E_HIP;
+    const int iters = 4000;
+    hipError_t err = hipSuccess;
+    if (kind == ANAKIN_PROBE_COPY) {
+        const size_t half = (scratch_bytes / 2) & ~(size_t)255;
+        if (half < 256) return ANAKIN_E_INVALID_ARG;
+        const size_t n4 = half / 16;
+        auto* src = static_cast<pf4v*>(scratch);
+        auto* dst = reinterpret_cast<pf4v*>(static_cast<char*>(scratch) + half);
+        const int blocks = variant > 0 ? variant : 4096;
+        hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);   // warm-up
+        hipEventRecord(e0, s);
+        for (int r = 0; r < 10; ++r) hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);
+        hipEventRecord(e1, s);
+        *amount = 10.0 * 2.0 * (double)half;                 // bytes read + written
+    } else {
+        const int blocks = variant > 0 ? variant : 768;
+        if (scratch_bytes < (size_t)blocks * WG * 4) return ANAKIN_E_INVALID_ARG;
+        float* out = static_cast<float*>(scratch);
+        auto launch = [&](int n) {
+            if (kind == ANAKIN_PROBE_MFMA_F32) hipLaunchKernelGGL(probe_mfma_f32, dim3(blocks), dim3(WG), 0, s, out, n, 1.0f);
+            else hipLaunchKernelGGL(probe_mfma_bf16, dim3(blocks), dim3(WG), 0, s, out, n, 1.0f);
+        };
+        launch(10);
+        hipEventRecord(e0, s);
+        launch(iters);
+        hipEventRecord(e1, s);
+        const double flop_per_mfma = kind == ANAKIN_PROBE_MFMA_F32 ? 4096.0 : 32768.0;
+        *amount = (double)blocks * 4.0 * iters * 8.0 * 4.0 * flop_per_mfma;
+    }
+    err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+    hipEventDestroy(e0); hipEventDestroy(e1);
+    if (err != hipSuccess || hipGetLastError() != hipSuccess) return ANAKIN_E_HIP;
+    *milliseconds = (double)ms;
+    return ANAKIN_OK;
+}
