@@ -166,6 +166,7 @@ hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);
 hipError_t launch_adam(anakin* h);
 hipError_t launch_first_layer_grad(anakin* h);
+hipError_t launch_adam_probe(float* base, int P, hipStream_t s);
 hipError_t launch_learn_one_layer(anakin* h);
 // single hidden layer on a one-hot or 3-feature observation: the update rebuilds the layer from the state
 inline bool one_layer_fused(const anakin* h) { return h->net.L == 1 && h->env.kind != ENV_MAZE && !h->net.bf16 && !(h->mode & ANAKIN_MODE_VALU_GEMM) && h->net.dims[1] <= 128 && (size_t)128 * h->net.dims[0] * 4 + (size_t)h->net.dims[0] * h->net.dims[1] * 4 <= 64 * 1024; }

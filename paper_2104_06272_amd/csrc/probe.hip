@@ -55,7 +55,7 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
                                      double* amount, double* milliseconds)
 {
     using namespace ank;
-    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 2 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
+    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 3 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ANAKIN_E_HIP;
@@ -73,6 +73,20 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
         for (int r = 0; r < 10; ++r) hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);
         hipEventRecord(e1, s);
         *amount = 10.0 * 2.0 * (double)half;                 // bytes read + written
+    } else if (kind == ANAKIN_PROBE_ADAM) {
+        // theta | grad | m | v | one partial, P floats each; zeroed so that no value overflows over the repetitions
+        size_t P = scratch_bytes / 20;
+        if (P > ((size_t)1 << 26)) P = (size_t)1 << 26;
+        P &= ~(size_t)63;
+        if (P < 64) return ANAKIN_E_INVALID_ARG;
+        float* base = static_cast<float*>(scratch);
+        if (hipMemsetAsync(base, 0, P * 20, s) != hipSuccess) return ANAKIN_E_HIP;
+        err = launch_adam_probe(base, (int)P, s);            // warm-up
+        hipEventRecord(e0, s);
+        for (int r = 0; r < 5 && err == hipSuccess; ++r) err = launch_adam_probe(base, (int)P, s);
+        hipEventRecord(e1, s);
+        if (err != hipSuccess) return ANAKIN_E_HIP;
+        *amount = 5.0 * 32.0 * (double)P;                    // 28 B of Adam state per parameter + 4 B of the partial
     } else {
         const int blocks = variant > 0 ? variant : 768;
         if (scratch_bytes < (size_t)blocks * WG * 4) return ANAKIN_E_INVALID_ARG;
