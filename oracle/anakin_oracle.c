@@ -775,26 +775,28 @@ static double qround(const orc_t* h, double v)
     return h->net.dtype == 1 ? (double)orc_bf16_round((float)v) : v;
 }
 
-void orc_loss_and_grad(orc_t* h)
+/* Loss and gradient over the samples tb_begin <= t*B + b < tb_end (mean over    */
+/* those samples), with the parameters theta_src.                              */
+static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begin, size_t tb_end)
 {
-    int B = h->B, T = h->T, NH = h->NH, L = h->L;
-    size_t n = (size_t)T * B;
+    int B = h->B, NH = h->NH, L = h->L;
+    size_t n = tb_end - tb_begin;
     double inv_n = 1.0 / (double)n;
     double beta = (double)h->net.entropy_coef, cv = (double)h->net.value_coef;
     double* g = (double*)zalloc(h->P * sizeof(double));
     double* wq = (double*)zalloc(h->P * sizeof(double));     /* parameters as the forward sees them */
-    for (size_t i = 0; i < h->P; ++i) wq[i] = (double)h->theta[i];
+    for (size_t i = 0; i < h->P; ++i) wq[i] = (double)theta_src[i];
     if (h->net.dtype == 1) {
         for (int l = 0; l < L; ++l)
             for (size_t i = 0; i < (size_t)h->dims[l] * h->dims[l + 1]; ++i)
-                wq[h->w_off[l] + i] = (double)orc_bf16_round(h->theta[h->w_off[l] + i]);
+                wq[h->w_off[l] + i] = (double)orc_bf16_round(theta_src[h->w_off[l] + i]);
         for (size_t i = 0; i < (size_t)h->dims[L] * NH; ++i)
-            wq[h->wh_off + i] = (double)orc_bf16_round(h->theta[h->wh_off + i]);
+            wq[h->wh_off + i] = (double)orc_bf16_round(theta_src[h->wh_off + i]);
     }
     float xf[1024];
     double act[5][1024], dz[2][1024], head[16], dhead[16];
     double Lp = 0, Lv = 0, Le = 0;
-    for (size_t tb = 0; tb < n; ++tb) {
+    for (size_t tb = tb_begin; tb < tb_end; ++tb) {
         int b = (int)(tb % (size_t)B);
         render_obs(h, b, h->tr_si + tb * 4, h->tr_sf + tb * 2, xf);
         for (int k = 0; k < h->D; ++k) act[0][k] = (double)xf[k];
@@ -874,6 +876,11 @@ void orc_loss_and_grad(orc_t* h)
     free(g); free(wq);
 }
 
+void orc_loss_and_grad(orc_t* h)
+{
+    loss_and_grad_range(h, h->theta, 0, (size_t)h->T * h->B);
+}
+
 /* ------------------------------------------------------------------------- */
 /* Adam (Kingma & Ba), R-27: bias-corrected, epsilon outside the square root, */
 /* no weight decay, no clipping.  Binary64 arithmetic on binary32 parameters. */
@@ -901,6 +908,37 @@ int orc_learn(orc_t* h)
     h->adam_t += 1;
     orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t,
              (double)h->net.lr, (double)h->net.beta1, (double)h->net.beta2, (double)h->net.eps);
+    h->have_traj = 0;
+    return 0;
+}
+
+/* N updates on one stored trajectory (paper section 4, the remark on decoupling   */
+/* the acting batch from the learning batch: split the batch on the learner and  */
+/* apply N updates instead of one larger one).  Reading: the T steps are cut     */
+/* into N equal, consecutive time chunks; returns and advantages come from the   */
+/* whole unroll; chunk k's gradient is that of its own mean loss at the          */
+/* parameters the unroll was acted with (the update reuses the acting forward    */
+/* pass, paper section 3.1), and the N Adam steps are applied in chunk order.    */
+/* loss[] ends up as the mean of the N chunk losses, grad as the last chunk's.   */
+int orc_learn_n(orc_t* h, int n_updates)
+{
+    if (!h->have_traj) return -1;
+    if (n_updates < 1 || h->T % n_updates != 0) return -2;
+    orc_returns(h->T, h->B, h->tr_rew, h->tr_done, h->tr_val,
+                (double)h->net.gamma, (double)h->net.lambda_, h->ret, h->adv);
+    float* theta0 = (float*)malloc(h->P * sizeof(float));
+    memcpy(theta0, h->theta, h->P * sizeof(float));
+    size_t chunk = (size_t)(h->T / n_updates) * h->B;
+    double acc[4] = {0, 0, 0, 0};
+    for (int k = 0; k < n_updates; ++k) {
+        loss_and_grad_range(h, theta0, (size_t)k * chunk, (size_t)(k + 1) * chunk);
+        for (int i = 0; i < 4; ++i) acc[i] += h->loss[i];
+        h->adam_t += 1;
+        orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t,
+                 (double)h->net.lr, (double)h->net.beta1, (double)h->net.beta2, (double)h->net.eps);
+    }
+    for (int i = 0; i < 4; ++i) h->loss[i] = acc[i] / (double)n_updates;
+    free(theta0);
     h->have_traj = 0;
     return 0;
 }

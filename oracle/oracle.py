@@ -87,6 +87,7 @@ def lib():
                                C.c_double, C.c_double]
         L.orc_adam.restype = None
         L.orc_learn.argtypes = [C.c_void_p]; L.orc_learn.restype = C.c_int
+        L.orc_learn_n.argtypes = [C.c_void_p, C.c_int]; L.orc_learn_n.restype = C.c_int
         L.orc_step.argtypes = [C.c_void_p]; L.orc_step.restype = None
         _lib = L
     return _lib
@@ -262,6 +263,13 @@ class Oracle:
         rc = self.L.orc_learn(self.h)
         if rc != 0:
             raise RuntimeError("learn without a stored trajectory")
+
+    def learn_n(self, n_updates):
+        """N Adam updates on the stored unroll, one per consecutive time chunk (gradients at the acting-time
+        parameters)."""
+        rc = self.L.orc_learn_n(self.h, int(n_updates))
+        if rc != 0:
+            raise RuntimeError("learn_n: no stored trajectory" if rc == -1 else "learn_n: T is not a multiple of n_updates")
 
     def loss_and_grad(self):
         self.L.orc_loss_and_grad(self.h)

@@ -728,6 +728,42 @@ def test_unroll_continues_across_calls(orc):
     assert a.global_step == b.global_step == 20
 
 
+def test_n_updates_per_unroll(orc):
+    """N updates on one unroll (the paper's remark on splitting the learner batch): with N = 1 it is the plain
+    update; with N = 2 the two chunk gradients (at the acting-time parameters) average to the full-batch gradient,
+    the reported loss is the full-batch loss, and the parameters are what two Adam steps in chunk order give."""
+    cfg = W.get("catch_small", B=32, T=8)
+    a = orc.Oracle(cfg, seed=5); b = orc.Oracle(cfg, seed=5)
+    a.rollout(); b.rollout()
+    a.learn(); b.learn_n(1)
+    assert np.array_equal(a.theta, b.theta) and np.array_equal(a.m, b.m) and np.array_equal(a.v, b.v)
+    # N = 2 from non-zero moments
+    a.rollout(); b.rollout()
+    assert np.array_equal(a.tr_action, b.tr_action)
+    theta0 = b.theta.copy().astype(np.float64); m0 = b.m.copy(); v0 = b.v.copy(); t0 = b.adam_t
+    # full-batch gradient and loss at theta0 (learn computes the returns first; loss_and_grad needs them)
+    ret, adv = orc.returns(a.tr_reward, a.tr_done, a.tr_value, cfg["net"]["gamma"], cfg["net"]["lambda"])
+    a.ret[:] = ret; a.adv[:] = adv
+    a.loss_and_grad()
+    g_full = a.grad.copy().astype(np.float64); loss_full = a.loss.copy()
+    b.learn_n(2)
+    g2 = b.grad.copy().astype(np.float64)
+    g1 = 2.0 * g_full - g2
+    assert np.abs(b.loss - loss_full).max() <= 1e-7 * max(1.0, np.abs(loss_full).max())
+    lr, b1, b2, eps = cfg["net"]["lr"], cfg["net"]["beta1"], cfg["net"]["beta2"], cfg["net"]["eps"]
+    th, m, v = theta0.copy(), m0.copy(), v0.copy()
+    for k, g in enumerate((g1, g2)):
+        t = t0 + k + 1
+        m = b1 * m + (1 - b1) * g; v = b2 * v + (1 - b2) * g * g
+        th = th - lr * (m / (1 - b1 ** t)) / (np.sqrt(v / (1 - b2 ** t)) + eps)
+    assert b.adam_t == t0 + 2
+    # g1 is known only through float32 gradients: a few 1e-7 relative on the step, far below one step (3e-4)
+    assert np.abs(b.theta - th).max() <= 2e-6, np.abs(b.theta - th).max()
+    assert np.abs(b.m - m).max() <= 1e-6 * max(1.0, np.abs(m).max()) and np.abs(b.v - v).max() <= 1e-6 * max(1e-3, np.abs(v).max())
+    with pytest.raises(RuntimeError):
+        b.rollout(); b.learn_n(3)               # 8 steps do not split into 3 chunks
+
+
 def test_catch_learning_sanity(orc):
     # not a parity criterion: the mean episode return should rise from about -0.6
     cfg = W.get("catch_small", B=64, T=20)
