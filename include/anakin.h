@@ -151,6 +151,17 @@ int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* out);
 int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out);
 int32_t anakin_set_mode(anakin_t* h, int32_t flags);
 
+/* Several Adam updates per unroll (paper section 4, the remark on decoupling the acting batch from
+ * the learning batch by splitting the batch on the learner and applying N updates instead of one
+ * larger one).  With n_updates = N > 1, anakin_learn cuts the stored unroll into N consecutive
+ * chunks of T/N time steps (all B envs each); returns and advantages still come from the whole
+ * unroll; chunk k's gradient is that of its own mean loss at the parameters the unroll was acted
+ * with (the update reuses the acting forward pass), and the N Adam steps are applied in chunk
+ * order.  The metrics then average over the chunks; anakin_get_grads returns the last chunk's
+ * gradient.  ANAKIN_E_BAD_CONFIG if T is not a multiple of n_updates or a chunk does not fit the
+ * kernels' row granularity; the setting is kept until changed.  Default 1. */
+int32_t anakin_set_updates_per_unroll(anakin_t* h, int32_t n_updates);
+
 /* Per-kernel timing for measurement.  While enabled, every kernel launch is
  * bracketed by two events recorded on the handle's stream (this adds a few
  * microseconds per launch, so throughput is timed with profiling off).

@@ -59,7 +59,7 @@ EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
-           "anakin_get_metrics", "anakin_set_mode", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
+           "anakin_get_metrics", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
            "anakin_last_error"]
 
 _lib = None
@@ -101,6 +101,7 @@ def load():
     L.anakin_get_trajectory.argtypes = [vp, C.POINTER(TrajView)]
     L.anakin_get_metrics.argtypes = [vp, C.POINTER(Metrics)]
     L.anakin_set_mode.argtypes = [vp, C.c_int32]
+    L.anakin_set_updates_per_unroll.argtypes = [vp, C.c_int32]
     L.anakin_profile.argtypes = [vp, C.c_int32]
     L.anakin_kernel_times.argtypes = [vp, C.POINTER(KernelTime), C.c_int32, C.POINTER(C.c_int32)]
     L.anakin_last_error.argtypes = [vp]
@@ -192,6 +193,9 @@ class Anakin:
 
     def set_mode(self, flags):
         self._chk(self.L.anakin_set_mode(self.h, int(flags)))
+
+    def set_updates_per_unroll(self, n):
+        self._chk(self.L.anakin_set_updates_per_unroll(self.h, int(n)))
 
     # ---- introspection ----------------------------------------------------------
     def get_params(self):

@@ -93,6 +93,8 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     const size_t P = (size_t)ns.P, n = (size_t)B, tn = (size_t)T * B, t1n = (size_t)(T + 1) * B;
     L.theta = take(P * 4); L.grad = take(P * 4); L.m = take(P * 4); L.v = take(P * 4);
     L.w_bf16 = take(ns.bf16 ? P * 2 : 0); L.wt_bf16 = take(ns.bf16 ? P * 2 : 0);
+    L.theta0 = take(P * 4); L.w0_bf16 = take(ns.bf16 ? P * 2 : 0);
+    L.w_src = L.theta; L.w16_src = L.w_bf16;
     L.s0 = take(n * 4); L.f0 = take(n * 4); L.f1 = take(n * 4); L.walls = take(n * 8 * 4);
     L.tr_s0 = take(t1n * 4); L.tr_f0 = take(t1n * 4); L.tr_f1 = take(t1n * 4);
     L.tr_act = take(tn); L.tr_eps = take(tn * 4); L.tr_actf = take(tn * 4);
@@ -119,7 +121,7 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     }
     L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
     L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
-    L.loss_part = take((size_t)loss_blocks * 8 * 4);
+    L.loss_part = take((size_t)(loss_blocks + T) * 8 * 4);     // + T: with N updates per unroll every chunk rounds its block count up
     L.total = off;
 }
 
@@ -308,6 +310,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
         g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";
         delete h; return ANAKIN_E_WORKSPACE_TOO_SMALL;
     }
+    h->n_updates = 1;
     h->TM = rollout_pick_tile(ns, B);
     h->TM_mfma = rollout_pick_tile_mfma(ns, B);
     h->TM_res = rollout_resident_tile(ns, B);
@@ -457,19 +460,82 @@ extern "C" int32_t anakin_rollout(anakin_t* h)
     return ANAKIN_OK;
 }
 
-extern "C" int32_t anakin_learn(anakin_t* h)
+// loss, backward pass and Adam on the samples the handle's layout and T currently describe
+static int32_t run_update(anakin* h)
 {
-    NEED(h);
-    if (!h->have_traj) { h->err = "learn needs a stored trajectory: call anakin_rollout first"; return ANAKIN_E_STATE; }
-    HIPCHK(h, launch_returns(h));
     HIPCHK(h, launch_head_grad(h));
-    if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
-    if (h->traj_no_acts != (one_layer_fused(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     if (h->traj_packed) HIPCHK(h, launch_backward_bf16(h));
     else if (h->traj_no_acts) HIPCHK(h, launch_learn_one_layer(h));
     else HIPCHK(h, launch_backward(h));
     HIPCHK(h, launch_adam(h));
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_learn(anakin_t* h)
+{
+    NEED(h);
+    if (!h->have_traj) { h->err = "learn needs a stored trajectory: call anakin_rollout first"; return ANAKIN_E_STATE; }
+    if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
+    if (h->traj_no_acts != (one_layer_fused(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
+    HIPCHK(h, launch_returns(h));
+    if (h->n_updates == 1) {
+        int32_t rc = run_update(h);
+        if (rc != ANAKIN_OK) return rc;
+        h->have_traj = 0;
+        return ANAKIN_OK;
+    }
+    // Several updates on one unroll: chunk k is the time steps [k T/n, (k+1) T/n).  Every chunk's gradient is taken
+    // at the parameters the unroll was acted with (the stored forward pass), so the backward kernels read a copy of
+    // the weights made now while Adam moves the live ones.  The kernels see a chunk as a shorter unroll: T and the
+    // offsets of the per-sample arrays are switched for the duration of one update.
+    const Layout full = h->lay;
+    const NetShape& n = h->net;
+    const int T = h->T, B = h->B, Ts = T / h->n_updates;
+    HIPCHK(h, hipMemcpyAsync(h->ws + full.theta0, h->ws + full.theta, (size_t)n.P * 4, hipMemcpyDeviceToDevice, h->stream));
+    if (n.bf16) HIPCHK(h, hipMemcpyAsync(h->ws + full.w0_bf16, h->ws + full.w_bf16, (size_t)n.P * 2, hipMemcpyDeviceToDevice, h->stream));
+    int full_splits[MAX_REGIONS];
+    for (int l = 0; l < MAX_REGIONS; ++l) { full_splits[l] = h->splits[l]; h->splits[l] = h->sub_splits[l]; }
+    const int full_sw = h->splits_w, full_fan = h->head_fan, full_lb = h->loss_blocks;
+    h->splits_w = h->sub_splits_w; h->head_fan = h->sub_head_fan; h->loss_blocks = h->sub_loss_blocks;
+    h->T = Ts;
+    int32_t rc = ANAKIN_OK;
+    for (int k = 0; k < h->n_updates && rc == ANAKIN_OK; ++k) {
+        const size_t r0 = (size_t)k * Ts * B;                         // first sample of the chunk
+        Layout& L = h->lay;
+        L = full;
+        L.w_src = full.theta0; L.w16_src = n.bf16 ? full.w0_bf16 : full.w_bf16;
+        L.tr_s0 += r0 * 4; L.tr_f0 += r0 * 4; L.tr_f1 += r0 * 4;
+        L.tr_act += r0; L.tr_eps += r0 * 4; L.tr_actf += r0 * 4; L.tr_rew += r0 * 4; L.tr_done += r0;
+        L.tr_val += r0 * 4; L.tr_head += r0 * n.NHP * 4;
+        L.adv += r0 * 4; L.ret += r0 * 4;
+        for (int l = 0; l < n.L; ++l) L.act[l] += r0 * n.dims[l + 1] * (h->traj_packed ? 2 : 4);
+        L.loss_part += (size_t)k * h->sub_loss_blocks * 8 * 4;
+        rc = run_update(h);
+    }
+    h->lay = full; h->T = T;
+    for (int l = 0; l < MAX_REGIONS; ++l) h->splits[l] = full_splits[l];
+    h->splits_w = full_sw; h->head_fan = full_fan; h->loss_blocks = full_lb;
+    if (rc != ANAKIN_OK) return rc;
     h->have_traj = 0;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_set_updates_per_unroll(anakin_t* h, int32_t n_updates)
+{
+    NEED(h);
+    if (n_updates < 1 || h->T % n_updates != 0) { h->err = "updates per unroll: T must be a positive multiple of it"; return ANAKIN_E_BAD_CONFIG; }
+    if (n_updates == 1) { h->n_updates = 1; return ANAKIN_OK; }
+    int sw = 0, fan = 1, lb = 0;
+    int sp[MAX_REGIONS];
+    plan(h->env, h->net, h->B, h->T / n_updates, sp, &sw, &fan, &lb);
+    // the scratch buffers were sized for the full unroll: a chunk's plan has to fit them
+    bool ok = (sw > 0) == (h->splits_w > 0) && lb * n_updates <= h->loss_blocks + h->T && sp[h->net.L] * fan <= h->splits[h->net.L] * h->head_fan;
+    for (int l = 0; l <= h->net.L && ok; ++l) ok = sp[l] > 0 && sp[l] <= h->splits[l];
+    if (ok && sw > 0) ok = sw <= h->splits_w;
+    if (!ok) { h->err = "updates per unroll: the chunk size does not fit the kernels' row granularity for this B and T"; return ANAKIN_E_BAD_CONFIG; }
+    for (int l = 0; l < MAX_REGIONS; ++l) h->sub_splits[l] = sp[l];
+    h->sub_splits_w = sw; h->sub_head_fan = fan; h->sub_loss_blocks = lb;
+    h->n_updates = n_updates;
     return ANAKIN_OK;
 }
 
@@ -614,11 +680,13 @@ extern "C" int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out)
 {
     NEED(h);
     if (!out) return ANAKIN_E_INVALID_ARG;
-    std::vector<float> part((size_t)h->loss_blocks * 8);
+    // with several updates per unroll every chunk wrote its own run of blocks
+    const int blocks = h->n_updates > 1 ? h->n_updates * h->sub_loss_blocks : h->loss_blocks;
+    std::vector<float> part((size_t)blocks * 8);
     int rc = download(h, part.data(), h->lay.loss_part, part.size() * 4);
     if (rc) return rc;
     double s[5] = {0, 0, 0, 0, 0};
-    for (int b = 0; b < h->loss_blocks; ++b) for (int k = 0; k < 5; ++k) s[k] += (double)part[(size_t)b * 8 + k];
+    for (int b = 0; b < blocks; ++b) for (int k = 0; k < 5; ++k) s[k] += (double)part[(size_t)b * 8 + k];
     const double M = (double)h->B * h->T;
     out->policy_loss = s[0] / M; out->value_loss = s[1] / M; out->entropy_loss = s[2] / M;
     out->loss = out->policy_loss + out->value_loss + out->entropy_loss;

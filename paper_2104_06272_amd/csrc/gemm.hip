@@ -197,7 +197,7 @@ hipError_t launch_backward(anakin* h)
             GemmNtArgs g;
             g.M = M; g.K = n.dims[l]; g.N = n.dims[l + 1];
             g.dy = at<const float>(h, L.dz[l]);
-            g.w = at<const float>(h, L.theta) + n.w_off[l];
+            g.w = at<const float>(h, L.w_src) + n.w_off[l];
             g.x = at<const float>(h, L.act[l - 1]);
             g.dx = at<float>(h, L.dz[l - 1]);
             g.bf16 = n.bf16;

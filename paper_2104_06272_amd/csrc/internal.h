@@ -99,6 +99,8 @@ struct AdamArgs {
 
 struct Layout {
     size_t theta, grad, m, v, w_bf16, wt_bf16;
+    size_t theta0, w0_bf16;      // copies of theta / w_bf16 taken before the first of several updates on one unroll
+    size_t w_src, w16_src;       // where the backward kernels read weights: theta / w_bf16, or the copies
     size_t s0, f0, f1, walls;
     size_t tr_s0, tr_f0, tr_f1, tr_act, tr_eps, tr_actf, tr_rew, tr_done, tr_val, tr_head;
     size_t adv, ret, dhead;
@@ -132,6 +134,8 @@ struct anakin {
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
     int head_fan;                 // first-stage workgroups per split of the head-gradient pass
+    int n_updates;                // Adam updates per unroll (consecutive time chunks of the unroll), 1 by default
+    int sub_splits[ank::MAX_REGIONS], sub_splits_w, sub_head_fan, sub_loss_blocks;   // split plan of one chunk
     int splits_w;                 // maze first layer of a bf16 net: split count of the wall-plane product (0: one product
                                   // over all observation rows); splits[0] is then the split count of the agent-plane product
     int bf16_path;                // the bf16 matrix-core kernels support this net

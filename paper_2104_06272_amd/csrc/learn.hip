@@ -702,7 +702,7 @@ hipError_t launch_learn_one_layer(anakin* h)
     OneLayerArgs a;
     a.M = h->B * h->T; a.D = n.dims[0]; a.H = n.dims[1]; a.NH = n.NH; a.NHP = n.NHP;
     a.rows = a.M / h->splits[0];
-    a.theta = at<const float>(h, L.theta); a.w1_off = n.w_off[0]; a.b1_off = n.b_off[0]; a.wh_off = n.wh_off;
+    a.theta = at<const float>(h, L.w_src); a.w1_off = n.w_off[0]; a.b1_off = n.b_off[0]; a.wh_off = n.wh_off;
     a.dhead = at<const float>(h, L.dhead);
     a.partial0 = at<float>(h, L.part[0]); a.partial1 = at<float>(h, L.part[1]);
     a.obs.env = h->env; a.obs.s0 = at<const uint32_t>(h, L.tr_s0);
@@ -859,7 +859,7 @@ hipError_t launch_head_backward(anakin* h)
     const int stage1 = splits * fan;                        // workgroups of the streaming pass
     a.rows = a.M / stage1;
     a.h = at<const float>(h, L.act[n.L - 1]); a.dhead = at<const float>(h, L.dhead);
-    a.wh = at<const float>(h, L.theta) + n.wh_off;
+    a.wh = at<const float>(h, L.w_src) + n.wh_off;
     a.dz = at<float>(h, L.dz[n.L - 1]);
     a.partial = fan > 1 ? at<float>(h, L.head_stage) : at<float>(h, L.part[n.L]);
     a.bf16 = n.bf16;

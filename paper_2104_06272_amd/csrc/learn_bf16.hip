@@ -754,7 +754,7 @@ hipError_t launch_backward_bf16(anakin* h)
         const int stage1 = h->splits[n.L] * h->head_fan;
         a.rows = M / stage1;
         a.hP = actP(n.L - 1); a.dhead = at<const float>(h, L.dhead);
-        a.wh16 = at<const uint16_t>(h, L.w_bf16) + n.wh_off;
+        a.wh16 = at<const uint16_t>(h, L.w16_src) + n.wh_off;
         a.dzR = dzR(n.L - 1); a.dzP = dzP(n.L - 1);
         a.partial = h->head_fan > 1 ? at<float>(h, L.head_stage) : at<float>(h, L.part[n.L]);
         {
@@ -844,7 +844,7 @@ hipError_t launch_backward_bf16(anakin* h)
             GemmNtBf16Args g;
             g.M = M; g.K = n.dims[l]; g.N = n.dims[l + 1];
             g.dyR = dzR(l);
-            g.w16 = at<const uint16_t>(h, L.w_bf16) + n.w_off[l];
+            g.w16 = at<const uint16_t>(h, L.w16_src) + n.w_off[l];
             g.hP = actP(l - 1);
             g.dxR = l - 1 > 0 ? dzR(l - 1) : nullptr;               // dZ of the first layer feeds only dW products, which read the packed form
             g.dxP = dzP(l - 1);

@@ -281,6 +281,54 @@ def test_full_size_maze_bf16_sampled_envs(gpu, orc):
     _forced_lockstep(gpu, orc, cfg, 0, 2, sel=sel, learn=False)
 
 
+N_UPDATE_CASES = {
+    # name: (cfg, seed, N, tolerance)
+    "catch_256x256_N2": (variant("catch_4096", B=128, T=8), 0, 2, TOL_F32),
+    "catch_tiny_net_N4": (variant("catch_262144", B=512, T=16), 1, 4, TOL_F32),
+    "pendulum_N2": (variant("pendulum_8192", B=128, T=8), 2, 2, TOL_F32),
+    "maze_fp32_N2": (variant("maze_16384", hidden=[64, 64], B=64, T=16, dtype="fp32", max_steps=20), 3, 2, TOL_F32),
+}
+
+
+@pytest.mark.parametrize("case", list(N_UPDATE_CASES))
+def test_n_updates_per_unroll(gpu, orc, case):
+    """N Adam updates on one unroll, one per consecutive time chunk, gradients at the acting-time parameters
+    (paper section 4): parameters, moments, loss and the last chunk's gradient against the oracle's learn_n."""
+    cfg, seed, N, tol = N_UPDATE_CASES[case]
+    say(f"[n updates] {case} seed={seed} N={N} B={cfg['B']} T={cfg['T']}")
+    g = gpu.Anakin(cfg, seed=seed); o = orc.Oracle(cfg, seed=seed)
+    g.set_updates_per_unroll(N)
+    kind = cfg["env"]["kind"]
+    for u in range(2):
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout(); o.rollout()
+        PT.assert_rollout_equal(g, o, kind)
+        g.learn(); o.learn_n(N)
+        e_g, e_p = PT.assert_learn_close(g, o, tol)
+        say(f"  unroll {u}: gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
+    with pytest.raises(gpu.AnakinError):
+        g.set_updates_per_unroll(3 if cfg["T"] % 3 else 5)
+    g.set_updates_per_unroll(1)                   # and back to one update per unroll
+    PT.sync_oracle_from_gpu(g, o)
+    g.rollout(); o.rollout(); g.learn(); o.learn()
+    PT.assert_learn_close(g, o, tol)
+    g.close()
+
+
+def test_n_updates_per_unroll_bf16(gpu, orc):
+    """the same on the bf16 matrix-core path (logit-forced unroll), 256-wide maze net, N = 3"""
+    cfg = variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20)
+    g = gpu.Anakin(cfg, seed=6); o = orc.Oracle(cfg, seed=6)
+    g.set_updates_per_unroll(3)
+    PT.sync_oracle_from_gpu(g, o)
+    g.rollout()
+    tr = g.trajectory()
+    o.rollout(forced_head=tr["head"])
+    g.learn(); o.learn_n(3)
+    PT.assert_learn_close(g, o, TOL_BF16)
+    g.close()
+
+
 def test_determinism_and_resume(gpu):
     """Same seed twice gives the same bytes; a byte copy of the workspace plus the two host counters
     resumes bit-exactly (explicit, device-resident state; counter-based RNG)."""
