@@ -55,6 +55,9 @@ LOCKSTEP_CASES = {
     # 512 -> 256: the weights-resident dX kernel with two column blocks, tiled dW; three 256-wide layers: resident both ways
     "catch_512x256": (variant("catch_4096", hidden=[512, 256], B=64, T=10), 3, 2, TOL_F32),
     "catch_256x256x256": (variant("catch_4096", hidden=[256, 256, 256], B=96, T=9), 4, 2, TOL_F32),
+    # 512-wide last layer: two column blocks in the head pass; 512-wide first layer of the pendulum kernel
+    "catch_256x512": (variant("catch_4096", hidden=[256, 512], B=64, T=10), 5, 2, TOL_F32),
+    "pendulum_512x256": (variant("pendulum_8192", hidden=[512, 256], B=64, T=12, max_steps=9), 6, 2, TOL_F32),
 }
 
 
