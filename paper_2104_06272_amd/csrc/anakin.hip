@@ -166,7 +166,13 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         }
     }
     int fan = 1;
-    while (fan < 16 && (M / hq) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 2 * hq) fan *= 2;
+    bool one_stage = false;
+    if (!ns.bf16 && ns.dims[ns.L] % 64 == 0 && M % 32 == 0) {
+        // matrix-core head pass: two workgroups per CU stream enough on their own, and their partials go straight to Adam
+        const int s = pick_divisor_splits(M, 32, 512);
+        if (s >= 64) { splits[ns.L] = s; one_stage = true; }
+    }
+    while (!one_stage && fan < 16 && (M / hq) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 2 * hq) fan *= 2;
     *head_fan = fan;
     *loss_blocks = (M + WG - 1) / WG;
 }
