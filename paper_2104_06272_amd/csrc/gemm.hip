@@ -10,7 +10,8 @@
 // state snapshot while the tile is loaded.
 //
 // This file holds the vector-ALU versions (64x64 tiles, 4x4 per lane); the
-// matrix-core versions are in gemm_mfma.hip and share the argument blocks.
+// matrix-core versions are in gemm_mfma.hip (tiled) and gemm_resident.hip
+// (persistent, 256-wide layers) and share the argument blocks.
 #include "gemm.h"
 
 namespace ank {
