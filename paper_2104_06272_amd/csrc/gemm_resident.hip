@@ -91,13 +91,23 @@ __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
         const float* a_rd = cur + l32 * NTR_LD + 4 * kg;
+        // the LDS read of group p + 2 is issued before the MFMAs of group p: its latency hides under eight MFMAs
+        f4v_r av0 = *reinterpret_cast<const f4v_r*>(a_rd), av1 = *reinterpret_cast<const f4v_r*>(a_rd + 8);
 #pragma unroll
-        for (int p = 0; p < 32; ++p) {
-            const float4 av = *reinterpret_cast<const float4*>(a_rd + 8 * p);
-            acc = mfma_r(av.x, wreg[4 * p], acc);
-            acc = mfma_r(av.y, wreg[4 * p + 1], acc);
-            acc = mfma_r(av.z, wreg[4 * p + 2], acc);
-            acc = mfma_r(av.w, wreg[4 * p + 3], acc);
+        for (int p = 0; p < 32; p += 2) {
+            const f4v_r nx0 = *reinterpret_cast<const f4v_r*>(a_rd + 8 * (p + 2 < 32 ? p + 2 : 0));
+            __builtin_amdgcn_sched_barrier(0);
+            acc = mfma_r(av0[0], wreg[4 * p], acc);
+            acc = mfma_r(av0[1], wreg[4 * p + 1], acc);
+            acc = mfma_r(av0[2], wreg[4 * p + 2], acc);
+            acc = mfma_r(av0[3], wreg[4 * p + 3], acc);
+            const f4v_r nx1 = *reinterpret_cast<const f4v_r*>(a_rd + 8 * (p + 3 < 32 ? p + 3 : 1));
+            __builtin_amdgcn_sched_barrier(0);
+            acc = mfma_r(av1[0], wreg[4 * p + 4], acc);
+            acc = mfma_r(av1[1], wreg[4 * p + 5], acc);
+            acc = mfma_r(av1[2], wreg[4 * p + 6], acc);
+            acc = mfma_r(av1[3], wreg[4 * p + 7], acc);
+            av0 = nx0; av1 = nx1;
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -159,18 +169,29 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
         __builtin_amdgcn_sched_barrier(0);
         const float* xs = Xs + t * RT * 256 + wm * 128 + l32;
         const float* ys = Ys + t * RT * 256 + wn * 64 + l32;
+        // operands of step ks + 2 are read from LDS before the eight MFMAs of step ks are issued
+        float av[4], bv[2];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) av[q] = xs[kg * 256 + 32 * q];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) bv[q] = ys[kg * 256 + 32 * q];
 #pragma unroll
         for (int ks = 0; ks < RT; ks += 2) {
-            const int k = ks + kg;
-            float av[4], bv[2];
+            const int kn = (ks + 2 < RT ? ks + 2 : 0) + kg;
+            float an[4], bn[2];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) av[q] = xs[k * 256 + 32 * q];
+            for (int q = 0; q < 4; ++q) an[q] = xs[kn * 256 + 32 * q];
 #pragma unroll
-            for (int q = 0; q < 2; ++q) bv[q] = ys[k * 256 + 32 * q];
+            for (int q = 0; q < 2; ++q) bn[q] = ys[kn * 256 + 32 * q];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = mfma_r(av[i], bv[j], acc[i][j]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) av[q] = an[q];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) bv[q] = bn[q];
         }
         if (m0 + RT < m_end) store(t ^ 1);
         __syncthreads();
