@@ -608,9 +608,17 @@ __device__ __forceinline__ void resident_m16(const float (&wreg)[KS][NT], const 
         for (int t = 0; t < NT; ++t) { acc[t][0] = bv[t]; acc[t][1] = bv[t]; acc[t][2] = bv[t]; acc[t][3] = bv[t]; }
     }
     const float* xp = X + (lane & 15) * ldx + kq;
+    // the activation operand of step s + PF is read from LDS before the MFMAs of step s are issued: with one
+    // wavefront per SIMD nothing else would hide the LDS latency
+    constexpr int PF = 4;
+    float ap[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) ap[u] = xp[4 * u];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        const float av = xp[4 * s];
+        const float av = ap[s % PF];
+        ap[s % PF] = xp[4 * (s + PF < KS ? s + PF : 0)];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wreg[s][t], acc[t], 0, 0, 0);
     }
@@ -641,9 +649,15 @@ __device__ __forceinline__ void resident_m32(const float (&wreg)[KS][NT], const 
             for (int r = 0; r < 16; ++r) acc[t][r] = bv[t];
     }
     const float* xp = X + (lane & 31) * ldx + kq;
+    constexpr int PF = 4;                                        // LDS reads run this many steps ahead of their MFMAs
+    float ap[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) ap[u] = xp[2 * u];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        const float av = xp[2 * s];
+        const float av = ap[s % PF];
+        ap[s % PF] = xp[2 * (s + PF < KS ? s + PF : 0)];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, wreg[s][t], acc[t], 0, 0, 0);
     }
