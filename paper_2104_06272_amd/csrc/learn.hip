@@ -512,14 +512,18 @@ __global__ __launch_bounds__(512) void first_layer_grad_mfma(const FirstGradArgs
         xs[buf][1][wave][lane] = x1;
     };
     auto compute = [&](const float (&d)[32], int buf) {
+        // the board operand of group g + 1 is read from LDS before the MFMAs of group g are issued
+        f4v_l x0 = xs[buf][0][0][lane], x1 = xs[buf][1][0][lane];
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
-            const f4v_l x0 = xs[buf][0][g][lane], x1 = xs[buf][1][g][lane];
+            const f4v_l n0 = xs[buf][0][g + 1 < 8 ? g + 1 : 0][lane], n1 = xs[buf][1][g + 1 < 8 ? g + 1 : 0][lane];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[e], d[4 * g + e], acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[e], d[4 * g + e], acc1, 0, 0, 0);
             }
+            x0 = n0; x1 = n1;
         }
     };
     float dA[32], dB[32];

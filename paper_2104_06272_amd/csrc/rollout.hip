@@ -378,40 +378,40 @@ __device__ __forceinline__ float heads_fma(const float4 (&xv)[U], const float4 (
     }
     return acc;
 }
-// U: float4 per register block (a block covers 4U values of k; HL is a multiple of 4U)
-// The same chains on the matrix cores for tiles of 16 envs: v_mfma_f32_16x16x4_f32 adds its four
-// products to the accumulator in ascending k, and chained instructions continue the same chain, so
-// 64 of them starting from the bias reproduce acc = fmaf(x_k, w_k, acc), k = 0..255, bit for bit --
-// at four steps per instruction instead of one dependent fma per step.  Lane l feeds
-// A[env l%16][k l/16] and B[k l/16][head l%16]; accumulator register r is D[env 4*(l/16) + r][head l%16].
-// Wavefront w takes envs 16w..16w+15; heads beyond NH are zero columns.
 typedef float f4v_h __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void heads_mfma16(const float* __restrict__ X, int ldx, const float* __restrict__ whT, int ldw,
-                                             const float* __restrict__ bhs, float* __restrict__ heads,
-                                             int HL, int NH, int NHP, int TM, int tid)
+// The chains on the vector ALU with the operand reads taken off the critical path: lane (m, j)
+// keeps a ring of PF blocks of four k (16-byte LDS reads of row m of X and row j of the transposed
+// head matrix) and refills each slot, PF blocks ahead, before the four dependent fused multiply-adds
+// of the block it just handed over.  HL is a multiple of 4 * PF.
+template <int PF, int HL>
+__device__ __forceinline__ void heads_pipe(const float* __restrict__ X, int ldx, const float* __restrict__ whT, int ldw,
+                                           const float* __restrict__ bhs, float* __restrict__ heads,
+                                           int NH, int NHP, int TM, int tid)
 {
-    const int wave = tid >> 6, lane = tid & 63;
-    if (wave * 16 >= TM) return;
-    const int c16 = lane & 15, kq = lane >> 4;
-    const bool real = c16 < NH;
-    const float* x = X + (wave * 16 + c16) * ldx + kq;
-    const float* w = whT + (real ? c16 : 0) * ldw + kq;
-    const float b = real ? bhs[c16] : 0.0f;
-    f4v_h acc = {b, b, b, b};
-    constexpr int UB = 16;                                      // steps per block of operand loads
-    for (int s0 = 0; s0 < HL; s0 += 4 * UB) {
-        float xv[UB], wv[UB];
+    constexpr int S = HL >> 2;
+    for (int idx = tid; idx < TM * NH; idx += WG) {
+        const int m = idx % TM, j = idx / TM;
+        const f4v_h* x = reinterpret_cast<const f4v_h*>(X + m * ldx);
+        const f4v_h* w = reinterpret_cast<const f4v_h*>(whT + j * ldw);
+        f4v_h xr[PF], wr[PF];
 #pragma unroll
-        for (int u = 0; u < UB; ++u) { xv[u] = x[s0 + 4 * u]; wv[u] = real ? w[s0 + 4 * u] : 0.0f; }
+        for (int u = 0; u < PF; ++u) { xr[u] = x[u]; wr[u] = w[u]; }
+        float acc = bhs[j];
 #pragma unroll
-        for (int u = 0; u < UB; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xv[u], wv[u], acc, 0, 0, 0);
-    }
-    if (real) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) heads[(wave * 16 + 4 * kq + r) * NHP + c16] = acc[r];
+        for (int s = 0; s < S; ++s) {
+            const f4v_h xv = xr[s % PF], wv = wr[s % PF];
+            if (s + PF < S) { xr[s % PF] = x[s + PF]; wr[s % PF] = w[s + PF]; }
+            __builtin_amdgcn_sched_barrier(0);
+            acc = fmaf(xv[0], wv[0], acc);
+            acc = fmaf(xv[1], wv[1], acc);
+            acc = fmaf(xv[2], wv[2], acc);
+            acc = fmaf(xv[3], wv[3], acc);
+        }
+        heads[m * NHP + j] = acc;
     }
 }
 
+// U: float4 per register block (a block covers 4U values of k; HL is a multiple of 4U)
 template <int U>
 __device__ __forceinline__ void heads_chain(const float* __restrict__ X, int ldx, const float* __restrict__ whT, int ldw,
                                             const float* __restrict__ bhs, float* __restrict__ heads,
@@ -435,6 +435,18 @@ __device__ __forceinline__ void heads_chain(const float* __restrict__ X, int ldx
             }
         }
         heads[m * NHP + j] = acc;
+    }
+}
+
+__device__ __forceinline__ void run_heads(const float* X, int ldx, const float* whT, int ldw, const float* bhs, float* heads,
+                                          int HL, int NH, int NHP, int TM, int tid)
+{
+    switch (HL) {
+        case 64: heads_pipe<4, 64>(X, ldx, whT, ldw, bhs, heads, NH, NHP, TM, tid); break;
+        case 128: heads_pipe<4, 128>(X, ldx, whT, ldw, bhs, heads, NH, NHP, TM, tid); break;
+        case 256: heads_pipe<4, 256>(X, ldx, whT, ldw, bhs, heads, NH, NHP, TM, tid); break;
+        case 512: heads_pipe<4, 512>(X, ldx, whT, ldw, bhs, heads, NH, NHP, TM, tid); break;
+        default: heads_chain<8>(X, ldx, whT, ldw, bhs, heads, HL, NH, NHP, TM, tid);
     }
 }
 
@@ -516,7 +528,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
             __syncthreads();
             float* tmp = cur; cur = nxt; nxt = tmp;
         }
-        heads_chain<8>(cur, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
+        run_heads(cur, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
         if (t < T) {
@@ -775,8 +787,7 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         else resident_m16<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
         __syncthreads();
         PH(2);
-        if (TM % 16 == 0 && HL % 64 == 0) heads_mfma16(bufB, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
-        else heads_chain<(RK * RN >= 256 * 256 ? 2 : 8)>(bufB, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
+        heads_pipe<4, HL>(bufB, ldx, whs, ldw, bhs, heads, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
         if (t < T) {
