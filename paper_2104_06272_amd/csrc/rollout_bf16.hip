@@ -33,6 +33,11 @@ namespace ank {
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
+#ifdef ANK_EXP_NOSTORE
+constexpr bool EXP_NOSTORE = true;
+#else
+constexpr bool EXP_NOSTORE = false;
+#endif
 constexpr int BTM = 64;                 // envs per workgroup
 constexpr int BWG = 512;                // threads per workgroup: two wavefronts per SIMD
 constexpr int BOBS = 12;                // observation words per env (as in the fp32 kernels)
@@ -136,6 +141,103 @@ __device__ __forceinline__ void bf16_layer(const uint16_t* __restrict__ X, uint1
         }
 }
 
+// The same layer for nets whose hidden layers all have this width, with the weight stream running
+// across layer boundaries: the first two blocks of the next layer's weights are requested before this
+// layer's activations are stored.  Loads and stores of a wavefront complete in issue order, so a load
+// issued behind the activation stores is not seen as complete until the stores are acknowledged;
+// issued ahead of them it costs nothing, and the next layer starts without waiting.
+// w0/w1: on entry steps 0..2U-1 of this layer (bf16_layer_first loads them for the first one); on exit,
+// with Wt_next, steps 0..2U-1 of the next.
+template <int NT>
+__device__ __forceinline__ void bf16_layer_stream(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int ldx,
+                                                  const uint16_t* __restrict__ Wt, const uint16_t* __restrict__ Wt_next,
+                                                  const float* __restrict__ bias, int K, int N, int wave, int lane,
+                                                  uint16_t* __restrict__ gP, size_t g8,
+                                                  bf8 (&w0)[4][NT], bf8 (&w1)[4][NT])
+{
+    constexpr int U = 4;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int n0 = wave * 32 * NT;
+    if (n0 >= N) return;
+    f16v acc[2][NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const float b = bias[n0 + 32 * t + l32];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc[0][t][r] = b; acc[1][t][r] = b; }
+    }
+    const uint16_t* xa = X + l32 * ldx + 8 * kg;
+    const int KS = K >> 4;                                       // the next layer has the same K and N
+    const size_t wave_off = ((size_t)(n0 >> 5) * KS << 9) + lane * 8;
+    const uint16_t* wb = Wt + wave_off;
+    const uint16_t* wn = Wt_next ? Wt_next + wave_off : wb;
+    auto load = [&](bf8 (&d)[U][NT], const uint16_t* base, int s) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) d[u][t] = *reinterpret_cast<const bf8*>(base + ((size_t)(t * KS + s + u) << 9));
+    };
+    auto compute = [&](const bf8 (&d)[U][NT], int s) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bf8 a0 = *reinterpret_cast<const bf8*>(xa + 16 * (s + u));
+            const bf8 a1 = *reinterpret_cast<const bf8*>(xa + 32 * ldx + 16 * (s + u));
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, d[u][t], acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, d[u][t], acc[1][t], 0, 0, 0);
+            }
+        }
+    };
+    for (int s = 0; s < KS; s += 2 * U) {
+        const bool last = s + 2 * U >= KS;
+        __builtin_amdgcn_sched_barrier(0);
+        compute(w0, s);
+        if (!last) load(w0, wb, s + 2 * U);
+        else if (Wt_next) load(w0, wn, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(w1, s + U);
+        if (!last) load(w1, wb, s + 3 * U);
+        else if (Wt_next) load(w1, wn, U);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int col = n0 + 32 * t + l32;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int row = mt * 32 + 8 * g + 4 * kg;
+                const uint32_t p01 = pack_bf16x2(relu(acc[mt][t][4 * g]), relu(acc[mt][t][4 * g + 1]));
+                const uint32_t p23 = pack_bf16x2(relu(acc[mt][t][4 * g + 2]), relu(acc[mt][t][4 * g + 3]));
+                Y[(row + 0) * ldx + col] = (uint16_t)p01; Y[(row + 1) * ldx + col] = (uint16_t)(p01 >> 16);
+                Y[(row + 2) * ldx + col] = (uint16_t)p23; Y[(row + 3) * ldx + col] = (uint16_t)(p23 >> 16);
+                if (gP) {
+                    u32v2 pv; pv[0] = p01; pv[1] = p23;
+                    __builtin_nontemporal_store(pv, reinterpret_cast<u32v2*>(gP + ((g8 + mt * 4 + g) * N + col) * 8 + 4 * kg));
+                }
+            }
+        }
+}
+
+template <int NT>
+__device__ __forceinline__ void bf16_layer_first(const uint16_t* __restrict__ Wt, int K, int N, int wave, int lane,
+                                                 bf8 (&w0)[4][NT], bf8 (&w1)[4][NT])
+{
+    const int n0 = wave * 32 * NT;
+    if (n0 >= N) return;
+    const int KS = K >> 4;
+    const uint16_t* wb = Wt + ((size_t)(n0 >> 5) * KS << 9) + lane * 8;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            w0[u][t] = *reinterpret_cast<const bf8*>(wb + ((size_t)(t * KS + u) << 9));
+            w1[u][t] = *reinterpret_cast<const bf8*>(wb + ((size_t)(t * KS + 4 + u) << 9));
+        }
+}
+
 __device__ __forceinline__ void run_bf16_layer(const uint16_t* X, uint16_t* Y, int ldx, const uint16_t* Wt, const float* bias,
                                                int K, int N, int wave, int lane, uint16_t* gP, size_t g8)
 {
@@ -145,7 +247,7 @@ __device__ __forceinline__ void run_bf16_layer(const uint16_t* X, uint16_t* Y, i
 
 // H1: width of the first hidden layer (128, 256 or 512).  Thread (pair of columns cp, env slice eq)
 // owns columns 2*cp, 2*cp+1 of the first layer for EPT = H1/16 consecutive environments.
-template <int ENV, int H1>
+template <int ENV, int H1, bool UNI>
 __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args a)
 {
     extern __shared__ uint4 smem4[];
@@ -256,7 +358,18 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
 #else
 #define PH(i) do { } while (0)
 #endif
+    const int tid_outer = tid;
     for (int t = 0; t <= T; ++t) {
+        // everything derived from the thread index is recomputed every step from a value the compiler
+        // cannot see through: dozens of loop-invariant addresses would otherwise be kept in registers
+        // across the whole time loop, on top of the 2 * EPT prefix values, and spilled
+        int tid_step = tid_outer;
+        asm volatile("" : "+v"(tid_step));
+        const int tid = tid_step, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int cp = tid % (H1 / 2), eq = tid / (H1 / 2);
+        const int c = 2 * cp, e0 = eq * EPT;
+        const bool owner = tid < BTM;
+        const int b = b0 + tid;
         const size_t tb = (size_t)t * B + b;
         if (owner) {
             tp.tr_s0[tb] = st.s0;
@@ -299,7 +412,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                         r1[ENV == ENV_CATCH ? m : 0] = *reinterpret_cast<const uint32_t*>(w1 + (size_t)obs[(e0 + m) * BOBS + 1] * H1 + c);
                 }
             }
-            uint16_t* actP = keep ? reinterpret_cast<uint16_t*>(tp.act[0]) : nullptr;
+            uint16_t* actP = (keep && !EXP_NOSTORE) ? reinterpret_cast<uint16_t*>(tp.act[0]) : nullptr;
 #pragma unroll
             for (int m0 = 0; m0 < EPT; m0 += 8) {
                 float v[8][2];
@@ -334,7 +447,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                     *reinterpret_cast<uint32_t*>(bufA + (e0 + m0 + 2 * q + 1) * ldx + c) = (px[q] >> 16) | (py[q] & 0xffff0000u);
                 }
                 if (actP) {
-                    u32v4* dst = reinterpret_cast<u32v4*>(actP + ((g8 + ((e0 + m0) >> 3)) * H1 + c) * 8);
+                    u32v4* dst = reinterpret_cast<u32v4*>(actP + ((g8 + (e0 >> 3)) * H1 + c) * 8) + (size_t)(m0 >> 3) * H1;   // 16-byte units: one group of eight samples is H1 of them
                     u32v4 vx4, vy4;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) { vx4[q] = px[q]; vy4[q] = py[q]; }
@@ -347,12 +460,25 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
         PH(1);
         uint16_t* cur = bufA;
         uint16_t* nxt = bufB;
-        for (int l = 1; l < L; ++l) {
-            const int K = a.net.dims[l], N = a.net.dims[l + 1];
-            run_bf16_layer(cur, nxt, ldx, a.wt + a.net.w_off[l], a.theta + a.net.b_off[l], K, N, wave, lane,
-                           keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8);
-            __syncthreads();
-            uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+        if (UNI) {
+            constexpr int NTU = H1 >= 512 ? 2 : 1;
+            bf8 w0[4][NTU], w1[4][NTU];
+            bf16_layer_first<NTU>(a.wt + a.net.w_off[1], H1, H1, wave, lane, w0, w1);
+            for (int l = 1; l < L; ++l) {
+                bf16_layer_stream<NTU>(cur, nxt, ldx, a.wt + a.net.w_off[l], l + 1 < L ? a.wt + a.net.w_off[l + 1] : nullptr,
+                                       a.theta + a.net.b_off[l], H1, H1, wave, lane,
+                                       (keep && !EXP_NOSTORE) ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8, w0, w1);
+                __syncthreads();
+                uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+            }
+        } else {
+            for (int l = 1; l < L; ++l) {
+                const int K = a.net.dims[l], N = a.net.dims[l + 1];
+                run_bf16_layer(cur, nxt, ldx, a.wt + a.net.w_off[l], a.theta + a.net.b_off[l], K, N, wave, lane,
+                               (keep && !EXP_NOSTORE) ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8);
+                __syncthreads();
+                uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+            }
         }
         PH(3);
         // ---- heads: wavefront (tile, quarter) sums one quarter of the last layer for 32 envs ----
@@ -365,6 +491,10 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             const uint16_t* xa = cur + (tile * 32 + l32) * ldx + kq * kq_len + 8 * kg;
             const uint16_t* wbs = whs + (l32 & 7) * ldh + kq * kq_len + 8 * kg;
             const bool real = l32 < 8;
+            // one base address, recomputed every step, and constant offsets from it: sixteen loop-invariant
+            // addresses would otherwise be kept (and spilled) across the time loop
+            int hp_base = (kq * BTM + tile * 32 + 4 * kg) * 8 + l32;
+            asm volatile("" : "+v"(hp_base));
             for (int k0 = 0; k0 < kq_len; k0 += 16) {
                 const bf8 av = *reinterpret_cast<const bf8*>(xa + k0);
                 bf8 bvv = *reinterpret_cast<const bf8*>(wbs + k0);
@@ -376,7 +506,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             }
             if (real) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) hp[(kq * BTM + tile * 32 + 8 * (r >> 2) + 4 * kg + (r & 3)) * 8 + l32] = acc[r];
+                for (int r = 0; r < 16; ++r) hp[hp_base + (8 * (r >> 2) + (r & 3)) * 8] = acc[r];
             }
         }
         __syncthreads();
@@ -477,14 +607,17 @@ hipError_t launch_rollout_bf16(anakin* h)
         hipLaunchKernelGGL(kern, dim3(h->B / BTM), dim3(BWG), lds, h->stream, a);
         return hipGetLastError();
     };
-#define ANK_BF16_CASE(ENVK) \
-    (H1 == 128 ? launch(rollout_bf16_kernel<ENVK, 128>) : H1 == 256 ? launch(rollout_bf16_kernel<ENVK, 256>) : launch(rollout_bf16_kernel<ENVK, 512>))
+    bool uni = true;                                             // every hidden layer H1 wide: the weight stream runs across layers
+    for (int l = 2; l <= h->net.L; ++l) uni = uni && h->net.dims[l] == H1;
+#define ANK_BF16_W(ENVK, W) (uni ? launch(rollout_bf16_kernel<ENVK, W, true>) : launch(rollout_bf16_kernel<ENVK, W, false>))
+#define ANK_BF16_CASE(ENVK) (H1 == 128 ? ANK_BF16_W(ENVK, 128) : H1 == 256 ? ANK_BF16_W(ENVK, 256) : ANK_BF16_W(ENVK, 512))
     switch (h->env.kind) {
         case ENV_CATCH:    return ANK_BF16_CASE(ENV_CATCH);
         case ENV_PENDULUM: return ANK_BF16_CASE(ENV_PENDULUM);
         default:           return ANK_BF16_CASE(ENV_MAZE);
     }
 #undef ANK_BF16_CASE
+#undef ANK_BF16_W
 }
 
 }  // namespace ank
