@@ -253,6 +253,8 @@ typedef struct {
     double *adv, *ret;             /* [T][B] */
     double loss[4];                /* total, policy, value, entropy terms (means) */
     int have_traj;
+    double *cur_head;              /* [T+1][B][NH] head outputs of the learner's parameters (off-policy update) */
+    double *rho;                   /* [T][B] truncated importance weights of the last off-policy update */
 } orc_t;
 
 /* ------------------------------------------------------------------------- */
@@ -564,7 +566,7 @@ void orc_destroy(orc_t* h)
     free(h->si); free(h->sf); free(h->walls);
     free(h->tr_si); free(h->tr_sf); free(h->tr_act); free(h->tr_actf); free(h->tr_eps); free(h->tr_z);
     free(h->tr_rew); free(h->tr_done); free(h->tr_val); free(h->tr_head);
-    free(h->adv); free(h->ret);
+    free(h->adv); free(h->ret); free(h->cur_head); free(h->rho);
     free(h);
 }
 
@@ -616,6 +618,8 @@ orc_t* orc_create(const orc_env_cfg* env, const orc_net_cfg* net, int B, int T, 
     h->tr_head = (float*)zalloc(t1n * h->NH * sizeof(float));
     h->adv = (double*)zalloc(tn * sizeof(double));
     h->ret = (double*)zalloc(tn * sizeof(double));
+    h->cur_head = (double*)zalloc(t1n * h->NH * sizeof(double));
+    h->rho = (double*)zalloc(tn * sizeof(double));
     init_params(h);
     for (int b = 0; b < B; ++b) {
         uint32_t w4[4];
@@ -660,6 +664,8 @@ float* orc_traj_head(orc_t* h) { return h->tr_head; }
 double* orc_adv(orc_t* h) { return h->adv; }
 double* orc_ret(orc_t* h) { return h->ret; }
 double* orc_loss(orc_t* h) { return h->loss; }
+double* orc_cur_head(orc_t* h) { return h->cur_head; }
+double* orc_rho(orc_t* h) { return h->rho; }
 
 /* observation of env b in its current state, and the forward pass on it */
 void orc_observe(const orc_t* h, int b, float* x)
@@ -775,16 +781,11 @@ static double qround(const orc_t* h, double v)
     return h->net.dtype == 1 ? (double)orc_bf16_round((float)v) : v;
 }
 
-/* Loss and gradient over the samples tb_begin <= t*B + b < tb_end (mean over    */
-/* those samples), with the parameters theta_src.                              */
-static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begin, size_t tb_end)
+/* the parameters as the binary64 forward pass sees them (bfloat16-rounded weights when dtype = 1) */
+static double* forward_params64(const orc_t* h, const float* theta_src)
 {
-    int B = h->B, NH = h->NH, L = h->L;
-    size_t n = tb_end - tb_begin;
-    double inv_n = 1.0 / (double)n;
-    double beta = (double)h->net.entropy_coef, cv = (double)h->net.value_coef;
-    double* g = (double*)zalloc(h->P * sizeof(double));
-    double* wq = (double*)zalloc(h->P * sizeof(double));     /* parameters as the forward sees them */
+    int L = h->L, NH = h->NH;
+    double* wq = (double*)zalloc(h->P * sizeof(double));
     for (size_t i = 0; i < h->P; ++i) wq[i] = (double)theta_src[i];
     if (h->net.dtype == 1) {
         for (int l = 0; l < L; ++l)
@@ -793,32 +794,51 @@ static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begi
         for (size_t i = 0; i < (size_t)h->dims[L] * NH; ++i)
             wq[h->wh_off + i] = (double)orc_bf16_round(theta_src[h->wh_off + i]);
     }
+    return wq;
+}
+
+/* binary64 forward pass from the stored state of sample tb: act[0] the observation, act[l] the
+ * output of hidden layer l, head the NH head outputs */
+static void forward64(const orc_t* h, const double* wq, size_t tb, double act[5][1024], double* head)
+{
+    int B = h->B, NH = h->NH, L = h->L;
     float xf[1024];
+    int b = (int)(tb % (size_t)B);
+    render_obs(h, b, h->tr_si + tb * 4, h->tr_sf + tb * 2, xf);
+    for (int k = 0; k < h->D; ++k) act[0][k] = (double)xf[k];
+    for (int l = 0; l < L; ++l) {
+        int K = h->dims[l], N = h->dims[l + 1];
+        const double* W = wq + h->w_off[l];
+        const double* bias = wq + h->b_off[l];
+        for (int j = 0; j < N; ++j) {
+            double s = bias[j];
+            for (int k = 0; k < K; ++k) s += act[l][k] * W[(size_t)k * N + j];
+            act[l + 1][j] = qround(h, s > 0.0 ? s : 0.0);
+        }
+    }
+    int K = h->dims[L];
+    const double* W = wq + h->wh_off;
+    for (int j = 0; j < NH; ++j) {
+        double s = wq[h->bh_off + j];
+        for (int k = 0; k < K; ++k) s += act[L][k] * W[(size_t)k * NH + j];
+        head[j] = s;
+    }
+}
+
+/* Loss and gradient over the samples tb_begin <= t*B + b < tb_end (mean over    */
+/* those samples), with the parameters theta_src.                              */
+static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begin, size_t tb_end)
+{
+    int NH = h->NH, L = h->L;
+    size_t n = tb_end - tb_begin;
+    double inv_n = 1.0 / (double)n;
+    double beta = (double)h->net.entropy_coef, cv = (double)h->net.value_coef;
+    double* g = (double*)zalloc(h->P * sizeof(double));
+    double* wq = forward_params64(h, theta_src);             /* parameters as the forward sees them */
     double act[5][1024], dz[2][1024], head[16], dhead[16];
     double Lp = 0, Lv = 0, Le = 0;
     for (size_t tb = tb_begin; tb < tb_end; ++tb) {
-        int b = (int)(tb % (size_t)B);
-        render_obs(h, b, h->tr_si + tb * 4, h->tr_sf + tb * 2, xf);
-        for (int k = 0; k < h->D; ++k) act[0][k] = (double)xf[k];
-        for (int l = 0; l < L; ++l) {
-            int K = h->dims[l], N = h->dims[l + 1];
-            const double* W = wq + h->w_off[l];
-            const double* bias = wq + h->b_off[l];
-            for (int j = 0; j < N; ++j) {
-                double s = bias[j];
-                for (int k = 0; k < K; ++k) s += act[l][k] * W[(size_t)k * N + j];
-                act[l + 1][j] = qround(h, s > 0.0 ? s : 0.0);
-            }
-        }
-        {
-            int K = h->dims[L];
-            const double* W = wq + h->wh_off;
-            for (int j = 0; j < NH; ++j) {
-                double s = wq[h->bh_off + j];
-                for (int k = 0; k < K; ++k) s += act[L][k] * W[(size_t)k * NH + j];
-                head[j] = s;
-            }
-        }
+        forward64(h, wq, tb, act, head);
         double A_ = h->adv[tb], G_ = h->ret[tb];
         double V = head[NH - 1];
         Lv += cv * (G_ - V) * (G_ - V);
@@ -941,6 +961,98 @@ int orc_learn_n(orc_t* h, int n_updates)
     free(theta0);
     h->have_traj = 0;
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Off-policy update (paper section 3.2 and section 4, "Sebulba": acting and   */
+/* learning are decoupled, the actor runs on parameters that lag the learner,   */
+/* and the agent the paper runs this way is IMPALA's V-trace).  Reading R-32:   */
+/* the targets are V-trace (Espeholt et al. 2018, equations 1 and 4) with the   */
+/* learner's own value estimates.  With pi the learner's policy, mu the         */
+/* behaviour policy that produced the stored action, disc = gamma (1 - done):   */
+/*   w_t   = pi(a_t|s_t) / mu(a_t|s_t)                                          */
+/*   rho_t = min(rho_bar, w_t),   c_t = lambda min(c_bar, w_t)                  */
+/*   delta_t = rho_t (r_t + disc_t V(s_{t+1}) - V(s_t))                          */
+/*   v_t - V(s_t) = delta_t + disc_t c_t (v_{t+1} - V(s_{t+1})),   v_T = V(s_T)  */
+/*   policy-gradient advantage  rho_t (r_t + disc_t v_{t+1} - V(s_t))            */
+/* and the update is the objective of R-24 with G := v and A := that advantage  */
+/* (both constants), at the learner's parameters.  mu comes from the head       */
+/* outputs stored at acting time, pi and V from a binary64 forward pass of the  */
+/* current parameters over the stored states.  For the tanh-Gaussian policy the  */
+/* ratio is taken at the stored pre-squash sample z (the squashing Jacobian is   */
+/* the same in both densities).  On-policy (w = 1) with lambda = 1 this is the   */
+/* update of orc_learn.                                                         */
+/* ------------------------------------------------------------------------- */
+static double log_prob_of_stored_action(const orc_t* h, const double* head, size_t tb)
+{
+    if (h->net.policy == POLICY_CATEGORICAL) {
+        int A = h->A, a = h->tr_act[tb];
+        double mx = head[0], Z = 0;
+        for (int i = 1; i < A; ++i) if (head[i] > mx) mx = head[i];
+        for (int i = 0; i < A; ++i) Z += exp(head[i] - mx);
+        return head[a] - mx - log(Z);
+    }
+    double mu = head[0], ls = head[1];
+    double lsc = ls < -5.0 ? -5.0 : (ls > 2.0 ? 2.0 : ls);
+    double eps = ((double)h->tr_z[tb] - mu) / exp(lsc);
+    return -0.5 * eps * eps - lsc - 0.5 * log(2.0 * ORC_PI);
+}
+
+void orc_vtrace_targets(orc_t* h, double rho_bar, double c_bar)
+{
+    int B = h->B, T = h->T, NH = h->NH;
+    double gamma = (double)h->net.gamma, lambda = (double)h->net.lambda_;
+    double* wq = forward_params64(h, h->theta);
+    double act[5][1024];
+    for (size_t tb = 0; tb < (size_t)(T + 1) * B; ++tb) forward64(h, wq, tb, act, h->cur_head + tb * NH);
+    free(wq);
+    for (int b = 0; b < B; ++b) {
+        double tail = 0.0;                                   /* v_{t+1} - V(s_{t+1}) */
+        for (int t = T - 1; t >= 0; --t) {
+            size_t tb = (size_t)t * B + b;
+            double beh[16];
+            for (int j = 0; j < NH; ++j) beh[j] = (double)h->tr_head[tb * NH + j];
+            double w = exp(log_prob_of_stored_action(h, h->cur_head + tb * NH, tb) - log_prob_of_stored_action(h, beh, tb));
+            double rho = w < rho_bar ? w : rho_bar;
+            double c = lambda * (w < c_bar ? w : c_bar);
+            double disc = h->tr_done[tb] ? 0.0 : gamma;
+            double V = h->cur_head[tb * NH + NH - 1], Vn = h->cur_head[(tb + B) * NH + NH - 1];
+            double r = (double)h->tr_rew[tb];
+            h->rho[tb] = rho;
+            h->adv[tb] = rho * (r + disc * (Vn + tail) - V);
+            tail = rho * (r + disc * Vn - V) + disc * c * tail;
+            h->ret[tb] = V + tail;
+        }
+    }
+}
+
+int orc_learn_vtrace(orc_t* h, double rho_bar, double c_bar)
+{
+    if (!h->have_traj) return -1;
+    orc_vtrace_targets(h, rho_bar, c_bar);
+    orc_loss_and_grad(h);
+    h->adam_t += 1;
+    orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t,
+             (double)h->net.lr, (double)h->net.beta1, (double)h->net.beta2, (double)h->net.eps);
+    h->have_traj = 0;
+    return 0;
+}
+
+/* One decoupled step (reading R-33, the one-device form of the actor/learner split of paper
+ * section 3.2 and figure 3): the actor unrolls T steps with a copy of the parameters taken at the
+ * start of the step, while the learner applies one off-policy update to the trajectory collected
+ * by the previous step.  Neither reads what the other writes, so the order below is one of two
+ * equivalent ones.  The first step only collects.  Clipping thresholds rho_bar = c_bar = 1. */
+void orc_step_decoupled(orc_t* h)
+{
+    float* behaviour = (float*)malloc(h->P * sizeof(float));
+    memcpy(behaviour, h->theta, h->P * sizeof(float));
+    if (h->have_traj) orc_learn_vtrace(h, 1.0, 1.0);
+    float* learner = h->theta;
+    h->theta = behaviour;
+    orc_rollout(h, NULL);
+    h->theta = learner;
+    free(behaviour);
 }
 
 /* the surrogate objective only (no gradient, no update): used by the finite-

@@ -71,7 +71,8 @@ def lib():
                          ("orc_traj_state_i", i32p), ("orc_traj_state_f", f32p), ("orc_traj_action", i32p),
                          ("orc_traj_action_f", f32p), ("orc_traj_eps", f32p), ("orc_traj_z", f32p),
                          ("orc_traj_reward", f32p), ("orc_traj_done", u8p), ("orc_traj_value", f32p),
-                         ("orc_traj_head", f32p), ("orc_adv", f64p), ("orc_ret", f64p), ("orc_loss", f64p)):
+                         ("orc_traj_head", f32p), ("orc_adv", f64p), ("orc_ret", f64p), ("orc_loss", f64p),
+                         ("orc_cur_head", f64p), ("orc_rho", f64p)):
             getattr(L, name).argtypes = [C.c_void_p]; getattr(L, name).restype = rt
         L.orc_observe.argtypes = [C.c_void_p, C.c_int, f32p]; L.orc_observe.restype = None
         L.orc_forward.argtypes = [C.c_void_p, f32p, f32p, f32p]; L.orc_forward.restype = None
@@ -89,6 +90,9 @@ def lib():
         L.orc_learn.argtypes = [C.c_void_p]; L.orc_learn.restype = C.c_int
         L.orc_learn_n.argtypes = [C.c_void_p, C.c_int]; L.orc_learn_n.restype = C.c_int
         L.orc_step.argtypes = [C.c_void_p]; L.orc_step.restype = None
+        L.orc_vtrace_targets.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_vtrace_targets.restype = None
+        L.orc_learn_vtrace.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_learn_vtrace.restype = C.c_int
+        L.orc_step_decoupled.argtypes = [C.c_void_p]; L.orc_step_decoupled.restype = None
         _lib = L
     return _lib
 
@@ -202,6 +206,8 @@ class Oracle:
         self.adv = g("orc_adv", (T, B), np.float64)
         self.ret = g("orc_ret", (T, B), np.float64)
         self.loss = g("orc_loss", (4,), np.float64)
+        self.cur_head = g("orc_cur_head", (T + 1, B, NH), np.float64)
+        self.rho = g("orc_rho", (T, B), np.float64)
 
     def __del__(self):
         try:
@@ -279,3 +285,16 @@ class Oracle:
 
     def step(self):
         self.L.orc_step(self.h)
+
+    def vtrace_targets(self, rho_bar=1.0, c_bar=1.0):
+        """Fills ret (v_t), adv (the policy-gradient advantage), rho and cur_head for the stored trajectory
+        at the current parameters."""
+        self.L.orc_vtrace_targets(self.h, float(rho_bar), float(c_bar))
+
+    def learn_vtrace(self, rho_bar=1.0, c_bar=1.0):
+        if self.L.orc_learn_vtrace(self.h, float(rho_bar), float(c_bar)) != 0:
+            raise RuntimeError("learn_vtrace without a stored trajectory")
+
+    def step_decoupled(self):
+        """Actor unroll with the parameters as they are now, learner update on the previous unroll."""
+        self.L.orc_step_decoupled(self.h)

@@ -764,6 +764,114 @@ def test_n_updates_per_unroll(orc):
         b.rollout(); b.learn_n(3)               # 8 steps do not split into 3 chunks
 
 
+# --------------------------------------------------------------------------- off-policy update, decoupled step
+def _np_log_prob(head, kind, act, z):
+    """log-probability of the stored action under head outputs [..., NH] (binary64, written out here)."""
+    head = np.asarray(head, np.float64)
+    if kind == "pendulum":
+        mu, ls = head[..., 0], np.clip(head[..., 1], -5.0, 2.0)
+        return -0.5 * ((z - mu) / np.exp(ls)) ** 2 - ls - 0.5 * math.log(2 * math.pi)
+    lg = head[..., :-1]
+    lse = np.log(np.exp(lg - lg.max(-1, keepdims=True)).sum(-1)) + lg.max(-1)
+    return np.take_along_axis(lg, act[..., None], -1)[..., 0] - lse
+
+
+@pytest.mark.parametrize("kind", ["catch", "pendulum"])
+def test_vtrace_targets_vs_definition(orc, kind):
+    """The backward recursion against V-trace written as its defining sum (Espeholt et al. 2018, eq. 1):
+    v_s = V(x_s) + sum_{t>=s} (prod_{i=s}^{t-1} disc_i c_i) delta_t, delta_t = rho_t (r_t + disc_t V(x_{t+1}) - V(x_t)),
+    with truncation levels below and above the ratios that occur, plus the advantage rho_s (r_s + disc_s v_{s+1} - V(x_s))."""
+    cfg = tiny(kind, hidden=(8, 8), B=6, T=12, lam=0.9, max_steps=7)
+    o = orc.Oracle(cfg, seed=3)
+    for _ in range(2):
+        o.rollout()
+    rng = np.random.default_rng(0)
+    o.theta[:] = o.theta + rng.normal(0, 0.08, o.P).astype(np.float32)      # the learner has moved on
+    rho_bar, c_bar = 1.05, 0.9
+    o.vtrace_targets(rho_bar, c_bar)
+    T, B = o.T, o.B
+    gamma, lam = float(np.float32(cfg["net"]["gamma"])), float(np.float32(cfg["net"]["lambda"]))   # stored as binary32
+    # the learner's heads are the network's: float32 canonical forward of the same states, a few samples
+    for (t, b) in [(0, 0), (5, 3), (T, B - 1)]:
+        si, sf = o.tr_state_i[t, b].copy(), o.tr_state_f[t, b].copy()
+        keep_i, keep_f = o.state_i[b].copy(), o.state_f[b].copy()
+        o.state_i[b] = si; o.state_f[b] = sf
+        h32 = o.forward(o.observe(b))
+        o.state_i[b] = keep_i; o.state_f[b] = keep_f
+        assert np.abs(o.cur_head[t, b] - h32).max() <= 1e-5 * max(1.0, np.abs(h32).max())
+    V = o.cur_head[..., -1]
+    w = np.exp(_np_log_prob(o.cur_head[:T], kind, o.tr_action, o.tr_z) - _np_log_prob(o.tr_head[:T], kind, o.tr_action, o.tr_z))
+    assert (w > rho_bar).any() and (w < c_bar).any() and ((w > c_bar) & (w < rho_bar)).any()   # every branch of both min()
+    rho = np.minimum(rho_bar, w); c = lam * np.minimum(c_bar, w)
+    assert np.allclose(o.rho, rho, rtol=1e-12, atol=0)
+    disc = gamma * (1.0 - o.tr_done.astype(np.float64))
+    assert o.tr_done.sum() > 0
+    delta = rho * (o.tr_reward + disc * V[1:] - V[:-1])
+    vs = np.zeros((T + 1, B)); vs[T] = V[T]
+    for s_ in range(T):
+        acc = np.zeros(B); coef = np.ones(B)
+        for t in range(s_, T):
+            acc += coef * delta[t]
+            coef = coef * disc[t] * c[t]
+        vs[s_] = V[s_] + acc
+    adv = rho * (o.tr_reward + disc * vs[1:] - V[:-1])
+    assert np.abs(o.ret - vs[:T]).max() <= 1e-12 * max(1.0, np.abs(vs).max())
+    assert np.abs(o.adv - adv).max() <= 1e-12 * max(1.0, np.abs(adv).max())
+
+
+@pytest.mark.parametrize("kind", ["catch", "pendulum"])
+def test_vtrace_on_policy_is_the_a2c_update(orc, kind):
+    """With the acting-time parameters (ratios 1 up to the float32/binary64 forward difference) and lambda = 1,
+    the off-policy update is the on-policy one: same targets, same gradient, same step."""
+    cfg = tiny(kind, hidden=(8, 8), B=8, T=10, lam=1.0, max_steps=6)
+    a = orc.Oracle(cfg, seed=9); b = orc.Oracle(cfg, seed=9)
+    for _ in range(2):
+        a.rollout(); a.learn(); b.rollout(); b.learn_vtrace(1.0, 1.0)
+        assert np.abs(a.ret - b.ret).max() <= 1e-5 * max(1.0, np.abs(a.ret).max())
+        assert np.abs(a.adv - b.adv).max() <= 1e-5 * max(1.0, np.abs(a.adv).max())
+        assert np.abs(a.grad - b.grad).max() <= 1e-5 * max(1e-3, np.abs(a.grad).max())
+        assert np.abs(a.loss - b.loss).max() <= 1e-5 * max(1.0, np.abs(a.loss).max())
+        # Adam normalises the step: near-zero gradient entries may move by a fraction of lr either way
+        assert np.abs(a.theta - b.theta).max() <= 0.02 * cfg["net"]["lr"]
+        b.theta[:] = a.theta; b.m[:] = a.m; b.v[:] = a.v
+    assert a.adam_t == b.adam_t == 2
+
+
+def test_decoupled_step_semantics(orc):
+    """The first decoupled step only collects; from then on the learner is one unroll behind the actor, and the
+    actor's parameters are those from before the update that runs beside it."""
+    cfg = tiny("catch", hidden=(8, 8), B=8, T=6, lam=1.0)
+    a = orc.Oracle(cfg, seed=4); ref = orc.Oracle(cfg, seed=4)
+    theta0 = a.theta.copy()
+    a.step_decoupled()
+    ref.rollout()
+    assert np.array_equal(a.theta, theta0) and a.adam_t == 0
+    assert np.array_equal(a.tr_action, ref.tr_action) and np.array_equal(a.tr_head, ref.tr_head)
+    # second step: update on unroll 0 (on-policy at theta0), unroll 1 acted with theta0
+    a.step_decoupled()
+    ref.learn_vtrace()
+    theta1 = a.theta.copy()
+    assert a.adam_t == 1 and np.array_equal(a.theta, ref.theta)
+    ref_theta1 = ref.theta.copy()
+    ref.theta[:] = theta0
+    ref.rollout()
+    assert np.array_equal(a.tr_action, ref.tr_action) and np.array_equal(a.tr_head, ref.tr_head)
+    assert a.global_step == 2 * cfg["T"]
+    # third step: off-policy update (behaviour theta0, learner theta1), unroll 2 acted with theta1
+    ref.theta[:] = ref_theta1
+    a.step_decoupled()
+    ref.learn_vtrace()
+    assert a.adam_t == 2 and np.array_equal(a.theta, ref.theta)
+    assert (a.rho < 1.0 - 1e-4).any()                       # the update really was off-policy
+    theta2 = ref.theta.copy()
+    ref.theta[:] = theta1
+    ref.rollout()
+    assert np.array_equal(a.tr_head, ref.tr_head) and np.array_equal(a.tr_state_i, ref.tr_state_i)
+    ref.theta[:] = theta2
+    ref.forward(ref.observe(0))
+    assert not np.array_equal(theta1, theta2)
+
+
 def test_catch_learning_sanity(orc):
     # not a parity criterion: the mean episode return should rise from about -0.6
     cfg = W.get("catch_small", B=64, T=20)
