@@ -130,6 +130,22 @@ int32_t anakin_learn(anakin_t* h);
 /* anakin_rollout followed by anakin_learn: the timed unit. */
 int32_t anakin_step(anakin_t* h);
 
+/* One decoupled step: acting and learning run side by side on one device (the one-device form of
+ * the actor/learner split of paper section 3.2 and figure 3, where the actors run on parameters
+ * that lag the learner's).  A copy of the parameters is taken; the actor then unrolls T steps with
+ * that copy on a second stream of the library's own, while on the handle's stream the learner
+ * applies one update to the unroll the previous decoupled step (or anakin_rollout) stored: a
+ * forward pass over its states with the current parameters, V-trace targets (Espeholt et al. 2018;
+ * truncation levels 1, trace decay lambda) from the stored behaviour head outputs and the new ones,
+ * then the same loss, backward pass and Adam as anakin_learn.  The first call only collects.  The
+ * handle's stream waits for the actor before any later work, so the usual stream semantics hold;
+ * the result does not depend on how the two streams interleave.  anakin_get_trajectory then shows
+ * the unroll just collected (its adv / ret / act fields belong to the update that ran beside it).
+ * fp32 nets, one update per unroll: ANAKIN_E_BAD_CONFIG otherwise.  After a decoupled step
+ * anakin_learn returns ANAKIN_E_STATE (the stored unroll has no activations); anakin_step and
+ * anakin_rollout start a fresh on-policy unroll.  Asynchronous. */
+int32_t anakin_step_decoupled(anakin_t* h);
+
 /* Frees the host-side handle (never the workspace).  Synchronises the stream. */
 int32_t anakin_destroy(anakin_t* h);
 

@@ -55,7 +55,7 @@ class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("calls", C.c_int64), ("total_ms", C.c_double)]
 
 
-EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_step",
+EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled",
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
@@ -85,7 +85,7 @@ def load():
     L.anakin_workspace_bytes.restype = C.c_size_t
     L.anakin_create.argtypes = [C.POINTER(vp), C.POINTER(EnvCfg), C.POINTER(NetCfg), C.c_int32, C.c_int32,
                                 C.c_uint64, vp, C.c_size_t, vp]
-    for name in ("anakin_rollout", "anakin_learn", "anakin_step", "anakin_destroy"):
+    for name in ("anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled", "anakin_destroy"):
         getattr(L, name).argtypes = [vp]
     L.anakin_param_count.argtypes = [vp, C.POINTER(C.c_int64)]
     L.anakin_get_params.argtypes = [vp, f32p, C.c_size_t]
@@ -190,6 +190,9 @@ class Anakin:
 
     def step(self):
         self._chk(self.L.anakin_step(self.h))
+
+    def step_decoupled(self):
+        self._chk(self.L.anakin_step_decoupled(self.h))
 
     def set_mode(self, flags):
         self._chk(self.L.anakin_set_mode(self.h, int(flags)))

@@ -8,6 +8,7 @@
 #include <string.h>
 #include <new>
 #include <vector>
+#include <utility>
 #include "internal.h"
 
 using namespace ank;
@@ -122,6 +123,14 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
     L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
     L.loss_part = take((size_t)(loss_blocks + T) * 8 * 4);     // + T: with N updates per unroll every chunk rounds its block count up
+    // decoupled steps (fp32 nets): behaviour parameters, second record set, the learner's forward results
+    const bool dec = !ns.bf16;
+    L.theta_b = take(dec ? P * 4 : 0);
+    L.alt_tr_s0 = take(dec ? t1n * 4 : 0); L.alt_tr_f0 = take(dec ? t1n * 4 : 0); L.alt_tr_f1 = take(dec ? t1n * 4 : 0);
+    L.alt_tr_act = take(dec ? tn : 0); L.alt_tr_eps = take(dec ? tn * 4 : 0); L.alt_tr_actf = take(dec ? tn * 4 : 0);
+    L.alt_tr_rew = take(dec ? tn * 4 : 0); L.alt_tr_done = take(dec ? tn : 0);
+    L.alt_tr_val = take(dec ? t1n * 4 : 0); L.alt_tr_head = take(dec ? t1n * ns.NHP * 4 : 0);
+    L.head_new = take(dec ? t1n * ns.NHP * 4 : 0); L.val_new = take(dec ? t1n * 4 : 0); L.eps_new = take(dec ? tn * 4 : 0);
     L.total = off;
 }
 
@@ -308,6 +317,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0; h->traj_no_acts = 0;
+    h->traj_decoupled = 0; h->actor_stream = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ed, ns, B, T, h->splits, &h->splits_w, &h->head_fan, &h->loss_blocks);
@@ -364,6 +374,9 @@ extern "C" int32_t anakin_destroy(anakin_t* h)
     if (!h) return ANAKIN_E_INVALID_ARG;
     (void)prof_resolve(h);
     for (hipEvent_t e : h->prof_pool) (void)hipEventDestroy(e);
+    if (h->actor_stream) { (void)hipStreamSynchronize(h->actor_stream); (void)hipStreamDestroy(h->actor_stream); }
+    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
     delete h;
     return ANAKIN_OK;
 }
@@ -461,6 +474,7 @@ extern "C" int32_t anakin_rollout(anakin_t* h)
     else HIPCHK(h, launch_rollout(h));
     h->traj_packed = bf16_mfma(h) ? 1 : 0;
     h->traj_no_acts = one_layer_fused(h) ? 1 : 0;
+    h->traj_decoupled = 0;
     h->gstep += (uint64_t)h->T;
     h->have_traj = 1;
     return ANAKIN_OK;
@@ -481,6 +495,7 @@ extern "C" int32_t anakin_learn(anakin_t* h)
 {
     NEED(h);
     if (!h->have_traj) { h->err = "learn needs a stored trajectory: call anakin_rollout first"; return ANAKIN_E_STATE; }
+    if (h->traj_decoupled) { h->err = "the stored unroll was collected by a decoupled step (older parameters, no activations): continue with anakin_step_decoupled"; return ANAKIN_E_STATE; }
     if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     if (h->traj_no_acts != (one_layer_fused(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     HIPCHK(h, launch_returns(h));
@@ -551,6 +566,64 @@ extern "C" int32_t anakin_step(anakin_t* h)
     int32_t rc = anakin_rollout(h);
     if (rc != ANAKIN_OK) return rc;
     return anakin_learn(h);
+}
+
+// ---- decoupled acting and learning on one device -------------------------------------
+// The two record sets change roles by exchanging their offsets in the layout.
+static void swap_record_sets(Layout& L)
+{
+    std::swap(L.tr_s0, L.alt_tr_s0); std::swap(L.tr_f0, L.alt_tr_f0); std::swap(L.tr_f1, L.alt_tr_f1);
+    std::swap(L.tr_act, L.alt_tr_act); std::swap(L.tr_eps, L.alt_tr_eps); std::swap(L.tr_actf, L.alt_tr_actf);
+    std::swap(L.tr_rew, L.alt_tr_rew); std::swap(L.tr_done, L.alt_tr_done);
+    std::swap(L.tr_val, L.alt_tr_val); std::swap(L.tr_head, L.alt_tr_head);
+}
+
+extern "C" int32_t anakin_step_decoupled(anakin_t* h)
+{
+    NEED(h);
+    if (h->net.bf16) { h->err = "decoupled steps run fp32 nets only"; return ANAKIN_E_BAD_CONFIG; }
+    if (h->n_updates != 1) { h->err = "decoupled steps apply one update per unroll"; return ANAKIN_E_BAD_CONFIG; }
+    if (h->prof_pending.size() > 8192) HIPCHK(h, prof_resolve(h));
+    if (!h->actor_stream) {
+        HIPCHK(h, hipStreamCreateWithFlags(&h->actor_stream, hipStreamNonBlocking));
+        HIPCHK(h, hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+        HIPCHK(h, hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
+    }
+    const NetShape& n = h->net;
+    hipStream_t learner = h->stream;
+    // the actor's parameters: the learner's as they are now, before this step's update touches them
+    HIPCHK(h, hipMemcpyAsync(h->ws + h->lay.theta_b, h->ws + h->lay.theta, (size_t)n.P * 4, hipMemcpyDeviceToDevice, learner));
+    HIPCHK(h, hipEventRecord(h->ev_fork, learner));
+    HIPCHK(h, hipStreamWaitEvent(h->actor_stream, h->ev_fork, 0));
+    // actor: T steps into the free record set, on its own stream
+    swap_record_sets(h->lay);
+    h->stream = h->actor_stream;
+    hipError_t e = launch_rollout_behaviour(h);
+    h->stream = learner;
+    swap_record_sets(h->lay);
+    HIPCHK(h, e);
+    HIPCHK(h, hipEventRecord(h->ev_join, h->actor_stream));
+    // learner: one off-policy update on the unroll of the previous step
+    int32_t rc = ANAKIN_OK;
+    if (h->have_traj) {
+        HIPCHK(h, launch_replay_forward(h));
+        HIPCHK(h, launch_vtrace(h));
+        const int no_acts = h->traj_no_acts;
+        h->traj_packed = 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0;
+        const Layout keep = h->lay;
+        h->lay.tr_head = keep.head_new; h->lay.tr_eps = keep.eps_new;   // the loss kernel reads the learner's heads
+        rc = run_update(h);
+        h->lay = keep;
+        h->traj_no_acts = no_acts;
+    }
+    // the record set just filled becomes the stored unroll; later work on the handle's stream follows the actor
+    swap_record_sets(h->lay);
+    HIPCHK(h, hipStreamWaitEvent(learner, h->ev_join, 0));
+    if (rc != ANAKIN_OK) return rc;
+    h->traj_packed = 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0; h->traj_decoupled = 1;
+    h->gstep += (uint64_t)h->T;
+    h->have_traj = 1;
+    return ANAKIN_OK;
 }
 
 // ---- introspection ----------------------------------------------------------

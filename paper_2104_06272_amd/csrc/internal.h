@@ -109,6 +109,12 @@ struct Layout {
     size_t head_stage;           // first-stage partials of the head gradient
     size_t prefix;               // bf16 acting: per-env first-layer prefix [B][H1] fp32
     size_t loss_part;
+    // decoupled acting and learning: the behaviour copy of the parameters the actor runs on, the second set of
+    // trajectory records (the actor fills one set while the learner reads the other), and the learner's own
+    // forward results on the stored unroll
+    size_t theta_b;
+    size_t alt_tr_s0, alt_tr_f0, alt_tr_f1, alt_tr_act, alt_tr_eps, alt_tr_actf, alt_tr_rew, alt_tr_done, alt_tr_val, alt_tr_head;
+    size_t head_new, val_new, eps_new;
     size_t total;
 };
 
@@ -141,6 +147,9 @@ struct anakin {
     int bf16_path;                // the bf16 matrix-core kernels support this net
     int traj_packed;              // the stored unroll holds packed bf16 activations
     int traj_no_acts;             // the stored unroll holds no hidden activations (one-layer nets)
+    int traj_decoupled;           // the stored unroll was collected by a decoupled step: behaviour parameters, no activations
+    hipStream_t actor_stream;     // decoupled steps: the actor's stream (created on first use), and the fork/join events
+    hipEvent_t ev_fork, ev_join;
     std::string err;
     // optional per-kernel timing with events on the launch stream
     int prof_on;
@@ -165,6 +174,9 @@ hipError_t prof_resolve(anakin* h);
 
 // kernel launchers (each enqueues on h->stream and returns the HIP status)
 hipError_t launch_rollout(anakin* h);
+hipError_t launch_rollout_behaviour(anakin* h);
+hipError_t launch_replay_forward(anakin* h);
+hipError_t launch_vtrace(anakin* h);
 hipError_t launch_returns(anakin* h);
 hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);

@@ -44,6 +44,89 @@ __global__ __launch_bounds__(WG) void returns_scan(int B, int T, const float* __
 }
 
 // ---------------------------------------------------------------------------
+// Off-policy targets for a stored unroll whose actions came from older parameters (decoupled acting
+// and learning, paper section 3.2; the correction is IMPALA's V-trace, which the paper runs on that
+// architecture).  head_old: head outputs stored at acting time (the behaviour policy mu); head_new:
+// the learner's forward pass over the same states (policy pi and values V).  Per env, backwards in t:
+//   w = pi(a|s) / mu(a|s),  rho = min(1, w),  c = lambda min(1, w),  disc = gamma (1 - done)
+//   adv_t = rho (r + disc v_{t+1} - V_t)
+//   v_t - V_t = rho (r + disc V_{t+1} - V_t) + disc c (v_{t+1} - V_{t+1}),   v_T = V_T
+// ret = v, adv = the policy-gradient advantage: the loss kernel then treats them as it treats the
+// on-policy return and advantage.  Gaussian policy: the densities are compared at the stored
+// pre-squash sample z = mu_old + sigma_old eps_old, and eps_new = (z - mu_new) / sigma_new is
+// written for the loss kernel's score function.  One lane per env, coalesced as in returns_scan.
+// ---------------------------------------------------------------------------
+struct VtraceArgs {
+    int B, T, A, NH, NHP, policy;
+    const float* head_old; const float* head_new; const uint8_t* act; const float* eps_old;
+    const float* rew; const uint8_t* done;
+    float gamma, lambda;
+    float* adv; float* ret; float* eps_new;
+};
+
+__device__ __forceinline__ void load_head(const float* p, int NHP, float (&hv)[8])
+{
+    const float4 h0 = *reinterpret_cast<const float4*>(p);
+    hv[0] = h0.x; hv[1] = h0.y; hv[2] = h0.z; hv[3] = h0.w;
+    if (NHP == 8) {
+        const float4 h1 = *reinterpret_cast<const float4*>(p + 4);
+        hv[4] = h1.x; hv[5] = h1.y; hv[6] = h1.z; hv[7] = h1.w;
+    } else { hv[4] = hv[5] = hv[6] = hv[7] = 0.0f; }
+}
+
+__device__ __forceinline__ float log_softmax_at(const float (&hv)[8], int A, int act)
+{
+    float mx = hv[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) if (j < A) mx = fmaxf(mx, hv[j]);
+    float Z = 0.0f, ha = hv[0];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { if (j < A) Z += det_exp(hv[j] - mx); if (j == act) ha = hv[j]; }
+    return ha - mx - det_log(Z);
+}
+
+__global__ __launch_bounds__(WG) void vtrace_scan(const VtraceArgs a)
+{
+    const int b = blockIdx.x * WG + threadIdx.x;
+    if (b >= a.B) return;
+    const int B = a.B, T = a.T, NHP = a.NHP, vi = a.NH - 1;
+    float hn[8], ho[8];
+    load_head(a.head_new + ((size_t)T * B + b) * NHP, NHP, hn);
+    float Vnext = hn[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) if (j == vi) Vnext = hn[j];
+    float tail = 0.0f;                                       // v_{t+1} - V_{t+1}
+    for (int t = T - 1; t >= 0; --t) {
+        const size_t i = (size_t)t * B + b;
+        load_head(a.head_new + i * NHP, NHP, hn);
+        load_head(a.head_old + i * NHP, NHP, ho);
+        float V = hn[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) if (j == vi) V = hn[j];
+        float lw;
+        if (a.policy == POLICY_CATEGORICAL) {
+            const int act = a.act[i];
+            lw = log_softmax_at(hn, a.A, act) - log_softmax_at(ho, a.A, act);
+        } else {
+            const float lso = fminf(fmaxf(ho[1], -5.0f), 2.0f), lsn = fminf(fmaxf(hn[1], -5.0f), 2.0f);
+            const float eo = a.eps_old[i];
+            const float z = fmaf(det_exp(lso), eo, ho[0]);   // the sampler's own expression
+            const float en = (z - hn[0]) / det_exp(lsn);
+            a.eps_new[i] = en;
+            lw = (-0.5f * en * en - lsn) - (-0.5f * eo * eo - lso);
+        }
+        const float w = det_exp(lw);
+        const float rho = fminf(1.0f, w), c = a.lambda * rho;
+        const float r = a.rew[i];
+        const float disc = a.done[i] ? 0.0f : a.gamma;
+        a.adv[i] = rho * (fmaf(disc, Vnext + tail, r) - V);
+        tail = fmaf(disc * c, tail, rho * (fmaf(disc, Vnext, r) - V));
+        a.ret[i] = V + tail;
+        Vnext = V;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Per sample: l = -A log pi(a|s) + c_v (G - V)^2 - beta H, and d l / d head / M.
 // Categorical: d/dlogit_i = -A (1[i=a] - p_i) + beta p_i (log p_i + H).
 // Gaussian (score function at the stored noise, log_sigma clamped to [-5,2]):
@@ -833,6 +916,21 @@ hipError_t launch_returns(anakin* h)
     hipLaunchKernelGGL(returns_scan, dim3((h->B + WG - 1) / WG), dim3(WG), 0, h->stream, h->B, h->T,
                        at<const float>(h, L.tr_rew), at<const uint8_t>(h, L.tr_done), at<const float>(h, L.tr_val),
                        h->net_cfg.gamma, h->net_cfg.lambda_, at<float>(h, L.adv), at<float>(h, L.ret));
+    return hipGetLastError();
+}
+
+hipError_t launch_vtrace(anakin* h)
+{
+    const Layout& L = h->lay;
+    VtraceArgs a;
+    a.B = h->B; a.T = h->T; a.A = h->net.A; a.NH = h->net.NH; a.NHP = h->net.NHP; a.policy = h->net.policy;
+    a.head_old = at<const float>(h, L.tr_head); a.head_new = at<const float>(h, L.head_new);
+    a.act = at<const uint8_t>(h, L.tr_act); a.eps_old = at<const float>(h, L.tr_eps);
+    a.rew = at<const float>(h, L.tr_rew); a.done = at<const uint8_t>(h, L.tr_done);
+    a.gamma = h->net_cfg.gamma; a.lambda = h->net_cfg.lambda_;
+    a.adv = at<float>(h, L.adv); a.ret = at<float>(h, L.ret); a.eps_new = at<float>(h, L.eps_new);
+    ProfScope prof(h, "vtrace_scan");
+    hipLaunchKernelGGL(vtrace_scan, dim3((h->B + WG - 1) / WG), dim3(WG), 0, h->stream, a);
     return hipGetLastError();
 }
 

@@ -450,7 +450,11 @@ __device__ __forceinline__ void run_heads(const float* X, int ldx, const float* 
     }
 }
 
-template <int ENV, bool BF, bool MF>
+// REPLAY: the learner's pass over a stored unroll (decoupled acting and learning): the state of
+// step t comes from the stored snapshots, the forward pass is the acting one with the parameters
+// in a.theta, head outputs and values go to tp.tr_head / tp.tr_val (the caller points them at the
+// learner's buffers) and hidden activations to tp.act; nothing is sampled or stepped.
+template <int ENV, bool BF, bool MF, bool REPLAY>
 __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const int TM)
 {
     extern __shared__ float4 smem4[];
@@ -484,8 +488,10 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
     const bool owner = tid < TM;
     const int b = b0 + tid;
     if (owner) {
-        st.s0 = tp.s0[b];
-        if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        if (!REPLAY) {
+            st.s0 = tp.s0[b];
+            if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        }
         if (ENV == ENV_MAZE) {
             for (int w = 0; w < 8; ++w) obs[tid * OBS_WORDS + w] = tp.walls[(size_t)w * B + b];
         }
@@ -495,15 +501,19 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         const size_t tb = (size_t)t * B + b;
         // ---- observe -------------------------------------------------------
         if (owner) {
-            tp.tr_s0[tb] = st.s0;
+            if (REPLAY) {
+                st.s0 = tp.tr_s0[tb];
+                if (ENV == ENV_PENDULUM) { st.f0 = tp.tr_f0[tb]; st.f1 = tp.tr_f1[tb]; }
+            } else {
+                tp.tr_s0[tb] = st.s0;
+                if (ENV == ENV_PENDULUM) { tp.tr_f0[tb] = st.f0; tp.tr_f1[tb] = st.f1; }
+            }
             if (ENV == ENV_CATCH) {
                 int bc, pc;
                 catch_obs_cells(a.env, st.s0, bc, pc);
                 obs[tid * OBS_WORDS + 0] = (uint32_t)bc;
                 obs[tid * OBS_WORDS + 1] = (uint32_t)pc;
             } else if (ENV == ENV_PENDULUM) {
-                tp.tr_f0[tb] = st.f0;
-                tp.tr_f1[tb] = st.f1;
                 float sn, cs;
                 det_sincos(st.f0, sn, cs);
                 obs[tid * OBS_WORDS + 0] = bits_from_f(cs);
@@ -531,7 +541,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         run_heads(cur, ldx, whs, ldw, bhs, heads, HL, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
-        if (t < T) {
+        if (!REPLAY && t < T) {
             for (int e = WG - 1 - tid; e < TM; e += WG) {
                 const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
                 rng[e * 4] = w.x;
@@ -551,7 +561,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
 #pragma unroll
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
-            if (t < T) {
+            if (!REPLAY && t < T) {
                 const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);   // action draw, words 0 and 1
                 float r; int done;
                 // the reset draw is only needed where an episode ends: the step runs with a placeholder
@@ -587,7 +597,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         // the next observe phase writes obs words that only the first layer reads, and
         // two barriers separate that read from this point
     }
-    if (owner) {
+    if (!REPLAY && owner) {
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
     }
@@ -686,7 +696,7 @@ __device__ __forceinline__ void resident_m32(const float (&wreg)[KS][NT], const 
 
 
 // RK x RN: shape of the resident hidden-to-hidden layer; M32: 32 envs per workgroup, else 16
-template <int ENV, bool M32, int RK, int RN>
+template <int ENV, bool M32, int RK, int RN, bool REPLAY>
 __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs a)
 {
     constexpr int TM = M32 ? 32 : 16;
@@ -740,8 +750,10 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
     const bool owner = tid < TM;
     const int b = b0 + tid;
     if (owner) {
-        st.s0 = tp.s0[b];
-        if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        if (!REPLAY) {
+            st.s0 = tp.s0[b];
+            if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        }
         if (ENV == ENV_MAZE) {
             for (int w = 0; w < 8; ++w) obs[tid * OBS_WORDS + w] = tp.walls[(size_t)w * B + b];
         }
@@ -757,15 +769,19 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
     for (int t = 0; t <= T; ++t) {
         const size_t tb = (size_t)t * B + b;
         if (owner) {
-            tp.tr_s0[tb] = st.s0;
+            if (REPLAY) {
+                st.s0 = tp.tr_s0[tb];
+                if (ENV == ENV_PENDULUM) { st.f0 = tp.tr_f0[tb]; st.f1 = tp.tr_f1[tb]; }
+            } else {
+                tp.tr_s0[tb] = st.s0;
+                if (ENV == ENV_PENDULUM) { tp.tr_f0[tb] = st.f0; tp.tr_f1[tb] = st.f1; }
+            }
             if (ENV == ENV_CATCH) {
                 int bc, pc;
                 catch_obs_cells(a.env, st.s0, bc, pc);
                 obs[tid * OBS_WORDS + 0] = (uint32_t)bc;
                 obs[tid * OBS_WORDS + 1] = (uint32_t)pc;
             } else if (ENV == ENV_PENDULUM) {
-                tp.tr_f0[tb] = st.f0;
-                tp.tr_f1[tb] = st.f1;
                 float sn, cs;
                 det_sincos(st.f0, sn, cs);
                 obs[tid * OBS_WORDS + 0] = bits_from_f(cs);
@@ -790,7 +806,7 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         heads_pipe<4, HL>(bufB, ldx, whs, ldw, bhs, heads, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
-        if (t < T) {
+        if (!REPLAY && t < T) {
             for (int e = WG - 1 - tid; e < TM; e += WG) {
                 const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
                 rng[e * 4] = w.x;
@@ -810,7 +826,7 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
 #pragma unroll
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
-            if (t < T) {
+            if (!REPLAY && t < T) {
                 const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);   // action draw, words 0 and 1
                 float r; int done;
                 // the reset draw is only needed where an episode ends: the step runs with a placeholder
@@ -851,7 +867,7 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
                ph[0] / (T + 1), ph[1] / (T + 1), ph[2] / (T + 1), ph[3] / (T + 1), ph[4] / (T + 1));
 #endif
 #undef PH
-    if (owner) {
+    if (!REPLAY && owner) {
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
     }
@@ -932,68 +948,95 @@ size_t rollout_lds_bytes(const NetShape& net, const EnvDims&, int TM, int* ldx_o
     return words * 4;
 }
 
-template <int ENV, bool BF, bool MF>
+template <int ENV, bool BF, bool MF, bool REPLAY>
 static hipError_t launch_one(anakin* h, const RolloutArgs& a, int TM)
 {
     const size_t lds = rollout_lds_bytes(h->net, h->env, TM, nullptr);
-    auto kern = rollout_kernel<ENV, BF, MF>;
+    auto kern = rollout_kernel<ENV, BF, MF, REPLAY>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    ProfScope prof(h, "rollout");
+    ProfScope prof(h, REPLAY ? "replay_forward" : "rollout");
     hipLaunchKernelGGL(kern, dim3(h->B / TM), dim3(WG), lds, h->stream, a, TM);
     return hipGetLastError();
 }
 
 void fill_rollout_args(anakin* h, RolloutArgs& a);
 
-template <int ENV, bool M32, int RW>
+template <int ENV, bool M32, int RW, bool REPLAY>
 static hipError_t launch_resident(anakin* h, const RolloutArgs& a)
 {
     constexpr int TM = M32 ? 32 : 16;
     size_t lds = rollout_lds_bytes(h->net, h->env, TM, nullptr);
     if (ENV != ENV_MAZE) lds += (size_t)h->net.dims[0] * RW * 4;
-    auto kern = rollout_resident_kernel<ENV, M32, RW, RW>;
+    auto kern = rollout_resident_kernel<ENV, M32, RW, RW, REPLAY>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    ProfScope prof(h, "rollout");
+    ProfScope prof(h, REPLAY ? "replay_forward" : "rollout");
     hipLaunchKernelGGL(kern, dim3(h->B / TM), dim3(WG), lds, h->stream, a);
     return hipGetLastError();
 }
 
-template <int ENV>
+template <int ENV, bool REPLAY>
 static hipError_t launch_resident_env(anakin* h, const RolloutArgs& a, int width, int tm)
 {
-    if (width == 256) return tm == 32 ? launch_resident<ENV, true, 256>(h, a) : launch_resident<ENV, false, 256>(h, a);
-    if (width == 128) return tm == 32 ? launch_resident<ENV, true, 128>(h, a) : launch_resident<ENV, false, 128>(h, a);
-    return launch_resident<ENV, false, 64>(h, a);
+    if (width == 256) return tm == 32 ? launch_resident<ENV, true, 256, REPLAY>(h, a) : launch_resident<ENV, false, 256, REPLAY>(h, a);
+    if (width == 128) return tm == 32 ? launch_resident<ENV, true, 128, REPLAY>(h, a) : launch_resident<ENV, false, 128, REPLAY>(h, a);
+    return launch_resident<ENV, false, 64, REPLAY>(h, a);
+}
+
+template <bool REPLAY>
+static hipError_t launch_forward(anakin* h, const RolloutArgs& a)
+{
+    const bool bf = h->net.bf16 != 0;
+    if (h->TM_res > 0 && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS))) {
+        const int w = rollout_resident_width(h->net);
+        switch (h->env.kind) {
+            case ENV_CATCH:    return launch_resident_env<ENV_CATCH, REPLAY>(h, a, w, h->TM_res);
+            case ENV_PENDULUM: return launch_resident_env<ENV_PENDULUM, REPLAY>(h, a, w, h->TM_res);
+            default:           return launch_resident_env<ENV_MAZE, REPLAY>(h, a, w, h->TM_res);
+        }
+    }
+    const bool mf = h->TM_mfma > 0 && !(h->mode & ANAKIN_MODE_CANONICAL_ACTING);
+    if (mf) {
+        switch (h->env.kind) {
+            case ENV_CATCH:    return launch_one<ENV_CATCH, false, true, REPLAY>(h, a, h->TM_mfma);
+            case ENV_PENDULUM: return launch_one<ENV_PENDULUM, false, true, REPLAY>(h, a, h->TM_mfma);
+            default:           return launch_one<ENV_MAZE, false, true, REPLAY>(h, a, h->TM_mfma);
+        }
+    }
+    switch (h->env.kind) {
+        case ENV_CATCH:    return bf ? launch_one<ENV_CATCH, true, false, REPLAY>(h, a, h->TM) : launch_one<ENV_CATCH, false, false, REPLAY>(h, a, h->TM);
+        case ENV_PENDULUM: return bf ? launch_one<ENV_PENDULUM, true, false, REPLAY>(h, a, h->TM) : launch_one<ENV_PENDULUM, false, false, REPLAY>(h, a, h->TM);
+        default:           return bf ? launch_one<ENV_MAZE, true, false, REPLAY>(h, a, h->TM) : launch_one<ENV_MAZE, false, false, REPLAY>(h, a, h->TM);
+    }
 }
 
 hipError_t launch_rollout(anakin* h)
 {
     RolloutArgs a;
     fill_rollout_args(h, a);
-    const bool bf = h->net.bf16 != 0;
-    if (h->TM_res > 0 && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS))) {
-        const int w = rollout_resident_width(h->net);
-        switch (h->env.kind) {
-            case ENV_CATCH:    return launch_resident_env<ENV_CATCH>(h, a, w, h->TM_res);
-            case ENV_PENDULUM: return launch_resident_env<ENV_PENDULUM>(h, a, w, h->TM_res);
-            default:           return launch_resident_env<ENV_MAZE>(h, a, w, h->TM_res);
-        }
-    }
-    const bool mf = h->TM_mfma > 0 && !(h->mode & ANAKIN_MODE_CANONICAL_ACTING);
-    if (mf) {
-        switch (h->env.kind) {
-            case ENV_CATCH:    return launch_one<ENV_CATCH, false, true>(h, a, h->TM_mfma);
-            case ENV_PENDULUM: return launch_one<ENV_PENDULUM, false, true>(h, a, h->TM_mfma);
-            default:           return launch_one<ENV_MAZE, false, true>(h, a, h->TM_mfma);
-        }
-    }
-    switch (h->env.kind) {
-        case ENV_CATCH:    return bf ? launch_one<ENV_CATCH, true, false>(h, a, h->TM) : launch_one<ENV_CATCH, false, false>(h, a, h->TM);
-        case ENV_PENDULUM: return bf ? launch_one<ENV_PENDULUM, true, false>(h, a, h->TM) : launch_one<ENV_PENDULUM, false, false>(h, a, h->TM);
-        default:           return bf ? launch_one<ENV_MAZE, true, false>(h, a, h->TM) : launch_one<ENV_MAZE, false, false>(h, a, h->TM);
-    }
+    return launch_forward<false>(h, a);
+}
+
+// the actor of a decoupled step: parameters from the behaviour copy, no hidden activations kept
+hipError_t launch_rollout_behaviour(anakin* h)
+{
+    RolloutArgs a;
+    fill_rollout_args(h, a);
+    a.theta = at<const float>(h, h->lay.theta_b);
+    a.keep_acts = 0;
+    return launch_forward<false>(h, a);
+}
+
+// the learner's forward pass over the stored unroll with the current parameters: hidden activations
+// for the backward pass, head outputs and values into the learner's own buffers
+hipError_t launch_replay_forward(anakin* h)
+{
+    RolloutArgs a;
+    fill_rollout_args(h, a);
+    a.tp.tr_head = at<float>(h, h->lay.head_new);
+    a.tp.tr_val = at<float>(h, h->lay.val_new);
+    return launch_forward<true>(h, a);
 }
 
 }  // namespace ank

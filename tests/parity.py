@@ -69,17 +69,20 @@ def assert_final_state_equal(g, o, kind, sel=None):
     assert g.global_step == o.global_step
 
 
-def assert_learn_close(g, o, tol, tr_after=None):
-    """after both sides learned on the same unroll: returns, loss, gradient, parameters, moments"""
+def assert_learn_close(g, o, tol, tr_after=None, learned_on=None):
+    """after both sides learned on the same unroll: returns, loss, gradient, parameters, moments.
+    learned_on: (rewards, dones) of the unroll the update used when that is not the one now stored
+    (decoupled steps learn on the previous unroll)."""
     tr = tr_after if tr_after is not None else g.trajectory()
+    rew, done = learned_on if learned_on is not None else (o.tr_reward, o.tr_done)
     scale = max(1.0, float(np.abs(o.ret).max()))
     assert np.abs(tr["ret"] - o.ret).max() <= 1e-5 * scale, "returns differ"
     assert np.abs(tr["adv"] - o.adv).max() <= 1e-5 * scale, "advantages differ"
     m = g.metrics()
     for k, i in (("loss", 0), ("policy_loss", 1), ("value_loss", 2), ("entropy_loss", 3)):
         assert abs(m[k] - o.loss[i]) <= tol * max(abs(o.loss[i]), 1e-3 * abs(o.loss).max()) + 1e-7, (k, m[k], o.loss[i])
-    assert abs(m["reward_sum"] - float(o.tr_reward.astype(np.float64).sum())) <= 1e-4 * max(1.0, np.abs(o.tr_reward).sum())
-    assert m["episodes"] == int(o.tr_done.sum())
+    assert abs(m["reward_sum"] - float(rew.astype(np.float64).sum())) <= 1e-4 * max(1.0, np.abs(rew).sum())
+    assert m["episodes"] == int(done.sum())
     e_g = rel(g.get_grads(), o.grad)
     assert e_g <= tol, f"gradient rel error {e_g:.3e} > {tol}"
     e_p = rel(g.get_params(), o.theta)

@@ -332,6 +332,67 @@ def test_n_updates_per_unroll_bf16(gpu, orc):
     g.close()
 
 
+def _fast_lr(cfg, lr=1e-2):
+    cfg = copy.deepcopy(cfg)
+    cfg["net"]["lr"] = lr          # one update moves the policy enough for importance ratios on both sides of 1
+    return cfg
+
+
+DECOUPLED_CASES = {
+    # name: (cfg, seed, steps) -- every fp32 acting kernel in its replay form, both policies, the one-layer update
+    "catch_small": (_fast_lr(variant("catch_small")), 0, 4),
+    "catch_256x256_B256": (_fast_lr(variant("catch_4096", B=256)), 1, 3),
+    "catch_tiny_net_B512": (_fast_lr(variant("catch_262144", B=512)), 0, 3),
+    "pendulum_B128": (_fast_lr(variant("pendulum_8192", B=128), 3e-3), 0, 3),
+    "pendulum_short_episodes": (_fast_lr(variant("pendulum_8192", hidden=[64, 64], B=64, T=32, max_steps=25), 3e-3), 2, 3),
+    "maze_fp32_small": (_fast_lr(variant("maze_16384", hidden=[64, 64], B=64, T=32, dtype="fp32", max_steps=20)), 1, 3),
+    "catch_512x256": (_fast_lr(variant("catch_4096", hidden=[512, 256], B=64, T=10)), 3, 3),
+    "catch_ragged_B80_T7": (_fast_lr(variant("catch_small", B=80, T=7)), 2, 3),
+}
+
+
+@pytest.mark.parametrize("case", list(DECOUPLED_CASES))
+def test_decoupled_lockstep(gpu, orc, case):
+    """Decoupled steps, parameter-synchronised: the actor's unroll (with the parameters from before the update
+    that runs beside it) is bitwise the oracle's; the learner's off-policy update on the previous unroll --
+    V-trace targets, loss, gradient, parameters, moments -- within tolerance."""
+    cfg, seed, steps = DECOUPLED_CASES[case]
+    kind = cfg["env"]["kind"]
+    say(f"[decoupled] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+    g = gpu.Anakin(cfg, seed=seed)
+    o = orc.Oracle(cfg, seed=seed)
+    off_policy = 0
+    for k in range(steps):
+        PT.sync_oracle_from_gpu(g, o)
+        before = g.get_params().copy()
+        learned_on = (o.tr_reward.copy(), o.tr_done.copy())
+        g.step_decoupled(); o.step_decoupled()
+        tr = PT.assert_rollout_equal(g, o, kind)
+        PT.assert_final_state_equal(g, o, kind)
+        if k == 0:
+            assert np.array_equal(g.get_params(), before) and g.get_opt_state()[2] == 0      # the first step only collects
+            continue
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=learned_on)
+        off_policy += int((o.rho < 1.0 - 1e-3).sum())
+        say(f"  step {k}: grad rel {e_g:.2e}, param rel {e_p:.2e}, loss {o.loss[0]:+.5f}, min rho {o.rho.min():.4f}")
+    assert off_policy > 0, "no update was off-policy"
+    # an on-policy update cannot use this unroll (older parameters, no activations kept)
+    with pytest.raises(gpu.AnakinError):
+        g.learn()
+    # a plain step afterwards starts a fresh on-policy unroll
+    PT.sync_oracle_from_gpu(g, o)
+    g.step(); o.step()
+    PT.assert_learn_close(g, o, TOL_F32)
+    g.close()
+
+
+def test_decoupled_rejects_bf16(gpu):
+    g = gpu.Anakin(variant("maze_16384", hidden=[128, 128], B=64, T=8), seed=0)
+    with pytest.raises(gpu.AnakinError):
+        g.step_decoupled()
+    g.close()
+
+
 def test_determinism_and_resume(gpu):
     """Same seed twice gives the same bytes; a byte copy of the workspace plus the two host counters
     resumes bit-exactly (explicit, device-resident state; counter-based RNG)."""
