@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--workload", default="catch_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--valu-gemm", action="store_true", help="learn-phase GEMMs on vector ALUs")
+    ap.add_argument("--decoupled", action="store_true",
+                    help="also time K decoupled steps (actor on a second stream with lagging parameters, off-policy "
+                         "update on the previous unroll; fp32 workloads) and report them under \"decoupled\"")
     ap.add_argument("--peak-probe", action="store_true",
                     help="instead of the benchmark, measure what this GPU delivers for the rooflines: register-only "
                          "fp32 and bf16 MFMA loops and a 2 x 1 GiB streaming copy; prints one JSON line")
@@ -243,6 +246,27 @@ def main():
         "wall_s": round(wall, 3),
         "loss": metrics["loss"], "mean_episode_return": metrics["reward_sum"] / max(1, metrics["episodes"]),
     }
+    if args.decoupled:
+        if cfg["net"].get("dtype") == "bf16":
+            out["decoupled"] = None                       # fp32 nets only
+        else:
+            for _ in range(max(args.warmup, 2)):
+                g.step_decoupled()
+            torch.cuda.synchronize()
+            d0 = torch.cuda.Event(enable_timing=True); d1 = torch.cuda.Event(enable_timing=True)
+            d0.record(g.stream)
+            for _ in range(args.steps):
+                g.step_decoupled()
+            d1.record(g.stream)                           # the handle's stream waits for the actor's at the end of every step
+            torch.cuda.synchronize()
+            ms_dec = d0.elapsed_time(d1) / args.steps
+            g.profile(True)
+            for _ in range(args.steps):
+                g.step_decoupled()
+            dk = {k: {"calls_per_step": c / args.steps, "avg_us": round(t / c * 1e3, 2)} for k, (c, t) in g.kernel_times().items()}
+            g.profile(False)
+            out["decoupled"] = {"ms_per_step": round(ms_dec, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_dec * 1e-3),
+                                "kernels": dk}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     g.close()

@@ -54,11 +54,12 @@ __global__ __launch_bounds__(WG) void returns_scan(int B, int T, const float* __
 // ret = v, adv = the policy-gradient advantage: the loss kernel then treats them as it treats the
 // on-policy return and advantage.  Gaussian policy: the densities are compared at the stored
 // pre-squash sample z = mu_old + sigma_old eps_old, and eps_new = (z - mu_new) / sigma_new is
-// written for the loss kernel's score function.  One lane per env, coalesced as in returns_scan.
+// written for the loss kernel's score function.  The ratios need no order and take a pass of
+// their own, one lane per sample; the recursion then walks each env's column as returns_scan does.
 // ---------------------------------------------------------------------------
 struct VtraceArgs {
     int B, T, A, NH, NHP, policy;
-    const float* head_old; const float* head_new; const uint8_t* act; const float* eps_old;
+    const float* head_old; const float* head_new; const float* val_new; const uint8_t* act; const float* eps_old;
     const float* rew; const uint8_t* done;
     float gamma, lambda;
     float* adv; float* ret; float* eps_new;
@@ -85,39 +86,43 @@ __device__ __forceinline__ float log_softmax_at(const float (&hv)[8], int A, int
     return ha - mx - det_log(Z);
 }
 
+// first pass, one lane per sample, no order: the truncated ratio rho (parked in ret, where the scan
+// picks it up before it overwrites the slot with v) and eps_new
+__global__ __launch_bounds__(WG) void vtrace_ratio(const VtraceArgs a)
+{
+    const size_t i = (size_t)blockIdx.x * WG + threadIdx.x;
+    if (i >= (size_t)a.B * a.T) return;
+    float hn[8], ho[8];
+    load_head(a.head_new + i * a.NHP, a.NHP, hn);
+    load_head(a.head_old + i * a.NHP, a.NHP, ho);
+    float lw;
+    if (a.policy == POLICY_CATEGORICAL) {
+        const int act = a.act[i];
+        lw = log_softmax_at(hn, a.A, act) - log_softmax_at(ho, a.A, act);
+    } else {
+        const float lso = fminf(fmaxf(ho[1], -5.0f), 2.0f), lsn = fminf(fmaxf(hn[1], -5.0f), 2.0f);
+        const float eo = a.eps_old[i];
+        const float z = fmaf(det_exp(lso), eo, ho[0]);       // the sampler's own expression
+        const float en = (z - hn[0]) / det_exp(lsn);
+        a.eps_new[i] = en;
+        lw = (-0.5f * en * en - lsn) - (-0.5f * eo * eo - lso);
+    }
+    a.ret[i] = fminf(1.0f, det_exp(lw));
+}
+
+// second pass, one lane per env, backwards in t
 __global__ __launch_bounds__(WG) void vtrace_scan(const VtraceArgs a)
 {
     const int b = blockIdx.x * WG + threadIdx.x;
     if (b >= a.B) return;
-    const int B = a.B, T = a.T, NHP = a.NHP, vi = a.NH - 1;
-    float hn[8], ho[8];
-    load_head(a.head_new + ((size_t)T * B + b) * NHP, NHP, hn);
-    float Vnext = hn[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) if (j == vi) Vnext = hn[j];
+    const int B = a.B, T = a.T;
+    float Vnext = a.val_new[(size_t)T * B + b];
     float tail = 0.0f;                                       // v_{t+1} - V_{t+1}
+#pragma unroll 4
     for (int t = T - 1; t >= 0; --t) {
         const size_t i = (size_t)t * B + b;
-        load_head(a.head_new + i * NHP, NHP, hn);
-        load_head(a.head_old + i * NHP, NHP, ho);
-        float V = hn[0];
-#pragma unroll
-        for (int j = 1; j < 8; ++j) if (j == vi) V = hn[j];
-        float lw;
-        if (a.policy == POLICY_CATEGORICAL) {
-            const int act = a.act[i];
-            lw = log_softmax_at(hn, a.A, act) - log_softmax_at(ho, a.A, act);
-        } else {
-            const float lso = fminf(fmaxf(ho[1], -5.0f), 2.0f), lsn = fminf(fmaxf(hn[1], -5.0f), 2.0f);
-            const float eo = a.eps_old[i];
-            const float z = fmaf(det_exp(lso), eo, ho[0]);   // the sampler's own expression
-            const float en = (z - hn[0]) / det_exp(lsn);
-            a.eps_new[i] = en;
-            lw = (-0.5f * en * en - lsn) - (-0.5f * eo * eo - lso);
-        }
-        const float w = det_exp(lw);
-        const float rho = fminf(1.0f, w), c = a.lambda * rho;
-        const float r = a.rew[i];
+        const float rho = a.ret[i], V = a.val_new[i], r = a.rew[i];
+        const float c = a.lambda * rho;
         const float disc = a.done[i] ? 0.0f : a.gamma;
         a.adv[i] = rho * (fmaf(disc, Vnext + tail, r) - V);
         tail = fmaf(disc * c, tail, rho * (fmaf(disc, Vnext, r) - V));
@@ -924,11 +929,17 @@ hipError_t launch_vtrace(anakin* h)
     const Layout& L = h->lay;
     VtraceArgs a;
     a.B = h->B; a.T = h->T; a.A = h->net.A; a.NH = h->net.NH; a.NHP = h->net.NHP; a.policy = h->net.policy;
-    a.head_old = at<const float>(h, L.tr_head); a.head_new = at<const float>(h, L.head_new);
+    a.head_old = at<const float>(h, L.tr_head); a.head_new = at<const float>(h, L.head_new); a.val_new = at<const float>(h, L.val_new);
     a.act = at<const uint8_t>(h, L.tr_act); a.eps_old = at<const float>(h, L.tr_eps);
     a.rew = at<const float>(h, L.tr_rew); a.done = at<const uint8_t>(h, L.tr_done);
     a.gamma = h->net_cfg.gamma; a.lambda = h->net_cfg.lambda_;
     a.adv = at<float>(h, L.adv); a.ret = at<float>(h, L.ret); a.eps_new = at<float>(h, L.eps_new);
+    {
+        ProfScope prof(h, "vtrace_ratio");
+        hipLaunchKernelGGL(vtrace_ratio, dim3((unsigned)(((size_t)h->B * h->T + WG - 1) / WG)), dim3(WG), 0, h->stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     ProfScope prof(h, "vtrace_scan");
     hipLaunchKernelGGL(vtrace_scan, dim3((h->B + WG - 1) / WG), dim3(WG), 0, h->stream, a);
     return hipGetLastError();
