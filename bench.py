@@ -30,15 +30,15 @@ PEAK_BF16_TFLOPS = 2500.0
 # Reported as roofline.traffic when the dominant kernel of the benchmarked workload is listed.
 MEASURED_TRAFFIC_MB = {
     ("catch_4096", "rollout"): 173.3,
-    ("catch_4096", "gemm_nt_mask"): 254.4,
+    ("catch_4096", "gemm_nt_mask"): 254.2,
     ("catch_4096", "gemm_tn"): 235.3,
     ("catch_4096", "head_backward"): 171.3,
-    ("catch_4096", "first_layer_grad"): 97.9,
+    ("catch_4096", "first_layer_grad"): 98.0,
     ("catch_4096", "adam_reduce"): 86.1,
-    ("maze_16384", "rollout"): 2062.5,
+    ("maze_16384", "rollout"): 1736.7,
     ("maze_16384", "gemm_nt_mask"): 1887.5,      # mean of the two launches (2155.9 with the row-major copy, 1619.0 without)
-    ("maze_16384", "gemm_tn"): 1178.4,
-    ("maze_16384", "gemm_tn_agent"): 606.2,
+    ("maze_16384", "gemm_tn"): 1179.0,
+    ("maze_16384", "gemm_tn_agent"): 606.3,
     ("maze_16384", "gemm_tn_walls"): 68.2,
     ("maze_16384", "head_backward"): 1687.0,
     ("maze_16384", "time_sum"): 570.4,
@@ -80,6 +80,16 @@ def kernel_models(cfg, P):
     nt = tn
     models["gemm_tn"] = ("mfma", tn / 1e12, mfma_peak, "TFLOP/s")
     models["gemm_nt_mask"] = ("mfma", nt / 1e12, mfma_peak, "TFLOP/s")
+    if bf16:
+        # 2-byte operands: 2 K N flop per sample against 2 (N + 2 K) B (dX: dY and the relu mask read, dX written)
+        # resp. 2 (K + N) B (dW: both operands read) is 170 resp. 256 flop/B for 512-wide layers, below the
+        # machine balance of 2500 / 8 = 312 flop/B: both GEMMs sit on the HBM roof, not the matrix-core one
+        nt_bytes = sum(2.0 * (dims[i + 1] + 2 * dims[i]) * M for i in range(1, len(dims) - 1))
+        tn_bytes = sum(2.0 * (dims[i] + dims[i + 1]) * M for i in range(1, len(dims) - 1))
+        if nt / max(nt_bytes, 1.0) < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+            models["gemm_nt_mask"] = ("hbm", nt_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
+        if tn / max(tn_bytes, 1.0) < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+            models["gemm_tn"] = ("hbm", tn_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
     models["gemm_tn_obs"] = ("mfma", 2.0 * dims[0] * dims[1] * M / 1e12, mfma_peak, "TFLOP/s")
     if kind == "maze":
         cells = cfg["env"]["rows"] * cfg["env"]["cols"]
