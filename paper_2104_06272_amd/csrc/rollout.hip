@@ -873,6 +873,156 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
     }
 }
 
+// ---------------------------------------------------------------------------
+// One hidden layer of at most 64 units on a Catch board or the pendulum's three features: the
+// whole agent fits one lane.  Lane b keeps its env's state and the H hidden activations in
+// registers, gathers its two first-layer rows (or takes three fmas per unit) from an LDS copy
+// of W1, runs the NH head chains with the head matrix broadcast from LDS, draws its own random
+// numbers, samples, steps and records -- no exchange between lanes, so no barrier inside the
+// time loop, and every vector instruction works for 64 envs.  The arithmetic per env is the
+// same canonical chain as in rollout_kernel.  No hidden activations are kept: the update of
+// such nets rebuilds the layer from the state.
+// ---------------------------------------------------------------------------
+template <int ENV, int H, bool REPLAY>
+__global__ __launch_bounds__(WG) void rollout_lane_kernel(const RolloutArgs a)
+{
+    constexpr int LDW = H + 4;                                    // row stride of W1 in LDS
+    extern __shared__ float4 smem4[];
+    float* w1s = reinterpret_cast<float*>(smem4);                 // [D][LDW]
+    const int D = a.net.dims[0], NH = a.net.NH, NHP = a.net.NHP;
+    float* b1s = w1s + D * LDW;                                   // [H]
+    float* whs = b1s + H;                                         // [H][8] head weights, k-major, columns >= NH zero
+    float* bhs = whs + H * 8;                                     // [8]
+    const int tid = threadIdx.x;
+    for (int i = tid; i < D * H; i += WG) w1s[(i / H) * LDW + i % H] = a.theta[a.net.w_off[0] + i];
+    for (int i = tid; i < H; i += WG) b1s[i] = a.theta[a.net.b_off[0] + i];
+    for (int i = tid; i < H * 8; i += WG) { const int k = i >> 3, j = i & 7; whs[i] = j < NH ? a.theta[a.net.wh_off + k * NH + j] : 0.0f; }
+    if (tid < 8) bhs[tid] = tid < NH ? a.theta[a.net.bh_off + tid] : 0.0f;
+    __syncthreads();
+
+    const int B = a.B, T = a.T;
+    const int b = blockIdx.x * WG + tid;
+    if (b >= B) return;
+    const TrajPtrs& tp = a.tp;
+    EnvState st{0u, 0.0f, 0.0f};
+    if (!REPLAY) {
+        st.s0 = tp.s0[b];
+        if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+    }
+    for (int t = 0; t <= T; ++t) {
+        const size_t tb = (size_t)t * B + b;
+        if (REPLAY) {
+            st.s0 = tp.tr_s0[tb];
+            if (ENV == ENV_PENDULUM) { st.f0 = tp.tr_f0[tb]; st.f1 = tp.tr_f1[tb]; }
+        } else {
+            tp.tr_s0[tb] = st.s0;
+            if (ENV == ENV_PENDULUM) { tp.tr_f0[tb] = st.f0; tp.tr_f1[tb] = st.f1; }
+        }
+        // the action draw does not depend on the network: issued first, used last
+        u32x4 dr{0u, 0u, 0u, 0u};
+        if (!REPLAY && t < T) dr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_ACTION);
+        // ---- first layer -------------------------------------------------------
+        float h[H];
+        if (ENV == ENV_CATCH) {
+            int bc, pc;
+            catch_obs_cells(a.env, st.s0, bc, pc);
+            const float* r0 = w1s + bc * LDW;
+            const float* r1 = w1s + pc * LDW;
+#pragma unroll
+            for (int j = 0; j < H; j += 4) {
+                const float4 bb = ld4(b1s + j), w0 = ld4(r0 + j), w1 = ld4(r1 + j);
+                h[j] = (bb.x + w0.x) + w1.x; h[j + 1] = (bb.y + w0.y) + w1.y;
+                h[j + 2] = (bb.z + w0.z) + w1.z; h[j + 3] = (bb.w + w0.w) + w1.w;
+            }
+        } else {
+            float sn, cs;
+            det_sincos(st.f0, sn, cs);
+            const float x[3] = {cs, sn, st.f1};
+#pragma unroll
+            for (int j = 0; j < H; j += 4) {
+                const float4 bb = ld4(b1s + j);
+                float v[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    const float4 w = ld4(w1s + k * LDW + j);
+                    v[0] = fmaf(x[k], w.x, v[0]); v[1] = fmaf(x[k], w.y, v[1]);
+                    v[2] = fmaf(x[k], w.z, v[2]); v[3] = fmaf(x[k], w.w, v[3]);
+                }
+                h[j] = v[0]; h[j + 1] = v[1]; h[j + 2] = v[2]; h[j + 3] = v[3];
+            }
+        }
+        // ---- heads: NH chains over k, ascending --------------------------------
+        float hv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) hv[j] = bhs[j];
+#pragma unroll
+        for (int k = 0; k < H; ++k) {
+            const float x = h[k] > 0.0f ? h[k] : 0.0f;
+            const float4 wa = ld4(whs + k * 8);
+            hv[0] = fmaf(x, wa.x, hv[0]); hv[1] = fmaf(x, wa.y, hv[1]);
+            hv[2] = fmaf(x, wa.z, hv[2]); hv[3] = fmaf(x, wa.w, hv[3]);
+            if (NHP == 8) {
+                const float4 wb = ld4(whs + k * 8 + 4);
+                hv[4] = fmaf(x, wb.x, hv[4]); hv[5] = fmaf(x, wb.y, hv[5]);
+                hv[6] = fmaf(x, wb.z, hv[6]); hv[7] = fmaf(x, wb.w, hv[7]);
+            }
+        }
+        float* hd = tp.tr_head + tb * NHP;
+        *reinterpret_cast<float4*>(hd) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = make_float4(hv[4], hv[5], hv[6], hv[7]);
+        float val = hv[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
+        tp.tr_val[tb] = val;
+        if (!REPLAY && t < T) {
+            float r; int done;
+            if (ENV == ENV_PENDULUM) {
+                float eps, act;
+                sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
+                tp.tr_eps[tb] = eps;
+                tp.tr_actf[tb] = act;
+                pendulum_step(a.env, st, act, 0u, 0u, r, done);
+                if (done) {
+                    const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                    pendulum_reset(st, wr.x, wr.y);
+                }
+            } else {
+                const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
+                tp.tr_act[tb] = (uint8_t)act;
+                catch_step(a.env, st, act, 0u, r, done);
+                if (done) {
+                    const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
+                    st.s0 = catch_reset(a.env, wr.x);
+                }
+            }
+            tp.tr_rew[tb] = r;
+            tp.tr_done[tb] = (uint8_t)done;
+        }
+    }
+    if (!REPLAY) {
+        tp.s0[b] = st.s0;
+        if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
+    }
+}
+
+// one-hidden-layer nets the lane kernel takes: width 32 or 64 on Catch or the pendulum, fp32, no kept activations
+static int rollout_lane_width(const anakin* h)
+{
+    const NetShape& n = h->net;
+    if (n.bf16 || n.L != 1 || h->env.kind == ENV_MAZE || !one_layer_fused(h)) return 0;
+    if (h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS)) return 0;
+    return (n.dims[1] == 32 || n.dims[1] == 64) ? n.dims[1] : 0;
+}
+
+template <int ENV, int H, bool REPLAY>
+static hipError_t launch_lane(anakin* h, const RolloutArgs& a)
+{
+    const size_t lds = ((size_t)h->net.dims[0] * (H + 4) + H + H * 8 + 8) * 4;
+    ProfScope prof(h, REPLAY ? "replay_forward" : "rollout");
+    hipLaunchKernelGGL((rollout_lane_kernel<ENV, H, REPLAY>), dim3((h->B + WG - 1) / WG), dim3(WG), lds, h->stream, a);
+    return hipGetLastError();
+}
+
 // which resident shape (if any) fits this net: 0 none, else the width (64, 128, 256)
 int rollout_resident_width(const NetShape& net)
 {
@@ -988,6 +1138,12 @@ template <bool REPLAY>
 static hipError_t launch_forward(anakin* h, const RolloutArgs& a)
 {
     const bool bf = h->net.bf16 != 0;
+    if (const int lw = rollout_lane_width(h)) {
+        if (a.keep_acts == 0) {
+            if (h->env.kind == ENV_CATCH) return lw == 32 ? launch_lane<ENV_CATCH, 32, REPLAY>(h, a) : launch_lane<ENV_CATCH, 64, REPLAY>(h, a);
+            return lw == 32 ? launch_lane<ENV_PENDULUM, 32, REPLAY>(h, a) : launch_lane<ENV_PENDULUM, 64, REPLAY>(h, a);
+        }
+    }
     if (h->TM_res > 0 && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_STREAM_WEIGHTS))) {
         const int w = rollout_resident_width(h->net);
         switch (h->env.kind) {
