@@ -825,17 +825,51 @@ static void forward64(const orc_t* h, const double* wq, size_t tb, double act[5]
     }
 }
 
+/* Backward pass of one sample: given the forward activations and the gradient dhead of a scalar
+ * with respect to the head outputs, adds that scalar's parameter gradient to g; dobs (optional)
+ * receives its gradient with respect to the observation. */
+static void backprop_sample(const orc_t* h, const double* wq, double act[5][1024], const double* dhead,
+                            double* g, double* dobs)
+{
+    int NH = h->NH, L = h->L;
+    double dz[2][1024];
+    {
+        int K = h->dims[L];
+        double* gW = g + h->wh_off;
+        const double* W = wq + h->wh_off;
+        for (int j = 0; j < NH; ++j) g[h->bh_off + j] += dhead[j];
+        for (int k = 0; k < K; ++k) {
+            double s = 0;
+            for (int j = 0; j < NH; ++j) { gW[(size_t)k * NH + j] += act[L][k] * dhead[j]; s += W[(size_t)k * NH + j] * dhead[j]; }
+            dz[L & 1][k] = act[L][k] > 0.0 ? s : 0.0;
+        }
+    }
+    for (int l = L - 1; l >= 0; --l) {
+        int K = h->dims[l], N = h->dims[l + 1];
+        double* gW = g + h->w_off[l];
+        const double* W = wq + h->w_off[l];
+        const double* d = dz[(l + 1) & 1];
+        for (int j = 0; j < N; ++j) g[h->b_off[l] + j] += d[j];
+        for (int k = 0; k < K; ++k) {
+            double xk = act[l][k], s = 0;
+            for (int j = 0; j < N; ++j) { gW[(size_t)k * N + j] += xk * d[j]; s += W[(size_t)k * N + j] * d[j]; }
+            if (l > 0) dz[l & 1][k] = xk > 0.0 ? s : 0.0;
+            else if (dobs) dobs[k] = s;
+        }
+    }
+}
+
 /* Loss and gradient over the samples tb_begin <= t*B + b < tb_end (mean over    */
 /* those samples), with the parameters theta_src.                              */
 static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begin, size_t tb_end)
 {
-    int NH = h->NH, L = h->L;
+    int NH = h->NH;
     size_t n = tb_end - tb_begin;
     double inv_n = 1.0 / (double)n;
     double beta = (double)h->net.entropy_coef, cv = (double)h->net.value_coef;
     double* g = (double*)zalloc(h->P * sizeof(double));
     double* wq = forward_params64(h, theta_src);             /* parameters as the forward sees them */
-    double act[5][1024], dz[2][1024], head[16], dhead[16];
+    double act[5][1024], head[16], dhead[16];
     double Lp = 0, Lv = 0, Le = 0;
     for (size_t tb = tb_begin; tb < tb_end; ++tb) {
         forward64(h, wq, tb, act, head);
@@ -865,30 +899,7 @@ static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begi
             dhead[0] = (-A_ * eps / sigma) * inv_n;
             dhead[1] = clamped ? 0.0 : (-A_ * (eps * eps - 1.0) - beta) * inv_n;
         }
-        /* backward: heads, then hidden layers from last to first */
-        {
-            int K = h->dims[L];
-            double* gW = g + h->wh_off;
-            const double* W = wq + h->wh_off;
-            for (int j = 0; j < NH; ++j) g[h->bh_off + j] += dhead[j];
-            for (int k = 0; k < K; ++k) {
-                double s = 0;
-                for (int j = 0; j < NH; ++j) { gW[(size_t)k * NH + j] += act[L][k] * dhead[j]; s += W[(size_t)k * NH + j] * dhead[j]; }
-                dz[L & 1][k] = act[L][k] > 0.0 ? s : 0.0;
-            }
-        }
-        for (int l = L - 1; l >= 0; --l) {
-            int K = h->dims[l], N = h->dims[l + 1];
-            double* gW = g + h->w_off[l];
-            const double* W = wq + h->w_off[l];
-            const double* d = dz[(l + 1) & 1];
-            for (int j = 0; j < N; ++j) g[h->b_off[l] + j] += d[j];
-            for (int k = 0; k < K; ++k) {
-                double xk = act[l][k], s = 0;
-                for (int j = 0; j < N; ++j) { gW[(size_t)k * N + j] += xk * d[j]; s += W[(size_t)k * N + j] * d[j]; }
-                if (l > 0) dz[l & 1][k] = xk > 0.0 ? s : 0.0;
-            }
-        }
+        backprop_sample(h, wq, act, dhead, g, NULL);
     }
     h->loss[1] = Lp * inv_n; h->loss[2] = Lv * inv_n; h->loss[3] = Le * inv_n;
     h->loss[0] = h->loss[1] + h->loss[2] + h->loss[3];
@@ -1053,6 +1064,93 @@ void orc_step_decoupled(orc_t* h)
     orc_rollout(h, NULL);
     h->theta = learner;
     free(behaviour);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Pathwise policy gradient (paper section 3.1: with the environment part of    */
+/* the same program, the unit of T interactions can be differentiated all the   */
+/* way through).  Reading R-34, pendulum with the tanh-Gaussian policy only      */
+/* (its dynamics are differentiable; the board games are not):                   */
+/*   L = L_path + L_value + L_entropy,   L_path = -(1/(B T)) sum_{b,t} r_{b,t}    */
+/* where the rewards are those of the stored unroll seen as a function of the     */
+/* parameters: the noise eps_t is fixed, a_t = tanh(mu(o_t) + sigma(o_t) eps_t),   */
+/* u_t = 2 a_t, r_t and s_{t+1} follow the env's step from (s_t, u_t), and the     */
+/* state after an episode end is a reset state that does not depend on the        */
+/* parameters.  The velocity clip passes no gradient where it is active; angle    */
+/* wrapping and the (never active) torque clip pass it unchanged.  L_value and     */
+/* L_entropy are the terms of R-24 with the states held fixed.  The gradient of    */
+/* L_path is taken by reverse accumulation over t with the adjoint                 */
+/* lambda_t = dL_path/ds_t, linearised at the stored binary32 states:              */
+/*   through the step   th' = th + dt thd',  thd' = clip(thd + dt (15 sin th + 3u)) */
+/*   through the reward r = -(th^2 + 0.1 thd^2 + 0.001 u^2)                          */
+/*   through the policy  u = 2 tanh(mu + exp(clamp(ls)) eps),  o = (cos th, sin th, thd) */
+/* path_dhead[t][b][0..1] holds dL_path/d(mu, log_sigma) at every sample.          */
+/* ------------------------------------------------------------------------- */
+void orc_pathwise_grad(orc_t* h, double* g, double* path_dhead)
+{
+    int B = h->B, T = h->T, NH = h->NH;
+    const double dt = (double)0x1.99999ap-5f, c_thd = (double)0x1.99999ap-4f, c_u = (double)0x1.0624dep-10f;
+    const double w = -1.0 / ((double)B * (double)T);           /* dL_path / dr */
+    double* wq = forward_params64(h, h->theta);
+    double act[5][1024], head[16], dhead[16], dobs[8];
+    for (int b = 0; b < B; ++b) {
+        double lam_th = 0.0, lam_thd = 0.0;                       /* adjoint of the state after step t */
+        for (int t = T - 1; t >= 0; --t) {
+            size_t tb = (size_t)t * B + b;
+            if (h->tr_done[tb]) { lam_th = 0.0; lam_thd = 0.0; }   /* the next state is a reset state */
+            forward64(h, wq, tb, act, head);
+            double th = (double)h->tr_sf[tb * 2], thd = (double)h->tr_sf[tb * 2 + 1];
+            double mu = head[0], ls = head[1];
+            int clamped = (ls < -5.0) || (ls > 2.0);
+            double sigma = exp(ls < -5.0 ? -5.0 : (ls > 2.0 ? 2.0 : ls));
+            double eps = (double)h->tr_eps[tb];
+            double a = tanh(mu + sigma * eps), u = 2.0 * a;
+            double pre = thd + dt * (15.0 * sin(th) + 3.0 * u);
+            int clipped = (pre < -8.0) || (pre > 8.0);
+            /* adjoint through th' = th + dt thd' and the clip */
+            double g_nthd = lam_thd + dt * lam_th;
+            double g_pre = clipped ? 0.0 : g_nthd;
+            double g_th = lam_th + g_pre * dt * 15.0 * cos(th) + w * (-2.0 * th);
+            double g_thd = g_pre + w * (-2.0 * c_thd * thd);
+            double g_u = g_pre * dt * 3.0 + w * (-2.0 * c_u * u);
+            double g_z = 2.0 * g_u * (1.0 - a * a);
+            for (int j = 0; j < NH; ++j) dhead[j] = 0.0;
+            dhead[0] = g_z;
+            dhead[1] = clamped ? 0.0 : g_z * sigma * eps;
+            if (path_dhead) { path_dhead[tb * 2] = dhead[0]; path_dhead[tb * 2 + 1] = dhead[1]; }
+            backprop_sample(h, wq, act, dhead, g, dobs);
+            /* o = (cos th, sin th, thd) */
+            lam_th = g_th - sin(th) * dobs[0] + cos(th) * dobs[1];
+            lam_thd = g_thd + dobs[2];
+        }
+    }
+    free(wq);
+}
+
+/* one update with the objective of R-34 on the stored unroll */
+int orc_learn_pathwise(orc_t* h)
+{
+    if (!h->have_traj) return -1;
+    if (h->env.kind != ENV_PENDULUM || h->net.policy != POLICY_TANH_GAUSSIAN) return -2;
+    size_t tn = (size_t)h->T * h->B;
+    orc_returns(h->T, h->B, h->tr_rew, h->tr_done, h->tr_val,
+                (double)h->net.gamma, (double)h->net.lambda_, h->ret, h->adv);
+    for (size_t i = 0; i < tn; ++i) h->adv[i] = 0.0;          /* no score-function term */
+    orc_loss_and_grad(h);
+    double* g = (double*)zalloc(h->P * sizeof(double));
+    for (size_t i = 0; i < h->P; ++i) g[i] = (double)h->grad[i];
+    orc_pathwise_grad(h, g, NULL);
+    for (size_t i = 0; i < h->P; ++i) h->grad[i] = (float)g[i];
+    free(g);
+    double rs = 0.0;
+    for (size_t i = 0; i < tn; ++i) rs += (double)h->tr_rew[i];
+    h->loss[1] = -rs / (double)tn;
+    h->loss[0] = h->loss[1] + h->loss[2] + h->loss[3];
+    h->adam_t += 1;
+    orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t,
+             (double)h->net.lr, (double)h->net.beta1, (double)h->net.beta2, (double)h->net.eps);
+    h->have_traj = 0;
+    return 0;
 }
 
 /* the surrogate objective only (no gradient, no update): used by the finite-

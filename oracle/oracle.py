@@ -93,6 +93,8 @@ def lib():
         L.orc_vtrace_targets.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_vtrace_targets.restype = None
         L.orc_learn_vtrace.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_learn_vtrace.restype = C.c_int
         L.orc_step_decoupled.argtypes = [C.c_void_p]; L.orc_step_decoupled.restype = None
+        L.orc_pathwise_grad.argtypes = [C.c_void_p, f64p, f64p]; L.orc_pathwise_grad.restype = None
+        L.orc_learn_pathwise.argtypes = [C.c_void_p]; L.orc_learn_pathwise.restype = C.c_int
         _lib = L
     return _lib
 
@@ -294,6 +296,18 @@ class Oracle:
     def learn_vtrace(self, rho_bar=1.0, c_bar=1.0):
         if self.L.orc_learn_vtrace(self.h, float(rho_bar), float(c_bar)) != 0:
             raise RuntimeError("learn_vtrace without a stored trajectory")
+
+    def pathwise_grad(self):
+        """Gradient of L_path = -mean reward of the stored unroll through env and policy (binary64), and
+        dL_path/d(mu, log_sigma) per sample."""
+        g = np.zeros(self.P); ph = np.zeros((self.T, self.B, 2))
+        self.L.orc_pathwise_grad(self.h, _ptr(g, C.c_double), _ptr(ph, C.c_double))
+        return g, ph
+
+    def learn_pathwise(self):
+        rc = self.L.orc_learn_pathwise(self.h)
+        if rc != 0:
+            raise RuntimeError("learn_pathwise: no stored trajectory" if rc == -1 else "learn_pathwise: pendulum with the tanh-Gaussian policy only")
 
     def step_decoupled(self):
         """Actor unroll with the parameters as they are now, learner update on the previous unroll."""

@@ -872,6 +872,94 @@ def test_decoupled_step_semantics(orc):
     assert not np.array_equal(theta1, theta2)
 
 
+# --------------------------------------------------------------------------- pathwise gradient through the env
+def _simulate_path_loss(o, theta, max_steps):
+    """-mean reward of the unroll as a function of the parameters, written out in float64: same noise, same start
+    states, same reset states after an episode end; the pendulum's step and the tanh-Gaussian policy in plain
+    formulas."""
+    Ws, bs, Wh, bh = _unpack(o, theta)
+    T, B = o.T, o.B
+    dt, c_thd, c_u = float(np.float32(0.05)), float(np.float32(0.1)), float(np.float32(0.001))
+    th = o.tr_state_f[0, :, 0].astype(np.float64); thd = o.tr_state_f[0, :, 1].astype(np.float64)
+    total = 0.0
+    for t in range(T):
+        x = np.stack([np.cos(th), np.sin(th), thd], 1)
+        for Wm, bv in zip(Ws, bs):
+            x = np.maximum(x @ Wm + bv, 0)
+        head = x @ Wh + bh
+        u = 2 * np.tanh(head[:, 0] + np.exp(np.clip(head[:, 1], -5, 2)) * o.tr_eps[t])
+        total += -(th ** 2 + c_thd * thd ** 2 + c_u * u ** 2).sum()
+        nthd = np.clip(thd + dt * (15 * np.sin(th) + 3 * u), -8, 8)
+        nth = th + dt * nthd
+        nth = np.where(nth >= math.pi, nth - 2 * math.pi, np.where(nth < -math.pi, nth + 2 * math.pi, nth))
+        done = o.tr_done[t].astype(bool)
+        th = np.where(done, o.tr_state_f[t + 1, :, 0], nth); thd = np.where(done, o.tr_state_f[t + 1, :, 1], nthd)
+    return -total / (T * B)
+
+
+def test_pathwise_gradient_vs_finite_differences(orc):
+    """Reverse accumulation through policy and dynamics against central differences of the re-simulated unroll
+    (episode ends inside the unroll cut the adjoint; one env runs into the velocity clip)."""
+    cfg = tiny("pendulum", hidden=(6, 5), B=5, T=9, max_steps=4)
+    o = orc.Oracle(cfg, seed=21)
+    rng = np.random.default_rng(5)
+    o.theta[:] += rng.standard_normal(o.P).astype(np.float32) * 0.4
+    o.state_f[0] = (2.0, 7.9)                       # fast enough to hit the clip at +-8 within the unroll
+    o.rollout()
+    assert o.tr_done.sum() >= 2 and (np.abs(o.tr_state_f[..., 1]) == 8.0).any()
+    th0 = o.theta.astype(np.float64)
+    # the re-simulation follows the stored unroll (binary32 states) to rounding
+    assert abs(_simulate_path_loss(o, th0, 4) + o.tr_reward.astype(np.float64).mean()) < 1e-5
+    g, ph = o.pathwise_grad()
+    h = 1e-6
+    fd = np.zeros(o.P)
+    for i in range(o.P):
+        tp, tm = th0.copy(), th0.copy()
+        tp[i] += h; tm[i] -= h
+        fd[i] = (_simulate_path_loss(o, tp, 4) - _simulate_path_loss(o, tm, 4)) / (2 * h)
+    assert np.linalg.norm(fd) > 1e-3
+    # the adjoint is linearised at the stored binary32 states, the differences re-simulate in float64
+    assert np.linalg.norm(g - fd) / np.linalg.norm(fd) < 2e-5, np.linalg.norm(g - fd) / np.linalg.norm(fd)
+    # a one-step unroll has no dynamics in it: d(-r)/du = 0.002 u through u = 2 tanh(z)
+    cfg1 = tiny("pendulum", hidden=(6, 5), B=4, T=1)
+    o1 = orc.Oracle(cfg1, seed=2)
+    o1.rollout()
+    _, ph1 = o1.pathwise_grad()
+    a = o1.tr_action_f[0].astype(np.float64)
+    sigma = np.exp(np.clip(o1.tr_head[0, :, 1].astype(np.float64), -5, 2))
+    gz = (2 * float(np.float32(0.001)) * 2 * a) * 2 * (1 - a * a) / 4
+    assert np.allclose(ph1[0, :, 0], gz, rtol=1e-5, atol=1e-12)
+    assert np.allclose(ph1[0, :, 1], gz * sigma * o1.tr_eps[0], rtol=1e-5, atol=1e-12)
+
+
+def test_pathwise_update_composition(orc):
+    """learn_pathwise = value and entropy terms of the usual objective (no score-function term) plus the pathwise
+    gradient, one Adam step; the reported policy loss is minus the mean reward.  Board envs are refused."""
+    cfg = tiny("pendulum", hidden=(6, 5), B=6, T=8, max_steps=5)
+    a = orc.Oracle(cfg, seed=8); b = orc.Oracle(cfg, seed=8)
+    a.rollout(); b.rollout()
+    ret, adv = orc.returns(b.tr_reward, b.tr_done, b.tr_value, float(np.float32(cfg["net"]["gamma"])),
+                           float(np.float32(cfg["net"]["lambda"])))
+    b.ret[:] = ret; b.adv[:] = 0.0
+    b.loss_and_grad()
+    gp, _ = b.pathwise_grad()
+    g = b.grad.astype(np.float64) + gp
+    a.learn_pathwise()
+    assert np.abs(a.grad - g).max() <= 1e-6 * max(1.0, np.abs(g).max())
+    assert abs(a.loss[1] + a.tr_reward.astype(np.float64).mean()) < 1e-12
+    assert abs(a.loss[2] - b.loss[2]) < 1e-12 and abs(a.loss[3] - b.loss[3]) < 1e-12
+    th = b.theta.astype(np.float64); m = np.zeros(b.P); v = np.zeros(b.P)
+    lr, b1, b2, eps = (cfg["net"][k] for k in ("lr", "beta1", "beta2", "eps"))
+    gf = a.grad.astype(np.float64)
+    m = (1 - b1) * gf; v = (1 - b2) * gf * gf
+    th = th - lr * (m / (1 - b1)) / (np.sqrt(v / (1 - b2)) + eps)
+    assert np.abs(a.theta - th).max() <= 2e-7 and a.adam_t == 1
+    c = orc.Oracle(tiny("catch"), seed=0)
+    c.rollout()
+    with pytest.raises(RuntimeError):
+        c.learn_pathwise()
+
+
 def test_catch_learning_sanity(orc):
     # not a parity criterion: the mean episode return should rise from about -0.6
     cfg = W.get("catch_small", B=64, T=20)
