@@ -178,6 +178,17 @@ int32_t anakin_set_mode(anakin_t* h, int32_t flags);
  * kernels' row granularity; the setting is kept until changed.  Default 1. */
 int32_t anakin_set_updates_per_unroll(anakin_t* h, int32_t n_updates);
 
+/* Which policy gradient anakin_learn takes.  ANAKIN_PG_SCORE_FUNCTION (default): the actor-critic
+ * term -A log pi(a|s).  ANAKIN_PG_PATHWISE: the gradient of minus the mean reward of the stored
+ * unroll through the environment's dynamics and the reparameterised policy (paper section 3.1:
+ * the unit of T interactions, environment included, can be differentiated all the way through);
+ * value and entropy terms stay as they are, the reported policy loss becomes minus the mean
+ * reward.  Pendulum with the tanh-Gaussian policy, fp32 net of two equal hidden layers of 64, 128
+ * or 256 units, B a multiple of 16, one update per unroll: ANAKIN_E_BAD_CONFIG otherwise (for the
+ * last, from anakin_learn).  Kept until changed. */
+enum { ANAKIN_PG_SCORE_FUNCTION = 0, ANAKIN_PG_PATHWISE = 1 };
+int32_t anakin_set_policy_gradient(anakin_t* h, int32_t kind);
+
 /* Per-kernel timing for measurement.  While enabled, every kernel launch is
  * bracketed by two events recorded on the handle's stream (this adds a few
  * microseconds per launch, so throughput is timed with profiling off).

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("ANAKIN_LIB", os.path.join(_HERE, "libanakin.so"))
 OK = 0
 E_INVALID_ARG, E_BAD_CONFIG, E_WORKSPACE_TOO_SMALL, E_MISALIGNED, E_HIP, E_NONFINITE, E_STATE = -1, -2, -3, -4, -5, -6, -7
 MODE_VALU_GEMM, MODE_CANONICAL_ACTING, MODE_STREAM_WEIGHTS = 1, 2, 4
+PG_SCORE_FUNCTION, PG_PATHWISE = 0, 1
 
 ENV_KINDS = {"catch": 0, "pendulum": 1, "maze": 2}
 POLICIES = {"categorical": 0, "tanh_gaussian": 1}
@@ -59,7 +60,7 @@ EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
-           "anakin_get_metrics", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
+           "anakin_get_metrics", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_set_policy_gradient", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
            "anakin_last_error"]
 
 _lib = None
@@ -102,6 +103,7 @@ def load():
     L.anakin_get_metrics.argtypes = [vp, C.POINTER(Metrics)]
     L.anakin_set_mode.argtypes = [vp, C.c_int32]
     L.anakin_set_updates_per_unroll.argtypes = [vp, C.c_int32]
+    L.anakin_set_policy_gradient.argtypes = [vp, C.c_int32]
     L.anakin_profile.argtypes = [vp, C.c_int32]
     L.anakin_kernel_times.argtypes = [vp, C.POINTER(KernelTime), C.c_int32, C.POINTER(C.c_int32)]
     L.anakin_last_error.argtypes = [vp]
@@ -190,6 +192,9 @@ class Anakin:
 
     def step(self):
         self._chk(self.L.anakin_step(self.h))
+
+    def set_policy_gradient(self, kind):
+        self._chk(self.L.anakin_set_policy_gradient(self.h, int(kind)))
 
     def step_decoupled(self):
         self._chk(self.L.anakin_step_decoupled(self.h))

@@ -131,6 +131,7 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     L.alt_tr_rew = take(dec ? tn * 4 : 0); L.alt_tr_done = take(dec ? tn : 0);
     L.alt_tr_val = take(dec ? t1n * 4 : 0); L.alt_tr_head = take(dec ? t1n * ns.NHP * 4 : 0);
     L.head_new = take(dec ? t1n * ns.NHP * 4 : 0); L.val_new = take(dec ? t1n * 4 : 0); L.eps_new = take(dec ? tn * 4 : 0);
+    L.path = take(ed.kind == ENV_PENDULUM && !ns.bf16 ? tn * 2 * 4 : 0);
     L.total = off;
 }
 
@@ -317,6 +318,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0; h->traj_no_acts = 0;
+    h->pathwise = 0;
     h->traj_decoupled = 0; h->actor_stream = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
@@ -499,6 +501,10 @@ extern "C" int32_t anakin_learn(anakin_t* h)
     if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     if (h->traj_no_acts != (one_layer_fused(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     HIPCHK(h, launch_returns(h));
+    if (h->pathwise) {
+        if (h->n_updates != 1) { h->err = "the pathwise policy gradient takes one update per unroll (chunks would cut the adjoint)"; return ANAKIN_E_BAD_CONFIG; }
+        HIPCHK(h, launch_pathwise(h));
+    }
     if (h->n_updates == 1) {
         int32_t rc = run_update(h);
         if (rc != ANAKIN_OK) return rc;
@@ -538,6 +544,18 @@ extern "C" int32_t anakin_learn(anakin_t* h)
     h->splits_w = full_sw; h->head_fan = full_fan; h->loss_blocks = full_lb;
     if (rc != ANAKIN_OK) return rc;
     h->have_traj = 0;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_set_policy_gradient(anakin_t* h, int32_t kind)
+{
+    NEED(h);
+    if (kind != ANAKIN_PG_SCORE_FUNCTION && kind != ANAKIN_PG_PATHWISE) { h->err = "unknown policy-gradient kind"; return ANAKIN_E_INVALID_ARG; }
+    if (kind == ANAKIN_PG_PATHWISE && !pathwise_ok(h)) {
+        h->err = "the pathwise policy gradient needs the pendulum with the tanh-Gaussian policy, an fp32 net of two equal hidden layers of 64, 128 or 256 units, and B a multiple of 16";
+        return ANAKIN_E_BAD_CONFIG;
+    }
+    h->pathwise = kind == ANAKIN_PG_PATHWISE ? 1 : 0;
     return ANAKIN_OK;
 }
 
@@ -583,6 +601,7 @@ extern "C" int32_t anakin_step_decoupled(anakin_t* h)
     NEED(h);
     if (h->net.bf16) { h->err = "decoupled steps run fp32 nets only"; return ANAKIN_E_BAD_CONFIG; }
     if (h->n_updates != 1) { h->err = "decoupled steps apply one update per unroll"; return ANAKIN_E_BAD_CONFIG; }
+    if (h->pathwise) { h->err = "decoupled steps use the score-function gradient"; return ANAKIN_E_BAD_CONFIG; }
     if (h->prof_pending.size() > 8192) HIPCHK(h, prof_resolve(h));
     if (!h->actor_stream) {
         HIPCHK(h, hipStreamCreateWithFlags(&h->actor_stream, hipStreamNonBlocking));

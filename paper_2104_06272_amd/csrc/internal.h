@@ -115,6 +115,7 @@ struct Layout {
     size_t theta_b;
     size_t alt_tr_s0, alt_tr_f0, alt_tr_f1, alt_tr_act, alt_tr_eps, alt_tr_actf, alt_tr_rew, alt_tr_done, alt_tr_val, alt_tr_head;
     size_t head_new, val_new, eps_new;
+    size_t path;                 // pathwise policy gradient: dL_path / d(mu, log_sigma) per sample, [T*B][2]
     size_t total;
 };
 
@@ -147,6 +148,7 @@ struct anakin {
     int bf16_path;                // the bf16 matrix-core kernels support this net
     int traj_packed;              // the stored unroll holds packed bf16 activations
     int traj_no_acts;             // the stored unroll holds no hidden activations (one-layer nets)
+    int pathwise;                 // policy gradient through the environment instead of the score function (pendulum)
     int traj_decoupled;           // the stored unroll was collected by a decoupled step: behaviour parameters, no activations
     hipStream_t actor_stream;     // decoupled steps: the actor's stream (created on first use), and the fork/join events
     hipEvent_t ev_fork, ev_join;
@@ -177,6 +179,8 @@ hipError_t launch_rollout(anakin* h);
 hipError_t launch_rollout_behaviour(anakin* h);
 hipError_t launch_replay_forward(anakin* h);
 hipError_t launch_vtrace(anakin* h);
+hipError_t launch_pathwise(anakin* h);
+bool pathwise_ok(const anakin* h);
 hipError_t launch_returns(anakin* h);
 hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);

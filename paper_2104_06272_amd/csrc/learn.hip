@@ -144,6 +144,8 @@ struct HeadGradArgs {
     const float* rew; const uint8_t* done;
     float* dhead; float* loss_part;        // [blocks][8]
     float beta, cv, inv_m;
+    const float* path;                     // pathwise policy gradient: dL/d(mu, log_sigma) per sample replaces the
+                                           // score-function term, and the reported policy loss is minus the mean reward
 };
 
 __global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
             const float4 h1 = *reinterpret_cast<const float4*>(h + 4);
             hv[4] = h1.x; hv[5] = h1.y; hv[6] = h1.z; hv[7] = h1.w;
         } else { hv[4] = hv[5] = hv[6] = hv[7] = 0.0f; }
-        const float A_ = a.adv[i], G_ = a.ret[i];
+        const float A_ = a.path ? 0.0f : a.adv[i], G_ = a.ret[i];
         float V = hv[0];
 #pragma unroll
         for (int j = 1; j < 8; ++j) if (j == a.NH - 1) V = hv[j];
@@ -202,6 +204,11 @@ __global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) if (j == a.NH - 1) d[j] = gV;
+        if (a.path) {
+            const float2 pg = *reinterpret_cast<const float2*>(a.path + (size_t)i * 2);
+            d[0] += pg.x; d[1] += pg.y;
+            lp_term = -a.rew[i];
+        }
         float* o = a.dhead + (size_t)i * a.NHP;
         *reinterpret_cast<float4*>(o) = make_float4(d[0], d[1], d[2], d[3]);
         if (a.NHP == 8) *reinterpret_cast<float4*>(o + 4) = make_float4(d[4], d[5], d[6], d[7]);
@@ -955,6 +962,7 @@ hipError_t launch_head_grad(anakin* h)
     a.rew = at<const float>(h, L.tr_rew); a.done = at<const uint8_t>(h, L.tr_done);
     a.dhead = at<float>(h, L.dhead); a.loss_part = at<float>(h, L.loss_part);
     a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef; a.inv_m = (float)(1.0 / (double)a.M);
+    a.path = h->pathwise ? at<const float>(h, L.path) : nullptr;
     ProfScope prof(h, "head_grad");
     hipLaunchKernelGGL(head_grad, dim3(h->loss_blocks), dim3(WG), 0, h->stream, a);
     return hipGetLastError();

@@ -393,6 +393,67 @@ def test_decoupled_rejects_bf16(gpu):
     g.close()
 
 
+def _path_only(cfg):
+    cfg = copy.deepcopy(cfg)
+    cfg["net"]["value_coef"] = 0.0; cfg["net"]["entropy_coef"] = 0.0     # nothing but the pathwise term in the gradient
+    return cfg
+
+
+PATHWISE_CASES = {
+    "pendulum_64_path_term_only": (_path_only(variant("pendulum_8192", hidden=[64, 64], B=32, T=20, max_steps=13)), 7, 2),
+    # name: (cfg, seed, updates) -- the three widths of the sweep kernel, episode ends inside the unroll
+    "pendulum_256_B128": (variant("pendulum_8192", B=128), 0, 2),
+    "pendulum_64_short_episodes": (variant("pendulum_8192", hidden=[64, 64], B=64, T=32, max_steps=25), 2, 3),
+    "pendulum_128_B48": (variant("pendulum_8192", hidden=[128, 128], B=48, T=12, max_steps=7), 4, 2),
+}
+
+
+@pytest.mark.parametrize("case", list(PATHWISE_CASES))
+def test_pathwise_lockstep(gpu, orc, case):
+    """Policy gradient through the pendulum's dynamics: per-sample head gradients of the reverse sweep and the whole
+    update against the oracle's binary64 reverse accumulation, parameter-synchronised."""
+    cfg, seed, updates = PATHWISE_CASES[case]
+    say(f"[pathwise] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+    g = gpu.Anakin(cfg, seed=seed)
+    o = orc.Oracle(cfg, seed=seed)
+    g.set_policy_gradient(gpu.PG_PATHWISE)
+    for u in range(updates):
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout(); o.rollout()
+        PT.assert_rollout_equal(g, o, "pendulum")
+        _, ph = o.pathwise_grad()
+        rew, done = o.tr_reward.copy(), o.tr_done.copy()
+        adv_zero = np.zeros_like(o.adv)
+        g.learn(); o.learn_pathwise()
+        tr = g.trajectory()
+        tr["adv"] = adv_zero                 # the score-function advantage is not used on either side
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=(rew, done))
+        say(f"  update {u}: grad rel {e_g:.2e}, param rel {e_p:.2e}, -mean reward {o.loss[1]:+.4f}, |path dhead| {np.abs(ph).max():.3e}")
+    if cfg["env"]["max_steps"] < cfg["T"]:
+        assert o.tr_done.sum() > 0                   # the adjoint was cut inside the unroll
+    g.set_policy_gradient(gpu.PG_SCORE_FUNCTION)
+    PT.sync_oracle_from_gpu(g, o)
+    g.step(); o.step()
+    PT.assert_learn_close(g, o, TOL_F32)
+    g.close()
+
+
+def test_pathwise_rejections(gpu):
+    c = gpu.Anakin(variant("catch_small"), seed=0)
+    with pytest.raises(gpu.AnakinError):
+        c.set_policy_gradient(gpu.PG_PATHWISE)
+    c.close()
+    p = gpu.Anakin(variant("pendulum_8192", hidden=[64, 64], B=32, T=8), seed=0)
+    p.set_policy_gradient(gpu.PG_PATHWISE)
+    with pytest.raises(gpu.AnakinError):
+        p.step_decoupled()
+    with pytest.raises(gpu.AnakinError):        # chunks would cut the adjoint
+        p.set_updates_per_unroll(2)
+        p.rollout()
+        p.learn()
+    p.close()
+
+
 def test_determinism_and_resume(gpu):
     """Same seed twice gives the same bytes; a byte copy of the workspace plus the two host counters
     resumes bit-exactly (explicit, device-resident state; counter-based RNG)."""
