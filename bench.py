@@ -131,6 +131,9 @@ def main():
     ap.add_argument("--workload", default="catch_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--valu-gemm", action="store_true", help="learn-phase GEMMs on vector ALUs")
+    ap.add_argument("--pathwise", action="store_true",
+                    help="also time K steps with the policy gradient taken through the environment (pendulum "
+                         "workloads) and report them under \"pathwise\"")
     ap.add_argument("--decoupled", action="store_true",
                     help="also time K decoupled steps (actor on a second stream with lagging parameters, off-policy "
                          "update on the previous unroll; fp32 workloads) and report them under \"decoupled\"")
@@ -256,6 +259,35 @@ def main():
         "wall_s": round(wall, 3),
         "loss": metrics["loss"], "mean_episode_return": metrics["reward_sum"] / max(1, metrics["episodes"]),
     }
+    if args.pathwise:
+        if cfg["env"]["kind"] != "pendulum":
+            out["pathwise"] = None                        # differentiable dynamics only
+        else:
+            g.set_policy_gradient(binding.PG_PATHWISE)
+            for _ in range(max(args.warmup, 2)):
+                g.step()
+            torch.cuda.synchronize()
+            p0 = torch.cuda.Event(enable_timing=True); p1 = torch.cuda.Event(enable_timing=True)
+            p0.record(g.stream)
+            for _ in range(args.steps):
+                g.step()
+            p1.record(g.stream)
+            torch.cuda.synchronize()
+            ms_pw = p0.elapsed_time(p1) / args.steps
+            g.profile(True)
+            for _ in range(args.steps):
+                g.step()
+            pk = g.kernel_times()
+            g.profile(False)
+            g.set_policy_gradient(binding.PG_SCORE_FUNCTION)
+            c, tms = pk["pathwise_sweep"]
+            sweep_us = tms / c * 1e3
+            # the sweep's matrix-core work: dZ1 = dZ2 W2^T for every sample
+            hid = cfg["net"]["hidden"]
+            tf = 2.0 * hid[0] * hid[1] * cfg["B"] * cfg["T"] / 1e12 / (sweep_us * 1e-6)
+            out["pathwise"] = {"ms_per_step": round(ms_pw, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_pw * 1e-3),
+                               "pathwise_sweep": {"avg_us": round(sweep_us, 2), "bound": "mfma", "achieved": round(tf, 3),
+                                                  "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_FP32_TFLOPS, 4)}}
     if args.decoupled:
         if cfg["net"].get("dtype") == "bf16":
             out["decoupled"] = None                       # fp32 nets only

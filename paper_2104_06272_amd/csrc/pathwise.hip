@@ -57,6 +57,15 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
     const bool owner = tid < TM;
     const int b = b0 + tid;
     float lam_th = 0.0f, lam_thd = 0.0f, g_th = 0.0f, g_thd = 0.0f, sn = 0.0f, cs = 1.0f;
+    // this thread's pieces of h2 for phase (B): loaded one step ahead, while the phases before it run
+    constexpr int NQ = TM * RW / 4 / WG;
+    f4v_p h2v[NQ];
+    auto fetch_h2 = [&](int t) {
+        const float* h2 = a.act1 + ((size_t)t * B + b0) * RW;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) h2v[q] = *reinterpret_cast<const f4v_p*>(h2 + (size_t)(q * WG + tid) * 4);
+    };
+    fetch_h2(T - 1);
     __syncthreads();
 
     for (int t = T - 1; t >= 0; --t) {
@@ -87,18 +96,17 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
         }
         __syncthreads();
         // ---- (B) dZ2[m][j] = (h2 > 0) (Wh[j][mu] g_mu + Wh[j][ls] g_ls) ---------------
-        {
-            const float* h2 = a.act1 + ((size_t)t * B + b0) * RW;
-            for (int q = tid; q < TM * RW / 4; q += WG) {
-                const int m = q / (RW / 4), j = (q - m * (RW / 4)) * 4;
-                const f4v_p hv = *reinterpret_cast<const f4v_p*>(h2 + (size_t)m * RW + j);
-                const f4v_p w0 = *reinterpret_cast<const f4v_p*>(whs + j), w1 = *reinterpret_cast<const f4v_p*>(whs + RW + j);
-                const float g0 = gh[m * 2], g1 = gh[m * 2 + 1];
-                f4v_p d;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) d[e] = hv[e] > 0.0f ? fmaf(w1[e], g1, w0[e] * g0) : 0.0f;
-                *reinterpret_cast<f4v_p*>(bufA + m * LDX + j) = d;
-            }
+        for (int qq = 0; qq < NQ; ++qq) {
+            const int q = qq * WG + tid;                     // the tile's rows are contiguous: piece q is row q / (RW/4)
+            const int m = q / (RW / 4), j = (q - m * (RW / 4)) * 4;
+            const f4v_p hv = h2v[qq];
+            const f4v_p w0 = *reinterpret_cast<const f4v_p*>(whs + j), w1 = *reinterpret_cast<const f4v_p*>(whs + RW + j);
+            const float g0 = gh[m * 2], g1 = gh[m * 2 + 1];
+            f4v_p d;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) d[e] = hv[e] > 0.0f ? fmaf(w1[e], g1, w0[e] * g0) : 0.0f;
+            *reinterpret_cast<f4v_p*>(bufA + m * LDX + j) = d;
         }
         __syncthreads();
         // ---- (C) dZ1 = (h1 > 0) (dZ2 W2^T) -------------------------------------------
@@ -106,6 +114,13 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
             f4v_p acc[NT];
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) acc[tt] = f4v_p{0.0f, 0.0f, 0.0f, 0.0f};
+            // the relu mask of the result: requested before the products so the loads overlap them
+            const float* h1 = a.act0 + ((size_t)t * B + b0) * RW;
+            float h1v[4][NT];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int tt = 0; tt < NT; ++tt) h1v[r][tt] = h1[(size_t)(4 * kq + r) * RW + col0 + tt];
             const float* xp = bufA + (lane & 15) * LDX + kq;
             constexpr int PF = 4;
             float ap[PF];
@@ -119,15 +134,15 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
 #pragma unroll
                 for (int tt = 0; tt < NT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wreg[s][tt], acc[tt], 0, 0, 0);
             }
-            const float* h1 = a.act0 + ((size_t)t * B + b0) * RW;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = 4 * kq + r;
 #pragma unroll
                 for (int tt = 0; tt < NT; ++tt)
-                    bufB[row * LDX + col0 + tt] = h1[(size_t)row * RW + col0 + tt] > 0.0f ? acc[tt][r] : 0.0f;
+                    bufB[row * LDX + col0 + tt] = h1v[r][tt] > 0.0f ? acc[tt][r] : 0.0f;
             }
         }
+        if (t > 0) fetch_h2(t - 1);
         __syncthreads();
         // ---- (D) g_obs[m][c] = sum_i dZ1[m][i] W1[c][i] ----------------------------------
         {
