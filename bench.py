@@ -136,7 +136,7 @@ def main():
                          "workloads) and report them under \"pathwise\"")
     ap.add_argument("--decoupled", action="store_true",
                     help="also time K decoupled steps (actor on a second stream with lagging parameters, off-policy "
-                         "update on the previous unroll; fp32 workloads) and report them under \"decoupled\"")
+                         "update on the previous unroll) and report them under \"decoupled\"")
     ap.add_argument("--peak-probe", action="store_true",
                     help="instead of the benchmark, measure what this GPU delivers for the rooflines: register-only "
                          "fp32 and bf16 MFMA loops and a 2 x 1 GiB streaming copy; prints one JSON line")
@@ -289,9 +289,7 @@ def main():
                                "pathwise_sweep": {"avg_us": round(sweep_us, 2), "bound": "mfma", "achieved": round(tf, 3),
                                                   "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_FP32_TFLOPS, 4)}}
     if args.decoupled:
-        if cfg["net"].get("dtype") == "bf16":
-            out["decoupled"] = None                       # fp32 nets only
-        else:
+        if True:
             for _ in range(max(args.warmup, 2)):
                 g.step_decoupled()
             torch.cuda.synchronize()

@@ -141,7 +141,7 @@ int32_t anakin_step(anakin_t* h);
  * handle's stream waits for the actor before any later work, so the usual stream semantics hold;
  * the result does not depend on how the two streams interleave.  anakin_get_trajectory then shows
  * the unroll just collected (its adv / ret / act fields belong to the update that ran beside it).
- * fp32 nets, one update per unroll: ANAKIN_E_BAD_CONFIG otherwise.  After a decoupled step
+ * One update per unroll, score-function gradient: ANAKIN_E_BAD_CONFIG otherwise.  After a decoupled step
  * anakin_learn returns ANAKIN_E_STATE (the stored unroll has no activations); anakin_step and
  * anakin_rollout start a fresh on-policy unroll.  Asynchronous. */
 int32_t anakin_step_decoupled(anakin_t* h);

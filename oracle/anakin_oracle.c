@@ -1054,17 +1054,18 @@ int orc_learn_vtrace(orc_t* h, double rho_bar, double c_bar)
  * start of the step, while the learner applies one off-policy update to the trajectory collected
  * by the previous step.  Neither reads what the other writes, so the order below is one of two
  * equivalent ones.  The first step only collects.  Clipping thresholds rho_bar = c_bar = 1. */
-void orc_step_decoupled(orc_t* h)
+void orc_step_decoupled_forced(orc_t* h, const float* forced_head)
 {
     float* behaviour = (float*)malloc(h->P * sizeof(float));
     memcpy(behaviour, h->theta, h->P * sizeof(float));
     if (h->have_traj) orc_learn_vtrace(h, 1.0, 1.0);
     float* learner = h->theta;
     h->theta = behaviour;
-    orc_rollout(h, NULL);
+    orc_rollout(h, forced_head);                            /* forced_head: as in orc_rollout */
     h->theta = learner;
     free(behaviour);
 }
+void orc_step_decoupled(orc_t* h) { orc_step_decoupled_forced(h, NULL); }
 
 /* ------------------------------------------------------------------------- */
 /* Pathwise policy gradient (paper section 3.1: with the environment part of    */

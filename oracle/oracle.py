@@ -93,6 +93,7 @@ def lib():
         L.orc_vtrace_targets.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_vtrace_targets.restype = None
         L.orc_learn_vtrace.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_learn_vtrace.restype = C.c_int
         L.orc_step_decoupled.argtypes = [C.c_void_p]; L.orc_step_decoupled.restype = None
+        L.orc_step_decoupled_forced.argtypes = [C.c_void_p, f32p]; L.orc_step_decoupled_forced.restype = None
         L.orc_pathwise_grad.argtypes = [C.c_void_p, f64p, f64p]; L.orc_pathwise_grad.restype = None
         L.orc_learn_pathwise.argtypes = [C.c_void_p]; L.orc_learn_pathwise.restype = C.c_int
         _lib = L
@@ -309,6 +310,12 @@ class Oracle:
         if rc != 0:
             raise RuntimeError("learn_pathwise: no stored trajectory" if rc == -1 else "learn_pathwise: pendulum with the tanh-Gaussian policy only")
 
-    def step_decoupled(self):
-        """Actor unroll with the parameters as they are now, learner update on the previous unroll."""
-        self.L.orc_step_decoupled(self.h)
+    def step_decoupled(self, forced_head=None):
+        """Actor unroll with the parameters as they are now, learner update on the previous unroll.
+        forced_head: as in rollout (the actor samples from these head outputs)."""
+        if forced_head is None:
+            self.L.orc_step_decoupled(self.h)
+        else:
+            fh = np.ascontiguousarray(forced_head, np.float32)
+            assert fh.shape == (self.T + 1, self.B, self.NH)
+            self.L.orc_step_decoupled_forced(self.h, _ptr(fh, C.c_float))

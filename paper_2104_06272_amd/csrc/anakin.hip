@@ -123,9 +123,11 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
     L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
     L.loss_part = take((size_t)(loss_blocks + T) * 8 * 4);     // + T: with N updates per unroll every chunk rounds its block count up
-    // decoupled steps (fp32 nets): behaviour parameters, second record set, the learner's forward results
-    const bool dec = !ns.bf16;
+    // decoupled steps: behaviour parameters, second record set, the learner's forward results
+    const bool dec = true;
     L.theta_b = take(dec ? P * 4 : 0);
+    L.w_bf16_b = take(ns.bf16 ? P * 2 : 0); L.wt_bf16_b = take(ns.bf16 ? P * 2 : 0);
+    L.prefix_b = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
     L.alt_tr_s0 = take(dec ? t1n * 4 : 0); L.alt_tr_f0 = take(dec ? t1n * 4 : 0); L.alt_tr_f1 = take(dec ? t1n * 4 : 0);
     L.alt_tr_act = take(dec ? tn : 0); L.alt_tr_eps = take(dec ? tn * 4 : 0); L.alt_tr_actf = take(dec ? tn * 4 : 0);
     L.alt_tr_rew = take(dec ? tn * 4 : 0); L.alt_tr_done = take(dec ? tn : 0);
@@ -599,7 +601,6 @@ static void swap_record_sets(Layout& L)
 extern "C" int32_t anakin_step_decoupled(anakin_t* h)
 {
     NEED(h);
-    if (h->net.bf16) { h->err = "decoupled steps run fp32 nets only"; return ANAKIN_E_BAD_CONFIG; }
     if (h->n_updates != 1) { h->err = "decoupled steps apply one update per unroll"; return ANAKIN_E_BAD_CONFIG; }
     if (h->pathwise) { h->err = "decoupled steps use the score-function gradient"; return ANAKIN_E_BAD_CONFIG; }
     if (h->prof_pending.size() > 8192) HIPCHK(h, prof_resolve(h));
@@ -612,12 +613,17 @@ extern "C" int32_t anakin_step_decoupled(anakin_t* h)
     hipStream_t learner = h->stream;
     // the actor's parameters: the learner's as they are now, before this step's update touches them
     HIPCHK(h, hipMemcpyAsync(h->ws + h->lay.theta_b, h->ws + h->lay.theta, (size_t)n.P * 4, hipMemcpyDeviceToDevice, learner));
+    const bool mc = bf16_mfma(h);                                 // bf16 net on the matrix-core path: packed activations
+    if (mc) {
+        HIPCHK(h, hipMemcpyAsync(h->ws + h->lay.w_bf16_b, h->ws + h->lay.w_bf16, (size_t)n.P * 2, hipMemcpyDeviceToDevice, learner));
+        HIPCHK(h, hipMemcpyAsync(h->ws + h->lay.wt_bf16_b, h->ws + h->lay.wt_bf16, (size_t)n.P * 2, hipMemcpyDeviceToDevice, learner));
+    }
     HIPCHK(h, hipEventRecord(h->ev_fork, learner));
     HIPCHK(h, hipStreamWaitEvent(h->actor_stream, h->ev_fork, 0));
     // actor: T steps into the free record set, on its own stream
     swap_record_sets(h->lay);
     h->stream = h->actor_stream;
-    hipError_t e = launch_rollout_behaviour(h);
+    hipError_t e = mc ? launch_rollout_bf16_behaviour(h) : launch_rollout_behaviour(h);
     h->stream = learner;
     swap_record_sets(h->lay);
     HIPCHK(h, e);
@@ -625,10 +631,10 @@ extern "C" int32_t anakin_step_decoupled(anakin_t* h)
     // learner: one off-policy update on the unroll of the previous step
     int32_t rc = ANAKIN_OK;
     if (h->have_traj) {
-        HIPCHK(h, launch_replay_forward(h));
+        HIPCHK(h, mc ? launch_replay_bf16(h) : launch_replay_forward(h));
         HIPCHK(h, launch_vtrace(h));
         const int no_acts = h->traj_no_acts;
-        h->traj_packed = 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0;
+        h->traj_packed = mc ? 1 : 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0;
         const Layout keep = h->lay;
         h->lay.tr_head = keep.head_new; h->lay.tr_eps = keep.eps_new;   // the loss kernel reads the learner's heads
         rc = run_update(h);
@@ -639,7 +645,7 @@ extern "C" int32_t anakin_step_decoupled(anakin_t* h)
     swap_record_sets(h->lay);
     HIPCHK(h, hipStreamWaitEvent(learner, h->ev_join, 0));
     if (rc != ANAKIN_OK) return rc;
-    h->traj_packed = 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0; h->traj_decoupled = 1;
+    h->traj_packed = mc ? 1 : 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0; h->traj_decoupled = 1;
     h->gstep += (uint64_t)h->T;
     h->have_traj = 1;
     return ANAKIN_OK;

@@ -112,7 +112,7 @@ struct Layout {
     // decoupled acting and learning: the behaviour copy of the parameters the actor runs on, the second set of
     // trajectory records (the actor fills one set while the learner reads the other), and the learner's own
     // forward results on the stored unroll
-    size_t theta_b;
+    size_t theta_b, w_bf16_b, wt_bf16_b, prefix_b;      // bf16 nets: the actor's own rounded copies and first-layer prefix
     size_t alt_tr_s0, alt_tr_f0, alt_tr_f1, alt_tr_act, alt_tr_eps, alt_tr_actf, alt_tr_rew, alt_tr_done, alt_tr_val, alt_tr_head;
     size_t head_new, val_new, eps_new;
     size_t path;                 // pathwise policy gradient: dL_path / d(mu, log_sigma) per sample, [T*B][2]
@@ -192,6 +192,8 @@ hipError_t launch_learn_one_layer(anakin* h);
 inline bool one_layer_fused(const anakin* h) { return h->net.L == 1 && h->env.kind != ENV_MAZE && !h->net.bf16 && !(h->mode & ANAKIN_MODE_VALU_GEMM) && h->net.dims[1] <= 128 && (size_t)128 * h->net.dims[0] * 4 + (size_t)h->net.dims[0] * h->net.dims[1] * 4 <= 64 * 1024; }
 hipError_t launch_partial_reduce(const float* src, float* dst, int count, int fan, int splits, hipStream_t s);
 hipError_t launch_rollout_bf16(anakin* h);
+hipError_t launch_rollout_bf16_behaviour(anakin* h);
+hipError_t launch_replay_bf16(anakin* h);
 hipError_t launch_backward_bf16(anakin* h);
 hipError_t launch_refresh_bf16(anakin* h);
 bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B);

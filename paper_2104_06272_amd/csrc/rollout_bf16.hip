@@ -65,6 +65,7 @@ struct RolloutBf16Args {
     const uint16_t* wt;                  // bf16 copy in matrix-core operand tiles (heads: [NH][HL])
     float* prefix;                       // [B][H1] first-layer prefix (bias + wall rows + goal row), maze only
     int B, T, ldx;                       // ldx: LDS row stride in bf16 elements
+    int keep_acts;                       // store the packed hidden activations for the update
     uint64_t seed, gstep;
 };
 
@@ -247,7 +248,10 @@ __device__ __forceinline__ void run_bf16_layer(const uint16_t* X, uint16_t* Y, i
 
 // H1: width of the first hidden layer (128, 256 or 512).  Thread (pair of columns cp, env slice eq)
 // owns columns 2*cp, 2*cp+1 of the first layer for EPT = H1/16 consecutive environments.
-template <int ENV, int H1, bool UNI>
+// REPLAY: the learner's pass over a stored unroll (decoupled acting and learning): states from the stored
+// snapshots, head outputs and values to tp.tr_head / tp.tr_val (pointed at the learner's buffers), nothing
+// sampled or stepped.
+template <int ENV, int H1, bool UNI, bool REPLAY>
 __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args a)
 {
     extern __shared__ uint4 smem4[];
@@ -277,8 +281,10 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
 #pragma unroll
     for (int j = 0; j < 8; ++j) hb[j] = j < NH ? a.theta[a.net.bh_off + j] : 0.0f;
     if (owner) {
-        st.s0 = tp.s0[b];
-        if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        if (!REPLAY) {
+            st.s0 = tp.s0[b];
+            if (ENV == ENV_PENDULUM) { st.f0 = tp.f0[b]; st.f1 = tp.f1[b]; }
+        }
         if (ENV == ENV_MAZE) for (int w = 0; w < 8; ++w) obs[tid * BOBS + w] = tp.walls[(size_t)w * B + b];
     }
     for (int i = tid; i < 8 * ldh; i += BWG) {
@@ -372,13 +378,18 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
         const int b = b0 + tid;
         const size_t tb = (size_t)t * B + b;
         if (owner) {
-            tp.tr_s0[tb] = st.s0;
+            if (REPLAY) {
+                st.s0 = tp.tr_s0[tb];
+                if (ENV == ENV_PENDULUM) { st.f0 = tp.tr_f0[tb]; st.f1 = tp.tr_f1[tb]; }
+            } else {
+                tp.tr_s0[tb] = st.s0;
+                if (ENV == ENV_PENDULUM) { tp.tr_f0[tb] = st.f0; tp.tr_f1[tb] = st.f1; }
+            }
             if (ENV == ENV_CATCH) {
                 int bc, pc;
                 catch_obs_cells(a.env, st.s0, bc, pc);
                 obs[tid * BOBS + 0] = (uint32_t)bc; obs[tid * BOBS + 1] = (uint32_t)pc;
             } else if (ENV == ENV_PENDULUM) {
-                tp.tr_f0[tb] = st.f0; tp.tr_f1[tb] = st.f1;
                 float sn, cs;
                 det_sincos(st.f0, sn, cs);
                 obs[tid * BOBS + 0] = bits_from_f(bf16_to_f(bf16_bits(cs)));
@@ -390,10 +401,10 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
         }
         __syncthreads();
         PH(0);
-        const bool keep = t < T;
+        const bool keep = t < T && a.keep_acts;
         const size_t g8 = ((size_t)t * B + b0) >> 3;             // first sample group of this tile
         // the last wavefront draws this step's random numbers while it waits for its weight rows
-        if (wave == 7 && keep) {
+        if (!REPLAY && wave == 7 && t < T) {
             const u32x4 w = philox(a.seed, (uint32_t)(b0 + lane), a.gstep + (uint64_t)t, DOM_ACTION);
             rng[lane * 2] = w.x;
             rng[lane * 2 + 1] = w.y;
@@ -528,7 +539,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
 #pragma unroll
             for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
             tp.tr_val[tb] = val;
-            if (t < T) {
+            if (!REPLAY && t < T) {
                 const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 2);
                 float r; int done;
                 if (ENV == ENV_PENDULUM) {
@@ -566,7 +577,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                ph[0] / (T + 1), ph[1] / (T + 1), ph[3] / (T + 1), ph[4] / (T + 1), ph[5] / (T + 1));
 #endif
 #undef PH
-    if (owner) {
+    if (!REPLAY && owner) {
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }
     }
@@ -586,14 +597,26 @@ bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B)
 
 void fill_rollout_args(anakin* h, RolloutArgs& a);
 
-hipError_t launch_rollout_bf16(anakin* h)
+// what: 0 the acting unroll, 1 the actor of a decoupled step (behaviour copies of the parameters, its own prefix
+// buffer, no activations kept), 2 the learner's replay of the stored unroll with the current parameters
+template <bool REPLAY>
+static hipError_t launch_bf16_forward(anakin* h, int what)
 {
     RolloutArgs base;
     fill_rollout_args(h, base);
+    const Layout& L = h->lay;
     RolloutBf16Args a;
     a.env = base.env; a.net = base.net; a.tp = base.tp; a.theta = base.theta;
-    a.w = at<const uint16_t>(h, h->lay.w_bf16); a.wt = at<const uint16_t>(h, h->lay.wt_bf16);
-    a.prefix = at<float>(h, h->lay.prefix);
+    a.w = at<const uint16_t>(h, L.w_bf16); a.wt = at<const uint16_t>(h, L.wt_bf16);
+    a.prefix = at<float>(h, L.prefix);
+    a.keep_acts = 1;
+    if (what == 1) {
+        a.theta = at<const float>(h, L.theta_b); a.w = at<const uint16_t>(h, L.w_bf16_b); a.wt = at<const uint16_t>(h, L.wt_bf16_b);
+        a.prefix = at<float>(h, L.prefix_b);
+        a.keep_acts = 0;
+    } else if (what == 2) {
+        a.tp.tr_head = at<float>(h, L.head_new); a.tp.tr_val = at<float>(h, L.val_new);
+    }
     a.B = h->B; a.T = h->T; a.seed = h->seed; a.gstep = h->gstep;
     int hmax = 0;
     for (int l = 1; l <= h->net.L; ++l) hmax = h->net.dims[l] > hmax ? h->net.dims[l] : hmax;
@@ -603,13 +626,13 @@ hipError_t launch_rollout_bf16(anakin* h)
     auto launch = [&](auto kern) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        ProfScope prof(h, "rollout");
+        ProfScope prof(h, REPLAY ? "replay_forward" : "rollout");
         hipLaunchKernelGGL(kern, dim3(h->B / BTM), dim3(BWG), lds, h->stream, a);
         return hipGetLastError();
     };
     bool uni = true;                                             // every hidden layer H1 wide: the weight stream runs across layers
     for (int l = 2; l <= h->net.L; ++l) uni = uni && h->net.dims[l] == H1;
-#define ANK_BF16_W(ENVK, W) (uni ? launch(rollout_bf16_kernel<ENVK, W, true>) : launch(rollout_bf16_kernel<ENVK, W, false>))
+#define ANK_BF16_W(ENVK, W) (uni ? launch(rollout_bf16_kernel<ENVK, W, true, REPLAY>) : launch(rollout_bf16_kernel<ENVK, W, false, REPLAY>))
 #define ANK_BF16_CASE(ENVK) (H1 == 128 ? ANK_BF16_W(ENVK, 128) : H1 == 256 ? ANK_BF16_W(ENVK, 256) : ANK_BF16_W(ENVK, 512))
     switch (h->env.kind) {
         case ENV_CATCH:    return ANK_BF16_CASE(ENV_CATCH);
@@ -619,5 +642,9 @@ hipError_t launch_rollout_bf16(anakin* h)
 #undef ANK_BF16_CASE
 #undef ANK_BF16_W
 }
+
+hipError_t launch_rollout_bf16(anakin* h) { return launch_bf16_forward<false>(h, 0); }
+hipError_t launch_rollout_bf16_behaviour(anakin* h) { return launch_bf16_forward<false>(h, 1); }
+hipError_t launch_replay_bf16(anakin* h) { return launch_bf16_forward<true>(h, 2); }
 
 }  // namespace ank

@@ -69,15 +69,16 @@ def assert_final_state_equal(g, o, kind, sel=None):
     assert g.global_step == o.global_step
 
 
-def assert_learn_close(g, o, tol, tr_after=None, learned_on=None):
+def assert_learn_close(g, o, tol, tr_after=None, learned_on=None, target_tol=1e-5):
     """after both sides learned on the same unroll: returns, loss, gradient, parameters, moments.
     learned_on: (rewards, dones) of the unroll the update used when that is not the one now stored
-    (decoupled steps learn on the previous unroll)."""
+    (decoupled steps learn on the previous unroll).  target_tol: tolerance on returns and advantages (they come
+    from stored binary32 values on both sides, except where the learner's own bf16 forward pass feeds them)."""
     tr = tr_after if tr_after is not None else g.trajectory()
     rew, done = learned_on if learned_on is not None else (o.tr_reward, o.tr_done)
     scale = max(1.0, float(np.abs(o.ret).max()))
-    assert np.abs(tr["ret"] - o.ret).max() <= 1e-5 * scale, "returns differ"
-    assert np.abs(tr["adv"] - o.adv).max() <= 1e-5 * scale, "advantages differ"
+    assert np.abs(tr["ret"] - o.ret).max() <= target_tol * scale, "returns differ"
+    assert np.abs(tr["adv"] - o.adv).max() <= target_tol * scale, "advantages differ"
     m = g.metrics()
     for k, i in (("loss", 0), ("policy_loss", 1), ("value_loss", 2), ("entropy_loss", 3)):
         assert abs(m[k] - o.loss[i]) <= tol * max(abs(o.loss[i]), 1e-3 * abs(o.loss).max()) + 1e-7, (k, m[k], o.loss[i])

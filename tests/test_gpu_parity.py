@@ -386,10 +386,50 @@ def test_decoupled_lockstep(gpu, orc, case):
     g.close()
 
 
-def test_decoupled_rejects_bf16(gpu):
-    g = gpu.Anakin(variant("maze_16384", hidden=[128, 128], B=64, T=8), seed=0)
-    with pytest.raises(gpu.AnakinError):
+DECOUPLED_BF16_CASES = {
+    "maze_bf16_16x16_256": (_fast_lr(variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20), 3e-3), 4, 3),
+    "maze_bf16_16x16_512": (_fast_lr(variant("maze_16384", B=64, T=8, max_steps=20), 3e-3), 5, 3),
+    "pendulum_bf16_128": (_fast_lr(variant("pendulum_8192", hidden=[128, 128], B=64, T=10, dtype="bf16", max_steps=7), 3e-3), 2, 3),
+    "catch_bf16_128": (_fast_lr(variant("catch_4096", hidden=[128, 128], B=64, T=12, dtype="bf16"), 3e-3), 0, 3),
+}
+
+
+@pytest.mark.parametrize("case", list(DECOUPLED_BF16_CASES))
+def test_decoupled_bf16_forced_lockstep(gpu, orc, case):
+    """Decoupled steps of a bf16 net on the matrix-core path, logit-forced: the oracle's actor samples from the GPU
+    actor's head outputs (which must be its own forward within the bf16 tolerance) and must then reproduce the
+    unroll bit for bit; the learner's off-policy update on the previous unroll agrees within 2e-2."""
+    cfg, seed, steps = DECOUPLED_BF16_CASES[case]
+    kind = cfg["env"]["kind"]
+    say(f"[decoupled bf16] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+    g = gpu.Anakin(cfg, seed=seed)
+    o = orc.Oracle(cfg, seed=seed)
+    for k in range(steps):
+        PT.sync_oracle_from_gpu(g, o)
+        behaviour = o.theta.copy()
+        learned_on = (o.tr_reward.copy(), o.tr_done.copy())
         g.step_decoupled()
+        tr = g.trajectory()
+        o.step_decoupled(forced_head=tr["head"])
+        PT.assert_rollout_equal(g, o, kind, head_tol=TOL_BF16)
+        PT.assert_final_state_equal(g, o, kind)
+        # the actor's head outputs are the forward pass of the parameters from before this step's update
+        learner = o.theta.copy()
+        o.theta[:] = behaviour
+        scale = max(1e-3, float(np.abs(tr["head"]).max()))
+        for (t, b) in [(0, 0), (g.T // 2, g.B // 2), (g.T, g.B - 1)]:
+            save = (o.state_i[b].copy(), o.state_f[b].copy())
+            o.state_i[b] = o.tr_state_i[t, b]; o.state_f[b] = o.tr_state_f[t, b]
+            head = o.forward(o.observe(b))
+            o.state_i[b], o.state_f[b] = save
+            assert np.abs(head - tr["head"][t, b]).max() <= TOL_BF16 * scale, "actor head outputs differ"
+        o.theta[:] = learner
+        if k == 0:
+            assert g.get_opt_state()[2] == 0
+            continue
+        # the V-trace targets come from the learner's own forward pass: bf16 tolerance for them too
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_BF16, tr_after=tr, learned_on=learned_on, target_tol=TOL_BF16)
+        say(f"  step {k}: grad rel {e_g:.2e}, param rel {e_p:.2e}, min rho {o.rho.min():.4f}")
     g.close()
 
 
