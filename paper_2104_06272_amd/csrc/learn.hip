@@ -701,11 +701,13 @@ struct OneLayerArgs {
 // OLW threads per workgroup: small workgroups keep the LDS accumulators small, so more of them fit a CU
 constexpr int OLW = 128;
 // NH (number of head outputs) is a template parameter: the per-sample inner loops are the whole cost here
-template <int ENV, int NH>
+// FULL: the chunk is a whole number of RB x groups sample blocks, so no load needs a bounds check.
+// HC: the hidden width when it is known at compile time (index arithmetic by shifts, constant load offsets), else 0.
+template <int ENV, int NH, bool FULL, int HC>
 __global__ __launch_bounds__(OLW) void learn_one_layer(const OneLayerArgs a)
 {
     extern __shared__ float lds[];
-    const int H = a.H, D = a.D;
+    const int H = HC ? HC : a.H, D = a.D;
     constexpr int NHP = NH <= 4 ? 4 : 8;
     const int cw = H < OLW ? H : OLW, groups = OLW / cw;
     float* w1s = lds;                                         // [D][H]
@@ -728,18 +730,23 @@ __global__ __launch_bounds__(OLW) void learn_one_layer(const OneLayerArgs a)
         float4 d0[RB], d1[RB];
         uint32_t sw[RB];
         float f0[RB], f1[RB];
+        // one base address per array and trip; the samples of a trip sit at constant distances from it
+        const float* dh = a.dhead + (size_t)mb * NHP;
+        const uint32_t* sp = a.obs.s0 + mb;
+        const float* fp0 = a.obs.f0 + mb;
+        const float* fp1 = a.obs.f1 + mb;
 #pragma unroll
         for (int u = 0; u < RB; ++u) {
-            const int m = mb + u * groups;
-            const bool ok = m < m_end;
-            d0[u] = ok ? *reinterpret_cast<const float4*>(a.dhead + (size_t)m * NHP) : make_float4(0, 0, 0, 0);
-            d1[u] = (ok && NHP == 8) ? *reinterpret_cast<const float4*>(a.dhead + (size_t)m * NHP + 4) : make_float4(0, 0, 0, 0);
-            if (ENV == ENV_CATCH) sw[u] = ok ? a.obs.s0[m] : 0u;
-            else { f0[u] = ok ? a.obs.f0[m] : 0.0f; f1[u] = ok ? a.obs.f1[m] : 0.0f; }
+            const int du = u * groups;
+            const bool ok = FULL || mb + du < m_end;
+            d0[u] = ok ? *reinterpret_cast<const float4*>(dh + du * NHP) : make_float4(0, 0, 0, 0);
+            d1[u] = (ok && NHP == 8) ? *reinterpret_cast<const float4*>(dh + du * NHP + 4) : make_float4(0, 0, 0, 0);
+            if (ENV == ENV_CATCH) sw[u] = ok ? sp[du] : 0u;
+            else { f0[u] = ok ? fp0[du] : 0.0f; f1[u] = ok ? fp1[du] : 0.0f; }
         }
 #pragma unroll
         for (int u = 0; u < RB; ++u) {
-            if (mb + u * groups >= m_end) break;
+            if (!FULL && mb + u * groups >= m_end) break;
             const float d[8] = {d0[u].x, d0[u].y, d0[u].z, d0[u].w, d1[u].x, d1[u].y, d1[u].z, d1[u].w};
             float hv, x0 = 0.0f, x1 = 0.0f, x2 = 0.0f;
             int bc = 0, pc = 0;
@@ -819,7 +826,13 @@ hipError_t launch_learn_one_layer(anakin* h)
         hipLaunchKernelGGL(kern, grid, dim3(OLW), lds, h->stream, a);
         return hipGetLastError();
     };
-    return h->env.kind == ENV_CATCH ? go(learn_one_layer<ENV_CATCH, 4>) : go(learn_one_layer<ENV_PENDULUM, 3>);
+    const int cw = a.H < OLW ? a.H : OLW;
+    const bool full = a.rows % (8 * (OLW / cw)) == 0;             // RB x groups samples per loop trip
+    if (h->env.kind == ENV_CATCH) {
+        if (full && a.H == 32) return go(learn_one_layer<ENV_CATCH, 4, true, 32>);
+        return full ? go(learn_one_layer<ENV_CATCH, 4, true, 0>) : go(learn_one_layer<ENV_CATCH, 4, false, 0>);
+    }
+    return full ? go(learn_one_layer<ENV_PENDULUM, 3, true, 0>) : go(learn_one_layer<ENV_PENDULUM, 3, false, 0>);
 }
 
 // ---------------------------------------------------------------------------
