@@ -14,8 +14,20 @@ struct ObsSrc {
 };
 
 // dX[m][i] = (x[m][i] > 0) * sum_j dY[m][j] W[i][j];  W is [K][N] row-major (K = inputs, N = outputs)
+// heads folded into the top hidden layer's products: dY is not read but formed on the way in,
+//   dY[m][j] = (hl[m][j] > 0) * sum_a wh[j][a] dhead[m][a]
+// from the layer's own forward activations hl, the per-sample head gradient and the head matrix
+struct HeadFuse {
+    const float* hl;      // [M][N] activations of the top hidden layer (null: dY is read from memory)
+    const float* dhead;   // [M][NHP]
+    const float* wh;      // [N][NH]
+    int NH, NHP;
+    float* head_partial;  // dW product only: [splits][N*NH + NH] partial sums of the head matrix and bias gradients
+};
+
 struct GemmNtArgs {
     int M, K, N, bf16;
+    HeadFuse hf;
     const float* dy;      // [M][N]
     const float* w;       // [K][N]
     const float* x;       // [M][K] forward activations (relu mask)
@@ -25,6 +37,7 @@ struct GemmNtArgs {
 // partial[s][i][j] = sum over rows of chunk s of x[m][i] dY[m][j]; partial[s][K*N + j] = column sums of dY
 struct GemmTnArgs {
     int M, K, N, ldy, bf16, splits, rows, tiles_i, use_obs;   // ldy: row stride of dy (>= N)
+    HeadFuse hf;
     const float* x;       // [M][K], unused when use_obs
     const float* dy;      // [M][N]
     float* partial;       // [splits][K*N + N]

@@ -168,8 +168,24 @@ hipError_t launch_backward(anakin* h)
     const NetShape& n = h->net;
     const int M = h->B * h->T;
     hipError_t e;
-    e = launch_head_backward(h);
-    if (e != hipSuccess) return e;
+    // Top hidden layer 256 -> 256 on the matrix cores: its dW and dX products form dZ_L on the way in from the
+    // layer's forward activations and the head gradient, and the dW product also sums the head matrix's gradient,
+    // so dZ_L is neither written nor read and the head pass is no kernel of its own.
+    HeadFuse hf{};
+    hf.hl = nullptr;
+    {
+        const int lt = n.L - 1;
+        const bool mfma = !(h->mode & ANAKIN_MODE_VALU_GEMM) && !n.bf16;
+        if (mfma && heads_fused_shape(n, M) && h->head_fan == 1 && h->splits[n.L] == h->splits[lt] && (M / h->splits[lt]) % 32 == 0) {
+            hf.hl = at<const float>(h, L.act[lt]); hf.dhead = at<const float>(h, L.dhead);
+            hf.wh = at<const float>(h, L.w_src) + n.wh_off; hf.NH = n.NH; hf.NHP = n.NHP;
+            hf.head_partial = at<float>(h, L.part[n.L]);
+        }
+    }
+    if (!hf.hl) {
+        e = launch_head_backward(h);
+        if (e != hipSuccess) return e;
+    }
     for (int l = n.L - 1; l >= 0; --l) {
         // one-hot boards (Catch) and the 3-feature pendulum need no GEMM for the first layer
         if (l == 0 && h->env.kind != ENV_MAZE && !(h->mode & ANAKIN_MODE_VALU_GEMM) && (size_t)WG * n.dims[0] * 4 <= 96 * 1024) {
@@ -188,6 +204,8 @@ hipError_t launch_backward(anakin* h)
         t.obs.s0 = at<const uint32_t>(h, L.tr_s0); t.obs.f0 = at<const float>(h, L.tr_f0);
         t.obs.f1 = at<const float>(h, L.tr_f1); t.obs.walls = at<const uint32_t>(h, L.walls);
         t.bf16 = n.bf16; t.tiles_i = 0;
+        t.hf = HeadFuse{}; t.hf.hl = nullptr;
+        if (l == n.L - 1 && hf.hl) t.hf = hf;
         const bool mfma = !(h->mode & ANAKIN_MODE_VALU_GEMM) && !n.bf16;
         {
             ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
@@ -202,6 +220,8 @@ hipError_t launch_backward(anakin* h)
             g.x = at<const float>(h, L.act[l - 1]);
             g.dx = at<float>(h, L.dz[l - 1]);
             g.bf16 = n.bf16;
+            g.hf = HeadFuse{}; g.hf.hl = nullptr;
+            if (l == n.L - 1 && hf.hl) g.hf = hf;
             {
                 ProfScope prof(h, "gemm_nt_mask");
                 e = !mfma ? launch_gemm_nt_valu(g, h->stream) : gemm_nt_res_ok(g) ? launch_gemm_nt_res(g, h->stream) : launch_gemm_nt_mfma(g, h->stream);

@@ -37,6 +37,28 @@ __device__ __forceinline__ f16v_r mfma_r(float a, float b, f16v_r c) { return __
 // The order of the reduction is free: step 4p + e of lane half kg takes j = 8p + 4kg + e, so both
 // the resident weights and the LDS operand are fetched 16 bytes at a time.
 // ---------------------------------------------------------------------------
+// head weights of this thread's four loader columns, and dY formed from the forward activations
+struct HeadCols { float w[4][4]; };
+__device__ __forceinline__ void load_head_cols(const HeadFuse& hf, int lc, HeadCols& hc)
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) hc.w[e][k] = k < hf.NH ? hf.wh[(size_t)(lc + e) * hf.NH + k] : 0.0f;
+}
+__device__ __forceinline__ f4v_r head_dy(const HeadCols& hc, f4v_r hv, f4v_r d)
+{
+    f4v_r o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float s = hc.w[e][0] * d[0];
+        s = fmaf(hc.w[e][1], d[1], s); s = fmaf(hc.w[e][2], d[2], s); s = fmaf(hc.w[e][3], d[3], s);
+        o[e] = hv[e] > 0.0f ? s : 0.0f;
+    }
+    return o;
+}
+
+template <bool HEADS>
 __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const int rows_per_block)
 {
     extern __shared__ float4 smem_r[];
@@ -57,17 +79,23 @@ __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const 
     // loader: 32 rows x 64 pieces of 16 B, four per thread: row 8q + tid/64, piece tid%64
     const int lrow = __builtin_amdgcn_readfirstlane(tid >> 6), lc = (tid & 63) << 2;
     const int m_clamp = m_end - 1;
-    f4v_r st[4];
+    f4v_r st[4], dh[HEADS ? 4 : 1];
+    HeadCols hc;
+    if (HEADS) load_head_cols(a.hf, lc, hc);
+    const float* src = HEADS ? a.hf.hl : a.dy;
     auto fetch = [&](int m0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int m = m0 + 8 * q + lrow;                                                          // uniform in a wavefront
-            st[q] = *reinterpret_cast<const f4v_r*>(a.dy + (size_t)(m < m_end ? m : m_clamp) * N + lc);   // rows past the end are never used
+            const int mc = m < m_end ? m : m_clamp;                                                   // rows past the end are never used
+            st[q] = *reinterpret_cast<const f4v_r*>(src + (size_t)mc * N + lc);
+            if (HEADS) dh[HEADS ? q : 0] = *reinterpret_cast<const f4v_r*>(a.hf.dhead + (size_t)mc * a.hf.NHP);
         }
     };
     auto store = [&](float* buf) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<f4v_r*>(buf + (8 * q + lrow) * NTR_LD + lc) = st[q];
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<f4v_r*>(buf + (8 * q + lrow) * NTR_LD + lc) = HEADS ? head_dy(hc, st[q], dh[HEADS ? q : 0]) : st[q];
     };
     fetch(m_begin);
     store(As0);
@@ -124,6 +152,7 @@ __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const 
 // column sums of dY.  Wavefront (wm, wn) owns rows 128 wm.., columns 64 wn.. of the product.
 // a.rows is a multiple of 32.
 // ---------------------------------------------------------------------------
+template <bool HEADS>
 __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
 {
     extern __shared__ float4 smem_r[];
@@ -135,20 +164,45 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
     const int split = blockIdx.x;
     const int m_begin = split * a.rows, m_end = m_begin + a.rows;
     const int lrow = __builtin_amdgcn_readfirstlane(tid >> 6), lc = (tid & 63) << 2;
-    f4v_r sx[4], sy[4];
+    f4v_r sx[4], sy[4], dh[HEADS ? 4 : 1];
     f4v_r bsum = {0.0f, 0.0f, 0.0f, 0.0f};
+    HeadCols hc;
+    float gwh[HEADS ? 4 : 1][4];                                     // head-matrix gradient of this thread's four columns
+    f4v_r gbh = {0.0f, 0.0f, 0.0f, 0.0f};                            // head-bias gradient (every thread of a loader row holds the same)
+    if (HEADS) {
+        load_head_cols(a.hf, lc, hc);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) gwh[HEADS ? e : 0][k] = 0.0f;
+    }
     auto fetch = [&](int m0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int m = m0 + 8 * q + lrow;                                                          // uniform in a wavefront
             sx[q] = *reinterpret_cast<const f4v_r*>(a.x + (size_t)m * K + lc);
-            sy[q] = *reinterpret_cast<const f4v_r*>(a.dy + (size_t)m * a.ldy + lc);
+            if (HEADS) {
+                sy[q] = *reinterpret_cast<const f4v_r*>(a.hf.hl + (size_t)m * N + lc);
+                dh[HEADS ? q : 0] = *reinterpret_cast<const f4v_r*>(a.hf.dhead + (size_t)m * a.hf.NHP);
+            } else {
+                sy[q] = *reinterpret_cast<const f4v_r*>(a.dy + (size_t)m * a.ldy + lc);
+            }
         }
     };
     auto store = [&](int b) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             *reinterpret_cast<f4v_r*>(Xs + (b * RT + 8 * q + lrow) * 256 + lc) = sx[q];
+            if (HEADS) {
+                // the head matrix's own gradient: hl^T dhead, from the activations just loaded (zero where the relu cut)
+                const f4v_r d = dh[HEADS ? q : 0];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) gwh[HEADS ? e : 0][k] = fmaf(sy[q][e], d[k], gwh[HEADS ? e : 0][k]);
+                gbh += d;
+                sy[q] = head_dy(hc, sy[q], d);
+            }
             *reinterpret_cast<f4v_r*>(Ys + (b * RT + 8 * q + lrow) * 256 + lc) = sy[q];
             bsum += sy[q];
         }
@@ -218,6 +272,34 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
         for (int g = 0; g < 8; ++g) s += red[g * 256 + tid];
         out[(size_t)K * N + tid] = s;
     }
+    if (HEADS) {
+        // head-matrix and head-bias gradients: the eight loader rows of a column add up in ascending order
+        const int NH = a.hf.NH;
+        float* hout = a.hf.head_partial + (size_t)split * ((size_t)N * NH + NH);
+        float* red4 = Ys;                                            // [8][256][4]
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f4v_r v = {gwh[HEADS ? e : 0][0], gwh[HEADS ? e : 0][1], gwh[HEADS ? e : 0][2], gwh[HEADS ? e : 0][3]};
+            *reinterpret_cast<f4v_r*>(red4 + ((size_t)lrow * 256 + lc + e) * 4) = v;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            f4v_r s4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int g = 0; g < 8; ++g) s4 += *reinterpret_cast<const f4v_r*>(red4 + ((size_t)g * 256 + tid) * 4);
+            for (int k = 0; k < NH; ++k) hout[(size_t)tid * NH + k] = s4[k];
+        }
+        __syncthreads();
+        // bias: one thread per loader row holds that row's sum (lane 0 of each wavefront)
+        if (lane == 0) *reinterpret_cast<f4v_r*>(red4 + lrow * 4) = gbh;
+        __syncthreads();
+        if (tid < NH) {
+            float s = 0.0f;
+            for (int g = 0; g < 8; ++g) s += red4[g * 4 + tid];
+            hout[(size_t)N * NH + tid] = s;
+        }
+    }
 }
 
 bool gemm_nt_res_ok(const GemmNtArgs& a) { return a.N == 256 && a.K % 256 == 0 && a.M >= 8 && a.M % 8 == 0; }
@@ -229,18 +311,20 @@ hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s)
     const int blocks = tiles < 256 ? tiles : 256;
     const int rows_per_block = ((tiles + blocks - 1) / blocks) * RT;
     const size_t lds = (size_t)2 * RT * NTR_LD * sizeof(float);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_res256), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    auto kern = a.hf.hl ? gemm_nt_res256<true> : gemm_nt_res256<false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_nt_res256, dim3((a.M + rows_per_block - 1) / rows_per_block, a.K / 256), dim3(RWG), lds, s, a, rows_per_block);
+    hipLaunchKernelGGL(kern, dim3((a.M + rows_per_block - 1) / rows_per_block, a.K / 256), dim3(RWG), lds, s, a, rows_per_block);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s)
 {
     const size_t lds = (size_t)4 * RT * 256 * sizeof(float);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_res256), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    auto kern = a.hf.hl ? gemm_tn_res256<true> : gemm_tn_res256<false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gemm_tn_res256, dim3(a.splits), dim3(RWG), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(a.splits), dim3(RWG), lds, s, a);
     return hipGetLastError();
 }
 

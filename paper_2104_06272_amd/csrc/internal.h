@@ -201,6 +201,9 @@ bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B);
 // the stored unroll was produced by the bf16 matrix-core kernels and the maze first layer is reduced in pieces
 inline bool first_layer_split(const anakin* h) { return h->splits_w > 0 && h->traj_packed; }
 inline bool bf16_mfma(const anakin* h) { return h->bf16_path && !(h->mode & (ANAKIN_MODE_CANONICAL_ACTING | ANAKIN_MODE_VALU_GEMM)); }
+// the head backward pass can ride in the loaders of the top hidden layer's two resident products: a 256 -> 256 top
+// layer, at most four head outputs, sample count in whole 32-row stages
+inline bool heads_fused_shape(const NetShape& n, int M) { return !n.bf16 && n.L >= 2 && n.NH <= 4 && n.dims[n.L] == 256 && n.dims[n.L - 1] == 256 && M % 32 == 0; }
 int rollout_pick_tile(const NetShape& net, int B);
 int rollout_pick_tile_mfma(const NetShape& net, int B);
 int rollout_resident_tile(const NetShape& net, int B);
