@@ -570,9 +570,38 @@ __global__ __launch_bounds__(WG) void first_layer_grad_pendulum(const FirstGradA
 typedef float f16v_l __attribute__((ext_vector_type(16)));
 typedef float f4v_l __attribute__((ext_vector_type(4)));
 
+typedef __bf16 bf8_l __attribute__((ext_vector_type(8)));
+typedef __bf16 bf2_l __attribute__((ext_vector_type(2)));
+typedef uint32_t u4v_l __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t pk_bf16_l(float lo, float hi)
+{
+    bf2_l v; v[0] = (__bf16)lo; v[1] = (__bf16)hi;               // round to nearest even, one instruction for the pair
+    return __builtin_bit_cast(uint32_t, v);
+}
+// x as three bfloat16 terms whose sum is x (8 + 8 + 8 significand bits): with the 0/1 board as the other operand
+// every product is exact and the fp32 accumulation is the one an fp32 matrix instruction would do, at a fifth of
+// its matrix-core time (three 8-pass instructions of 16 samples instead of eight 16-pass ones of 2)
+__device__ __forceinline__ void split3(const float (&x)[8], u4v_l& hi, u4v_l& mid, u4v_l& lo)
+{
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t p = pk_bf16_l(x[2 * i], x[2 * i + 1]);
+        hi[i] = p;
+        r[2 * i] = x[2 * i] - f_from_bits(p << 16);
+        r[2 * i + 1] = x[2 * i + 1] - f_from_bits(p & 0xffff0000u);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t p = pk_bf16_l(r[2 * i], r[2 * i + 1]);
+        mid[i] = p;
+        lo[i] = pk_bf16_l(r[2 * i] - f_from_bits(p << 16), r[2 * i + 1] - f_from_bits(p & 0xffff0000u));
+    }
+}
+
 __global__ __launch_bounds__(512) void first_layer_grad_mfma(const FirstGradArgs a)
 {
-    __shared__ f4v_l xs[2][2][8][64];                          // [buffer][tile][group of four steps][lane]
+    __shared__ u4v_l xs[2][2][4][64];                          // [buffer][tile of 32 cells][step of 16 samples][lane]
     const int N = a.N, K = a.K;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l32 = lane & 31, kg = lane >> 5;
     const int j = blockIdx.y * 256 + wave * 32 + l32;
@@ -582,43 +611,56 @@ __global__ __launch_bounds__(512) void first_layer_grad_mfma(const FirstGradArgs
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc0[r] = 0.0f; acc1[r] = 0.0f; }
     const uint32_t lane_off = (uint32_t)(32 * kg) * (uint32_t)N + (uint32_t)j;
-    // loads of one block of 64 samples: this lane's 32 values of dZ1 and the state word of sample m0 + lane
+    // loads of one block of 64 samples: this lane's 32 values of dZ1 (samples 32 kg + 0..31 of column j) and the
+    // state word of sample m0 + lane
     auto load = [&](float (&d)[32], uint32_t& sw, int m0) {
         sw = a.obs.s0[m0 + lane];
 #pragma unroll
         for (int s = 0; s < 32; ++s) d[s] = (a.dy + (size_t)(m0 + s) * N)[lane_off];
     };
-    // this wavefront's share of the board operand: steps 4w..4w+3, both tiles
+    // The reduction index of step t is k = 8 kg + q for sample 32 kg + 8 t + q of the block: lane (cell l32, half kg)
+    // of the board operand holds the 0/1 entries of its cell for those eight samples as bfloat16.  Wavefront w builds
+    // the operand of (tile w & 1, step w >> 1) for everybody.
     auto build = [&](uint32_t sw, int buf) {
         int bc, pc;
         catch_obs_cells(a.obs.env, sw, bc, pc);
         const unsigned long long bits = (1ull << bc) | (1ull << pc) | (1ull << K);   // lane l: board of sample l, ones row K
-        const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
-        f4v_l x0, x1;
+        const uint32_t mine = (wave & 1) ? (uint32_t)(bits >> 32) : (uint32_t)bits;  // the 32 cells of this wavefront's tile
+        const int t = wave >> 1;
+        u4v_l x;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int s = 4 * wave + e;
-            const uint32_t lo0 = (uint32_t)__builtin_amdgcn_readlane((int)lo, s), lo1 = (uint32_t)__builtin_amdgcn_readlane((int)lo, 32 + s);
-            const uint32_t hi0 = (uint32_t)__builtin_amdgcn_readlane((int)hi, s), hi1 = (uint32_t)__builtin_amdgcn_readlane((int)hi, 32 + s);
-            x0[e] = (float)(((kg ? lo1 : lo0) >> l32) & 1u);
-            x1[e] = (float)(((kg ? hi1 : hi0) >> l32) & 1u);
+        for (int i = 0; i < 4; ++i) {
+            uint32_t w2 = 0;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int q = 2 * i + e;
+                const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)mine, 8 * t + q);
+                const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane((int)mine, 32 + 8 * t + q);
+                const uint32_t bit = ((kg ? b1 : b0) >> l32) & 1u;
+                w2 |= (bit * 0x3f80u) << (16 * e);                 // bfloat16 1.0
+            }
+            x[i] = w2;
         }
-        xs[buf][0][wave][lane] = x0;
-        xs[buf][1][wave][lane] = x1;
+        xs[buf][wave & 1][t][lane] = x;
     };
     auto compute = [&](const float (&d)[32], int buf) {
-        // the board operand of group g + 1 is read from LDS before the MFMAs of group g are issued
-        f4v_l x0 = xs[buf][0][0][lane], x1 = xs[buf][1][0][lane];
 #pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            const f4v_l n0 = xs[buf][0][g + 1 < 8 ? g + 1 : 0][lane], n1 = xs[buf][1][g + 1 < 8 ? g + 1 : 0][lane];
-            __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < 4; ++t) {
+            const u4v_l x0 = xs[buf][0][t][lane], x1 = xs[buf][1][t][lane];
+            float v[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[e], d[4 * g + e], acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[e], d[4 * g + e], acc1, 0, 0, 0);
-            }
-            x0 = n0; x1 = n1;
+            for (int q = 0; q < 8; ++q) v[q] = d[8 * t + q];
+            u4v_l hi, mid, lo;
+            split3(v, hi, mid, lo);
+            const bf8_l a0 = __builtin_bit_cast(bf8_l, x0), a1 = __builtin_bit_cast(bf8_l, x1);
+            const bf8_l bh = __builtin_bit_cast(bf8_l, hi), bm = __builtin_bit_cast(bf8_l, mid), bl = __builtin_bit_cast(bf8_l, lo);
+            // smallest terms first
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bl, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bl, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bm, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bm, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bh, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bh, acc1, 0, 0, 0);
         }
     };
     float dA[32], dB[32];
