@@ -341,30 +341,38 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     for (int s2 = 0; s2 < KS; ++s2) wreg[s2] = *reinterpret_cast<const bf8*>(a.w16 + (size_t)i * NR + 16 * s2 + 8 * kg);
     // loader: row RPP*q + tid/PPR (uniform in a wavefront when PPR >= 64), piece tid%PPR
     const int lrow = tid / PPR, lc = (tid % PPR) * 8;
-    u32x4_l st[NQ];
-    auto fetch = [&](int m0) {
+    // Two register sets of staged rows: the rows of stage s + 2 are requested while stage s is computed, so a load
+    // has two stage times to come back (one stage is shorter than the memory latency under load, and this kernel
+    // lives on the HBM roof).  The relu mask of stage s + 1 is requested one stage ahead for the same reason.
+    u32x4_l stA[NQ], stB[NQ];
+    auto fetch = [&](u32x4_l (&st)[NQ], int m0) {
 #pragma unroll
         for (int q = 0; q < NQ; ++q) st[q] = *reinterpret_cast<const u32x4_l*>(a.dyR + (size_t)(m0 + RPP * q + lrow) * NR + lc);
     };
-    auto store = [&](uint16_t* buf) {
+    auto store = [&](const u32x4_l (&st)[NQ], uint16_t* buf) {
 #pragma unroll
         for (int q = 0; q < NQ; ++q) *reinterpret_cast<u32x4_l*>(buf + (RPP * q + lrow) * LD + lc) = st[q];
     };
-    fetch(m_begin);
-    store(As0);
-    __syncthreads();
     const uint32_t lane_off = (uint32_t)i * 8u + 4u * kg;        // inside a packed group of eight samples
     const int cl = wave * 32 + l32;                              // column inside the 256-column block
-    int t = 0;
-    for (int m0 = m_begin; m0 < m_end; m0 += NRES_RT, t ^= 1) {
-        const uint16_t* cur = t ? As1 : As0;
-        uint16_t* nxt = t ? As0 : As1;
-        uint16_t* Ts = t ? Ts1 : Ts0;
-        fetch(m0 + NRES_RT < m_end ? m0 + NRES_RT : m0);        // the last step re-reads its own rows, unused
-        u32x2_l mask[4];
+    u32x2_l maskA[4], maskB[4];
+    auto fetch_mask = [&](u32x2_l (&mk)[4], int m0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-            mask[g] = *reinterpret_cast<const u32x2_l*>(a.hP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off);
+            mk[g] = *reinterpret_cast<const u32x2_l*>(a.hP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off);
+    };
+    const int m_lastst = m_end - NRES_RT;                        // loads past the end re-read the last stage, unused
+    auto clampm = [&](int m) { return m < m_end ? m : m_lastst; };
+    fetch(stA, m_begin);
+    store(stA, As0);
+    fetch(stA, clampm(m_begin + NRES_RT));                       // stage 1, stored at the end of stage 0
+    fetch_mask(maskA, m_begin);
+    __syncthreads();
+    // one stage: MFMAs on `cur`, epilogue with `mask`, then the staged rows `st` (stage s + 1) go to `nxt`
+    auto stage = [&](int m0, const uint16_t* cur, uint16_t* nxt, uint16_t* Ts, const u32x2_l (&mask)[4],
+                     u32x4_l (&st_next)[NQ], u32x4_l (&st_fill)[NQ], u32x2_l (&mask_fill)[4]) {
+        fetch(st_fill, clampm(m0 + 2 * NRES_RT));                // two stages ahead
+        fetch_mask(mask_fill, clampm(m0 + NRES_RT));             // one stage ahead
         __builtin_amdgcn_sched_barrier(0);
         f16v acc;
 #pragma unroll
@@ -390,7 +398,7 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
             u32x2_l pv; pv[0] = p01; pv[1] = p23;
             *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
         }
-        if (m0 + NRES_RT < m_end) store(nxt);
+        if (m0 + NRES_RT < m_end) store(st_next, nxt);
         __syncthreads();
         // row-major copy of this stage: 32 rows x 256 columns, two 16-byte pieces per thread
 #pragma unroll
@@ -399,6 +407,10 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
             const int p = q * NRES_WG + tid, row = p >> 5, c = (p & 31) << 3;
             *reinterpret_cast<u32x4_l*>(a.dxR + (size_t)(m0 + row) * a.K + i0 + c) = *reinterpret_cast<const u32x4_l*>(Ts + row * NRES_LDT + c);
         }
+    };
+    for (int m0 = m_begin; m0 < m_end; m0 += 2 * NRES_RT) {
+        stage(m0, As0, As1, Ts0, maskA, stA, stB, maskB);
+        if (m0 + NRES_RT < m_end) stage(m0 + NRES_RT, As1, As0, Ts1, maskB, stB, stA, maskA);
     }
 }
 
