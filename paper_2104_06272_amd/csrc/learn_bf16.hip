@@ -639,17 +639,29 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     auto compute = [&]() {
+        // the operands of step ks + 2 are read from LDS before the eight MFMAs of step ks are issued
+        bf8 av[4], bv[2];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[kg * 256 + wm * 128 + 32 * t + l32]);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[kg * 256 + wn * 64 + 32 * t + l32]);
 #pragma unroll
         for (int ks = 0; ks < TB_BG; ks += 2) {                  // one MFMA step = 16 samples = 2 groups
-            bf8 av[4], bv[2];
+            const int kn = (ks + 2 < TB_BG ? ks + 2 : 0) + kg;
+            bf8 an[4], bn[2];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32]);
+            for (int t = 0; t < 4; ++t) an[t] = *reinterpret_cast<const bf8*>(&Xs[kn * 256 + wm * 128 + 32 * t + l32]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
+            for (int t = 0; t < 2; ++t) bn[t] = *reinterpret_cast<const bf8*>(&Ys[kn * 256 + wn * 64 + 32 * t + l32]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) av[t] = an[t];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) bv[t] = bn[t];
         }
     };
     // one pipeline step: stage g0 (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage
