@@ -5,13 +5,14 @@
 // backwards with the adjoint lambda_t = dL_path/ds_t and writes dL_path/d(mu, log_sigma) per
 // sample; the ordinary backward pass then turns head gradients into parameter gradients.
 //
-// A workgroup owns 16 envs for the whole sweep.  Per step: (A) the env's lane turns lambda_{t+1}
+// A workgroup owns 16 (or 32) envs for the whole sweep.  Per step: (A) the env's lane turns lambda_{t+1}
 // into the gradient of the action and of (mu, log_sigma); (B) dZ2 = relu'(h2) (Wh g); (C)
 // dZ1 = relu'(h1) (dZ2 W2^T) on the matrix cores, W2^T resident in registers for the whole sweep
 // exactly as the acting kernel keeps W2; (D) g_obs = dZ1 W1^T, three dot products per env; (E)
 // lambda_t from the step's and the reward's own derivatives plus g_obs through o = (cos, sin, thd).
 // An episode end cuts the adjoint (the next state is a reset state).  The velocity clip is decided
 // with the env step's own binary32 expression, so it agrees with what the env did.
+#include <type_traits>
 #include "internal.h"
 #include "detmath.cuh"
 
@@ -29,30 +30,37 @@ struct PathArgs {
     float w;                                  // dL_path / dr = -1 / (B T)
 };
 
-template <int RW>
+typedef float f16v_p __attribute__((ext_vector_type(16)));
+
+// M32: 32 envs per workgroup on v_mfma_f32_32x32x2_f32 (for batches of at least 32 envs per compute unit), else 16
+// envs on v_mfma_f32_16x16x4_f32; the operand layouts are those of the two acting kernels.
+template <int RW, bool M32>
 __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
 {
-    constexpr int TM = 16, KS = RW / 4, NT = RW / 64, LDX = RW + 4;
-    __shared__ __attribute__((aligned(16))) float bufA[TM * LDX];      // dZ2
-    __shared__ __attribute__((aligned(16))) float bufB[TM * LDX];      // dZ1
-    __shared__ __attribute__((aligned(16))) float w1s[3 * RW];         // first-layer matrix, [3][RW]
-    __shared__ __attribute__((aligned(16))) float whs[2 * RW];         // head matrix columns of mu and log_sigma, [2][RW]
-    __shared__ float gh[TM * 2];
-    __shared__ float gobs[TM * 4];
+    constexpr int TM = M32 ? 32 : 16, KS = M32 ? RW / 2 : RW / 4, NT = M32 ? RW / 128 : RW / 64, LDX = RW + 4;
+    constexpr int RL = M32 ? 32 : 16;                                  // rows an operand lane indexes
+    constexpr int KSTEP = M32 ? 2 : 4;                                 // reduction indices per MFMA
+    extern __shared__ float4 smem_p[];
+    float* bufA = reinterpret_cast<float*>(smem_p);                    // [TM][LDX] dZ2
+    float* bufB = bufA + TM * LDX;                                     // [TM][LDX] dZ1
+    float* w1s = bufB + TM * LDX;                                      // first-layer matrix, [3][RW]
+    float* whs = w1s + 3 * RW;                                         // head matrix columns of mu and log_sigma, [2][RW]
+    float* gh = whs + 2 * RW;                                          // [TM][2]
+    float* gobs = gh + TM * 2;                                         // [TM][4]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.x * TM, B = a.B, T = a.T;
 
     for (int i = tid; i < 3 * RW; i += WG) w1s[i] = a.theta[a.w1_off + i];
     for (int i = tid; i < 2 * RW; i += WG) { const int c = i / RW, k = i - c * RW; whs[i] = a.theta[a.wh_off + k * a.NH + c]; }
-    // B operand of step s, tile t: W2^T[4s + kq][col0 + t] = W2[col0 + t][4s + kq]
-    const int col0 = wave * (RW >> 2) + NT * (lane & 15), kq = lane >> 4;
+    // B operand of step s, tile t: W2^T[KSTEP s + kq][col0 + t] = W2[col0 + t][KSTEP s + kq]
+    const int col0 = wave * (RW >> 2) + NT * (lane & (RL - 1)), kq = lane / RL;
     float wreg[KS][NT];
     {
         const float* W2 = a.theta + a.w2_off;
 #pragma unroll
         for (int s = 0; s < KS; ++s)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) wreg[s][t] = W2[(size_t)(col0 + t) * RW + 4 * s + kq];
+            for (int t = 0; t < NT; ++t) wreg[s][t] = W2[(size_t)(col0 + t) * RW + KSTEP * s + kq];
     }
     const bool owner = tid < TM;
     const int b = b0 + tid;
@@ -111,32 +119,41 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
         __syncthreads();
         // ---- (C) dZ1 = (h1 > 0) (dZ2 W2^T) -------------------------------------------
         {
-            f4v_p acc[NT];
+            typedef typename std::conditional<M32, f16v_p, f4v_p>::type acc_t;
+            constexpr int NR_ = M32 ? 16 : 4;                          // accumulator registers per tile
+            acc_t acc[NT];
 #pragma unroll
-            for (int tt = 0; tt < NT; ++tt) acc[tt] = f4v_p{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+                for (int r = 0; r < NR_; ++r) acc[tt][r] = 0.0f;
             // the relu mask of the result: requested before the products so the loads overlap them
             const float* h1 = a.act0 + ((size_t)t * B + b0) * RW;
-            float h1v[4][NT];
+            float h1v[NR_][NT];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+            for (int r = 0; r < NR_; ++r) {
+                const int row = M32 ? 8 * (r >> 2) + 4 * kq + (r & 3) : 4 * kq + r;
 #pragma unroll
-                for (int tt = 0; tt < NT; ++tt) h1v[r][tt] = h1[(size_t)(4 * kq + r) * RW + col0 + tt];
-            const float* xp = bufA + (lane & 15) * LDX + kq;
+                for (int tt = 0; tt < NT; ++tt) h1v[r][tt] = h1[(size_t)row * RW + col0 + tt];
+            }
+            const float* xp = bufA + (lane & (RL - 1)) * LDX + kq;
             constexpr int PF = 4;
             float ap[PF];
 #pragma unroll
-            for (int u = 0; u < PF; ++u) ap[u] = xp[4 * u];
+            for (int u = 0; u < PF; ++u) ap[u] = xp[KSTEP * u];
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const float av = ap[s % PF];
-                ap[s % PF] = xp[4 * (s + PF < KS ? s + PF : 0)];
+                ap[s % PF] = xp[KSTEP * (s + PF < KS ? s + PF : 0)];
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int tt = 0; tt < NT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wreg[s][tt], acc[tt], 0, 0, 0);
+                for (int tt = 0; tt < NT; ++tt) {
+                    if constexpr (M32) acc[tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, wreg[s][tt], acc[tt], 0, 0, 0);
+                    else acc[tt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wreg[s][tt], acc[tt], 0, 0, 0);
+                }
             }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = 4 * kq + r;
+            for (int r = 0; r < NR_; ++r) {
+                const int row = M32 ? 8 * (r >> 2) + 4 * kq + (r & 3) : 4 * kq + r;
 #pragma unroll
                 for (int tt = 0; tt < NT; ++tt)
                     bufB[row * LDX + col0 + tt] = h1v[r][tt] > 0.0f ? acc[tt][r] : 0.0f;
@@ -146,8 +163,8 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
         __syncthreads();
         // ---- (D) g_obs[m][c] = sum_i dZ1[m][i] W1[c][i] ----------------------------------
         {
-            const int m = tid >> 4, part = tid & 15;
-            constexpr int SEG = RW / 16;
+            constexpr int PARTS = WG / TM, SEG = RW / PARTS;          // PARTS lanes share an env's three dot products
+            const int m = tid / PARTS, part = tid % PARTS;
             float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
             for (int e = 0; e < SEG; ++e) {
@@ -156,8 +173,8 @@ __global__ __launch_bounds__(WG) void pathwise_sweep(const PathArgs a)
                 s0 = fmaf(d, w1s[i], s0); s1 = fmaf(d, w1s[RW + i], s1); s2 = fmaf(d, w1s[2 * RW + i], s2);
             }
 #pragma unroll
-            for (int off = 8; off > 0; off >>= 1) {
-                s0 += __shfl_xor(s0, off, 16); s1 += __shfl_xor(s1, off, 16); s2 += __shfl_xor(s2, off, 16);
+            for (int off = PARTS / 2; off > 0; off >>= 1) {
+                s0 += __shfl_xor(s0, off, PARTS); s1 += __shfl_xor(s1, off, PARTS); s2 += __shfl_xor(s2, off, PARTS);
             }
             if (part == 0) { gobs[m * 4] = s0; gobs[m * 4 + 1] = s1; gobs[m * 4 + 2] = s2; }
         }
@@ -191,13 +208,22 @@ hipError_t launch_pathwise(anakin* h)
     a.path = at<float>(h, L.path);
     a.B = h->B; a.T = h->T; a.w = (float)(-1.0 / ((double)h->B * (double)h->T));
     ProfScope prof(h, "pathwise_sweep");
-    const dim3 grid(h->B / 16);
-    switch (n.dims[1]) {
-        case 64:  hipLaunchKernelGGL(pathwise_sweep<64>, grid, dim3(WG), 0, h->stream, a); break;
-        case 128: hipLaunchKernelGGL(pathwise_sweep<128>, grid, dim3(WG), 0, h->stream, a); break;
-        default:  hipLaunchKernelGGL(pathwise_sweep<256>, grid, dim3(WG), 0, h->stream, a); break;
+    // 32 envs per workgroup once that still leaves a workgroup per compute unit (as the acting kernel chooses)
+    const bool m32 = n.dims[1] >= 128 && h->B % 32 == 0 && h->B / 32 >= 256;
+    const int TM = m32 ? 32 : 16, RW = n.dims[1];
+    const dim3 grid(h->B / TM);
+    const size_t lds = ((size_t)2 * TM * (RW + 4) + 5 * RW + 6 * TM) * sizeof(float);
+    auto go = [&](auto kern) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, grid, dim3(WG), lds, h->stream, a);
+        return hipGetLastError();
+    };
+    switch (RW) {
+        case 64:  return go(pathwise_sweep<64, false>);
+        case 128: return m32 ? go(pathwise_sweep<128, true>) : go(pathwise_sweep<128, false>);
+        default:  return m32 ? go(pathwise_sweep<256, true>) : go(pathwise_sweep<256, false>);
     }
-    return hipGetLastError();
 }
 
 }  // namespace ank

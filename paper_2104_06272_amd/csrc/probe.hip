@@ -69,9 +69,9 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
         auto* dst = reinterpret_cast<pf4v*>(static_cast<char*>(scratch) + half);
         const int blocks = variant > 0 ? variant : 4096;
         hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);   // warm-up
-        hipEventRecord(e0, s);
+        (void)hipEventRecord(e0, s);
         for (int r = 0; r < 10; ++r) hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);
-        hipEventRecord(e1, s);
+        (void)hipEventRecord(e1, s);
         *amount = 10.0 * 2.0 * (double)half;                 // bytes read + written
     } else if (kind == ANAKIN_PROBE_ADAM) {
         // theta | grad | m | v | one partial, P floats each; zeroed so that no value overflows over the repetitions
@@ -82,9 +82,9 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
         float* base = static_cast<float*>(scratch);
         if (hipMemsetAsync(base, 0, P * 20, s) != hipSuccess) return ANAKIN_E_HIP;
         err = launch_adam_probe(base, (int)P, s);            // warm-up
-        hipEventRecord(e0, s);
+        (void)hipEventRecord(e0, s);
         for (int r = 0; r < 5 && err == hipSuccess; ++r) err = launch_adam_probe(base, (int)P, s);
-        hipEventRecord(e1, s);
+        (void)hipEventRecord(e1, s);
         if (err != hipSuccess) return ANAKIN_E_HIP;
         *amount = 5.0 * 32.0 * (double)P;                    // 28 B of Adam state per parameter + 4 B of the partial
     } else {
@@ -96,16 +96,16 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
             else hipLaunchKernelGGL(probe_mfma_bf16, dim3(blocks), dim3(WG), 0, s, out, n, 1.0f);
         };
         launch(10);
-        hipEventRecord(e0, s);
+        (void)hipEventRecord(e0, s);
         launch(iters);
-        hipEventRecord(e1, s);
+        (void)hipEventRecord(e1, s);
         const double flop_per_mfma = kind == ANAKIN_PROBE_MFMA_F32 ? 4096.0 : 32768.0;
         *amount = (double)blocks * 4.0 * iters * 8.0 * 4.0 * flop_per_mfma;
     }
     err = hipEventSynchronize(e1);
     float ms = 0.0f;
     if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
-    hipEventDestroy(e0); hipEventDestroy(e1);
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
     if (err != hipSuccess || hipGetLastError() != hipSuccess) return ANAKIN_E_HIP;
     *milliseconds = (double)ms;
     return ANAKIN_OK;

@@ -445,6 +445,8 @@ PATHWISE_CASES = {
     "pendulum_256_B128": (variant("pendulum_8192", B=128), 0, 2),
     "pendulum_64_short_episodes": (variant("pendulum_8192", hidden=[64, 64], B=64, T=32, max_steps=25), 2, 3),
     "pendulum_128_B48": (variant("pendulum_8192", hidden=[128, 128], B=48, T=12, max_steps=7), 4, 2),
+    # enough envs for the 32-env form of the sweep (32x32x2 matrix instruction)
+    "pendulum_128_B8192": (_path_only(variant("pendulum_8192", hidden=[128, 128], B=8192, T=6, max_steps=4)), 5, 1),
 }
 
 
