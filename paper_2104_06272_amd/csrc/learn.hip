@@ -884,7 +884,101 @@ hipError_t launch_learn_one_layer(anakin* h)
 // the rounded copies the matrix-core kernels read are refreshed here too.
 // ---------------------------------------------------------------------------
 constexpr int ADAM_WAVES = 16;
+typedef float f4v_a __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int adam_region_of(const AdamArgs& a, int i)
+{
+    int r = 0;
+#pragma unroll
+    for (int k = 1; k < MAX_ADAM_REGIONS; ++k) if (k < a.n_regions && i >= a.reg[k].start) r = k;
+    return r;
+}
 __global__ __launch_bounds__(ADAM_WAVES * 64) void adam_reduce(const AdamArgs a)
+{
+    // 256 consecutive parameters per workgroup, four per lane; each of the 16 wavefronts adds its share of the
+    // split-K partials (splits w, w+16, w+32, ...) with 16-byte loads -- one KiB per wavefront and partial row --
+    // then the 16 sums are combined in wave order.  A group of four that straddles two regions, or lies in a
+    // region whose rows are not 16-byte aligned, is summed parameter by parameter.
+    __shared__ f4v_a red[ADAM_WAVES][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = (blockIdx.x * 64 + lane) * 4;
+    f4v_a g = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (i < a.P) {
+        const int r = adam_region_of(a, i);
+        const Region rg = a.reg[r];
+        const int off = i - rg.start;
+        if (i + 3 < a.P && off + 3 < rg.count && ((rg.count | off) & 3) == 0) {
+            const float* p = rg.partial + off;
+#pragma unroll 4
+            for (int s = wave; s < rg.splits; s += ADAM_WAVES) g += *reinterpret_cast<const f4v_a*>(p + (size_t)s * rg.count);
+        } else {
+            // the four parameters side by side, so that their loads overlap as the 16-byte ones do
+            const float* pe[4]; size_t cnt[4]; int sp[4], smax = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ie = i + e < a.P ? i + e : i;
+                const Region re = a.reg[adam_region_of(a, ie)];
+                pe[e] = re.partial + (ie - re.start); cnt[e] = (size_t)re.count;
+                sp[e] = i + e < a.P ? re.splits : 0;
+                smax = sp[e] > smax ? sp[e] : smax;
+            }
+#pragma unroll 4
+            for (int s = wave; s < smax; s += ADAM_WAVES) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) g[e] += s < sp[e] ? pe[e][(size_t)s * cnt[e]] : 0.0f;
+            }
+        }
+    }
+    red[wave][lane] = g;
+    __syncthreads();
+    if (wave != 0 || i >= a.P) return;
+    g = red[0][lane];
+#pragma unroll
+    for (int w = 1; w < ADAM_WAVES; ++w) g += red[w][lane];
+    if (i + 3 < a.P) {
+        const f4v_a mo = *reinterpret_cast<const f4v_a*>(a.m + i), vo = *reinterpret_cast<const f4v_a*>(a.v + i);
+        const f4v_a to = *reinterpret_cast<const f4v_a*>(a.theta + i);
+        f4v_a m, v, th;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            m[e] = a.beta1 * mo[e] + (1.0f - a.beta1) * g[e];
+            v[e] = a.beta2 * vo[e] + (1.0f - a.beta2) * g[e] * g[e];
+            const float mh = m[e] / a.bc1, vh = v[e] / a.bc2;
+            th[e] = to[e] - a.lr * mh / (sqrtf(vh) + a.eps);
+        }
+        *reinterpret_cast<f4v_a*>(a.grad + i) = g;
+        *reinterpret_cast<f4v_a*>(a.m + i) = m;
+        *reinterpret_cast<f4v_a*>(a.v + i) = v;
+        *reinterpret_cast<f4v_a*>(a.theta + i) = th;
+        if (a.w_bf16) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint16_t hb = bf16_bits(th[e]);
+                a.w_bf16[i + e] = hb;
+                a.wt_bf16[transposed_index(a.net, i + e)] = hb;
+            }
+        }
+        return;
+    }
+    for (int e = 0; e < 4 && i + e < a.P; ++e) {
+        const float m = a.beta1 * a.m[i + e] + (1.0f - a.beta1) * g[e];
+        const float v = a.beta2 * a.v[i + e] + (1.0f - a.beta2) * g[e] * g[e];
+        const float mh = m / a.bc1, vh = v / a.bc2;
+        const float th = a.theta[i + e] - a.lr * mh / (sqrtf(vh) + a.eps);
+        a.grad[i + e] = g[e];
+        a.m[i + e] = m;
+        a.v[i + e] = v;
+        a.theta[i + e] = th;
+        if (a.w_bf16) {
+            const uint16_t hb = bf16_bits(th);
+            a.w_bf16[i + e] = hb;
+            a.wt_bf16[transposed_index(a.net, i + e)] = hb;
+        }
+    }
+}
+
+// One parameter per lane, 64 per workgroup: four times the workgroups of adam_reduce, which is what small parameter
+// vectors (under about 2^18) need to keep every compute unit loading.
+__global__ __launch_bounds__(ADAM_WAVES * 64) void adam_reduce_narrow(const AdamArgs a)
 {
     // 64 consecutive parameters per workgroup; each of the 16 wavefronts adds its share of the
     // split-K partials (splits w, w+16, w+32, ...), then the 16 sums are combined in wave order
@@ -970,7 +1064,8 @@ static void launch_adam_kernel(const AdamArgs& a, hipStream_t s)
     int max_splits = 0;
     for (int r = 0; r < a.n_regions; ++r) max_splits = a.reg[r].splits > max_splits ? a.reg[r].splits : max_splits;
     if (max_splits <= 16) hipLaunchKernelGGL(adam_reduce_flat, dim3((a.P + 4 * WG - 1) / (4 * WG)), dim3(WG), 0, s, a);
-    else hipLaunchKernelGGL(adam_reduce, dim3((a.P + 63) / 64), dim3(ADAM_WAVES * 64), 0, s, a);
+    else if (a.P >= (1 << 18)) hipLaunchKernelGGL(adam_reduce, dim3((a.P + 255) / 256), dim3(ADAM_WAVES * 64), 0, s, a);
+    else hipLaunchKernelGGL(adam_reduce_narrow, dim3((a.P + 63) / 64), dim3(ADAM_WAVES * 64), 0, s, a);
 }
 
 // ---------------------------------------------------------------------------
