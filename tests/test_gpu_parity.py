@@ -58,6 +58,12 @@ LOCKSTEP_CASES = {
     # 512-wide last layer: two column blocks in the head pass; 512-wide first layer of the pendulum kernel
     "catch_256x512": (variant("catch_4096", hidden=[256, 512], B=64, T=10), 5, 2, TOL_F32),
     "pendulum_512x256": (variant("pendulum_8192", hidden=[512, 256], B=64, T=12, max_steps=9), 6, 2, TOL_F32),
+    # degenerate shapes: a one-step unroll (the return is reward + bootstrap only), a single tile of envs,
+    # an episode end at every step (max_steps = 1: every transition is terminal, nothing bootstraps)
+    "catch_T1": (variant("catch_small", B=64, T=1), 7, 3, TOL_F32),
+    "pendulum_T1_B16": (variant("pendulum_8192", hidden=[64, 64], B=16, T=1), 8, 2, TOL_F32),
+    "pendulum_every_step_terminal": (variant("pendulum_8192", hidden=[64, 64], B=32, T=6, max_steps=1), 9, 2, TOL_F32),
+    "maze_fp32_one_step_episodes": (variant("maze_16384", hidden=[64, 64], B=32, T=5, dtype="fp32", max_steps=1), 10, 2, TOL_F32),
 }
 
 
