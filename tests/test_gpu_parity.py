@@ -200,6 +200,33 @@ def test_full_size_headline_update(gpu, orc):
     g.close()
 
 
+@pytest.mark.parametrize("name", ["catch_262144", "pendulum_8192"])
+def test_full_size_whole_step(gpu, orc, name):
+    """Two more workloads at their full size, one whole step in lockstep, in the launch shape the benchmark times:
+    every env of the unroll bit-exact, then the update (the lane-per-env acting kernel and the one-layer update for
+    the tiny net; the 32-env resident acting kernel, the pendulum's first-layer kernel and the head-folded products
+    for the pendulum).  The oracle needs ten to thirty seconds for each."""
+    cfg = W.get(name)
+    kind = cfg["env"]["kind"]
+    say(f"[full size] {name} whole step, all envs")
+    g = gpu.Anakin(cfg, seed=11); o = orc.Oracle(cfg, seed=11)
+    g.step()
+    PT.sync_oracle_from_gpu(g, o)
+    si, sf = g.get_env_state()
+    o.state_i[:] = si; o.state_f[:] = sf
+    o.global_step = g.global_step
+    g.rollout()
+    say("  unroll on the oracle ...")
+    o.rollout()
+    PT.assert_rollout_equal(g, o, kind)
+    PT.assert_final_state_equal(g, o, kind)
+    say("  update on the oracle ...")
+    g.learn(); o.learn()
+    e_g, e_p = PT.assert_learn_close(g, o, TOL_F32)
+    say(f"  gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
+    g.close()
+
+
 # --------------------------------------------------------------------------- bf16 on the matrix cores
 BF16_CASES = {
     "maze_bf16_128": (variant("maze_16384", hidden=[128, 128, 128], B=64, T=16, max_steps=40), 3, 2),
