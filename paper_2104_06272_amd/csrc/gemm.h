@@ -53,5 +53,6 @@ bool gemm_nt_res_ok(const GemmNtArgs& a);
 bool gemm_tn_res_ok(const GemmTnArgs& a);
 hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s);
 hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s);
+hipError_t launch_gemm_tn_nt_res(const GemmTnArgs& t, const GemmNtArgs& n, hipStream_t s);   // both products of a layer, one launch
 
 }  // namespace ank

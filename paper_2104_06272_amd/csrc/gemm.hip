@@ -207,13 +207,8 @@ hipError_t launch_backward(anakin* h)
         t.hf = HeadFuse{}; t.hf.hl = nullptr;
         if (l == n.L - 1 && hf.hl) t.hf = hf;
         const bool mfma = !(h->mode & ANAKIN_MODE_VALU_GEMM) && !n.bf16;
-        {
-            ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
-            e = !mfma ? launch_gemm_tn_valu(t, h->stream) : gemm_tn_res_ok(t) ? launch_gemm_tn_res(t, h->stream) : launch_gemm_tn_mfma(t, h->stream);
-        }
-        if (e != hipSuccess) return e;
+        GemmNtArgs g;
         if (l > 0) {
-            GemmNtArgs g;
             g.M = M; g.K = n.dims[l]; g.N = n.dims[l + 1];
             g.dy = at<const float>(h, L.dz[l]);
             g.w = at<const float>(h, L.w_src) + n.w_off[l];
@@ -222,10 +217,22 @@ hipError_t launch_backward(anakin* h)
             g.bf16 = n.bf16;
             g.hf = HeadFuse{}; g.hf.hl = nullptr;
             if (l == n.L - 1 && hf.hl) g.hf = hf;
-            {
-                ProfScope prof(h, "gemm_nt_mask");
-                e = !mfma ? launch_gemm_nt_valu(g, h->stream) : gemm_nt_res_ok(g) ? launch_gemm_nt_res(g, h->stream) : launch_gemm_nt_mfma(g, h->stream);
+            if (mfma && gemm_tn_res_ok(t) && gemm_nt_res_ok(g)) {
+                // the layer's two resident products share one launch
+                ProfScope prof(h, "gemm_tn_nt");
+                e = launch_gemm_tn_nt_res(t, g, h->stream);
+                if (e != hipSuccess) return e;
+                continue;
             }
+        }
+        {
+            ProfScope prof(h, l == 0 ? "gemm_tn_obs" : "gemm_tn");
+            e = !mfma ? launch_gemm_tn_valu(t, h->stream) : gemm_tn_res_ok(t) ? launch_gemm_tn_res(t, h->stream) : launch_gemm_tn_mfma(t, h->stream);
+        }
+        if (e != hipSuccess) return e;
+        if (l > 0) {
+            ProfScope prof(h, "gemm_nt_mask");
+            e = !mfma ? launch_gemm_nt_valu(g, h->stream) : gemm_nt_res_ok(g) ? launch_gemm_nt_res(g, h->stream) : launch_gemm_nt_mfma(g, h->stream);
             if (e != hipSuccess) return e;
         }
     }

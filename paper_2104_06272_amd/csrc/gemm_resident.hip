@@ -59,15 +59,15 @@ __device__ __forceinline__ f4v_r head_dy(const HeadCols& hc, f4v_r hv, f4v_r d)
 }
 
 template <bool HEADS>
-__global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const int rows_per_block)
+__device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const int rows_per_block, const int bx, const int by)
 {
     extern __shared__ float4 smem_r[];
     float* As0 = reinterpret_cast<float*>(smem_r);
     float* As1 = As0 + RT * NTR_LD;
     constexpr int N = 256;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
-    const int i = blockIdx.y * 256 + wave * 32 + l32;               // this lane's output column
-    const int m_begin = blockIdx.x * rows_per_block;
+    const int i = by * 256 + wave * 32 + l32;                       // this lane's output column
+    const int m_begin = bx * rows_per_block;
     const int m_end = m_begin + rows_per_block < a.M ? m_begin + rows_per_block : a.M;
     if (m_begin >= a.M) return;
     float wreg[128];
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const 
 // a.rows is a multiple of 32.
 // ---------------------------------------------------------------------------
 template <bool HEADS>
-__global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
+__device__ __forceinline__ void gemm_tn_res256_body(const GemmTnArgs& a, const int split)
 {
     extern __shared__ float4 smem_r[];
     float* Xs = reinterpret_cast<float*>(smem_r);                    // [2][32][256]
@@ -161,7 +161,6 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
     constexpr int K = 256, N = 256;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
     const int wm = wave >> 2, wn = wave & 3;
-    const int split = blockIdx.x;
     const int m_begin = split * a.rows, m_end = m_begin + a.rows;
     const int lrow = __builtin_amdgcn_readfirstlane(tid >> 6), lc = (tid & 63) << 2;
     f4v_r sx[4], sy[4], dh[HEADS ? 4 : 1];
@@ -302,6 +301,29 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
     }
 }
 
+template <bool HEADS>
+__global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const int rows_per_block)
+{
+    gemm_nt_res256_body<HEADS>(a, rows_per_block, (int)blockIdx.x, (int)blockIdx.y);
+}
+template <bool HEADS>
+__global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
+{
+    gemm_tn_res256_body<HEADS>(a, (int)blockIdx.x);
+}
+// Both products of one layer in one launch: they read the same operands and do not depend on each other.  The
+// dW workgroups come first in the grid; as each retires (its long tail is the write of a 256 KB partial, with the
+// matrix cores idle) a dX workgroup takes its compute unit, so the tail of one product overlaps the start of the
+// other instead of the two kernels running back to back.
+template <bool HEADS>
+__global__ __launch_bounds__(RWG) void gemm_tn_nt_res256(const GemmTnArgs t, const GemmNtArgs n, const int rows_per_block,
+                                                         const int tn_blocks, const int nt_bx)
+{
+    const int b = (int)blockIdx.x;
+    if (b < tn_blocks) gemm_tn_res256_body<HEADS>(t, b);
+    else gemm_nt_res256_body<HEADS>(n, rows_per_block, (b - tn_blocks) % nt_bx, (b - tn_blocks) / nt_bx);
+}
+
 bool gemm_nt_res_ok(const GemmNtArgs& a) { return a.N == 256 && a.K % 256 == 0 && a.M >= 8 && a.M % 8 == 0; }
 bool gemm_tn_res_ok(const GemmTnArgs& a) { return a.K == 256 && a.N == 256 && !a.use_obs && a.rows % RT == 0 && a.ldy % 4 == 0; }
 
@@ -325,6 +347,21 @@ hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.splits), dim3(RWG), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_tn_nt_res(const GemmTnArgs& t, const GemmNtArgs& n, hipStream_t s)
+{
+    const int tiles = (n.M + RT - 1) / RT;
+    const int blocks = tiles < 256 ? tiles : 256;
+    const int rows_per_block = ((tiles + blocks - 1) / blocks) * RT;
+    const int nt_bx = (n.M + rows_per_block - 1) / rows_per_block, nt_by = n.K / 256;
+    const size_t lds_nt = (size_t)2 * RT * NTR_LD * sizeof(float), lds_tn = (size_t)4 * RT * 256 * sizeof(float);
+    const size_t lds = lds_nt > lds_tn ? lds_nt : lds_tn;
+    auto kern = t.hf.hl ? gemm_tn_nt_res256<true> : gemm_tn_nt_res256<false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(t.splits + nt_bx * nt_by), dim3(RWG), lds, s, t, n, rows_per_block, t.splits, nt_bx);
     return hipGetLastError();
 }
 
