@@ -129,14 +129,23 @@ ANK_HD int sample_categorical(const float (&logits)[MAXA], int A, float u)
 }
 
 // Box-Muller noise, z = mu + sigma eps, squashed by tanh; log_sigma clamped to [-5, 2]
-ANK_HD void sample_gaussian(float mu, float log_sigma, uint32_t w0, uint32_t w1, float& eps, float& act)
+// the two halves of the sampler: the noise does not depend on the network, so a kernel can draw it early
+ANK_HD float gaussian_noise(uint32_t w0, uint32_t w1)
+{
+    const float rad = sqrtf(-2.0f * det_log(u01_plus(w0)));
+    return rad * det_cos2pi(u01(w1));
+}
+ANK_HD float gaussian_action(float mu, float log_sigma, float eps)
 {
     float ls = log_sigma < -5.0f ? -5.0f : log_sigma;
     ls = ls > 2.0f ? 2.0f : ls;
     const float sigma = det_exp(ls);
-    const float rad = sqrtf(-2.0f * det_log(u01_plus(w0)));
-    eps = rad * det_cos2pi(u01(w1));
-    act = det_tanh(fmaf(sigma, eps, mu));
+    return det_tanh(fmaf(sigma, eps, mu));
+}
+ANK_HD void sample_gaussian(float mu, float log_sigma, uint32_t w0, uint32_t w1, float& eps, float& act)
+{
+    eps = gaussian_noise(w0, w1);
+    act = gaussian_action(mu, log_sigma, eps);
 }
 
 }  // namespace ank

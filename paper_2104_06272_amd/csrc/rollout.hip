@@ -544,7 +544,8 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
         if (!REPLAY && t < T) {
             for (int e = WG - 1 - tid; e < TM; e += WG) {
                 const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
-                rng[e * 4] = w.x;
+                // the pendulum's noise is ready-made when the heads are: only z and tanh remain on the critical path
+                rng[e * 4] = ENV == ENV_PENDULUM ? bits_from_f(gaussian_noise(w.x, w.y)) : w.x;
                 rng[e * 4 + 1] = w.y;
             }
         }
@@ -567,8 +568,8 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
                 // the reset draw is only needed where an episode ends: the step runs with a placeholder
                 // and the few lanes that finished an episode draw and reset afterwards
                 if (ENV == ENV_PENDULUM) {
-                    float eps, act;
-                    sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
+                    const float eps = f_from_bits(dr.x);
+                    const float act = gaussian_action(hv[0], hv[1], eps);
                     tp.tr_eps[tb] = eps;
                     tp.tr_actf[tb] = act;
                     pendulum_step(a.env, st, act, 0u, 0u, r, done);
@@ -809,7 +810,8 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         if (!REPLAY && t < T) {
             for (int e = WG - 1 - tid; e < TM; e += WG) {
                 const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
-                rng[e * 4] = w.x;
+                // the pendulum's noise is ready-made when the heads are: only z and tanh remain on the critical path
+                rng[e * 4] = ENV == ENV_PENDULUM ? bits_from_f(gaussian_noise(w.x, w.y)) : w.x;
                 rng[e * 4 + 1] = w.y;
             }
         }
@@ -832,8 +834,8 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
                 // the reset draw is only needed where an episode ends: the step runs with a placeholder
                 // and the few lanes that finished an episode draw and reset afterwards
                 if (ENV == ENV_PENDULUM) {
-                    float eps, act;
-                    sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
+                    const float eps = f_from_bits(dr.x);
+                    const float act = gaussian_action(hv[0], hv[1], eps);
                     tp.tr_eps[tb] = eps;
                     tp.tr_actf[tb] = act;
                     pendulum_step(a.env, st, act, 0u, 0u, r, done);

@@ -406,7 +406,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
         // the last wavefront draws this step's random numbers while it waits for its weight rows
         if (!REPLAY && wave == 7 && t < T) {
             const u32x4 w = philox(a.seed, (uint32_t)(b0 + lane), a.gstep + (uint64_t)t, DOM_ACTION);
-            rng[lane * 2] = w.x;
+            rng[lane * 2] = ENV == ENV_PENDULUM ? bits_from_f(gaussian_noise(w.x, w.y)) : w.x;   // the noise is ready when the heads are
             rng[lane * 2 + 1] = w.y;
         }
         // ---- first layer: fp32 gather-sum / three fmas, rounded to bf16 ----------
@@ -543,8 +543,8 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                 const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 2);
                 float r; int done;
                 if (ENV == ENV_PENDULUM) {
-                    float eps, act;
-                    sample_gaussian(hv[0], hv[1], dr.x, dr.y, eps, act);
+                    const float eps = f_from_bits(dr.x);
+                    const float act = gaussian_action(hv[0], hv[1], eps);
                     tp.tr_eps[tb] = eps; tp.tr_actf[tb] = act;
                     pendulum_step(a.env, st, act, 0u, 0u, r, done);
                     if (done) {
