@@ -30,17 +30,17 @@ PEAK_BF16_TFLOPS = 2500.0
 # Reported as roofline.traffic when the dominant kernel of the benchmarked workload is listed.
 MEASURED_TRAFFIC_MB = {
     ("catch_4096", "rollout"): 173.3,
-    ("catch_4096", "gemm_tn_nt"): 494.8,       # dW 239.0 + dX 255.8, measured as separate launches
+    ("catch_4096", "gemm_tn_nt"): 493.5,
     ("catch_4096", "first_layer_grad"): 97.9,
-    ("catch_4096", "adam_reduce"): 84.6,
-    ("maze_16384", "rollout"): 1740.3,
+    ("catch_4096", "adam_reduce"): 84.5,
+    ("maze_16384", "rollout"): 1737.0,
     ("maze_16384", "gemm_nt_mask"): 1887.5,      # mean of the two launches (2155.9 with the row-major copy, 1619.0 without)
-    ("maze_16384", "gemm_tn"): 1174.3,
+    ("maze_16384", "gemm_tn"): 1176.3,
     ("maze_16384", "gemm_tn_agent"): 606.2,
     ("maze_16384", "gemm_tn_walls"): 68.2,
     ("maze_16384", "head_backward"): 1687.0,
     ("maze_16384", "time_sum"): 570.4,
-    ("maze_16384", "adam_reduce"): 268.7,
+    ("maze_16384", "adam_reduce"): 273.8,
 }
 
 
