@@ -13,6 +13,11 @@
 //                    registers (eight wavefronts x 128 x 64); X and dY stream through
 //                    LDS 32 samples at a time, double buffered; one partial per unit
 //
+// For the top hidden layer both kernels can form dY on the way in from the layer's
+// forward activations and the head gradient (HeadFuse), and the dW kernel then also
+// sums the head matrix's gradient; the two products of one layer share a launch
+// (gemm_tn_nt_res256).
+//
 // Eight wavefronts per workgroup, two per SIMD: while one waits at the barrier
 // or for LDS the other feeds the matrix core.  Loads that prefetch past the end
 // re-read the last tile instead of branching, so the wait counters the compiler

@@ -1,13 +1,16 @@
 // The update on a stored unroll (paper section 3.1: the parameter update that
 // follows the T interactions and reuses the policy's forward pass):
 //   returns_scan          reverse scan over t of the lambda-return recursion
+//   vtrace_ratio / _scan  off-policy targets for an unroll acted by older parameters (decoupled steps)
 //   head_grad             actor-critic loss terms and the gradient w.r.t. head outputs
 //   head_backward(_mfma)  gradient of the head matrix, and of the last hidden layer
 //   first_layer_grad*     gradient of the first layer from the compact state (Catch, Pendulum)
 //   learn_one_layer       the whole backward pass of a one-hidden-layer net
-//   adam_reduce(_flat)    fixed-order sum of split-K partials fused with Adam
+//   adam_reduce(_narrow, _flat)  fixed-order sum of split-K partials fused with Adam
 // Hidden-layer GEMMs live in gemm.hip (vector ALU), gemm_mfma.hip (tiled) and
-// gemm_resident.hip (persistent, 256-wide layers); the bf16 update in learn_bf16.hip.
+// gemm_resident.hip (persistent, 256-wide layers, which also take over the head
+// pass of a 256-wide top layer); the bf16 update in learn_bf16.hip; the reverse
+// sweep of the pathwise policy gradient in pathwise.hip.
 // No floating-point atomics anywhere: every reduction has a fixed order, so runs
 // are reproducible bit for bit.
 #include "internal.h"

@@ -13,6 +13,11 @@
 // for bit and independent of the tiling.  One-hot observations (Catch, Maze)
 // turn the first layer into a gather-sum of weight rows in ascending row
 // order: fma(0,w,acc) = acc and fma(1,w,acc) = acc + w, the same bits.
+//
+// Kernels: rollout_kernel (weights streamed, vector ALU or matrix cores),
+// rollout_resident_kernel (two-layer nets up to 256 wide, W2 in registers),
+// rollout_lane_kernel (one hidden layer: one lane per env).  Each has a REPLAY
+// form, the learner's forward pass over a stored unroll for decoupled steps.
 #include "internal.h"
 
 namespace ank {
