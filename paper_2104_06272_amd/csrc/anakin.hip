@@ -159,6 +159,7 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         const int s = pick_divisor_splits(M, 64, 256);
         if (s > 0) splits[0] = s;
     }
+    if (const int s = first_fused_splits(ns, ed.kind, M)) splits[0] = s;                           // first layer folded into the dX product of the second
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
     const bool bfp = rollout_bf16_ok(ns, ed, B);

@@ -25,9 +25,26 @@ struct HeadFuse {
     float* head_partial;  // dW product only: [splits][N*NH + NH] partial sums of the head matrix and bias gradients
 };
 
+// pendulum first layer folded into the dX product that forms dZ_1: dW_1[c][i] = sum_m o_c(m) dZ_1[m][i] for the three
+// observation features o = (cos th, sin th, thd) of sample m, db_1[i] = sum_m dZ_1[m][i], one partial per workgroup
+struct FirstFuse {
+    const float* f0; const float* f1;   // [M] stored angle and angular velocity (null: not folded)
+    float* partial;                     // [workgroups][3*K + K]
+};
+// workgroups (along the samples) the resident dX kernel is launched with
+inline int gemm_nt_res_blocks(int M, int* rows_per_block_out = nullptr)
+{
+    const int tiles = (M + 31) / 32;
+    const int blocks = tiles < 256 ? tiles : 256;
+    const int rows_per_block = ((tiles + blocks - 1) / blocks) * 32;
+    if (rows_per_block_out) *rows_per_block_out = rows_per_block;
+    return (M + rows_per_block - 1) / rows_per_block;
+}
+
 struct GemmNtArgs {
     int M, K, N, bf16;
     HeadFuse hf;
+    FirstFuse ff;
     const float* dy;      // [M][N]
     const float* w;       // [K][N]
     const float* x;       // [M][K] forward activations (relu mask)

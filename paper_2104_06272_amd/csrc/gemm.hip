@@ -186,7 +186,10 @@ hipError_t launch_backward(anakin* h)
         e = launch_head_backward(h);
         if (e != hipSuccess) return e;
     }
+    // pendulum: the first layer's gradient is summed in the epilogue of the dX product that forms dZ_1
+    const bool first_fused = !(h->mode & ANAKIN_MODE_VALU_GEMM) && first_fused_splits(n, h->env.kind, M) == h->splits[0] && h->splits[0] > 0;
     for (int l = n.L - 1; l >= 0; --l) {
+        if (l == 0 && first_fused) continue;
         // one-hot boards (Catch) and the 3-feature pendulum need no GEMM for the first layer
         if (l == 0 && h->env.kind != ENV_MAZE && !(h->mode & ANAKIN_MODE_VALU_GEMM) && (size_t)WG * n.dims[0] * 4 <= 96 * 1024) {
             e = launch_first_layer_grad(h);
@@ -217,6 +220,11 @@ hipError_t launch_backward(anakin* h)
             g.bf16 = n.bf16;
             g.hf = HeadFuse{}; g.hf.hl = nullptr;
             if (l == n.L - 1 && hf.hl) g.hf = hf;
+            g.ff = FirstFuse{nullptr, nullptr, nullptr};
+            if (l == 1 && first_fused && gemm_nt_res_ok(g)) {
+                g.ff.f0 = at<const float>(h, L.tr_f0); g.ff.f1 = at<const float>(h, L.tr_f1);
+                g.ff.partial = at<float>(h, L.part[0]);
+            }
             if (mfma && gemm_tn_res_ok(t) && gemm_nt_res_ok(g)) {
                 // the layer's two resident products share one launch
                 ProfScope prof(h, "gemm_tn_nt");

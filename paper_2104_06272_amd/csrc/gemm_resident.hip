@@ -25,6 +25,7 @@
 //
 // Operand layout of v_mfma_f32_32x32x2_f32: see gemm_mfma.hip.
 #include "gemm.h"
+#include "detmath.cuh"
 
 namespace ank {
 
@@ -63,12 +64,13 @@ __device__ __forceinline__ f4v_r head_dy(const HeadCols& hc, f4v_r hv, f4v_r d)
     return o;
 }
 
-template <bool HEADS>
+template <bool HEADS, bool FIRST>
 __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const int rows_per_block, const int bx, const int by)
 {
     extern __shared__ float4 smem_r[];
     float* As0 = reinterpret_cast<float*>(smem_r);
     float* As1 = As0 + RT * NTR_LD;
+    float* obsS = As1 + RT * NTR_LD;                                 // FIRST: [2][RT][4] features of the stage's samples
     constexpr int N = 256;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
     const int i = by * 256 + wave * 32 + l32;                       // this lane's output column
@@ -102,8 +104,21 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
         for (int q = 0; q < 4; ++q)
             *reinterpret_cast<f4v_r*>(buf + (8 * q + lrow) * NTR_LD + lc) = HEADS ? head_dy(hc, st[q], dh[HEADS ? q : 0]) : st[q];
     };
+    // FIRST: the first RT threads work out (cos, sin, thd, 1) of one sample of a stage each; the epilogue of that
+    // stage multiplies them into this lane's column of dZ_1
+    float gw0 = 0.0f, gw1 = 0.0f, gw2 = 0.0f, gb = 0.0f;
+    auto features = [&](int m0, int buf) {
+        if (FIRST && tid < RT) {
+            const int m = m0 + tid < m_end ? m0 + tid : m_clamp;
+            float sn, cs;
+            det_sincos(a.ff.f0[m], sn, cs);
+            f4v_r o = {cs, sn, a.ff.f1[m], 1.0f};
+            *reinterpret_cast<f4v_r*>(obsS + (buf * RT + tid) * 4) = o;
+        }
+    };
     fetch(m_begin);
     store(As0);
+    features(m_begin, 0);
     __syncthreads();
     const uint32_t lane_off = (uint32_t)(4 * kg) * (uint32_t)a.K + (uint32_t)i;
     int t = 0;
@@ -111,6 +126,8 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
         const float* cur = t ? As1 : As0;
         float* nxt = t ? As0 : As1;
         fetch(m0 + RT < m_end ? m0 + RT : m0);                      // the last step re-reads its own rows
+        // the next stage's features: one wavefront's long sine/cosine chain runs under the other wavefronts' MFMAs
+        if (FIRST && m0 + RT < m_end) features(m0 + RT, t ^ 1);
         // rows come in whole groups of eight (M and the rows per workgroup are multiples of 8), so the row
         // part of every address and every bounds check is uniform: scalar base + one 32-bit lane offset
         float xm[16];
@@ -145,10 +162,25 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int mu = m0 + 8 * (r >> 2) + (r & 3);
-            if (mu < m_end) (a.dx + (size_t)mu * a.K)[lane_off] = xm[r] > 0.0f ? acc[r] : 0.0f;
+            const float o = xm[r] > 0.0f ? acc[r] : 0.0f;
+            if (mu < m_end) {
+                (a.dx + (size_t)mu * a.K)[lane_off] = o;
+                if (FIRST) {
+                    const f4v_r f = *reinterpret_cast<const f4v_r*>(obsS + (t * RT + 8 * (r >> 2) + 4 * kg + (r & 3)) * 4);
+                    gw0 = fmaf(f[0], o, gw0); gw1 = fmaf(f[1], o, gw1); gw2 = fmaf(f[2], o, gw2); gb += o;
+                }
+            }
         }
         if (m0 + RT < m_end) store(nxt);
         __syncthreads();
+    }
+    if (FIRST) {
+        // the two halves of a wavefront hold the same column for different rows: lower half first
+        gw0 += __shfl_xor(gw0, 32, 64); gw1 += __shfl_xor(gw1, 32, 64); gw2 += __shfl_xor(gw2, 32, 64); gb += __shfl_xor(gb, 32, 64);
+        if (kg == 0) {
+            float* out = a.ff.partial + (size_t)bx * (4 * (size_t)a.K);
+            out[i] = gw0; out[(size_t)a.K + i] = gw1; out[2 * (size_t)a.K + i] = gw2; out[3 * (size_t)a.K + i] = gb;
+        }
     }
 }
 
@@ -306,10 +338,10 @@ __device__ __forceinline__ void gemm_tn_res256_body(const GemmTnArgs& a, const i
     }
 }
 
-template <bool HEADS>
+template <bool HEADS, bool FIRST>
 __global__ __launch_bounds__(RWG) void gemm_nt_res256(const GemmNtArgs a, const int rows_per_block)
 {
-    gemm_nt_res256_body<HEADS>(a, rows_per_block, (int)blockIdx.x, (int)blockIdx.y);
+    gemm_nt_res256_body<HEADS, FIRST>(a, rows_per_block, (int)blockIdx.x, (int)blockIdx.y);
 }
 template <bool HEADS>
 __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
@@ -320,13 +352,13 @@ __global__ __launch_bounds__(RWG) void gemm_tn_res256(const GemmTnArgs a)
 // dW workgroups come first in the grid; as each retires (its long tail is the write of a 256 KB partial, with the
 // matrix cores idle) a dX workgroup takes its compute unit, so the tail of one product overlaps the start of the
 // other instead of the two kernels running back to back.
-template <bool HEADS>
+template <bool HEADS, bool FIRST>
 __global__ __launch_bounds__(RWG) void gemm_tn_nt_res256(const GemmTnArgs t, const GemmNtArgs n, const int rows_per_block,
                                                          const int tn_blocks, const int nt_bx)
 {
     const int b = (int)blockIdx.x;
     if (b < tn_blocks) gemm_tn_res256_body<HEADS>(t, b);
-    else gemm_nt_res256_body<HEADS>(n, rows_per_block, (b - tn_blocks) % nt_bx, (b - tn_blocks) / nt_bx);
+    else gemm_nt_res256_body<HEADS, FIRST>(n, rows_per_block, (b - tn_blocks) % nt_bx, (b - tn_blocks) / nt_bx);
 }
 
 bool gemm_nt_res_ok(const GemmNtArgs& a) { return a.N == 256 && a.K % 256 == 0 && a.M >= 8 && a.M % 8 == 0; }
@@ -334,14 +366,14 @@ bool gemm_tn_res_ok(const GemmTnArgs& a) { return a.K == 256 && a.N == 256 && !a
 
 hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s)
 {
-    const int tiles = (a.M + RT - 1) / RT;
-    const int blocks = tiles < 256 ? tiles : 256;
-    const int rows_per_block = ((tiles + blocks - 1) / blocks) * RT;
-    const size_t lds = (size_t)2 * RT * NTR_LD * sizeof(float);
-    auto kern = a.hf.hl ? gemm_nt_res256<true> : gemm_nt_res256<false>;
+    int rows_per_block;
+    const int bx = gemm_nt_res_blocks(a.M, &rows_per_block);
+    const size_t lds = ((size_t)2 * RT * NTR_LD + (a.ff.f0 ? 2 * RT * 4 : 0)) * sizeof(float);
+    auto kern = a.ff.f0 ? (a.hf.hl ? gemm_nt_res256<true, true> : gemm_nt_res256<false, true>)
+                        : (a.hf.hl ? gemm_nt_res256<true, false> : gemm_nt_res256<false, false>);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((a.M + rows_per_block - 1) / rows_per_block, a.K / 256), dim3(RWG), lds, s, a, rows_per_block);
+    hipLaunchKernelGGL(kern, dim3(bx, a.K / 256), dim3(RWG), lds, s, a, rows_per_block);
     return hipGetLastError();
 }
 
@@ -357,13 +389,12 @@ hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s)
 
 hipError_t launch_gemm_tn_nt_res(const GemmTnArgs& t, const GemmNtArgs& n, hipStream_t s)
 {
-    const int tiles = (n.M + RT - 1) / RT;
-    const int blocks = tiles < 256 ? tiles : 256;
-    const int rows_per_block = ((tiles + blocks - 1) / blocks) * RT;
-    const int nt_bx = (n.M + rows_per_block - 1) / rows_per_block, nt_by = n.K / 256;
-    const size_t lds_nt = (size_t)2 * RT * NTR_LD * sizeof(float), lds_tn = (size_t)4 * RT * 256 * sizeof(float);
+    int rows_per_block;
+    const int nt_bx = gemm_nt_res_blocks(n.M, &rows_per_block), nt_by = n.K / 256;
+    const size_t lds_nt = ((size_t)2 * RT * NTR_LD + (n.ff.f0 ? 2 * RT * 4 : 0)) * sizeof(float), lds_tn = (size_t)4 * RT * 256 * sizeof(float);
     const size_t lds = lds_nt > lds_tn ? lds_nt : lds_tn;
-    auto kern = t.hf.hl ? gemm_tn_nt_res256<true> : gemm_tn_nt_res256<false>;
+    auto kern = n.ff.f0 ? (t.hf.hl ? gemm_tn_nt_res256<true, true> : gemm_tn_nt_res256<false, true>)
+                        : (t.hf.hl ? gemm_tn_nt_res256<true, false> : gemm_tn_nt_res256<false, false>);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(t.splits + nt_bx * nt_by), dim3(RWG), lds, s, t, n, rows_per_block, t.splits, nt_bx);

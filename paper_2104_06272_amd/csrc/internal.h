@@ -204,6 +204,15 @@ inline bool bf16_mfma(const anakin* h) { return h->bf16_path && !(h->mode & (ANA
 // the head backward pass can ride in the loaders of the top hidden layer's two resident products: a 256 -> 256 top
 // layer, at most four head outputs, sample count in whole 32-row stages
 inline bool heads_fused_shape(const NetShape& n, int M) { return !n.bf16 && n.L >= 2 && n.NH <= 4 && n.dims[n.L] == 256 && n.dims[n.L - 1] == 256 && M % 32 == 0; }
+// the pendulum's first-layer gradient can ride in the epilogue of the resident dX product that forms dZ_1 (second
+// layer n x 256 with n a multiple of 256); returns the number of partials that kernel writes (its workgroups along
+// the samples, which must cut the samples evenly so that the chunking also serves the other kernels), else 0
+inline int first_fused_splits(const NetShape& n, int env_kind, int M)
+{
+    if (env_kind != ENV_PENDULUM || n.bf16 || n.L < 2 || n.dims[0] != 3 || n.dims[1] % 256 != 0 || n.dims[2] != 256 || M % 32 != 0) return 0;
+    const int tiles = M / 32, blocks = tiles < 256 ? tiles : 256;
+    return tiles % blocks == 0 ? blocks : 0;
+}
 int rollout_pick_tile(const NetShape& net, int B);
 int rollout_pick_tile_mfma(const NetShape& net, int B);
 int rollout_resident_tile(const NetShape& net, int B);
