@@ -58,6 +58,10 @@ LOCKSTEP_CASES = {
     # 512-wide last layer: two column blocks in the head pass; 512-wide first layer of the pendulum kernel
     "catch_256x512": (variant("catch_4096", hidden=[256, 512], B=64, T=10), 5, 2, TOL_F32),
     "pendulum_512x256": (variant("pendulum_8192", hidden=[512, 256], B=64, T=12, max_steps=9), 6, 2, TOL_F32),
+    # pendulum first layer summed inside the dX product of a middle layer, two 32-sample stages per workgroup;
+    # and a sample count (272 tiles of 32) that 256 dX workgroups do not cut evenly, which keeps the separate kernel
+    "pendulum_256x256x256_B512": (variant("pendulum_8192", hidden=[256, 256, 256], B=512, T=32), 11, 1, TOL_F32),
+    "pendulum_256x256_B272": (variant("pendulum_8192", B=272, T=32), 12, 1, TOL_F32),
     # degenerate shapes: a one-step unroll (the return is reward + bootstrap only), a single tile of envs,
     # an episode end at every step (max_steps = 1: every transition is terminal, nothing bootstraps)
     "catch_T1": (variant("catch_small", B=64, T=1), 7, 3, TOL_F32),
