@@ -26,14 +26,21 @@ PEAK_FP32_TFLOPS = 157.3      # fp32 vector (packed) = fp32 matrix-core peak
 PEAK_BF16_TFLOPS = 2500.0
 
 # HBM bytes per launch (MB) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy-kernel calibration; source: profiles/catch_4096_hbm_traffic.md and profiles/maze_16384_hbm_traffic.md.
+# copy-kernel calibration; source: profiles/<workload>_hbm_traffic.md.
 # Reported as roofline.traffic when the dominant kernel of the benchmarked workload is listed.
 MEASURED_TRAFFIC_MB = {
     ("catch_4096", "rollout"): 173.3,
     ("catch_4096", "gemm_tn_nt"): 493.5,
     ("catch_4096", "first_layer_grad"): 97.9,
     ("catch_4096", "adam_reduce"): 84.5,
-    ("maze_16384", "rollout"): 1737.0,
+    ("pendulum_8192", "rollout"): 553.4,
+    ("pendulum_8192", "gemm_tn_nt"): 1160.0,
+    ("pendulum_8192", "adam_reduce"): 71.6,
+    ("catch_262144", "rollout"): 134.4,
+    ("catch_262144", "returns_scan"): 72.4,
+    ("catch_262144", "head_grad"): 193.5,
+    ("catch_262144", "learn_one_layer"): 91.2,
+    ("maze_16384", "rollout"): 1737.5,
     ("maze_16384", "gemm_nt_mask"): 1887.5,      # mean of the two launches (2155.9 with the row-major copy, 1619.0 without)
     ("maze_16384", "gemm_tn"): 1176.3,
     ("maze_16384", "gemm_tn_agent"): 606.2,

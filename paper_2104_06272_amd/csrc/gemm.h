@@ -27,6 +27,7 @@ struct HeadFuse {
 
 // pendulum first layer folded into the dX product that forms dZ_1: dW_1[c][i] = sum_m o_c(m) dZ_1[m][i] for the three
 // observation features o = (cos th, sin th, thd) of sample m, db_1[i] = sum_m dZ_1[m][i], one partial per workgroup
+// (dZ_1 itself is then not written: nothing else reads it)
 struct FirstFuse {
     const float* f0; const float* f1;   // [M] stored angle and angular velocity (null: not folded)
     float* partial;                     // [workgroups][3*K + K]

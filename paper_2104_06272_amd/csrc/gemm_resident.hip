@@ -164,7 +164,7 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
             const int mu = m0 + 8 * (r >> 2) + (r & 3);
             const float o = xm[r] > 0.0f ? acc[r] : 0.0f;
             if (mu < m_end) {
-                (a.dx + (size_t)mu * a.K)[lane_off] = o;
+                if (!FIRST) (a.dx + (size_t)mu * a.K)[lane_off] = o;   // FIRST: dZ_1 has no other reader and stays on chip
                 if (FIRST) {
                     const f4v_r f = *reinterpret_cast<const f4v_r*>(obsS + (t * RT + 8 * (r >> 2) + 4 * kg + (r & 3)) * 4);
                     gw0 = fmaf(f[0], o, gw0); gw1 = fmaf(f[1], o, gw1); gw2 = fmaf(f[2], o, gw2); gb += o;
