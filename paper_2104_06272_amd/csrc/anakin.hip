@@ -149,8 +149,12 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     if (!ns.bf16)
         for (int l = 1; l < ns.L; ++l)
             if (ns.dims[l] == 256 && ns.dims[l + 1] == 256) {
-                // persistent 256 x 256 dW kernel: one chunk per compute unit, 32-sample steps
-                const int s = pick_divisor_splits(M, 32, 256);
+                // persistent 256 x 256 dW kernel, 32-sample steps.  It shares its launch with the dX kernel of the
+                // layer, whose workgroups take the compute units the dW ones leave free, so the chunk count sets no
+                // occupancy, only the balance of the two and the partial sums (256 KB per chunk, written here, read
+                // by Adam).  Short unrolls: one chunk per two compute units, half the partial traffic; long ones: one
+                // per unit, because the dX workgroups would otherwise finish in two uneven rounds.
+                const int s = pick_divisor_splits(M, 32, M <= 131072 ? 128 : 256);
                 if (s > 0) splits[l] = s;
             }
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
