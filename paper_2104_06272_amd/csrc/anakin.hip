@@ -150,11 +150,11 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         for (int l = 1; l < ns.L; ++l)
             if (ns.dims[l] == 256 && ns.dims[l + 1] == 256) {
                 // persistent 256 x 256 dW kernel, 32-sample steps.  It shares its launch with the dX kernel of the
-                // layer, whose workgroups take the compute units the dW ones leave free, so the chunk count sets no
-                // occupancy, only the balance of the two and the partial sums (256 KB per chunk, written here, read
-                // by Adam).  Short unrolls: one chunk per two compute units, half the partial traffic; long ones: one
-                // per unit, because the dX workgroups would otherwise finish in two uneven rounds.
-                const int s = pick_divisor_splits(M, 32, M <= 131072 ? 128 : 256);
+                // layer and the two kinds of workgroup run side by side, one per compute unit: half the units take
+                // a dW chunk each, the other half a dX row range each (their costs per sample are within 10 %).
+                // Compared with one chunk per unit followed by one row range per unit this halves the partial sums
+                // (256 KB per chunk, written here, read by Adam) and every unit pays one prologue instead of two.
+                const int s = pick_divisor_splits(M, 32, 128);
                 if (s > 0) splits[l] = s;
             }
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
@@ -163,7 +163,7 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         const int s = pick_divisor_splits(M, 64, 256);
         if (s > 0) splits[0] = s;
     }
-    if (const int s = first_fused_splits(ns, ed.kind, M)) splits[0] = s;                           // first layer folded into the dX product of the second
+    if (const int s = first_fused_splits(ns, ed.kind, M, splits[1])) splits[0] = s;                           // first layer folded into the dX product of the second
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
     const bool bfp = rollout_bf16_ok(ns, ed, B);

@@ -32,15 +32,18 @@ struct FirstFuse {
     const float* f0; const float* f1;   // [M] stored angle and angular velocity (null: not folded)
     float* partial;                     // [workgroups][3*K + K]
 };
-// workgroups (along the samples) the resident dX kernel is launched with
-inline int gemm_nt_res_blocks(int M, int* rows_per_block_out = nullptr)
+// workgroups (along the samples) the resident dX kernel is launched with: at most `cap`, whole 32-sample stages each
+inline int gemm_nt_res_blocks(int M, int cap, int* rows_per_block_out = nullptr)
 {
     const int tiles = (M + 31) / 32;
-    const int blocks = tiles < 256 ? tiles : 256;
+    const int blocks = tiles < cap ? tiles : cap;
     const int rows_per_block = ((tiles + blocks - 1) / blocks) * 32;
     if (rows_per_block_out) *rows_per_block_out = rows_per_block;
     return (M + rows_per_block - 1) / rows_per_block;
 }
+// In a launch shared with the dW kernel the two kinds of workgroup run side by side, one per compute unit: the dX
+// kernel gets the units the dW chunks leave free.
+inline int gemm_nt_res_cap(int tn_splits) { return tn_splits > 0 && tn_splits < 256 ? 256 - tn_splits : 256; }
 
 struct GemmNtArgs {
     int M, K, N, bf16;

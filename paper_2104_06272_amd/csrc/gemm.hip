@@ -187,7 +187,8 @@ hipError_t launch_backward(anakin* h)
         if (e != hipSuccess) return e;
     }
     // pendulum: the first layer's gradient is summed in the epilogue of the dX product that forms dZ_1
-    const bool first_fused = !(h->mode & ANAKIN_MODE_VALU_GEMM) && first_fused_splits(n, h->env.kind, M) == h->splits[0] && h->splits[0] > 0;
+    const bool first_shape = !(h->mode & ANAKIN_MODE_VALU_GEMM) && first_fused_splits(n, h->env.kind, M, h->splits[1]) > 0;
+    bool first_fused = false;
     for (int l = n.L - 1; l >= 0; --l) {
         if (l == 0 && first_fused) continue;
         // one-hot boards (Catch) and the 3-feature pendulum need no GEMM for the first layer
@@ -221,11 +222,18 @@ hipError_t launch_backward(anakin* h)
             g.hf = HeadFuse{}; g.hf.hl = nullptr;
             if (l == n.L - 1 && hf.hl) g.hf = hf;
             g.ff = FirstFuse{nullptr, nullptr, nullptr};
-            if (l == 1 && first_fused && gemm_nt_res_ok(g)) {
-                g.ff.f0 = at<const float>(h, L.tr_f0); g.ff.f1 = at<const float>(h, L.tr_f1);
-                g.ff.partial = at<float>(h, L.part[0]);
+            const bool merged = mfma && gemm_tn_res_ok(t) && gemm_nt_res_ok(g);
+            if (l == 1 && first_shape && gemm_nt_res_ok(g)) {
+                // the kernel writes one partial per workgroup along the samples: that count has to be the planned one
+                int rpb;
+                const int bx = gemm_nt_res_blocks(M, merged ? gemm_nt_res_cap(t.splits) : 256, &rpb);
+                if (bx == h->splits[0] && (long long)bx * rpb == M) {
+                    g.ff.f0 = at<const float>(h, L.tr_f0); g.ff.f1 = at<const float>(h, L.tr_f1);
+                    g.ff.partial = at<float>(h, L.part[0]);
+                    first_fused = true;
+                }
             }
-            if (mfma && gemm_tn_res_ok(t) && gemm_nt_res_ok(g)) {
+            if (merged) {
                 // the layer's two resident products share one launch
                 ProfScope prof(h, "gemm_tn_nt");
                 e = launch_gemm_tn_nt_res(t, g, h->stream);

@@ -367,7 +367,7 @@ bool gemm_tn_res_ok(const GemmTnArgs& a) { return a.K == 256 && a.N == 256 && !a
 hipError_t launch_gemm_nt_res(const GemmNtArgs& a, hipStream_t s)
 {
     int rows_per_block;
-    const int bx = gemm_nt_res_blocks(a.M, &rows_per_block);
+    const int bx = gemm_nt_res_blocks(a.M, 256, &rows_per_block);
     const size_t lds = ((size_t)2 * RT * NTR_LD + (a.ff.f0 ? 2 * RT * 4 : 0)) * sizeof(float);
     auto kern = a.ff.f0 ? (a.hf.hl ? gemm_nt_res256<true, true> : gemm_nt_res256<false, true>)
                         : (a.hf.hl ? gemm_nt_res256<true, false> : gemm_nt_res256<false, false>);
@@ -390,7 +390,7 @@ hipError_t launch_gemm_tn_res(const GemmTnArgs& a, hipStream_t s)
 hipError_t launch_gemm_tn_nt_res(const GemmTnArgs& t, const GemmNtArgs& n, hipStream_t s)
 {
     int rows_per_block;
-    const int nt_bx = gemm_nt_res_blocks(n.M, &rows_per_block), nt_by = n.K / 256;
+    const int nt_bx = gemm_nt_res_blocks(n.M, gemm_nt_res_cap(t.splits), &rows_per_block), nt_by = n.K / 256;
     const size_t lds_nt = ((size_t)2 * RT * NTR_LD + (n.ff.f0 ? 2 * RT * 4 : 0)) * sizeof(float), lds_tn = (size_t)4 * RT * 256 * sizeof(float);
     const size_t lds = lds_nt > lds_tn ? lds_nt : lds_tn;
     auto kern = n.ff.f0 ? (t.hf.hl ? gemm_tn_nt_res256<true, true> : gemm_tn_nt_res256<false, true>)

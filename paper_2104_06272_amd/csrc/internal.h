@@ -207,10 +207,12 @@ inline bool heads_fused_shape(const NetShape& n, int M) { return !n.bf16 && n.L 
 // the pendulum's first-layer gradient can ride in the epilogue of the resident dX product that forms dZ_1 (second
 // layer n x 256 with n a multiple of 256); returns the number of partials that kernel writes (its workgroups along
 // the samples, which must cut the samples evenly so that the chunking also serves the other kernels), else 0
-inline int first_fused_splits(const NetShape& n, int env_kind, int M)
+inline int first_fused_splits(const NetShape& n, int env_kind, int M, int tn_splits)
 {
     if (env_kind != ENV_PENDULUM || n.bf16 || n.L < 2 || n.dims[0] != 3 || n.dims[1] % 256 != 0 || n.dims[2] != 256 || M % 32 != 0) return 0;
-    const int tiles = M / 32, blocks = tiles < 256 ? tiles : 256;
+    // a 256 -> 256 second layer shares its launch with the dW kernel, which then leaves it only part of the compute units
+    const int cap = n.dims[1] == 256 ? (tn_splits > 0 && tn_splits < 256 ? 256 - tn_splits : 256) : 256;
+    const int tiles = M / 32, blocks = tiles < cap ? tiles : cap;
     return tiles % blocks == 0 ? blocks : 0;
 }
 int rollout_pick_tile(const NetShape& net, int B);
