@@ -30,12 +30,12 @@ PEAK_BF16_TFLOPS = 2500.0
 # Reported as roofline.traffic when the dominant kernel of the benchmarked workload is listed.
 MEASURED_TRAFFIC_MB = {
     ("catch_4096", "rollout"): 173.3,
-    ("catch_4096", "gemm_tn_nt"): 493.5,
+    ("catch_4096", "gemm_tn_nt"): 353.8,
     ("catch_4096", "first_layer_grad"): 97.9,
-    ("catch_4096", "adam_reduce"): 84.5,
+    ("catch_4096", "adam_reduce"): 50.1,
     ("pendulum_8192", "rollout"): 553.4,
-    ("pendulum_8192", "gemm_tn_nt"): 1160.0,
-    ("pendulum_8192", "adam_reduce"): 71.6,
+    ("pendulum_8192", "gemm_tn_nt"): 895.4,
+    ("pendulum_8192", "adam_reduce"): 36.8,
     ("catch_262144", "rollout"): 134.4,
     ("catch_262144", "returns_scan"): 72.4,
     ("catch_262144", "head_grad"): 193.5,

@@ -3,7 +3,7 @@
 // of the update).  With M = B*T samples and 256 x 256 weights the tiled
 // kernels in gemm_mfma.hip lose time to tile-count quantisation, to a prologue
 // and an epilogue per 128 x 128 tile and to re-reading operands per tile.
-// Here every compute unit takes M/256 consecutive samples and keeps, for the
+// Here a workgroup takes a range of consecutive samples and keeps, for the
 // whole launch, the operand that does not depend on the sample in registers:
 //
 //   gemm_nt_res256   dX = (dY W^T) masked: W lives in registers (wavefront w holds
@@ -11,12 +11,15 @@
 //                    through LDS 32 rows at a time, double buffered
 //   gemm_tn_res256   dW partial = X^T dY: the whole 256 x 256 accumulator lives in
 //                    registers (eight wavefronts x 128 x 64); X and dY stream through
-//                    LDS 32 samples at a time, double buffered; one partial per unit
+//                    LDS 32 samples at a time, double buffered; one partial per workgroup
 //
 // For the top hidden layer both kernels can form dY on the way in from the layer's
 // forward activations and the head gradient (HeadFuse), and the dW kernel then also
-// sums the head matrix's gradient; the two products of one layer share a launch
-// (gemm_tn_nt_res256).
+// sums the head matrix's gradient; the dX kernel of the pendulum's second layer also
+// sums the first layer's gradient in its epilogue (FirstFuse).  The two products of
+// one layer share a launch (gemm_tn_nt_res256) and run side by side: half the compute
+// units take one dW chunk each, the other half one dX row range each, so every unit
+// pays one prologue (dX: reading W) or one tail (dW: writing its partial), not both.
 //
 // Eight wavefronts per workgroup, two per SIMD: while one waits at the barrier
 // or for LDS the other feeds the matrix core.  Loads that prefetch past the end
