@@ -155,7 +155,9 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
                 // Compared with one chunk per unit followed by one row range per unit this halves the partial sums
                 // (256 KB per chunk, written here, read by Adam) and every unit pays one prologue instead of two.
                 const int s = pick_divisor_splits(M, 32, 128);
-                if (s > 0) splits[l] = s;
+                // a sample count without a usable divisor (few, long chunks) stays with the tiled kernels
+                const int tiles32 = M / 32;
+                if (s > 0 && s >= (tiles32 < 64 ? tiles32 : 64)) splits[l] = s;
             }
     if (ed.kind != ENV_MAZE) splits[0] = pick_splits(M, 2 * ((ns.dims[1] + WG - 1) / WG), 512);   // scatter kernel: more, smaller chunks
     if (ed.kind == ENV_CATCH && ns.dims[0] < 64 && !ns.bf16) {

@@ -62,6 +62,9 @@ LOCKSTEP_CASES = {
     # and a sample count (272 tiles of 32) that 256 dX workgroups do not cut evenly, which keeps the separate kernel
     "pendulum_256x256x256_B512": (variant("pendulum_8192", hidden=[256, 256, 256], B=512, T=32), 11, 1, TOL_F32),
     "pendulum_256x256_B272": (variant("pendulum_8192", B=272, T=32), 12, 1, TOL_F32),
+    # 143 = 11 x 13 stages of 32 samples: no chunk count near the number of compute units divides them, so the
+    # 256 -> 256 layer's dW product stays with the tiled kernel while its dX product is the resident one
+    "catch_256x256_B208_T22": (variant("catch_4096", B=208, T=22), 13, 1, TOL_F32),
     # degenerate shapes: a one-step unroll (the return is reward + bootstrap only), a single tile of envs,
     # an episode end at every step (max_steps = 1: every transition is terminal, nothing bootstraps)
     "catch_T1": (variant("catch_small", B=64, T=1), 7, 3, TOL_F32),
