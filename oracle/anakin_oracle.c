@@ -805,7 +805,7 @@ static void forward64(const orc_t* h, const double* wq, size_t tb, double act[5]
     float xf[1024];
     int b = (int)(tb % (size_t)B);
     render_obs(h, b, h->tr_si + tb * 4, h->tr_sf + tb * 2, xf);
-    for (int k = 0; k < h->D; ++k) act[0][k] = (double)xf[k];
+    for (int k = 0; k < h->D; ++k) act[0][k] = qround(h, (double)xf[k]);   /* R-20: every layer input, the observation too */
     for (int l = 0; l < L; ++l) {
         int K = h->dims[l], N = h->dims[l + 1];
         const double* W = wq + h->w_off[l];

@@ -973,3 +973,156 @@ def test_catch_learning_sanity(orc):
         if i >= 140: last += r / 10
         o.learn()
     assert last > first + 0.3
+
+
+# ------------------------------------------- bf16 nets: the learn-time forward pass and its gradient
+def _bf(a):
+    """binary32 -> bfloat16 -> binary64 through the library's cast (round to nearest even)"""
+    import torch
+    a32 = np.ascontiguousarray(np.asarray(a, np.float64).astype(np.float32))
+    return torch.from_numpy(a32).to(torch.bfloat16).to(torch.float32).numpy().astype(np.float64)
+
+
+def _obs_rows(o, kind, rows=4, cols=3, t_max=None):
+    """observations rebuilt by the test from the stored states, [(t_max)*B][D] in binary64"""
+    T1, B = (o.T + 1 if t_max is None else t_max), o.B
+    obs = np.zeros((T1 * B, o.D))
+    for t in range(T1):
+        for b in range(B):
+            si, sf = o.tr_state_i[t, b], o.tr_state_f[t, b]
+            if kind == "catch":
+                x = np.zeros((rows, cols)); x[si[1], si[0]] = 1; x[rows - 1, si[2]] = 1
+            elif kind == "pendulum":
+                x = np.array([math.cos(sf[0]), math.sin(sf[0]), sf[1]])
+            else:
+                n = rows * cols
+                wb = np.unpackbits(o.walls[b].view(np.uint8), bitorder="little")[:n].astype(float)
+                ag = np.zeros(n); ag[si[0]] = 1
+                gl = np.zeros(n); gl[n - 1] = 1
+                x = np.concatenate([wb, ag, gl])
+            obs[t * B + b] = np.ravel(x)
+    return obs
+
+
+def _np_forward_bf16(o, theta, obs):
+    """The bf16 forward pass with explicit casts at every rounding point: layer inputs (the observation
+    included) and weight matrices rounded to bfloat16, sums in binary64, bias and ReLU, the result rounded to
+    binary32 and then to bfloat16; the head outputs are left unrounded."""
+    Ws, bs, Wh, bh = _unpack(o, np.asarray(theta, np.float64))
+    h = _bf(obs)
+    acts = []
+    for Wm, bv in zip(Ws, bs):
+        h = _bf(np.maximum(h @ _bf(Wm) + bv, 0))
+        acts.append(h)
+    return h @ _bf(Wh) + bh, acts
+
+
+@pytest.mark.parametrize("kind", ["pendulum", "maze", "catch"])
+def test_bf16_learn_forward_rounding_points(orc, kind):
+    """The binary64 forward pass the bf16 update differentiates (weights, observation and hidden activations
+    rounded to bfloat16, heads not) against (a) a numpy forward with the library's bfloat16 casts written out
+    here and (b) the acting-time binary32 forward, which has its own pin."""
+    cfg = tiny(kind, hidden=(16, 8), B=5, T=6, rows=4, cols=4 if kind == "maze" else 3, max_steps=4, p_wall=0.1, dtype="bf16")
+    o = orc.Oracle(cfg, seed=21)
+    rng = np.random.default_rng(8)
+    o.theta[:] += rng.standard_normal(o.P).astype(np.float32) * 0.2      # biases off zero and off the bf16 grid
+    assert not np.array_equal(_bf(o.theta), o.theta.astype(np.float64))
+    o.rollout()
+    o.vtrace_targets()                                                    # fills cur_head at the current parameters
+    obs = _obs_rows(o, kind, rows=4, cols=4 if kind == "maze" else 3)
+    if kind == "pendulum":
+        assert not np.array_equal(_bf(obs), obs)                          # the observation itself needs rounding
+    ref, _ = _np_forward_bf16(o, o.theta, obs)
+    got = o.cur_head.reshape(-1, o.NH)
+    # same rounding points, binary64 sums: equal up to the order of the sums, except where that order decides a
+    # bfloat16 tie in a hidden activation (rare)
+    close = np.isclose(got, ref, rtol=1e-9, atol=1e-12).all(1)
+    assert close.mean() > 0.9 and np.allclose(got, ref, rtol=0, atol=2e-2 * np.abs(ref).max())
+    # the acting-time forward differs only by binary32 accumulation
+    act_head = o.tr_head.reshape(-1, o.NH).astype(np.float64)
+    assert np.isclose(got, act_head, rtol=1e-4, atol=1e-5).all(1).mean() > 0.9
+    assert np.allclose(got, act_head, rtol=0, atol=2e-2 * np.abs(ref).max())
+    # and a forward without the rounding points is measurably different (the pin would see a dropped cast)
+    Ws, bs, Wh, bh = _unpack(o, o.theta.astype(np.float64))
+    for drop in ("weights", "heads", "obs", "acts"):
+        h = obs if drop == "obs" else _bf(obs)
+        for Wm, bv in zip(Ws, bs):
+            z = np.maximum(h @ (Wm if drop == "weights" else _bf(Wm)) + bv, 0)
+            h = z if drop == "acts" else _bf(z)
+        alt = h @ (Wh if drop == "heads" else _bf(Wh)) + bh
+        if drop == "obs" and kind != "pendulum":
+            continue                                                      # 0/1 boards are bfloat16 values already
+        assert np.isclose(got, alt, rtol=1e-9, atol=1e-12).all(1).mean() < 0.5, drop
+
+
+def _np_surrogate_frozen(o, wvars, obs_q, deltas, kind):
+    """The objective of a bf16 net as a smooth binary64 function of the *rounded* weights: every rounding of a
+    hidden activation is replaced by the additive offset it had at the point of expansion."""
+    Ws, bs, Wh, bh = _unpack(o, wvars)
+    h = obs_q
+    for Wm, bv, d in zip(Ws, bs, deltas):
+        h = np.maximum(h @ Wm + bv, 0) + d
+    head = h @ Wh + bh
+    A, G = o.adv.reshape(-1), o.ret.reshape(-1)
+    beta, cv = o.cfg["net"]["entropy_coef"], o.cfg["net"]["value_coef"]
+    V = head[:, -1]
+    if kind == "categorical":
+        lg = head[:, :-1]
+        lp = lg - lg.max(1, keepdims=True)
+        lp = lp - np.log(np.exp(lp).sum(1, keepdims=True))
+        H = -(np.exp(lp) * lp).sum(1)
+        lpa = lp[np.arange(lp.shape[0]), o.tr_action.reshape(-1)]
+    else:
+        mu, ls = head[:, 0], np.clip(head[:, 1], -5, 2)
+        z = o.tr_z.reshape(-1).astype(np.float64)
+        lpa = -0.5 * ((z - mu) / np.exp(ls)) ** 2 - ls - 0.5 * math.log(2 * math.pi)
+        H = ls + 0.5 * math.log(2 * math.pi * math.e)
+    return (-A * lpa + cv * (G - V) ** 2 - beta * H).mean()
+
+
+@pytest.mark.parametrize("kind", ["pendulum", "maze"])
+def test_bf16_gradient_vs_finite_differences(orc, kind):
+    """Gradient of a bf16 net (taken with respect to the rounded weights the forward pass uses and applied to the
+    binary32 master weights) against central differences of a binary64 objective written here, with the rounded
+    weights as the variables and every activation rounding frozen as an offset."""
+    cfg = tiny(kind, hidden=(6, 5), B=3, T=5, rows=4, cols=4, max_steps=3, p_wall=0.1, dtype="bf16")
+    o = orc.Oracle(cfg, seed=17)
+    rng = np.random.default_rng(5)
+    o.theta[:] += rng.standard_normal(o.P).astype(np.float32) * 0.3
+    o.rollout()
+    ret, adv = orc.returns(o.tr_reward, o.tr_done, o.tr_value, cfg["net"]["gamma"], cfg["net"]["lambda"])
+    o.ret[:] = ret; o.adv[:] = adv + rng.standard_normal(adv.shape)
+    o.loss_and_grad()
+    obs_q = _bf(_obs_rows(o, kind, rows=4, cols=4, t_max=o.T))
+    # point of expansion: weight matrices rounded, biases as they are
+    Ws, bs, Wh, bh = _unpack(o, o.theta.astype(np.float64))
+    w0 = np.concatenate([np.concatenate([_bf(Wm).ravel(), bv]) for Wm, bv in zip(Ws, bs)] + [_bf(Wh).ravel(), bh])
+    assert w0.size == o.P and not np.array_equal(w0, o.theta.astype(np.float64))
+    Wq, bq, _, _ = _unpack(o, w0)
+    deltas, h = [], obs_q
+    for Wm, bv in zip(Wq, bq):
+        z = np.maximum(h @ Wm + bv, 0)
+        h = _bf(z)
+        deltas.append(h - z)
+    assert max(np.abs(d).max() for d in deltas) > 0                       # some activation really was rounded
+    pol = "categorical" if kind != "pendulum" else "gauss"
+    assert abs(_np_surrogate_frozen(o, w0, obs_q, deltas, pol) - o.loss[0]) < 1e-9 * max(1.0, abs(o.loss[0]))
+    hstep = 1e-5
+    fd = np.zeros(o.P)
+    for i in range(o.P):
+        tp, tm = w0.copy(), w0.copy()
+        tp[i] += hstep; tm[i] -= hstep
+        fd[i] = (_np_surrogate_frozen(o, tp, obs_q, deltas, pol) - _np_surrogate_frozen(o, tm, obs_q, deltas, pol)) / (2 * hstep)
+    g = o.grad.astype(np.float64)
+    assert np.linalg.norm(g) > 1e-3
+    assert np.linalg.norm(g - fd) / np.linalg.norm(fd) < 1e-5
+    assert np.abs(g - fd).max() < 1e-5 * np.abs(fd).max() + 1e-7
+    # the same differences taken at the unrounded weights, or without the frozen offsets, do not reproduce it
+    th = o.theta.astype(np.float64)
+    zero = [np.zeros_like(d) for d in deltas]
+    alt = np.zeros(o.P)
+    for i in range(o.P):
+        tp, tm = th.copy(), th.copy()
+        tp[i] += hstep; tm[i] -= hstep
+        alt[i] = (_np_surrogate_frozen(o, tp, obs_q, zero, pol) - _np_surrogate_frozen(o, tm, obs_q, zero, pol)) / (2 * hstep)
+    assert np.linalg.norm(g - alt) / np.linalg.norm(alt) > 1e-4
