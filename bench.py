@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Throughput of the Anakin actor-learner step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload catch_4096]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload maze_16384]
 
 A step is one pass of the whole hot path (unroll of T interactions for B envs,
 then one update) through the C ABI.  Prints ONE JSON line: env-steps/s over K
-steps, the roofline of the dominant kernel (per-kernel durations from HIP
-events recorded on the launch stream in a second, instrumented pass of the
-same K steps), and the CPU oracle timed on a bounded sample of the workload.
+steps of the named workload (default: the largest one, the bf16 maze), the
+roofline of its dominant kernel (per-kernel durations from HIP events recorded
+on the launch stream in a second, instrumented pass of the same K steps), a
+"workloads" block with the same measurement of all five workloads, and the CPU
+oracle timed on a bounded sample of the named workload.
 """
 import argparse
 import json
@@ -25,30 +27,30 @@ PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3      # fp32 vector (packed) = fp32 matrix-core peak
 PEAK_BF16_TFLOPS = 2500.0
 
-# HBM bytes per launch (MB) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy-kernel calibration; source: profiles/<workload>_hbm_traffic.md.
-# Reported as roofline.traffic when the dominant kernel of the benchmarked workload is listed.
-MEASURED_TRAFFIC_MB = {
-    ("catch_4096", "rollout"): 173.3,
-    ("catch_4096", "gemm_tn_nt"): 353.8,
-    ("catch_4096", "first_layer_grad"): 97.9,
-    ("catch_4096", "adam_reduce"): 50.1,
-    ("pendulum_8192", "rollout"): 553.4,
-    ("pendulum_8192", "gemm_tn_nt"): 895.4,
-    ("pendulum_8192", "adam_reduce"): 36.8,
-    ("catch_262144", "rollout"): 134.4,
-    ("catch_262144", "returns_scan"): 72.4,
-    ("catch_262144", "head_grad"): 193.5,
-    ("catch_262144", "learn_one_layer"): 91.2,
-    ("maze_16384", "rollout"): 1737.5,
-    ("maze_16384", "gemm_nt_mask"): 1887.5,      # mean of the two launches (2155.9 with the row-major copy, 1619.0 without)
-    ("maze_16384", "gemm_tn"): 1176.3,
-    ("maze_16384", "gemm_tn_agent"): 606.2,
-    ("maze_16384", "gemm_tn_walls"): 68.2,
-    ("maze_16384", "head_backward"): 1687.0,
-    ("maze_16384", "time_sum"): 570.4,
-    ("maze_16384", "adam_reduce"): 273.8,
-}
+def measured_traffic(workload):
+    """HBM bytes per launch (MB) of each kernel of a workload, read from profiles/<workload>_hbm_traffic.md: the
+    table under "per bench.py kernel" (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy-kernel
+    calibration; the file names the commands and the commit it was measured at).  Returns ({kernel: MB}, commit)
+    -- empty when the workload has no such file."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
+    out, commit, in_table = {}, None, False
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return out, commit
+    for line in lines:
+        if line.lower().startswith("measured at commit"):
+            commit = line.split()[-1].strip("`. ")
+        if line.startswith("## "):
+            in_table = "per bench.py kernel" in line
+            continue
+        if in_table and line.startswith("| `"):
+            cells = [c.strip() for c in line.strip("|").split("|")]
+            try:
+                out[cells[0].strip("`")] = float(cells[-1])
+            except ValueError:
+                pass
+    return out, commit
 
 
 def kernel_models(cfg, P):
@@ -112,22 +114,117 @@ def kernel_models(cfg, P):
 
 
 def cpu_baseline(cfg, budget_s=20.0):
-    """The oracle as it stands, single-threaded, on a bounded sample: the same network, T and
-    hyper-parameters with B cut so that one full step takes roughly the budget."""
+    """The oracle as it stands, single-threaded and pinned to one core, on a bounded sample: the same network, T and
+    hyper-parameters with B cut so that one full step takes roughly the budget (envs are independent, so the
+    per-env-step rate of a B-slice is the rate of the workload; labelled as scaled when B is cut)."""
     from oracle import oracle as O
-    from paper_2104_06272_amd import workloads as W
-    probe_B = 16
-    c = dict(cfg); c["B"] = probe_B
-    o = O.Oracle(c, seed=0)
-    t0 = time.perf_counter(); o.step(); dt = time.perf_counter() - t0
-    per_env = max(dt / probe_B, 1e-9)
-    B = int(max(16, min(cfg["B"], (budget_s / per_env) // 16 * 16)))
-    c["B"] = B
-    o = O.Oracle(c, seed=0)
-    t0 = time.perf_counter(); o.step(); dt = time.perf_counter() - t0
-    return {"value": B * cfg["T"] / dt, "unit": "env steps/s", "cores": 1, "kind": "oracle",
+    host_cores = os.cpu_count()
+    pinned = None
+    try:
+        allowed = sorted(os.sched_getaffinity(0))
+        os.sched_setaffinity(0, {allowed[-1]})
+        pinned = allowed
+    except (AttributeError, OSError):
+        pass
+    try:
+        probe_B = 16
+        c = dict(cfg); c["B"] = probe_B
+        o = O.Oracle(c, seed=0)
+        t0 = time.perf_counter(); o.step(); dt = time.perf_counter() - t0
+        per_env = max(dt / probe_B, 1e-9)
+        B = int(max(16, min(cfg["B"], (budget_s / per_env) // 16 * 16)))
+        c["B"] = B
+        o = O.Oracle(c, seed=0)
+        t0 = time.perf_counter(); o.step(); dt = time.perf_counter() - t0
+    finally:
+        if pinned is not None:
+            os.sched_setaffinity(0, set(pinned))
+    rate = B * cfg["T"] / dt
+    usable = len(pinned) if pinned is not None else host_cores
+    return {"value": rate, "unit": "env steps/s", "cores": 1, "kind": "oracle",
+            "host_cores": host_cores, "usable_cores": usable,
+            "ideal_all_cores_estimate": rate * usable,
+            "ideal_all_cores_note": "value x usable cores: an ideal-scaling estimate (one oracle process per core over "
+                                    "disjoint env shards), not a measurement",
+            "scaled_from_B_slice": B != cfg["B"],
             "sample": f"1 full step (rollout + update) at B={B} of {cfg['B']} envs, T={cfg['T']}, same network; "
-                      f"{dt:.1f} s single-threaded"}
+                      f"{dt:.1f} s single-threaded, pinned to one core"}
+
+
+def measure(binding, torch, name, cfg, steps, warmup, halves=False, valu_gemm=False):
+    """K timed steps of one workload (events on the launch stream), then the same K steps instrumented (two events
+    around every kernel launch) for the per-kernel table and the dominant kernel's roofline.  Returns (agent, dict)."""
+    g = binding.Anakin(cfg, seed=0, device="cuda:0")
+    if valu_gemm:
+        g.set_mode(binding.MODE_VALU_GEMM)
+    for _ in range(max(warmup, 1)):
+        g.step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(g.stream)
+    for _ in range(steps):
+        g.step()
+    e1.record(g.stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1)
+    res = {"ms_per_step": ms / steps, "value": cfg["B"] * cfg["T"] * steps / (ms / 1e3), "wall_s": round(wall, 3), "steps": steps}
+    metrics = g.metrics()
+    res["loss"] = metrics["loss"]
+    res["mean_episode_return"] = metrics["reward_sum"] / max(1, metrics["episodes"])
+    if halves:
+        # the two halves on their own (same K): unrolls only, then the updates of K further steps bracketed by events
+        a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
+        a0.record(g.stream)
+        for _ in range(steps):
+            g.rollout()
+        a1.record(g.stream)
+        torch.cuda.synchronize()
+        ms_rollout = a0.elapsed_time(a1) / steps
+        pairs = []
+        for _ in range(steps):
+            g.rollout()
+            b0 = torch.cuda.Event(enable_timing=True); b1 = torch.cuda.Event(enable_timing=True)
+            b0.record(g.stream)
+            g.learn()
+            b1.record(g.stream)
+            pairs.append((b0, b1))
+        torch.cuda.synchronize()
+        ms_learn = sum(x.elapsed_time(y) for x, y in pairs) / steps
+        res["rollout_only"] = {"ms": round(ms_rollout, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_rollout * 1e-3)}
+        res["learn_only"] = {"ms": round(ms_learn, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_learn * 1e-3)}
+    # instrumented pass: the same K steps with two events around every kernel launch
+    g.profile(True)
+    for _ in range(steps):
+        g.step()
+    times = g.kernel_times()
+    g.profile(False)
+    models, _ = kernel_models(cfg, g.P)
+    per_kernel = {}
+    for kname, (calls, total) in times.items():
+        launches_per_step = calls / steps
+        avg_us = total / calls * 1e3
+        entry = {"calls_per_step": launches_per_step, "avg_us": round(avg_us, 2),
+                 "us_per_step": round(total / steps * 1e3, 2)}
+        if kname in models:
+            bound, amount, peak, unit = models[kname]
+            per_launch = amount / launches_per_step
+            ach = per_launch / (avg_us * 1e-6)
+            entry.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit,
+                          "frac": round(ach / peak, 4)})
+        per_kernel[kname] = entry
+    dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
+    d = per_kernel[dominant]
+    traffic, commit = measured_traffic(name)
+    res["roofline"] = {"kernel": dominant, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
+                       "unit": d.get("unit"), "frac": d.get("frac"),
+                       "traffic": traffic.get(dominant), "traffic_unit": "MB per launch",
+                       "traffic_source": (f"profiles/{name}_hbm_traffic.md" + (f" (measured at commit {commit})" if commit else "")) if dominant in traffic else None,
+                       "avg_launch_us": d["avg_us"]}
+    res["kernels"] = per_kernel
+    res["plan"] = g.plan()
+    return g, res
 
 
 def main():
@@ -135,8 +232,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="catch_4096")
+    ap.add_argument("--workload", default="maze_16384",
+                    help="the workload the headline value is measured on (default: the largest single-GPU one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the \"workloads\" block (the other four workloads, measured the same way with fewer steps)")
     ap.add_argument("--valu-gemm", action="store_true", help="learn-phase GEMMs on vector ALUs")
     ap.add_argument("--pathwise", action="store_true",
                     help="also time K steps with the policy gradient taken through the environment (pendulum "
@@ -188,70 +288,8 @@ def main():
         return
     cfg = W.get(args.workload)
     torch.cuda.set_device(0)
-    g = binding.Anakin(cfg, seed=0, device="cuda:0")
-    if args.valu_gemm:
-        g.set_mode(binding.MODE_VALU_GEMM)
-    for _ in range(max(args.warmup, 1)):
-        g.step()
-    torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(g.stream)
-    for _ in range(args.steps):
-        g.step()
-    e1.record(g.stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms = e0.elapsed_time(e1)
-    ms_per_step = ms / args.steps
-    value = cfg["B"] * cfg["T"] * args.steps / (ms / 1e3)
-    metrics = g.metrics()
-
-    # the two halves on their own (same K): unrolls only, then the updates of K further steps bracketed by events
-    a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
-    a0.record(g.stream)
-    for _ in range(args.steps):
-        g.rollout()
-    a1.record(g.stream)
-    torch.cuda.synchronize()
-    ms_rollout = a0.elapsed_time(a1) / args.steps
-    pairs = []
-    for _ in range(args.steps):
-        g.rollout()
-        b0 = torch.cuda.Event(enable_timing=True); b1 = torch.cuda.Event(enable_timing=True)
-        b0.record(g.stream)
-        g.learn()
-        b1.record(g.stream)
-        pairs.append((b0, b1))
-    torch.cuda.synchronize()
-    ms_learn = sum(x.elapsed_time(y) for x, y in pairs) / args.steps
-
-    # instrumented pass: the same K steps with two events around every kernel launch
-    g.profile(True)
-    for _ in range(args.steps):
-        g.step()
-    times = g.kernel_times()
-    g.profile(False)
-    models, _ = kernel_models(cfg, g.P)
-    per_kernel = {}
-    for name, (calls, total) in times.items():
-        launches_per_step = calls / args.steps
-        avg_us = total / calls * 1e3
-        entry = {"calls_per_step": launches_per_step, "avg_us": round(avg_us, 2),
-                 "us_per_step": round(total / args.steps * 1e3, 2)}
-        if name in models:
-            bound, amount, peak, unit = models[name]
-            per_launch = amount / launches_per_step
-            ach = per_launch / (avg_us * 1e-6) * (1.0 if unit == "TFLOP/s" else 1.0)
-            entry.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit,
-                          "frac": round(ach / peak, 4)})
-        per_kernel[name] = entry
-    dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
-    d = per_kernel[dominant]
-    roofline = {"kernel": dominant, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
-                "unit": d.get("unit"), "frac": d.get("frac"),
-                "traffic": MEASURED_TRAFFIC_MB.get((args.workload, dominant)), "traffic_unit": "MB per launch",
-                "avg_launch_us": d["avg_us"]}
+    g, r = measure(binding, torch, args.workload, cfg, args.steps, args.warmup, halves=True, valu_gemm=args.valu_gemm)
+    value, ms_per_step = r["value"], r["ms_per_step"]
     out = {
         "metric": "env steps/sec (rollout+learn) on 1 MI355X", "value": value, "unit": "env steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -259,12 +297,13 @@ def main():
         "dtype": "bf16" if cfg["net"].get("dtype") == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "env": cfg["env"]["kind"], "B": cfg["B"], "T": cfg["T"],
                    "hidden": cfg["net"]["hidden"], "params": g.P},
-        "roofline": roofline,
-        "kernels": per_kernel,
-        "rollout_only": {"ms": round(ms_rollout, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_rollout * 1e-3)},
-        "learn_only": {"ms": round(ms_learn, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_learn * 1e-3)},
-        "wall_s": round(wall, 3),
-        "loss": metrics["loss"], "mean_episode_return": metrics["reward_sum"] / max(1, metrics["episodes"]),
+        "roofline": r["roofline"],
+        "kernels": r["kernels"],
+        "plan": r["plan"],
+        "rollout_only": r["rollout_only"],
+        "learn_only": r["learn_only"],
+        "wall_s": r["wall_s"],
+        "loss": r["loss"], "mean_episode_return": r["mean_episode_return"],
     }
     if args.pathwise:
         if cfg["env"]["kind"] != "pendulum":
@@ -314,9 +353,32 @@ def main():
             g.profile(False)
             out["decoupled"] = {"ms_per_step": round(ms_dec, 4), "env_steps_per_s": cfg["B"] * cfg["T"] / (ms_dec * 1e-3),
                                 "kernels": dk}
+    g.close()
+    del g
+    if not args.no_sweep:
+        # the other workloads, each measured the same way in this same run (shorter K): one line covers all five
+        sweep = {}
+        for name in W.ORDER:
+            if name == args.workload:
+                sweep[name] = {"ms_per_step": round(ms_per_step, 5), "env_steps_per_s": value, "steps": args.steps,
+                               "dtype": out["dtype"], "dominant_kernel": r["roofline"]["kernel"], "bound": r["roofline"]["bound"],
+                               "frac": r["roofline"]["frac"], "avg_launch_us": r["roofline"]["avg_launch_us"]}
+                continue
+            c = W.get(name)
+            k = max(10, min(args.steps, 100))
+            torch.cuda.empty_cache()
+            gg, rr = measure(binding, torch, name, c, k, max(3, min(args.warmup, 10)))
+            gg.close()
+            del gg
+            sweep[name] = {"ms_per_step": round(rr["ms_per_step"], 5), "env_steps_per_s": rr["value"], "steps": k,
+                           "dtype": "bf16" if c["net"].get("dtype") == "bf16" else "f32",
+                           "dominant_kernel": rr["roofline"]["kernel"], "bound": rr["roofline"]["bound"],
+                           "frac": rr["roofline"]["frac"], "avg_launch_us": rr["roofline"]["avg_launch_us"],
+                           "traffic": rr["roofline"]["traffic"],
+                           "kernels_us_per_step": {kn: kv["us_per_step"] for kn, kv in rr["kernels"].items()}}
+        out["workloads"] = sweep
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
-    g.close()
     print(json.dumps(out))
 
 

@@ -104,10 +104,14 @@ typedef struct {
     int32_t nonfinite;                                    /* 1 if any of the above is not finite */
 } anakin_metrics;
 
-/* Bytes of device workspace needed for this configuration (0 if it is invalid). */
+/* Bytes of device workspace needed for this configuration (0 if it is invalid).  The workspace holds everything
+ * paper section 2.3 keeps in device memory between executions: parameters and optimiser state, the environment
+ * states (section 3.1: explicit state handed from step to step), the stored unroll of figure 2 (top) and the
+ * update's scratch. */
 size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin_net_cfg* net, int32_t B, int32_t T);
 
-/* Create an agent: B environments in their initial states (drawn from the
+/* Create an agent (paper section 3.1: `initial_state` of every environment; section 2.3: the program's inputs
+ * are placed in device memory once): B environments in their initial states (drawn from the
  * seed), Glorot-initialised parameters, zero optimiser state -- all written
  * into d_workspace on hip_stream (a hipStream_t, may be null for the default
  * stream).  B must be a multiple of 16.  Synchronises the stream before
@@ -127,7 +131,8 @@ int32_t anakin_rollout(anakin_t* h);
  * forward pass).  ANAKIN_E_STATE without a preceding rollout.  Asynchronous. */
 int32_t anakin_learn(anakin_t* h);
 
-/* anakin_rollout followed by anakin_learn: the timed unit. */
+/* anakin_rollout followed by anakin_learn: Anakin's minimal unit of computation (paper section 3.1 and
+ * figure 2 top: T interactions, then one update), the timed unit.  Asynchronous. */
 int32_t anakin_step(anakin_t* h);
 
 /* One decoupled step: acting and learning run side by side on one device (the one-device form of
@@ -143,28 +148,58 @@ int32_t anakin_step(anakin_t* h);
  * the unroll just collected (its adv / ret / act fields belong to the update that ran beside it).
  * One update per unroll, score-function gradient: ANAKIN_E_BAD_CONFIG otherwise.  After a decoupled step
  * anakin_learn returns ANAKIN_E_STATE (the stored unroll has no activations); anakin_step and
- * anakin_rollout start a fresh on-policy unroll.  Asynchronous. */
+ * anakin_rollout start a fresh on-policy unroll.  Asynchronous.
+ * Streams: this is the one call that uses a second stream.  The caller may hand one over with
+ * anakin_set_actor_stream; otherwise the library creates a non-blocking stream of default priority on first use
+ * and destroys it in anakin_destroy (the one exception to "the caller owns the streams").
+ * Errors: if the learner's half fails, the unroll the actor collected is still stored, the handle's stream is
+ * still ordered behind the actor and the error code of the update is returned. */
 int32_t anakin_step_decoupled(anakin_t* h);
 
-/* Frees the host-side handle (never the workspace).  Synchronises the stream. */
+/* The stream the actor of anakin_step_decoupled runs on: a hipStream_t of the caller's, distinct from the
+ * handle's stream and not the null stream, of default priority; it must outlive the handle or be replaced first.
+ * Synchronises a previously used actor stream.  ANAKIN_E_INVALID_ARG otherwise. */
+int32_t anakin_set_actor_stream(anakin_t* h, void* hip_stream);
+
+/* Frees the host-side handle (never the workspace: paper section 2.3, device memory outlives an execution and
+ * here belongs to the caller).  Synchronises the stream. */
 int32_t anakin_destroy(anakin_t* h);
 
-/* ---- introspection for parity tests and measurement (all synchronise) ---- */
+/* ---- introspection for parity tests and measurement ----
+ * None of these is on the hot path.  Each synchronises the handle's stream and copies between host buffers of the
+ * caller and the device workspace; together they expose the explicit, device-resident state that paper sections
+ * 2.3 and 3.1 describe (parameters, optimiser state, environment state, the stored unroll), which is also what a
+ * checkpoint consists of.  All return ANAKIN_E_INVALID_ARG for a null pointer or a wrong length. */
+
+/* Number of parameters P of the policy/value network (flat vector: W_1, b_1, ..., W_L, b_L, W_heads, b_heads). */
 int32_t anakin_param_count(const anakin_t* h, int64_t* out);
-int32_t anakin_get_params(anakin_t* h, float* h_dst, size_t n);          /* n must equal the count */
-int32_t anakin_set_params(anakin_t* h, const float* h_src, size_t n);    /* also refreshes bf16 copies */
-int32_t anakin_get_grads(anakin_t* h, float* h_dst, size_t n);           /* gradient of the last learn */
+/* The parameters the next unroll acts with (section 3.1: the update's output).  n must equal P. */
+int32_t anakin_get_params(anakin_t* h, float* h_dst, size_t n);
+/* Replaces them (bf16 nets: the rounded copies are refreshed too). */
+int32_t anakin_set_params(anakin_t* h, const float* h_src, size_t n);
+/* The gradient the last update applied (of the last chunk with several updates per unroll). */
+int32_t anakin_get_grads(anakin_t* h, float* h_dst, size_t n);
+/* Adam's moments and step count (the optimiser state of the "parameter update" of section 3.1). */
 int32_t anakin_get_opt_state(anakin_t* h, float* h_m, float* h_v, int32_t* h_step, size_t n);
 int32_t anakin_set_opt_state(anakin_t* h, const float* h_m, const float* h_v, int32_t step, size_t n);
-/* env state as [B][4] int32 + [B][2] float rows:
- * catch (ball_x, ball_y, paddle_x, 0); pendulum (steps,0,0,0) + (theta, theta_dot); maze (cell, steps,0,0) */
+/* The environments' explicit state (section 3.1: `step(state, action)` takes and returns it) as [B][4] int32 +
+ * [B][2] float rows: catch (ball_x, ball_y, paddle_x, 0); pendulum (steps,0,0,0) + (theta, theta_dot);
+ * maze (cell, steps,0,0).  The setter checks ranges: ANAKIN_E_INVALID_ARG for a state the env cannot be in. */
 int32_t anakin_get_env_state(anakin_t* h, int32_t* h_si, float* h_sf);
 int32_t anakin_set_env_state(anakin_t* h, const int32_t* h_si, const float* h_sf);
-int32_t anakin_get_walls(anakin_t* h, uint32_t* h_walls);                /* [B][8], maze only */
+/* The mazes drawn at create, [B][8] words of 32 cells, bit set = wall.  ANAKIN_E_STATE for other envs. */
+int32_t anakin_get_walls(anakin_t* h, uint32_t* h_walls);
+/* Environment steps taken so far per env (the time coordinate of every random draw: runs are deterministic,
+ * paper section 3.1, and a resumed run continues the same streams). */
 int32_t anakin_get_global_step(const anakin_t* h, uint64_t* out);
 int32_t anakin_set_global_step(anakin_t* h, uint64_t g);
+/* Where the stored unroll (figure 2 top) lies in the workspace; see anakin_traj_view. */
 int32_t anakin_get_trajectory(anakin_t* h, anakin_traj_view* out);
+/* Loss terms of the last update and reward / episode counts of the last unroll.  Returns ANAKIN_E_NONFINITE
+ * (with *out filled) if a loss term is not finite; all zero before the first update. */
 int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out);
+/* Selects reference implementations (ANAKIN_MODE_* flags) for cross-checks; 0 is the product path.
+ * ANAKIN_E_INVALID_ARG for an unknown flag or a combination a bf16 net cannot run. */
 int32_t anakin_set_mode(anakin_t* h, int32_t flags);
 
 /* Several Adam updates per unroll (paper section 4, the remark on decoupling the acting batch from
@@ -188,6 +223,25 @@ int32_t anakin_set_updates_per_unroll(anakin_t* h, int32_t n_updates);
  * last, from anakin_learn).  Kept until changed. */
 enum { ANAKIN_PG_SCORE_FUNCTION = 0, ANAKIN_PG_PATHWISE = 1 };
 int32_t anakin_set_policy_gradient(anakin_t* h, int32_t kind);
+
+/* How the update of this handle is cut into workgroups (what the parity tests assert their cases reach, and
+ * what the benchmark prints).  splits[l], l < n_hidden: chunks of the B*T samples whose partial dW_{l+1} / db_{l+1}
+ * sums are written separately and added in a fixed order; splits[n_hidden]: the same for the head matrix;
+ * splits_walls: bf16 maze nets whose first layer is reduced plane by plane -- chunks of the 2 B time-summed rows of
+ * the wall-plane product (splits[0] then counts the agent-plane product's chunks), else 0;
+ * dx_rows[l], 1 <= l < n_hidden: samples one workgroup of the weights-resident bf16 dX kernel of layer l+1 walks
+ * (it stages 32 at a time), 0 where another kernel runs; bf16_matrix_path: 1 when acting and update of a bf16
+ * net run on the matrix-core kernels (packed activations). */
+typedef struct {
+    int32_t n_hidden;
+    int32_t splits[5];
+    int32_t splits_walls;
+    int32_t head_fan;
+    int32_t dx_rows[4];
+    int32_t bf16_matrix_path;
+    int32_t updates_per_unroll;
+} anakin_plan;
+int32_t anakin_get_plan(const anakin_t* h, anakin_plan* out);
 
 /* Per-kernel timing for measurement.  While enabled, every kernel launch is
  * bracketed by two events recorded on the handle's stream (this adds a few

@@ -484,7 +484,7 @@ static void init_params(orc_t* h)
  * bfloat16 (products are then exact in binary32), the accumulation, bias and
  * ReLU stay binary32, hidden activations are rounded to bfloat16, head
  * outputs are not.  acts (optional) receives the hidden activations. */
-static void forward_f32(const orc_t* h, const float* x, float* head, float* acts)
+static void forward_f32_with(const orc_t* h, const float* theta, int weights_rounded, const float* x, float* head, float* acts)
 {
     float bufa[1024], bufb[1024];
     const float* in = x;
@@ -494,15 +494,15 @@ static void forward_f32(const orc_t* h, const float* x, float* head, float* acts
     for (int l = 0; l <= h->L; ++l) {
         int K = h->dims[l];
         int N = (l < h->L) ? h->dims[l + 1] : h->NH;
-        const float* W = h->theta + ((l < h->L) ? h->w_off[l] : h->wh_off);
-        const float* bias = h->theta + ((l < h->L) ? h->b_off[l] : h->bh_off);
+        const float* W = theta + ((l < h->L) ? h->w_off[l] : h->wh_off);
+        const float* bias = theta + ((l < h->L) ? h->b_off[l] : h->bh_off);
         float* y = (l < h->L) ? out : head;
         for (int j = 0; j < N; ++j) y[j] = bias[j];
         for (int k = 0; k < K; ++k) {
             float xk = bf ? orc_bf16_round(in[k]) : in[k];
             for (int j = 0; j < N; ++j) {
                 float w = W[(size_t)k * N + j];
-                if (bf) w = orc_bf16_round(w);
+                if (bf && !weights_rounded) w = orc_bf16_round(w);
                 y[j] = fmaf(xk, w, y[j]);
             }
         }
@@ -516,6 +516,12 @@ static void forward_f32(const orc_t* h, const float* x, float* head, float* acts
             out = (y == bufa) ? bufb : bufa;
         }
     }
+}
+
+/* with the agent's current parameters (weights rounded on the fly when dtype = 1) */
+static void forward_f32(const orc_t* h, const float* x, float* head, float* acts)
+{
+    forward_f32_with(h, h->theta, 0, x, head, acts);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -797,15 +803,33 @@ static double* forward_params64(const orc_t* h, const float* theta_src)
     return wq;
 }
 
-/* binary64 forward pass from the stored state of sample tb: act[0] the observation, act[l] the
- * output of hidden layer l, head the NH head outputs */
-static void forward64(const orc_t* h, const double* wq, size_t tb, double act[5][1024], double* head)
+/* the same values in binary32 (exact: they are binary32 or bfloat16 numbers), for the pass that takes the
+ * branch decisions */
+static float* forward_params32(const orc_t* h, const double* wq)
+{
+    float* w32 = (float*)zalloc(h->P * sizeof(float));
+    for (size_t i = 0; i < h->P; ++i) w32[i] = (float)wq[i];
+    return w32;
+}
+
+/* Learn-time forward pass from the stored state of sample tb.  The VALUES are binary64: act[0] the observation,
+ * act[l] the output of hidden layer l, head the NH head outputs.  The BRANCHES are those of the pass the update
+ * differentiates, which ran in binary32 (paper section 3.1: the update reuses the policy's forward pass): whether
+ * a hidden unit is on the active side of its ReLU (on[l][j]) and whether log_sigma is inside its clamp (head32) are
+ * read off the binary32 forward pass of R-18 / R-20 with the same parameters, so a pre-activation within rounding
+ * of zero takes the same side here as there.  On the active side a unit's value is its binary64 sum (rounded to
+ * bfloat16 when dtype = 1), whatever its sign. */
+static void forward64(const orc_t* h, const double* wq, const float* w32, size_t tb, double act[5][1024],
+                      unsigned char on[5][1024], double* head, float* head32)
 {
     int B = h->B, NH = h->NH, L = h->L;
-    float xf[1024];
+    float xf[1024], acts32[4 * 1024], h32[16];
     int b = (int)(tb % (size_t)B);
     render_obs(h, b, h->tr_si + tb * 4, h->tr_sf + tb * 2, xf);
+    forward_f32_with(h, w32, 1, xf, h32, acts32);
+    if (head32) memcpy(head32, h32, (size_t)NH * sizeof(float));
     for (int k = 0; k < h->D; ++k) act[0][k] = qround(h, (double)xf[k]);   /* R-20: every layer input, the observation too */
+    size_t aoff = 0;
     for (int l = 0; l < L; ++l) {
         int K = h->dims[l], N = h->dims[l + 1];
         const double* W = wq + h->w_off[l];
@@ -813,8 +837,10 @@ static void forward64(const orc_t* h, const double* wq, size_t tb, double act[5]
         for (int j = 0; j < N; ++j) {
             double s = bias[j];
             for (int k = 0; k < K; ++k) s += act[l][k] * W[(size_t)k * N + j];
-            act[l + 1][j] = qround(h, s > 0.0 ? s : 0.0);
+            on[l + 1][j] = acts32[aoff + (size_t)j] > 0.0f;
+            act[l + 1][j] = on[l + 1][j] ? qround(h, s) : 0.0;
         }
+        aoff += (size_t)N;
     }
     int K = h->dims[L];
     const double* W = wq + h->wh_off;
@@ -825,11 +851,11 @@ static void forward64(const orc_t* h, const double* wq, size_t tb, double act[5]
     }
 }
 
-/* Backward pass of one sample: given the forward activations and the gradient dhead of a scalar
+/* Backward pass of one sample: given the forward activations, the ReLU sides and the gradient dhead of a scalar
  * with respect to the head outputs, adds that scalar's parameter gradient to g; dobs (optional)
  * receives its gradient with respect to the observation. */
-static void backprop_sample(const orc_t* h, const double* wq, double act[5][1024], const double* dhead,
-                            double* g, double* dobs)
+static void backprop_sample(const orc_t* h, const double* wq, double act[5][1024], unsigned char on[5][1024],
+                            const double* dhead, double* g, double* dobs)
 {
     int NH = h->NH, L = h->L;
     double dz[2][1024];
@@ -841,7 +867,7 @@ static void backprop_sample(const orc_t* h, const double* wq, double act[5][1024
         for (int k = 0; k < K; ++k) {
             double s = 0;
             for (int j = 0; j < NH; ++j) { gW[(size_t)k * NH + j] += act[L][k] * dhead[j]; s += W[(size_t)k * NH + j] * dhead[j]; }
-            dz[L & 1][k] = act[L][k] > 0.0 ? s : 0.0;
+            dz[L & 1][k] = on[L][k] ? s : 0.0;
         }
     }
     for (int l = L - 1; l >= 0; --l) {
@@ -853,7 +879,7 @@ static void backprop_sample(const orc_t* h, const double* wq, double act[5][1024
         for (int k = 0; k < K; ++k) {
             double xk = act[l][k], s = 0;
             for (int j = 0; j < N; ++j) { gW[(size_t)k * N + j] += xk * d[j]; s += W[(size_t)k * N + j] * d[j]; }
-            if (l > 0) dz[l & 1][k] = xk > 0.0 ? s : 0.0;
+            if (l > 0) dz[l & 1][k] = on[l][k] ? s : 0.0;
             else if (dobs) dobs[k] = s;
         }
     }
@@ -869,10 +895,13 @@ static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begi
     double beta = (double)h->net.entropy_coef, cv = (double)h->net.value_coef;
     double* g = (double*)zalloc(h->P * sizeof(double));
     double* wq = forward_params64(h, theta_src);             /* parameters as the forward sees them */
+    float* w32 = forward_params32(h, wq);
     double act[5][1024], head[16], dhead[16];
+    unsigned char on[5][1024];
+    float head32[16];
     double Lp = 0, Lv = 0, Le = 0;
     for (size_t tb = tb_begin; tb < tb_end; ++tb) {
-        forward64(h, wq, tb, act, head);
+        forward64(h, wq, w32, tb, act, on, head, head32);
         double A_ = h->adv[tb], G_ = h->ret[tb];
         double V = head[NH - 1];
         Lv += cv * (G_ - V) * (G_ - V);
@@ -890,7 +919,7 @@ static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begi
                 dhead[i] = (-A_ * ((i == a ? 1.0 : 0.0) - p[i]) + beta * p[i] * (lp[i] + H)) * inv_n;
         } else {
             double mu = head[0], ls = head[1];
-            int clamped = (ls < -5.0) || (ls > 2.0);
+            int clamped = (head32[1] < -5.0f) || (head32[1] > 2.0f);   /* side of the clamp: the binary32 pass decides */
             double lsc = ls < -5.0 ? -5.0 : (ls > 2.0 ? 2.0 : ls);
             double sigma = exp(lsc);
             double eps = ((double)h->tr_z[tb] - mu) / sigma;     /* the sample z is the fixed quantity */
@@ -899,17 +928,26 @@ static void loss_and_grad_range(orc_t* h, const float* theta_src, size_t tb_begi
             dhead[0] = (-A_ * eps / sigma) * inv_n;
             dhead[1] = clamped ? 0.0 : (-A_ * (eps * eps - 1.0) - beta) * inv_n;
         }
-        backprop_sample(h, wq, act, dhead, g, NULL);
+        backprop_sample(h, wq, act, on, dhead, g, NULL);
     }
     h->loss[1] = Lp * inv_n; h->loss[2] = Lv * inv_n; h->loss[3] = Le * inv_n;
     h->loss[0] = h->loss[1] + h->loss[2] + h->loss[3];
     for (size_t i = 0; i < h->P; ++i) h->grad[i] = (float)g[i];
-    free(g); free(wq);
+    free(g); free(wq); free(w32);
 }
 
 void orc_loss_and_grad(orc_t* h)
 {
     loss_and_grad_range(h, h->theta, 0, (size_t)h->T * h->B);
+}
+
+/* the same over the samples begin <= t*B + b < end only (their own mean): lets a test spread the
+ * per-sample work of a large update over several oracle instances, one range each */
+int orc_loss_and_grad_range(orc_t* h, int64_t begin, int64_t end)
+{
+    if (begin < 0 || end <= begin || end > (int64_t)h->T * h->B) return -1;
+    loss_and_grad_range(h, h->theta, (size_t)begin, (size_t)end);
+    return 0;
 }
 
 /* ------------------------------------------------------------------------- */
@@ -1014,9 +1052,11 @@ void orc_vtrace_targets(orc_t* h, double rho_bar, double c_bar)
     int B = h->B, T = h->T, NH = h->NH;
     double gamma = (double)h->net.gamma, lambda = (double)h->net.lambda_;
     double* wq = forward_params64(h, h->theta);
+    float* w32 = forward_params32(h, wq);
     double act[5][1024];
-    for (size_t tb = 0; tb < (size_t)(T + 1) * B; ++tb) forward64(h, wq, tb, act, h->cur_head + tb * NH);
-    free(wq);
+    unsigned char on[5][1024];
+    for (size_t tb = 0; tb < (size_t)(T + 1) * B; ++tb) forward64(h, wq, w32, tb, act, on, h->cur_head + tb * NH, NULL);
+    free(wq); free(w32);
     for (int b = 0; b < B; ++b) {
         double tail = 0.0;                                   /* v_{t+1} - V(s_{t+1}) */
         for (int t = T - 1; t >= 0; --t) {
@@ -1093,16 +1133,19 @@ void orc_pathwise_grad(orc_t* h, double* g, double* path_dhead)
     const double dt = (double)0x1.99999ap-5f, c_thd = (double)0x1.99999ap-4f, c_u = (double)0x1.0624dep-10f;
     const double w = -1.0 / ((double)B * (double)T);           /* dL_path / dr */
     double* wq = forward_params64(h, h->theta);
+    float* w32 = forward_params32(h, wq);
     double act[5][1024], head[16], dhead[16], dobs[8];
+    unsigned char on[5][1024];
+    float head32[16];
     for (int b = 0; b < B; ++b) {
         double lam_th = 0.0, lam_thd = 0.0;                       /* adjoint of the state after step t */
         for (int t = T - 1; t >= 0; --t) {
             size_t tb = (size_t)t * B + b;
             if (h->tr_done[tb]) { lam_th = 0.0; lam_thd = 0.0; }   /* the next state is a reset state */
-            forward64(h, wq, tb, act, head);
+            forward64(h, wq, w32, tb, act, on, head, head32);
             double th = (double)h->tr_sf[tb * 2], thd = (double)h->tr_sf[tb * 2 + 1];
             double mu = head[0], ls = head[1];
-            int clamped = (ls < -5.0) || (ls > 2.0);
+            int clamped = (head32[1] < -5.0f) || (head32[1] > 2.0f);
             double sigma = exp(ls < -5.0 ? -5.0 : (ls > 2.0 ? 2.0 : ls));
             double eps = (double)h->tr_eps[tb];
             double a = tanh(mu + sigma * eps), u = 2.0 * a;
@@ -1119,13 +1162,13 @@ void orc_pathwise_grad(orc_t* h, double* g, double* path_dhead)
             dhead[0] = g_z;
             dhead[1] = clamped ? 0.0 : g_z * sigma * eps;
             if (path_dhead) { path_dhead[tb * 2] = dhead[0]; path_dhead[tb * 2 + 1] = dhead[1]; }
-            backprop_sample(h, wq, act, dhead, g, dobs);
+            backprop_sample(h, wq, act, on, dhead, g, dobs);
             /* o = (cos th, sin th, thd) */
             lam_th = g_th - sin(th) * dobs[0] + cos(th) * dobs[1];
             lam_thd = g_thd + dobs[2];
         }
     }
-    free(wq);
+    free(wq); free(w32);
 }
 
 /* one update with the objective of R-34 on the stored unroll */

@@ -83,6 +83,7 @@ def lib():
         L.orc_returns.argtypes = [C.c_int, C.c_int, f32p, u8p, f32p, C.c_double, C.c_double, f64p, f64p]
         L.orc_returns.restype = None
         L.orc_loss_and_grad.argtypes = [C.c_void_p]; L.orc_loss_and_grad.restype = None
+        L.orc_loss_and_grad_range.argtypes = [C.c_void_p, C.c_int64, C.c_int64]; L.orc_loss_and_grad_range.restype = C.c_int
         L.orc_surrogate_loss.argtypes = [C.c_void_p]; L.orc_surrogate_loss.restype = C.c_double
         L.orc_adam.argtypes = [C.c_int64, f32p, f32p, f64p, f64p, C.c_int, C.c_double, C.c_double,
                                C.c_double, C.c_double]
@@ -280,8 +281,13 @@ class Oracle:
         if rc != 0:
             raise RuntimeError("learn_n: no stored trajectory" if rc == -1 else "learn_n: T is not a multiple of n_updates")
 
-    def loss_and_grad(self):
-        self.L.orc_loss_and_grad(self.h)
+    def loss_and_grad(self, begin=None, end=None):
+        """loss[] and grad of the stored unroll at the current parameters with the adv / ret now held;
+        begin, end: only the samples begin <= t*B + b < end (their own mean)."""
+        if begin is None and end is None:
+            self.L.orc_loss_and_grad(self.h)
+        elif self.L.orc_loss_and_grad_range(self.h, int(begin), int(end)) != 0:
+            raise ValueError("sample range outside the unroll")
 
     def surrogate_loss(self):
         return self.L.orc_surrogate_loss(self.h)

@@ -52,15 +52,20 @@ class Metrics(C.Structure):
                 ("nonfinite", C.c_int32)]
 
 
+class Plan(C.Structure):
+    _fields_ = [("n_hidden", C.c_int32), ("splits", C.c_int32 * 5), ("splits_walls", C.c_int32), ("head_fan", C.c_int32),
+                ("dx_rows", C.c_int32 * 4), ("bf16_matrix_path", C.c_int32), ("updates_per_unroll", C.c_int32)]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("calls", C.c_int64), ("total_ms", C.c_double)]
 
 
-EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled",
+EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled", "anakin_set_actor_stream",
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
-           "anakin_get_metrics", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_set_policy_gradient", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
+           "anakin_get_metrics", "anakin_get_plan", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_set_policy_gradient", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
            "anakin_last_error"]
 
 _lib = None
@@ -86,7 +91,7 @@ def load():
     L.anakin_workspace_bytes.restype = C.c_size_t
     L.anakin_create.argtypes = [C.POINTER(vp), C.POINTER(EnvCfg), C.POINTER(NetCfg), C.c_int32, C.c_int32,
                                 C.c_uint64, vp, C.c_size_t, vp]
-    for name in ("anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled", "anakin_destroy"):
+    for name in ("anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled", "anakin_set_actor_stream", "anakin_destroy"):
         getattr(L, name).argtypes = [vp]
     L.anakin_param_count.argtypes = [vp, C.POINTER(C.c_int64)]
     L.anakin_get_params.argtypes = [vp, f32p, C.c_size_t]
@@ -101,6 +106,8 @@ def load():
     L.anakin_set_global_step.argtypes = [vp, C.c_uint64]
     L.anakin_get_trajectory.argtypes = [vp, C.POINTER(TrajView)]
     L.anakin_get_metrics.argtypes = [vp, C.POINTER(Metrics)]
+    L.anakin_get_plan.argtypes = [vp, C.POINTER(Plan)]
+    L.anakin_set_actor_stream.argtypes = [vp, vp]
     L.anakin_set_mode.argtypes = [vp, C.c_int32]
     L.anakin_set_updates_per_unroll.argtypes = [vp, C.c_int32]
     L.anakin_set_policy_gradient.argtypes = [vp, C.c_int32]
@@ -196,6 +203,11 @@ class Anakin:
     def set_policy_gradient(self, kind):
         self._chk(self.L.anakin_set_policy_gradient(self.h, int(kind)))
 
+    def set_actor_stream(self, stream):
+        """stream: a torch.cuda.Stream the actor of step_decoupled runs on (kept alive by this object)"""
+        self._chk(self.L.anakin_set_actor_stream(self.h, C.c_void_p(stream.cuda_stream if stream is not None else None)))
+        self._actor_stream = stream
+
     def step_decoupled(self):
         self._chk(self.L.anakin_step_decoupled(self.h))
 
@@ -259,6 +271,13 @@ class Anakin:
         if rc not in (OK, E_NONFINITE):
             self._chk(rc)
         return {k: getattr(m, k) for k, _ in Metrics._fields_}
+
+    def plan(self):
+        p = Plan()
+        self._chk(self.L.anakin_get_plan(self.h, C.byref(p)))
+        return {"n_hidden": p.n_hidden, "splits": list(p.splits)[:p.n_hidden + 1], "splits_walls": p.splits_walls,
+                "head_fan": p.head_fan, "dx_rows": list(p.dx_rows)[:p.n_hidden], "bf16_matrix_path": p.bf16_matrix_path,
+                "updates_per_unroll": p.updates_per_unroll}
 
     def trajectory(self):
         """Host copies (numpy) of the stored unroll; synchronises the stream."""

@@ -333,7 +333,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0; h->traj_no_acts = 0;
     h->pathwise = 0;
-    h->traj_decoupled = 0; h->actor_stream = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
+    h->traj_decoupled = 0; h->actor_stream = nullptr; h->actor_stream_owned = 0; h->ev_fork = nullptr; h->ev_join = nullptr;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ed, ns, B, T, h->splits, &h->splits_w, &h->head_fan, &h->loss_blocks);
@@ -356,6 +356,8 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     hipError_t e = hipMemsetAsync(h->ws + h->lay.grad, 0, (size_t)ns.P * 4, h->stream);
     if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.m, 0, (size_t)ns.P * 4, h->stream);
     if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.v, 0, (size_t)ns.P * 4, h->stream);
+    // the metrics are sums over these blocks: zero until the first update has written them
+    if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.loss_part, 0, (size_t)(h->loss_blocks + T) * 8 * 4, h->stream);
     if (e != hipSuccess) { h->err = std::string("hipMemsetAsync: ") + hipGetErrorString(e); return fail(ANAKIN_E_HIP); }
     if (ns.bf16) {
         e = launch_refresh_bf16(h);
@@ -390,7 +392,7 @@ extern "C" int32_t anakin_destroy(anakin_t* h)
     if (!h) return ANAKIN_E_INVALID_ARG;
     (void)prof_resolve(h);
     for (hipEvent_t e : h->prof_pool) (void)hipEventDestroy(e);
-    if (h->actor_stream) { (void)hipStreamSynchronize(h->actor_stream); (void)hipStreamDestroy(h->actor_stream); }
+    if (h->actor_stream) { (void)hipStreamSynchronize(h->actor_stream); if (h->actor_stream_owned) (void)hipStreamDestroy(h->actor_stream); }
     if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
     if (h->ev_join) (void)hipEventDestroy(h->ev_join);
     delete h;
@@ -617,10 +619,12 @@ extern "C" int32_t anakin_step_decoupled(anakin_t* h)
     if (h->pathwise) { h->err = "decoupled steps use the score-function gradient"; return ANAKIN_E_BAD_CONFIG; }
     if (h->prof_pending.size() > 8192) HIPCHK(h, prof_resolve(h));
     if (!h->actor_stream) {
+        // no stream given by the caller (anakin_set_actor_stream): one of the library's own, default priority
         HIPCHK(h, hipStreamCreateWithFlags(&h->actor_stream, hipStreamNonBlocking));
-        HIPCHK(h, hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
-        HIPCHK(h, hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
+        h->actor_stream_owned = 1;
     }
+    if (!h->ev_fork) HIPCHK(h, hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+    if (!h->ev_join) HIPCHK(h, hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
     const NetShape& n = h->net;
     hipStream_t learner = h->stream;
     // the actor's parameters: the learner's as they are now, before this step's update touches them
@@ -639,27 +643,46 @@ extern "C" int32_t anakin_step_decoupled(anakin_t* h)
     h->stream = learner;
     swap_record_sets(h->lay);
     HIPCHK(h, e);
-    HIPCHK(h, hipEventRecord(h->ev_join, h->actor_stream));
-    // learner: one off-policy update on the unroll of the previous step
-    int32_t rc = ANAKIN_OK;
-    if (h->have_traj) {
+    const bool join_recorded = hipEventRecord(h->ev_join, h->actor_stream) == hipSuccess;
+    // learner: one off-policy update on the unroll of the previous step.  Whatever happens in it, the layout is
+    // put back, the record set the actor is filling becomes the stored unroll and the handle's stream is ordered
+    // behind the actor, so an error leaves the handle consistent and the fresh unroll usable.
+    auto learner_update = [&]() -> int32_t {
+        if (!h->have_traj) return ANAKIN_OK;
         HIPCHK(h, mc ? launch_replay_bf16(h) : launch_replay_forward(h));
         HIPCHK(h, launch_vtrace(h));
         const int no_acts = h->traj_no_acts;
         h->traj_packed = mc ? 1 : 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0;
         const Layout keep = h->lay;
         h->lay.tr_head = keep.head_new; h->lay.tr_eps = keep.eps_new;   // the loss kernel reads the learner's heads
-        rc = run_update(h);
+        const int32_t r = run_update(h);
         h->lay = keep;
         h->traj_no_acts = no_acts;
-    }
-    // the record set just filled becomes the stored unroll; later work on the handle's stream follows the actor
+        return r;
+    };
+    const int32_t rc = learner_update();
     swap_record_sets(h->lay);
-    HIPCHK(h, hipStreamWaitEvent(learner, h->ev_join, 0));
-    if (rc != ANAKIN_OK) return rc;
+    hipError_t ej = join_recorded ? hipStreamWaitEvent(learner, h->ev_join, 0) : hipErrorUnknown;
+    if (ej != hipSuccess) ej = hipStreamSynchronize(h->actor_stream);     // order by waiting on the host instead
     h->traj_packed = mc ? 1 : 0; h->traj_no_acts = one_layer_fused(h) ? 1 : 0; h->traj_decoupled = 1;
     h->gstep += (uint64_t)h->T;
     h->have_traj = 1;
+    if (rc != ANAKIN_OK) return rc;
+    HIPCHK(h, ej);
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_set_actor_stream(anakin_t* h, void* hip_stream)
+{
+    NEED(h);
+    if (!hip_stream) { h->err = "the actor stream must be a stream of its own (not the null stream)"; return ANAKIN_E_INVALID_ARG; }
+    if (static_cast<hipStream_t>(hip_stream) == h->stream) { h->err = "the actor stream must differ from the handle's stream"; return ANAKIN_E_INVALID_ARG; }
+    if (h->actor_stream) {
+        HIPCHK(h, hipStreamSynchronize(h->actor_stream));
+        if (h->actor_stream_owned) HIPCHK(h, hipStreamDestroy(h->actor_stream));
+    }
+    h->actor_stream = static_cast<hipStream_t>(hip_stream);
+    h->actor_stream_owned = 0;
     return ANAKIN_OK;
 }
 
@@ -810,6 +833,22 @@ extern "C" int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out)
     out->episodes = (int64_t)llround(s[4]);
     out->nonfinite = !(isfinite(out->loss) && isfinite(out->reward_sum));
     return out->nonfinite ? ANAKIN_E_NONFINITE : ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_get_plan(const anakin_t* h, anakin_plan* out)
+{
+    if (!h || !out) return ANAKIN_E_INVALID_ARG;
+    memset(out, 0, sizeof *out);
+    const NetShape& n = h->net;
+    out->n_hidden = n.L;
+    for (int l = 0; l <= n.L; ++l) out->splits[l] = h->splits[l];
+    out->splits_walls = h->splits_w;
+    out->head_fan = h->head_fan;
+    out->bf16_matrix_path = bf16_mfma(h) ? 1 : 0;
+    if (out->bf16_matrix_path)
+        for (int l = 1; l < n.L; ++l) out->dx_rows[l] = bf16_dx_rows_per_workgroup(h->B * h->T, n.dims[l], n.dims[l + 1]);
+    out->updates_per_unroll = h->n_updates;
+    return ANAKIN_OK;
 }
 
 extern "C" int32_t anakin_set_mode(anakin_t* h, int32_t flags)

@@ -4,7 +4,7 @@
 // Compile with contraction off; every fused multiply-add below is explicit.
 #pragma once
 #include <math.h>
-#include "philox.cuh"
+#include "philox.h"
 
 namespace ank {
 

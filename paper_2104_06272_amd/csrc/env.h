@@ -5,7 +5,7 @@
 //   Pendulum: s0 = steps taken, f0 = theta (kept in [-pi_f, pi_f)), f1 = theta_dot
 //   Maze:     s0 = cell | steps << 16; walls: one bit per cell (8 words per env)
 #pragma once
-#include "detmath.cuh"
+#include "detmath.h"
 
 namespace ank {
 

@@ -28,7 +28,7 @@
 //
 // Operand layout of v_mfma_f32_32x32x2_f32: see gemm_mfma.hip.
 #include "gemm.h"
-#include "detmath.cuh"
+#include "detmath.h"
 
 namespace ank {
 

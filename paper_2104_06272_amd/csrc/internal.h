@@ -6,7 +6,7 @@
 #include <string>
 #include <vector>
 #include <hip/hip_runtime.h>
-#include "env.cuh"
+#include "env.h"
 #include "../../include/anakin.h"
 
 namespace ank {
@@ -150,7 +150,8 @@ struct anakin {
     int traj_no_acts;             // the stored unroll holds no hidden activations (one-layer nets)
     int pathwise;                 // policy gradient through the environment instead of the score function (pendulum)
     int traj_decoupled;           // the stored unroll was collected by a decoupled step: behaviour parameters, no activations
-    hipStream_t actor_stream;     // decoupled steps: the actor's stream (created on first use), and the fork/join events
+    hipStream_t actor_stream;     // decoupled steps: the actor's stream (the caller's, or created on first use), and the fork/join events
+    int actor_stream_owned;       // the library created actor_stream and destroys it
     hipEvent_t ev_fork, ev_join;
     std::string err;
     // optional per-kernel timing with events on the launch stream
@@ -196,6 +197,7 @@ hipError_t launch_rollout_bf16_behaviour(anakin* h);
 hipError_t launch_replay_bf16(anakin* h);
 hipError_t launch_backward_bf16(anakin* h);
 hipError_t launch_refresh_bf16(anakin* h);
+int bf16_dx_rows_per_workgroup(int M, int K, int N);
 bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B);
 // bf16 network running on the matrix-core path (packed bf16 activations) rather than the fp32 reference path
 // the stored unroll was produced by the bf16 matrix-core kernels and the maze first layer is reduced in pieces

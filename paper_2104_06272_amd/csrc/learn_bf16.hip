@@ -763,6 +763,16 @@ hipError_t launch_refresh_bf16(anakin* h)
 // ---------------------------------------------------------------------------
 // backward through all layers for a bf16 network
 // ---------------------------------------------------------------------------
+// Rows of dZ_l (samples) one workgroup of the weights-resident bf16 dX kernel walks, in stages of NRES_RT rows;
+// 0 when the layer's shape goes to the tiled kernel instead.  At most 256 row ranges per 256-column block of W.
+int bf16_dx_rows_per_workgroup(int M, int K, int N)
+{
+    if (!((N == 256 || N == 512) && K % 256 == 0 && M % NRES_RT == 0)) return 0;
+    const int tiles = M / NRES_RT;
+    const int blocks = tiles < 256 ? tiles : 256;
+    return ((tiles + blocks - 1) / blocks) * NRES_RT;
+}
+
 hipError_t launch_backward_bf16(anakin* h)
 {
     const Layout& L = h->lay;
@@ -875,9 +885,7 @@ hipError_t launch_backward_bf16(anakin* h)
             const bool res = (g.N == 256 || g.N == 512) && g.K % 256 == 0 && g.M % NRES_RT == 0;
             ProfScope prof(h, "gemm_nt_mask");
             if (res) {
-                const int tiles = g.M / NRES_RT;
-                const int blocks = tiles < 256 ? tiles : 256;
-                const int rows_per_block = ((tiles + blocks - 1) / blocks) * NRES_RT;
+                const int rows_per_block = bf16_dx_rows_per_workgroup(g.M, g.K, g.N);
                 const size_t lds2 = ((size_t)2 * NRES_RT * (g.N + 8) + (size_t)2 * NRES_RT * NRES_LDT) * sizeof(uint16_t);
                 const bool rm = g.dxR != nullptr;
                 const void* fn = g.N == 512 ? (rm ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<512, false>))

@@ -14,7 +14,7 @@
 // with the env step's own binary32 expression, so it agrees with what the env did.
 #include <type_traits>
 #include "internal.h"
-#include "detmath.cuh"
+#include "detmath.h"
 
 namespace ank {
 

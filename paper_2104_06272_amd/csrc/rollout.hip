@@ -765,13 +765,6 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         }
     }
 
-#ifdef ANK_PHASE_TIMING
-    long long ph[6] = {0, 0, 0, 0, 0, 0}, c0, c1;
-#define PH(i) do { c1 = clock64(); ph[i] += c1 - c0; c0 = c1; } while (0)
-    c0 = clock64();
-#else
-#define PH(i) do { } while (0)
-#endif
     for (int t = 0; t <= T; ++t) {
         const size_t tb = (size_t)t * B + b;
         if (owner) {
@@ -798,17 +791,14 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
             }
         }
         __syncthreads();
-        PH(0);
         const bool keep = t < T && a.keep_acts;
         float* g0 = keep ? tp.act[0] + ((size_t)t * B + b0) * RK : nullptr;
         first_layer<ENV, TM * RK / 1024, false>(a, obs, bufA, ldx, tid, g0, w1);
         __syncthreads();
-        PH(1);
         float* g1 = keep ? tp.act[1] + ((size_t)t * B + b0) * RN : nullptr;
         if (M32) resident_m32<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
         else resident_m16<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
         __syncthreads();
-        PH(2);
         heads_pipe<4, HL>(bufB, ldx, whs, ldw, bhs, heads, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
         // idle during the head chains, produce them now
@@ -821,7 +811,6 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
             }
         }
         __syncthreads();
-        PH(3);
         if (owner) {
             const float4 h0 = ld4(heads + tid * NHP);
             const float4 h1 = NHP == 8 ? ld4(heads + tid * NHP + 4) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -866,14 +855,7 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
                 tp.tr_done[tb] = (uint8_t)done;
             }
         }
-        PH(4);
     }
-#ifdef ANK_PHASE_TIMING
-    if (tid == 0 && (blockIdx.x == 0 || blockIdx.x == 100))
-        printf("block %d phases (cycles/step): observe %lld first %lld mfma %lld heads %lld sample %lld\n", (int)blockIdx.x,
-               ph[0] / (T + 1), ph[1] / (T + 1), ph[2] / (T + 1), ph[3] / (T + 1), ph[4] / (T + 1));
-#endif
-#undef PH
     if (!REPLAY && owner) {
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }

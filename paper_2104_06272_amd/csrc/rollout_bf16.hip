@@ -33,11 +33,6 @@ namespace ank {
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-#ifdef ANK_EXP_NOSTORE
-constexpr bool EXP_NOSTORE = true;
-#else
-constexpr bool EXP_NOSTORE = false;
-#endif
 constexpr int BTM = 64;                 // envs per workgroup
 constexpr int BWG = 512;                // threads per workgroup: two wavefronts per SIMD
 constexpr int BOBS = 12;                // observation words per env (as in the fp32 kernels)
@@ -357,13 +352,6 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
         }
     }
 
-#ifdef ANK_PHASE_TIMING
-    long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, c0, c1;
-#define PH(i) do { c1 = clock64(); ph[i] += c1 - c0; c0 = c1; } while (0)
-    c0 = clock64();
-#else
-#define PH(i) do { } while (0)
-#endif
     const int tid_outer = tid;
     for (int t = 0; t <= T; ++t) {
         // everything derived from the thread index is recomputed every step from a value the compiler
@@ -400,7 +388,6 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             }
         }
         __syncthreads();
-        PH(0);
         const bool keep = t < T && a.keep_acts;
         const size_t g8 = ((size_t)t * B + b0) >> 3;             // first sample group of this tile
         // the last wavefront draws this step's random numbers while it waits for its weight rows
@@ -423,7 +410,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                         r1[ENV == ENV_CATCH ? m : 0] = *reinterpret_cast<const uint32_t*>(w1 + (size_t)obs[(e0 + m) * BOBS + 1] * H1 + c);
                 }
             }
-            uint16_t* actP = (keep && !EXP_NOSTORE) ? reinterpret_cast<uint16_t*>(tp.act[0]) : nullptr;
+            uint16_t* actP = keep ? reinterpret_cast<uint16_t*>(tp.act[0]) : nullptr;
 #pragma unroll
             for (int m0 = 0; m0 < EPT; m0 += 8) {
                 float v[8][2];
@@ -468,7 +455,6 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             }
         }
         __syncthreads();
-        PH(1);
         uint16_t* cur = bufA;
         uint16_t* nxt = bufB;
         if (UNI) {
@@ -478,7 +464,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             for (int l = 1; l < L; ++l) {
                 bf16_layer_stream<NTU>(cur, nxt, ldx, a.wt + a.net.w_off[l], l + 1 < L ? a.wt + a.net.w_off[l + 1] : nullptr,
                                        a.theta + a.net.b_off[l], H1, H1, wave, lane,
-                                       (keep && !EXP_NOSTORE) ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8, w0, w1);
+                                       keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8, w0, w1);
                 __syncthreads();
                 uint16_t* tmp = cur; cur = nxt; nxt = tmp;
             }
@@ -486,12 +472,11 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             for (int l = 1; l < L; ++l) {
                 const int K = a.net.dims[l], N = a.net.dims[l + 1];
                 run_bf16_layer(cur, nxt, ldx, a.wt + a.net.w_off[l], a.theta + a.net.b_off[l], K, N, wave, lane,
-                               (keep && !EXP_NOSTORE) ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8);
+                               keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8);
                 __syncthreads();
                 uint16_t* tmp = cur; cur = nxt; nxt = tmp;
             }
         }
-        PH(3);
         // ---- heads: wavefront (tile, quarter) sums one quarter of the last layer for 32 envs ----
         {
             const int l32 = lane & 31, kg = lane >> 5;
@@ -521,7 +506,6 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             }
         }
         __syncthreads();
-        PH(4);
         if (owner) {
             float hv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -569,14 +553,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                 tp.tr_done[tb] = (uint8_t)done;
             }
         }
-        PH(5);
     }
-#ifdef ANK_PHASE_TIMING
-    if (tid == 0 && (blockIdx.x == 0 || blockIdx.x == 100))
-        printf("block %d phases (cycles/step): observe %lld first %lld layers %lld heads %lld sample %lld\n", (int)blockIdx.x,
-               ph[0] / (T + 1), ph[1] / (T + 1), ph[3] / (T + 1), ph[4] / (T + 1), ph[5] / (T + 1));
-#endif
-#undef PH
     if (!REPLAY && owner) {
         tp.s0[b] = st.s0;
         if (ENV == ENV_PENDULUM) { tp.f0[b] = st.f0; tp.f1[b] = st.f1; }

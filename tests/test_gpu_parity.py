@@ -91,11 +91,7 @@ def test_lockstep(gpu, orc, case):
         PT.assert_final_state_equal(g, o, kind)
         # hidden activations kept for the update equal the oracle's forward on the same states
         for (t, b) in ((0, 0), (g.T - 1, g.B - 1), (g.T // 2, g.B // 3)):
-            keep = (o.state_i[b].copy(), o.state_f[b].copy())
-            o.state_i[b] = o.tr_state_i[t, b]; o.state_f[b] = o.tr_state_f[t, b]
-            x = o.observe(b)
-            o.state_i[b], o.state_f[b] = keep
-            head, acts = o.forward(x, want_acts=True)
+            head, acts = PT.oracle_forward_at(o, t, b)
             if tr["act"]:                 # one-layer nets keep no activations: the update rebuilds the layer
                 got = np.concatenate([a[t, b] for a in tr["act"]])
                 assert np.array_equal(got, acts), "stored activations differ"
@@ -262,23 +258,11 @@ def _forced_lockstep(gpu, orc, cfg, seed, updates, sel=None, learn=True):
         g.rollout()
         tr = g.trajectory()
         o.rollout(forced_head=tr["head"], sel=sel)
-        PT.assert_rollout_equal(g, o, kind, sel=sel, head_tol=TOL_BF16)
+        PT.assert_rollout_equal(g, o, kind, sel=sel, forced=True)
         PT.assert_final_state_equal(g, o, kind, sel=sel)
-        # (1) head outputs and stored activations against the oracle's own forward on the same states
-        scale = max(1e-3, float(np.abs(tr["head"]).max()))
-        cols = range(g.B) if sel is None else list(sel)
-        worst = 0.0
-        for (t, b) in [(0, cols[0]), (g.T - 1, cols[-1]), (g.T // 2, cols[len(cols) // 2]), (g.T, cols[1])]:
-            save = (o.state_i[b].copy(), o.state_f[b].copy())
-            o.state_i[b] = o.tr_state_i[t, b]; o.state_f[b] = o.tr_state_f[t, b]
-            x = o.observe(b)
-            o.state_i[b], o.state_f[b] = save
-            head, acts = o.forward(x, want_acts=True)
-            worst = max(worst, float(np.abs(head - tr["head"][t, b]).max()) / scale)
-            if t < g.T:
-                got = np.concatenate([a[t, b] for a in tr["act"]])
-                assert np.abs(got - acts).max() <= 2 ** -6 * max(1.0, float(np.abs(acts).max())), "activations differ"
-        assert worst <= TOL_BF16, f"head outputs differ by {worst:.3e} of their scale"
+        # (1) head outputs and stored activations against the oracle's own forward on the same states, at every
+        # step of every compared env
+        worst = PT.assert_heads_close(g, o, tr, TOL_BF16, sel=sel)
         if learn:
             g.learn(); o.learn()
             e_g, e_p = PT.assert_learn_close(g, o, TOL_BF16)
@@ -295,6 +279,50 @@ def test_bf16_matrix_core_path(gpu, orc, case):
     cfg, seed, updates = BF16_CASES[case]
     say(f"[bf16] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
     _forced_lockstep(gpu, orc, cfg, seed, updates)
+
+
+@pytest.mark.parametrize("B,T", [(1024, 32), (8192, 2)])
+def test_bf16_benchmark_widths_steady_state(gpu, orc, B, T):
+    """The maze workload's own layer widths (768-512-512-512, bf16) with enough samples that every update kernel
+    runs its steady-state loop, not just its prologue.  B = 1024, T = 32: the weights-resident dX kernel walks
+    >= 4 stages of 32 samples per workgroup (its ring holds rows two stages and the mask one stage ahead), the
+    256 x 256-tile dW kernel >= 8 LDS stages of 64 samples per chunk on the hidden layers (double-buffered, next
+    step prefetched) and >= 4 on the agent plane.  B = 8192, T = 2: the wall-plane product, whose rows are the
+    2 B time-summed ones, reaches >= 4 stages per chunk in several chunks, and the time sum runs at a large B.
+    Logit-forced lockstep over all envs; the oracle's update is spread over threads by sample range."""
+    cfg = variant("maze_16384", B=B, T=T)
+    say(f"[bf16 steady state] B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+    g = gpu.Anakin(cfg, seed=9); o = orc.Oracle(cfg, seed=9)
+    M = B * T
+    plan = g.plan()
+    say(f"  plan {plan}")
+    assert plan["bf16_matrix_path"] == 1
+    if T == 32:
+        assert all(plan["dx_rows"][l] >= 4 * 32 for l in (1, 2)), "dX kernel: fewer than 4 stages per workgroup"
+        assert all(M // plan["splits"][l] >= 8 * 64 for l in (1, 2)), "dW kernel: fewer than 8 LDS stages per chunk"
+        assert M // plan["splits"][0] >= 4 * 64, "agent-plane product: fewer than 4 LDS stages per chunk"
+    else:
+        assert plan["splits_walls"] > 1 and 2 * B // plan["splits_walls"] >= 4 * 64, "wall-plane product: fewer than 4 LDS stages per chunk"
+    PT.assert_same_init(g, o, "maze")
+    g.step()                                     # the compared update starts from non-initial parameters and moments
+    PT.sync_oracle_from_gpu(g, o)
+    si, sf = g.get_env_state()
+    o.state_i[:] = si
+    o.global_step = g.global_step
+    g.rollout()
+    tr = g.trajectory()
+    o.rollout(forced_head=tr["head"])
+    PT.assert_rollout_equal(g, o, "maze", forced=True)
+    PT.assert_final_state_equal(g, o, "maze")
+    rng = np.random.default_rng(9)
+    sel = np.unique(np.concatenate([[0, 63, 64, B - 1], rng.integers(0, B, 12 if T == 32 else 60)])).astype(np.int32)
+    worst = PT.assert_heads_close(g, o, tr, TOL_BF16, sel=sel)
+    say(f"  head err {worst:.2e} over {sel.size} envs x {g.T + 1} steps; update on the oracle ...")
+    g.learn()
+    PT.oracle_learn_parallel(o, workers=16)
+    e_g, e_p = PT.assert_learn_close(g, o, TOL_BF16)
+    say(f"  gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
+    g.close()
 
 
 def test_bf16_reference_mode_is_exact(gpu, orc):
@@ -347,7 +375,7 @@ def test_n_updates_per_unroll(gpu, orc, case):
         g.rollout(); o.rollout()
         PT.assert_rollout_equal(g, o, kind)
         g.learn(); o.learn_n(N)
-        e_g, e_p = PT.assert_learn_close(g, o, tol)
+        e_g, e_p = PT.assert_learn_close(g, o, tol, n_updates=N)
         say(f"  unroll {u}: gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
     with pytest.raises(gpu.AnakinError):
         g.set_updates_per_unroll(3 if cfg["T"] % 3 else 5)
@@ -368,7 +396,7 @@ def test_n_updates_per_unroll_bf16(gpu, orc):
     tr = g.trajectory()
     o.rollout(forced_head=tr["head"])
     g.learn(); o.learn_n(3)
-    PT.assert_learn_close(g, o, TOL_BF16)
+    PT.assert_learn_close(g, o, TOL_BF16, n_updates=3)
     g.close()
 
 
@@ -401,6 +429,12 @@ def test_decoupled_lockstep(gpu, orc, case):
     say(f"[decoupled] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
     g = gpu.Anakin(cfg, seed=seed)
     o = orc.Oracle(cfg, seed=seed)
+    if case == "catch_small":
+        # the actor on a stream of the caller's instead of one the library creates
+        import torch
+        with pytest.raises(gpu.AnakinError):
+            g.set_actor_stream(g.stream)            # must differ from the handle's own stream
+        g.set_actor_stream(torch.cuda.Stream())
     off_policy = 0
     for k in range(steps):
         PT.sync_oracle_from_gpu(g, o)
@@ -451,7 +485,7 @@ def test_decoupled_bf16_forced_lockstep(gpu, orc, case):
         g.step_decoupled()
         tr = g.trajectory()
         o.step_decoupled(forced_head=tr["head"])
-        PT.assert_rollout_equal(g, o, kind, head_tol=TOL_BF16)
+        PT.assert_rollout_equal(g, o, kind, forced=True)
         PT.assert_final_state_equal(g, o, kind)
         # the actor's head outputs are the forward pass of the parameters from before this step's update
         learner = o.theta.copy()
@@ -509,7 +543,10 @@ def test_pathwise_lockstep(gpu, orc, case):
         g.learn(); o.learn_pathwise()
         tr = g.trajectory()
         tr["adv"] = adv_zero                 # the score-function advantage is not used on either side
-        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=(rew, done))
+        # 49 152 path-only samples whose terms nearly cancel (the sums are ~1e-5 of the terms): binary32 summation
+        # noise reaches a few tol of a region's largest entry in single elements, the norms stay within tol
+        ef = 5.0 if case == "pendulum_128_B8192" else 1.0
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=(rew, done), elem_factor=ef)
         say(f"  update {u}: grad rel {e_g:.2e}, param rel {e_p:.2e}, -mean reward {o.loss[1]:+.4f}, |path dhead| {np.abs(ph).max():.3e}")
     if cfg["env"]["max_steps"] < cfg["T"]:
         assert o.tr_done.sum() > 0                   # the adjoint was cut inside the unroll
@@ -569,6 +606,8 @@ def test_determinism_and_resume(gpu):
 def test_error_paths(gpu):
     cfg = variant("catch_small", B=64)
     g = gpu.Anakin(cfg, seed=0)
+    m0 = g.metrics()                                # before the first update: zeros, not whatever the workspace held
+    assert m0["nonfinite"] == 0 and m0["loss"] == 0.0 and m0["reward_sum"] == 0.0 and m0["episodes"] == 0
     with pytest.raises(gpu.AnakinError) as e:
         g.learn()
     assert e.value.code == gpu.E_STATE

@@ -1126,3 +1126,45 @@ def test_bf16_gradient_vs_finite_differences(orc, kind):
         tp[i] += hstep; tm[i] -= hstep
         alt[i] = (_np_surrogate_frozen(o, tp, obs_q, zero, pol) - _np_surrogate_frozen(o, tm, obs_q, zero, pol)) / (2 * hstep)
     assert np.linalg.norm(g - alt) / np.linalg.norm(alt) > 1e-4
+
+
+def test_relu_side_is_taken_from_the_binary32_forward(orc):
+    """A pre-activation within rounding of zero: the update differentiates the pass that acted, which ran in
+    binary32, so its ReLU side is the binary32 one even where the binary64 sum lands on the other side.  Two
+    hand-built units on the pendulum observation (1, 0, theta_dot) at theta = 0:
+      unit 0: 1 - 2^-26 - (1 - 2^-26): binary32 rounds the first sum to 1 and ends at +2^-26 (on), binary64 at 0
+      unit 1: 1 + 2^-25 - 1:           binary32 rounds the first sum to 1 and ends at 0 (off),     binary64 at +2^-25
+    """
+    cfg = tiny("pendulum", hidden=(2,), B=2, T=1)
+    o = orc.Oracle(cfg, seed=1)
+    rng = np.random.default_rng(2)
+    o.theta[:] = rng.standard_normal(o.P).astype(np.float32) * 0.3
+    Ws, bs, Wh, bh = _unpack(o)                      # views into o.theta
+    Ws[0][:, 0] = (-2.0 ** -26, 0.0, -8193.0 / 8192.0); bs[0][0] = 1.0
+    Ws[0][:, 1] = (2.0 ** -25, 0.0, -1.0); bs[0][1] = 1.0
+    # unit 0 is probed at theta_dot = 8191/8192 (env 0), unit 1 at theta_dot = 1 (env 1)
+    o.state_f[:] = [[0.0, 8191.0 / 8192.0], [0.0, 1.0]]
+    o.state_i[:] = 0
+    x0, x1 = o.observe(0), o.observe(1)
+    assert np.array_equal(x0, np.array([1.0, 0.0, 8191.0 / 8192.0], np.float32)) and np.array_equal(x1, np.array([1.0, 0.0, 1.0], np.float32))
+    _, a0 = o.forward(x0, want_acts=True); _, a1 = o.forward(x1, want_acts=True)
+    assert a0[0] == np.float32(2.0 ** -26) and a1[1] == 0.0                     # binary32 sides: on, off
+    z64 = lambda x, j: float(bs[0][j]) + sum(float(x[k]) * float(Ws[0][k, j]) for k in range(3))
+    assert z64(x0, 0) == 0.0 and z64(x1, 1) == 2.0 ** -25                       # binary64 sides: off, on
+    o.rollout()
+    o.ret[:] = rng.standard_normal(o.ret.shape); o.adv[:] = rng.standard_normal(o.adv.shape)
+    # per-sample head gradients from single-sample calls: dhead = gradient of the head bias
+    regions, _ = __import__("parity").param_regions(cfg)
+    R = dict(regions)
+    grads = []
+    for b in range(2):
+        o.loss_and_grad(b, b + 1)
+        grads.append(o.grad.astype(np.float64).copy())
+    for b, unit, expect_on in ((0, 0, True), (1, 1, False)):
+        g = grads[b]
+        dhead = g[R["bh"]]
+        assert np.abs(dhead).max() > 1e-3
+        want = float(Wh[unit].astype(np.float64) @ dhead) if expect_on else 0.0
+        got = g[R["b1"]][unit]
+        assert abs(got - want) <= 1e-6 * max(abs(want), 1e-3), (b, unit, got, want)
+        assert (got != 0.0) == expect_on
