@@ -543,10 +543,7 @@ def test_pathwise_lockstep(gpu, orc, case):
         g.learn(); o.learn_pathwise()
         tr = g.trajectory()
         tr["adv"] = adv_zero                 # the score-function advantage is not used on either side
-        # 49 152 path-only samples whose terms nearly cancel (the sums are ~1e-5 of the terms): binary32 summation
-        # noise reaches a few tol of a region's largest entry in single elements, the norms stay within tol
-        ef = 5.0 if case == "pendulum_128_B8192" else 1.0
-        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=(rew, done), elem_factor=ef)
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=(rew, done))
         say(f"  update {u}: grad rel {e_g:.2e}, param rel {e_p:.2e}, -mean reward {o.loss[1]:+.4f}, |path dhead| {np.abs(ph).max():.3e}")
     if cfg["env"]["max_steps"] < cfg["T"]:
         assert o.tr_done.sum() > 0                   # the adjoint was cut inside the unroll
