@@ -131,6 +131,21 @@ int32_t anakin_rollout(anakin_t* h);
  * forward pass).  ANAKIN_E_STATE without a preceding rollout.  Asynchronous. */
 int32_t anakin_learn(anakin_t* h);
 
+/* anakin_learn for callers that cannot allocate device memory or hand over a larger workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same update on the same stored
+ * trajectory with the same result, but the scratch of the backward pass (per-sample head gradients, dZ_l,
+ * split-K partial sums) is placed in a static device array of ANAKIN_STATIC_SCRATCH_BYTES that the library holds
+ * once per GPU for the life of the process, instead of in the caller's workspace; inputs and outputs (trajectory,
+ * parameters, optimiser state, gradient, metrics) stay where anakin_learn has them.  Calls no hipMalloc / hipFree
+ * and no allocating routine.  ANAKIN_E_WORKSPACE_TOO_SMALL (with the bytes needed in anakin_last_error) when the
+ * configuration's update needs more than the array holds; ANAKIN_E_STATE while per-kernel timing is on (it creates
+ * events) or without a stored trajectory.  The array is shared by every handle on a GPU and keeps the last call's
+ * contents (nothing in it needs clearing: every byte is written before it is read within one update): calls that
+ * overlap in time on one GPU -- different handles on different streams -- race and must be serialised by the
+ * caller.  Asynchronous like anakin_learn. */
+#define ANAKIN_STATIC_SCRATCH_BYTES (64u << 20)
+int32_t anakin_learn_static(anakin_t* h);
+
 /* anakin_rollout followed by anakin_learn: Anakin's minimal unit of computation (paper section 3.1 and
  * figure 2 top: T interactions, then one update), the timed unit.  Asynchronous. */
 int32_t anakin_step(anakin_t* h);

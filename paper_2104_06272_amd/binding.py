@@ -17,6 +17,7 @@ OK = 0
 E_INVALID_ARG, E_BAD_CONFIG, E_WORKSPACE_TOO_SMALL, E_MISALIGNED, E_HIP, E_NONFINITE, E_STATE = -1, -2, -3, -4, -5, -6, -7
 MODE_VALU_GEMM, MODE_CANONICAL_ACTING, MODE_STREAM_WEIGHTS = 1, 2, 4
 PG_SCORE_FUNCTION, PG_PATHWISE = 0, 1
+STATIC_SCRATCH_BYTES = 64 << 20
 
 ENV_KINDS = {"catch": 0, "pendulum": 1, "maze": 2}
 POLICIES = {"categorical": 0, "tanh_gaussian": 1}
@@ -61,7 +62,7 @@ class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("calls", C.c_int64), ("total_ms", C.c_double)]
 
 
-EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_step", "anakin_step_decoupled", "anakin_set_actor_stream",
+EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_learn", "anakin_learn_static", "anakin_step", "anakin_step_decoupled", "anakin_set_actor_stream",
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
@@ -196,6 +197,9 @@ class Anakin:
 
     def learn(self):
         self._chk(self.L.anakin_learn(self.h))
+
+    def learn_static(self):
+        self._chk(self.L.anakin_learn_static(self.h))
 
     def step(self):
         self._chk(self.L.anakin_step(self.h))

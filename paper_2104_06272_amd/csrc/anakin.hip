@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 #include <vector>
 #include <utility>
@@ -14,6 +15,32 @@
 using namespace ank;
 
 static thread_local std::string g_create_error;
+
+// ---- the library's own update scratch, for callers that cannot allocate (anakin_learn_static) --------------
+// One array per GPU (every device that loads the library holds its own copy until the process ends).  In host
+// code the array's name is only a stand-in: its device address is asked for once per device, with that device
+// current, and kept here; kernels receive that address like any other scratch pointer.
+static __device__ __align__(256) unsigned char scratch[ANAKIN_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[MAX_DEVICES];
+
+static hipError_t resolve_static_scratch(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return hipSuccess;
+    int current = -1;
+    hipError_t e = hipGetDevice(&current);
+    if (e != hipSuccess) return e;
+    if (current != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (current != device) (void)hipSetDevice(current);
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = p;
+    return hipSuccess;
+}
 
 namespace ank { void fill_rollout_args(anakin* h, RolloutArgs& a); }
 
@@ -87,24 +114,18 @@ static int pick_divisor_splits(int M, int quantum, int cap)
     return M % quantum == 0 ? 1 : 0;
 }
 
-static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int* splits, int splits_w, int head_fan, int loss_blocks, Layout& L)
+// The scratch of the backward pass: per-sample head gradients, dZ_l, split-K partial sums, first-stage partials
+// of the head gradient.  Nothing here outlives one update and every byte is written before it is read.  Offsets
+// are placed from `base` (a workspace offset, or SCRATCH_TAG for the static array); returns the bytes taken.
+static size_t carve_update_scratch(const EnvDims& ed, const NetShape& ns, int B, int T, const int* splits, int splits_w, int head_fan,
+                                   Layout& L, size_t base)
 {
     size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
-    const size_t P = (size_t)ns.P, n = (size_t)B, tn = (size_t)T * B, t1n = (size_t)(T + 1) * B;
-    L.theta = take(P * 4); L.grad = take(P * 4); L.m = take(P * 4); L.v = take(P * 4);
-    L.w_bf16 = take(ns.bf16 ? P * 2 : 0); L.wt_bf16 = take(ns.bf16 ? P * 2 : 0);
-    L.theta0 = take(P * 4); L.w0_bf16 = take(ns.bf16 ? P * 2 : 0);
-    L.w_src = L.theta; L.w16_src = L.w_bf16;
-    L.s0 = take(n * 4); L.f0 = take(n * 4); L.f1 = take(n * 4); L.walls = take(n * 8 * 4);
-    L.tr_s0 = take(t1n * 4); L.tr_f0 = take(t1n * 4); L.tr_f1 = take(t1n * 4);
-    L.tr_act = take(tn); L.tr_eps = take(tn * 4); L.tr_actf = take(tn * 4);
-    L.tr_rew = take(tn * 4); L.tr_done = take(tn);
-    L.tr_val = take(t1n * 4); L.tr_head = take(t1n * ns.NHP * 4);
-    L.adv = take(tn * 4); L.ret = take(tn * 4); L.dhead = take(tn * ns.NHP * 4);
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return base + o; };
+    const size_t tn = (size_t)T * B;
+    L.dhead = take(tn * ns.NHP * 4);
     for (int l = 0; l < MAX_LAYERS; ++l) {
         const size_t w = l < ns.L ? (size_t)ns.dims[l + 1] : 0;
-        L.act[l] = take(tn * w * 4);
         L.dz[l] = take(tn * w * 4);
     }
     for (int l = 0; l < MAX_REGIONS; ++l) {
@@ -121,6 +142,29 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
         L.part[l] = take(floats * 4);
     }
     L.head_stage = take(head_fan > 1 ? (size_t)splits[ns.L] * head_fan * ((size_t)ns.dims[ns.L] * ns.NH + ns.NH) * 4 : 0);
+    return off;
+}
+
+static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int* splits, int splits_w, int head_fan, int loss_blocks, Layout& L)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    const size_t P = (size_t)ns.P, n = (size_t)B, tn = (size_t)T * B, t1n = (size_t)(T + 1) * B;
+    L.theta = take(P * 4); L.grad = take(P * 4); L.m = take(P * 4); L.v = take(P * 4);
+    L.w_bf16 = take(ns.bf16 ? P * 2 : 0); L.wt_bf16 = take(ns.bf16 ? P * 2 : 0);
+    L.theta0 = take(P * 4); L.w0_bf16 = take(ns.bf16 ? P * 2 : 0);
+    L.w_src = L.theta; L.w16_src = L.w_bf16;
+    L.s0 = take(n * 4); L.f0 = take(n * 4); L.f1 = take(n * 4); L.walls = take(n * 8 * 4);
+    L.tr_s0 = take(t1n * 4); L.tr_f0 = take(t1n * 4); L.tr_f1 = take(t1n * 4);
+    L.tr_act = take(tn); L.tr_eps = take(tn * 4); L.tr_actf = take(tn * 4);
+    L.tr_rew = take(tn * 4); L.tr_done = take(tn);
+    L.tr_val = take(t1n * 4); L.tr_head = take(t1n * ns.NHP * 4);
+    L.adv = take(tn * 4); L.ret = take(tn * 4);
+    for (int l = 0; l < MAX_LAYERS; ++l) {
+        const size_t w = l < ns.L ? (size_t)ns.dims[l + 1] : 0;
+        L.act[l] = take(tn * w * 4);
+    }
+    off += carve_update_scratch(ed, ns, B, T, splits, splits_w, head_fan, L, off);
     L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
     L.loss_part = take((size_t)(loss_blocks + T) * 8 * 4);     // + T: with N updates per unroll every chunk rounds its block count up
     // decoupled steps: behaviour parameters, second record set, the learner's forward results
@@ -335,12 +379,24 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->pathwise = 0;
     h->traj_decoupled = 0; h->actor_stream = nullptr; h->actor_stream_owned = 0; h->ev_fork = nullptr; h->ev_join = nullptr;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
+    h->scratch = nullptr;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ed, ns, B, T, h->splits, &h->splits_w, &h->head_fan, &h->loss_blocks);
     carve(ed, ns, B, T, h->splits, h->splits_w, h->head_fan, h->loss_blocks, h->lay);
     if (h->lay.total > workspace_bytes) {
         g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";
         delete h; return ANAKIN_E_WORKSPACE_TOO_SMALL;
+    }
+    {
+        // the device the workspace lives on (the current one if the runtime cannot tell), and this device's copy
+        // of the static scratch array: resolved here, at set-up, so that anakin_learn_static has nothing left to do
+        int dev = 0;
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, d_workspace) == hipSuccess) dev = attr.device;
+        else { (void)hipGetLastError(); if (hipGetDevice(&dev) != hipSuccess) dev = 0; }
+        h->device = dev;
+        const hipError_t es = resolve_static_scratch(dev);
+        if (es != hipSuccess) { g_create_error = std::string("hipGetSymbolAddress(static scratch): ") + hipGetErrorString(es); delete h; return ANAKIN_E_HIP; }
     }
     h->n_updates = 1;
     h->TM = rollout_pick_tile(ns, B);
@@ -561,6 +617,32 @@ extern "C" int32_t anakin_learn(anakin_t* h)
     if (rc != ANAKIN_OK) return rc;
     h->have_traj = 0;
     return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_learn_static(anakin_t* h)
+{
+    NEED(h);
+    if (h->prof_on) { h->err = "anakin_learn_static: switch per-kernel timing off first (it creates events)"; return ANAKIN_E_STATE; }
+    Layout probe = h->lay;
+    const size_t need = carve_update_scratch(h->env, h->net, h->B, h->T, h->splits, h->splits_w, h->head_fan, probe, SCRATCH_TAG);
+    if (need > (size_t)ANAKIN_STATIC_SCRATCH_BYTES) {
+        h->err = "anakin_learn_static: the update of this configuration needs " + std::to_string(need) + " bytes of scratch, the static array holds " +
+                 std::to_string((size_t)ANAKIN_STATIC_SCRATCH_BYTES) + ": use anakin_learn, or fewer envs / a shorter unroll / a narrower net";
+        return ANAKIN_E_WORKSPACE_TOO_SMALL;
+    }
+    void* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        base = (h->device >= 0 && h->device < MAX_DEVICES) ? g_scratch_ptr[h->device] : nullptr;
+    }
+    if (!base) { h->err = "anakin_learn_static: no static scratch on this handle's device"; return ANAKIN_E_STATE; }
+    const Layout keep = h->lay;
+    h->lay = probe;                                   // the same layout with the update's scratch inside the static array
+    h->scratch = static_cast<char*>(base);
+    const int32_t rc = anakin_learn(h);
+    h->lay = keep;
+    h->scratch = nullptr;
+    return rc;
 }
 
 extern "C" int32_t anakin_set_policy_gradient(anakin_t* h, int32_t kind)

@@ -133,6 +133,8 @@ struct anakin {
     int mode;
     char* ws;
     size_t ws_bytes;
+    char* scratch;                // base of tagged offsets (see SCRATCH_TAG); null outside anakin_learn_static
+    int device;                   // the device the workspace lives on
     hipStream_t stream;
     ank::Layout lay;
     int TM;                       // envs per workgroup in the vector-ALU rollout kernel
@@ -165,7 +167,13 @@ struct anakin {
 
 namespace ank {
 
-template <class T> inline T* at(const anakin* h, size_t off) { return reinterpret_cast<T*>(h->ws + off); }
+// An offset with this bit set is relative to the handle's update-scratch base instead of the workspace base
+// (anakin_learn_static points the backward pass's scratch at the library's own static device array).
+constexpr size_t SCRATCH_TAG = (size_t)1 << 62;
+template <class T> inline T* at(const anakin* h, size_t off)
+{
+    return reinterpret_cast<T*>((off & SCRATCH_TAG) ? h->scratch + (off & ~SCRATCH_TAG) : h->ws + off);
+}
 
 // per-kernel timing: brackets one launch with two events when profiling is on
 struct ProfScope {

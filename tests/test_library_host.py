@@ -77,7 +77,7 @@ def test_create_checks_workspace_before_any_device_call(lib):
     assert lib.anakin_create(C.byref(h), C.byref(env), C.byref(net), 64, 20, 0, C.c_void_p(0x1000), 4096, None) == binding.E_WORKSPACE_TOO_SMALL
     assert b"need" in lib.anakin_last_error(None)
     assert lib.anakin_create(None, C.byref(env), C.byref(net), 64, 20, 0, None, 0, None) == binding.E_INVALID_ARG
-    for fn in (lib.anakin_rollout, lib.anakin_learn, lib.anakin_step, lib.anakin_destroy):
+    for fn in (lib.anakin_rollout, lib.anakin_learn, lib.anakin_learn_static, lib.anakin_step, lib.anakin_destroy):
         assert fn(None) == binding.E_INVALID_ARG
 
 

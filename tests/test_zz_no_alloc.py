@@ -1,0 +1,86 @@
+"""anakin_learn_static -- the update with its backward scratch in the library's static device array, for callers
+that cannot allocate -- against anakin_learn on the same stored unroll: called through the C ABI, two calls in a
+row, the second on a smaller input.  Same kernels on the same data in the same order, so the results must agree
+bit for bit (which is inside every tolerance of the parity tests)."""
+import numpy as np
+import pytest
+
+from paper_2104_06272_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from paper_2104_06272_amd import binding
+    binding.load()
+    return binding
+
+
+def _pair(gpu, cfg, seed, steps=2):
+    a = gpu.Anakin(cfg, seed=seed); b = gpu.Anakin(cfg, seed=seed)
+    for _ in range(steps):
+        a.rollout(); a.learn()
+        b.rollout(); b.learn_static()
+        a.synchronize(); b.synchronize()
+        assert np.array_equal(a.get_grads(), b.get_grads()), "gradients differ"
+        assert np.array_equal(a.get_params(), b.get_params()), "parameters differ"
+        ma, va, ta = a.get_opt_state(); mb, vb, tb = b.get_opt_state()
+        assert ta == tb and np.array_equal(ma, mb) and np.array_equal(va, vb), "Adam state differs"
+        xa, xb = a.metrics(), b.metrics()
+        assert xa == xb, "metrics differ"
+        ra, rb = a.trajectory(), b.trajectory()
+        assert np.array_equal(ra["adv"], rb["adv"]) and np.array_equal(ra["ret"], rb["ret"])
+    assert np.abs(a.get_grads()).max() > 0
+    a.close(); b.close()
+
+
+def _cfg(name, hidden=None, dtype=None, **kw):
+    cfg = W.get(name, **{k: v for k, v in kw.items() if k in ("B", "T")})
+    if hidden is not None:
+        cfg["net"]["hidden"] = list(hidden)
+    if dtype is not None:
+        cfg["net"]["dtype"] = dtype
+    return cfg
+
+
+def test_static_scratch_update_equals_workspace_update(gpu):
+    # two calls in a row on one size, then a smaller input: stale contents of the shared array must not matter
+    _pair(gpu, _cfg("catch_4096", B=256), seed=3)
+    _pair(gpu, _cfg("catch_small", B=64, T=7), seed=4)
+    # other kernel families through the same entry point: pendulum, the one-layer update, bf16 maze, N updates per unroll
+    _pair(gpu, _cfg("pendulum_8192", hidden=[64, 64], B=64, T=12), seed=5)
+    _pair(gpu, _cfg("catch_262144", B=512), seed=6)
+    cfg = _cfg("maze_16384", hidden=[128, 128], B=64, T=8)
+    _pair(gpu, cfg, seed=7)
+
+
+def test_static_scratch_with_several_updates_per_unroll(gpu):
+    cfg = _cfg("catch_4096", B=128, T=8)
+    a = gpu.Anakin(cfg, seed=1); b = gpu.Anakin(cfg, seed=1)
+    a.set_updates_per_unroll(2); b.set_updates_per_unroll(2)
+    a.rollout(); a.learn(); b.rollout(); b.learn_static()
+    assert np.array_equal(a.get_params(), b.get_params())
+    a.close(); b.close()
+
+
+def test_static_scratch_rejections(gpu):
+    # the headline workload's update needs ~170 MB of scratch: more than the static array holds
+    g = gpu.Anakin(W.get("catch_4096"), seed=0)
+    g.rollout()
+    with pytest.raises(gpu.AnakinError) as e:
+        g.learn_static()
+    assert e.value.code == gpu.E_WORKSPACE_TOO_SMALL and "bytes of scratch" in str(e.value)
+    g.learn()                                         # the stored unroll is still there for the ordinary update
+    g.close()
+    s = gpu.Anakin(W.get("catch_small"), seed=0)
+    with pytest.raises(gpu.AnakinError) as e:
+        s.learn_static()                              # no stored trajectory
+    assert e.value.code == gpu.E_STATE
+    s.profile(True)
+    s.rollout()
+    with pytest.raises(gpu.AnakinError):
+        s.learn_static()                              # per-kernel timing creates events
+    s.profile(False)
+    s.learn_static()
+    s.close()
