@@ -928,7 +928,8 @@ extern "C" int32_t anakin_get_plan(const anakin_t* h, anakin_plan* out)
     out->head_fan = h->head_fan;
     out->bf16_matrix_path = bf16_mfma(h) ? 1 : 0;
     if (out->bf16_matrix_path)
-        for (int l = 1; l < n.L; ++l) out->dx_rows[l] = bf16_dx_rows_per_workgroup(h->B * h->T, n.dims[l], n.dims[l + 1]);
+        for (int l = 1; l < n.L; ++l)
+            out->dx_rows[l] = bf16_dx_resident(n, h->B * h->T, l) ? bf16_dx_rows_per_workgroup(h->B * h->T, n.dims[l], n.dims[l + 1]) : 0;
     out->updates_per_unroll = h->n_updates;
     return ANAKIN_OK;
 }

@@ -154,8 +154,10 @@ __global__ __launch_bounds__(WG) void head_backward_bf16(const HeadBwdBf16Args a
                     }
                     const uint32_t p01 = cvt_pk_bf16(o[0], o[1]), p23 = cvt_pk_bf16(o[2], o[3]);
                     const int row = 32 * mt + 8 * g + 4 * kg;
-                    tile[(row + 0) * LDT + col] = (uint16_t)p01; tile[(row + 1) * LDT + col] = (uint16_t)(p01 >> 16);
-                    tile[(row + 2) * LDT + col] = (uint16_t)p23; tile[(row + 3) * LDT + col] = (uint16_t)(p23 >> 16);
+                    if (a.dzR) {
+                        tile[(row + 0) * LDT + col] = (uint16_t)p01; tile[(row + 1) * LDT + col] = (uint16_t)(p01 >> 16);
+                        tile[(row + 2) * LDT + col] = (uint16_t)p23; tile[(row + 3) * LDT + col] = (uint16_t)(p23 >> 16);
+                    }
                     if (live[jt]) {
                         const size_t G = (size_t)((m0 + 32 * mt) >> 3) + g;
                         *reinterpret_cast<uint2*>(a.dzP + (G * H + jw + 32 * jt + l32) * 8 + 4 * kg) = make_uint2(p01, p23);
@@ -164,12 +166,13 @@ __global__ __launch_bounds__(WG) void head_backward_bf16(const HeadBwdBf16Args a
             }
         }
         __syncthreads();
-        // row-major copy: 64 rows x 256 columns, 16-byte pieces
-        for (int i = tid; i < 64 * (WG / 8); i += WG) {
-            const int row = i / (WG / 8), c = (i % (WG / 8)) * 8;
-            if (jb + c < H)
-                *reinterpret_cast<uint4*>(a.dzR + (size_t)(m0 + row) * H + jb + c) = *reinterpret_cast<const uint4*>(&tile[row * LDT + c]);
-        }
+        // row-major copy (only where the tiled dX kernel reads it): 64 rows x 256 columns, 16-byte pieces
+        if (a.dzR)
+            for (int i = tid; i < 64 * (WG / 8); i += WG) {
+                const int row = i / (WG / 8), c = (i % (WG / 8)) * 8;
+                if (jb + c < H)
+                    *reinterpret_cast<uint4*>(a.dzR + (size_t)(m0 + row) * H + jb + c) = *reinterpret_cast<const uint4*>(&tile[row * LDT + c]);
+            }
     }
     __syncthreads();
     // dWh: rows j of the accumulator, columns k (hi parts) and 8+k (lo parts)
@@ -204,7 +207,8 @@ __global__ __launch_bounds__(WG) void head_backward_bf16(const HeadBwdBf16Args a
 // ---------------------------------------------------------------------------
 struct GemmNtBf16Args {
     int M, K, N;
-    const uint16_t* dyR;      // [M][N]
+    const uint16_t* dyR;      // [M][N] (tiled kernel), or null
+    const uint16_t* dyP;      // packed [M/8][N][8] (weights-resident kernel)
     const uint16_t* w16;      // [K][N]
     const uint16_t* hP;       // packed h_{l-1}: [M/8][K][8]
     uint16_t* dxR;            // [M][K], or null when no product below reads the row-major form
@@ -302,32 +306,31 @@ __global__ __launch_bounds__(WG) void gemm_nt_bf16(const GemmNtBf16Args a)
 }
 
 // ---------------------------------------------------------------------------
-// The same product as one persistent workgroup per compute unit with the weights in registers:
-// wavefront w of eight keeps the 32 output columns 32w.. of a 256-column block of W (NR/4
-// registers per lane, the B operand of every step), dY streams through LDS 32 rows at a time,
-// double buffered, and nothing but dY, the mask and the result crosses the memory system.  The
-// kernel is HBM-bound by design: about 5 bytes per output element.  NR: reduction length N (256 or
-// 512); K a multiple of 256; M a multiple of 32.
+// The same product as a persistent workgroup with the weights in registers: wavefront w of eight
+// keeps the 32 output columns 32w.. of a 256-column block of W (NR/4 registers per lane, the B
+// operand of every step), dY streams through LDS 32 rows at a time, double buffered, and nothing
+// but dY, the mask and the result crosses the memory system.  The kernel is HBM-bound by design:
+// about 4 bytes per output element.
+// dY is read in its sample-packed form, the one its producer writes for the dW product anyway, and
+// turned into rows on the way into LDS: a loader thread takes one 16-byte piece (eight samples of
+// one column) and stores its eight values into eight rows.  So dZ_l exists in one layout only, and
+// the result is written packed only.  NR: reduction length N (256 or 512); K a multiple of 256; M a
+// multiple of 32.
 // ---------------------------------------------------------------------------
 typedef uint32_t u32x4_l __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_l __attribute__((ext_vector_type(2)));
 constexpr int NRES_WG = 512;
 constexpr int NRES_RT = 32;             // rows per stage
-constexpr int NRES_LDT = 256 + 8;       // staging rows of the row-major copy
 
-template <int NR, bool ROWMAJOR>
+template <int NR>
 __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args a, const int rows_per_block)
 {
     constexpr int LD = NR + 8;                                   // row stride in bf16: eight rows cover all banks
     constexpr int KS = NR / 16;                                  // MFMA steps
-    constexpr int PPR = NR / 8;                                  // 16-byte pieces per row
-    constexpr int RPP = NRES_WG / PPR;                           // rows per loader pass
-    constexpr int NQ = NRES_RT / RPP;                            // loader passes per stage
+    constexpr int NQ = (NRES_RT / 8) * NR / NRES_WG;             // 16-byte pieces per thread and stage: 4 groups x NR columns
     extern __shared__ uint4 smem4[];
     uint16_t* As0 = reinterpret_cast<uint16_t*>(smem4);
     uint16_t* As1 = As0 + NRES_RT * LD;
-    uint16_t* Ts0 = As1 + NRES_RT * LD;
-    uint16_t* Ts1 = Ts0 + NRES_RT * NRES_LDT;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
     int rb_, cb_;
     xcd_map((int)blockIdx.x, (a.M + rows_per_block - 1) / rows_per_block, a.K / 256, rb_, cb_);   // column blocks of the same rows share dY in one L2
@@ -339,22 +342,28 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     bf8 wreg[KS];
 #pragma unroll
     for (int s2 = 0; s2 < KS; ++s2) wreg[s2] = *reinterpret_cast<const bf8*>(a.w16 + (size_t)i * NR + 16 * s2 + 8 * kg);
-    // loader: row RPP*q + tid/PPR (uniform in a wavefront when PPR >= 64), piece tid%PPR
-    const int lrow = tid / PPR, lc = (tid % PPR) * 8;
-    // Two register sets of staged rows: the rows of stage s + 2 are requested while stage s is computed, so a load
+    // loader: piece p = q * NRES_WG + tid is sample group p / NR of the stage, column p % NR
+    // Two register sets of staged pieces: those of stage s + 2 are requested while stage s is computed, so a load
     // has two stage times to come back (one stage is shorter than the memory latency under load, and this kernel
     // lives on the HBM roof).  The relu mask of stage s + 1 is requested one stage ahead for the same reason.
     u32x4_l stA[NQ], stB[NQ];
     auto fetch = [&](u32x4_l (&st)[NQ], int m0) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) st[q] = *reinterpret_cast<const u32x4_l*>(a.dyR + (size_t)(m0 + RPP * q + lrow) * NR + lc);
+        for (int q = 0; q < NQ; ++q) {
+            const int p = q * NRES_WG + tid;
+            st[q] = *reinterpret_cast<const u32x4_l*>(a.dyP + ((size_t)((m0 >> 3) + p / NR) * NR + p % NR) * 8);
+        }
     };
     auto store = [&](const u32x4_l (&st)[NQ], uint16_t* buf) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) *reinterpret_cast<u32x4_l*>(buf + (RPP * q + lrow) * LD + lc) = st[q];
+        for (int q = 0; q < NQ; ++q) {
+            const int p = q * NRES_WG + tid;
+            uint16_t* dst = buf + (8 * (p / NR)) * LD + p % NR;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[e * LD] = (uint16_t)(st[q][e >> 1] >> ((e & 1) * 16));
+        }
     };
     const uint32_t lane_off = (uint32_t)i * 8u + 4u * kg;        // inside a packed group of eight samples
-    const int cl = wave * 32 + l32;                              // column inside the 256-column block
     u32x2_l maskA[4], maskB[4];
     auto fetch_mask = [&](u32x2_l (&mk)[4], int m0) {
 #pragma unroll
@@ -368,8 +377,8 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     fetch(stA, clampm(m_begin + NRES_RT));                       // stage 1, stored at the end of stage 0
     fetch_mask(maskA, m_begin);
     __syncthreads();
-    // one stage: MFMAs on `cur`, epilogue with `mask`, then the staged rows `st` (stage s + 1) go to `nxt`
-    auto stage = [&](int m0, const uint16_t* cur, uint16_t* nxt, uint16_t* Ts, const u32x2_l (&mask)[4],
+    // one stage: MFMAs on `cur`, epilogue with `mask`, then the staged pieces `st_next` (stage s + 1) go to `nxt`
+    auto stage = [&](int m0, const uint16_t* cur, uint16_t* nxt, const u32x2_l (&mask)[4],
                      u32x4_l (&st_next)[NQ], u32x4_l (&st_fill)[NQ], u32x2_l (&mask_fill)[4]) {
         fetch(st_fill, clampm(m0 + 2 * NRES_RT));                // two stages ahead
         fetch_mask(mask_fill, clampm(m0 + NRES_RT));             // one stage ahead
@@ -389,28 +398,15 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
                 const float hv = bfu((uint16_t)((mask[g][q >> 1] >> ((q & 1) * 16)) & 0xffffu));
                 o[q] = hv > 0.0f ? acc[4 * g + q] : 0.0f;
             }
-            const uint32_t p01 = cvt_pk_bf16(o[0], o[1]), p23 = cvt_pk_bf16(o[2], o[3]);
-            const int rowl = 8 * g + 4 * kg;
-            if (ROWMAJOR) {
-                Ts[(rowl + 0) * NRES_LDT + cl] = (uint16_t)p01; Ts[(rowl + 1) * NRES_LDT + cl] = (uint16_t)(p01 >> 16);
-                Ts[(rowl + 2) * NRES_LDT + cl] = (uint16_t)p23; Ts[(rowl + 3) * NRES_LDT + cl] = (uint16_t)(p23 >> 16);
-            }
-            u32x2_l pv; pv[0] = p01; pv[1] = p23;
+            u32x2_l pv; pv[0] = cvt_pk_bf16(o[0], o[1]); pv[1] = cvt_pk_bf16(o[2], o[3]);
             *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
         }
         if (m0 + NRES_RT < m_end) store(st_next, nxt);
         __syncthreads();
-        // row-major copy of this stage: 32 rows x 256 columns, two 16-byte pieces per thread
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            if (!ROWMAJOR) break;
-            const int p = q * NRES_WG + tid, row = p >> 5, c = (p & 31) << 3;
-            *reinterpret_cast<u32x4_l*>(a.dxR + (size_t)(m0 + row) * a.K + i0 + c) = *reinterpret_cast<const u32x4_l*>(Ts + row * NRES_LDT + c);
-        }
     };
     for (int m0 = m_begin; m0 < m_end; m0 += 2 * NRES_RT) {
-        stage(m0, As0, As1, Ts0, maskA, stA, stB, maskB);
-        if (m0 + NRES_RT < m_end) stage(m0 + NRES_RT, As1, As0, Ts1, maskB, stB, stA, maskA);
+        stage(m0, As0, As1, maskA, stA, stB, maskB);
+        if (m0 + NRES_RT < m_end) stage(m0 + NRES_RT, As1, As0, maskB, stB, stA, maskA);
     }
 }
 
@@ -773,6 +769,15 @@ int bf16_dx_rows_per_workgroup(int M, int K, int N)
     return ((tiles + blocks - 1) / blocks) * NRES_RT;
 }
 
+// Whether the dX product of layer l + 1 (reading dZ_l, l >= 1) runs as the weights-resident kernel.  That kernel reads
+// and writes the packed layout only, so it is used only where the product below it (which reads its output) does too.
+bool bf16_dx_resident(const NetShape& n, int M, int l)
+{
+    if (l < 1 || l >= n.L) return false;
+    if (bf16_dx_rows_per_workgroup(M, n.dims[l], n.dims[l + 1]) == 0) return false;
+    return l == 1 || bf16_dx_resident(n, M, l - 1);
+}
+
 hipError_t launch_backward_bf16(anakin* h)
 {
     const Layout& L = h->lay;
@@ -782,6 +787,8 @@ hipError_t launch_backward_bf16(anakin* h)
     auto dzR = [&](int l) { return at<uint16_t>(h, L.dz[l]); };
     auto dzP = [&](int l) { return at<uint16_t>(h, L.dz[l]) + (size_t)M * n.dims[l + 1]; };
     auto actP = [&](int l) { return at<uint16_t>(h, L.act[l]); };
+    // dZ_l is kept sample-packed; the row-major copy exists only where the tiled dX kernel of layer l + 1 reads it
+    auto needs_rows = [&](int l) { return l >= 1 && !bf16_dx_resident(n, M, l); };
     {   // heads
         HeadBwdBf16Args a;
         a.M = M; a.H = n.dims[n.L]; a.NH = n.NH; a.NHP = n.NHP;
@@ -789,7 +796,7 @@ hipError_t launch_backward_bf16(anakin* h)
         a.rows = M / stage1;
         a.hP = actP(n.L - 1); a.dhead = at<const float>(h, L.dhead);
         a.wh16 = at<const uint16_t>(h, L.w16_src) + n.wh_off;
-        a.dzR = dzR(n.L - 1); a.dzP = dzP(n.L - 1);
+        a.dzR = needs_rows(n.L - 1) ? dzR(n.L - 1) : nullptr; a.dzP = dzP(n.L - 1);
         a.partial = h->head_fan > 1 ? at<float>(h, L.head_stage) : at<float>(h, L.part[n.L]);
         {
             ProfScope prof(h, "head_backward");
@@ -877,26 +884,22 @@ hipError_t launch_backward_bf16(anakin* h)
         if (l > 0) {
             GemmNtBf16Args g;
             g.M = M; g.K = n.dims[l]; g.N = n.dims[l + 1];
-            g.dyR = dzR(l);
+            g.dyR = needs_rows(l) ? dzR(l) : nullptr;
+            g.dyP = dzP(l);
             g.w16 = at<const uint16_t>(h, L.w16_src) + n.w_off[l];
             g.hP = actP(l - 1);
-            g.dxR = l - 1 > 0 ? dzR(l - 1) : nullptr;               // dZ of the first layer feeds only dW products, which read the packed form
+            g.dxR = needs_rows(l - 1) ? dzR(l - 1) : nullptr;
             g.dxP = dzP(l - 1);
-            const bool res = (g.N == 256 || g.N == 512) && g.K % 256 == 0 && g.M % NRES_RT == 0;
+            const int rows_per_block = bf16_dx_rows_per_workgroup(g.M, g.K, g.N);
             ProfScope prof(h, "gemm_nt_mask");
-            if (res) {
-                const int rows_per_block = bf16_dx_rows_per_workgroup(g.M, g.K, g.N);
-                const size_t lds2 = ((size_t)2 * NRES_RT * (g.N + 8) + (size_t)2 * NRES_RT * NRES_LDT) * sizeof(uint16_t);
-                const bool rm = g.dxR != nullptr;
-                const void* fn = g.N == 512 ? (rm ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<512, false>))
-                                            : (rm ? reinterpret_cast<const void*>(gemm_nt_bf16_res<256, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256, false>));
+            if (bf16_dx_resident(n, M, l)) {
+                const size_t lds2 = (size_t)2 * NRES_RT * (g.N + 8) * sizeof(uint16_t);
+                const void* fn = g.N == 512 ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256>);
                 e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
                 if (e != hipSuccess) return e;
                 const dim3 grid(((g.M + rows_per_block - 1) / rows_per_block) * (g.K / 256));
-                if (g.N == 512 && rm) hipLaunchKernelGGL((gemm_nt_bf16_res<512, true>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
-                else if (g.N == 512) hipLaunchKernelGGL((gemm_nt_bf16_res<512, false>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
-                else if (rm) hipLaunchKernelGGL((gemm_nt_bf16_res<256, true>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
-                else hipLaunchKernelGGL((gemm_nt_bf16_res<256, false>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                if (g.N == 512) hipLaunchKernelGGL((gemm_nt_bf16_res<512>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else hipLaunchKernelGGL((gemm_nt_bf16_res<256>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
             } else {
                 const size_t lds2 = (size_t)2 * 128 * NB_LD * sizeof(uint16_t);
                 e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_bf16), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);

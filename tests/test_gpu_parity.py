@@ -238,6 +238,10 @@ BF16_CASES = {
     "maze_bf16_16x16_256": (variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20), 4, 2),
     # the benchmark's layer widths at a size the oracle can follow: every 512-wide update kernel
     "maze_bf16_16x16_512": (variant("maze_16384", B=64, T=8, max_steps=20), 5, 1),
+    # three layers: all 256 wide (both dX products weights-resident, dZ in the packed layout only) and 128-256-256
+    # (the 128 -> 256 layer's dX product is the tiled one, which reads rows: the layer above then runs tiled too)
+    "maze_bf16_8x8_256x3": (variant("maze_16384", hidden=[256, 256, 256], B=64, T=8, rows=8, cols=8, max_steps=20), 6, 2),
+    "maze_bf16_8x8_128_256_256": (variant("maze_16384", hidden=[128, 256, 256], B=64, T=8, rows=8, cols=8, max_steps=20), 7, 2),
     "catch_bf16_128": (variant("catch_4096", hidden=[128, 128], B=64, T=12, dtype="bf16"), 0, 2),
     "pendulum_bf16_128": (variant("pendulum_8192", hidden=[128, 128], B=64, T=10, dtype="bf16", max_steps=7), 2, 2),
 }
