@@ -211,6 +211,12 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     }
     if (const int s = first_fused_splits(ns, ed.kind, M, splits[1])) splits[0] = s;                           // first layer folded into the dX product of the second
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
+    if (ns.L == 1 && ed.kind == ENV_CATCH && !ns.bf16 && ns.dims[1] == 32 && B % 256 == 0) {
+        // the single-launch update (scan, loss and backward pass): a workgroup owns whole blocks of 256 envs
+        int s = B / 256;
+        while (s > 1024 && s % 2 == 0) s /= 2;
+        if (s <= 1024) { splits[0] = s; splits[1] = s; }
+    }
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
     const bool bfp = rollout_bf16_ok(ns, ed, B);
     const int hq = bfp ? 64 : (M % 32 == 0 ? 32 : 16);  // row quantum of the head pass
@@ -376,7 +382,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     if (!h) { g_create_error = "out of host memory"; return ANAKIN_E_INVALID_ARG; }
     h->env_cfg = *env; h->net_cfg = *net; h->env = ed; h->net = ns; h->B = B; h->T = T;
     h->seed = seed; h->gstep = 0; h->adam_t = 0; h->have_traj = 0; h->mode = 0; h->prof_on = 0; h->traj_packed = 0; h->traj_no_acts = 0;
-    h->pathwise = 0;
+    h->pathwise = 0; h->metric_blocks = 0;
     h->traj_decoupled = 0; h->actor_stream = nullptr; h->actor_stream_owned = 0; h->ev_fork = nullptr; h->ev_join = nullptr;
     h->ws = static_cast<char*>(d_workspace); h->ws_bytes = workspace_bytes;
     h->scratch = nullptr;
@@ -572,6 +578,13 @@ extern "C" int32_t anakin_learn(anakin_t* h)
     if (h->traj_decoupled) { h->err = "the stored unroll was collected by a decoupled step (older parameters, no activations): continue with anakin_step_decoupled"; return ANAKIN_E_STATE; }
     if (h->traj_packed != (bf16_mfma(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
     if (h->traj_no_acts != (one_layer_fused(h) ? 1 : 0)) { h->err = "the mode changed between rollout and learn"; return ANAKIN_E_STATE; }
+    if (catch_fused_ok(h)) {
+        // scan, loss, backward pass in one launch; then Adam
+        HIPCHK(h, launch_learn_catch_fused(h));
+        HIPCHK(h, launch_adam(h));
+        h->have_traj = 0;
+        return ANAKIN_OK;
+    }
     HIPCHK(h, launch_returns(h));
     if (h->pathwise) {
         if (h->n_updates != 1) { h->err = "the pathwise policy gradient takes one update per unroll (chunks would cut the adjoint)"; return ANAKIN_E_BAD_CONFIG; }
@@ -902,7 +915,7 @@ extern "C" int32_t anakin_get_metrics(anakin_t* h, anakin_metrics* out)
     NEED(h);
     if (!out) return ANAKIN_E_INVALID_ARG;
     // with several updates per unroll every chunk wrote its own run of blocks
-    const int blocks = h->n_updates > 1 ? h->n_updates * h->sub_loss_blocks : h->loss_blocks;
+    const int blocks = h->n_updates > 1 ? (h->metric_blocks > 0 ? h->n_updates * h->sub_loss_blocks : 0) : h->metric_blocks;
     std::vector<float> part((size_t)blocks * 8);
     int rc = download(h, part.data(), h->lay.loss_part, part.size() * 4);
     if (rc) return rc;

@@ -142,6 +142,7 @@ struct anakin {
     int TM_res;                   // envs per workgroup in the weights-resident rollout kernel (0: not applicable)
     int splits[ank::MAX_REGIONS]; // split-K factor per parameter region
     int loss_blocks;
+    int metric_blocks;            // blocks of loss partials the last update wrote (0 before the first)
     int head_fan;                 // first-stage workgroups per split of the head-gradient pass
     int n_updates;                // Adam updates per unroll (consecutive time chunks of the unroll), 1 by default
     int sub_splits[ank::MAX_REGIONS], sub_splits_w, sub_head_fan, sub_loss_blocks;   // split plan of one chunk
@@ -197,6 +198,8 @@ hipError_t launch_adam(anakin* h);
 hipError_t launch_first_layer_grad(anakin* h);
 hipError_t launch_adam_probe(float* base, int P, hipStream_t s);
 hipError_t launch_learn_one_layer(anakin* h);
+hipError_t launch_learn_catch_fused(anakin* h);
+bool catch_fused_ok(const anakin* h);
 // single hidden layer on a one-hot or 3-feature observation: the update rebuilds the layer from the state
 inline bool one_layer_fused(const anakin* h) { return h->net.L == 1 && h->env.kind != ENV_MAZE && !h->net.bf16 && !(h->mode & ANAKIN_MODE_VALU_GEMM) && h->net.dims[1] <= 128 && (size_t)128 * h->net.dims[0] * 4 + (size_t)h->net.dims[0] * h->net.dims[1] * 4 <= 64 * 1024; }
 hipError_t launch_partial_reduce(const float* src, float* dst, int count, int fan, int splits, hipStream_t s);

@@ -850,6 +850,234 @@ __global__ __launch_bounds__(OLW) void learn_one_layer(const OneLayerArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Catch with one hidden layer of 32 units (the throughput workload): the WHOLE update up to the
+// partial sums in one launch -- returns and advantages, loss and head gradients, and the backward
+// pass above -- so that advantages, returns and head gradients never make a round trip through
+// HBM (the returns are still written once, for the caller to see) and three launches become one.
+// A workgroup of four wavefronts owns a range of envs for all T steps; each wavefront takes 64 of
+// them at a time:
+//   A1  lane = env: the reverse scan of its column (returns_scan's recursion), adv / ret to HBM
+//   A2  lane = env, four time steps at a time: the loss terms and head gradients of its samples
+//       (head_grad's arithmetic) into LDS, with the two board cells of the sample as LDS offsets
+//   B   lane = (hidden unit, half): each half-wavefront walks every other sample of the chunk:
+//       h = relu(b1 + W1[ball] + W1[paddle]) in the acting order, dZ1, the head-matrix sums, and
+//       the scatter of dZ1 into the two rows of its own LDS copy of dW1
+// All waves run the same trip counts, so workgroup barriers separate A2 from B.
+// ---------------------------------------------------------------------------
+struct CatchFusedArgs {
+    int B, T, D, envs_per_wg;
+    EnvDims env;
+    const float* theta; int w1_off, b1_off, wh_off;
+    const uint32_t* s0; const uint8_t* act; const float* rew; const uint8_t* done; const float* val; const float* head;
+    float* adv; float* ret;
+    float* partial0;          // [workgroups][D*32 + 32]
+    float* partial1;          // [workgroups][32*4 + 4]
+    float* loss_part;         // [workgroups][8]
+    float gamma, lambda, beta, cv, inv_m;
+};
+
+// loss terms and head gradient of one categorical sample with three actions and one value (NH = 4); the
+// operation order is head_grad's
+__device__ __forceinline__ void catch_head_grad(const float4 hv4, int act, float A_, float G_, float beta, float cv, float inv_m,
+                                                float (&d)[4], float& lp_term, float& v_term, float& e_term)
+{
+    const float hv[3] = {hv4.x, hv4.y, hv4.z};
+    const float dv = G_ - hv4.w;
+    v_term = cv * dv * dv;
+    float mx = hv[0];
+#pragma unroll
+    for (int j = 1; j < 3; ++j) mx = fmaxf(mx, hv[j]);
+    float e[3], Z = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) { e[j] = det_exp(hv[j] - mx); Z += e[j]; }
+    const float logZ = det_log(Z), invZ = 1.0f / Z;
+    float H = 0.0f, lpa = 0.0f, p[3], lp[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        lp[j] = hv[j] - mx - logZ;
+        p[j] = e[j] * invZ;
+        H -= p[j] * lp[j];
+        if (j == act) lpa = lp[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 3; ++j) d[j] = (-A_ * ((j == act ? 1.0f : 0.0f) - p[j]) + beta * p[j] * (lp[j] + H)) * inv_m;
+    d[3] = -2.0f * cv * dv * inv_m;
+    lp_term = -A_ * lpa;
+    e_term = -beta * H;
+}
+
+constexpr int CF_WG = 256;              // four wavefronts
+constexpr int CF_H = 32;                // hidden units
+constexpr int CF_TC = 4;                // time steps per chunk of phases A2 / B
+
+__global__ __launch_bounds__(CF_WG) void learn_catch_fused(const CatchFusedArgs a)
+{
+    extern __shared__ float lds[];
+    const int D = a.D, B = a.B, T = a.T;
+    constexpr int H = CF_H;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* w1s = lds;                                            // [D][H]
+    float* accw = w1s + D * H + (size_t)wave * (2 * D * H + CF_TC * 64 * 4 + CF_TC * 64);
+    float* acc = accw;                                           // [2 halves][D][H] this wavefront's dW1 sums
+    float4* dh = reinterpret_cast<float4*>(accw + 2 * D * H);    // [CF_TC][64] head gradients of the chunk
+    uint32_t* cells = reinterpret_cast<uint32_t*>(dh + CF_TC * 64);   // [CF_TC][64] LDS offsets of the two board cells
+    for (int i = tid; i < D * H; i += CF_WG) w1s[i] = a.theta[a.w1_off + i];
+    for (int i = lane; i < 2 * D * H; i += 64) acc[i] = 0.0f;
+    // phase B identity: hidden unit u, half hf (the two halves of a wavefront take alternate samples)
+    const int u = lane & 31, hf = lane >> 5;
+    float wh[4], dwh[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wh[k] = a.theta[a.wh_off + u * 4 + k];
+    const float b1 = a.theta[a.b1_off + u];
+    float db1 = 0.0f;
+    float* mine = acc + (size_t)hf * D * H + u;
+    const float* w1c = w1s + u;
+    // phase A identity: env e of the wavefront's block; sums of the loss terms and of the head gradients
+    float dbh[4] = {0, 0, 0, 0}, sums[5] = {0, 0, 0, 0, 0};
+    __syncthreads();
+    const float oml = 1.0f - a.lambda;
+    const int wg_b0 = blockIdx.x * a.envs_per_wg;
+    for (int blk = 0; blk < a.envs_per_wg; blk += CF_WG) {
+        const int b = wg_b0 + blk + wave * 64 + lane;
+        // ---- A1: returns and advantages of this env, newest step first ----
+        {
+            float G = a.val[(size_t)T * B + b], vnext = G;
+#pragma unroll 4
+            for (int t = T - 1; t >= 0; --t) {
+                const size_t i = (size_t)t * B + b;
+                const float r = a.rew[i], v = a.val[i];
+                const float disc = a.done[i] ? 0.0f : a.gamma;
+                const float mix = fmaf(a.lambda, G, oml * vnext);
+                G = fmaf(disc, mix, r);
+                a.ret[i] = G;
+                a.adv[i] = G - v;
+                vnext = v;
+            }
+        }
+        for (int t0 = 0; t0 < T; t0 += CF_TC) {
+            const int tn = T - t0 < CF_TC ? T - t0 : CF_TC;
+            // ---- A2: loss terms and head gradients of (t0 .. t0 + tn - 1, b) ----
+            for (int tt = 0; tt < tn; ++tt) {
+                const size_t i = (size_t)(t0 + tt) * B + b;
+                const float4 hv4 = *reinterpret_cast<const float4*>(a.head + i * 4);
+                float d[4], lp_term, v_term, e_term;
+                catch_head_grad(hv4, (int)a.act[i], a.adv[i], a.ret[i], a.beta, a.cv, a.inv_m, d, lp_term, v_term, e_term);
+                sums[0] += lp_term; sums[1] += v_term; sums[2] += e_term; sums[3] += a.rew[i]; sums[4] += a.done[i] ? 1.0f : 0.0f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) dbh[k] += d[k];
+                dh[tt * 64 + lane] = make_float4(d[0], d[1], d[2], d[3]);
+                int bc, pc;
+                catch_obs_cells(a.env, a.s0[i], bc, pc);
+                cells[tt * 64 + lane] = (uint32_t)(bc * H) | ((uint32_t)(pc * H) << 16);
+            }
+            __syncthreads();
+            // ---- B: half hf takes samples hf, hf + 2, ... of the chunk's tn * 64 ----
+            const int ns = tn * 64;
+            constexpr int RB = 8;
+            for (int s0 = 0; s0 < ns; s0 += 2 * RB) {
+                float4 dd[RB];
+                uint32_t cc[RB];
+#pragma unroll
+                for (int q = 0; q < RB; ++q) { dd[q] = dh[s0 + 2 * q + hf]; cc[q] = cells[s0 + 2 * q + hf]; }
+                float w0[RB], w1[RB];
+#pragma unroll
+                for (int q = 0; q < RB; ++q) { w0[q] = w1c[cc[q] & 0xffffu]; w1[q] = w1c[cc[q] >> 16]; }
+#pragma unroll
+                for (int q = 0; q < RB; ++q) {
+                    const float d[4] = {dd[q].x, dd[q].y, dd[q].z, dd[q].w};
+                    float hv = (b1 + w0[q]) + w1[q];
+                    hv = hv > 0.0f ? hv : 0.0f;
+                    float s = 0.0f;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) { s = fmaf(wh[k], d[k], s); dwh[k] = fmaf(hv, d[k], dwh[k]); }
+                    const float dz = hv > 0.0f ? s : 0.0f;
+                    db1 += dz;
+                    mine[cc[q] & 0xffffu] += dz;
+                    mine[cc[q] >> 16] += dz;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // ---- sums of the workgroup, in a fixed order: wavefronts ascending, half 0 before half 1 ----
+    // every wavefront's dW1 copies are complete (barrier above); the per-lane sums go through the wavefront's
+    // head-gradient area, free now: 16 floats per lane
+    const size_t ws = (size_t)2 * D * H + CF_TC * 64 * 4 + CF_TC * 64;        // floats per wavefront
+    auto red_of = [&](int w, int l) { return w1s + D * H + (size_t)w * ws + 2 * D * H + (size_t)l * 16; };
+    {
+        float* r = red_of(wave, lane);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { r[k] = dwh[k]; r[4 + k] = dbh[k]; }
+        r[8] = db1;
+#pragma unroll
+        for (int k = 0; k < 5; ++k) r[9 + k] = sums[k];
+    }
+    __syncthreads();
+    float* out0 = a.partial0 + (size_t)blockIdx.x * ((size_t)D * H + H);
+    float* out1 = a.partial1 + (size_t)blockIdx.x * ((size_t)H * 4 + 4);
+    const float* acc_all = w1s + D * H;                          // wavefront w at stride ws
+    for (int i = tid; i < D * H; i += CF_WG) {
+        float sum = 0.0f;
+        for (int w = 0; w < 4; ++w) { sum += acc_all[w * ws + i]; sum += acc_all[w * ws + D * H + i]; }
+        out0[i] = sum;
+    }
+    if (tid < H) {
+        float sb = 0.0f, sw[4] = {0, 0, 0, 0};
+        for (int w = 0; w < 4; ++w)
+            for (int hh = 0; hh < 2; ++hh) {
+                const float* r = red_of(w, hh * 32 + tid);
+                sb += r[8];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) sw[k] += r[k];
+            }
+        out0[(size_t)D * H + tid] = sb;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) out1[(size_t)tid * 4 + k] = sw[k];
+    }
+    if (tid < 9) {
+        // dbh[0..3] and the five metric sums: over all 256 lanes (envs), ascending
+        const int off = tid < 4 ? 4 + tid : 9 + (tid - 4);
+        float sum = 0.0f;
+        for (int l = 0; l < CF_WG; ++l) sum += red_of(l >> 6, l & 63)[off];
+        if (tid < 4) out1[(size_t)H * 4 + tid] = sum;
+        else a.loss_part[(size_t)blockIdx.x * 8 + (tid - 4)] = sum;
+    }
+    if (tid >= 9 && tid < 12) a.loss_part[(size_t)blockIdx.x * 8 + tid - 4] = 0.0f;
+}
+
+// whether the fused launch above serves this handle's update (else: scan, loss and one-layer kernels)
+bool catch_fused_ok(const anakin* h)
+{
+    const NetShape& n = h->net;
+    return one_layer_fused(h) && h->env.kind == ENV_CATCH && n.dims[1] == CF_H && n.NH == 4 && h->n_updates == 1 &&
+           !h->traj_decoupled && !h->pathwise && h->splits[0] > 0 && h->B % (h->splits[0] * CF_WG) == 0 &&
+           n.dims[0] * CF_H < 65536;                                  // board-cell offsets are packed into 16 bits
+}
+
+hipError_t launch_learn_catch_fused(anakin* h)
+{
+    const Layout& L = h->lay;
+    const NetShape& n = h->net;
+    CatchFusedArgs a;
+    a.B = h->B; a.T = h->T; a.D = n.dims[0]; a.envs_per_wg = h->B / h->splits[0];
+    a.env = h->env;
+    a.theta = at<const float>(h, L.w_src); a.w1_off = n.w_off[0]; a.b1_off = n.b_off[0]; a.wh_off = n.wh_off;
+    a.s0 = at<const uint32_t>(h, L.tr_s0); a.act = at<const uint8_t>(h, L.tr_act); a.rew = at<const float>(h, L.tr_rew);
+    a.done = at<const uint8_t>(h, L.tr_done); a.val = at<const float>(h, L.tr_val); a.head = at<const float>(h, L.tr_head);
+    a.adv = at<float>(h, L.adv); a.ret = at<float>(h, L.ret);
+    a.partial0 = at<float>(h, L.part[0]); a.partial1 = at<float>(h, L.part[1]); a.loss_part = at<float>(h, L.loss_part);
+    a.gamma = h->net_cfg.gamma; a.lambda = h->net_cfg.lambda_; a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef;
+    a.inv_m = (float)(1.0 / ((double)h->B * h->T));
+    const size_t lds = ((size_t)a.D * CF_H + 4 * ((size_t)2 * a.D * CF_H + CF_TC * 64 * 4 + CF_TC * 64)) * sizeof(float);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(learn_catch_fused), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    h->metric_blocks = h->splits[0];
+    ProfScope prof(h, "learn_catch_fused");
+    hipLaunchKernelGGL(learn_catch_fused, dim3(h->splits[0]), dim3(CF_WG), lds, h->stream, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_learn_one_layer(anakin* h)
 {
     const Layout& L = h->lay;
@@ -1116,6 +1344,7 @@ hipError_t launch_head_grad(anakin* h)
     a.dhead = at<float>(h, L.dhead); a.loss_part = at<float>(h, L.loss_part);
     a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef; a.inv_m = (float)(1.0 / (double)a.M);
     a.path = h->pathwise ? at<const float>(h, L.path) : nullptr;
+    h->metric_blocks = h->loss_blocks;
     ProfScope prof(h, "head_grad");
     hipLaunchKernelGGL(head_grad, dim3(h->loss_blocks), dim3(WG), 0, h->stream, a);
     return hipGetLastError();
