@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.environ.get("ANAKIN_OUT", os.path.join(HERE, "libanakin.so"))
-SOURCES = ["anakin.hip", "rollout.hip", "rollout_bf16.hip", "learn.hip", "learn_bf16.hip", "gemm.hip", "gemm_mfma.hip", "gemm_resident.hip", "probe.hip", "pathwise.hip"]
+SOURCES = ["anakin.hip", "rollout.hip", "rollout_bf16.hip", "learn.hip", "learn_small.hip", "learn_bf16.hip", "gemm.hip", "gemm_mfma.hip", "gemm_resident.hip", "probe.hip", "pathwise.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -178,6 +178,8 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     L.alt_tr_val = take(dec ? t1n * 4 : 0); L.alt_tr_head = take(dec ? t1n * ns.NHP * 4 : 0);
     L.head_new = take(dec ? t1n * ns.NHP * 4 : 0); L.val_new = take(dec ? t1n * 4 : 0); L.eps_new = take(dec ? tn * 4 : 0);
     L.path = take(ed.kind == ENV_PENDULUM && !ns.bf16 ? tn * 2 * 4 : 0);
+    L.small_part = take(small_fused_part_bytes(ed, ns, B, T));
+    L.counters = take(256);
     L.total = off;
 }
 
@@ -420,6 +422,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.v, 0, (size_t)ns.P * 4, h->stream);
     // the metrics are sums over these blocks: zero until the first update has written them
     if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.loss_part, 0, (size_t)(h->loss_blocks + T) * 8 * 4, h->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(h->ws + h->lay.counters, 0, 256, h->stream);
     if (e != hipSuccess) { h->err = std::string("hipMemsetAsync: ") + hipGetErrorString(e); return fail(ANAKIN_E_HIP); }
     if (ns.bf16) {
         e = launch_refresh_bf16(h);
@@ -582,6 +585,12 @@ extern "C" int32_t anakin_learn(anakin_t* h)
         // scan, loss, backward pass in one launch; then Adam
         HIPCHK(h, launch_learn_catch_fused(h));
         HIPCHK(h, launch_adam(h));
+        h->have_traj = 0;
+        return ANAKIN_OK;
+    }
+    if (small_fused_ok(h)) {
+        // scan, loss, backward pass and Adam in one launch
+        HIPCHK(h, launch_learn_small_fused(h));
         h->have_traj = 0;
         return ANAKIN_OK;
     }

@@ -115,6 +115,8 @@ struct Layout {
     size_t theta_b, w_bf16_b, wt_bf16_b, prefix_b;      // bf16 nets: the actor's own rounded copies and first-layer prefix
     size_t alt_tr_s0, alt_tr_f0, alt_tr_f1, alt_tr_act, alt_tr_eps, alt_tr_actf, alt_tr_rew, alt_tr_done, alt_tr_val, alt_tr_head;
     size_t head_new, val_new, eps_new;
+    size_t small_part;           // single-launch update of small nets: one whole gradient per workgroup, [workgroups][P]
+    size_t counters;             // arrival counters of kernels whose last workgroup finishes the job (zero between launches)
     size_t path;                 // pathwise policy gradient: dL_path / d(mu, log_sigma) per sample, [T*B][2]
     size_t total;
 };
@@ -199,6 +201,9 @@ hipError_t launch_first_layer_grad(anakin* h);
 hipError_t launch_adam_probe(float* base, int P, hipStream_t s);
 hipError_t launch_learn_one_layer(anakin* h);
 hipError_t launch_learn_catch_fused(anakin* h);
+hipError_t launch_learn_small_fused(anakin* h);
+bool small_fused_ok(const anakin* h);
+size_t small_fused_part_bytes(const EnvDims& ed, const NetShape& ns, int B, int T);
 bool catch_fused_ok(const anakin* h);
 // single hidden layer on a one-hot or 3-feature observation: the update rebuilds the layer from the state
 inline bool one_layer_fused(const anakin* h) { return h->net.L == 1 && h->env.kind != ENV_MAZE && !h->net.bf16 && !(h->mode & ANAKIN_MODE_VALU_GEMM) && h->net.dims[1] <= 128 && (size_t)128 * h->net.dims[0] * 4 + (size_t)h->net.dims[0] * h->net.dims[1] * 4 <= 64 * 1024; }
