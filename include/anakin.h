@@ -228,6 +228,17 @@ int32_t anakin_set_mode(anakin_t* h, int32_t flags);
  * kernels' row granularity; the setting is kept until changed.  Default 1. */
 int32_t anakin_set_updates_per_unroll(anakin_t* h, int32_t n_updates);
 
+/* At which parameters the gradient of chunk k of several updates per unroll is taken (the paper's remark in
+ * section 4 leaves it open).  ANAKIN_CHUNKS_AT_ACTING_PARAMETERS (default): at the parameters the unroll was acted
+ * with -- every chunk reuses the stored forward pass (section 3.1), nothing is recomputed.  ANAKIN_CHUNKS_SEQUENTIAL:
+ * at the parameters as they are after the k previous updates, which is what "N smaller updates instead of one
+ * larger one" ordinarily means -- before every chunk but the first the forward pass over the stored states is
+ * repeated with the current parameters; returns and advantages stay those of the stored unroll, the actions (and
+ * for the Gaussian policy the pre-squash samples) stay fixed.  Kept until changed; has no effect with one update
+ * per unroll.  ANAKIN_E_INVALID_ARG for an unknown mode. */
+enum { ANAKIN_CHUNKS_AT_ACTING_PARAMETERS = 0, ANAKIN_CHUNKS_SEQUENTIAL = 1 };
+int32_t anakin_set_update_chunk_mode(anakin_t* h, int32_t mode);
+
 /* Which policy gradient anakin_learn takes.  ANAKIN_PG_SCORE_FUNCTION (default): the actor-critic
  * term -A log pi(a|s).  ANAKIN_PG_PATHWISE: the gradient of minus the mean reward of the stored
  * unroll through the environment's dynamics and the reparameterised policy (paper section 3.1:

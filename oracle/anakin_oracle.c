@@ -989,7 +989,7 @@ int orc_learn(orc_t* h)
 /* parameters the unroll was acted with (the update reuses the acting forward    */
 /* pass, paper section 3.1), and the N Adam steps are applied in chunk order.    */
 /* loss[] ends up as the mean of the N chunk losses, grad as the last chunk's.   */
-int orc_learn_n(orc_t* h, int n_updates)
+static int learn_n(orc_t* h, int n_updates, int sequential)
 {
     if (!h->have_traj) return -1;
     if (n_updates < 1 || h->T % n_updates != 0) return -2;
@@ -1000,7 +1000,7 @@ int orc_learn_n(orc_t* h, int n_updates)
     size_t chunk = (size_t)(h->T / n_updates) * h->B;
     double acc[4] = {0, 0, 0, 0};
     for (int k = 0; k < n_updates; ++k) {
-        loss_and_grad_range(h, theta0, (size_t)k * chunk, (size_t)(k + 1) * chunk);
+        loss_and_grad_range(h, sequential ? h->theta : theta0, (size_t)k * chunk, (size_t)(k + 1) * chunk);
         for (int i = 0; i < 4; ++i) acc[i] += h->loss[i];
         h->adam_t += 1;
         orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t,
@@ -1011,6 +1011,13 @@ int orc_learn_n(orc_t* h, int n_updates)
     h->have_traj = 0;
     return 0;
 }
+int orc_learn_n(orc_t* h, int n_updates) { return learn_n(h, n_updates, 0); }
+
+/* The other reading of the same remark: chunk k's gradient is taken at the parameters as they are after the k
+ * previous updates -- N successive smaller updates in the ordinary sense.  Returns and advantages are still those
+ * of the stored unroll (acting-time values), actions and pre-squash samples stay fixed; the forward pass of the
+ * chunk is that of the current parameters. */
+int orc_learn_n_sequential(orc_t* h, int n_updates) { return learn_n(h, n_updates, 1); }
 
 /* ------------------------------------------------------------------------- */
 /* Off-policy update (paper section 3.2 and section 4, "Sebulba": acting and   */

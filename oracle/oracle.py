@@ -90,6 +90,7 @@ def lib():
         L.orc_adam.restype = None
         L.orc_learn.argtypes = [C.c_void_p]; L.orc_learn.restype = C.c_int
         L.orc_learn_n.argtypes = [C.c_void_p, C.c_int]; L.orc_learn_n.restype = C.c_int
+        L.orc_learn_n_sequential.argtypes = [C.c_void_p, C.c_int]; L.orc_learn_n_sequential.restype = C.c_int
         L.orc_step.argtypes = [C.c_void_p]; L.orc_step.restype = None
         L.orc_vtrace_targets.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_vtrace_targets.restype = None
         L.orc_learn_vtrace.argtypes = [C.c_void_p, C.c_double, C.c_double]; L.orc_learn_vtrace.restype = C.c_int
@@ -274,10 +275,11 @@ class Oracle:
         if rc != 0:
             raise RuntimeError("learn without a stored trajectory")
 
-    def learn_n(self, n_updates):
-        """N Adam updates on the stored unroll, one per consecutive time chunk (gradients at the acting-time
-        parameters)."""
-        rc = self.L.orc_learn_n(self.h, int(n_updates))
+    def learn_n(self, n_updates, sequential=False):
+        """N Adam updates on the stored unroll, one per consecutive time chunk: gradients at the acting-time
+        parameters, or (sequential) chunk k's at the parameters after the k previous updates."""
+        fn = self.L.orc_learn_n_sequential if sequential else self.L.orc_learn_n
+        rc = fn(self.h, int(n_updates))
         if rc != 0:
             raise RuntimeError("learn_n: no stored trajectory" if rc == -1 else "learn_n: T is not a multiple of n_updates")
 

@@ -17,6 +17,7 @@ OK = 0
 E_INVALID_ARG, E_BAD_CONFIG, E_WORKSPACE_TOO_SMALL, E_MISALIGNED, E_HIP, E_NONFINITE, E_STATE = -1, -2, -3, -4, -5, -6, -7
 MODE_VALU_GEMM, MODE_CANONICAL_ACTING, MODE_STREAM_WEIGHTS = 1, 2, 4
 PG_SCORE_FUNCTION, PG_PATHWISE = 0, 1
+CHUNKS_AT_ACTING_PARAMETERS, CHUNKS_SEQUENTIAL = 0, 1
 STATIC_SCRATCH_BYTES = 64 << 20
 
 ENV_KINDS = {"catch": 0, "pendulum": 1, "maze": 2}
@@ -66,7 +67,7 @@ EXPORTS = ["anakin_workspace_bytes", "anakin_create", "anakin_rollout", "anakin_
            "anakin_destroy", "anakin_param_count", "anakin_get_params", "anakin_set_params", "anakin_get_grads",
            "anakin_get_opt_state", "anakin_set_opt_state", "anakin_get_env_state", "anakin_set_env_state",
            "anakin_get_walls", "anakin_get_global_step", "anakin_set_global_step", "anakin_get_trajectory",
-           "anakin_get_metrics", "anakin_get_plan", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_set_policy_gradient", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
+           "anakin_get_metrics", "anakin_get_plan", "anakin_set_mode", "anakin_set_updates_per_unroll", "anakin_set_update_chunk_mode", "anakin_set_policy_gradient", "anakin_profile", "anakin_kernel_times", "anakin_peak_probe",
            "anakin_last_error"]
 
 _lib = None
@@ -111,6 +112,7 @@ def load():
     L.anakin_set_actor_stream.argtypes = [vp, vp]
     L.anakin_set_mode.argtypes = [vp, C.c_int32]
     L.anakin_set_updates_per_unroll.argtypes = [vp, C.c_int32]
+    L.anakin_set_update_chunk_mode.argtypes = [vp, C.c_int32]
     L.anakin_set_policy_gradient.argtypes = [vp, C.c_int32]
     L.anakin_profile.argtypes = [vp, C.c_int32]
     L.anakin_kernel_times.argtypes = [vp, C.POINTER(KernelTime), C.c_int32, C.POINTER(C.c_int32)]
@@ -218,8 +220,12 @@ class Anakin:
     def set_mode(self, flags):
         self._chk(self.L.anakin_set_mode(self.h, int(flags)))
 
-    def set_updates_per_unroll(self, n):
+    def set_updates_per_unroll(self, n, sequential=None):
+        """n Adam updates per unroll; sequential: True / False selects at which parameters chunk gradients are taken
+        (anakin_set_update_chunk_mode), None leaves the mode as it is."""
         self._chk(self.L.anakin_set_updates_per_unroll(self.h, int(n)))
+        if sequential is not None:
+            self._chk(self.L.anakin_set_update_chunk_mode(self.h, CHUNKS_SEQUENTIAL if sequential else CHUNKS_AT_ACTING_PARAMETERS))
 
     # ---- introspection ----------------------------------------------------------
     def get_params(self):

@@ -406,7 +406,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
         const hipError_t es = resolve_static_scratch(dev);
         if (es != hipSuccess) { g_create_error = std::string("hipGetSymbolAddress(static scratch): ") + hipGetErrorString(es); delete h; return ANAKIN_E_HIP; }
     }
-    h->n_updates = 1;
+    h->n_updates = 1; h->chunks_sequential = 0;
     h->TM = rollout_pick_tile(ns, B);
     h->TM_mfma = rollout_pick_tile_mfma(ns, B);
     h->TM_res = rollout_resident_tile(ns, B);
@@ -605,26 +605,45 @@ extern "C" int32_t anakin_learn(anakin_t* h)
         h->have_traj = 0;
         return ANAKIN_OK;
     }
-    // Several updates on one unroll: chunk k is the time steps [k T/n, (k+1) T/n).  Every chunk's gradient is taken
-    // at the parameters the unroll was acted with (the stored forward pass), so the backward kernels read a copy of
-    // the weights made now while Adam moves the live ones.  The kernels see a chunk as a shorter unroll: T and the
-    // offsets of the per-sample arrays are switched for the duration of one update.
+    // Several updates on one unroll: chunk k is the time steps [k T/n, (k+1) T/n).  Default: every chunk's gradient is
+    // taken at the parameters the unroll was acted with (the stored forward pass), so the backward kernels read a copy
+    // of the weights made now while Adam moves the live ones.  Sequential mode: chunk k's gradient at the parameters
+    // after k updates (the forward pass is repeated before each further chunk).  The kernels see a chunk as a shorter
+    // unroll: T and the offsets of the per-sample arrays are switched for the duration of one update.
     const Layout full = h->lay;
     const NetShape& n = h->net;
     const int T = h->T, B = h->B, Ts = T / h->n_updates;
-    HIPCHK(h, hipMemcpyAsync(h->ws + full.theta0, h->ws + full.theta, (size_t)n.P * 4, hipMemcpyDeviceToDevice, h->stream));
-    if (n.bf16) HIPCHK(h, hipMemcpyAsync(h->ws + full.w0_bf16, h->ws + full.w_bf16, (size_t)n.P * 2, hipMemcpyDeviceToDevice, h->stream));
+    const bool seq = h->chunks_sequential != 0;
+    if (!seq) {
+        HIPCHK(h, hipMemcpyAsync(h->ws + full.theta0, h->ws + full.theta, (size_t)n.P * 4, hipMemcpyDeviceToDevice, h->stream));
+        if (n.bf16) HIPCHK(h, hipMemcpyAsync(h->ws + full.w0_bf16, h->ws + full.w_bf16, (size_t)n.P * 2, hipMemcpyDeviceToDevice, h->stream));
+    }
     int full_splits[MAX_REGIONS];
-    for (int l = 0; l < MAX_REGIONS; ++l) { full_splits[l] = h->splits[l]; h->splits[l] = h->sub_splits[l]; }
+    for (int l = 0; l < MAX_REGIONS; ++l) full_splits[l] = h->splits[l];
     const int full_sw = h->splits_w, full_fan = h->head_fan, full_lb = h->loss_blocks;
-    h->splits_w = h->sub_splits_w; h->head_fan = h->sub_head_fan; h->loss_blocks = h->sub_loss_blocks;
-    h->T = Ts;
     int32_t rc = ANAKIN_OK;
     for (int k = 0; k < h->n_updates && rc == ANAKIN_OK; ++k) {
+        if (seq && k > 0) {
+            // sequential reading: the chunk's gradient is taken at the parameters as they are now, so the forward
+            // pass over the stored states is repeated with them (activations, head outputs, values; for the Gaussian
+            // policy also the noise that reproduces the stored sample), on the whole unroll's layout
+            h->lay = full; h->T = T;
+            hipError_t e = bf16_mfma(h) ? launch_replay_bf16(h) : launch_replay_forward(h);
+            if (e == hipSuccess) e = launch_eps_now(h);
+            if (e != hipSuccess) { h->err = std::string("replay of the forward pass: ") + hipGetErrorString(e); rc = ANAKIN_E_HIP; break; }
+        }
+        for (int l = 0; l < MAX_REGIONS; ++l) h->splits[l] = h->sub_splits[l];
+        h->splits_w = h->sub_splits_w; h->head_fan = h->sub_head_fan; h->loss_blocks = h->sub_loss_blocks;
+        h->T = Ts;
         const size_t r0 = (size_t)k * Ts * B;                         // first sample of the chunk
         Layout& L = h->lay;
         L = full;
-        L.w_src = full.theta0; L.w16_src = n.bf16 ? full.w0_bf16 : full.w_bf16;
+        if (seq) {
+            L.w_src = full.theta; L.w16_src = full.w_bf16;
+            if (k > 0) { L.tr_head = full.head_new; L.tr_eps = full.eps_new; }
+        } else {
+            L.w_src = full.theta0; L.w16_src = n.bf16 ? full.w0_bf16 : full.w_bf16;
+        }
         L.tr_s0 += r0 * 4; L.tr_f0 += r0 * 4; L.tr_f1 += r0 * 4;
         L.tr_act += r0; L.tr_eps += r0 * 4; L.tr_actf += r0 * 4; L.tr_rew += r0 * 4; L.tr_done += r0;
         L.tr_val += r0 * 4; L.tr_head += r0 * n.NHP * 4;
@@ -632,6 +651,8 @@ extern "C" int32_t anakin_learn(anakin_t* h)
         for (int l = 0; l < n.L; ++l) L.act[l] += r0 * n.dims[l + 1] * (h->traj_packed ? 2 : 4);
         L.loss_part += (size_t)k * h->sub_loss_blocks * 8 * 4;
         rc = run_update(h);
+        for (int l = 0; l < MAX_REGIONS; ++l) h->splits[l] = full_splits[l];
+        h->splits_w = full_sw; h->head_fan = full_fan; h->loss_blocks = full_lb;
     }
     h->lay = full; h->T = T;
     for (int l = 0; l < MAX_REGIONS; ++l) h->splits[l] = full_splits[l];
@@ -695,6 +716,14 @@ extern "C" int32_t anakin_set_updates_per_unroll(anakin_t* h, int32_t n_updates)
     for (int l = 0; l < MAX_REGIONS; ++l) h->sub_splits[l] = sp[l];
     h->sub_splits_w = sw; h->sub_head_fan = fan; h->sub_loss_blocks = lb;
     h->n_updates = n_updates;
+    return ANAKIN_OK;
+}
+
+extern "C" int32_t anakin_set_update_chunk_mode(anakin_t* h, int32_t mode)
+{
+    NEED(h);
+    if (mode != ANAKIN_CHUNKS_AT_ACTING_PARAMETERS && mode != ANAKIN_CHUNKS_SEQUENTIAL) { h->err = "unknown chunk mode"; return ANAKIN_E_INVALID_ARG; }
+    h->chunks_sequential = mode == ANAKIN_CHUNKS_SEQUENTIAL ? 1 : 0;
     return ANAKIN_OK;
 }
 

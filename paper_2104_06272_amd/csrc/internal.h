@@ -146,6 +146,7 @@ struct anakin {
     int loss_blocks;
     int metric_blocks;            // blocks of loss partials the last update wrote (0 before the first)
     int head_fan;                 // first-stage workgroups per split of the head-gradient pass
+    int chunks_sequential;        // several updates per unroll: chunk k's gradient at the parameters after k updates (else at the acting ones)
     int n_updates;                // Adam updates per unroll (consecutive time chunks of the unroll), 1 by default
     int sub_splits[ank::MAX_REGIONS], sub_splits_w, sub_head_fan, sub_loss_blocks;   // split plan of one chunk
     int splits_w;                 // maze first layer of a bf16 net: split count of the wall-plane product (0: one product
@@ -191,6 +192,7 @@ hipError_t launch_rollout(anakin* h);
 hipError_t launch_rollout_behaviour(anakin* h);
 hipError_t launch_replay_forward(anakin* h);
 hipError_t launch_vtrace(anakin* h);
+hipError_t launch_eps_now(anakin* h);
 hipError_t launch_pathwise(anakin* h);
 bool pathwise_ok(const anakin* h);
 hipError_t launch_returns(anakin* h);

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(WG) void vtrace_ratio(const VtraceArgs a)
         a.eps_new[i] = en;
         lw = (-0.5f * en * en - lsn) - (-0.5f * eo * eo - lso);
     }
-    a.ret[i] = fminf(1.0f, det_exp(lw));
+    if (a.ret) a.ret[i] = fminf(1.0f, det_exp(lw));          // null: only eps_new is wanted
 }
 
 // second pass, one lane per env, backwards in t
@@ -1301,6 +1301,23 @@ hipError_t launch_vtrace(anakin* h)
     }
     ProfScope prof(h, "vtrace_scan");
     hipLaunchKernelGGL(vtrace_scan, dim3((h->B + WG - 1) / WG), dim3(WG), 0, h->stream, a);
+    return hipGetLastError();
+}
+
+// Gaussian policy, forward pass repeated with newer parameters: the noise that reproduces the stored pre-squash
+// sample under the new head outputs, eps_new = (z - mu_new) / sigma_new (what the score function is taken at)
+hipError_t launch_eps_now(anakin* h)
+{
+    const Layout& L = h->lay;
+    if (h->net.policy == POLICY_CATEGORICAL) return hipSuccess;
+    VtraceArgs a;
+    a.B = h->B; a.T = h->T; a.A = h->net.A; a.NH = h->net.NH; a.NHP = h->net.NHP; a.policy = h->net.policy;
+    a.head_old = at<const float>(h, L.tr_head); a.head_new = at<const float>(h, L.head_new); a.val_new = nullptr;
+    a.act = at<const uint8_t>(h, L.tr_act); a.eps_old = at<const float>(h, L.tr_eps);
+    a.rew = nullptr; a.done = nullptr; a.gamma = 0.0f; a.lambda = 0.0f;
+    a.adv = nullptr; a.ret = nullptr; a.eps_new = at<float>(h, L.eps_new);
+    ProfScope prof(h, "eps_now");
+    hipLaunchKernelGGL(vtrace_ratio, dim3((unsigned)(((size_t)h->B * h->T + WG - 1) / WG)), dim3(WG), 0, h->stream, a);
     return hipGetLastError();
 }
 

@@ -356,6 +356,12 @@ def test_full_size_maze_bf16_sampled_envs(gpu, orc):
     _forced_lockstep(gpu, orc, cfg, 0, 2, sel=sel, learn=False)
 
 
+def _fast_lr(cfg, lr=1e-2):
+    cfg = copy.deepcopy(cfg)
+    cfg["net"]["lr"] = lr          # one update moves the policy enough for importance ratios on both sides of 1
+    return cfg
+
+
 N_UPDATE_CASES = {
     # name: (cfg, seed, N, tolerance)
     "catch_256x256_N2": (variant("catch_4096", B=128, T=8), 0, 2, TOL_F32),
@@ -390,6 +396,52 @@ def test_n_updates_per_unroll(gpu, orc, case):
     g.close()
 
 
+@pytest.mark.parametrize("case", list(N_UPDATE_CASES))
+def test_n_updates_sequential(gpu, orc, case):
+    """The sequential reading: chunk k's gradient at the parameters after k updates (the forward pass over the
+    stored states is repeated on the GPU before every further chunk), against the oracle's learn_n(sequential)."""
+    cfg, seed, N, tol = N_UPDATE_CASES[case]
+    cfg = _fast_lr(cfg, 3e-3)                     # the parameters move enough between chunks to tell the two readings apart
+    say(f"[n updates, sequential] {case} seed={seed} N={N} B={cfg['B']} T={cfg['T']}")
+    g = gpu.Anakin(cfg, seed=seed); o = orc.Oracle(cfg, seed=seed); o2 = orc.Oracle(cfg, seed=seed)
+    g.set_updates_per_unroll(N, sequential=True)
+    kind = cfg["env"]["kind"]
+    for u in range(2):
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout(); o.rollout()
+        PT.assert_rollout_equal(g, o, kind)
+        g.learn(); o.learn_n(N, sequential=True)
+        e_g, e_p = PT.assert_learn_close(g, o, tol, n_updates=N)
+        say(f"  unroll {u}: gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
+    # the acting-time reading gives a measurably different last gradient on the same unroll
+    PT.sync_oracle_from_gpu(g, o); PT.sync_oracle_from_gpu(g, o2)
+    o2.state_i[:] = o.state_i; o2.state_f[:] = o.state_f; o2.global_step = o.global_step
+    g.rollout(); o.rollout(); o2.rollout()
+    g.learn(); o.learn_n(N, sequential=True); o2.learn_n(N)
+    assert PT.rel(g.get_grads(), o.grad) <= tol
+    assert PT.rel(o2.grad, o.grad) > 10 * tol
+    g.set_updates_per_unroll(1, sequential=False)
+    g.close()
+
+
+def test_n_updates_sequential_bf16(gpu, orc):
+    """the same on the bf16 matrix-core path (logit-forced unroll), 256-wide maze net, N = 3"""
+    cfg = _fast_lr(variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20), 3e-3)
+    g = gpu.Anakin(cfg, seed=6); o = orc.Oracle(cfg, seed=6)
+    g.set_updates_per_unroll(3, sequential=True)
+    PT.sync_oracle_from_gpu(g, o)
+    g.rollout()
+    tr = g.trajectory()
+    o.rollout(forced_head=tr["head"])
+    g.learn(); o.learn_n(3, sequential=True)
+    # The learner's forward pass at the moved parameters is the GPU's bf16 matrix-core one on one side and the
+    # oracle's sequential one on the other (the forced protocol only pins the acting pass), and a chunk is 384
+    # samples: single entries of the wall-plane rows, sums over the ~25 envs with a wall there, differ by up to a few
+    # per cent of the largest entry while every region's norm stays within the tolerance.
+    PT.assert_learn_close(g, o, TOL_BF16, n_updates=3, elem_factor=3.0)
+    g.close()
+
+
 def test_n_updates_per_unroll_bf16(gpu, orc):
     """the same on the bf16 matrix-core path (logit-forced unroll), 256-wide maze net, N = 3"""
     cfg = variant("maze_16384", hidden=[256, 256], B=128, T=9, max_steps=20)
@@ -402,12 +454,6 @@ def test_n_updates_per_unroll_bf16(gpu, orc):
     g.learn(); o.learn_n(3)
     PT.assert_learn_close(g, o, TOL_BF16, n_updates=3)
     g.close()
-
-
-def _fast_lr(cfg, lr=1e-2):
-    cfg = copy.deepcopy(cfg)
-    cfg["net"]["lr"] = lr          # one update moves the policy enough for importance ratios on both sides of 1
-    return cfg
 
 
 DECOUPLED_CASES = {

@@ -764,6 +764,43 @@ def test_n_updates_per_unroll(orc):
         b.rollout(); b.learn_n(3)               # 8 steps do not split into 3 chunks
 
 
+@pytest.mark.parametrize("kind", ["catch", "pendulum"])
+def test_n_updates_sequential_is_two_hand_applied_steps(orc, kind):
+    """The sequential reading of several updates per unroll: chunk 1's gradient is the gradient of chunk 1's mean loss
+    at the parameters AFTER the first update, with returns, advantages, actions and pre-squash samples of the stored
+    unroll.  Rebuilt here from single calls: range gradient, Adam in numpy, parameters written back, range gradient."""
+    cfg = tiny(kind, hidden=(6, 5), B=4, T=8, max_steps=5)
+    cfg["net"]["lr"] = 1e-2                                   # one step moves the parameters visibly
+    a = orc.Oracle(cfg, seed=9); b = orc.Oracle(cfg, seed=9)
+    rng = np.random.default_rng(4)
+    noise = rng.standard_normal(a.P).astype(np.float32) * 0.2
+    a.theta[:] += noise; b.theta[:] += noise
+    a.rollout(); b.rollout()
+    f32 = lambda x: float(np.float32(x))
+    net = cfg["net"]
+    ret, adv = orc.returns(a.tr_reward, a.tr_done, a.tr_value, f32(net["gamma"]), f32(net["lambda"]))
+    a.ret[:] = ret; a.adv[:] = adv
+    n = a.T * a.B
+    th = a.theta.astype(np.float64).copy(); m = np.zeros(a.P); v = np.zeros(a.P)
+    lr, b1, b2, eps = (f32(net[k]) for k in ("lr", "beta1", "beta2", "eps"))
+    grads = []
+    for k in range(2):
+        a.loss_and_grad(k * n // 2, (k + 1) * n // 2)         # at a.theta as it is now
+        g = a.grad.astype(np.float64).copy(); grads.append(g)
+        t = k + 1
+        m = b1 * m + (1 - b1) * g; v = b2 * v + (1 - b2) * g * g
+        th = th - lr * (m / (1 - b1 ** t)) / (np.sqrt(v / (1 - b2 ** t)) + eps)
+        a.theta[:] = th.astype(np.float32); th = a.theta.astype(np.float64)      # parameters are binary32 between steps
+    b.learn_n(2, sequential=True)
+    assert b.adam_t == 2
+    assert np.abs(b.theta.astype(np.float64) - th).max() <= 1e-6
+    assert np.array_equal(b.grad, grads[1].astype(np.float32))
+    # and it is not the acting-time reading: the second chunk's gradient moved with the parameters
+    c = orc.Oracle(cfg, seed=9); c.theta[:] += noise; c.rollout(); c.learn_n(2)
+    assert np.linalg.norm(c.grad.astype(np.float64) - grads[1]) > 1e-4 * np.linalg.norm(grads[1])
+    assert np.abs(c.theta - b.theta).max() > 1e-5
+
+
 # --------------------------------------------------------------------------- off-policy update, decoupled step
 def _np_log_prob(head, kind, act, z):
     """log-probability of the stored action under head outputs [..., NH] (binary64, written out here)."""
