@@ -425,6 +425,10 @@ struct GemmTnBf16Args {
     float* bias_out;          // [splits][bias_stride]: N column sums of each split, or null
     size_t bias_stride;
     ObsSrc obs;
+    // agent-plane product only: chunks are blocks of env_block environments over all T time steps, and the sum of
+    // dY over time is written to sP (two bfloat16 terms per entry) on the way; null: chunks are sample ranges
+    uint16_t* sP;
+    int T, env_block;
 };
 
 constexpr int TB_G = 16;      // sample groups (of 8) per LDS stage: 128 samples
@@ -581,14 +585,25 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
     xcd_map((int)blockIdx.x, a.splits, a.tiles_i * (a.N / 256), split, tile);   // the tiles of one split share its samples
     const int ti = tile % a.tiles_i, tj = tile / a.tiles_i;
     const int i0 = ti * 256, j0 = tj * 256;
-    const int g_begin = (split * a.rows) >> 3, g_end = g_begin + (a.rows >> 3);
-    const int g_last = g_end - TB_BG;                            // first group of the last stage
+    const int n_stages = a.rows >> 6;
+    const bool by_env = XMODE == 1 && a.sP != nullptr;
+    // first sample group of stage i of this chunk.  Sample ranges: consecutive stages.  Blocks of environments: the 64
+    // environments of one stage at t = 0 .. T-1, then the next 64 (so a thread meets every time step of its samples
+    // in order and can add them up)
+    auto stage_g0 = [&](int i) -> int {
+        if (by_env) {
+            const int p = i / a.T, t = i - p * a.T;
+            return (t * a.obs.B + split * a.env_block + 64 * p) >> 3;
+        }
+        return ((split * a.rows) >> 3) + i * TB_BG;
+    };
     // loader: thread = (column, parity of the sample group), four groups of the stage each
     const int lc = tid & 255, lg = tid >> 8;
     struct Set { u32x4_l x[TB_BG / 2]; u32x4_l y[TB_BG / 2]; uint32_t pos; };
     Set S0, S1;
-    auto fetch = [&](Set& st, int g0) {
-        if (g0 > g_last) g0 = g_last;                            // past the end: re-read the last stage, never used
+    auto fetch = [&](Set& st, int i) {
+        if (i >= n_stages) i = n_stages - 1;                     // past the end: re-read the last stage, never used
+        const int g0 = stage_g0(i);
 #pragma unroll
         for (int q = 0; q < TB_BG / 2; ++q) {
             const int g = g0 + 2 * q + lg;
@@ -597,11 +612,16 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
         }
         if (XMODE == 1) st.pos = a.obs.s0[(size_t)g0 * 8 + (tid & 63)] & 0xffffu;
     };
+    float tsum[TB_BG / 2][8];                                    // by_env: sum over time of this thread's dY entries
+#pragma unroll
+    for (int q = 0; q < TB_BG / 2; ++q)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tsum[q][e] = 0.0f;
     float bsum = 0.0f;
     const bool sums = ti == 0 && a.bias_out != nullptr;
     const int cell = a.obs_row0 + i0 + lc - a.obs.env.rows * a.obs.env.cols;   // XMODE 1: the cell this thread's row stands for
     // stage -> LDS; pb: parity of the stage (selects the cell buffer)
-    auto store = [&](const Set& st, int g0, int pb) {
+    auto store = [&](const Set& st, int i, int pb) {
 #pragma unroll
         for (int q = 0; q < TB_BG / 2; ++q) {
             const int gl = 2 * q + lg;
@@ -616,7 +636,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
                 x[2] = ((int)p1[0] == cell ? one : 0u) | ((int)p1[1] == cell ? one << 16 : 0u);
                 x[3] = ((int)p1[2] == cell ? one : 0u) | ((int)p1[3] == cell ? one << 16 : 0u);
             } else {
-                const uint4 v = obs_piece(a.obs, g0 + gl, a.obs_row0 + i0 + lc, true);
+                const uint4 v = obs_piece(a.obs, stage_g0(i) + gl, a.obs_row0 + i0 + lc, true);
                 x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
             }
             *reinterpret_cast<u32x4_l*>(&Xs[gl * 256 + lc]) = x;
@@ -625,6 +645,30 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bsum += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
             }
+            if (by_env) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) tsum[q][e] += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
+            }
+        }
+    };
+    // by_env, after the last time step of a block of 64 environments: the sums leave as two bfloat16 terms, hi in
+    // sample rows 0..B-1 and lo in rows B..2B-1 of a packed matrix with 2B samples
+    auto flush_time_sum = [&](int i) {
+        const int p = i / a.T;
+        const size_t n = (size_t)(a.obs.B >> 3) * a.N;
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q) {
+            const size_t idx = (size_t)(((split * a.env_block + 64 * p) >> 3) + 2 * q + lg) * a.N + j0 + lc;
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                hi[w] = cvt_pk_bf16(tsum[q][2 * w], tsum[q][2 * w + 1]);
+                lo[w] = cvt_pk_bf16(tsum[q][2 * w] - bfu((uint16_t)hi[w]), tsum[q][2 * w + 1] - bfu((uint16_t)(hi[w] >> 16)));
+            }
+            *reinterpret_cast<uint4*>(a.sP + idx * 8) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *reinterpret_cast<uint4*>(a.sP + (n + idx) * 8) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tsum[q][e] = 0.0f;
         }
     };
     f16v acc[4][2];
@@ -635,6 +679,23 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     auto compute = [&]() {
+        if (XMODE == 1) {
+            // the registers of the look-ahead below hold the sums over time here; the second wavefront of the SIMD
+            // covers the LDS latency instead
+#pragma unroll
+            for (int ks = 0; ks < TB_BG; ks += 2) {
+                bf8 av[4], bv[2];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32]);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
+            }
+            return;
+        }
         // the operands of step ks + 2 are read from LDS before the eight MFMAs of step ks are issued
         bf8 av[4], bv[2];
 #pragma unroll
@@ -660,26 +721,27 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
             for (int t = 0; t < 2; ++t) bv[t] = bn[t];
         }
     };
-    // one pipeline step: stage g0 (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage
-    // g0 + 2 stages; the cells of stage g0 + 1 stage (held in `nxt`) go to the other cell buffer
-    auto step = [&](Set& cur, const Set& nxt, int g0, int pb) {
-        store(cur, g0, pb);
+    // one pipeline step: stage i (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage
+    // i + 2; the cells of stage i + 1 (held in `nxt`) go to the other cell buffer
+    auto step = [&](Set& cur, const Set& nxt, int i, int pb) {
+        store(cur, i, pb);
         if (XMODE == 1 && tid < 64) posL[pb ^ 1][tid] = nxt.pos;
         __syncthreads();
-        fetch(cur, g0 + 2 * TB_BG);
+        fetch(cur, i + 2);
         __builtin_amdgcn_sched_barrier(0);
         compute();
+        if (by_env && ti == 0 && (i + 1) % a.T == 0) flush_time_sum(i);
         __syncthreads();
     };
-    fetch(S0, g_begin);
-    fetch(S1, g_begin + TB_BG);
+    fetch(S0, 0);
+    fetch(S1, 1);
     if (XMODE == 1) {
         if (tid < 64) posL[0][tid] = S0.pos;
         __syncthreads();
     }
-    for (int g0 = g_begin; g0 < g_end; g0 += 2 * TB_BG) {
-        step(S0, S1, g0, 0);
-        if (g0 + TB_BG < g_end) step(S1, S0, g0 + TB_BG, 1);
+    for (int i = 0; i < n_stages; i += 2) {
+        step(S0, S1, i, 0);
+        if (i + 1 < n_stages) step(S1, S0, i + 1, 1);
     }
     float* out = a.partial + (size_t)split * a.split_stride;
 #pragma unroll
@@ -708,8 +770,10 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 //   dW1[wall cell c]  = sum_b walls[b][c] * S[b],   S[b] = sum_t dZ1[t][b]   (B samples, not B*T)
 //   dW1[agent cell c] = sum_m [pos_m == c] dZ1[m]                             (the only full-length product)
 //   dW1[goal cell]    = db1 = sum_b S[b]  for the one goal cell, zero for the others
-// time_sum_bf16 writes S as two bfloat16 terms (hi rows 0..B-1, lo rows B..2B-1 of a packed
-// matrix with 2B samples); the wall product then runs over those 2B samples.
+// S leaves as two bfloat16 terms (hi rows 0..B-1, lo rows B..2B-1 of a packed matrix with 2B
+// samples) and the wall product runs over those 2B samples.  The agent product reads every dZ1
+// entry anyway and writes S itself when its chunks are blocks of environments; time_sum_bf16 is
+// the separate pass for batch sizes that do not divide that way.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(WG) void time_sum_bf16(const uint16_t* __restrict__ dzP, uint16_t* __restrict__ sP, int B, int T, int H)
 {
@@ -851,22 +915,26 @@ hipError_t launch_backward_bf16(anakin* h)
             float* pw = at<float>(h, L.part[0]);
             float* pa = pw + (size_t)plane * h->splits_w;
             float* pg = pa + (size_t)plane * h->splits[0];
-            {
+            // the agent product adds dZ1 up over time on its way when its chunks can be blocks of 64 k environments
+            const bool sum_in_product = h->B % (64 * h->splits[0]) == 0;
+            if (!sum_in_product) {
                 ProfScope prof(h, "time_sum");
                 hipLaunchKernelGGL(time_sum_bf16, dim3(((h->B >> 3) * H1 + WG - 1) / WG), dim3(WG), 0, h->stream,
                                    dzP(0), sP, h->B, h->T, H1);
+                if ((e = hipGetLastError()) != hipSuccess) return e;
             }
-            if ((e = hipGetLastError()) != hipSuccess) return e;
             GemmTnBf16Args t;
-            t.M = 2 * h->B; t.K = cells; t.N = H1; t.splits = h->splits_w; t.rows = t.M / t.splits;
-            t.use_obs = 1; t.obs_row0 = 0; t.xP = nullptr; t.dyP = sP;
-            t.partial = pw; t.split_stride = (size_t)plane; t.bias_out = pg; t.bias_stride = (size_t)H1;
+            t.M = M; t.K = cells; t.N = H1; t.splits = h->splits[0]; t.rows = t.M / t.splits;
+            t.use_obs = 1; t.obs_row0 = cells; t.xP = nullptr; t.dyP = dzP(0);
+            t.partial = pa; t.split_stride = (size_t)plane; t.bias_out = nullptr; t.bias_stride = 0;
             t.obs = obs_src();
-            if ((e = run_tn(t, true, "gemm_tn_walls")) != hipSuccess) return e;
-            t.M = M; t.splits = h->splits[0]; t.rows = t.M / t.splits;
-            t.obs_row0 = cells; t.dyP = dzP(0);
-            t.partial = pa; t.bias_out = nullptr; t.bias_stride = 0;
+            t.sP = sum_in_product ? sP : nullptr; t.T = h->T; t.env_block = h->B / h->splits[0];
             if ((e = run_tn(t, true, "gemm_tn_agent")) != hipSuccess) return e;
+            t.M = 2 * h->B; t.splits = h->splits_w; t.rows = t.M / t.splits;
+            t.obs_row0 = 0; t.dyP = sP;
+            t.partial = pw; t.bias_out = pg; t.bias_stride = (size_t)H1;
+            t.sP = nullptr;
+            if ((e = run_tn(t, true, "gemm_tn_walls")) != hipSuccess) return e;
             continue;
         }
         GemmTnBf16Args t;
@@ -879,6 +947,7 @@ hipError_t launch_backward_bf16(anakin* h)
         t.split_stride = (size_t)t.K * t.N + t.N;
         t.bias_out = t.partial + (size_t)t.K * t.N; t.bias_stride = t.split_stride;
         t.obs = obs_src();
+        t.sP = nullptr; t.T = h->T; t.env_block = 0;
         const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0 && t.rows % 64 == 0;
         if ((e = run_tn(t, big, l == 0 ? "gemm_tn_obs" : "gemm_tn")) != hipSuccess) return e;
         if (l > 0) {
