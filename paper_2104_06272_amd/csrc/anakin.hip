@@ -248,6 +248,10 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         const int st = splits[ns.L - 1];
         if (st > 0 && M % st == 0 && (M / st) % 32 == 0) { splits[ns.L] = st; one_stage = true; }
     }
+    if (bfp && bf16_top_fused(ns, M, splits[ns.L - 1])) {
+        // the head gradients come out of the top layer's dW product here too
+        splits[ns.L] = splits[ns.L - 1]; one_stage = true;
+    }
     while (!one_stage && fan < 16 && (M / hq) % (splits[ns.L] * fan * 2) == 0 && M / (splits[ns.L] * fan * 2) >= 2 * hq) fan *= 2;
     *head_fan = fan;
     *loss_blocks = (M + WG - 1) / WG;

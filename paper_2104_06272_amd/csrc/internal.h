@@ -216,6 +216,7 @@ hipError_t launch_replay_bf16(anakin* h);
 hipError_t launch_backward_bf16(anakin* h);
 hipError_t launch_refresh_bf16(anakin* h);
 int bf16_dx_rows_per_workgroup(int M, int K, int N);
+bool bf16_top_fused(const NetShape& n, int M, int splits_top);
 bool bf16_dx_resident(const NetShape& n, int M, int l);
 bool rollout_bf16_ok(const NetShape& net, const EnvDims& env, int B);
 // bf16 network running on the matrix-core path (packed bf16 activations) rather than the fp32 reference path

@@ -51,6 +51,18 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// two ReLU outputs as bfloat16 in a word (never negative, never -0: relu() returns +0 for every non-positive input)
+// -> 0xffff in the halves that are positive, i.e. not zero, and 0 in the others.  Packed 16-bit integer instructions:
+// min(h, 1) is 0 or 1, and 0 - that is 0 or 0xffff.
+__device__ __forceinline__ uint32_t positive_mask_pk(uint32_t w)
+{
+    uint32_t r;
+    const uint32_t zero = 0u, one = 0x00010001u;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(w), "v"(one));
+    asm("v_pk_sub_u16 %0, %1, %2" : "=v"(r) : "v"(zero), "v"(r));
+    return r;
+}
+
 __global__ __launch_bounds__(WG) void head_backward_bf16(const HeadBwdBf16Args a)
 {
     constexpr int LDT = WG + 8;
@@ -213,6 +225,12 @@ struct GemmNtBf16Args {
     const uint16_t* hP;       // packed h_{l-1}: [M/8][K][8]
     uint16_t* dxR;            // [M][K], or null when no product below reads the row-major form
     uint16_t* dxP;            // [M/8][K][8]
+    // top layer of the weights-resident kernel: dY = dZ_L is not read but formed from the head gradient,
+    // dZ_L[m][j] = relu'(hTop[m][j]) * sum_k dhead[m][k] Wh[j][k]
+    const uint16_t* hTop;     // packed h_L: [M/8][N][8]
+    const float* dhead;       // [M][NHP]
+    const uint16_t* wh16;     // bf16 copy of Wh: [N][NH]
+    int NH, NHP;
 };
 
 constexpr int NB_BK = 128;
@@ -322,15 +340,17 @@ typedef uint32_t u32x2_l __attribute__((ext_vector_type(2)));
 constexpr int NRES_WG = 512;
 constexpr int NRES_RT = 32;             // rows per stage
 
-template <int NR>
+template <int NR, bool HEADS>
 __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args a, const int rows_per_block)
 {
     constexpr int LD = NR + 8;                                   // row stride in bf16: eight rows cover all banks
     constexpr int KS = NR / 16;                                  // MFMA steps
     constexpr int NQ = (NRES_RT / 8) * NR / NRES_WG;             // 16-byte pieces per thread and stage: 4 groups x NR columns
+    constexpr int TJ = NR / 256;                                 // HEADS: 32-column tiles of dZ_L a wavefront forms per stage
     extern __shared__ uint4 smem4[];
     uint16_t* As0 = reinterpret_cast<uint16_t*>(smem4);
     uint16_t* As1 = As0 + NRES_RT * LD;
+    __shared__ uint4 Ahl[2][64];                                 // HEADS: head gradient of a stage's 32 rows as (hi, lo) bfloat16 terms
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
     int rb_, cb_;
     xcd_map((int)blockIdx.x, (a.M + rows_per_block - 1) / rows_per_block, a.K / 256, rb_, cb_);   // column blocks of the same rows share dY in one L2
@@ -346,15 +366,61 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     // Two register sets of staged pieces: those of stage s + 2 are requested while stage s is computed, so a load
     // has two stage times to come back (one stage is shorter than the memory latency under load, and this kernel
     // lives on the HBM roof).  The relu mask of stage s + 1 is requested one stage ahead for the same reason.
+    // HEADS: the staged pieces are those of packed h_L in accumulator order instead (tile jt of the wavefront's
+    // columns, group g, samples 4kg..4kg+3: 8 bytes, two per register quad), and going to LDS means one MFMA per
+    // tile, d (hi, lo) against (Wh, Wh), masked by them
     u32x4_l stA[NQ], stB[NQ];
+    __shared__ uint4 WhB[HEADS ? NR : 1];                        // row j of Wh, eight entries (zero past NH): the B operand of column j
+    if (HEADS) {
+        for (int j = tid; j < NR; j += NRES_WG) {
+            uint32_t w8[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w8[k] = k < a.NH ? (uint32_t)a.wh16[(size_t)j * a.NH + k] : 0u;
+            WhB[j] = make_uint4(w8[0] | (w8[1] << 16), w8[2] | (w8[3] << 16), w8[4] | (w8[5] << 16), w8[6] | (w8[7] << 16));
+        }
+    }
     auto fetch = [&](u32x4_l (&st)[NQ], int m0) {
+        if (HEADS) {
+#pragma unroll
+            for (int jt = 0; jt < TJ; ++jt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const u32x2_l v = *reinterpret_cast<const u32x2_l*>(
+                        a.hTop + ((size_t)((m0 >> 3) + g) * NR + wave * (NR / 8) + 32 * jt + l32) * 8 + 4 * kg);
+                    st[(4 * jt + g) >> 1][2 * (g & 1)] = v[0];
+                    st[(4 * jt + g) >> 1][2 * (g & 1) + 1] = v[1];
+                }
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int p = q * NRES_WG + tid;
             st[q] = *reinterpret_cast<const u32x4_l*>(a.dyP + ((size_t)((m0 >> 3) + p / NR) * NR + p % NR) * 8);
         }
     };
-    auto store = [&](const u32x4_l (&st)[NQ], uint16_t* buf) {
+    // par (HEADS): which half of Ahl holds the head gradient of the stage being stored
+    auto store = [&](const u32x4_l (&st)[NQ], uint16_t* buf, int par) {
+        if (HEADS) {
+            const uint4 a1v = Ahl[par][lane];
+            const bf8 a1 = *reinterpret_cast<const bf8*>(&a1v);
+#pragma unroll
+            for (int jt = 0; jt < TJ; ++jt) {
+                f16v acc1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+                const uint4 wv = WhB[wave * (NR / 8) + 32 * jt + l32];
+                acc1 = mfma_bf16(a1, *reinterpret_cast<const bf8*>(&wv), acc1);
+                uint16_t* dst = buf + (4 * kg) * LD + wave * (NR / 8) + 32 * jt + l32;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t p01 = cvt_pk_bf16(acc1[4 * g], acc1[4 * g + 1]) & positive_mask_pk(st[(4 * jt + g) >> 1][2 * (g & 1)]);
+                    const uint32_t p23 = cvt_pk_bf16(acc1[4 * g + 2], acc1[4 * g + 3]) & positive_mask_pk(st[(4 * jt + g) >> 1][2 * (g & 1) + 1]);
+                    dst[(8 * g + 0) * LD] = (uint16_t)p01; dst[(8 * g + 1) * LD] = (uint16_t)(p01 >> 16);
+                    dst[(8 * g + 2) * LD] = (uint16_t)p23; dst[(8 * g + 3) * LD] = (uint16_t)(p23 >> 16);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int p = q * NRES_WG + tid;
@@ -362,6 +428,22 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
 #pragma unroll
             for (int e = 0; e < 8; ++e) dst[e * LD] = (uint16_t)(st[q][e >> 1] >> ((e & 1) * 16));
         }
+    };
+    // HEADS: the first 256 threads carry one entry (row tid / 8, head output tid % 8) of the head gradient each, two
+    // stages ahead
+    float dreg = 0.0f;
+    auto fetch_d = [&](int m0) {
+        if (!HEADS || tid >= 256) return;
+        const int k = tid & 7;
+        dreg = k < a.NH ? a.dhead[(size_t)(m0 + (tid >> 3)) * a.NHP + k] : 0.0f;
+    };
+    auto store_d = [&](int par) {
+        if (!HEADS || tid >= 256) return;
+        const uint32_t hi = cvt_pk_bf16(dreg, 0.0f) & 0xffffu;
+        const uint32_t lo = cvt_pk_bf16(dreg - bfu((uint16_t)hi), 0.0f) & 0xffffu;
+        uint16_t* A16 = reinterpret_cast<uint16_t*>(&Ahl[par][0]);
+        A16[tid] = (uint16_t)hi;                                 // row tid / 8 of the hi half, entry tid % 8
+        A16[256 + tid] = (uint16_t)lo;
     };
     const uint32_t lane_off = (uint32_t)i * 8u + 4u * kg;        // inside a packed group of eight samples
     u32x2_l maskA[4], maskB[4];
@@ -373,16 +455,26 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     const int m_lastst = m_end - NRES_RT;                        // loads past the end re-read the last stage, unused
     auto clampm = [&](int m) { return m < m_end ? m : m_lastst; };
     fetch(stA, m_begin);
-    store(stA, As0);
+    if (HEADS) {
+        fetch_d(m_begin); store_d(0);
+        fetch_d(clampm(m_begin + NRES_RT)); store_d(1);
+        __syncthreads();
+    }
+    store(stA, As0, 0);
     fetch(stA, clampm(m_begin + NRES_RT));                       // stage 1, stored at the end of stage 0
     fetch_mask(maskA, m_begin);
     __syncthreads();
-    // one stage: MFMAs on `cur`, epilogue with `mask`, then the staged pieces `st_next` (stage s + 1) go to `nxt`
-    auto stage = [&](int m0, const uint16_t* cur, uint16_t* nxt, const u32x2_l (&mask)[4],
+    // one stage (of parity par): MFMAs on `cur`, epilogue with `mask`, then the staged pieces `st_next` (stage s + 1)
+    // go to `nxt`; the head gradient of stage s + 2 replaces that of stage s
+    auto stage = [&](int m0, int par, const uint16_t* cur, uint16_t* nxt, const u32x2_l (&mask)[4],
                      u32x4_l (&st_next)[NQ], u32x4_l (&st_fill)[NQ], u32x2_l (&mask_fill)[4]) {
         fetch(st_fill, clampm(m0 + 2 * NRES_RT));                // two stages ahead
+        fetch_d(clampm(m0 + 2 * NRES_RT));
         fetch_mask(mask_fill, clampm(m0 + NRES_RT));             // one stage ahead
         __builtin_amdgcn_sched_barrier(0);
+        // HEADS: the next stage is formed first (nobody reads `nxt` in this stage), so that its vector work can run
+        // in the shadow of the MFMAs below; past the end it re-forms the last stage, unused
+        if (HEADS) store(st_next, nxt, par ^ 1);
         f16v acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -401,12 +493,13 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
             u32x2_l pv; pv[0] = cvt_pk_bf16(o[0], o[1]); pv[1] = cvt_pk_bf16(o[2], o[3]);
             *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
         }
-        if (m0 + NRES_RT < m_end) store(st_next, nxt);
+        if (!HEADS && m0 + NRES_RT < m_end) store(st_next, nxt, par ^ 1);
+        store_d(par);
         __syncthreads();
     };
     for (int m0 = m_begin; m0 < m_end; m0 += 2 * NRES_RT) {
-        stage(m0, As0, As1, maskA, stA, stB, maskB);
-        if (m0 + NRES_RT < m_end) stage(m0 + NRES_RT, As1, As0, maskB, stB, stA, maskA);
+        stage(m0, 0, As0, As1, maskA, stA, stB, maskB);
+        if (m0 + NRES_RT < m_end) stage(m0 + NRES_RT, 1, As1, As0, maskB, stB, stA, maskA);
     }
 }
 
@@ -765,6 +858,198 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 }
 
 // ---------------------------------------------------------------------------
+// Top layer with the heads folded in.  dZ_L never reaches memory: this kernel and the dX kernel
+// above (HEADS) both form it from the head gradient, stage by stage.  Here the stage's 64 samples
+// x 256 columns of dZ_L go to LDS as the Y operand of dW_L = h_{L-1}^T dZ_L: wavefront w forms
+// columns 32w.. (two MFMAs, d (hi, lo) against (Wh, Wh), masked by the 8-byte pieces of packed
+// h_L it holds in accumulator order).  The workgroups of the first row of tiles also add up
+// dWh = h_L^T d for their 256 columns (the same pieces of h_L are the A operand, see
+// head_backward_bf16 for the sample order) and, in the first of them, dbh; those of the second
+// row the column sums of dZ_L (the layer's bias gradient).  K and N multiples of 256; chunks are
+// whole stages.
+// ---------------------------------------------------------------------------
+struct GemmTnTopArgs {
+    int M, K, N, splits, rows, tiles_i, NH, NHP;
+    const uint16_t* xP;       // packed h_{L-1}: [M/8][K][8]
+    const uint16_t* hTop;     // packed h_L: [M/8][N][8]
+    const float* dhead;       // [M][NHP]
+    const uint16_t* wh16;     // bf16 copy of Wh: [N][NH]
+    float* partial;           // [splits][split_stride]: K x N partial, then the N column sums
+    size_t split_stride;
+    float* head_partial;      // [splits][head_stride]: N x NH partial of dWh, then dbh
+    size_t head_stride;
+};
+
+__global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
+{
+    extern __shared__ uint4 smem4[];
+    uint4* Xs = smem4;                       // [TB_BG][256] pieces of 8 samples
+    uint4* Ys = Xs + TB_BG * 256;
+    __shared__ uint4 Ahl[2][2][64];          // [stage parity][32-sample tile]: d as (hi, lo), the A operand of the dZ_L product
+    __shared__ uint4 Bhl[2][2][2][64];       // [stage parity][tile][16-sample step]: the same as the B operand of the dWh product
+    __shared__ uint4 WhB[256];               // row j0 + c of Wh, eight entries (zero past NH)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, kg = lane >> 5;
+    int split, tile;
+    xcd_map((int)blockIdx.x, a.splits, a.tiles_i * (a.N / 256), split, tile);
+    const int ti = tile % a.tiles_i, tj = tile / a.tiles_i;
+    const int i0 = ti * 256, j0 = tj * 256;
+    const int n_stages = a.rows >> 6;
+    const int g_first = (split * a.rows) >> 3;
+    // extras, one kind per row of tiles so that no workgroup carries both: the first row adds up dWh (and dbh), the
+    // second (the first, if there is only one) the column sums of dZ_L
+    const bool heads_row = ti == 0, sums_row = ti == (a.tiles_i > 1 ? 1 : 0);
+    const int lc = tid & 255, lg = tid >> 8;                     // X loader: (row of the tile, parity of the sample group)
+    const int col = wave * 32 + l32;                             // dZ_L: this lane's column of the tile
+    const int ds = tid >> 3, dk = tid & 7;                       // head gradient: (sample of the stage, head output)
+    struct Set { u32x4_l x[TB_BG / 2]; u32x2_l hq[TB_BG]; float d; };
+    Set S0, S1;
+    auto fetch = [&](Set& st, int i) {
+        if (i >= n_stages) i = n_stages - 1;                     // past the end: re-read the last stage, never used
+        const int g0 = g_first + i * TB_BG;
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q)
+            st.x[q] = *reinterpret_cast<const u32x4_l*>(a.xP + ((size_t)(g0 + 2 * q + lg) * a.K + i0 + lc) * 8);
+#pragma unroll
+        for (int G = 0; G < TB_BG; ++G)
+            st.hq[G] = *reinterpret_cast<const u32x2_l*>(a.hTop + ((size_t)(g0 + G) * a.N + j0 + col) * 8 + 4 * kg);
+        st.d = dk < a.NH ? a.dhead[((size_t)g0 * 8 + ds) * a.NHP + dk] : 0.0f;
+    };
+    float bsum = 0.0f, dbsum = 0.0f;
+    f16v acc2;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc2[r] = 0.0f;
+    // the head gradient of a stage -> both operand forms
+    auto stage_d = [&](const Set& st, int par) {
+        const uint16_t hi = (uint16_t)cvt_pk_bf16(st.d, 0.0f);
+        const uint16_t lo = (uint16_t)cvt_pk_bf16(st.d - bfu(hi), 0.0f);
+        const int mt = ds >> 5, s32 = ds & 31;
+        uint16_t* A16 = reinterpret_cast<uint16_t*>(&Ahl[par][mt][0]);
+        A16[s32 * 8 + dk] = hi;
+        A16[256 + s32 * 8 + dk] = lo;
+        const int g = s32 >> 3, r = s32 & 7, kgs = r >> 2, q = (g & 1) * 4 + (r & 3);
+        uint16_t* B16 = reinterpret_cast<uint16_t*>(&Bhl[par][mt][g >> 1][0]);
+        B16[(kgs * 32 + dk) * 8 + q] = hi;
+        B16[(kgs * 32 + 8 + dk) * 8 + q] = lo;
+    };
+    auto store = [&](const Set& st, int pb) {
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q) *reinterpret_cast<u32x4_l*>(&Xs[(2 * q + lg) * 256 + lc]) = st.x[q];
+        const uint4 wv = WhB[col];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const uint4 a1v = Ahl[pb][mt][lane];
+            f16v acc1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+            acc1 = mfma_bf16(*reinterpret_cast<const bf8*>(&a1v), *reinterpret_cast<const bf8*>(&wv), acc1);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int G = 4 * mt + g;
+                u32x2_l pv;
+                pv[0] = cvt_pk_bf16(acc1[4 * g], acc1[4 * g + 1]) & positive_mask_pk(st.hq[G][0]);
+                pv[1] = cvt_pk_bf16(acc1[4 * g + 2], acc1[4 * g + 3]) & positive_mask_pk(st.hq[G][1]);
+                *reinterpret_cast<u32x2_l*>(reinterpret_cast<char*>(&Ys[G * 256 + col]) + 8 * kg) = pv;
+                if (sums_row) bsum += (bfu((uint16_t)pv[0]) + bfu((uint16_t)(pv[0] >> 16))) + (bfu((uint16_t)pv[1]) + bfu((uint16_t)(pv[1] >> 16)));
+            }
+            if (heads_row) {
+                const uint4 b0v = Bhl[pb][mt][0][lane], b1v = Bhl[pb][mt][1][lane];
+                u32x4_l x0, x1;
+                x0[0] = st.hq[4 * mt][0]; x0[1] = st.hq[4 * mt][1]; x0[2] = st.hq[4 * mt + 1][0]; x0[3] = st.hq[4 * mt + 1][1];
+                x1[0] = st.hq[4 * mt + 2][0]; x1[1] = st.hq[4 * mt + 2][1]; x1[2] = st.hq[4 * mt + 3][0]; x1[3] = st.hq[4 * mt + 3][1];
+                acc2 = mfma_bf16(*reinterpret_cast<const bf8*>(&x0), *reinterpret_cast<const bf8*>(&b0v), acc2);
+                acc2 = mfma_bf16(*reinterpret_cast<const bf8*>(&x1), *reinterpret_cast<const bf8*>(&b1v), acc2);
+            }
+        }
+    };
+    f16v acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    auto compute = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < TB_BG; ks += 2) {                  // one MFMA step = 16 samples = 2 groups
+            bf8 bv[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bf8 av = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * i + l32]);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av, bv[j], acc[i][j]);
+            }
+        }
+    };
+    // stage i (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage i + 2; the head gradient of
+    // stage i + 1 (held in `nxt`) goes to the other halves of Ahl and Bhl
+    auto step = [&](Set& cur, const Set& nxt, int i, int pb) {
+        store(cur, pb);
+        if (i + 1 < n_stages) { stage_d(nxt, pb ^ 1); dbsum += nxt.d; }
+        __syncthreads();
+        fetch(cur, i + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        compute();
+        __syncthreads();
+    };
+    fetch(S0, 0);
+    fetch(S1, 1);
+    if (tid < 256) {
+        uint32_t w8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w8[k] = k < a.NH ? (uint32_t)a.wh16[(size_t)(j0 + tid) * a.NH + k] : 0u;
+        WhB[tid] = make_uint4(w8[0] | (w8[1] << 16), w8[2] | (w8[3] << 16), w8[4] | (w8[5] << 16), w8[6] | (w8[7] << 16));
+    }
+    reinterpret_cast<uint4*>(Bhl)[tid] = make_uint4(0, 0, 0, 0);  // output columns 16..31 of the dWh product stay zero
+    __syncthreads();
+    stage_d(S0, 0); dbsum += S0.d;
+    __syncthreads();
+    for (int i = 0; i < n_stages; i += 2) {
+        step(S0, S1, i, 0);
+        if (i + 1 < n_stages) step(S1, S0, i + 1, 1);
+    }
+    float* out = a.partial + (size_t)split * a.split_stride;
+#pragma unroll
+    for (int tr = 0; tr < 4; ++tr)
+#pragma unroll
+        for (int tc = 0; tc < 2; ++tc) {
+            const int j = j0 + wn * 64 + tc * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wm * 128 + tr * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+                out[(size_t)i * a.N + j] = acc[tr][tc][r];
+            }
+        }
+    if (!heads_row && !sums_row) return;
+    // column sums: the two lanes of a column add up in a fixed order; dWh: accumulator rows are columns j of the
+    // tile, accumulator columns k (hi terms) and 8 + k (lo terms)
+    float* red = reinterpret_cast<float*>(smem4);               // [256]
+    float* Sw = red + 256;                                      // [256 columns][16]
+    float* Sd = Sw + 256 * 16;                                  // [64 samples][8]
+    if (sums_row && kg == 1) red[col] = bsum;
+    if (heads_row) {
+        if (l32 < 16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Sw[(wave * 32 + 8 * (r >> 2) + 4 * kg + (r & 3)) * 16 + l32] = acc2[r];
+        }
+        Sd[ds * 8 + dk] = dbsum;
+    }
+    __syncthreads();
+    if (sums_row && kg == 0) out[(size_t)a.K * a.N + j0 + col] = bsum + red[col];
+    if (!heads_row) return;
+    float* hout = a.head_partial + (size_t)split * a.head_stride;
+    if (tid < 256)
+        for (int k = 0; k < a.NH; ++k) hout[(size_t)(j0 + tid) * a.NH + k] = Sw[tid * 16 + k] + Sw[tid * 16 + 8 + k];
+    if (tj == 0 && tid < a.NH) {
+        float sum = 0.0f;
+        for (int i = 0; i < 64; ++i) sum += Sd[i * 8 + tid];
+        hout[(size_t)a.N * a.NH + tid] = sum;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Maze first layer.  The observation has three one-hot planes (paper section 2.1 style grid
 // world: walls, agent, goal) and only the agent plane changes within an unroll, so
 //   dW1[wall cell c]  = sum_b walls[b][c] * S[b],   S[b] = sum_t dZ1[t][b]   (B samples, not B*T)
@@ -842,6 +1127,16 @@ bool bf16_dx_resident(const NetShape& n, int M, int l)
     return l == 1 || bf16_dx_resident(n, M, l - 1);
 }
 
+// Whether the top layer's products form dZ_L themselves (no head pass, no dZ_L in memory): both sides of the layer
+// multiples of 256, the dX product weights-resident, chunks of whole 64-sample stages.
+bool bf16_top_fused(const NetShape& n, int M, int splits_top)
+{
+    if (!n.bf16 || n.L < 2 || n.NH > 8) return false;
+    if (n.dims[n.L] % 256 != 0 || n.dims[n.L - 1] % 256 != 0) return false;
+    if (!bf16_dx_resident(n, M, n.L - 1)) return false;
+    return splits_top > 0 && M % splits_top == 0 && (M / splits_top) % 64 == 0;
+}
+
 hipError_t launch_backward_bf16(anakin* h)
 {
     const Layout& L = h->lay;
@@ -853,7 +1148,8 @@ hipError_t launch_backward_bf16(anakin* h)
     auto actP = [&](int l) { return at<uint16_t>(h, L.act[l]); };
     // dZ_l is kept sample-packed; the row-major copy exists only where the tiled dX kernel of layer l + 1 reads it
     auto needs_rows = [&](int l) { return l >= 1 && !bf16_dx_resident(n, M, l); };
-    {   // heads
+    const bool top_fused = bf16_top_fused(n, M, h->splits[n.L - 1]) && h->splits[n.L] == h->splits[n.L - 1] && h->head_fan == 1;
+    if (!top_fused) {   // heads
         HeadBwdBf16Args a;
         a.M = M; a.H = n.dims[n.L]; a.NH = n.NH; a.NHP = n.NHP;
         const int stage1 = h->splits[n.L] * h->head_fan;
@@ -949,7 +1245,20 @@ hipError_t launch_backward_bf16(anakin* h)
         t.obs = obs_src();
         t.sP = nullptr; t.T = h->T; t.env_block = 0;
         const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0 && t.rows % 64 == 0;
-        if ((e = run_tn(t, big, l == 0 ? "gemm_tn_obs" : "gemm_tn")) != hipSuccess) return e;
+        if (l == n.L - 1 && top_fused) {
+            GemmTnTopArgs u;
+            u.M = M; u.K = t.K; u.N = t.N; u.splits = t.splits; u.rows = t.rows; u.tiles_i = t.K / 256;
+            u.NH = n.NH; u.NHP = n.NHP;
+            u.xP = t.xP; u.hTop = actP(l); u.dhead = at<const float>(h, L.dhead);
+            u.wh16 = at<const uint16_t>(h, L.w16_src) + n.wh_off;
+            u.partial = t.partial; u.split_stride = t.split_stride;
+            u.head_partial = at<float>(h, L.part[n.L]); u.head_stride = (size_t)t.N * n.NH + n.NH;
+            const size_t lds = (size_t)2 * TB_BG * 256 * sizeof(uint4);
+            if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_bf16_top), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
+            ProfScope prof(h, "gemm_tn_top");
+            hipLaunchKernelGGL(gemm_tn_bf16_top, dim3(u.tiles_i * (u.N / 256) * u.splits), dim3(BIGWG), lds, h->stream, u);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        } else if ((e = run_tn(t, big, l == 0 ? "gemm_tn_obs" : "gemm_tn")) != hipSuccess) return e;
         if (l > 0) {
             GemmNtBf16Args g;
             g.M = M; g.K = n.dims[l]; g.N = n.dims[l + 1];
@@ -963,12 +1272,18 @@ hipError_t launch_backward_bf16(anakin* h)
             ProfScope prof(h, "gemm_nt_mask");
             if (bf16_dx_resident(n, M, l)) {
                 const size_t lds2 = (size_t)2 * NRES_RT * (g.N + 8) * sizeof(uint16_t);
-                const void* fn = g.N == 512 ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256>);
+                const bool top = l == n.L - 1 && top_fused;      // dZ_L comes out of the head gradient inside the kernel
+                g.hTop = actP(l); g.dhead = at<const float>(h, L.dhead);
+                g.wh16 = at<const uint16_t>(h, L.w16_src) + n.wh_off; g.NH = n.NH; g.NHP = n.NHP;
+                const void* fn = g.N == 512 ? (top ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<512, false>))
+                                            : (top ? reinterpret_cast<const void*>(gemm_nt_bf16_res<256, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256, false>));
                 e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
                 if (e != hipSuccess) return e;
                 const dim3 grid(((g.M + rows_per_block - 1) / rows_per_block) * (g.K / 256));
-                if (g.N == 512) hipLaunchKernelGGL((gemm_nt_bf16_res<512>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
-                else hipLaunchKernelGGL((gemm_nt_bf16_res<256>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                if (g.N == 512 && top) hipLaunchKernelGGL((gemm_nt_bf16_res<512, true>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else if (g.N == 512) hipLaunchKernelGGL((gemm_nt_bf16_res<512, false>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else if (top) hipLaunchKernelGGL((gemm_nt_bf16_res<256, true>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
+                else hipLaunchKernelGGL((gemm_nt_bf16_res<256, false>), grid, dim3(NRES_WG), lds2, h->stream, g, rows_per_block);
             } else {
                 const size_t lds2 = (size_t)2 * 128 * NB_LD * sizeof(uint16_t);
                 e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_bf16), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
