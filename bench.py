@@ -53,8 +53,9 @@ def measured_traffic(workload):
     return out, commit
 
 
-def kernel_models(cfg, P):
-    """Algorithmic work per launch of each kernel: (bound, amount, unit-peak, unit)."""
+def kernel_models(cfg, P, launched=()):
+    """Algorithmic work per launch of each kernel: (bound, amount, unit-peak, unit).  `launched`: the kernel names the
+    instrumented pass saw (which products a fused kernel took over depends on the plan)."""
     B, T = cfg["B"], cfg["T"]
     M = B * T
     kind = cfg["env"]["kind"]
@@ -83,8 +84,12 @@ def kernel_models(cfg, P):
         # scatter of dZ1 rows into the selected weight rows: one read of dZ1
         "first_layer_grad": ("hbm", 4.0 * dims[1] * M / 1e9, PEAK_HBM_GBS, "GB/s"),
     }
-    tn = sum(2.0 * dims[i] * dims[i + 1] * M for i in range(1, len(dims) - 1))
-    nt = tn
+    # bf16 top layer with the heads folded in: its dW product is a launch of its own (gemm_tn_top) that reads
+    # h_{L-1}, h_L and the head gradient and forms dZ_L itself
+    top_fused = "gemm_tn_top" in launched
+    tn_layers = range(1, len(dims) - (2 if top_fused else 1))
+    tn = sum(2.0 * dims[i] * dims[i + 1] * M for i in tn_layers)
+    nt = sum(2.0 * dims[i] * dims[i + 1] * M for i in range(1, len(dims) - 1))
     models["gemm_tn"] = ("mfma", tn / 1e12, mfma_peak, "TFLOP/s")
     models["gemm_nt_mask"] = ("mfma", nt / 1e12, mfma_peak, "TFLOP/s")
     if bf16:
@@ -92,11 +97,17 @@ def kernel_models(cfg, P):
         # resp. 2 (K + N) B (dW: both operands read) is 170 resp. 256 flop/B for 512-wide layers, below the
         # machine balance of 2500 / 8 = 312 flop/B: both GEMMs sit on the HBM roof, not the matrix-core one
         nt_bytes = sum(2.0 * (dims[i + 1] + 2 * dims[i]) * M for i in range(1, len(dims) - 1))
-        tn_bytes = sum(2.0 * (dims[i] + dims[i + 1]) * M for i in range(1, len(dims) - 1))
+        tn_bytes = sum(2.0 * (dims[i] + dims[i + 1]) * M for i in tn_layers)
         if nt / max(nt_bytes, 1.0) < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
             models["gemm_nt_mask"] = ("hbm", nt_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
         if tn / max(tn_bytes, 1.0) < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
             models["gemm_tn"] = ("hbm", tn_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
+    if top_fused:
+        top_flop = 2.0 * dims[-2] * dims[-1] * M
+        top_bytes = (2.0 * (dims[-2] + dims[-1]) + 4.0 * NH) * M
+        models["gemm_tn_top"] = ("mfma", top_flop / 1e12, mfma_peak, "TFLOP/s")
+        if top_flop / top_bytes < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+            models["gemm_tn_top"] = ("hbm", top_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
     # a layer whose two products run as one launch (256-wide fp32 layers): both counted
     models["gemm_tn_nt"] = ("mfma", (tn + nt) / 1e12, mfma_peak, "TFLOP/s")
     models["gemm_tn_obs"] = ("mfma", 2.0 * dims[0] * dims[1] * M / 1e12, mfma_peak, "TFLOP/s")
@@ -107,9 +118,20 @@ def kernel_models(cfg, P):
         models["time_sum"] = ("hbm", (2.0 * dims[1] * M + 4.0 * dims[1] * B) / 1e9, PEAK_HBM_GBS, "GB/s")
         models["gemm_tn_walls"] = ("mfma", 2.0 * cells * dims[1] * 2 * B / 1e12, mfma_peak, "TFLOP/s")
         models["gemm_tn_agent"] = ("mfma", 2.0 * cells * dims[1] * M / 1e12, mfma_peak, "TFLOP/s")
+        # the X operand is a one-hot built in the kernel from 4 B per sample: what streams is dZ1 (2 B per entry), and at
+        # 2 cells flop per byte of it the product sits under the HBM roof for planes of up to 312 cells
+        agent_bytes = (2.0 * dims[1] + 4.0) * M + 4.0 * dims[1] * B
+        if bf16 and 2.0 * cells * dims[1] * M / agent_bytes < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+            models["gemm_tn_agent"] = ("hbm", agent_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
     if len(hid) == 1:
         # fused update of a one-hidden-layer net: reads state, head gradient and returns, rebuilds the layer
         models["learn_one_layer"] = ("alu", 2.0 * (2 * first_rows * dims[1] + 3 * dims[1] * NH) * M / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s")
+        # the same arithmetic with the scan and the loss in the launch (their flops are not counted)
+        models["learn_catch_fused"] = models["learn_one_layer"]
+    # small nets, whole update in one launch: the backward products (dZ, dW per layer and head) and 12 flop per
+    # parameter of Adam; a latency-bound launch, the model is there for the record
+    models["learn_small_fused"] = ("alu", (2.0 * (2 * first_rows * dims[1] + 2 * dense_act + 2 * dims[-1] * NH) * M + 12.0 * P) / 1e12,
+                                   PEAK_FP32_TFLOPS, "TFLOP/s")
     return models, snap
 
 
@@ -200,7 +222,7 @@ def measure(binding, torch, name, cfg, steps, warmup, halves=False, valu_gemm=Fa
         g.step()
     times = g.kernel_times()
     g.profile(False)
-    models, _ = kernel_models(cfg, g.P)
+    models, _ = kernel_models(cfg, g.P, launched=tuple(times))
     per_kernel = {}
     for kname, (calls, total) in times.items():
         launches_per_step = calls / steps
