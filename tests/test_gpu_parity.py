@@ -285,28 +285,16 @@ def test_bf16_matrix_core_path(gpu, orc, case):
     _forced_lockstep(gpu, orc, cfg, seed, updates)
 
 
-@pytest.mark.parametrize("B,T", [(1024, 32), (8192, 2)])
-def test_bf16_benchmark_widths_steady_state(gpu, orc, B, T):
-    """The maze workload's own layer widths (768-512-512-512, bf16) with enough samples that every update kernel
-    runs its steady-state loop, not just its prologue.  B = 1024, T = 32: the weights-resident dX kernel walks
-    >= 4 stages of 32 samples per workgroup (its ring holds rows two stages and the mask one stage ahead), the
-    256 x 256-tile dW kernel >= 8 LDS stages of 64 samples per chunk on the hidden layers (double-buffered, next
-    step prefetched) and >= 4 on the agent plane.  B = 8192, T = 2: the wall-plane product, whose rows are the
-    2 B time-summed ones, reaches >= 4 stages per chunk in several chunks, and the time sum runs at a large B.
-    Logit-forced lockstep over all envs; the oracle's update is spread over threads by sample range."""
-    cfg = variant("maze_16384", B=B, T=T)
-    say(f"[bf16 steady state] B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+def _steady_state_update(gpu, orc, cfg, check_plan, n_head_envs):
+    """One whole update of a bf16 maze net at a size where the update kernels run their steady-state loops:
+    logit-forced lockstep over all envs, head outputs checked on a sample of envs at every time step, the oracle's
+    update spread over threads by sample range.  check_plan(plan, B, T) asserts on the launch plan."""
+    B, T = cfg["B"], cfg["T"]
     g = gpu.Anakin(cfg, seed=9); o = orc.Oracle(cfg, seed=9)
-    M = B * T
     plan = g.plan()
     say(f"  plan {plan}")
     assert plan["bf16_matrix_path"] == 1
-    if T == 32:
-        assert all(plan["dx_rows"][l] >= 4 * 32 for l in (1, 2)), "dX kernel: fewer than 4 stages per workgroup"
-        assert all(M // plan["splits"][l] >= 8 * 64 for l in (1, 2)), "dW kernel: fewer than 8 LDS stages per chunk"
-        assert M // plan["splits"][0] >= 4 * 64, "agent-plane product: fewer than 4 LDS stages per chunk"
-    else:
-        assert plan["splits_walls"] > 1 and 2 * B // plan["splits_walls"] >= 4 * 64, "wall-plane product: fewer than 4 LDS stages per chunk"
+    check_plan(plan, B, T)
     PT.assert_same_init(g, o, "maze")
     g.step()                                     # the compared update starts from non-initial parameters and moments
     PT.sync_oracle_from_gpu(g, o)
@@ -319,7 +307,7 @@ def test_bf16_benchmark_widths_steady_state(gpu, orc, B, T):
     PT.assert_rollout_equal(g, o, "maze", forced=True)
     PT.assert_final_state_equal(g, o, "maze")
     rng = np.random.default_rng(9)
-    sel = np.unique(np.concatenate([[0, 63, 64, B - 1], rng.integers(0, B, 12 if T == 32 else 60)])).astype(np.int32)
+    sel = np.unique(np.concatenate([[0, 63, 64, B - 1], rng.integers(0, B, n_head_envs)])).astype(np.int32)
     worst = PT.assert_heads_close(g, o, tr, TOL_BF16, sel=sel)
     say(f"  head err {worst:.2e} over {sel.size} envs x {g.T + 1} steps; update on the oracle ...")
     g.learn()
@@ -327,6 +315,47 @@ def test_bf16_benchmark_widths_steady_state(gpu, orc, B, T):
     e_g, e_p = PT.assert_learn_close(g, o, TOL_BF16)
     say(f"  gradient rel err {e_g:.2e}, parameter rel err {e_p:.2e}")
     g.close()
+
+
+@pytest.mark.parametrize("B,T", [(1024, 32), (8192, 2)])
+def test_bf16_benchmark_widths_steady_state(gpu, orc, B, T):
+    """The maze workload's own layer widths (768-512-512-512, bf16) with enough samples that every update kernel
+    runs its steady-state loop, not just its prologue.  B = 1024, T = 32: the weights-resident dX kernel walks
+    >= 4 stages of 32 samples per workgroup (its ring holds rows two stages and the mask one stage ahead), the
+    256 x 256-tile dW kernels (the top one forms dZ_L itself) >= 8 LDS stages of 64 samples per chunk on the hidden
+    layers (double-buffered, next step prefetched) and >= 4 on the agent plane.  B = 8192, T = 2: the wall-plane
+    product, whose rows are the 2 B time-summed ones, reaches >= 4 stages per chunk in several chunks."""
+    cfg = variant("maze_16384", B=B, T=T)
+    say(f"[bf16 steady state] B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+
+    def check_plan(plan, B, T):
+        M = B * T
+        if T == 32:
+            assert all(plan["dx_rows"][l] >= 4 * 32 for l in (1, 2)), "dX kernel: fewer than 4 stages per workgroup"
+            assert all(M // plan["splits"][l] >= 8 * 64 for l in (1, 2)), "dW kernel: fewer than 8 LDS stages per chunk"
+            assert M // plan["splits"][0] >= 4 * 64, "agent-plane product: fewer than 4 LDS stages per chunk"
+            assert plan["splits"][3] == plan["splits"][2] and plan["head_fan"] == 1, "top layer: the head pass is not folded in"
+        else:
+            assert plan["splits_walls"] > 1 and 2 * B // plan["splits_walls"] >= 4 * 64, "wall-plane product: fewer than 4 LDS stages per chunk"
+
+    _steady_state_update(gpu, orc, cfg, check_plan, 12 if T == 32 else 60)
+
+
+def test_bf16_agent_plane_sums_over_time_in_the_product(gpu, orc):
+    """The benchmark's batch size with a narrower net (768-256-256, so the oracle can follow all 131072 samples):
+    B = 16384 divides into blocks of 128 environments per chunk of the agent-plane product, which then walks them as
+    two passes of 64 environments over the T = 8 time steps and writes the time sum of dZ1 itself (no separate
+    pass); the wall-plane product reads that sum.  Also the 256-wide form of the fused top layer (one row of tiles
+    carries both the head matrix's gradient and the column sums)."""
+    cfg = variant("maze_16384", hidden=[256, 256], B=16384, T=8)
+    say(f"[bf16 agent plane by environment blocks] B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
+
+    def check_plan(plan, B, T):
+        s0 = plan["splits"][0]
+        assert B % (64 * s0) == 0 and B // s0 >= 128, "agent-plane chunks are not blocks of >= 128 environments"
+        assert plan["splits"][2] == plan["splits"][1] and plan["head_fan"] == 1, "top layer: the head pass is not folded in"
+
+    _steady_state_update(gpu, orc, cfg, check_plan, 40)
 
 
 def test_bf16_reference_mode_is_exact(gpu, orc):
