@@ -296,9 +296,10 @@ def main():
         for name, kind, unit, peak in (("mfma_f32", binding.PROBE_MFMA_F32, "TFLOP/s", PEAK_FP32_TFLOPS),
                                        ("mfma_bf16", binding.PROBE_MFMA_BF16, "TFLOP/s", PEAK_BF16_TFLOPS),
                                        ("copy", binding.PROBE_COPY, "GB/s", PEAK_HBM_GBS),
+                                       ("read_only", binding.PROBE_READ, "GB/s", PEAK_HBM_GBS),
                                        ("adam_2^26_params", binding.PROBE_ADAM, "GB/s", PEAK_HBM_GBS)):
             best, best_wg = 0.0, 0
-            for wg in ((1024, 4096, 16384, 65536) if name == "copy" else (0,) if kind == binding.PROBE_ADAM else (256, 512, 768, 1024, 2048)):
+            for wg in ((1024, 4096, 16384, 65536) if name in ("copy", "read_only") else (0,) if kind == binding.PROBE_ADAM else (256, 512, 768, 1024, 2048)):
                 for _ in range(2):
                     amount, ms = binding.peak_probe(kind, scratch, stream, wg)
                     rate = amount / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)

@@ -49,13 +49,21 @@ __global__ __launch_bounds__(WG) void probe_copy(const pf4v* __restrict__ src, p
     for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n4; i += (size_t)gridDim.x * WG) dst[i] = src[i];
 }
 
+// read-only stream: every thread adds up what it reads; one word per thread leaves (so the loads cannot be dropped)
+__global__ __launch_bounds__(WG) void probe_read(const pf4v* __restrict__ src, float* __restrict__ out, size_t n4)
+{
+    pf4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n4; i += (size_t)gridDim.x * WG) acc += src[i];
+    out[(size_t)blockIdx.x * WG + threadIdx.x] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+}
+
 }  // namespace ank
 
 extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratch, size_t scratch_bytes, void* hip_stream,
                                      double* amount, double* milliseconds)
 {
     using namespace ank;
-    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 3 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
+    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 4 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ANAKIN_E_HIP;
@@ -73,6 +81,18 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
         for (int r = 0; r < 10; ++r) hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);
         (void)hipEventRecord(e1, s);
         *amount = 10.0 * 2.0 * (double)half;                 // bytes read + written
+    } else if (kind == ANAKIN_PROBE_READ) {
+        const int blocks = variant > 0 ? variant : 4096;
+        const size_t tail = ((size_t)blocks * WG * 4 + 255) & ~(size_t)255;   // the sums go behind the range that is read
+        if (scratch_bytes < tail + 256) return ANAKIN_E_INVALID_ARG;
+        const size_t n4 = ((scratch_bytes - tail) & ~(size_t)255) / 16;
+        auto* src = static_cast<pf4v*>(scratch);
+        float* out = reinterpret_cast<float*>(static_cast<char*>(scratch) + n4 * 16);
+        hipLaunchKernelGGL(probe_read, dim3(blocks), dim3(WG), 0, s, src, out, n4);    // warm-up
+        (void)hipEventRecord(e0, s);
+        for (int r = 0; r < 10; ++r) hipLaunchKernelGGL(probe_read, dim3(blocks), dim3(WG), 0, s, src, out, n4);
+        (void)hipEventRecord(e1, s);
+        *amount = 10.0 * 16.0 * (double)n4;                  // bytes read
     } else if (kind == ANAKIN_PROBE_ADAM) {
         // theta | grad | m | v | one partial, P floats each; zeroed so that no value overflows over the repetitions
         size_t P = scratch_bytes / 20;
