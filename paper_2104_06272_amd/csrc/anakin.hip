@@ -163,6 +163,7 @@ static void carve(const EnvDims& ed, const NetShape& ns, int B, int T, const int
     for (int l = 0; l < MAX_LAYERS; ++l) {
         const size_t w = l < ns.L ? (size_t)ns.dims[l + 1] : 0;
         L.act[l] = take(tn * w * 4);
+        L.mask[l] = L.act[l] + tn * w * 2;                       // packed bf16 activations use the lower half only
     }
     off += carve_update_scratch(ed, ns, B, T, splits, splits_w, head_fan, L, off);
     L.prefix = take(ns.bf16 ? (size_t)B * ns.dims[1] * 4 : 0);
@@ -482,7 +483,7 @@ void fill_rollout_args(anakin* h, RolloutArgs& a)
     t.tr_act = at<uint8_t>(h, L.tr_act); t.tr_eps = at<float>(h, L.tr_eps); t.tr_actf = at<float>(h, L.tr_actf);
     t.tr_rew = at<float>(h, L.tr_rew); t.tr_done = at<uint8_t>(h, L.tr_done);
     t.tr_val = at<float>(h, L.tr_val); t.tr_head = at<float>(h, L.tr_head);
-    for (int l = 0; l < MAX_LAYERS; ++l) t.act[l] = at<float>(h, L.act[l]);
+    for (int l = 0; l < MAX_LAYERS; ++l) { t.act[l] = at<float>(h, L.act[l]); t.mask[l] = at<uint32_t>(h, L.mask[l]); }
 }
 }  // namespace ank
 
@@ -652,7 +653,7 @@ extern "C" int32_t anakin_learn(anakin_t* h)
         L.tr_act += r0; L.tr_eps += r0 * 4; L.tr_actf += r0 * 4; L.tr_rew += r0 * 4; L.tr_done += r0;
         L.tr_val += r0 * 4; L.tr_head += r0 * n.NHP * 4;
         L.adv += r0 * 4; L.ret += r0 * 4;
-        for (int l = 0; l < n.L; ++l) L.act[l] += r0 * n.dims[l + 1] * (h->traj_packed ? 2 : 4);
+        for (int l = 0; l < n.L; ++l) { L.act[l] += r0 * n.dims[l + 1] * (h->traj_packed ? 2 : 4); L.mask[l] += r0 * n.dims[l + 1] / 4; }
         L.loss_part += (size_t)k * h->sub_loss_blocks * 8 * 4;
         rc = run_update(h);
         for (int l = 0; l < MAX_REGIONS; ++l) h->splits[l] = full_splits[l];

@@ -34,7 +34,17 @@ struct TrajPtrs {
     float* tr_val;                                                     // [T+1][B]
     float* tr_head;                                                    // [T+1][B][NHP]
     float* act[MAX_LAYERS];                                            // [T*B][H_l] hidden activations
+    uint32_t* mask[MAX_LAYERS];                                        // bf16 matrix-core path: which of them are positive, see relu_mask_index
 };
+
+// ReLU masks of the bf16 matrix-core path, written by the acting kernels beside the packed activations and read by
+// the dX products of the update in place of the activations themselves (1/8 of the bytes).  One 32-bit word per
+// (stage of 32 consecutive samples, half kg of the accumulator rows, column): [M/32][2][H].  Lane (column, kg) of a
+// 32 x 32 MFMA accumulator tile holds rows 8g + 4kg + q (g, q = 0..3) as value r = 4g + q; bit relu_mask_bit(r) of
+// its word says that this activation is positive.  (Values come in packed pairs; pair r/2 puts the flag of its low
+// half in bit r/2 and of its high half in bit 16 + r/2, which costs the producer two instructions per pair.)
+ANK_HD size_t relu_mask_index(size_t stage, int kg, int H, int col) { return (stage * 2 + (size_t)kg) * (size_t)H + (size_t)col; }
+ANK_HD int relu_mask_bit(int r) { return (r >> 1) + 16 * (r & 1); }
 
 struct RolloutArgs {
     EnvDims env;
@@ -105,6 +115,7 @@ struct Layout {
     size_t tr_s0, tr_f0, tr_f1, tr_act, tr_eps, tr_actf, tr_rew, tr_done, tr_val, tr_head;
     size_t adv, ret, dhead;
     size_t act[MAX_LAYERS], dz[MAX_LAYERS];
+    size_t mask[MAX_LAYERS];      // bf16 matrix-core path: ReLU masks, inside the unused upper half of act[l]
     size_t part[MAX_REGIONS];
     size_t head_stage;           // first-stage partials of the head gradient
     size_t prefix;               // bf16 acting: per-env first-layer prefix [B][H1] fp32

@@ -51,6 +51,14 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// value r of an accumulator tile where its flag in a ReLU mask word (relu_mask_bit) is set, else +0: the flag is
+// spread over the word by a signed one-bit field extract and ANDed onto the value's bits
+__device__ __forceinline__ float keep_if(float x, uint32_t mask_word, int r)
+{
+    const int m = (int)(mask_word << (31 - relu_mask_bit(r))) >> 31;
+    return __builtin_bit_cast(float, __builtin_bit_cast(int, x) & m);
+}
+
 // two ReLU outputs as bfloat16 in a word (never negative, never -0: relu() returns +0 for every non-positive input)
 // -> 0xffff in the halves that are positive, i.e. not zero, and 0 in the others.  Packed 16-bit integer instructions:
 // min(h, 1) is 0 or 1, and 0 - that is 0 or 0xffff.
@@ -227,7 +235,8 @@ struct GemmNtBf16Args {
     uint16_t* dxP;            // [M/8][K][8]
     // top layer of the weights-resident kernel: dY = dZ_L is not read but formed from the head gradient,
     // dZ_L[m][j] = relu'(hTop[m][j]) * sum_k dhead[m][k] Wh[j][k]
-    const uint16_t* hTop;     // packed h_L: [M/8][N][8]
+    const uint32_t* maskTop;  // ReLU mask words of h_L (relu_mask_index)
+    const uint32_t* maskLo;   // ReLU mask words of h_{l-1}, or null: the mask is then taken from hP
     const float* dhead;       // [M][NHP]
     const uint16_t* wh16;     // bf16 copy of Wh: [N][NH]
     int NH, NHP;
@@ -366,9 +375,9 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     // Two register sets of staged pieces: those of stage s + 2 are requested while stage s is computed, so a load
     // has two stage times to come back (one stage is shorter than the memory latency under load, and this kernel
     // lives on the HBM roof).  The relu mask of stage s + 1 is requested one stage ahead for the same reason.
-    // HEADS: the staged pieces are those of packed h_L in accumulator order instead (tile jt of the wavefront's
-    // columns, group g, samples 4kg..4kg+3: 8 bytes, two per register quad), and going to LDS means one MFMA per
-    // tile, d (hi, lo) against (Wh, Wh), masked by them
+    // HEADS: what is staged is the ReLU mask word of h_L for each 32-column tile jt of the wavefront's columns
+    // instead (16 flags, one per accumulator value), and going to LDS means one MFMA per tile, d (hi, lo) against
+    // (Wh, Wh), masked by them
     u32x4_l stA[NQ], stB[NQ];
     __shared__ uint4 WhB[HEADS ? NR : 1];                        // row j of Wh, eight entries (zero past NH): the B operand of column j
     if (HEADS) {
@@ -383,13 +392,7 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
         if (HEADS) {
 #pragma unroll
             for (int jt = 0; jt < TJ; ++jt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const u32x2_l v = *reinterpret_cast<const u32x2_l*>(
-                        a.hTop + ((size_t)((m0 >> 3) + g) * NR + wave * (NR / 8) + 32 * jt + l32) * 8 + 4 * kg);
-                    st[(4 * jt + g) >> 1][2 * (g & 1)] = v[0];
-                    st[(4 * jt + g) >> 1][2 * (g & 1) + 1] = v[1];
-                }
+                st[0][jt] = a.maskTop[relu_mask_index((size_t)(m0 >> 5), kg, NR, wave * (NR / 8) + 32 * jt + l32)];
             return;
         }
 #pragma unroll
@@ -411,10 +414,11 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
                 const uint4 wv = WhB[wave * (NR / 8) + 32 * jt + l32];
                 acc1 = mfma_bf16(a1, *reinterpret_cast<const bf8*>(&wv), acc1);
                 uint16_t* dst = buf + (4 * kg) * LD + wave * (NR / 8) + 32 * jt + l32;
+                const uint32_t bits = st[0][jt];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const uint32_t p01 = cvt_pk_bf16(acc1[4 * g], acc1[4 * g + 1]) & positive_mask_pk(st[(4 * jt + g) >> 1][2 * (g & 1)]);
-                    const uint32_t p23 = cvt_pk_bf16(acc1[4 * g + 2], acc1[4 * g + 3]) & positive_mask_pk(st[(4 * jt + g) >> 1][2 * (g & 1) + 1]);
+                    const uint32_t p01 = cvt_pk_bf16(keep_if(acc1[4 * g], bits, 4 * g), keep_if(acc1[4 * g + 1], bits, 4 * g + 1));
+                    const uint32_t p23 = cvt_pk_bf16(keep_if(acc1[4 * g + 2], bits, 4 * g + 2), keep_if(acc1[4 * g + 3], bits, 4 * g + 3));
                     dst[(8 * g + 0) * LD] = (uint16_t)p01; dst[(8 * g + 1) * LD] = (uint16_t)(p01 >> 16);
                     dst[(8 * g + 2) * LD] = (uint16_t)p23; dst[(8 * g + 3) * LD] = (uint16_t)(p23 >> 16);
                 }
@@ -448,6 +452,7 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     const uint32_t lane_off = (uint32_t)i * 8u + 4u * kg;        // inside a packed group of eight samples
     u32x2_l maskA[4], maskB[4];
     auto fetch_mask = [&](u32x2_l (&mk)[4], int m0) {
+        if (a.maskLo) { mk[0][0] = a.maskLo[relu_mask_index((size_t)(m0 >> 5), kg, a.K, i)]; return; }
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             mk[g] = *reinterpret_cast<const u32x2_l*>(a.hP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off);
@@ -485,10 +490,15 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             float o[4];
+            if (a.maskLo) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float hv = bfu((uint16_t)((mask[g][q >> 1] >> ((q & 1) * 16)) & 0xffffu));
-                o[q] = hv > 0.0f ? acc[4 * g + q] : 0.0f;
+                for (int q = 0; q < 4; ++q) o[q] = keep_if(acc[4 * g + q], mask[0][0], 4 * g + q);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float hv = bfu((uint16_t)((mask[g][q >> 1] >> ((q & 1) * 16)) & 0xffffu));
+                    o[q] = hv > 0.0f ? acc[4 * g + q] : 0.0f;
+                }
             }
             u32x2_l pv; pv[0] = cvt_pk_bf16(o[0], o[1]); pv[1] = cvt_pk_bf16(o[2], o[3]);
             *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
@@ -1273,7 +1283,10 @@ hipError_t launch_backward_bf16(anakin* h)
             if (bf16_dx_resident(n, M, l)) {
                 const size_t lds2 = (size_t)2 * NRES_RT * (g.N + 8) * sizeof(uint16_t);
                 const bool top = l == n.L - 1 && top_fused;      // dZ_L comes out of the head gradient inside the kernel
-                g.hTop = actP(l); g.dhead = at<const float>(h, L.dhead);
+                g.maskTop = at<const uint32_t>(h, L.mask[l]); g.dhead = at<const float>(h, L.dhead);
+                // the mask of the layer below as flag words where the acting kernel writes them (every layer it runs
+                // on the matrix cores; the first layer only at 512 columns)
+                g.maskLo = (l - 1 >= 1 || n.dims[1] == 512) ? at<const uint32_t>(h, L.mask[l - 1]) : nullptr;
                 g.wh16 = at<const uint16_t>(h, L.w16_src) + n.wh_off; g.NH = n.NH; g.NHP = n.NHP;
                 const void* fn = g.N == 512 ? (top ? reinterpret_cast<const void*>(gemm_nt_bf16_res<512, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<512, false>))
                                             : (top ? reinterpret_cast<const void*>(gemm_nt_bf16_res<256, true>) : reinterpret_cast<const void*>(gemm_nt_bf16_res<256, false>));

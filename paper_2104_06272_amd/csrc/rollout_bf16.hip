@@ -50,6 +50,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 __device__ __forceinline__ float relu(float x) { return x > 0.0f ? x : 0.0f; }
+// two packed ReLU outputs (never negative, never -0) -> 1 in bit 0 resp. bit 16 where the half is not zero
+__device__ __forceinline__ uint32_t nonzero_flags_pk(uint32_t w)
+{
+    uint32_t r;
+    const uint32_t one = 0x00010001u;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(w), "v"(one));
+    return r;
+}
 
 struct RolloutBf16Args {
     EnvDims env;
@@ -70,7 +78,8 @@ struct RolloutBf16Args {
 template <int NT>
 __device__ __forceinline__ void bf16_layer(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int ldx,
                                            const uint16_t* __restrict__ Wt, const float* __restrict__ bias,
-                                           int K, int N, int wave, int lane, uint16_t* __restrict__ gP, size_t g8)
+                                           int K, int N, int wave, int lane, uint16_t* __restrict__ gP, size_t g8,
+                                           uint32_t* __restrict__ gM)
 {
     const int l32 = lane & 31, kg = lane >> 5;
     const int n0 = wave * 32 * NT;
@@ -121,6 +130,7 @@ __device__ __forceinline__ void bf16_layer(const uint16_t* __restrict__ X, uint1
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int col = n0 + 32 * t + l32;
+            uint32_t mk = 0u;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int row = mt * 32 + 8 * g + 4 * kg;
@@ -132,8 +142,10 @@ __device__ __forceinline__ void bf16_layer(const uint16_t* __restrict__ X, uint1
                     // written once, read by the update: streaming stores leave the weights in L2
                     u32v2 pv; pv[0] = p01; pv[1] = p23;
                     __builtin_nontemporal_store(pv, reinterpret_cast<u32v2*>(gP + ((g8 + mt * 4 + g) * N + col) * 8 + 4 * kg));
+                    mk |= (nonzero_flags_pk(p01) << (2 * g)) | (nonzero_flags_pk(p23) << (2 * g + 1));
                 }
             }
+            if (gP) __builtin_nontemporal_store(mk, gM + relu_mask_index((g8 >> 2) + mt, kg, N, col));
         }
 }
 
@@ -148,7 +160,7 @@ template <int NT>
 __device__ __forceinline__ void bf16_layer_stream(const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int ldx,
                                                   const uint16_t* __restrict__ Wt, const uint16_t* __restrict__ Wt_next,
                                                   const float* __restrict__ bias, int K, int N, int wave, int lane,
-                                                  uint16_t* __restrict__ gP, size_t g8,
+                                                  uint16_t* __restrict__ gP, size_t g8, uint32_t* __restrict__ gM,
                                                   bf8 (&w0)[4][NT], bf8 (&w1)[4][NT])
 {
     constexpr int U = 4;
@@ -202,6 +214,7 @@ __device__ __forceinline__ void bf16_layer_stream(const uint16_t* __restrict__ X
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int col = n0 + 32 * t + l32;
+            uint32_t mk = 0u;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int row = mt * 32 + 8 * g + 4 * kg;
@@ -212,8 +225,10 @@ __device__ __forceinline__ void bf16_layer_stream(const uint16_t* __restrict__ X
                 if (gP) {
                     u32v2 pv; pv[0] = p01; pv[1] = p23;
                     __builtin_nontemporal_store(pv, reinterpret_cast<u32v2*>(gP + ((g8 + mt * 4 + g) * N + col) * 8 + 4 * kg));
+                    mk |= (nonzero_flags_pk(p01) << (2 * g)) | (nonzero_flags_pk(p23) << (2 * g + 1));
                 }
             }
+            if (gP) __builtin_nontemporal_store(mk, gM + relu_mask_index((g8 >> 2) + mt, kg, N, col));
         }
 }
 
@@ -235,10 +250,10 @@ __device__ __forceinline__ void bf16_layer_first(const uint16_t* __restrict__ Wt
 }
 
 __device__ __forceinline__ void run_bf16_layer(const uint16_t* X, uint16_t* Y, int ldx, const uint16_t* Wt, const float* bias,
-                                               int K, int N, int wave, int lane, uint16_t* gP, size_t g8)
+                                               int K, int N, int wave, int lane, uint16_t* gP, size_t g8, uint32_t* gM)
 {
-    if (N >= 512) bf16_layer<2>(X, Y, ldx, Wt, bias, K, N, wave, lane, gP, g8);
-    else bf16_layer<1>(X, Y, ldx, Wt, bias, K, N, wave, lane, gP, g8);
+    if (N >= 512) bf16_layer<2>(X, Y, ldx, Wt, bias, K, N, wave, lane, gP, g8, gM);
+    else bf16_layer<1>(X, Y, ldx, Wt, bias, K, N, wave, lane, gP, g8, gM);
 }
 
 // H1: width of the first hidden layer (128, 256 or 512).  Thread (pair of columns cp, env slice eq)
@@ -411,6 +426,9 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                 }
             }
             uint16_t* actP = keep ? reinterpret_cast<uint16_t*>(tp.act[0]) : nullptr;
+            // with 32 environments per thread (H1 = 512) a thread holds whole 32-sample stages of its two columns
+            // and writes their ReLU masks (both row halves); narrower first layers leave the mask to the activations
+            uint32_t mkx[2] = {0u, 0u}, mky[2] = {0u, 0u};
 #pragma unroll
             for (int m0 = 0; m0 < EPT; m0 += 8) {
                 float v[8][2];
@@ -451,6 +469,20 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                     for (int q = 0; q < 4; ++q) { vx4[q] = px[q]; vy4[q] = py[q]; }
                     __builtin_nontemporal_store(vx4, dst);
                     __builtin_nontemporal_store(vy4, dst + 1);
+                    if (EPT == 32) {
+#pragma unroll
+                        for (int k2 = 0; k2 < 2; ++k2) {
+                            mkx[k2] |= (nonzero_flags_pk(px[2 * k2]) << (m0 >> 2)) | (nonzero_flags_pk(px[2 * k2 + 1]) << ((m0 >> 2) + 1));
+                            mky[k2] |= (nonzero_flags_pk(py[2 * k2]) << (m0 >> 2)) | (nonzero_flags_pk(py[2 * k2 + 1]) << ((m0 >> 2) + 1));
+                        }
+                    }
+                }
+            }
+            if (actP && EPT == 32) {
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    u32v2 mv; mv[0] = mkx[k2]; mv[1] = mky[k2];
+                    __builtin_nontemporal_store(mv, reinterpret_cast<u32v2*>(tp.mask[0] + relu_mask_index((g8 >> 2) + (e0 >> 5), k2, H1, c)));
                 }
             }
         }
@@ -464,7 +496,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             for (int l = 1; l < L; ++l) {
                 bf16_layer_stream<NTU>(cur, nxt, ldx, a.wt + a.net.w_off[l], l + 1 < L ? a.wt + a.net.w_off[l + 1] : nullptr,
                                        a.theta + a.net.b_off[l], H1, H1, wave, lane,
-                                       keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8, w0, w1);
+                                       keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8, tp.mask[l], w0, w1);
                 __syncthreads();
                 uint16_t* tmp = cur; cur = nxt; nxt = tmp;
             }
@@ -472,7 +504,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             for (int l = 1; l < L; ++l) {
                 const int K = a.net.dims[l], N = a.net.dims[l + 1];
                 run_bf16_layer(cur, nxt, ldx, a.wt + a.net.w_off[l], a.theta + a.net.b_off[l], K, N, wave, lane,
-                               keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8);
+                               keep ? reinterpret_cast<uint16_t*>(tp.act[l]) : nullptr, g8, tp.mask[l]);
                 __syncthreads();
                 uint16_t* tmp = cur; cur = nxt; nxt = tmp;
             }
