@@ -104,7 +104,7 @@ static int pick_splits(int M, int tiles, int max_splits, int quantum = 16)
     if (cap < 1) cap = 1;
     int s = M / quantum;
     while (s > cap && s % 2 == 0) s /= 2;
-    return s;
+    return s > 0 ? s : 1;
 }
 
 // largest split count <= cap whose chunks are whole multiples of `quantum` rows (1 if none)
@@ -229,12 +229,12 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
         // 256 x 256 tiles where both sides of a layer are multiples of 256: about one workgroup per CU
         for (int l = 1; l < ns.L; ++l)
             if (ns.dims[l] % 256 == 0 && ns.dims[l + 1] % 256 == 0)
-                splits[l] = pick_splits(M, (ns.dims[l] / 256) * (ns.dims[l + 1] / 256), 64, 64);
+                splits[l] = pick_splits(M, (ns.dims[l] / 256) * (ns.dims[l + 1] / 256), 64, 128);   // chunks: pairs of 64-sample stages
         const int cells = ed.rows * ed.cols;
-        if (ed.kind == ENV_MAZE && cells % 256 == 0 && ns.dims[1] % 256 == 0) {
+        if (ed.kind == ENV_MAZE && cells % 256 == 0 && ns.dims[1] % 256 == 0 && M % 128 == 0) {
             const int tiles = (cells / 256) * (ns.dims[1] / 256);
-            splits[0] = pick_splits(M, tiles, 128, 64);            // agent plane: all B*T samples
-            *splits_w = pick_splits(2 * B, tiles, 64, 64);         // wall plane: time-summed, two bf16 terms per env
+            splits[0] = pick_splits(M, tiles, 128, 128);           // agent plane: all B*T samples
+            *splits_w = pick_splits(2 * B, tiles, 64, 128);        // wall plane: time-summed, two bf16 terms per env
         }
     }
     int fan = 1;

@@ -469,23 +469,67 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
     fetch(stA, clampm(m_begin + NRES_RT));                       // stage 1, stored at the end of stage 0
     fetch_mask(maskA, m_begin);
     __syncthreads();
-    // one stage (of parity par): MFMAs on `cur`, epilogue with `mask`, then the staged pieces `st_next` (stage s + 1)
-    // go to `nxt`; the head gradient of stage s + 2 replaces that of stage s
+    // one stage (of parity par): MFMAs on `cur` with the KS two-byte stores that put stage s + 1 (`st_next`) into
+    // `nxt` spread between them, one per MFMA, so that the LDS writes and the vector work behind them run in the
+    // shadow of the matrix cores instead of in a phase of their own (nobody reads `nxt` during this stage; past the
+    // end the last stage is formed again, unused); then the epilogue with `mask`; the head gradient of stage s + 2
+    // replaces that of stage s
     auto stage = [&](int m0, int par, const uint16_t* cur, uint16_t* nxt, const u32x2_l (&mask)[4],
                      u32x4_l (&st_next)[NQ], u32x4_l (&st_fill)[NQ], u32x2_l (&mask_fill)[4]) {
         fetch(st_fill, clampm(m0 + 2 * NRES_RT));                // two stages ahead
         fetch_d(clampm(m0 + 2 * NRES_RT));
         fetch_mask(mask_fill, clampm(m0 + NRES_RT));             // one stage ahead
         __builtin_amdgcn_sched_barrier(0);
-        // HEADS: the next stage is formed first (nobody reads `nxt` in this stage), so that its vector work can run
-        // in the shadow of the MFMAs below; past the end it re-forms the last stage, unused
-        if (HEADS) store(st_next, nxt, par ^ 1);
+        // the KS values of this lane for the next stage, two per word, and the rows they go to
+        uint32_t pk[KS / 2];
+        uint16_t* wbase[HEADS ? TJ : 1];
+        if (HEADS) {
+            const uint4 a1v = Ahl[par ^ 1][lane];
+            const bf8 a1 = *reinterpret_cast<const bf8*>(&a1v);
+#pragma unroll
+            for (int jt = 0; jt < TJ; ++jt) {
+                f16v acc1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+                const uint4 wv = WhB[wave * (NR / 8) + 32 * jt + l32];
+                acc1 = mfma_bf16(a1, *reinterpret_cast<const bf8*>(&wv), acc1);
+                const uint32_t bits = st_next[0][jt];
+#pragma unroll
+                for (int w = 0; w < 8; ++w)
+                    pk[8 * jt + w] = cvt_pk_bf16(keep_if(acc1[2 * w], bits, 2 * w), keep_if(acc1[2 * w + 1], bits, 2 * w + 1));
+                wbase[jt] = nxt + (4 * kg) * LD + wave * (NR / 8) + 32 * jt + l32;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) pk[4 * q + w] = st_next[q][w];
+            wbase[0] = nxt + (NR == 512 ? tid : 8 * (tid >> 8) * LD + (tid & 255));
+        }
+        // store k: half k % 2 of word k / 2.  HEADS: word 2g + j of a tile holds rows 8g + 4kg + 2j, + 1 of its
+        // column; otherwise piece q = k / 8 is sample group q (NR = 512) or 2q + tid / 256 (NR = 256), sample k % 8
+        auto put = [&](int k) {
+            const uint16_t v = (uint16_t)(pk[k >> 1] >> ((k & 1) * 16));
+            if (HEADS) {
+                const int jt = k >> 4, kk = k & 15;
+                wbase[HEADS ? jt : 0][(8 * (kk >> 2) + 2 * ((kk >> 1) & 1) + (kk & 1)) * LD] = v;
+            } else {
+                wbase[0][((NR == 512 ? 8 : 16) * (k >> 3) + (k & 7)) * LD] = v;
+            }
+        };
         f16v acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
         const uint16_t* a_rd = cur + l32 * LD + 8 * kg;
+        bf8 av0 = *reinterpret_cast<const bf8*>(a_rd), av1 = *reinterpret_cast<const bf8*>(a_rd + 16);
 #pragma unroll
-        for (int s2 = 0; s2 < KS; ++s2) acc = mfma_bf16(*reinterpret_cast<const bf8*>(a_rd + 16 * s2), wreg[s2], acc);
+        for (int s2 = 0; s2 < KS; ++s2) {
+            const bf8 an = *reinterpret_cast<const bf8*>(a_rd + 16 * (s2 + 2 < KS ? s2 + 2 : 0));
+            acc = mfma_bf16(av0, wreg[s2], acc);
+            put(s2);
+            av0 = av1; av1 = an;
+            __builtin_amdgcn_sched_barrier(0);                   // keeps the read / MFMA / store order as written
+        }
         // rows 8g + 4kg + q of the stage, column i: half of one packed group per g
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -503,7 +547,6 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
             u32x2_l pv; pv[0] = cvt_pk_bf16(o[0], o[1]); pv[1] = cvt_pk_bf16(o[2], o[3]);
             *reinterpret_cast<u32x2_l*>(a.dxP + ((size_t)((m0 >> 3) + g) * a.K) * 8 + lane_off) = pv;
         }
-        if (!HEADS && m0 + NRES_RT < m_end) store(st_next, nxt, par ^ 1);
         store_d(par);
         __syncthreads();
     };
@@ -674,7 +717,7 @@ constexpr int TB_BG = 8;      // sample groups (of 8) per LDS stage: 64 samples
 // maze observation, a one-hot of the agent cell, built from the stage's 64 cell indices which pass
 // through LDS one stage ahead; 2: any observation rows, rebuilt piece by piece (obs_piece).
 // Two register sets hold the next two stages while the current one is multiplied, so every load
-// has two MFMA phases to arrive.  Chunks are whole stages of 64 samples (a.rows % 64 == 0).
+// has two MFMA phases to arrive.  Chunks are whole pairs of stages of 64 samples (a.rows % 128 == 0).
 template <int XMODE>
 __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a)
 {
@@ -707,13 +750,14 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
     auto fetch = [&](Set& st, int i) {
         if (i >= n_stages) i = n_stages - 1;                     // past the end: re-read the last stage, never used
         const int g0 = stage_g0(i);
+        // the cells first: they are needed one step before the rest of the set, and loads complete in issue order
+        if (XMODE == 1) st.pos = a.obs.s0[(size_t)g0 * 8 + (tid & 63)];
 #pragma unroll
         for (int q = 0; q < TB_BG / 2; ++q) {
             const int g = g0 + 2 * q + lg;
             if (XMODE == 0) st.x[q] = *reinterpret_cast<const u32x4_l*>(a.xP + ((size_t)g * a.K + i0 + lc) * 8);
             st.y[q] = *reinterpret_cast<const u32x4_l*>(a.dyP + ((size_t)g * a.N + j0 + lc) * 8);
         }
-        if (XMODE == 1) st.pos = a.obs.s0[(size_t)g0 * 8 + (tid & 63)] & 0xffffu;
     };
     float tsum[TB_BG / 2][8];                                    // by_env: sum over time of this thread's dY entries
 #pragma unroll
@@ -744,7 +788,9 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
             }
             *reinterpret_cast<u32x4_l*>(&Xs[gl * 256 + lc]) = x;
             *reinterpret_cast<u32x4_l*>(&Ys[gl * 256 + lc]) = st.y[q];
-            if (sums) {
+            // column sums in every workgroup, used only where `sums` holds: a branch here would split the stores
+            // into several basic blocks (and the workgroups that need the sums set the pace anyway)
+            if (XMODE != 1) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bsum += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
             }
@@ -828,7 +874,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
     // i + 2; the cells of stage i + 1 (held in `nxt`) go to the other cell buffer
     auto step = [&](Set& cur, const Set& nxt, int i, int pb) {
         store(cur, i, pb);
-        if (XMODE == 1 && tid < 64) posL[pb ^ 1][tid] = nxt.pos;
+        if (XMODE == 1 && tid < 64) posL[pb ^ 1][tid] = nxt.pos & 0xffffu;
         __syncthreads();
         fetch(cur, i + 2);
         __builtin_amdgcn_sched_barrier(0);
@@ -836,15 +882,23 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
         if (by_env && ti == 0 && (i + 1) % a.T == 0) flush_time_sum(i);
         __syncthreads();
     };
+    // S0's loads strictly before S1's: the scheduler is otherwise free to issue S1's first, and then the wait-count
+    // pass, which merges this state with the loop's own at the loop header, has to wait for every load in flight
+    // there on every trip (loads complete in issue order), which halves the look-ahead of one of the two sets
     fetch(S0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     fetch(S1, 1);
+    __builtin_amdgcn_sched_barrier(0);
     if (XMODE == 1) {
-        if (tid < 64) posL[0][tid] = S0.pos;
+        if (tid < 64) posL[0][tid] = S0.pos & 0xffffu;
         __syncthreads();
     }
-    for (int i = 0; i < n_stages; i += 2) {
+    // two steps per trip without a branch between them (chunks are whole pairs of stages, a.rows % 128 == 0): with a
+    // conditional second step the compiler's wait-count pass gives up counting at the loop header and waits for every
+    // load in flight there, which cuts the look-ahead of the loads to one step
+    for (int i = 0; i + 1 < n_stages; i += 2) {
         step(S0, S1, i, 0);
-        if (i + 1 < n_stages) step(S1, S0, i + 1, 1);
+        step(S1, S0, i + 1, 1);
     }
     float* out = a.partial + (size_t)split * a.split_stride;
 #pragma unroll
@@ -876,7 +930,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 // dWh = h_L^T d for their 256 columns (the same pieces of h_L are the A operand, see
 // head_backward_bf16 for the sample order) and, in the first of them, dbh; those of the second
 // row the column sums of dZ_L (the layer's bias gradient).  K and N multiples of 256; chunks are
-// whole stages.
+// whole pairs of stages (rows % 128 == 0).
 // ---------------------------------------------------------------------------
 struct GemmTnTopArgs {
     int M, K, N, splits, rows, tiles_i, NH, NHP;
@@ -898,8 +952,19 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
     __shared__ uint4 Ahl[2][2][64];          // [stage parity][32-sample tile]: d as (hi, lo), the A operand of the dZ_L product
     __shared__ uint4 Bhl[2][2][2][64];       // [stage parity][tile][16-sample step]: the same as the B operand of the dWh product
     __shared__ uint4 WhB[256];               // row j0 + c of Wh, eight entries (zero past NH)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, kg = lane >> 5;
+    // everything derived from the thread index is worked out again at the start of every step from a value the
+    // compiler cannot see through (derive): the dozen loop-invariant addresses it would otherwise keep in registers
+    // across the whole loop do not fit beside the accumulators, and a spilled register is reloaded through the same
+    // in-order counter as the staged loads, which would end their look-ahead
+    int tid = threadIdx.x, lane, wave, wm, wn, l32, kg, lc, lg, col, ds, dk;
+    auto derive = [&]() {
+        asm volatile("" : "+v"(tid));
+        lane = tid & 63; wave = tid >> 6; wm = wave >> 2; wn = wave & 3; l32 = lane & 31; kg = lane >> 5;
+        lc = tid & 255; lg = tid >> 8;                           // X loader: (row of the tile, parity of the sample group)
+        col = wave * 32 + l32;                                   // dZ_L: this lane's column of the tile
+        ds = tid >> 3; dk = tid & 7;                             // head gradient: (sample of the stage, head output)
+    };
+    derive();
     int split, tile;
     xcd_map((int)blockIdx.x, a.splits, a.tiles_i * (a.N / 256), split, tile);
     const int ti = tile % a.tiles_i, tj = tile / a.tiles_i;
@@ -909,21 +974,19 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
     // extras, one kind per row of tiles so that no workgroup carries both: the first row adds up dWh (and dbh), the
     // second (the first, if there is only one) the column sums of dZ_L
     const bool heads_row = ti == 0, sums_row = ti == (a.tiles_i > 1 ? 1 : 0);
-    const int lc = tid & 255, lg = tid >> 8;                     // X loader: (row of the tile, parity of the sample group)
-    const int col = wave * 32 + l32;                             // dZ_L: this lane's column of the tile
-    const int ds = tid >> 3, dk = tid & 7;                       // head gradient: (sample of the stage, head output)
     struct Set { u32x4_l x[TB_BG / 2]; u32x2_l hq[TB_BG]; float d; };
     Set S0, S1;
     auto fetch = [&](Set& st, int i) {
         if (i >= n_stages) i = n_stages - 1;                     // past the end: re-read the last stage, never used
         const int g0 = g_first + i * TB_BG;
+        // the head gradient first: it is needed one step before the rest of the set, and loads complete in issue order
+        st.d = dk < a.NH ? a.dhead[((size_t)g0 * 8 + ds) * a.NHP + dk] : 0.0f;
 #pragma unroll
         for (int q = 0; q < TB_BG / 2; ++q)
             st.x[q] = *reinterpret_cast<const u32x4_l*>(a.xP + ((size_t)(g0 + 2 * q + lg) * a.K + i0 + lc) * 8);
 #pragma unroll
         for (int G = 0; G < TB_BG; ++G)
             st.hq[G] = *reinterpret_cast<const u32x2_l*>(a.hTop + ((size_t)(g0 + G) * a.N + j0 + col) * 8 + 4 * kg);
-        st.d = dk < a.NH ? a.dhead[((size_t)g0 * 8 + ds) * a.NHP + dk] : 0.0f;
     };
     float bsum = 0.0f, dbsum = 0.0f;
     f16v acc2;
@@ -996,6 +1059,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
     // stage i (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage i + 2; the head gradient of
     // stage i + 1 (held in `nxt`) goes to the other halves of Ahl and Bhl
     auto step = [&](Set& cur, const Set& nxt, int i, int pb) {
+        derive();
         store(cur, pb);
         if (i + 1 < n_stages) { stage_d(nxt, pb ^ 1); dbsum += nxt.d; }
         __syncthreads();
@@ -1004,8 +1068,10 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
         compute();
         __syncthreads();
     };
-    fetch(S0, 0);
+    fetch(S0, 0);                                             // in this order (see gemm_tn_bf16_big)
+    __builtin_amdgcn_sched_barrier(0);
     fetch(S1, 1);
+    __builtin_amdgcn_sched_barrier(0);
     if (tid < 256) {
         uint32_t w8[8];
 #pragma unroll
@@ -1016,9 +1082,9 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
     __syncthreads();
     stage_d(S0, 0); dbsum += S0.d;
     __syncthreads();
-    for (int i = 0; i < n_stages; i += 2) {
+    for (int i = 0; i < n_stages; i += 2) {                  // no branch between the two steps (see gemm_tn_bf16_big)
         step(S0, S1, i, 0);
-        if (i + 1 < n_stages) step(S1, S0, i + 1, 1);
+        step(S1, S0, i + 1, 1);
     }
     float* out = a.partial + (size_t)split * a.split_stride;
 #pragma unroll
@@ -1144,7 +1210,7 @@ bool bf16_top_fused(const NetShape& n, int M, int splits_top)
     if (!n.bf16 || n.L < 2 || n.NH > 8) return false;
     if (n.dims[n.L] % 256 != 0 || n.dims[n.L - 1] % 256 != 0) return false;
     if (!bf16_dx_resident(n, M, n.L - 1)) return false;
-    return splits_top > 0 && M % splits_top == 0 && (M / splits_top) % 64 == 0;
+    return splits_top > 0 && M % splits_top == 0 && (M / splits_top) % 128 == 0;
 }
 
 hipError_t launch_backward_bf16(anakin* h)
@@ -1254,7 +1320,7 @@ hipError_t launch_backward_bf16(anakin* h)
         t.bias_out = t.partial + (size_t)t.K * t.N; t.bias_stride = t.split_stride;
         t.obs = obs_src();
         t.sP = nullptr; t.T = h->T; t.env_block = 0;
-        const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0 && t.rows % 64 == 0;
+        const bool big = l > 0 && t.K % 256 == 0 && t.N % 256 == 0 && t.M % t.splits == 0 && t.rows % 128 == 0;
         if (l == n.L - 1 && top_fused) {
             GemmTnTopArgs u;
             u.M = M; u.K = t.K; u.N = t.N; u.splits = t.splits; u.rows = t.rows; u.tiles_i = t.K / 256;
