@@ -716,14 +716,16 @@ constexpr int TB_BG = 8;      // sample groups (of 8) per LDS stage: 64 samples
 // XMODE: where the X operand comes from.  0: packed activations in HBM; 1: the agent plane of the
 // maze observation, a one-hot of the agent cell, built from the stage's 64 cell indices which pass
 // through LDS one stage ahead; 2: any observation rows, rebuilt piece by piece (obs_piece).
-// Two register sets hold the next two stages while the current one is multiplied, so every load
-// has two MFMA phases to arrive.  Chunks are whole pairs of stages of 64 samples (a.rows % 128 == 0).
+// Pipeline: LDS holds two stages.  While the MFMAs run on stage i, the same wavefronts put stage
+// i + 1 into the other half -- its four (X, Y) pieces per thread go between the four MFMA steps, so
+// the LDS stores and the vector work behind them (the one-hot, the sums) run in the shadow of the
+// matrix cores -- and then ask for stage i + 3 into the registers just emptied: every load has two
+// stages to arrive, and there is one barrier per stage.  Chunks are whole pairs of stages of 64
+// samples (a.rows % 128 == 0).
 template <int XMODE>
 __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a)
 {
-    extern __shared__ uint4 smem4[];
-    uint4* Xs = smem4;                       // [TB_BG][256] pieces of 8 samples
-    uint4* Ys = Xs + TB_BG * 256;
+    extern __shared__ uint4 smem4[];         // [2 stages][X | Y][TB_BG][256] pieces of 8 samples
     __shared__ uint32_t posL[2][64];         // XMODE 1: agent cells of the 64 samples of a stage, double buffered
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, kg = lane >> 5;
@@ -767,41 +769,44 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
     float bsum = 0.0f;
     const bool sums = ti == 0 && a.bias_out != nullptr;
     const int cell = a.obs_row0 + i0 + lc - a.obs.env.rows * a.obs.env.cols;   // XMODE 1: the cell this thread's row stands for
-    // stage -> LDS; pb: parity of the stage (selects the cell buffer)
-    auto store = [&](const Set& st, int i, int pb) {
+    // piece q (sample group 2q + lg) of stage i, held in st, -> half nb of LDS; counted: a real stage (not the
+    // repeat of the last one that the last step stores), whose dY entries go into the sums
+    auto store_piece = [&](const Set& st, int i, int nb, int q, bool counted) {
+        uint4* Xs = smem4 + nb * (2 * TB_BG * 256);
+        uint4* Ys = Xs + TB_BG * 256;
+        const int gl = 2 * q + lg;
+        u32x4_l x;
+        if (XMODE == 0) x = st.x[q];
+        else if (XMODE == 1) {
+            const u32x4_l p0 = *reinterpret_cast<const u32x4_l*>(&posL[i & 1][gl * 8]);
+            const u32x4_l p1 = *reinterpret_cast<const u32x4_l*>(&posL[i & 1][gl * 8 + 4]);
+            const uint32_t one = 0x3f80u;
+            x[0] = ((int)p0[0] == cell ? one : 0u) | ((int)p0[1] == cell ? one << 16 : 0u);
+            x[1] = ((int)p0[2] == cell ? one : 0u) | ((int)p0[3] == cell ? one << 16 : 0u);
+            x[2] = ((int)p1[0] == cell ? one : 0u) | ((int)p1[1] == cell ? one << 16 : 0u);
+            x[3] = ((int)p1[2] == cell ? one : 0u) | ((int)p1[3] == cell ? one << 16 : 0u);
+        } else {
+            const uint4 v = obs_piece(a.obs, stage_g0(i < n_stages ? i : n_stages - 1) + gl, a.obs_row0 + i0 + lc, true);
+            x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        }
+        *reinterpret_cast<u32x4_l*>(&Xs[gl * 256 + lc]) = x;
+        *reinterpret_cast<u32x4_l*>(&Ys[gl * 256 + lc]) = st.y[q];
+        // column sums in every workgroup (used only where `sums` holds; the workgroups that need them set the pace
+        // anyway, and a branch on `sums` here would split the step into many basic blocks)
+        const float keep = counted ? 1.0f : 0.0f;
+        if (XMODE != 1) {
+            float part = 0.0f;
 #pragma unroll
-        for (int q = 0; q < TB_BG / 2; ++q) {
-            const int gl = 2 * q + lg;
-            u32x4_l x;
-            if (XMODE == 0) x = st.x[q];
-            else if (XMODE == 1) {
-                const u32x4_l p0 = *reinterpret_cast<const u32x4_l*>(&posL[pb][gl * 8]);
-                const u32x4_l p1 = *reinterpret_cast<const u32x4_l*>(&posL[pb][gl * 8 + 4]);
-                const uint32_t one = 0x3f80u;
-                x[0] = ((int)p0[0] == cell ? one : 0u) | ((int)p0[1] == cell ? one << 16 : 0u);
-                x[1] = ((int)p0[2] == cell ? one : 0u) | ((int)p0[3] == cell ? one << 16 : 0u);
-                x[2] = ((int)p1[0] == cell ? one : 0u) | ((int)p1[1] == cell ? one << 16 : 0u);
-                x[3] = ((int)p1[2] == cell ? one : 0u) | ((int)p1[3] == cell ? one << 16 : 0u);
-            } else {
-                const uint4 v = obs_piece(a.obs, stage_g0(i) + gl, a.obs_row0 + i0 + lc, true);
-                x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-            }
-            *reinterpret_cast<u32x4_l*>(&Xs[gl * 256 + lc]) = x;
-            *reinterpret_cast<u32x4_l*>(&Ys[gl * 256 + lc]) = st.y[q];
-            // column sums in every workgroup, used only where `sums` holds: a branch here would split the stores
-            // into several basic blocks (and the workgroups that need the sums set the pace anyway)
-            if (XMODE != 1) {
+            for (int e = 0; e < 8; ++e) part += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
+            bsum = fmaf(keep, part, bsum);
+        }
+        if (by_env) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) bsum += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
-            }
-            if (by_env) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) tsum[q][e] += bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu));
-            }
+            for (int e = 0; e < 8; ++e) tsum[q][e] = fmaf(keep, bfu((uint16_t)((st.y[q][e >> 1] >> ((e & 1) * 16)) & 0xffffu)), tsum[q][e]);
         }
     };
-    // by_env, after the last time step of a block of 64 environments: the sums leave as two bfloat16 terms, hi in
-    // sample rows 0..B-1 and lo in rows B..2B-1 of a packed matrix with 2B samples
+    // by_env, after the last time step of a block of 64 environments (stage i): the sums leave as two bfloat16 terms,
+    // hi in sample rows 0..B-1 and lo in rows B..2B-1 of a packed matrix with 2B samples
     auto flush_time_sum = [&](int i) {
         const int p = i / a.T;
         const size_t n = (size_t)(a.obs.B >> 3) * a.N;
@@ -827,78 +832,60 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    auto compute = [&]() {
-        if (XMODE == 1) {
-            // the registers of the look-ahead below hold the sums over time here; the second wavefront of the SIMD
-            // covers the LDS latency instead
-#pragma unroll
-            for (int ks = 0; ks < TB_BG; ks += 2) {
-                bf8 av[4], bv[2];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32]);
-#pragma unroll
-                for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
-            }
-            return;
-        }
-        // the operands of step ks + 2 are read from LDS before the eight MFMAs of step ks are issued
+    // MFMA step ks (16 samples = groups ks, ks + 1) on half cb of LDS
+    auto compute_step = [&](int cb, int ks) {
+        const uint4* Xs = smem4 + cb * (2 * TB_BG * 256);
+        const uint4* Ys = Xs + TB_BG * 256;
         bf8 av[4], bv[2];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[kg * 256 + wm * 128 + 32 * t + l32]);
+        for (int t = 0; t < 4; ++t) av[t] = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * t + l32]);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[kg * 256 + wn * 64 + 32 * t + l32]);
+        for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
 #pragma unroll
-        for (int ks = 0; ks < TB_BG; ks += 2) {                  // one MFMA step = 16 samples = 2 groups
-            const int kn = (ks + 2 < TB_BG ? ks + 2 : 0) + kg;
-            bf8 an[4], bn[2];
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) an[t] = *reinterpret_cast<const bf8*>(&Xs[kn * 256 + wm * 128 + 32 * t + l32]);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) bn[t] = *reinterpret_cast<const bf8*>(&Ys[kn * 256 + wn * 64 + 32 * t + l32]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) av[t] = an[t];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) bv[t] = bn[t];
-        }
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av[i], bv[j], acc[i][j]);
     };
-    // one pipeline step: stage i (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage
-    // i + 2; the cells of stage i + 1 (held in `nxt`) go to the other cell buffer
-    auto step = [&](Set& cur, const Set& nxt, int i, int pb) {
-        store(cur, i, pb);
-        if (XMODE == 1 && tid < 64) posL[pb ^ 1][tid] = nxt.pos & 0xffffu;
-        __syncthreads();
-        fetch(cur, i + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        compute();
-        if (by_env && ti == 0 && (i + 1) % a.T == 0) flush_time_sum(i);
+    // one step: the MFMAs of stage i on half i % 2 of LDS, stage i + 1 (held in `nxt`) into the other half piece by
+    // piece between them; then `nxt` is refilled with stage i + 3 and the cells of stage i + 2 (held in `aft`) go to
+    // the cell buffer that stage i's one-hot was built from
+    auto step = [&](Set& nxt, const Set& aft, int i) {
+        const int cb = i & 1;
+        const bool counted = i + 1 < n_stages;
+#pragma unroll
+        for (int q = 0; q < TB_BG / 2; ++q) {
+            store_piece(nxt, i + 1, cb ^ 1, q, counted);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_step(cb, 2 * q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (by_env && ti == 0 && counted && (i + 2) % a.T == 0) flush_time_sum(i + 1);
+        if (XMODE == 1 && tid < 64) posL[cb][tid] = aft.pos & 0xffffu;
+        fetch(nxt, i + 3);
         __syncthreads();
     };
     // S0's loads strictly before S1's: the scheduler is otherwise free to issue S1's first, and then the wait-count
     // pass, which merges this state with the loop's own at the loop header, has to wait for every load in flight
-    // there on every trip (loads complete in issue order), which halves the look-ahead of one of the two sets
+    // there on every trip (loads complete in issue order), which would end the look-ahead
     fetch(S0, 0);
     __builtin_amdgcn_sched_barrier(0);
     fetch(S1, 1);
     __builtin_amdgcn_sched_barrier(0);
     if (XMODE == 1) {
-        if (tid < 64) posL[0][tid] = S0.pos & 0xffffu;
+        if (tid < 64) { posL[0][tid] = S0.pos & 0xffffu; posL[1][tid] = S1.pos & 0xffffu; }
         __syncthreads();
     }
-    // two steps per trip without a branch between them (chunks are whole pairs of stages, a.rows % 128 == 0): with a
-    // conditional second step the compiler's wait-count pass gives up counting at the loop header and waits for every
-    // load in flight there, which cuts the look-ahead of the loads to one step
-    for (int i = 0; i + 1 < n_stages; i += 2) {
-        step(S0, S1, i, 0);
-        step(S1, S0, i + 1, 1);
+#pragma unroll
+    for (int q = 0; q < TB_BG / 2; ++q) store_piece(S0, 0, 0, q, true);
+    if (by_env && ti == 0 && a.T == 1) flush_time_sum(0);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(S0, 2);
+    __syncthreads();
+    // two steps per trip without a branch between them: with a conditional second step the wait-count pass gives up
+    // counting in the same way
+    for (int i = 0; i < n_stages; i += 2) {
+        step(S1, S0, i);
+        step(S0, S1, i + 1);
     }
     float* out = a.partial + (size_t)split * a.split_stride;
 #pragma unroll
@@ -946,9 +933,7 @@ struct GemmTnTopArgs {
 
 __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
 {
-    extern __shared__ uint4 smem4[];
-    uint4* Xs = smem4;                       // [TB_BG][256] pieces of 8 samples
-    uint4* Ys = Xs + TB_BG * 256;
+    extern __shared__ uint4 smem4[];         // [2 stages][X | Y][TB_BG][256] pieces of 8 samples
     __shared__ uint4 Ahl[2][2][64];          // [stage parity][32-sample tile]: d as (hi, lo), the A operand of the dZ_L product
     __shared__ uint4 Bhl[2][2][2][64];       // [stage parity][tile][16-sample step]: the same as the B operand of the dWh product
     __shared__ uint4 WhB[256];               // row j0 + c of Wh, eight entries (zero past NH)
@@ -992,7 +977,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
     f16v acc2;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc2[r] = 0.0f;
-    // the head gradient of a stage -> both operand forms
+    // the head gradient of a stage -> both operand forms, into the buffers of parity par
     auto stage_d = [&](const Set& st, int par) {
         const uint16_t hi = (uint16_t)cvt_pk_bf16(st.d, 0.0f);
         const uint16_t lo = (uint16_t)cvt_pk_bf16(st.d - bfu(hi), 0.0f);
@@ -1005,35 +990,42 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
         B16[(kgs * 32 + dk) * 8 + q] = hi;
         B16[(kgs * 32 + 8 + dk) * 8 + q] = lo;
     };
-    auto store = [&](const Set& st, int pb) {
-#pragma unroll
-        for (int q = 0; q < TB_BG / 2; ++q) *reinterpret_cast<u32x4_l*>(&Xs[(2 * q + lg) * 256 + lc]) = st.x[q];
-        const uint4 wv = WhB[col];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            const uint4 a1v = Ahl[pb][mt][lane];
-            f16v acc1;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
-            acc1 = mfma_bf16(*reinterpret_cast<const bf8*>(&a1v), *reinterpret_cast<const bf8*>(&wv), acc1);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int G = 4 * mt + g;
-                u32x2_l pv;
-                pv[0] = cvt_pk_bf16(acc1[4 * g], acc1[4 * g + 1]) & positive_mask_pk(st.hq[G][0]);
-                pv[1] = cvt_pk_bf16(acc1[4 * g + 2], acc1[4 * g + 3]) & positive_mask_pk(st.hq[G][1]);
-                *reinterpret_cast<u32x2_l*>(reinterpret_cast<char*>(&Ys[G * 256 + col]) + 8 * kg) = pv;
-                if (sums_row) bsum += (bfu((uint16_t)pv[0]) + bfu((uint16_t)(pv[0] >> 16))) + (bfu((uint16_t)pv[1]) + bfu((uint16_t)(pv[1] >> 16)));
-            }
-            if (heads_row) {
-                const uint4 b0v = Bhl[pb][mt][0][lane], b1v = Bhl[pb][mt][1][lane];
+    // part k (0..3) of putting stage i (held in st) into half nb of LDS: X piece k; k even: the dWh MFMAs of 32-sample
+    // tile k / 2; k odd: dZ_L of tile k / 2 (one MFMA, masked, to the Y operand).  counted: a real stage, whose
+    // values go into the sums (the last step stores the last stage once more)
+    auto store_part = [&](const Set& st, int i, int nb, int k, bool counted) {
+        uint4* Xs = smem4 + nb * (2 * TB_BG * 256);
+        uint4* Ys = Xs + TB_BG * 256;
+        const int par = i & 1, mt = k >> 1;
+        *reinterpret_cast<u32x4_l*>(&Xs[(2 * k + lg) * 256 + lc]) = st.x[k];
+        if ((k & 1) == 0) {
+            if (heads_row && counted) {
+                const uint4 b0v = Bhl[par][mt][0][lane], b1v = Bhl[par][mt][1][lane];
                 u32x4_l x0, x1;
                 x0[0] = st.hq[4 * mt][0]; x0[1] = st.hq[4 * mt][1]; x0[2] = st.hq[4 * mt + 1][0]; x0[3] = st.hq[4 * mt + 1][1];
                 x1[0] = st.hq[4 * mt + 2][0]; x1[1] = st.hq[4 * mt + 2][1]; x1[2] = st.hq[4 * mt + 3][0]; x1[3] = st.hq[4 * mt + 3][1];
                 acc2 = mfma_bf16(*reinterpret_cast<const bf8*>(&x0), *reinterpret_cast<const bf8*>(&b0v), acc2);
                 acc2 = mfma_bf16(*reinterpret_cast<const bf8*>(&x1), *reinterpret_cast<const bf8*>(&b1v), acc2);
             }
+            return;
         }
+        const uint4 wv = WhB[col];
+        const uint4 a1v = Ahl[par][mt][lane];
+        f16v acc1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+        acc1 = mfma_bf16(*reinterpret_cast<const bf8*>(&a1v), *reinterpret_cast<const bf8*>(&wv), acc1);
+        float part = 0.0f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int G = 4 * mt + g;
+            u32x2_l pv;
+            pv[0] = cvt_pk_bf16(acc1[4 * g], acc1[4 * g + 1]) & positive_mask_pk(st.hq[G][0]);
+            pv[1] = cvt_pk_bf16(acc1[4 * g + 2], acc1[4 * g + 3]) & positive_mask_pk(st.hq[G][1]);
+            *reinterpret_cast<u32x2_l*>(reinterpret_cast<char*>(&Ys[G * 256 + col]) + 8 * kg) = pv;
+            if (sums_row) part += (bfu((uint16_t)pv[0]) + bfu((uint16_t)(pv[0] >> 16))) + (bfu((uint16_t)pv[1]) + bfu((uint16_t)(pv[1] >> 16)));
+        }
+        if (sums_row && counted) bsum += part;
     };
     f16v acc[4][2];
 #pragma unroll
@@ -1042,30 +1034,37 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    auto compute = [&]() {
+    // MFMA step ks (16 samples = groups ks, ks + 1) on half cb of LDS
+    auto compute_step = [&](int cb, int ks) {
+        const uint4* Xs = smem4 + cb * (2 * TB_BG * 256);
+        const uint4* Ys = Xs + TB_BG * 256;
+        bf8 bv[2];
 #pragma unroll
-        for (int ks = 0; ks < TB_BG; ks += 2) {                  // one MFMA step = 16 samples = 2 groups
-            bf8 bv[2];
+        for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) bv[t] = *reinterpret_cast<const bf8*>(&Ys[(ks + kg) * 256 + wn * 64 + 32 * t + l32]);
+        for (int i = 0; i < 4; ++i) {
+            const bf8 av = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * i + l32]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const bf8 av = *reinterpret_cast<const bf8*>(&Xs[(ks + kg) * 256 + wm * 128 + 32 * i + l32]);
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av, bv[j], acc[i][j]);
-            }
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(av, bv[j], acc[i][j]);
         }
     };
-    // stage i (held in `cur`) goes to LDS and is multiplied; `cur` is refilled with stage i + 2; the head gradient of
-    // stage i + 1 (held in `nxt`) goes to the other halves of Ahl and Bhl
-    auto step = [&](Set& cur, const Set& nxt, int i, int pb) {
+    // one step: the MFMAs of stage i on half i % 2 of LDS with the four parts of stage i + 1 (held in `nxt`) between
+    // them; the head gradient of stage i + 2 (held in `aft`) goes to the operand buffers stage i used; then `nxt` is
+    // refilled with stage i + 3
+    auto step = [&](Set& nxt, const Set& aft, int i) {
         derive();
-        store(cur, pb);
-        if (i + 1 < n_stages) { stage_d(nxt, pb ^ 1); dbsum += nxt.d; }
-        __syncthreads();
-        fetch(cur, i + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        compute();
+        const int cb = i & 1;
+        const bool counted = i + 1 < n_stages;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            store_part(nxt, i + 1, cb ^ 1, k, counted);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_step(cb, 2 * k);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        stage_d(aft, cb);
+        if (i + 2 < n_stages) dbsum += aft.d;
+        fetch(nxt, i + 3);
         __syncthreads();
     };
     fetch(S0, 0);                                             // in this order (see gemm_tn_bf16_big)
@@ -1080,11 +1079,17 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_top(const GemmTnTopArgs a)
     }
     reinterpret_cast<uint4*>(Bhl)[tid] = make_uint4(0, 0, 0, 0);  // output columns 16..31 of the dWh product stay zero
     __syncthreads();
-    stage_d(S0, 0); dbsum += S0.d;
+    stage_d(S0, 0); stage_d(S1, 1);
+    dbsum += S0.d + S1.d;
     __syncthreads();
-    for (int i = 0; i < n_stages; i += 2) {                  // no branch between the two steps (see gemm_tn_bf16_big)
-        step(S0, S1, i, 0);
-        step(S1, S0, i + 1, 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) store_part(S0, 0, 0, k, true);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(S0, 2);
+    __syncthreads();
+    for (int i = 0; i < n_stages; i += 2) {                   // no branch between the two steps (see gemm_tn_bf16_big)
+        step(S1, S0, i);
+        step(S0, S1, i + 1);
     }
     float* out = a.partial + (size_t)split * a.split_stride;
 #pragma unroll
@@ -1260,7 +1265,7 @@ hipError_t launch_backward_bf16(anakin* h)
         t.tiles_i = (t.K + tile - 1) / tile;
         const int tiles = t.tiles_i * ((t.N + tile - 1) / tile);
         const dim3 grid = big ? dim3(tiles * t.splits) : dim3(tiles, t.splits);
-        const size_t lds = (size_t)2 * (big ? TB_BG * 256 : TB_G * 128) * sizeof(uint4);
+        const size_t lds = (size_t)2 * (big ? 2 * TB_BG * 256 : TB_G * 128) * sizeof(uint4);   // 256-tile kernel: two stages
         // X operand of the 256-tile kernel: packed activations, the agent plane (one-hot of the cell), or generic rows
         const int cells = h->env.rows * h->env.cols;
         const int xmode = !t.use_obs ? 0 : (h->env.kind == ENV_MAZE && t.obs_row0 == cells && t.K == cells) ? 1 : 2;
@@ -1329,7 +1334,7 @@ hipError_t launch_backward_bf16(anakin* h)
             u.wh16 = at<const uint16_t>(h, L.w16_src) + n.wh_off;
             u.partial = t.partial; u.split_stride = t.split_stride;
             u.head_partial = at<float>(h, L.part[n.L]); u.head_stride = (size_t)t.N * n.NH + n.NH;
-            const size_t lds = (size_t)2 * TB_BG * 256 * sizeof(uint4);
+            const size_t lds = (size_t)2 * 2 * TB_BG * 256 * sizeof(uint4);   // two stages
             if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_bf16_top), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess) return e;
             ProfScope prof(h, "gemm_tn_top");
             hipLaunchKernelGGL(gemm_tn_bf16_top, dim3(u.tiles_i * (u.N / 256) * u.splits), dim3(BIGWG), lds, h->stream, u);
