@@ -102,10 +102,12 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
             if (HEADS) dh[HEADS ? q : 0] = *reinterpret_cast<const f4v_r*>(a.hf.dhead + (size_t)mc * a.hf.NHP);
         }
     };
+    auto store_piece = [&](float* buf, int q) {
+        *reinterpret_cast<f4v_r*>(buf + (8 * q + lrow) * NTR_LD + lc) = HEADS ? head_dy(hc, st[q], dh[HEADS ? q : 0]) : st[q];
+    };
     auto store = [&](float* buf) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<f4v_r*>(buf + (8 * q + lrow) * NTR_LD + lc) = HEADS ? head_dy(hc, st[q], dh[HEADS ? q : 0]) : st[q];
+        for (int q = 0; q < 4; ++q) store_piece(buf, q);
     };
     // FIRST: the first RT threads work out (cos, sin, thd, 1) of one sample of a stage each; the epilogue of that
     // stage multiplies them into this lane's column of dZ_1
@@ -128,7 +130,8 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
     for (int m0 = m_begin; m0 < m_end; m0 += RT, t ^= 1) {
         const float* cur = t ? As1 : As0;
         float* nxt = t ? As0 : As1;
-        fetch(m0 + RT < m_end ? m0 + RT : m0);                      // the last step re-reads its own rows
+        const bool more = m0 + RT < m_end;
+        fetch(more ? m0 + RT : m0);                                 // the last step re-reads its own rows
         // the next stage's features: one wavefront's long sine/cosine chain runs under the other wavefronts' MFMAs
         if (FIRST && m0 + RT < m_end) features(m0 + RT, t ^ 1);
         // rows come in whole groups of eight (M and the rows per workgroup are multiples of 8), so the row
@@ -161,6 +164,9 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
             acc = mfma_r(av1[2], wreg[4 * p + 6], acc);
             acc = mfma_r(av1[3], wreg[4 * p + 7], acc);
             av0 = nx0; av1 = nx1;
+            // the next stage goes to `nxt` a quarter at a time between the MFMAs: each one waits for the one before
+            // it (same accumulator), so what is issued in between is free
+            if ((p & 6) == 6 && more) store_piece(nxt, p >> 3);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -174,7 +180,6 @@ __device__ __forceinline__ void gemm_nt_res256_body(const GemmNtArgs& a, const i
                 }
             }
         }
-        if (m0 + RT < m_end) store(nxt);
         __syncthreads();
     }
     if (FIRST) {
@@ -228,9 +233,8 @@ __device__ __forceinline__ void gemm_tn_res256_body(const GemmTnArgs& a, const i
             }
         }
     };
-    auto store = [&](int b) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
+    auto store_piece = [&](int b, int q) {
+        {
             *reinterpret_cast<f4v_r*>(Xs + (b * RT + 8 * q + lrow) * 256 + lc) = sx[q];
             if (HEADS) {
                 // the head matrix's own gradient: hl^T dhead, from the activations just loaded (zero where the relu cut)
@@ -246,6 +250,10 @@ __device__ __forceinline__ void gemm_tn_res256_body(const GemmTnArgs& a, const i
             bsum += sy[q];
         }
     };
+    auto store = [&](int b) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) store_piece(b, q);
+    };
     fetch(m_begin);
     store(0);
     __syncthreads();
@@ -258,7 +266,8 @@ __device__ __forceinline__ void gemm_tn_res256_body(const GemmTnArgs& a, const i
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
     int t = 0;
     for (int m0 = m_begin; m0 < m_end; m0 += RT, t ^= 1) {
-        fetch(m0 + RT < m_end ? m0 + RT : m0);                      // the last step re-reads its own rows, unused
+        const bool more = m0 + RT < m_end;
+        fetch(more ? m0 + RT : m0);                                 // the last step re-reads its own rows, unused
         __builtin_amdgcn_sched_barrier(0);
         const float* xs = Xs + t * RT * 256 + wm * 128 + l32;
         const float* ys = Ys + t * RT * 256 + wn * 64 + l32;
@@ -285,8 +294,10 @@ __device__ __forceinline__ void gemm_tn_res256_body(const GemmTnArgs& a, const i
             for (int q = 0; q < 4; ++q) av[q] = an[q];
 #pragma unroll
             for (int q = 0; q < 2; ++q) bv[q] = bn[q];
+            // the next stage goes to the other half of LDS a quarter at a time between the MFMA steps, so that its
+            // stores and the vector work behind them (the head terms) run while the matrix cores are busy
+            if ((ks & 6) == 6 && more) store_piece(t ^ 1, ks >> 3);
         }
-        if (m0 + RT < m_end) store(t ^ 1);
         __syncthreads();
     }
     float* out = a.partial + (size_t)split * ((size_t)K * N + N);
