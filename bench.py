@@ -96,7 +96,15 @@ def kernel_models(cfg, P, launched=()):
         # 2-byte operands: 2 K N flop per sample against 2 (N + 2 K) B (dX: dY and the relu mask read, dX written)
         # resp. 2 (K + N) B (dW: both operands read) is 170 resp. 256 flop/B for 512-wide layers, below the
         # machine balance of 2500 / 8 = 312 flop/B: both GEMMs sit on the HBM roof, not the matrix-core one
-        nt_bytes = sum(2.0 * (dims[i + 1] + 2 * dims[i]) * M for i in range(1, len(dims) - 1))
+        # dX of layer i -> i+1: dY read (2 B per entry; not for a fused top layer, which forms it from the head
+        # gradient), the ReLU mask of h_i (flag words, 1/4 B per entry, where the acting kernel writes them: every
+        # layer but a first one that is not 512 wide; else the 2-byte activations), dX written (2 B per entry)
+        def nt_layer_bytes(i):
+            top = top_fused and i == len(dims) - 2
+            dy = (dims[i + 1] / 4.0 + 4.0 * NH) if top else 2.0 * dims[i + 1]
+            mask = dims[i] / 4.0 if (i >= 2 or dims[1] == 512) else 2.0 * dims[i]
+            return (dy + mask + 2.0 * dims[i]) * M
+        nt_bytes = sum(nt_layer_bytes(i) for i in range(1, len(dims) - 1))
         tn_bytes = sum(2.0 * (dims[i] + dims[i + 1]) * M for i in tn_layers)
         if nt / max(nt_bytes, 1.0) < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
             models["gemm_nt_mask"] = ("hbm", nt_bytes / 1e9, PEAK_HBM_GBS, "GB/s")
