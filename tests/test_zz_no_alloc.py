@@ -53,6 +53,9 @@ def test_static_scratch_update_equals_workspace_update(gpu):
     _pair(gpu, _cfg("catch_262144", B=512), seed=6)
     cfg = _cfg("maze_16384", hidden=[128, 128], B=64, T=8)
     _pair(gpu, cfg, seed=7)
+    # 256-wide bf16 layers: the weights-resident dX product, the top layer with the head pass folded in and the
+    # first layer reduced plane by plane, all with their scratch in the static array
+    _pair(gpu, _cfg("maze_16384", hidden=[256, 256], B=64, T=8), seed=8)
 
 
 def test_static_scratch_with_several_updates_per_unroll(gpu):
