@@ -305,16 +305,18 @@ def main():
                                        ("mfma_bf16", binding.PROBE_MFMA_BF16, "TFLOP/s", PEAK_BF16_TFLOPS),
                                        ("copy", binding.PROBE_COPY, "GB/s", PEAK_HBM_GBS),
                                        ("read_only", binding.PROBE_READ, "GB/s", PEAK_HBM_GBS),
+                                       ("l2_weight_stream", binding.PROBE_L2_TILES, "GB/s", None),
                                        ("adam_2^26_params", binding.PROBE_ADAM, "GB/s", PEAK_HBM_GBS)):
             best, best_wg = 0.0, 0
-            for wg in ((1024, 4096, 16384, 65536) if name in ("copy", "read_only") else (0,) if kind == binding.PROBE_ADAM else (256, 512, 768, 1024, 2048)):
+            for wg in ((1024, 4096, 16384, 65536) if name in ("copy", "read_only") else (0,) if kind == binding.PROBE_ADAM
+                       else (256,) if kind == binding.PROBE_L2_TILES else (256, 512, 768, 1024, 2048)):
                 for _ in range(2):
                     amount, ms = binding.peak_probe(kind, scratch, stream, wg)
                     rate = amount / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
                     if rate > best:
                         best, best_wg = rate, wg
-            out[name] = {"measured": round(best, 1), "published": peak, "unit": unit, "frac": round(best / peak, 3),
-                         "workgroups": best_wg}
+            out[name] = {"measured": round(best, 1), "published": peak, "unit": unit,
+                         "frac": round(best / peak, 3) if peak else None, "workgroups": best_wg}
         print(json.dumps({"peak_probe": out}))
         return
     cfg = W.get(args.workload)

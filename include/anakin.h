@@ -290,12 +290,16 @@ int32_t anakin_kernel_times(anakin_t* h, anakin_kernel_time* out, int32_t cap, i
  * scratch: device memory owned by the caller, at least 1 MiB (MFMA probes) or as large as the copy
  * should be (copy probe: first half is read, second half written, ten times; Adam probe: the update
  * kernel on min(scratch_bytes / 20, 2^26) synthetic parameters, five times, 32 bytes per parameter; read
- * probe: the whole buffer but its last workgroups x 1 KiB is read ten times and summed, nothing else is written).
+ * probe: the whole buffer but its last workgroups x 1 KiB is read ten times and summed, nothing else is written;
+ * L2 probe: every workgroup (512 threads) streams the first MiB of the buffer 200 times in the access pattern of
+ * the bf16 acting kernel's weight stream -- the L2-to-CU rate with all units asking at once; needs 1 MiB plus
+ * workgroups x 2 KiB).
  * Synchronous: the
  * call enqueues on hip_stream, waits, and returns the work done (*amount: flop, or bytes read +
  * written) and the elapsed time from two events on that stream.  Returns ANAKIN_E_INVALID_ARG for
  * a null pointer, an unknown kind or a scratch buffer that is too small. */
-enum { ANAKIN_PROBE_MFMA_F32 = 0, ANAKIN_PROBE_MFMA_BF16 = 1, ANAKIN_PROBE_COPY = 2, ANAKIN_PROBE_ADAM = 3, ANAKIN_PROBE_READ = 4 };
+enum { ANAKIN_PROBE_MFMA_F32 = 0, ANAKIN_PROBE_MFMA_BF16 = 1, ANAKIN_PROBE_COPY = 2, ANAKIN_PROBE_ADAM = 3, ANAKIN_PROBE_READ = 4,
+       ANAKIN_PROBE_L2_TILES = 5 };
 int32_t anakin_peak_probe(int32_t kind, int32_t workgroups, void* scratch, size_t scratch_bytes, void* hip_stream,
                           double* amount, double* milliseconds);
 

@@ -353,7 +353,7 @@ def unpack_state_word(kind, s0):
     return out
 
 
-PROBE_MFMA_F32, PROBE_MFMA_BF16, PROBE_COPY, PROBE_ADAM, PROBE_READ = 0, 1, 2, 3, 4
+PROBE_MFMA_F32, PROBE_MFMA_BF16, PROBE_COPY, PROBE_ADAM, PROBE_READ, PROBE_L2_TILES = 0, 1, 2, 3, 4, 5
 
 
 def peak_probe(kind, scratch, stream_ptr, workgroups=0):

@@ -57,13 +57,42 @@ __global__ __launch_bounds__(WG) void probe_read(const pf4v* __restrict__ src, f
     out[(size_t)blockIdx.x * WG + threadIdx.x] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
 }
 
+// L2 read stream in the bf16 acting kernel's pattern: every workgroup of 512 threads walks the same 1 MiB (two layers
+// of 512 KiB in operand tiles: wavefront w reads tiles 2w and 2w + 1, 32 steps of 1 KiB each, four steps ahead) `reps`
+// times; the buffer stays in every L2, so this is what the L2-to-CU path delivers when all units ask at once
+typedef uint32_t pu4v __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512) void probe_l2_tiles(const pu4v* __restrict__ src, uint32_t* __restrict__ out, int reps)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t acc = 0;
+    for (int r = 0; r < reps; ++r) {
+        for (int layer = 0; layer < 2; ++layer) {
+            const pu4v* base = src + (size_t)layer * (512 * 1024 / 16);
+#pragma unroll 1
+            for (int s = 0; s < 32; s += 4) {
+                pu4v v[4][2];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) v[u][t] = base[((size_t)(wave * 2 + t) * 32 + (s + u)) * 64 + lane];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) acc += v[u][t][0] ^ v[u][t][1] ^ v[u][t][2] ^ v[u][t][3];
+            }
+        }
+        asm volatile("" : "+v"(acc));                            // the passes are not merged
+    }
+    out[(size_t)blockIdx.x * 512 + tid] = acc;
+}
+
 }  // namespace ank
 
 extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratch, size_t scratch_bytes, void* hip_stream,
                                      double* amount, double* milliseconds)
 {
     using namespace ank;
-    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 4 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
+    if (!scratch || !amount || !milliseconds || kind < 0 || kind > 5 || variant < 0 || variant > 65536) return ANAKIN_E_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return ANAKIN_E_HIP;
@@ -81,6 +110,18 @@ extern "C" int32_t anakin_peak_probe(int32_t kind, int32_t variant, void* scratc
         for (int r = 0; r < 10; ++r) hipLaunchKernelGGL(probe_copy, dim3(blocks), dim3(WG), 0, s, src, dst, n4);
         (void)hipEventRecord(e1, s);
         *amount = 10.0 * 2.0 * (double)half;                 // bytes read + written
+    } else if (kind == ANAKIN_PROBE_L2_TILES) {
+        const int blocks = variant > 0 ? variant : 256;
+        const size_t src_bytes = (size_t)1 << 20, out_bytes = (size_t)blocks * 512 * 4;
+        if (scratch_bytes < src_bytes + out_bytes) return ANAKIN_E_INVALID_ARG;
+        auto* src = static_cast<const pu4v*>(scratch);
+        uint32_t* out = reinterpret_cast<uint32_t*>(static_cast<char*>(scratch) + src_bytes);
+        const int reps = 200;
+        hipLaunchKernelGGL(probe_l2_tiles, dim3(blocks), dim3(512), 0, s, src, out, 2);      // warm-up
+        (void)hipEventRecord(e0, s);
+        hipLaunchKernelGGL(probe_l2_tiles, dim3(blocks), dim3(512), 0, s, src, out, reps);
+        (void)hipEventRecord(e1, s);
+        *amount = (double)reps * (double)src_bytes * blocks;     // bytes delivered to the compute units
     } else if (kind == ANAKIN_PROBE_READ) {
         const int blocks = variant > 0 ? variant : 4096;
         const size_t tail = ((size_t)blocks * WG * 4 + 255) & ~(size_t)255;   // the sums go behind the range that is read
