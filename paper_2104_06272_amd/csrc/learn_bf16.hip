@@ -715,7 +715,8 @@ constexpr int TB_BG = 8;      // sample groups (of 8) per LDS stage: 64 samples
 
 // XMODE: where the X operand comes from.  0: packed activations in HBM; 1: the agent plane of the
 // maze observation, a one-hot of the agent cell, built from the stage's 64 cell indices which pass
-// through LDS one stage ahead; 2: any observation rows, rebuilt piece by piece (obs_piece).
+// through LDS one stage ahead; 2: the wall plane of the maze observation (samples are environments,
+// rows are cells), built from the stage's 64 x 8 wall words which pass through LDS the same way.
 // Pipeline: LDS holds two stages.  While the MFMAs run on stage i, the same wavefronts put stage
 // i + 1 into the other half -- its four (X, Y) pieces per thread go between the four MFMA steps, so
 // the LDS stores and the vector work behind them (the one-hot, the sums) run in the shadow of the
@@ -727,6 +728,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
 {
     extern __shared__ uint4 smem4[];         // [2 stages][X | Y][TB_BG][256] pieces of 8 samples
     __shared__ uint32_t posL[2][64];         // XMODE 1: agent cells of the 64 samples of a stage, double buffered
+    __shared__ uint32_t wallsL[2][XMODE == 2 ? 8 : 1][64];   // XMODE 2: the eight wall words of the 64 environments of a stage
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3, l32 = lane & 31, kg = lane >> 5;
     int split, tile;
@@ -754,6 +756,9 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
         const int g0 = stage_g0(i);
         // the cells first: they are needed one step before the rest of the set, and loads complete in issue order
         if (XMODE == 1) st.pos = a.obs.s0[(size_t)g0 * 8 + (tid & 63)];
+        // wall words: thread = (environment of the stage, word); a stage never straddles the two halves of the 2B
+        // samples (B is a multiple of 64)
+        if (XMODE == 2) st.pos = a.obs.walls[(size_t)(tid & 7) * a.obs.B + (g0 * 8) % a.obs.B + (tid >> 3)];
 #pragma unroll
         for (int q = 0; q < TB_BG / 2; ++q) {
             const int g = g0 + 2 * q + lg;
@@ -786,8 +791,15 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
             x[2] = ((int)p1[0] == cell ? one : 0u) | ((int)p1[1] == cell ? one << 16 : 0u);
             x[3] = ((int)p1[2] == cell ? one : 0u) | ((int)p1[3] == cell ? one << 16 : 0u);
         } else {
-            const uint4 v = obs_piece(a.obs, stage_g0(i < n_stages ? i : n_stages - 1) + gl, a.obs_row0 + i0 + lc, true);
-            x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+            const int c = a.obs_row0 + i0 + lc;                  // this thread's cell: bit c % 32 of wall word c / 32
+            const u32x4_l w0 = *reinterpret_cast<const u32x4_l*>(&wallsL[i & 1][XMODE == 2 ? c >> 5 : 0][gl * 8]);
+            const u32x4_l w1 = *reinterpret_cast<const u32x4_l*>(&wallsL[i & 1][XMODE == 2 ? c >> 5 : 0][gl * 8 + 4]);
+            const uint32_t one = 0x3f80u;
+            const int sh = c & 31;
+            x[0] = (((w0[0] >> sh) & 1u) * one) | (((w0[1] >> sh) & 1u) * (one << 16));
+            x[1] = (((w0[2] >> sh) & 1u) * one) | (((w0[3] >> sh) & 1u) * (one << 16));
+            x[2] = (((w1[0] >> sh) & 1u) * one) | (((w1[1] >> sh) & 1u) * (one << 16));
+            x[3] = (((w1[2] >> sh) & 1u) * one) | (((w1[3] >> sh) & 1u) * (one << 16));
         }
         *reinterpret_cast<u32x4_l*>(&Xs[gl * 256 + lc]) = x;
         *reinterpret_cast<u32x4_l*>(&Ys[gl * 256 + lc]) = st.y[q];
@@ -861,6 +873,7 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
         }
         if (by_env && ti == 0 && counted && (i + 2) % a.T == 0) flush_time_sum(i + 1);
         if (XMODE == 1 && tid < 64) posL[cb][tid] = aft.pos & 0xffffu;
+        if (XMODE == 2) wallsL[cb][XMODE == 2 ? tid & 7 : 0][tid >> 3] = aft.pos;
         fetch(nxt, i + 3);
         __syncthreads();
     };
@@ -873,6 +886,10 @@ __global__ __launch_bounds__(BIGWG) void gemm_tn_bf16_big(const GemmTnBf16Args a
     __builtin_amdgcn_sched_barrier(0);
     if (XMODE == 1) {
         if (tid < 64) { posL[0][tid] = S0.pos & 0xffffu; posL[1][tid] = S1.pos & 0xffffu; }
+        __syncthreads();
+    }
+    if (XMODE == 2) {
+        wallsL[0][XMODE == 2 ? tid & 7 : 0][tid >> 3] = S0.pos; wallsL[1][XMODE == 2 ? tid & 7 : 0][tid >> 3] = S1.pos;
         __syncthreads();
     }
 #pragma unroll
@@ -1269,6 +1286,7 @@ hipError_t launch_backward_bf16(anakin* h)
         // X operand of the 256-tile kernel: packed activations, the agent plane (one-hot of the cell), or generic rows
         const int cells = h->env.rows * h->env.cols;
         const int xmode = !t.use_obs ? 0 : (h->env.kind == ENV_MAZE && t.obs_row0 == cells && t.K == cells) ? 1 : 2;
+        if (big && xmode == 2 && !(h->env.kind == ENV_MAZE && t.obs_row0 == 0 && t.K == cells && h->B % 64 == 0)) return hipErrorInvalidValue;
         const void* fn = big ? (xmode == 0 ? reinterpret_cast<const void*>(gemm_tn_bf16_big<0>) : xmode == 1 ? reinterpret_cast<const void*>(gemm_tn_bf16_big<1>)
                                                                                                               : reinterpret_cast<const void*>(gemm_tn_bf16_big<2>))
                              : (t.use_obs ? reinterpret_cast<const void*>(gemm_tn_bf16<true>) : reinterpret_cast<const void*>(gemm_tn_bf16<false>));
