@@ -75,9 +75,13 @@ ANK_HD void pendulum_step(const EnvDims& d, EnvState& s, float a, uint32_t w0, u
     nthd = nthd > 8.0f ? 8.0f : nthd;
     s.f0 = wrap_angle(fmaf(nthd, 0x1.99999ap-5f, th));
     s.f1 = nthd;
-    s.s0 += 1u;
-    if ((int)s.s0 >= d.max_steps) { done = 1; pendulum_reset(s, w0, w1); }
-    else done = 0;
+    const uint32_t steps = s.s0 + 1u;
+    s.s0 = steps;
+    // the flag is a value, not a store in either arm of the branch: written as two stores the compiler pairs
+    // the arms' zero stores (step count, flag) into one store through a selected address, and the state
+    // then lives in scratch memory instead of registers
+    done = (int)steps >= d.max_steps ? 1 : 0;
+    if (done) pendulum_reset(s, w0, w1);
 }
 
 // ---- Maze ------------------------------------------------------------------
@@ -126,6 +130,27 @@ ANK_HD int sample_categorical(const float (&logits)[MAXA], int A, float u)
 #pragma unroll
     for (int i = MAXA - 1; i >= 0; --i) if (i < A && c[i] > thr) a = i;
     return a;
+}
+
+// The same sampler with the usual action counts as constants: the comparisons against A fold away and
+// only A exponentials are left in the instruction stream.  Same operations in the same order for every A.
+// The heads come in as values: handed over as an array by reference, the branches' loads get merged into one
+// load through a selected address and the caller's array ends up in scratch memory.
+ANK_HD int sample_categorical_any(float l0, float l1, float l2, float l3, float l4, float l5, float l6, float l7,
+                                  int A, float u)
+{
+    const float lg[8] = {l0, l1, l2, l3, l4, l5, l6, l7};
+    if (A == 3) return sample_categorical<8>(lg, 3, u);
+    if (A == 4) return sample_categorical<8>(lg, 4, u);
+    return sample_categorical<8>(lg, A, u);
+}
+// the value is the last head
+ANK_HD float last_head(float h0, float h1, float h2, float h3, float h4, float h5, float h6, float h7, int NH)
+{
+    if (NH == 4) return h3;
+    if (NH == 5) return h4;
+    if (NH == 3) return h2;
+    return NH == 8 ? h7 : NH == 7 ? h6 : NH == 6 ? h5 : NH == 2 ? h1 : h0;
 }
 
 // Box-Muller noise, z = mu + sigma eps, squashed by tanh; log_sigma clamped to [-5, 2]

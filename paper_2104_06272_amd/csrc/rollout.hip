@@ -92,13 +92,13 @@ constexpr int OBS_WORDS = 12;
 template <int ENV, int RM, bool BF>
 __device__ __forceinline__ void first_layer(const RolloutArgs& a, const uint32_t* __restrict__ obs,
                                             float* __restrict__ Y, int ldx, int tid, float* __restrict__ gout,
-                                            const float* w1)
+                                            const float* w1, const float* b1)
 {
     const int N = a.net.dims[1];
     const int CG = N >> 2, tn = tid % CG, m0 = (tid / CG) * RM, c0 = tn << 2;
     const float* wp = w1 + c0;
     float acc[RM][4];
-    const float4 b = ld4(a.theta + a.net.b_off[0] + c0);
+    const float4 b = ld4(b1 + c0);
 #pragma unroll
     for (int r = 0; r < RM; ++r) { acc[r][0] = b.x; acc[r][1] = b.y; acc[r][2] = b.z; acc[r][3] = b.w; }
     if (ENV == ENV_CATCH) {
@@ -153,13 +153,14 @@ template <int ENV, bool BF>
 __device__ __forceinline__ void run_first_layer(const RolloutArgs& a, int TM, const uint32_t* obs, float* Y, int tid, float* gout,
                                                 const float* w1)
 {
+    const float* b1 = a.theta + a.net.b_off[0];
     const int RM = TM * a.net.dims[1] / 1024;
     switch (RM) {
-        case 1: first_layer<ENV, 1, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
-        case 2: first_layer<ENV, 2, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
-        case 4: first_layer<ENV, 4, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
-        case 8: first_layer<ENV, 8, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
-        default: first_layer<ENV, 16, BF>(a, obs, Y, a.ldx, tid, gout, w1); break;
+        case 1: first_layer<ENV, 1, BF>(a, obs, Y, a.ldx, tid, gout, w1, b1); break;
+        case 2: first_layer<ENV, 2, BF>(a, obs, Y, a.ldx, tid, gout, w1, b1); break;
+        case 4: first_layer<ENV, 4, BF>(a, obs, Y, a.ldx, tid, gout, w1, b1); break;
+        case 8: first_layer<ENV, 8, BF>(a, obs, Y, a.ldx, tid, gout, w1, b1); break;
+        default: first_layer<ENV, 16, BF>(a, obs, Y, a.ldx, tid, gout, w1, b1); break;
     }
 }
 
@@ -563,9 +564,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
             float* hd = tp.tr_head + tb * NHP;
             *reinterpret_cast<float4*>(hd) = h0;
             if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = h1;
-            float val = hv[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
+            const float val = last_head(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], NH);
             tp.tr_val[tb] = val;
             if (!REPLAY && t < T) {
                 const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);   // action draw, words 0 and 1
@@ -583,7 +582,7 @@ __global__ __launch_bounds__(WG) void rollout_kernel(const RolloutArgs a, const 
                         pendulum_reset(st, wr.x, wr.y);
                     }
                 } else {
-                    const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
+                    const int act = sample_categorical_any(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
                     if (ENV == ENV_CATCH) {
                         catch_step(a.env, st, act, 0u, r, done);
@@ -720,24 +719,40 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
     float* heads = bhs + 8;                       // [TM][NHP]
     uint32_t* obs = reinterpret_cast<uint32_t*>(heads + TM * NHP);   // [TM][OBS_WORDS]
     uint32_t* rng = obs + TM * OBS_WORDS;                            // [TM][4] draws of the current step
-    float* w1s = reinterpret_cast<float*>(rng + TM * 4);             // [D][RK] first-layer weights
+    float* b1s = reinterpret_cast<float*>(rng + TM * 4);             // [RK], [RN] biases of the two hidden layers
+    float* b2s = b1s + RK;
+    float* w1s = b2s + RN;                                           // [D][RK] first-layer weights
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.x * TM;
     const int B = a.B, T = a.T;
     const TrajPtrs& tp = a.tp;
 
+    // The prologue's loads are issued in batches and land while the hidden-to-hidden matrix streams into the
+    // registers: one load, one wait, one LDS store at a time would cost a memory round trip per 4 KB.
     constexpr int ldw = HL + 4;
-    for (int i = tid; i < HL * NH; i += WG) {
-        const int k = i / NH, j = i - k * NH;
-        whs[j * ldw + k] = a.theta[a.net.wh_off + i];
+    constexpr int NWH = HL * 8 / WG;                               // head-matrix elements per lane, at most
+    constexpr int W1B = 8;                                         // 16-byte pieces of W1 per lane and batch
+    static_assert(RK <= WG && RN <= WG, "one bias element per lane");
+    const f4v* w1src = reinterpret_cast<const f4v*>(a.theta + a.net.w_off[0]);
+    f4v* w1dst = reinterpret_cast<f4v*>(w1s);
+    const int n_w1 = W1_IN_LDS ? D * RK / 4 : 0;
+    float vwh[NWH];
+    f4v vw1[W1B];
+#pragma unroll
+    for (int u = 0; u < NWH; ++u) {
+        const int i = tid + u * WG;
+        vwh[u] = a.theta[a.net.wh_off + (i < HL * NH ? i : 0)];     // unconditional: the stores below select
     }
-    if (tid < 8) bhs[tid] = tid < NH ? a.theta[a.net.bh_off + tid] : 0.0f;
-    if (W1_IN_LDS) {
-        const float4* src = reinterpret_cast<const float4*>(a.theta + a.net.w_off[0]);
-        float4* dst = reinterpret_cast<float4*>(w1s);
-        for (int i = tid; i < D * RK / 4; i += WG) dst[i] = src[i];
+    const float vbh = a.theta[a.net.bh_off + (tid < NH ? tid : 0)];
+    const float vb1 = a.theta[a.net.b_off[0] + (tid < RK ? tid : 0)];
+    const float vb2 = a.theta[a.net.b_off[1] + (tid < RN ? tid : 0)];
+#pragma unroll
+    for (int u = 0; u < W1B; ++u) {
+        const int i = tid + u * WG;
+        if (W1_IN_LDS) vw1[u] = w1src[i < n_w1 ? i : 0];
     }
+    __builtin_amdgcn_sched_barrier(0);
     const float* w1 = W1_IN_LDS ? w1s : a.theta + a.net.w_off[0];
 
     // this lane's share of W2, in matrix-core operand order
@@ -750,7 +765,33 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
 #pragma unroll
         for (int s = 0; s < KS; ++s) load_nt<NT>(W2 + (size_t)(kstep * s + kq) * RN + col0, wreg[s]);
     }
-    const float* bias2 = a.theta + a.net.b_off[1];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < NWH; ++u) {
+        const int i = tid + u * WG;
+        const int k = i / NH, j = i - k * NH;
+        if (i < HL * NH) whs[j * ldw + k] = vwh[u];
+    }
+    if (tid < 8) bhs[tid] = tid < NH ? vbh : 0.0f;
+    if (tid < RK) b1s[tid] = vb1;
+    if (tid < RN) b2s[tid] = vb2;
+#pragma unroll
+    for (int u = 0; u < W1B; ++u) {
+        const int i = tid + u * WG;
+        if (i < n_w1) w1dst[i] = vw1[u];
+    }
+    for (int i0 = W1B * WG; i0 < n_w1; i0 += W1B * WG) {
+#pragma unroll
+        for (int u = 0; u < W1B; ++u) {
+            const int i = i0 + tid + u * WG;
+            vw1[u] = w1src[i < n_w1 ? i : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < W1B; ++u) {
+            const int i = i0 + tid + u * WG;
+            if (i < n_w1) w1dst[i] = vw1[u];
+        }
+    }
 
     EnvState st{0u, 0.0f, 0.0f};
     const bool owner = tid < TM;
@@ -764,6 +805,11 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
             for (int w = 0; w < 8; ++w) obs[tid * OBS_WORDS + w] = tp.walls[(size_t)w * B + b];
         }
     }
+
+    // Everything loaded so far (weights, the envs' states) has arrived before the loop starts.  Inside the
+    // loop the acting path then only stores to memory, and no step waits for an earlier step's stores: a
+    // wait for a load would be a wait for every older store of the wavefront as well.
+    if (!REPLAY) __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
 
     for (int t = 0; t <= T; ++t) {
         const size_t tb = (size_t)t * B + b;
@@ -793,21 +839,23 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
         __syncthreads();
         const bool keep = t < T && a.keep_acts;
         float* g0 = keep ? tp.act[0] + ((size_t)t * B + b0) * RK : nullptr;
-        first_layer<ENV, TM * RK / 1024, false>(a, obs, bufA, ldx, tid, g0, w1);
+        first_layer<ENV, TM * RK / 1024, false>(a, obs, bufA, ldx, tid, g0, w1, b1s);
         __syncthreads();
         float* g1 = keep ? tp.act[1] + ((size_t)t * B + b0) * RN : nullptr;
-        if (M32) resident_m32<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
-        else resident_m16<KS, NT>(wreg, bufA, bufB, ldx, bias2, RN, tid, g1);
+        if (M32) resident_m32<KS, NT>(wreg, bufA, bufB, ldx, b2s, RN, tid, g1);
+        else resident_m16<KS, NT>(wreg, bufA, bufB, ldx, b2s, RN, tid, g1);
         __syncthreads();
         heads_pipe<4, HL>(bufB, ldx, whs, ldw, bhs, heads, NH, NHP, TM, tid);
         // the step's random draws do not depend on the network: the last lanes of the workgroup,
-        // idle during the head chains, produce them now
+        // idle during the head chains, produce them now -- the action draw of every env and the draw
+        // that places the next episode, which then costs nothing where an episode ends
         if (!REPLAY && t < T) {
-            for (int e = WG - 1 - tid; e < TM; e += WG) {
-                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, DOM_ACTION);
+            for (int i = WG - 1 - tid; i < (ENV == ENV_MAZE ? TM : 2 * TM); i += WG) {
+                const int e = i < TM ? i : i - TM;
+                const u32x4 w = philox(a.seed, (uint32_t)(b0 + e), a.gstep + (uint64_t)t, i < TM ? DOM_ACTION : DOM_RESET);
                 // the pendulum's noise is ready-made when the heads are: only z and tanh remain on the critical path
-                rng[e * 4] = ENV == ENV_PENDULUM ? bits_from_f(gaussian_noise(w.x, w.y)) : w.x;
-                rng[e * 4 + 1] = w.y;
+                const uint32_t w0 = (ENV == ENV_PENDULUM && i < TM) ? bits_from_f(gaussian_noise(w.x, w.y)) : w.x;
+                *reinterpret_cast<uint2*>(rng + e * 4 + (i < TM ? 0 : 2)) = make_uint2(w0, w.y);
             }
         }
         __syncthreads();
@@ -818,34 +866,22 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
             float* hd = tp.tr_head + tb * NHP;
             *reinterpret_cast<float4*>(hd) = h0;
             if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = h1;
-            float val = hv[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
+            const float val = last_head(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], NH);
             tp.tr_val[tb] = val;
             if (!REPLAY && t < T) {
-                const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 4);   // action draw, words 0 and 1
+                const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);   // action draw, reset draw
                 float r; int done;
-                // the reset draw is only needed where an episode ends: the step runs with a placeholder
-                // and the few lanes that finished an episode draw and reset afterwards
                 if (ENV == ENV_PENDULUM) {
                     const float eps = f_from_bits(dr.x);
                     const float act = gaussian_action(hv[0], hv[1], eps);
                     tp.tr_eps[tb] = eps;
                     tp.tr_actf[tb] = act;
-                    pendulum_step(a.env, st, act, 0u, 0u, r, done);
-                    if (done) {
-                        const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
-                        pendulum_reset(st, wr.x, wr.y);
-                    }
+                    pendulum_step(a.env, st, act, dr.z, dr.w, r, done);
                 } else {
-                    const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
+                    const int act = sample_categorical_any(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
                     if (ENV == ENV_CATCH) {
-                        catch_step(a.env, st, act, 0u, r, done);
-                        if (done) {
-                            const u32x4 wr = philox(a.seed, (uint32_t)b, a.gstep + (uint64_t)t, DOM_RESET);
-                            st.s0 = catch_reset(a.env, wr.x);
-                        }
+                        catch_step(a.env, st, act, dr.z, r, done);
                     } else {
                         const uint32_t* wl = obs + tid * OBS_WORDS;
                         maze_step(a.env, st, act, [wl](int c) { return ((wl[c >> 5] >> (c & 31)) & 1u) != 0u; }, r, done);
@@ -959,9 +995,7 @@ __global__ __launch_bounds__(WG) void rollout_lane_kernel(const RolloutArgs a)
         float* hd = tp.tr_head + tb * NHP;
         *reinterpret_cast<float4*>(hd) = make_float4(hv[0], hv[1], hv[2], hv[3]);
         if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = make_float4(hv[4], hv[5], hv[6], hv[7]);
-        float val = hv[0];
-#pragma unroll
-        for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
+        const float val = last_head(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], NH);
         tp.tr_val[tb] = val;
         if (!REPLAY && t < T) {
             float r; int done;
@@ -976,7 +1010,7 @@ __global__ __launch_bounds__(WG) void rollout_lane_kernel(const RolloutArgs a)
                     pendulum_reset(st, wr.x, wr.y);
                 }
             } else {
-                const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
+                const int act = sample_categorical_any(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], a.net.A, u01(dr.x));
                 tp.tr_act[tb] = (uint8_t)act;
                 catch_step(a.env, st, act, 0u, r, done);
                 if (done) {
@@ -1106,6 +1140,7 @@ static hipError_t launch_resident(anakin* h, const RolloutArgs& a)
 {
     constexpr int TM = M32 ? 32 : 16;
     size_t lds = rollout_lds_bytes(h->net, h->env, TM, nullptr);
+    lds += (size_t)2 * RW * 4;                                     // the hidden layers' biases
     if (ENV != ENV_MAZE) lds += (size_t)h->net.dims[0] * RW * 4;
     auto kern = rollout_resident_kernel<ENV, M32, RW, RW, REPLAY>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -551,9 +551,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
             float* hd = tp.tr_head + tb * NHP;
             *reinterpret_cast<float4*>(hd) = make_float4(hv[0], hv[1], hv[2], hv[3]);
             if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = make_float4(hv[4], hv[5], hv[6], hv[7]);
-            float val = hv[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) if (j == NH - 1) val = hv[j];
+            const float val = last_head(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], NH);
             tp.tr_val[tb] = val;
             if (!REPLAY && t < T) {
                 const uint2 dr = *reinterpret_cast<const uint2*>(rng + tid * 2);
@@ -568,7 +566,7 @@ __global__ __launch_bounds__(BWG) void rollout_bf16_kernel(const RolloutBf16Args
                         pendulum_reset(st, wr.x, wr.y);
                     }
                 } else {
-                    const int act = sample_categorical<8>(hv, a.net.A, u01(dr.x));
+                    const int act = sample_categorical_any(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], a.net.A, u01(dr.x));
                     tp.tr_act[tb] = (uint8_t)act;
                     if (ENV == ENV_CATCH) {
                         catch_step(a.env, st, act, 0u, r, done);
