@@ -480,23 +480,23 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
         fetch_d(clampm(m0 + 2 * NRES_RT));
         fetch_mask(mask_fill, clampm(m0 + NRES_RT));             // one stage ahead
         __builtin_amdgcn_sched_barrier(0);
-        // the KS values of this lane for the next stage, two per word, and the rows they go to
-        uint32_t pk[KS / 2];
+        // the KS values of this lane for the next stage, two per word, and the rows they go to.  HEADS: the tiles of
+        // dZ_L stay in their accumulators and every word is masked and rounded right before its two stores, between
+        // the MFMAs, instead of all of them ahead of the first one
+        uint32_t pk[HEADS ? 1 : KS / 2];
         uint16_t* wbase[HEADS ? TJ : 1];
+        f16v accz[HEADS ? TJ : 1];
+        uint32_t zbits[HEADS ? TJ : 1];
         if (HEADS) {
             const uint4 a1v = Ahl[par ^ 1][lane];
             const bf8 a1 = *reinterpret_cast<const bf8*>(&a1v);
 #pragma unroll
             for (int jt = 0; jt < TJ; ++jt) {
-                f16v acc1;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+                for (int r = 0; r < 16; ++r) accz[jt][r] = 0.0f;
                 const uint4 wv = WhB[wave * (NR / 8) + 32 * jt + l32];
-                acc1 = mfma_bf16(a1, *reinterpret_cast<const bf8*>(&wv), acc1);
-                const uint32_t bits = st_next[0][jt];
-#pragma unroll
-                for (int w = 0; w < 8; ++w)
-                    pk[8 * jt + w] = cvt_pk_bf16(keep_if(acc1[2 * w], bits, 2 * w), keep_if(acc1[2 * w + 1], bits, 2 * w + 1));
+                accz[jt] = mfma_bf16(a1, *reinterpret_cast<const bf8*>(&wv), accz[jt]);
+                zbits[jt] = st_next[0][jt];
                 wbase[jt] = nxt + (4 * kg) * LD + wave * (NR / 8) + 32 * jt + l32;
             }
         } else {
@@ -508,12 +508,16 @@ __global__ __launch_bounds__(NRES_WG) void gemm_nt_bf16_res(const GemmNtBf16Args
         }
         // store k: half k % 2 of word k / 2.  HEADS: word 2g + j of a tile holds rows 8g + 4kg + 2j, + 1 of its
         // column; otherwise piece q = k / 8 is sample group q (NR = 512) or 2q + tid / 256 (NR = 256), sample k % 8
+        uint32_t zword = 0u;
         auto put = [&](int k) {
-            const uint16_t v = (uint16_t)(pk[k >> 1] >> ((k & 1) * 16));
             if (HEADS) {
                 const int jt = k >> 4, kk = k & 15;
-                wbase[HEADS ? jt : 0][(8 * (kk >> 2) + 2 * ((kk >> 1) & 1) + (kk & 1)) * LD] = v;
+                if ((kk & 1) == 0)
+                    zword = cvt_pk_bf16(keep_if(accz[HEADS ? jt : 0][kk], zbits[HEADS ? jt : 0], kk),
+                                        keep_if(accz[HEADS ? jt : 0][kk + 1], zbits[HEADS ? jt : 0], kk + 1));
+                wbase[HEADS ? jt : 0][(8 * (kk >> 2) + (kk & 3)) * LD] = (uint16_t)(zword >> ((kk & 1) * 16));
             } else {
+                const uint16_t v = (uint16_t)(pk[HEADS ? 0 : k >> 1] >> ((k & 1) * 16));
                 wbase[0][((NR == 512 ? 8 : 16) * (k >> 3) + (k & 7)) * LD] = v;
             }
         };
