@@ -964,8 +964,14 @@ __global__ __launch_bounds__(CF_WG) void learn_catch_fused(const CatchFusedArgs 
                     for (int k = 0; k < 4; ++k) { s = fmaf(wh[k], d[k], s); dwh[k] = fmaf(hv, d[k], dwh[k]); }
                     const float dz = hv > 0.0f ? s : 0.0f;
                     db1 += dz;
-                    mine[cc[q] & 0xffffu] += dz;
-                    mine[cc[q] >> 16] += dz;
+                    // the ball is never in the paddle's row, so the two sums are different words: both reads go out
+                    // before either store, one LDS round trip per sample instead of two (two samples per round
+                    // trip, with the second taking the first's result where they share a word, measured slower)
+                    float* pa = mine + (cc[q] & 0xffffu);
+                    float* pb = mine + (cc[q] >> 16);
+                    const float xa = *pa, xb = *pb;
+                    *pa = xa + dz;
+                    *pb = xb + dz;
                 }
             }
             __syncthreads();
@@ -1021,7 +1027,7 @@ __global__ __launch_bounds__(CF_WG) void learn_catch_fused(const CatchFusedArgs 
 bool catch_fused_ok(const anakin* h)
 {
     const NetShape& n = h->net;
-    return one_layer_fused(h) && h->env.kind == ENV_CATCH && n.dims[1] == CF_H && n.NH == 4 && h->n_updates == 1 &&
+    return one_layer_fused(h) && h->env.kind == ENV_CATCH && h->env.rows >= 2 && n.dims[1] == CF_H && n.NH == 4 && h->n_updates == 1 &&
            !h->traj_decoupled && !h->pathwise && h->splits[0] > 0 && h->B % (h->splits[0] * CF_WG) == 0 &&
            n.dims[0] * CF_H < 65536;                                  // board-cell offsets are packed into 16 bits
 }
