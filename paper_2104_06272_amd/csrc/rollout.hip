@@ -859,15 +859,24 @@ __global__ __launch_bounds__(WG) void rollout_resident_kernel(const RolloutArgs 
             }
         }
         __syncthreads();
+        // the record of the head outputs is written by the second wavefront, which has nothing else to do here:
+        // the lanes that sample and step the envs are the critical path of the whole workgroup (handing the rest
+        // of the step's record -- state, action, reward, episode end -- to idle lanes through LDS as well was
+        // measured: no further gain)
+        if (tid >= 64 && tid < 64 + TM) {
+            const int e = tid - 64;
+            const size_t te = (size_t)t * B + b0 + e;
+            const float4 h0 = ld4(heads + e * NHP);
+            const float4 h1 = NHP == 8 ? ld4(heads + e * NHP + 4) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            float* hd = tp.tr_head + te * NHP;
+            *reinterpret_cast<float4*>(hd) = h0;
+            if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = h1;
+            tp.tr_val[te] = last_head(h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w, NH);
+        }
         if (owner) {
             const float4 h0 = ld4(heads + tid * NHP);
             const float4 h1 = NHP == 8 ? ld4(heads + tid * NHP + 4) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-            float* hd = tp.tr_head + tb * NHP;
-            *reinterpret_cast<float4*>(hd) = h0;
-            if (NHP == 8) *reinterpret_cast<float4*>(hd + 4) = h1;
-            const float val = last_head(hv[0], hv[1], hv[2], hv[3], hv[4], hv[5], hv[6], hv[7], NH);
-            tp.tr_val[tb] = val;
             if (!REPLAY && t < T) {
                 const uint4 dr = *reinterpret_cast<const uint4*>(rng + tid * 4);   // action draw, reset draw
                 float r; int done;
