@@ -79,6 +79,9 @@ def kernel_models(cfg, P, launched=()):
         # 28 B per parameter: read theta,g,m,v, write theta,m,v
         "adam_reduce": ("hbm", 28.0 * P / 1e9, PEAK_HBM_GBS, "GB/s"),
         "head_grad": ("hbm", (NH * 4 + 1 + 8 + NH * 4) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
+        # the two above as one launch: r 4 + done 1 + V 4 read, A 4 + G 4 written (for the caller), heads NH*4 and
+        # the action 1 read, head gradient NH*4 written
+        "scan_loss": ("hbm", (17.0 + NH * 4 + 1 + NH * 4) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
         # read h_L, write dZ_L (bf16: written in two layouts)
         "head_backward": ("hbm", ((6.0 if bf16 else 8.0) * dims[-1] + 4 * NH) * M / 1e9, PEAK_HBM_GBS, "GB/s"),
         # scatter of dZ1 rows into the selected weight rows: one read of dZ1

@@ -264,6 +264,7 @@ extern "C" size_t anakin_workspace_bytes(const anakin_env_cfg* env, const anakin
     if (build_shapes(env, net, B, T, ed, ns, err) != ANAKIN_OK) return 0;
     int splits[MAX_REGIONS], sw, lb, fan;
     plan(ed, ns, B, T, splits, &sw, &fan, &lb);
+    if (lb < B / 8) lb = B / 8;                                  // as in anakin_create
     Layout L;
     carve(ed, ns, B, T, splits, sw, fan, lb, L);
     return L.total;
@@ -395,6 +396,8 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->scratch = nullptr;
     h->stream = static_cast<hipStream_t>(hip_stream);
     plan(ed, ns, B, T, h->splits, &h->splits_w, &h->head_fan, &h->loss_blocks);
+    // returns and loss in one launch write one block of sums per eight envs where the unroll is short
+    if (h->loss_blocks < B / 8) h->loss_blocks = B / 8;
     carve(ed, ns, B, T, h->splits, h->splits_w, h->head_fan, h->loss_blocks, h->lay);
     if (h->lay.total > workspace_bytes) {
         g_create_error = "workspace too small: need " + std::to_string(h->lay.total) + " bytes";
@@ -569,9 +572,9 @@ extern "C" int32_t anakin_rollout(anakin_t* h)
 }
 
 // loss, backward pass and Adam on the samples the handle's layout and T currently describe
-static int32_t run_update(anakin* h)
+static int32_t run_update(anakin* h, bool loss_done = false)
 {
-    HIPCHK(h, launch_head_grad(h));
+    if (!loss_done) HIPCHK(h, launch_head_grad(h));
     if (h->traj_packed) HIPCHK(h, launch_backward_bf16(h));
     else if (h->traj_no_acts) HIPCHK(h, launch_learn_one_layer(h));
     else HIPCHK(h, launch_backward(h));
@@ -599,13 +602,15 @@ extern "C" int32_t anakin_learn(anakin_t* h)
         h->have_traj = 0;
         return ANAKIN_OK;
     }
-    HIPCHK(h, launch_returns(h));
+    const bool fused_loss = scan_loss_ok(h);
+    if (fused_loss) HIPCHK(h, launch_scan_loss(h));
+    else HIPCHK(h, launch_returns(h));
     if (h->pathwise) {
         if (h->n_updates != 1) { h->err = "the pathwise policy gradient takes one update per unroll (chunks would cut the adjoint)"; return ANAKIN_E_BAD_CONFIG; }
         HIPCHK(h, launch_pathwise(h));
     }
     if (h->n_updates == 1) {
-        int32_t rc = run_update(h);
+        int32_t rc = run_update(h, fused_loss);
         if (rc != ANAKIN_OK) return rc;
         h->have_traj = 0;
         return ANAKIN_OK;

@@ -207,6 +207,8 @@ hipError_t launch_eps_now(anakin* h);
 hipError_t launch_pathwise(anakin* h);
 bool pathwise_ok(const anakin* h);
 hipError_t launch_returns(anakin* h);
+bool scan_loss_ok(const anakin* h);          // returns and loss as one launch
+hipError_t launch_scan_loss(anakin* h);
 hipError_t launch_head_grad(anakin* h);
 hipError_t launch_backward(anakin* h);
 hipError_t launch_adam(anakin* h);

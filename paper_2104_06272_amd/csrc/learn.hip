@@ -152,12 +152,11 @@ struct HeadGradArgs {
                                            // score-function term, and the reported policy loss is minus the mean reward
 };
 
-__global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
+// one sample: its loss terms, and its head gradient to a.dhead.  A_, G_: advantage and return of the sample
+__device__ __forceinline__ void head_grad_sample(const HeadGradArgs& a, const int i, float A_, const float G_,
+                                                 float& lp_term, float& v_term, float& e_term, float& rsum, float& dcount)
 {
-    __shared__ float red[WG / 64][8];
-    const int i = blockIdx.x * WG + threadIdx.x;
-    float lp_term = 0.0f, v_term = 0.0f, e_term = 0.0f, rsum = 0.0f, dcount = 0.0f;
-    if (i < a.M) {
+    {
         const float* h = a.head + (size_t)i * a.NHP;
         float hv[8];
         const float4 h0 = *reinterpret_cast<const float4*>(h);
@@ -166,7 +165,7 @@ __global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
             const float4 h1 = *reinterpret_cast<const float4*>(h + 4);
             hv[4] = h1.x; hv[5] = h1.y; hv[6] = h1.z; hv[7] = h1.w;
         } else { hv[4] = hv[5] = hv[6] = hv[7] = 0.0f; }
-        const float A_ = a.path ? 0.0f : a.adv[i], G_ = a.ret[i];
+        if (a.path) A_ = 0.0f;
         float V = hv[0];
 #pragma unroll
         for (int j = 1; j < 8; ++j) if (j == a.NH - 1) V = hv[j];
@@ -219,7 +218,12 @@ __global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
         rsum = a.rew[i];
         dcount = a.done[i] ? 1.0f : 0.0f;
     }
-    // fixed-order block reduction: butterfly inside a wave, then waves in order
+}
+
+// fixed-order block reduction of the five loss / metric sums: butterfly inside a wave, then waves in order
+__device__ __forceinline__ void loss_block_sums(float lp_term, float v_term, float e_term, float rsum, float dcount,
+                                                float (&red)[WG / 64][8], float* __restrict__ loss_part)
+{
     float vals[5] = {lp_term, v_term, e_term, rsum, dcount};
 #pragma unroll
     for (int k = 0; k < 5; ++k)
@@ -232,8 +236,77 @@ __global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
         float s = 0.0f;
         if (threadIdx.x < 5)
             for (int w = 0; w < WG / 64; ++w) s += red[w][threadIdx.x];
-        a.loss_part[(size_t)blockIdx.x * 8 + threadIdx.x] = s;
+        loss_part[(size_t)blockIdx.x * 8 + threadIdx.x] = s;
     }
+}
+
+__global__ __launch_bounds__(WG) void head_grad(const HeadGradArgs a)
+{
+    __shared__ float red[WG / 64][8];
+    const int i = blockIdx.x * WG + threadIdx.x;
+    float lp_term = 0.0f, v_term = 0.0f, e_term = 0.0f, rsum = 0.0f, dcount = 0.0f;
+    if (i < a.M) head_grad_sample(a, i, a.adv[i], a.ret[i], lp_term, v_term, e_term, rsum, dcount);
+    loss_block_sums(lp_term, v_term, e_term, rsum, dcount, red, a.loss_part);
+}
+
+// ---------------------------------------------------------------------------
+// Returns and loss in one launch (the plain on-policy update): a workgroup owns E envs for all T steps (8 or 16:
+// 256 samples or fewer where that is possible, so that every thread takes one).  Its
+// rewards, values and episode ends come into LDS with every thread loading, the first E lanes then run
+// returns_scan's recursion out of LDS (returns and advantages to memory, for the caller to see, and to LDS), and
+// every thread takes the samples s, s + 256, ... of the workgroup's T x E through head_grad's arithmetic.
+// One launch and no trip of the advantages through memory between the two.
+// ---------------------------------------------------------------------------
+constexpr int SL_MAXN = 1024;            // samples of a workgroup at most (T x envs)
+struct ScanLossArgs {
+    HeadGradArgs g;
+    int B, T, E;                           // E: envs per workgroup (8 or 16)
+    const float* val;                      // [T + 1][B]
+    float gamma, lambda;
+    float* adv_out; float* ret_out;
+};
+
+__global__ __launch_bounds__(WG) void scan_loss(const ScanLossArgs a)
+{
+    __shared__ float red[WG / 64][8];
+    __shared__ float rews[SL_MAXN], vals[SL_MAXN + 16], discs[SL_MAXN];
+    __shared__ float advs[SL_MAXN], rets[SL_MAXN];
+    const int B = a.B, T = a.T, SL_E = a.E, tid = threadIdx.x;
+    const int b0 = blockIdx.x * SL_E;
+    const int n = T * SL_E;
+    for (int s = tid; s < n + SL_E; s += WG) {
+        const int t = s / SL_E, e = s - t * SL_E;
+        const size_t i = (size_t)t * B + b0 + e;
+        vals[s] = a.val[i];
+        if (s < n) { rews[s] = a.g.rew[i]; discs[s] = a.g.done[i] ? 0.0f : a.gamma; }
+    }
+    __syncthreads();
+    if (tid < SL_E) {
+        const float oml = 1.0f - a.lambda;
+        float G = vals[n + tid], vnext = G;
+        for (int t = T - 1; t >= 0; --t) {
+            const int s = t * SL_E + tid;
+            const float v = vals[s];
+            const float mix = fmaf(a.lambda, G, oml * vnext);
+            G = fmaf(discs[s], mix, rews[s]);
+            rets[s] = G;
+            advs[s] = G - v;
+            vnext = v;
+        }
+    }
+    __syncthreads();
+    float lp_term = 0.0f, v_term = 0.0f, e_term = 0.0f, rsum = 0.0f, dcount = 0.0f;
+    for (int s = tid; s < n; s += WG) {
+        const int t = s / SL_E, e = s - t * SL_E;
+        const int i = t * B + b0 + e;
+        const float A_ = advs[s], G_ = rets[s];
+        a.adv_out[i] = A_;
+        a.ret_out[i] = G_;
+        float l0, l1, l2, l3, l4;
+        head_grad_sample(a.g, i, A_, G_, l0, l1, l2, l3, l4);
+        lp_term += l0; v_term += l1; e_term += l2; rsum += l3; dcount += l4;
+    }
+    loss_block_sums(lp_term, v_term, e_term, rsum, dcount, red, a.g.loss_part);
 }
 
 // ---------------------------------------------------------------------------
@@ -1341,6 +1414,38 @@ hipError_t launch_head_grad(anakin* h)
     h->metric_blocks = h->loss_blocks;
     ProfScope prof(h, "head_grad");
     hipLaunchKernelGGL(head_grad, dim3(h->loss_blocks), dim3(WG), 0, h->stream, a);
+    return hipGetLastError();
+}
+
+// whether returns and loss go out as one launch: the plain update of a whole unroll, and room for one block of loss
+// sums per workgroup
+// 16 envs per workgroup unless that leaves the second pass over the samples mostly empty (256 < 16 T < 512)
+static int scan_loss_envs(const anakin* h) { return (h->T * 16 <= WG || h->T * 16 >= 2 * WG) ? 16 : 8; }
+bool scan_loss_ok(const anakin* h)
+{
+    const int E = scan_loss_envs(h);
+    return h->n_updates == 1 && !h->pathwise && !h->traj_decoupled && h->B % E == 0 && h->T * E <= SL_MAXN &&
+           h->B / E <= h->loss_blocks;
+}
+
+hipError_t launch_scan_loss(anakin* h)
+{
+    const Layout& L = h->lay;
+    ScanLossArgs s;
+    HeadGradArgs& a = s.g;
+    a.M = h->B * h->T; a.A = h->net.A; a.NH = h->net.NH; a.NHP = h->net.NHP; a.policy = h->net.policy;
+    a.head = at<const float>(h, L.tr_head); a.act = at<const uint8_t>(h, L.tr_act); a.eps = at<const float>(h, L.tr_eps);
+    a.adv = nullptr; a.ret = nullptr;
+    a.rew = at<const float>(h, L.tr_rew); a.done = at<const uint8_t>(h, L.tr_done);
+    a.dhead = at<float>(h, L.dhead); a.loss_part = at<float>(h, L.loss_part);
+    a.beta = h->net_cfg.entropy_coef; a.cv = h->net_cfg.value_coef; a.inv_m = (float)(1.0 / (double)a.M);
+    a.path = nullptr;
+    s.B = h->B; s.T = h->T; s.E = scan_loss_envs(h); s.val = at<const float>(h, L.tr_val);
+    s.gamma = h->net_cfg.gamma; s.lambda = h->net_cfg.lambda_;
+    s.adv_out = at<float>(h, L.adv); s.ret_out = at<float>(h, L.ret);
+    h->metric_blocks = h->B / s.E;
+    ProfScope prof(h, "scan_loss");
+    hipLaunchKernelGGL(scan_loss, dim3(h->B / s.E), dim3(WG), 0, h->stream, s);
     return hipGetLastError();
 }
 
