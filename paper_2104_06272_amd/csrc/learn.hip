@@ -884,7 +884,14 @@ __global__ __launch_bounds__(OLW) void learn_one_layer(const OneLayerArgs a)
             for (int k = 0; k < NH; ++k) { s = fmaf(wh[k], d[k], s); dwh[k] = fmaf(hv, d[k], dwh[k]); dbh[k] += d[k]; }
             const float dz = hv > 0.0f ? s : 0.0f;
             db1 += dz;
-            if (ENV == ENV_CATCH) { mine[bc * cw] += dz; mine[pc * cw] += dz; }
+            if (ENV == ENV_CATCH) {
+                // the ball is never in the paddle's row: two different words, both read before either is stored
+                float* pa = mine + bc * cw;
+                float* pb = mine + pc * cw;
+                const float xa = *pa, xb = *pb;
+                *pa = xa + dz;
+                *pb = xb + dz;
+            }
             else { r0 = fmaf(x0, dz, r0); r1 = fmaf(x1, dz, r1); r2 = fmaf(x2, dz, r2); }
         }
     }
