@@ -994,35 +994,65 @@ __global__ __launch_bounds__(CF_WG) void learn_catch_fused(const CatchFusedArgs 
         // ---- A1: returns and advantages of this env, newest step first ----
         {
             float G = a.val[(size_t)T * B + b], vnext = G;
-#pragma unroll 4
-            for (int t = T - 1; t >= 0; --t) {
-                const size_t i = (size_t)t * B + b;
-                const float r = a.rew[i], v = a.val[i];
-                const float disc = a.done[i] ? 0.0f : a.gamma;
-                const float mix = fmaf(a.lambda, G, oml * vnext);
-                G = fmaf(disc, mix, r);
-                a.ret[i] = G;
-                a.adv[i] = G - v;
-                vnext = v;
+            // eight steps' records are asked for before the first of them is used: the stores of one step and the
+            // loads of the next may be the same memory as far as the compiler knows, so step by step every load
+            // would wait for its own round trip
+            for (int t1 = T; t1 > 0; t1 -= 8) {
+                float r8[8], v8[8], d8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t1 - 1 - u;
+                    const size_t i = (size_t)(t >= 0 ? t : 0) * B + b;
+                    r8[u] = a.rew[i]; v8[u] = a.val[i]; d8[u] = a.done[i] ? 0.0f : a.gamma;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t1 - 1 - u;
+                    if (t >= 0) {
+                        const size_t i = (size_t)t * B + b;
+                        const float mix = fmaf(a.lambda, G, oml * vnext);
+                        G = fmaf(d8[u], mix, r8[u]);
+                        a.ret[i] = G;
+                        a.adv[i] = G - v8[u];
+                        vnext = v8[u];
+                    }
+                }
             }
         }
+        // the records of a chunk's samples: asked for one chunk ahead, so that they arrive while the chunk before is in
+        // phase B (straight after the barrier every load would be a round trip to memory with nothing to hide it)
+        f4v_l in_h[CF_TC]; float in_adv[CF_TC], in_ret[CF_TC], in_rew[CF_TC]; uint32_t in_s0[CF_TC]; int in_act[CF_TC], in_done[CF_TC];
+        auto fetch_chunk = [&](int t0) {
+#pragma unroll
+            for (int tt = 0; tt < CF_TC; ++tt) {
+                const int t = t0 + tt < T ? t0 + tt : T - 1;         // past the end: re-read the last step, unused
+                const size_t i = (size_t)t * B + b;
+                in_h[tt] = *reinterpret_cast<const f4v_l*>(a.head + i * 4);
+                in_act[tt] = (int)a.act[i]; in_adv[tt] = a.adv[i]; in_ret[tt] = a.ret[i];
+                in_rew[tt] = a.rew[i]; in_done[tt] = a.done[i]; in_s0[tt] = a.s0[i];
+            }
+        };
+        fetch_chunk(0);
         for (int t0 = 0; t0 < T; t0 += CF_TC) {
             const int tn = T - t0 < CF_TC ? T - t0 : CF_TC;
             // ---- A2: loss terms and head gradients of (t0 .. t0 + tn - 1, b) ----
-            for (int tt = 0; tt < tn; ++tt) {
-                const size_t i = (size_t)(t0 + tt) * B + b;
-                const float4 hv4 = *reinterpret_cast<const float4*>(a.head + i * 4);
-                float d[4], lp_term, v_term, e_term;
-                catch_head_grad(hv4, (int)a.act[i], a.adv[i], a.ret[i], a.beta, a.cv, a.inv_m, d, lp_term, v_term, e_term);
-                sums[0] += lp_term; sums[1] += v_term; sums[2] += e_term; sums[3] += a.rew[i]; sums[4] += a.done[i] ? 1.0f : 0.0f;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) dbh[k] += d[k];
-                dh[tt * 64 + lane] = make_float4(d[0], d[1], d[2], d[3]);
-                int bc, pc;
-                catch_obs_cells(a.env, a.s0[i], bc, pc);
-                cells[tt * 64 + lane] = (uint32_t)(bc * H) | ((uint32_t)(pc * H) << 16);
+            for (int tt = 0; tt < CF_TC; ++tt) {
+                if (tt < tn) {
+                    const float4 hv4 = make_float4(in_h[tt][0], in_h[tt][1], in_h[tt][2], in_h[tt][3]);
+                    float d[4], lp_term, v_term, e_term;
+                    catch_head_grad(hv4, in_act[tt], in_adv[tt], in_ret[tt], a.beta, a.cv, a.inv_m, d, lp_term, v_term, e_term);
+                    sums[0] += lp_term; sums[1] += v_term; sums[2] += e_term; sums[3] += in_rew[tt]; sums[4] += in_done[tt] ? 1.0f : 0.0f;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) dbh[k] += d[k];
+                    dh[tt * 64 + lane] = make_float4(d[0], d[1], d[2], d[3]);
+                    int bc, pc;
+                    catch_obs_cells(a.env, in_s0[tt], bc, pc);
+                    cells[tt * 64 + lane] = (uint32_t)(bc * H) | ((uint32_t)(pc * H) << 16);
+                }
             }
             __syncthreads();
+            if (t0 + CF_TC < T) fetch_chunk(t0 + CF_TC);
             // ---- B: half hf takes samples hf, hf + 2, ... of the chunk's tn * 64 ----
             const int ns = tn * 64;
             constexpr int RB = 8;
