@@ -973,7 +973,20 @@ __global__ __launch_bounds__(CF_WG) void learn_catch_fused(const CatchFusedArgs 
     float* acc = accw;                                           // [2 halves][D][H] this wavefront's dW1 sums
     float4* dh = reinterpret_cast<float4*>(accw + 2 * D * H);    // [CF_TC][64] head gradients of the chunk
     uint32_t* cells = reinterpret_cast<uint32_t*>(dh + CF_TC * 64);   // [CF_TC][64] LDS offsets of the two board cells
-    for (int i = tid; i < D * H; i += CF_WG) w1s[i] = a.theta[a.w1_off + i];
+    // W1 into LDS in batches of four 16-byte loads per thread (one load, one wait, one store at a time would be a
+    // memory round trip per 4 KB); H is a multiple of 4, and so is the offset of W1 in the parameter vector
+    {
+        const int n4 = D * H / 4;
+        const f4v_l* src = reinterpret_cast<const f4v_l*>(a.theta + a.w1_off);
+        f4v_l* dst = reinterpret_cast<f4v_l*>(w1s);
+        for (int i0 = 0; i0 < n4; i0 += 4 * CF_WG) {
+            f4v_l pw[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { const int i = i0 + q * CF_WG + tid; pw[q] = src[i < n4 ? i : 0]; }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { const int i = i0 + q * CF_WG + tid; if (i < n4) dst[i] = pw[q]; }
+        }
+    }
     for (int i = lane; i < 2 * D * H; i += 64) acc[i] = 0.0f;
     // phase B identity: hidden unit u, half hf (the two halves of a wavefront take alternate samples)
     const int u = lane & 31, hf = lane >> 5;
@@ -1139,7 +1152,7 @@ bool catch_fused_ok(const anakin* h)
     const NetShape& n = h->net;
     return one_layer_fused(h) && h->env.kind == ENV_CATCH && h->env.rows >= 2 && n.dims[1] == CF_H && n.NH == 4 && h->n_updates == 1 &&
            !h->traj_decoupled && !h->pathwise && h->splits[0] > 0 && h->B % (h->splits[0] * CF_WG) == 0 &&
-           n.dims[0] * CF_H < 65536;                                  // board-cell offsets are packed into 16 bits
+           n.dims[0] * CF_H < 65536 && n.w_off[0] % 4 == 0;           // board-cell offsets are packed into 16 bits; W1 is read 16 bytes at a time
 }
 
 hipError_t launch_learn_catch_fused(anakin* h)
