@@ -928,10 +928,35 @@ __global__ __launch_bounds__(WG) void rollout_lane_kernel(const RolloutArgs a)
     float* whs = b1s + H;                                         // [H][8] head weights, k-major, columns >= NH zero
     float* bhs = whs + H * 8;                                     // [8]
     const int tid = threadIdx.x;
-    for (int i = tid; i < D * H; i += WG) w1s[(i / H) * LDW + i % H] = a.theta[a.net.w_off[0] + i];
-    for (int i = tid; i < H; i += WG) b1s[i] = a.theta[a.net.b_off[0] + i];
-    for (int i = tid; i < H * 8; i += WG) { const int k = i >> 3, j = i & 7; whs[i] = j < NH ? a.theta[a.net.wh_off + k * NH + j] : 0.0f; }
-    if (tid < 8) bhs[tid] = tid < NH ? a.theta[a.net.bh_off + tid] : 0.0f;
+    // the parameters come into LDS in batches of eight loads per thread: one load, one wait, one store at a time
+    // would be a memory round trip per KB
+    {
+        const float vb1 = a.theta[a.net.b_off[0] + (tid < H ? tid : 0)];
+        const float vbh = a.theta[a.net.bh_off + (tid < NH ? tid : 0)];
+        constexpr int NW = (H * 8 + WG - 1) / WG;
+        float vwh[NW];
+#pragma unroll
+        for (int q = 0; q < NW; ++q) {
+            const int i = q * WG + tid, k = i >> 3, j = i & 7;
+            vwh[q] = a.theta[a.net.wh_off + ((i < H * 8 && j < NH) ? k * NH + j : 0)];
+        }
+        const float* w1g = a.theta + a.net.w_off[0];
+        const int n = D * H;
+        for (int i0 = 0; i0 < n; i0 += 8 * WG) {
+            float pw[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { const int i = i0 + q * WG + tid; pw[q] = w1g[i < n ? i : 0]; }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) { const int i = i0 + q * WG + tid; if (i < n) w1s[(i / H) * LDW + i % H] = pw[q]; }
+        }
+        if (tid < H) b1s[tid] = vb1;
+        if (tid < 8) bhs[tid] = tid < NH ? vbh : 0.0f;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) {
+            const int i = q * WG + tid, j = i & 7;
+            if (i < H * 8) whs[i] = j < NH ? vwh[q] : 0.0f;
+        }
+    }
     __syncthreads();
 
     const int B = a.B, T = a.T;
