@@ -215,9 +215,13 @@ static void plan(const EnvDims& ed, const NetShape& ns, int B, int T, int* split
     if (const int s = first_fused_splits(ns, ed.kind, M, splits[1])) splits[0] = s;                           // first layer folded into the dX product of the second
     if (ns.L == 1 && ed.kind != ENV_MAZE) { splits[0] = pick_splits(M, 1, 1024); splits[1] = splits[0]; }                                     // fused one-layer update: one chunking for both regions
     if (ns.L == 1 && ed.kind == ENV_CATCH && !ns.bf16 && ns.dims[1] == 32 && B % 256 == 0) {
-        // the single-launch update (scan, loss and backward pass): a workgroup owns whole blocks of 256 envs
+        // the single-launch update (scan, loss and backward pass): a workgroup owns whole blocks of 256 envs; at most
+        // 512 workgroups -- two per compute unit, which is what fits one at a time -- so that a large batch pays the
+        // workgroup's prologue (W1 into LDS, 51 KB of sums cleared) and its tail once per two blocks or more, and the
+        // optimiser kernel adds half as many partial gradients (measured on B = 262144: 1024 -> 512 workgroups
+        // 151.5 -> 146 us and 10.5 -> 7.9 us in the optimiser kernel; 256 workgroups 220 us)
         int s = B / 256;
-        while (s > 1024 && s % 2 == 0) s /= 2;
+        while (s > 512 && s % 2 == 0) s /= 2;
         if (s <= 1024) { splits[0] = s; splits[1] = s; }
     }
     // the head-gradient pass streams the last hidden layer: many small workgroups, summed in two levels
