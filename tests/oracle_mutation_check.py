@@ -1,0 +1,197 @@
+"""Mutation check of the oracle's pins (CPU only; test infrastructure).
+
+Each entry plants one plausible mistake -- a wrong sign, coefficient, index, rounding point, clamp, draw or order --
+in a COPY of oracle/anakin_oracle.c, rebuilds that copy and runs tests/test_oracle_pins.py on it: the pins must
+turn red.  A mutation that survives names a part of the oracle no pin holds in place.
+
+    python tests/oracle_mutation_check.py            # all mutations (about a quarter of an hour)
+    python tests/oracle_mutation_check.py vtrace     # those whose name contains a word
+
+tests/test_oracle_mutations.py runs a short selection of them with the CPU suite.
+"""
+import os
+import shutil
+import subprocess
+import sys
+import tempfile
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# (name, text in the oracle source -- must occur exactly once, its replacement)
+MUTATIONS = [
+    # (name, old, new)
+    ("catch: paddle clamp upper", "if (px > h->env.cols - 1) px = h->env.cols - 1;", "if (px > h->env.cols - 1) px = h->env.cols - 2;"),
+    ("catch: reward sign", "*r = (px == si[0]) ? 1.0f : -1.0f;", "*r = (px == si[0]) ? -1.0f : 1.0f;"),
+    ("catch: ball before paddle", "*r = (px == si[0]) ? 1.0f : -1.0f;", "*r = (px - (a - 1) == si[0]) ? 1.0f : -1.0f;"),
+    ("catch: paddle start", "si[2] = h->env.cols / 2;", "si[2] = 0;"),
+    ("catch: obs row-major", "x[si[1] * h->env.cols + si[0]] = 1.0f;", "x[si[0] * h->env.rows + si[1]] = 1.0f;"),
+    ("catch: episode length", "if (si[1] == h->env.rows - 1) {", "if (si[1] == h->env.rows) {"),
+    ("pend: torque scale", "float u = 2.0f * a;", "float u = 1.0f * a;"),
+    ("pend: cost thd coef", "cost = fmaf(0x1.99999ap-4f, thd * thd, cost);", "cost = fmaf(0x1.99999ap-5f, thd * thd, cost);"),
+    ("pend: cost u coef dropped", "cost = fmaf(0x1.0624dep-10f, u * u, cost);", "cost = cost;"),
+    ("pend: sin coefficient", "fmaf(15.0f, orc_sin(th), 3.0f * u)", "fmaf(10.0f, orc_sin(th), 3.0f * u)"),
+    ("pend: torque coefficient", "fmaf(15.0f, orc_sin(th), 3.0f * u)", "fmaf(15.0f, orc_sin(th), 1.0f * u)"),
+    ("pend: explicit euler", "float nth = wrap_angle(fmaf(nthd, 0x1.99999ap-5f, th));", "float nth = wrap_angle(fmaf(thd, 0x1.99999ap-5f, th));"),
+    ("pend: velocity clip", "if (nthd > 8.0f) nthd = 8.0f;", "if (nthd > 9.0f) nthd = 9.0f;"),
+    ("pend: obs order", "x[0] = c; x[1] = s; x[2] = sf[1];", "x[0] = s; x[1] = c; x[2] = sf[1];"),
+    ("pend: init thd range", "sf[1] = fmaf(2.0f, orc_u01(w1), -1.0f);", "sf[1] = fmaf(1.0f, orc_u01(w1), -0.5f);"),
+    ("maze: action 0/2 swapped", "if (a == 0) nr = row - 1;", "if (a == 0) nr = row + 1;"),
+    ("maze: step reward", "*r = -0x1.47ae14p-7f;", "*r = -0x1.47ae14p-6f;"),
+    ("maze: cap", "*done = (si[1] >= h->env.max_steps);", "*done = (si[1] > h->env.max_steps);"),
+    ("maze: obs planes swapped", "x[n + c] = (c == si[0]) ? 1.0f : 0.0f;\n        x[2 * n + c] = (c == n - 1) ? 1.0f : 0.0f;", "x[2 * n + c] = (c == si[0]) ? 1.0f : 0.0f;\n        x[n + c] = (c == n - 1) ? 1.0f : 0.0f;"),
+    ("maze: goal not forced free", "w[(n - 1) >> 5] &= ~(1u << ((n - 1) & 31));", ";"),
+    ("maze: wall threshold", "if (r4[i] < thr) w[cell >> 5]", "if (r4[i] < thr / 2) w[cell >> 5]"),
+    ("init: glorot scale", "float a = (float)sqrt(6.0 / (double)(fan_in + fan_out));", "float a = (float)sqrt(3.0 / (double)(fan_in + fan_out));"),
+    ("fwd32: relu missing", "float v = y[j] > 0.0f ? y[j] : 0.0f;", "float v = y[j];"),
+    ("fwd32: transposed W", "float w = W[(size_t)k * N + j];", "float w = W[((size_t)j * K + k) % ((size_t)K * N)];"),
+    ("fwd32: bf16 activation round missing", "y[j] = bf ? orc_bf16_round(v) : v;", "y[j] = v;"),
+    ("fwd32: bf16 input round missing", "float xk = bf ? orc_bf16_round(in[k]) : in[k];", "float xk = in[k];"),
+    ("sample: cdf strict", "if (c[i] > thr) return i;", "if (c[i] >= thr) return i;"),
+    ("sample: no max shift / wrong", "float e = orc_exp(logits[i] - mx);", "float e = orc_exp(0.5f * (logits[i] - mx));"),
+    ("gauss: log sigma clamp", "if (ls > 2.0f) ls = 2.0f;", "if (ls > 1.0f) ls = 1.0f;"),
+    ("gauss: box-muller factor", "float rad = sqrtf(-2.0f * orc_log(orc_u01_plus(w0)));", "float rad = sqrtf(-1.0f * orc_log(orc_u01_plus(w0)));"),
+    ("returns: lambda mix", "G = (double)rew[tb] + disc * ((1.0 - lambda) * vnext + lambda * G);", "G = (double)rew[tb] + disc * (lambda * vnext + (1.0 - lambda) * G);"),
+    ("returns: done ignored", "double disc = done[tb] ? 0.0 : gamma;\n            double vnext", "double disc = gamma;\n            double vnext"),
+    ("returns: adv uses next value", "adv[tb] = G - (double)val[tb];", "adv[tb] = G - (double)val[tb + B];"),
+    ("fp64: head weights unrounded", "wq[h->wh_off + i] = (double)orc_bf16_round(theta_src[h->wh_off + i]);", "wq[h->wh_off + i] = (double)theta_src[h->wh_off + i];"),
+    ("fp64: layer weights unrounded", "wq[h->w_off[l] + i] = (double)orc_bf16_round(theta_src[h->w_off[l] + i]);", "wq[h->w_off[l] + i] = (double)theta_src[h->w_off[l] + i];"),
+    ("fp64: activation unrounded", "act[l + 1][j] = on[l + 1][j] ? qround(h, s) : 0.0;", "act[l + 1][j] = on[l + 1][j] ? s : 0.0;"),
+    ("fp64: obs unrounded", "act[0][k] = qround(h, (double)xf[k]);", "act[0][k] = (double)xf[k];"),
+    ("bp: relu mask dropped (top)", "dz[L & 1][k] = on[L][k] ? s : 0.0;", "dz[L & 1][k] = s;"),
+    ("bp: relu mask dropped (mid)", "if (l > 0) dz[l & 1][k] = on[l][k] ? s : 0.0;", "if (l > 0) dz[l & 1][k] = s;"),
+    ("bp: bias grad dropped", "for (int j = 0; j < N; ++j) g[h->b_off[l] + j] += d[j];", ";"),
+    ("bp: head bias grad dropped", "for (int j = 0; j < NH; ++j) g[h->bh_off + j] += dhead[j];", ";"),
+    ("loss: value factor", "dhead[NH - 1] = -2.0 * cv * (G_ - V) * inv_n;", "dhead[NH - 1] = -1.0 * cv * (G_ - V) * inv_n;"),
+    ("loss: entropy sign in grad", "+ beta * p[i] * (lp[i] + H)) * inv_n;", "- beta * p[i] * (lp[i] + H)) * inv_n;"),
+    ("loss: policy grad sign", "dhead[i] = (-A_ * ((i == a ? 1.0 : 0.0) - p[i])", "dhead[i] = (A_ * ((i == a ? 1.0 : 0.0) - p[i])"),
+    ("loss: entropy term value", "Le += -beta * H;", "Le += beta * H;"),
+    ("loss: gauss mu grad", "dhead[0] = (-A_ * eps / sigma) * inv_n;", "dhead[0] = (-A_ * eps) * inv_n;"),
+    ("loss: gauss ls grad", "(-A_ * (eps * eps - 1.0) - beta) * inv_n;", "(-A_ * (eps * eps - 1.0) + beta) * inv_n;"),
+    ("loss: gauss clamp ignored", "dhead[1] = clamped ? 0.0 : (-A_", "dhead[1] = 0 ? 0.0 : (-A_"),
+    ("adam: eps inside sqrt", "lr * mh / (sqrt(vh) + eps)", "lr * mh / sqrt(vh + eps)"),
+    ("adam: no bias correction 2", "bc2 = 1.0 - pow(beta2, (double)t);", "bc2 = 1.0;"),
+    ("adam: m coefficient", "m[i] = beta1 * m[i] + (1.0 - beta1) * gi;", "m[i] = beta1 * m[i] + gi;"),
+    ("learn_n: chunk uses theta always", "sequential ? h->theta : theta0", "h->theta"),
+    ("learn_n: sequential uses theta0", "sequential ? h->theta : theta0", "theta0"),
+    ("learn_n: loss mean", "h->loss[i] = acc[i] / (double)n_updates;", "h->loss[i] = acc[i];"),
+    ("vtrace: c uses rho_bar only / lambda dropped", "double c = lambda * (w < c_bar ? w : c_bar);", "double c = (w < c_bar ? w : c_bar);"),
+    ("vtrace: rho not clipped", "double rho = w < rho_bar ? w : rho_bar;", "double rho = w;"),
+    ("vtrace: adv without tail", "h->adv[tb] = rho * (r + disc * (Vn + tail) - V);", "h->adv[tb] = rho * (r + disc * Vn - V);"),
+    ("vtrace: tail recursion", "tail = rho * (r + disc * Vn - V) + disc * c * tail;", "tail = rho * (r + disc * Vn - V) + c * tail;"),
+    ("vtrace: ratio inverted", "log_prob_of_stored_action(h, h->cur_head + tb * NH, tb) - log_prob_of_stored_action(h, beh, tb)", "log_prob_of_stored_action(h, beh, tb) - log_prob_of_stored_action(h, h->cur_head + tb * NH, tb)"),
+    ("decoupled: learner acts with fresh params", "h->theta = behaviour;\n", ";\n"),
+    ("path: reset not cutting adjoint", "if (h->tr_done[tb]) { lam_th = 0.0; lam_thd = 0.0; }", ";"),
+    ("path: clip passes gradient", "double g_pre = clipped ? 0.0 : g_nthd;", "double g_pre = g_nthd;"),
+    ("path: cos term", "double g_th = lam_th + g_pre * dt * 15.0 * cos(th) + w * (-2.0 * th);", "double g_th = lam_th + g_pre * dt * 15.0 * sin(th) + w * (-2.0 * th);"),
+    ("path: tanh jacobian", "double g_z = 2.0 * g_u * (1.0 - a * a);", "double g_z = 2.0 * g_u;"),
+    ("path: obs adjoint sign", "lam_th = g_th - sin(th) * dobs[0] + cos(th) * dobs[1];", "lam_th = g_th + sin(th) * dobs[0] + cos(th) * dobs[1];"),
+    ("path: thd obs adjoint dropped", "lam_thd = g_thd + dobs[2];", "lam_thd = g_thd;"),
+    ("path: ls grad", "dhead[1] = clamped ? 0.0 : g_z * sigma * eps;", "dhead[1] = clamped ? 0.0 : g_z * eps;"),
+    ("path: score term kept", "for (size_t i = 0; i < tn; ++i) h->adv[i] = 0.0;", ";"),
+    ("philox: round constant", "0xD2511F53", "0xD2511F57"),
+    ("u01: shift", "return (float)(x >> 8) * 0x1p-24f;", "return (float)(x >> 9) * 0x1p-23f;"),
+
+    ("philox: key bump", "k1 += 0xBB67AE85u;", "k1 += 0xBB67AE86u;"),
+    ("philox: 9 rounds", "round < 10;", "round < 9;"),
+    ("draw4: domain/index swapped", "uint32_t ctr[4] = { index, (uint32_t)t, (uint32_t)(t >> 32), domain };", "uint32_t ctr[4] = { domain, (uint32_t)t, (uint32_t)(t >> 32), index };"),
+    ("draw4: key halves swapped", "uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };", "uint32_t key[2] = { (uint32_t)(seed >> 32), (uint32_t)seed };"),
+    ("u01_plus: no +1", "return (float)((x >> 8) + 1u) * 0x1p-24f;", "return (float)((x >> 8)) * 0x1p-24f;"),
+    ("bounded: modulo", "return (uint32_t)(((uint64_t)x * n) >> 32);", "return x % n;"),
+    ("exp: coefficient 1/4!", "p = fmaf(p, f, 0x1.555556p-5f);", "p = fmaf(p, f, 0x1.555556p-4f);"),
+    ("exp: ln2 low dropped", "f = fmaf(-n, 0x1.0bfbe8p-15f, f);", "f = f;"),
+    ("log: 1/3 coefficient", "p = fmaf(p, s2, 0x1.555556p-2f);", "p = fmaf(p, s2, 0x1.555556p-3f);"),
+    ("log: sqrt2 split dropped", "if (m > 0x1.6a09e6p+0f) { m = m * 0.5f; e += 1; }", ";"),
+    ("sincos: quadrant 1", "else if (qi == 1) { *s = cp;  *c = -sp; }", "else if (qi == 1) { *s = cp;  *c = sp; }"),
+    ("cos2pi: quadrant 3", "    return sin_poly(a);\n", "    return -sin_poly(a);\n"),
+    ("tanh: series coefficient", "p = fmaf(p, a2, 0x1.111112p-3f);", "p = fmaf(p, a2, 0x1.111112p-4f);"),
+    ("tanh: large branch", "float e = orc_exp(-2.0f * a);", "float e = orc_exp(-1.0f * a);"),
+    ("bf16: truncation", "u += 0x7fffu + ((u >> 16) & 1u);", "u += 0;"),
+    ("bf16: round half up", "u += 0x7fffu + ((u >> 16) & 1u);", "u += 0x8000u;"),
+    ("wrap: no correction", "if (th >= pi_f)      th = (th - 0x1.921fb6p+2f) - (-0x1.777a5cp-23f);", "if (th > pi_f)      th = (th - 0x1.921fb6p+2f) - (-0x1.777a5cp-23f);"),
+    ("pend: reward after step", "float cost = th * th;", "float cost = 0.5f * th * th;"),
+    ("pend: time limit", "if (si[0] >= h->env.max_steps) {", "if (si[0] > h->env.max_steps) {"),
+    ("pend: lower torque clip", "if (u < -2.0f) u = -2.0f;", "if (u < -1.0f) u = -1.0f;"),
+    ("pend: lower vel clip", "if (nthd < -8.0f) nthd = -8.0f;", "if (nthd < -7.0f) nthd = -7.0f;"),
+    ("pend: dt velocity", "float nthd = fmaf(acc, 0x1.99999ap-5f, thd);", "float nthd = fmaf(acc, 0x1.99999ap-4f, thd);"),
+    ("maze: right/left swapped", "else if (a == 1) nc = col + 1;", "else if (a == 1) nc = col - 1;"),
+    ("maze: walls ignored", "&& !maze_is_wall(w, nr * C + nc)) cell", "&& 1) cell"),
+    ("maze: goal reward", "if (cell == R * C - 1) { *r = 1.0f; *done = 1; }", "if (cell == R * C - 1) { *r = 1.0f; *done = 0; }"),
+    ("maze: reset keeps position", "if (*done) { si[0] = 0; si[1] = 0; }", "if (*done) { si[1] = 0; }"),
+    ("maze: start not forced free", "w[0] &= ~1u;", ";"),
+    ("maze: bfs 3 neighbours", "for (int i = 0; i < 4; ++i) {\n            int d = nb[i];", "for (int i = 0; i < 3; ++i) {\n            int d = nb[i];"),
+    ("catch: lower clamp", "if (px < 0) px = 0;", "if (px < 0) px = 1;"),
+    ("catch: paddle row in obs", "x[(h->env.rows - 1) * h->env.cols + si[2]] = 1.0f;", "x[(h->env.rows - 2) * h->env.cols + si[2]] = 1.0f;"),
+    ("init: bias nonzero / head fan", "float u = orc_u01(w4[e & 3]);", "float u = orc_u01(w4[(e + 1) & 3]);"),
+    ("fwd32: bias dropped", "for (int j = 0; j < N; ++j) y[j] = bias[j];", "for (int j = 0; j < N; ++j) y[j] = 0.0f;"),
+    ("fwd32: bf16 weight round missing", "if (bf && !weights_rounded) w = orc_bf16_round(w);", ";"),
+    ("rollout: value is head 0", "h->tr_val[tb] = head[NH - 1];", "h->tr_val[tb] = head[0];"),
+    ("rollout: action draw word", "orc_sample_categorical(head, h->A, orc_u01(wa[0]));", "orc_sample_categorical(head, h->A, orc_u01(wa[1]));"),
+    ("rollout: gstep not advanced", "h->gstep += (uint64_t)T;", ";"),
+    ("rollout: reset draw = action draw", "draw4(h->seed, (uint32_t)b, gt, DOM_RESET, wr);", "draw4(h->seed, (uint32_t)b, gt, DOM_ACTION, wr);"),
+    ("returns: bootstrap dropped", "double G = (double)val[(size_t)T * B + b];", "double G = 0.0;"),
+    ("loss: policy term value", "Lp += -A_ * lp[a];", "Lp += A_ * lp[a];"),
+    ("loss: value term coefficient", "Lv += cv * (G_ - V) * (G_ - V);", "Lv += 0.5 * cv * (G_ - V) * (G_ - V);"),
+    ("loss: gauss entropy const", "Le += -beta * (lsc + 0.5 * log(2.0 * ORC_PI * ORC_E));", "Le += -beta * (lsc + 0.5 * log(2.0 * ORC_PI));"),
+    ("loss: gauss logp const", "Lp += -A_ * (-0.5 * eps * eps - lsc - 0.5 * log(2.0 * ORC_PI));", "Lp += -A_ * (-0.5 * eps * eps - lsc);"),
+    ("loss: total without entropy", "h->loss[0] = h->loss[1] + h->loss[2] + h->loss[3];\n    for (size_t i", "h->loss[0] = h->loss[1] + h->loss[2];\n    for (size_t i"),
+    ("adam: bc1", "double bc1 = 1.0 - pow(beta1, (double)t),", "double bc1 = 1.0,"),
+    ("adam: v coefficient", "v[i] = beta2 * v[i] + (1.0 - beta2) * gi * gi;", "v[i] = beta2 * v[i] + (1.0 - beta2) * gi;"),
+    ("learn: adam_t not advanced", "orc_loss_and_grad(h);\n    h->adam_t += 1;\n    orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t,\n             (double)h->net.lr, (double)h->net.beta1, (double)h->net.beta2, (double)h->net.eps);\n    h->have_traj = 0;\n    return 0;\n}\n\n/* N updates", "orc_loss_and_grad(h);\n    h->adam_t += 0;\n    orc_adam((int64_t)h->P, h->theta, h->grad, h->m, h->v, h->adam_t + 1,\n             (double)h->net.lr, (double)h->net.beta1, (double)h->net.beta2, (double)h->net.eps);\n    h->have_traj = 0;\n    return 0;\n}\n\n/* N updates"),
+    ("vtrace: gaussian ratio clamp", "double lsc = ls < -5.0 ? -5.0 : (ls > 2.0 ? 2.0 : ls);\n    double eps = ((double)h->tr_z[tb] - mu) / exp(lsc);", "double lsc = ls;\n    double eps = ((double)h->tr_z[tb] - mu) / exp(lsc);"),
+    ("vtrace: ret without V", "h->ret[tb] = V + tail;", "h->ret[tb] = tail;"),
+    ("vtrace: done ignored", "double disc = h->tr_done[tb] ? 0.0 : gamma;\n            double V", "double disc = gamma;\n            double V"),
+    ("path: value/entropy dropped", "orc_pathwise_grad(h, g, NULL);", "for (size_t i = 0; i < h->P; ++i) g[i] = 0; orc_pathwise_grad(h, g, NULL);"),
+    ("path: reward theta term", "+ w * (-2.0 * th);", "+ w * (-1.0 * th);"),
+    ("path: u cost term", "double g_u = g_pre * dt * 3.0 + w * (-2.0 * c_u * u);", "double g_u = g_pre * dt * 3.0;"),
+    ("path: loss value", "h->loss[1] = -rs / (double)tn;", "h->loss[1] = rs / (double)tn;"),
+]
+
+
+def prepare(work):
+    """a private copy of what the pins import: oracle/, tests/, the package's Python files"""
+    shutil.copytree(os.path.join(ROOT, "oracle"), os.path.join(work, "oracle"),
+                    ignore=shutil.ignore_patterns("*.so", "__pycache__"))
+    shutil.copytree(os.path.join(ROOT, "tests"), os.path.join(work, "tests"), ignore=shutil.ignore_patterns("__pycache__"))
+    os.makedirs(os.path.join(work, "paper_2104_06272_amd"))
+    for f in os.listdir(os.path.join(ROOT, "paper_2104_06272_amd")):
+        if f.endswith(".py"):
+            shutil.copy(os.path.join(ROOT, "paper_2104_06272_amd", f), os.path.join(work, "paper_2104_06272_amd", f))
+
+
+def run_one(work, source, old, new):
+    """True if the pins fail on the mutated copy (the mutation is caught)"""
+    assert source.count(old) == 1, f"mutation text must occur exactly once: {old!r}"
+    with open(os.path.join(work, "oracle", "anakin_oracle.c"), "w") as f:
+        f.write(source.replace(old, new))
+    so = os.path.join(work, "oracle", "liboracle.so")
+    if os.path.exists(so):
+        os.remove(so)
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "-x", "-q", "-p", "no:cacheprovider"],
+                       cwd=work, capture_output=True, text=True)
+    return r.returncode != 0, r.stdout
+
+
+def run(names=None):
+    """runs the named mutations (all when None); returns the names of those that survive"""
+    with open(os.path.join(ROOT, "oracle", "anakin_oracle.c")) as f:
+        source = f.read()
+    survivors = []
+    with tempfile.TemporaryDirectory() as work:
+        prepare(work)
+        for name, old, new in MUTATIONS:
+            if names is not None and name not in names:
+                continue
+            caught, out = run_one(work, source, old, new)
+            where = [l for l in out.splitlines() if "Error" in l or l.startswith("FAILED")]
+            print(("caught:   " if caught else "SURVIVED: ") + name + ("   <- " + where[0][:100] if caught and where else ""), flush=True)
+            if not caught:
+                survivors.append(name)
+    return survivors
+
+
+if __name__ == "__main__":
+    words = sys.argv[1:]
+    chosen = None if not words else [n for n, _, _ in MUTATIONS if any(w in n for w in words)]
+    left = run(chosen)
+    print("survivors:", left)
+    sys.exit(1 if left else 0)

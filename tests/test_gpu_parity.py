@@ -101,6 +101,81 @@ def test_lockstep(gpu, orc, case):
     g.close()
 
 
+@pytest.mark.parametrize("hidden,B", [([64, 64], 64), ([256, 256], 128)])
+@pytest.mark.parametrize("shift", [3.5, -7.5, 1.97])
+def test_pendulum_log_sigma_at_and_outside_its_clamp(gpu, orc, hidden, B, shift):
+    """log_sigma is clamped to [-5, 2] in the sampler, and a clamped log_sigma passes no gradient (neither from the
+    score function nor from the entropy bonus).  With the head's bias pushed above or below the clamp every sample
+    is clamped; with the bias just under the upper end some are and some are not.  Unrolls bit-exact, updates within
+    tolerance, on the vector-ALU head pass (64-wide net) and on the head pass folded into the resident products
+    (256-wide net)."""
+    cfg = variant("pendulum_8192", hidden=hidden, B=B, T=16, max_steps=11)
+    say(f"[log_sigma clamp] hidden={hidden} B={B} bias={shift}")
+    g = gpu.Anakin(cfg, seed=31); o = orc.Oracle(cfg, seed=31)
+    theta = g.get_params()
+    theta[-2] = shift                              # heads: mu, log_sigma, value; their biases are the last three entries
+    g.set_params(theta)
+    for u in range(2):
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout(); o.rollout()
+        tr = PT.assert_rollout_equal(g, o, "pendulum")
+        ls = tr["head"][:-1, :, 1]
+        if shift > 2.5:
+            assert (ls > 2.0).all()
+        elif shift < -5.5:
+            assert (ls < -5.0).all()
+        else:
+            assert (ls > 2.0).any() and (ls < 2.0).any()
+        g.learn(); o.learn()
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32)
+        if abs(shift) > 2.5:
+            nh, hl = 3, hidden[-1]
+            wh = g.get_grads()[-(nh + hl * nh):-nh].reshape(hl, nh)
+            assert np.abs(wh[:, 1]).max() == 0.0 and g.get_grads()[-2] == 0.0, "a clamped log_sigma passed a gradient"
+        say(f"  update {u}: grad rel {e_g:.2e}, param rel {e_p:.2e}")
+    g.close()
+
+
+def test_pendulum_states_on_the_wrap_boundary(gpu, orc):
+    """The stored angle lies in [-pi_f, pi_f): the env step wraps an angle of exactly pi_f (binary32 pi) and leaves
+    the value just below it alone.  8192 envs start one binary32 step apart around the angle from which a step
+    with velocity 1 and (nearly) no torque lands on pi_f; the policy's noise (sigma = e^-5) spreads the landing points
+    over a few hundred steps, so several envs land exactly on pi_f, several just below and just above.  One step,
+    every env bit-exact against the oracle."""
+    cfg = variant("pendulum_8192", hidden=[64, 64], B=8192, T=1)
+    say("[wrap boundary] pendulum B=8192 T=1")
+    g = gpu.Anakin(cfg, seed=5); o = orc.Oracle(cfg, seed=5)
+    theta = np.zeros(g.P, np.float32)
+    theta[-2] = -7.5                                  # log_sigma below its clamp: sigma = e^-5; mu = 0, value = 0
+    g.set_params(theta); o.theta[:] = theta
+    pi_f = np.float32(np.pi)
+    # the starting angle whose torque-free step lands nearest pi_f, found with the oracle's own env step (pinned on the CPU)
+    lo, hi = int(np.float32(3.0).view(np.uint32)), int(np.float32(3.14).view(np.uint32))
+
+    def lands_past(bits):
+        o.state_i[0, 0] = 0; o.state_f[0] = (np.uint32(bits).view(np.float32), 1.0)
+        o.env_step(0, action_f=0.0, t=0)
+        return o.state_f[0, 0] < 0
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        lo, hi = (lo, mid) if lands_past(mid) else (mid, hi)
+    si = np.zeros((g.B, 4), np.int32)
+    sf = np.empty((g.B, 2), np.float32)
+    sf[:, 0] = (np.uint32(hi) + (np.arange(g.B, dtype=np.int64) % 1024 - 512).astype(np.int64)).astype(np.uint32).view(np.float32)
+    sf[:, 1] = 1.0
+    g.set_env_state(si, sf); o.state_i[:] = si; o.state_f[:] = sf
+    g.rollout(); o.rollout()
+    PT.assert_rollout_equal(g, o, "pendulum")
+    PT.assert_final_state_equal(g, o, "pendulum")
+    th = o.state_f[:, 0]
+    wrapped_pi = np.float32(np.float32(pi_f - np.float32(2) * pi_f) - np.float32(float.fromhex("-0x1.777a5cp-23")))
+    assert (th >= -pi_f).all() and (th < pi_f).all()
+    assert (th == np.nextafter(pi_f, np.float32(0))).sum() >= 1, "no env landed just below pi_f"
+    assert (th == wrapped_pi).sum() >= 1, "no env landed exactly on pi_f"
+    say(f"  {int((th == wrapped_pi).sum())} envs landed on pi_f, {int((th == np.nextafter(pi_f, np.float32(0))).sum())} just below")
+    g.close()
+
+
 def test_catch_small_100_updates_lockstep(gpu, orc):
     """The small Catch workload for its full 100 updates, parameter-synchronised."""
     cfg = W.get("catch_small")

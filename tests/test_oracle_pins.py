@@ -265,6 +265,32 @@ def test_pendulum_fixed_point_and_episode_length(orc):
     assert -math.pi - 1e-6 <= th <= math.pi + 1e-6 and -1 <= thd < 1
 
 
+def test_pendulum_angle_wrap_boundary(orc):
+    """The stored angle lies in [-pi_f, pi_f) with pi_f the binary32 pi (R-10): walking the starting angle one
+    binary32 step at a time takes the angle before wrapping through every value around pi_f, pi_f itself included,
+    and the half-open interval must hold at each (pi_f wraps, the value just below it does not)."""
+    o = orc.Oracle(tiny("pendulum", B=1, T=2, max_steps=200), seed=1)
+    pi_f = np.float32(math.pi)
+
+    def after_step(bits):
+        o.state_i[0, 0] = 0
+        o.state_f[0] = (np.uint32(bits).view(np.float32), 1.0)
+        o.env_step(0, action_f=0.0, t=0)
+        return o.state_f[0, 0]
+
+    lo, hi = int(np.float32(3.0).view(np.uint32)), int(np.float32(3.14).view(np.uint32))   # stays / wraps
+    assert after_step(lo) > 0 > after_step(hi)
+    while hi - lo > 1:                                       # the first starting angle whose step wraps
+        mid = (lo + hi) // 2
+        lo, hi = (mid, hi) if after_step(mid) > 0 else (lo, mid)
+    out = [after_step(hi + k) for k in range(-400, 400)]
+    out = np.array(out, np.float32)
+    assert (out >= -pi_f).all() and (out < pi_f).all()
+    assert (out > 3.14).any() and (out < -3.14).any()       # both sides of the wrap were visited
+    up = out[out > 0]
+    assert up.max() == np.nextafter(pi_f, np.float32(0))     # the last value that stays is the one just below pi_f
+
+
 def test_pendulum_init_distribution_and_obs(orc):
     B = 4000
     o = orc.Oracle(tiny("pendulum", B=B, T=2), seed=6)
@@ -273,6 +299,9 @@ def test_pendulum_init_distribution_and_obs(orc):
     assert abs(th.mean()) < 4 * (2 * math.pi / math.sqrt(12)) / math.sqrt(B)
     assert abs(th.var() - (2 * math.pi) ** 2 / 12) < 0.25
     assert thd.min() >= -1 and thd.max() < 1 and abs(thd.mean()) < 4 * (2 / math.sqrt(12)) / math.sqrt(B)
+    # the whole of U(-1, 1) and of U(-pi, pi): variance of the uniform law and both ends reached
+    assert abs(thd.var() - 4 / 12) < 0.03 and thd.min() < -0.99 and thd.max() > 0.99
+    assert th.min() < -0.99 * math.pi and th.max() > 0.99 * math.pi
     for b in range(0, B, 131):
         x = o.observe(b).astype(np.float64)
         assert abs(x[0] - math.cos(th[b])) < 3e-7 and abs(x[1] - math.sin(th[b])) < 3e-7 and x[2] == thd[b]
@@ -478,6 +507,10 @@ def test_categorical_sampler(orc):
     a = np.array([orc.sample_categorical([0.7, 0.7, 0.7], u) for u in us])
     assert np.mean(a == np.floor(3 * us.astype(np.float64))) > 0.9995
     assert np.all(np.diff(a) >= 0) and set(a) == {0, 1, 2}
+    # ties: "the first index whose running sum EXCEEDS u * total" -- with equal logits the running sums are exactly
+    # 1, 2, ..., so u = k / A sits on a boundary and belongs to the upper action
+    assert [orc.sample_categorical([0.0, 0.0], u) for u in (0.0, 0.25, 0.5, 0.75)] == [0, 0, 1, 1]
+    assert [orc.sample_categorical([1.5] * 4, u) for u in (0.0, 0.25, 0.5, 0.75, 1 - 2.0 ** -24)] == [0, 1, 2, 3, 3]
     # a dominant logit wins wherever it sits (the others have mass e^-40, below the grid's smallest u > 0)
     for i in range(3):
         lg = [0.0, 0.0, 0.0]; lg[i] = 40.0
@@ -656,6 +689,39 @@ def test_gradient_vs_finite_differences(orc, kind):
     assert np.abs(g - fd).max() < 1e-5 * np.abs(fd).max() + 1e-7
 
 
+@pytest.mark.parametrize("shift", [4.0, -8.0])
+def test_gaussian_gradient_outside_the_log_sigma_clamp(orc, shift):
+    """R-19: log_sigma is clamped to [-5, 2], and a clamped log_sigma passes no gradient.  With the head's bias pushed
+    far outside the clamp every sample is clamped: the objective (float64, written out by the test) then does not
+    depend on that head at all, and central differences of it say so for every parameter."""
+    cfg = tiny("pendulum", hidden=(5, 4), B=3, T=5, max_steps=3)
+    o = orc.Oracle(cfg, seed=17)
+    rng = np.random.default_rng(5)
+    o.theta[:] += rng.standard_normal(o.P).astype(np.float32) * 0.2
+    o.theta[-2] = shift                                   # bias of log_sigma (heads: mu, log_sigma, value)
+    o.rollout()
+    assert (o.tr_head[:-1, :, 1] > 2.5).all() if shift > 0 else (o.tr_head[:-1, :, 1] < -5.5).all()
+    ret, adv = orc.returns(o.tr_reward, o.tr_done, o.tr_value, cfg["net"]["gamma"], cfg["net"]["lambda"])
+    o.ret[:] = ret; o.adv[:] = adv + rng.standard_normal(adv.shape)
+    o.loss_and_grad()
+    T, B = o.T, o.B
+    obs = np.array([[math.cos(o.tr_state_f[t, b, 0]), math.sin(o.tr_state_f[t, b, 0]), o.tr_state_f[t, b, 1]]
+                    for t in range(T) for b in range(B)], np.float64)
+    th0 = o.theta.astype(np.float64)
+    assert np.allclose(o.loss, _np_surrogate(o, th0, obs, "gauss"), rtol=1e-6, atol=1e-7)
+    h = 1e-5
+    fd = np.zeros(o.P)
+    for i in range(o.P):
+        tp, tm = th0.copy(), th0.copy()
+        tp[i] += h; tm[i] -= h
+        fd[i] = (_np_surrogate(o, tp, obs, "gauss")[0] - _np_surrogate(o, tm, obs, "gauss")[0]) / (2 * h)
+    g = o.grad.astype(np.float64)
+    Wh = slice(o.P - 3 - 4 * 3, o.P - 3)
+    assert np.abs(g[Wh].reshape(4, 3)[:, 1]).max() == 0.0 and g[-2] == 0.0      # the clamped head's column and bias
+    assert np.abs(fd[Wh].reshape(4, 3)[:, 1]).max() < 1e-9 and abs(fd[-2]) < 1e-9
+    assert np.linalg.norm(g) > 1e-3 and np.linalg.norm(g - fd) / np.linalg.norm(fd) < 1e-5
+
+
 def test_head_gradient_identities(orc):
     cfg = tiny("catch", hidden=(4,), B=4, T=3)
     o = orc.Oracle(cfg, seed=3)
@@ -802,6 +868,65 @@ def test_n_updates_sequential_is_two_hand_applied_steps(orc, kind):
 
 
 # --------------------------------------------------------------------------- off-policy update, decoupled step
+def test_maze_random_walk_against_the_rule(orc):
+    """R-14 / R-15 written out by the test on its own copy of the wall bits: a move into a wall or off the grid
+    leaves the agent where it is, any other move takes it there; the agent is never on a wall."""
+    o = orc.Oracle(tiny("maze", hidden=(8,), B=6, T=2, max_steps=10 ** 6), seed=21)
+    rng = np.random.default_rng(9)
+    step = {0: (-1, 0), 1: (0, 1), 2: (1, 0), 3: (0, -1)}
+    blocked = moved = 0
+    for b in range(6):
+        w = _walls(o, b)
+        r_, c_ = 0, 0
+        for i in range(600):
+            a = int(rng.integers(4))
+            nr, nc = r_ + step[a][0], c_ + step[a][1]
+            ok = 0 <= nr < 16 and 0 <= nc < 16 and not w[nr, nc]
+            blocked += (0 <= nr < 16 and 0 <= nc < 16 and bool(w[nr, nc])); moved += ok
+            if ok:
+                r_, c_ = nr, nc
+            r, done = o.env_step(b, action=a, t=i)
+            if (r_, c_) == (15, 15):
+                assert done == 1 and r == 1.0 and o.state_i[b, 0] == 0
+                r_, c_ = 0, 0
+            else:
+                assert done == 0 and o.state_i[b, 0] == r_ * 16 + c_ and not w[r_, c_]
+    assert blocked > 100 and moved > 1000                  # walls were hit, and not every move was blocked
+
+
+@pytest.mark.parametrize("kind", ["catch", "pendulum"])
+def test_unroll_draws_follow_the_counter_layout(orc, kind):
+    """R-1 / R-21 / R-22: the action of env b at global step g comes from words 0 (and 1) of the draw
+    (index b, t = g, domain 0), the state after an episode end from the draw (b, g, domain 1); the test makes the
+    draws itself through the Philox routine pinned above and replays sampling and reset from the stored head outputs."""
+    cfg = tiny(kind, hidden=(6, 6), B=5, T=9, max_steps=4)
+    seed = 77
+    o = orc.Oracle(cfg, seed=seed)
+    L = orc.lib()
+    o.rollout()                                            # second unroll below: global step numbers 9..17
+    g0 = o.global_step
+    o.rollout()
+    ends = 0
+    for t in range(o.T):
+        for b in range(o.B):
+            wa, wr = orc.draw(seed, b, g0 + t, 0), orc.draw(seed, b, g0 + t, 1)
+            head = o.tr_head[t, b]
+            if kind == "catch":
+                assert o.tr_action[t, b] == orc.sample_categorical(head[:3], L.orc_u01(int(wa[0])))
+                if o.tr_done[t, b]:
+                    ends += 1
+                    assert tuple(o.tr_state_i[t + 1, b, :3]) == (int(L.orc_bounded(int(wr[0]), 3)), 0, 1)
+            else:
+                e, z, a = orc.sample_gaussian(head[0], head[1], wa[0], wa[1])
+                assert (o.tr_eps[t, b], o.tr_z[t, b], o.tr_action_f[t, b]) == (e, z, a)
+                if o.tr_done[t, b]:
+                    ends += 1
+                    th = np.float32(-math.pi) + np.float32(2 * math.pi) * np.float32(L.orc_u01(int(wr[0])))
+                    thd = -1.0 + 2.0 * L.orc_u01(int(wr[1]))
+                    assert abs(float(o.tr_state_f[t + 1, b, 0]) - float(th)) < 1e-6 and o.tr_state_f[t + 1, b, 1] == np.float32(thd)
+    assert ends >= o.B
+
+
 def _np_log_prob(head, kind, act, z):
     """log-probability of the stored action under head outputs [..., NH] (binary64, written out here)."""
     head = np.asarray(head, np.float64)
@@ -813,17 +938,23 @@ def _np_log_prob(head, kind, act, z):
     return np.take_along_axis(lg, act[..., None], -1)[..., 0] - lse
 
 
-@pytest.mark.parametrize("kind", ["catch", "pendulum"])
+@pytest.mark.parametrize("kind", ["catch", "pendulum", "pendulum-clamped"])
 def test_vtrace_targets_vs_definition(orc, kind):
     """The backward recursion against V-trace written as its defining sum (Espeholt et al. 2018, eq. 1):
     v_s = V(x_s) + sum_{t>=s} (prod_{i=s}^{t-1} disc_i c_i) delta_t, delta_t = rho_t (r_t + disc_t V(x_{t+1}) - V(x_t)),
     with truncation levels below and above the ratios that occur, plus the advantage rho_s (r_s + disc_s v_{s+1} - V(x_s))."""
+    clamped = kind == "pendulum-clamped"          # log_sigma above its clamp (R-19) in most samples, inside in a few
+    kind = kind.split("-")[0]
     cfg = tiny(kind, hidden=(8, 8), B=6, T=12, lam=0.9, max_steps=7)
     o = orc.Oracle(cfg, seed=3)
+    if clamped:
+        o.theta[-2] = 3.0
     for _ in range(2):
         o.rollout()
     rng = np.random.default_rng(0)
     o.theta[:] = o.theta + rng.normal(0, 0.08, o.P).astype(np.float32)      # the learner has moved on
+    if clamped:
+        assert (o.tr_head[..., 1] > 2.1).mean() > 0.5 and (o.tr_head[..., 1] < 1.9).any()
     rho_bar, c_bar = 1.05, 0.9
     o.vtrace_targets(rho_bar, c_bar)
     T, B = o.T, o.B
@@ -838,7 +969,10 @@ def test_vtrace_targets_vs_definition(orc, kind):
         assert np.abs(o.cur_head[t, b] - h32).max() <= 1e-5 * max(1.0, np.abs(h32).max())
     V = o.cur_head[..., -1]
     w = np.exp(_np_log_prob(o.cur_head[:T], kind, o.tr_action, o.tr_z) - _np_log_prob(o.tr_head[:T], kind, o.tr_action, o.tr_z))
-    assert (w > rho_bar).any() and (w < c_bar).any() and ((w > c_bar) & (w < rho_bar)).any()   # every branch of both min()
+    if not clamped:
+        assert (w > rho_bar).any() and (w < c_bar).any() and ((w > c_bar) & (w < rho_bar)).any()   # every branch of both min()
+    else:
+        assert (o.cur_head[..., 1] > 2.1).mean() > 0.5 and np.abs(w - 1).max() > 1e-3
     rho = np.minimum(rho_bar, w); c = lam * np.minimum(c_bar, w)
     assert np.allclose(o.rho, rho, rtol=1e-12, atol=0)
     disc = gamma * (1.0 - o.tr_done.astype(np.float64))
