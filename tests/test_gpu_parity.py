@@ -176,6 +176,57 @@ def test_pendulum_states_on_the_wrap_boundary(gpu, orc):
     g.close()
 
 
+def test_pendulum_velocity_clip_and_large_costs(gpu, orc):
+    """Envs started at the edge of the state space: angular velocities at and next to the clip (+-8) with angles that
+    push them further out, so the clip is active in most steps and the reward takes its largest magnitudes; two
+    updates in lockstep."""
+    cfg = variant("pendulum_8192", hidden=[64, 64], B=256, T=8)
+    say("[velocity clip] pendulum B=256 T=8")
+    g = gpu.Anakin(cfg, seed=9); o = orc.Oracle(cfg, seed=9)
+    rng = np.random.default_rng(2)
+    si = np.zeros((g.B, 4), np.int32)
+    sf = np.empty((g.B, 2), np.float32)
+    sign = np.where(np.arange(g.B) % 2 == 0, 1.0, -1.0).astype(np.float32)
+    sf[:, 0] = sign * rng.uniform(0.2, 2.9, g.B).astype(np.float32)            # sin(theta) has the sign of the velocity
+    sf[:, 1] = sign * rng.choice(np.float32([8.0, 7.999999, 7.9, 7.5]), g.B)
+    g.set_env_state(si, sf); o.state_i[:] = si; o.state_f[:] = sf
+    clipped = 0
+    for u in range(2):
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout(); o.rollout()
+        PT.assert_rollout_equal(g, o, "pendulum")
+        PT.assert_final_state_equal(g, o, "pendulum")
+        clipped += int((np.abs(o.tr_state_f[1:, :, 1]) == 8.0).sum())
+        assert o.tr_reward.min() < -10.0
+        g.learn(); o.learn()
+        e_g, e_p = PT.assert_learn_close(g, o, TOL_F32)
+        say(f"  update {u}: grad rel {e_g:.2e}, param rel {e_p:.2e}")
+    assert clipped > g.B                                  # the clip was active in many steps
+    g.close()
+
+
+@pytest.mark.parametrize("dtype,hidden", [("fp32", [64, 64]), ("bf16", [64, 64, 32])])
+def test_maze_goal_and_step_cap_inside_the_unroll(gpu, orc, dtype, hidden):
+    """Envs placed next to the goal with 250 of their 256 steps used: within one unroll many reach the goal (+1,
+    episode end, back to the start) and the rest run into the step cap; both kinds of episode end, the restart
+    from the start cell and the step counter next to its limit, bit-exact, then the update."""
+    cfg = variant("maze_16384", hidden=hidden, B=128, T=12, dtype=dtype)
+    say(f"[maze goal and cap] {dtype} hidden={hidden}")
+    g = gpu.Anakin(cfg, seed=4); o = orc.Oracle(cfg, seed=4)
+    PT.assert_same_init(g, o, "maze")
+    _place_next_to_goal(g, o)           # a free neighbour of the goal (it is reachable, so one of its two neighbours is free)
+    PT.sync_oracle_from_gpu(g, o)
+    g.rollout(); o.rollout()
+    PT.assert_rollout_equal(g, o, "maze")
+    PT.assert_final_state_equal(g, o, "maze")
+    goals = int((o.tr_reward == 1.0).sum()); caps = int(o.tr_done.sum()) - goals
+    assert goals >= 10 and caps >= 10, (goals, caps)
+    g.learn(); o.learn()
+    e_g, e_p = PT.assert_learn_close(g, o, TOL_F32 if dtype == "fp32" else TOL_BF16)
+    say(f"  {goals} goals, {caps} step caps; grad rel {e_g:.2e}, param rel {e_p:.2e}")
+    g.close()
+
+
 def test_catch_small_100_updates_lockstep(gpu, orc):
     """The small Catch workload for its full 100 updates, parameter-synchronised."""
     cfg = W.get("catch_small")
@@ -326,7 +377,7 @@ BF16_CASES = {
 }
 
 
-def _forced_lockstep(gpu, orc, cfg, seed, updates, sel=None, learn=True):
+def _forced_lockstep(gpu, orc, cfg, seed, updates, sel=None, learn=True, prepare=None):
     """Logit-forced protocol for the bf16 matrix-core acting path: the accumulation order inside the bf16
     MFMA is the hardware's, so (1) the GPU's head outputs are checked against the oracle's own sequential
     forward within the bf16 tolerance, (2) the oracle samples from the GPU's head outputs with its own
@@ -335,9 +386,10 @@ def _forced_lockstep(gpu, orc, cfg, seed, updates, sel=None, learn=True):
     kind = cfg["env"]["kind"]
     g = gpu.Anakin(cfg, seed=seed); o = orc.Oracle(cfg, seed=seed)
     PT.assert_same_init(g, o, kind)
+    if prepare is not None:
+        prepare(g, o)                            # e.g. places the envs of both sides in chosen states
     for u in range(updates):
         PT.sync_oracle_from_gpu(g, o)
-        keep_i, keep_f = o.state_i.copy(), o.state_f.copy()
         g.rollout()
         tr = g.trajectory()
         o.rollout(forced_head=tr["head"], sel=sel)
@@ -362,6 +414,36 @@ def test_bf16_matrix_core_path(gpu, orc, case):
     cfg, seed, updates = BF16_CASES[case]
     say(f"[bf16] {case} seed={seed} B={cfg['B']} T={cfg['T']} hidden={cfg['net']['hidden']}")
     _forced_lockstep(gpu, orc, cfg, seed, updates)
+
+
+def _place_next_to_goal(g, o):
+    """every env on a free neighbour of the goal with 250 - (b % 3) of its 256 steps used (16 x 16 maze)"""
+    walls = np.unpackbits(o.walls.view(np.uint8), axis=1, bitorder="little").reshape(g.B, 16, 16).astype(bool)
+    si = np.zeros((g.B, 4), np.int32)
+    _, sf = g.get_env_state()
+    for b in range(g.B):
+        si[b, 0] = 15 * 16 + 14 if not walls[b, 15, 14] else 14 * 16 + 15
+        assert not walls[b, si[b, 0] // 16, si[b, 0] % 16]
+        si[b, 1] = 250 - (b % 3)
+    g.set_env_state(si, sf); o.state_i[:] = si
+
+
+def test_bf16_matrix_core_goal_and_step_cap(gpu, orc):
+    """The matrix-core acting kernel keeps the maze state in registers and packs it on its own: goal arrivals, the
+    step cap next to its limit and the restart from the start cell inside one unroll, logit-forced, then the update."""
+    cfg = variant("maze_16384", hidden=[128, 128, 128], B=128, T=12)
+    say("[bf16 goal and cap] hidden=[128, 128, 128] B=128 T=12")
+    seen = {}
+
+    def prepare(g, o):
+        assert g.plan()["bf16_matrix_path"] == 1
+        _place_next_to_goal(g, o)
+        seen["o"] = o
+    _forced_lockstep(gpu, orc, cfg, 4, 1, prepare=prepare)
+    o = seen["o"]
+    goals = int((o.tr_reward == 1.0).sum()); caps = int(o.tr_done.sum()) - goals
+    say(f"  {goals} goals, {caps} step caps")
+    assert goals >= 10 and caps >= 10, (goals, caps)
 
 
 def _steady_state_update(gpu, orc, cfg, check_plan, n_head_envs):
