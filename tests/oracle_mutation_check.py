@@ -4,7 +4,7 @@ Each entry plants one plausible mistake -- a wrong sign, coefficient, index, rou
 in a COPY of oracle/anakin_oracle.c, rebuilds that copy and runs tests/test_oracle_pins.py on it: the pins must
 turn red.  A mutation that survives names a part of the oracle no pin holds in place.
 
-    python tests/oracle_mutation_check.py            # all mutations (about a quarter of an hour)
+    python tests/oracle_mutation_check.py -j 8       # all mutations, eight at a time (a few minutes)
     python tests/oracle_mutation_check.py vtrace     # those whose name contains a word
 
 tests/test_oracle_mutations.py runs a short selection of them with the CPU suite.
@@ -171,27 +171,40 @@ def run_one(work, source, old, new):
     return r.returncode != 0, r.stdout
 
 
-def run(names=None):
-    """runs the named mutations (all when None); returns the names of those that survive"""
-    with open(os.path.join(ROOT, "oracle", "anakin_oracle.c")) as f:
-        source = f.read()
-    survivors = []
+def _run_share(source, share):
+    """one worker: its own private copy, its share of the mutations in order"""
+    out = []
     with tempfile.TemporaryDirectory() as work:
         prepare(work)
-        for name, old, new in MUTATIONS:
-            if names is not None and name not in names:
-                continue
-            caught, out = run_one(work, source, old, new)
-            where = [l for l in out.splitlines() if "Error" in l or l.startswith("FAILED")]
+        for name, old, new in share:
+            caught, log = run_one(work, source, old, new)
+            where = [l for l in log.splitlines() if "Error" in l or l.startswith("FAILED")]
             print(("caught:   " if caught else "SURVIVED: ") + name + ("   <- " + where[0][:100] if caught and where else ""), flush=True)
-            if not caught:
-                survivors.append(name)
-    return survivors
+            out.append((name, caught))
+    return out
+
+
+def run(names=None, jobs=1):
+    """runs the named mutations (all when None) on `jobs` private copies side by side; returns the names of those
+    that survive"""
+    from concurrent.futures import ThreadPoolExecutor
+    with open(os.path.join(ROOT, "oracle", "anakin_oracle.c")) as f:
+        source = f.read()
+    todo = [m for m in MUTATIONS if names is None or m[0] in names]
+    jobs = max(1, min(jobs, len(todo)))
+    with ThreadPoolExecutor(jobs) as pool:
+        results = list(pool.map(lambda k: _run_share(source, todo[k::jobs]), range(jobs)))
+    return [name for share in results for name, caught in share if not caught]
 
 
 if __name__ == "__main__":
-    words = sys.argv[1:]
-    chosen = None if not words else [n for n, _, _ in MUTATIONS if any(w in n for w in words)]
-    left = run(chosen)
+    args = sys.argv[1:]
+    jobs = 1
+    if "-j" in args:
+        k = args.index("-j")
+        jobs = int(args[k + 1])
+        del args[k:k + 2]
+    chosen = None if not args else [n for n, _, _ in MUTATIONS if any(w in n for w in args)]
+    left = run(chosen, jobs)
     print("survivors:", left)
     sys.exit(1 if left else 0)

@@ -20,4 +20,4 @@ SELECTION = [
 def test_planted_mistakes_in_the_oracle_are_caught():
     names = {n for n, _, _ in M.MUTATIONS}
     assert set(SELECTION) <= names
-    assert M.run(SELECTION) == []
+    assert M.run(SELECTION, jobs=4) == []
