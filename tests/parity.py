@@ -245,3 +245,89 @@ def oracle_learn_parallel(o, workers=16):
     o.grad[:] = grad.astype(np.float32); o.loss[:] = loss
     o.adam_t = o.adam_t + 1
     O.adam(o.theta, o.grad, o.m, o.v, o.adam_t, f32(net["lr"]), f32(net["beta1"]), f32(net["beta2"]), f32(net["eps"]))
+
+
+def bf16_round_np(x):
+    """binary32 -> nearest bfloat16 (ties to even), as binary32; finite inputs"""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+def np_maze_backward_from_stored(cfg, theta, walls, pos, acts, head, action, adv, ret, t_chunk=2):
+    """The A2C objective's value and its gradient for a maze net, in binary64 with BLAS products, from a STORED
+    forward pass: hidden activations acts[l] [T][B][H_l], head outputs head [T][B][NH], actions, agent cells pos
+    [T][B] and wall bits walls [B][cells]; adv and ret [T][B] are constants.  Same objective and same backward rule
+    as the oracle's (mean over the T*B samples of -A log pi(a|s) + c_v (G - V)^2 - beta H; ReLU sides from the sign
+    of the stored activation; weights as the forward pass saw them, i.e. rounded to bfloat16 when dtype is bf16),
+    only arranged as matrix products over blocks of t_chunk time steps so that half a million samples take seconds.
+    It is checked against the oracle itself on small cases by the CPU suite, and stands in for it where the oracle
+    would need an hour.  Returns (loss[4], grad[P]) in binary64."""
+    net = cfg["net"]
+    hid = list(net["hidden"])
+    L = len(hid)
+    T, B = action.shape
+    cells = walls.shape[1]
+    D = 3 * cells
+    dims = [D] + hid
+    A = head.shape[2] - 1
+    NH = A + 1
+    beta, cv = float(np.float32(net["entropy_coef"])), float(np.float32(net["value_coef"]))
+    th = np.asarray(theta, np.float32)
+    bf = net.get("dtype", "fp32") == "bf16"
+    Ws, bs, off = [], [], 0
+    w_off, b_off = [], []
+    for l in range(L):
+        K, N = dims[l], dims[l + 1]
+        Wm = th[off:off + K * N]
+        Ws.append((bf16_round_np(Wm) if bf else Wm).astype(np.float64).reshape(K, N)); w_off.append(off); off += K * N
+        bs.append(th[off:off + N].astype(np.float64)); b_off.append(off); off += N
+    wh_off = off
+    Whm = th[off:off + hid[-1] * NH]
+    Wh = (bf16_round_np(Whm) if bf else Whm).astype(np.float64).reshape(hid[-1], NH); off += hid[-1] * NH
+    bh_off = off; off += NH
+    P = off
+    g = np.zeros(P)
+    n_all = T * B
+    wallsf = walls.astype(np.float64)                        # [B][cells]
+    S = np.zeros((B, hid[0]))                                # sum over time of dZ_1, per env
+    gW = [np.zeros((dims[l], dims[l + 1])) for l in range(L)]
+    gb = [np.zeros(dims[l + 1]) for l in range(L)]
+    gWh = np.zeros((hid[-1], NH)); gbh = np.zeros(NH)
+    Lp = Lv = Le = 0.0
+    for t0 in range(0, T, t_chunk):
+        t1 = min(T, t0 + t_chunk)
+        n = (t1 - t0) * B
+        hd = head[t0:t1].reshape(n, NH).astype(np.float64)
+        a = action[t0:t1].reshape(n).astype(np.int64)
+        A_ = adv[t0:t1].reshape(n).astype(np.float64); G_ = ret[t0:t1].reshape(n).astype(np.float64)
+        lg = hd[:, :A]
+        lp = lg - lg.max(1, keepdims=True)
+        lp = lp - np.log(np.exp(lp).sum(1, keepdims=True))
+        p = np.exp(lp)
+        H = -(p * lp).sum(1)
+        V = hd[:, A]
+        Lp += float((-A_ * lp[np.arange(n), a]).sum()); Lv += float((cv * (G_ - V) ** 2).sum()); Le += float((-beta * H).sum())
+        onehot = np.zeros((n, A)); onehot[np.arange(n), a] = 1.0
+        dhead = np.empty((n, NH))
+        dhead[:, :A] = (-A_[:, None] * (onehot - p) + beta * p * (lp + H[:, None])) / n_all
+        dhead[:, A] = -2.0 * cv * (G_ - V) / n_all
+        hs = [acts[l][t0:t1].reshape(n, hid[l]).astype(np.float64) for l in range(L)]
+        gWh += hs[-1].T @ dhead; gbh += dhead.sum(0)
+        dz = (hs[-1] > 0) * (dhead @ Wh.T)
+        for l in range(L - 1, 0, -1):
+            gW[l] += hs[l - 1].T @ dz; gb[l] += dz.sum(0)
+            dz = (hs[l - 1] > 0) * (dz @ Ws[l].T)
+        gb[0] += dz.sum(0)
+        S += dz.reshape(t1 - t0, B, hid[0]).sum(0)
+        oh = np.zeros((cells, n)); oh[pos[t0:t1].reshape(n), np.arange(n)] = 1.0
+        gW[0][cells:2 * cells] += oh @ dz
+    gW[0][:cells] = wallsf.T @ S
+    gW[0][2 * cells + cells - 1] = gb[0]                     # the goal plane has its one at the last cell, always
+    for l in range(L):
+        g[w_off[l]:w_off[l] + gW[l].size] = gW[l].ravel()
+        g[b_off[l]:b_off[l] + gb[l].size] = gb[l]
+    g[wh_off:wh_off + gWh.size] = gWh.ravel()
+    g[bh_off:bh_off + NH] = gbh
+    loss = np.array([Lp + Lv + Le, Lp, Lv, Le]) / n_all
+    return loss, g

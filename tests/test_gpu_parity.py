@@ -546,6 +546,58 @@ def test_full_size_maze_bf16_sampled_envs(gpu, orc):
     _forced_lockstep(gpu, orc, cfg, 0, 2, sel=sel, learn=False)
 
 
+def test_full_size_maze_bf16_update(gpu, orc):
+    """The update of the maze workload at its full size (B=16384, T=32, 768-512-512-512 bf16: 524288 samples), in
+    the launch shape the benchmark times.  The oracle would need an hour for it, so the reference is the same
+    objective and backward rule written as binary64 matrix products over the forward pass the GPU stored
+    (parity.np_maze_backward_from_stored, itself checked against the oracle on small cases by the CPU suite; the
+    stored forward pass is what test_full_size_maze_bf16_sampled_envs compares with the oracle): returns and
+    advantages by the oracle's routine, loss terms, every region of the gradient, then the Adam step replayed in
+    binary64 from the GPU's own gradient."""
+    from oracle import oracle as O
+    cfg = W.get("maze_16384")
+    net = cfg["net"]
+    f32 = lambda x: float(np.float32(x))
+    say("[full size] maze_16384 update against the binary64 backward pass over the stored forward pass")
+    g = gpu.Anakin(cfg, seed=2)
+    g.step()                                     # the compared update starts from non-initial parameters and moments
+    g.rollout()
+    theta0 = g.get_params()
+    m0, v0, t0 = g.get_opt_state()
+    tr = g.trajectory()
+    say("  trajectory on the host; update on the GPU ...")
+    g.learn()
+    assert g.metrics()["nonfinite"] == 0
+    ret, adv = O.returns(tr["reward"], tr["done"], tr["value"], f32(net["gamma"]), f32(net["lambda"]))
+    tr2 = g.trajectory()
+    scale = max(1.0, float(np.abs(ret).max()))
+    assert np.abs(tr2["ret"] - ret).max() <= 1e-5 * scale and np.abs(tr2["adv"] - adv).max() <= 1e-5 * scale
+    walls = np.unpackbits(g.get_walls().view(np.uint8), axis=1, bitorder="little").astype(bool)
+    pos = (tr["state_s0"][:-1] & 0xFFFF).astype(np.int64)
+    say("  binary64 backward pass on the host ...")
+    loss, ref = PT.np_maze_backward_from_stored(cfg, theta0, walls, pos, tr["act"], tr["head"][:-1], tr["action"], adv, ret)
+    m = g.metrics()
+    for k, i in (("loss", 0), ("policy_loss", 1), ("value_loss", 2), ("entropy_loss", 3)):
+        assert abs(m[k] - loss[i]) <= 1e-4 * max(abs(loss[i]), 1e-3 * np.abs(loss).max()) + 1e-7, (k, m[k], loss[i])
+    regions, P = PT.param_regions(cfg)
+    g_gpu = g.get_grads()
+    e_g = PT.rel(g_gpu, ref)
+    say(f"  gradient rel err {e_g:.2e}")
+    # both sides start from the same stored forward pass here, so what is left is the order of the sums and the
+    # bfloat16 rounding of dZ_l between the layers' products: a twentieth of the bf16 tolerance holds per region
+    worst = PT.assert_regions_close("gradient", g_gpu, ref, regions, TOL_BF16 / 20)
+    # Adam on its own: binary64 Adam (the oracle's routine) on the GPU's gradient from the state before the update
+    th_x, m_x, v_x = theta0.copy(), m0.astype(np.float64), v0.astype(np.float64)
+    O.adam(th_x, g_gpu, m_x, v_x, t0 + 1, f32(net["lr"]), f32(net["beta1"]), f32(net["beta2"]), f32(net["eps"]))
+    gm, gv, gt = g.get_opt_state()
+    assert gt == t0 + 1
+    th_gpu = g.get_params()
+    assert np.abs(th_gpu.astype(np.float64) - th_x).max() <= 2.0 ** -22 * np.abs(th_x).max() + 1e-4 * net["lr"]
+    assert np.abs(gm - m_x).max() <= 1e-6 * np.abs(m_x).max() and np.abs(gv - v_x).max() <= 1e-6 * np.abs(v_x).max()
+    say(f"  worst region {worst:.2e}; Adam step matches binary64 Adam on the same gradient")
+    g.close()
+
+
 def _fast_lr(cfg, lr=1e-2):
     cfg = copy.deepcopy(cfg)
     cfg["net"]["lr"] = lr          # one update moves the policy enough for importance ratios on both sides of 1

@@ -62,3 +62,50 @@ def test_threaded_oracle_update_equals_plain(orc, kind):
     assert PT.rel(b.grad, a.grad) < 1e-6
     assert PT.rel(b.theta, a.theta) < 1e-6 and a.adam_t == b.adam_t == 1
     assert np.allclose(a.m, b.m, rtol=1e-5, atol=1e-12)
+
+
+def _stored_forward(o):
+    """the oracle's own acting forward pass at every (t, b) of its stored unroll, as the arrays a GPU trajectory holds"""
+    T, B = o.T, o.B
+    hid = list(o.cfg["net"]["hidden"])
+    acts = [np.zeros((T, B, h), np.float32) for h in hid]
+    head = np.zeros((T, B, o.NH), np.float32)
+    for t in range(T):
+        for b in range(B):
+            hd, a = PT.oracle_forward_at(o, t, b)
+            head[t, b] = hd
+            off = 0
+            for l, h in enumerate(hid):
+                acts[l][t, b] = a[off:off + h]; off += h
+    return acts, head
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_numpy_maze_backward_equals_the_oracle(orc, dtype):
+    """np_maze_backward_from_stored (the stand-in for the oracle at sizes it cannot reach) against the oracle's own
+    loss and gradient on a small maze, to rounding in both precisions -- and, in bf16, clearly worse with the weights
+    left unrounded, so the rounding point is seen."""
+    cfg = W.get("maze_16384", B=24, T=6)
+    cfg["net"]["hidden"] = [48, 40, 32]
+    cfg["net"]["dtype"] = dtype
+    cfg["env"] = dict(cfg["env"], rows=6, cols=6, max_steps=9)
+    o = orc.Oracle(cfg, seed=5)
+    rng = np.random.default_rng(1)
+    o.theta[:] += (0.05 * rng.standard_normal(o.P)).astype(np.float32)       # biases away from zero
+    o.rollout()
+    theta0 = o.theta.copy()
+    acts, head = _stored_forward(o)
+    cells = 36
+    walls = np.unpackbits(o.walls.view(np.uint8), axis=1, bitorder="little")[:, :cells].astype(bool)
+    o.learn()
+    regions, P = PT.param_regions(cfg)
+    loss, g = PT.np_maze_backward_from_stored(cfg, theta0, walls, o.tr_state_i[:-1, :, 0], acts, head, o.tr_action,
+                                              o.adv, o.ret, t_chunk=4)
+    tol = 2e-6                # the oracle's gradient is stored in binary32; in this case no activation rounds differently
+    assert np.abs(loss - o.loss).max() <= tol * np.abs(o.loss).max()
+    worst = PT.assert_regions_close("gradient", g, o.grad, regions, tol)
+    if dtype == "bf16":
+        cfg32 = copy.deepcopy(cfg); cfg32["net"]["dtype"] = "fp32"
+        _, g_unrounded = PT.np_maze_backward_from_stored(cfg32, theta0, walls, o.tr_state_i[:-1, :, 0], acts, head,
+                                                         o.tr_action, o.adv, o.ret, t_chunk=4)
+        assert PT.rel(g_unrounded, o.grad) > 3 * max(PT.rel(g, o.grad), 1e-4)
