@@ -331,3 +331,54 @@ def np_maze_backward_from_stored(cfg, theta, walls, pos, acts, head, action, adv
     g[bh_off:bh_off + NH] = gbh
     loss = np.array([Lp + Lv + Le, Lp, Lv, Le]) / n_all
     return loss, g
+
+
+def np_maze_forward_layers_from_stored(cfg, theta, walls, pos, acts, t_chunk=2):
+    """Every layer of a bf16 maze net's acting forward pass on its own, in binary64 with BLAS products, each from
+    the STORED input of that layer: hidden layer 1 from the observation (wall bits of the env, agent cell pos[t][b],
+    goal at the last cell), hidden layer l from the stored acts[l-2], the heads from the stored last activations --
+    with the rounding points of the bf16 forward pass (weights and layer outputs rounded to bfloat16, biases and
+    heads binary32/64).  Yields (t0, t1, [reference of acts[0], ..., acts[L-1]], reference heads) per block of
+    time steps.  Because every layer starts from what the GPU stored, a difference is that layer's own."""
+    net = cfg["net"]
+    assert net.get("dtype") == "bf16"
+    hid = list(net["hidden"])
+    L = len(hid)
+    T, B = pos.shape
+    cells = walls.shape[1]
+    dims = [3 * cells] + hid
+    th = np.asarray(theta, np.float32)
+    Ws, bs, off = [], [], 0
+    for l in range(L):
+        K, N = dims[l], dims[l + 1]
+        Ws.append(bf16_round_np(th[off:off + K * N]).astype(np.float64).reshape(K, N)); off += K * N
+        bs.append(th[off:off + N].astype(np.float64)); off += N
+    NH = (th.size - off) // (hid[-1] + 1)
+    Wh = bf16_round_np(th[off:off + hid[-1] * NH]).astype(np.float64).reshape(hid[-1], NH); off += hid[-1] * NH
+    bh = th[off:off + NH].astype(np.float64)
+    # the part of layer 1 that does not change within an unroll: bias + wall rows + goal row, per env
+    prefix = bs[0] + walls.astype(np.float64) @ Ws[0][:cells] + Ws[0][2 * cells + cells - 1]
+    for t0 in range(0, T, t_chunk):
+        t1 = min(T, t0 + t_chunk)
+        n = (t1 - t0) * B
+        y = np.tile(prefix, (t1 - t0, 1)) + Ws[0][cells + pos[t0:t1].reshape(n)]
+        refs = [bf16_round_np(np.maximum(y, 0).astype(np.float32))]
+        for l in range(1, L):
+            x = acts[l - 1][t0:t1].reshape(n, hid[l - 1]).astype(np.float64)
+            refs.append(bf16_round_np(np.maximum(x @ Ws[l] + bs[l], 0).astype(np.float32)))
+        heads = acts[L - 1][t0:t1].reshape(n, hid[-1]).astype(np.float64) @ Wh + bh
+        yield t0, t1, [r.reshape(t1 - t0, B, -1) for r in refs], heads.reshape(t1 - t0, B, NH)
+
+
+def assert_bf16_layers_close(name, got, ref):
+    """stored bfloat16 activations against their reference: equal, or one bfloat16 step apart where the two
+    accumulation orders round the sum to different neighbours (a small share of the entries; a sum within rounding
+    of zero may sit on either side of the ReLU).  Returns the share of entries that differ."""
+    got = np.asarray(got, np.float32); ref = np.asarray(ref, np.float32)
+    d = np.abs(got - ref)
+    step = 2.0 ** -7 * np.maximum(np.abs(ref), np.abs(got))          # one step of an 8-bit significand, at most
+    bad = d > step + 1e-6
+    assert not bad.any(), f"{name}: {int(bad.sum())} entries differ by more than one bfloat16 step (worst {d.max():.3e})"
+    share = float((d > 0).mean())
+    assert share <= 0.02, f"{name}: {share:.2%} of the entries differ"
+    return share

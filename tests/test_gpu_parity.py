@@ -546,14 +546,15 @@ def test_full_size_maze_bf16_sampled_envs(gpu, orc):
     _forced_lockstep(gpu, orc, cfg, 0, 2, sel=sel, learn=False)
 
 
-def test_full_size_maze_bf16_update(gpu, orc):
-    """The update of the maze workload at its full size (B=16384, T=32, 768-512-512-512 bf16: 524288 samples), in
+def test_full_size_maze_bf16_every_sample(gpu, orc):
+    """The forward pass and the update of the maze workload at its full size (B=16384, T=32, 768-512-512-512 bf16: 524288 samples), in
     the launch shape the benchmark times.  The oracle would need an hour for it, so the reference is the same
     objective and backward rule written as binary64 matrix products over the forward pass the GPU stored
     (parity.np_maze_backward_from_stored, itself checked against the oracle on small cases by the CPU suite; the
-    stored forward pass is what test_full_size_maze_bf16_sampled_envs compares with the oracle): returns and
-    advantages by the oracle's routine, loss terms, every region of the gradient, then the Adam step replayed in
-    binary64 from the GPU's own gradient."""
+    stored forward pass is compared first, layer by layer at every sample, with binary64 products from each layer's
+    stored input; test_full_size_maze_bf16_sampled_envs replays whole envs on the oracle): returns and advantages by
+    the oracle's routine, loss terms, every region of the gradient, then the Adam step replayed in binary64 from
+    the GPU's own gradient."""
     from oracle import oracle as O
     cfg = W.get("maze_16384")
     net = cfg["net"]
@@ -563,17 +564,28 @@ def test_full_size_maze_bf16_update(gpu, orc):
     g.step()                                     # the compared update starts from non-initial parameters and moments
     g.rollout()
     theta0 = g.get_params()
-    m0, v0, t0 = g.get_opt_state()
+    m0, v0, step0 = g.get_opt_state()
     tr = g.trajectory()
-    say("  trajectory on the host; update on the GPU ...")
+    walls = np.unpackbits(g.get_walls().view(np.uint8), axis=1, bitorder="little").astype(bool)
+    pos = (tr["state_s0"][:-1] & 0xFFFF).astype(np.int64)
+    # the acting kernel's forward pass at EVERY one of the 524288 stored samples, layer by layer from the stored
+    # input of each layer (parity.np_maze_forward_layers_from_stored, checked against the oracle by the CPU suite)
+    say("  trajectory on the host; every layer of every stored sample against binary64 products ...")
+    share = [0.0] * len(tr["act"])
+    head_err = 0.0
+    hscale = float(np.abs(tr["head"]).max())
+    for t0, t1, refs, heads in PT.np_maze_forward_layers_from_stored(cfg, theta0, walls, pos, tr["act"]):
+        for l, r in enumerate(refs):
+            share[l] = max(share[l], PT.assert_bf16_layers_close(f"layer {l + 1}, steps {t0}..{t1 - 1}", tr["act"][l][t0:t1], r))
+        head_err = max(head_err, float(np.abs(heads - tr["head"][t0:t1]).max()) / hscale)
+    assert head_err <= 1e-4, f"head outputs differ by {head_err:.3e} of their scale"
+    say(f"  layers differ in at most {max(share):.4%} of their entries (one bfloat16 step), heads by {head_err:.2e}; update on the GPU ...")
     g.learn()
     assert g.metrics()["nonfinite"] == 0
     ret, adv = O.returns(tr["reward"], tr["done"], tr["value"], f32(net["gamma"]), f32(net["lambda"]))
     tr2 = g.trajectory()
     scale = max(1.0, float(np.abs(ret).max()))
     assert np.abs(tr2["ret"] - ret).max() <= 1e-5 * scale and np.abs(tr2["adv"] - adv).max() <= 1e-5 * scale
-    walls = np.unpackbits(g.get_walls().view(np.uint8), axis=1, bitorder="little").astype(bool)
-    pos = (tr["state_s0"][:-1] & 0xFFFF).astype(np.int64)
     say("  binary64 backward pass on the host ...")
     loss, ref = PT.np_maze_backward_from_stored(cfg, theta0, walls, pos, tr["act"], tr["head"][:-1], tr["action"], adv, ret)
     m = g.metrics()
@@ -588,9 +600,9 @@ def test_full_size_maze_bf16_update(gpu, orc):
     worst = PT.assert_regions_close("gradient", g_gpu, ref, regions, TOL_BF16 / 20)
     # Adam on its own: binary64 Adam (the oracle's routine) on the GPU's gradient from the state before the update
     th_x, m_x, v_x = theta0.copy(), m0.astype(np.float64), v0.astype(np.float64)
-    O.adam(th_x, g_gpu, m_x, v_x, t0 + 1, f32(net["lr"]), f32(net["beta1"]), f32(net["beta2"]), f32(net["eps"]))
+    O.adam(th_x, g_gpu, m_x, v_x, step0 + 1, f32(net["lr"]), f32(net["beta1"]), f32(net["beta2"]), f32(net["eps"]))
     gm, gv, gt = g.get_opt_state()
-    assert gt == t0 + 1
+    assert gt == step0 + 1
     th_gpu = g.get_params()
     assert np.abs(th_gpu.astype(np.float64) - th_x).max() <= 2.0 ** -22 * np.abs(th_x).max() + 1e-4 * net["lr"]
     assert np.abs(gm - m_x).max() <= 1e-6 * np.abs(m_x).max() and np.abs(gv - v_x).max() <= 1e-6 * np.abs(v_x).max()

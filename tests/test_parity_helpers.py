@@ -109,3 +109,33 @@ def test_numpy_maze_backward_equals_the_oracle(orc, dtype):
         _, g_unrounded = PT.np_maze_backward_from_stored(cfg32, theta0, walls, o.tr_state_i[:-1, :, 0], acts, head,
                                                          o.tr_action, o.adv, o.ret, t_chunk=4)
         assert PT.rel(g_unrounded, o.grad) > 3 * max(PT.rel(g, o.grad), 1e-4)
+
+
+def test_numpy_maze_layer_forward_equals_the_oracle(orc):
+    """np_maze_forward_layers_from_stored against the oracle's own bf16 acting forward pass on a small maze: fed with
+    the oracle's stored activations, every layer's reference reproduces the next stored activation and the heads."""
+    cfg = W.get("maze_16384", B=24, T=6)
+    cfg["net"]["hidden"] = [48, 40, 32]
+    cfg["env"] = dict(cfg["env"], rows=6, cols=6, max_steps=9)
+    o = orc.Oracle(cfg, seed=8)
+    rng = np.random.default_rng(2)
+    o.theta[:] += (0.05 * rng.standard_normal(o.P)).astype(np.float32)
+    o.rollout()
+    acts, head = _stored_forward(o)
+    walls = np.unpackbits(o.walls.view(np.uint8), axis=1, bitorder="little")[:, :36].astype(bool)
+    seen = 0
+    for t0, t1, refs, heads in PT.np_maze_forward_layers_from_stored(cfg, o.theta, walls, o.tr_state_i[:-1, :, 0], acts, t_chunk=4):
+        for l, r in enumerate(refs):
+            assert PT.assert_bf16_layers_close(f"layer {l + 1}", acts[l][t0:t1], r) <= 0.002
+        assert np.abs(heads - head[t0:t1]).max() <= 1e-5 * np.abs(head).max()
+        seen += t1 - t0
+    assert seen == o.T
+    # a planted mistake is seen: one weight of the second layer changed by a bfloat16 step
+    th = o.theta.copy()
+    regions, _ = PT.param_regions(cfg)
+    w2 = dict(regions)["W2"]
+    th[w2.start + 5] *= 1.02
+    with pytest.raises(AssertionError):
+        for t0, t1, refs, heads in PT.np_maze_forward_layers_from_stored(cfg, th, walls, o.tr_state_i[:-1, :, 0], acts, t_chunk=4):
+            for l, r in enumerate(refs):
+                PT.assert_bf16_layers_close(f"layer {l + 1}", acts[l][t0:t1], r)
