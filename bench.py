@@ -53,6 +53,51 @@ def measured_traffic(workload):
     return out, commit
 
 
+def measured_issue_utilisation(workload):
+    """VALU issue utilisation per bench.py kernel, read from profiles/<workload>_shader_counters.md (rocprofv3 --pmc
+    SQ_ACTIVE_INST_VALU over SQ_BUSY_CYCLES; the file names the commands and the commit) through the kernel-name
+    mapping of profiles/<workload>_hbm_traffic.md.  For kernels bound by plain vector arithmetic this, not a flop
+    count, says how busy the vector units were.  Returns ({kernel: utilisation}, commit)."""
+    out, commit, by_rocprof = {}, None, {}
+    try:
+        lines = open(os.path.join(ROOT, "profiles", f"{workload}_shader_counters.md")).read().splitlines()
+        names = open(os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")).read().splitlines()
+    except OSError:
+        return out, commit
+    col = None
+    for line in lines:
+        if line.lower().startswith("measured at commit"):
+            commit = line.split()[-1].strip("`. ")
+        if line.startswith("| kernel"):
+            heads = [c.strip() for c in line.strip("|").split("|")]
+            col = heads.index("VALU issue utilisation") if "VALU issue utilisation" in heads else None
+        elif col is not None and line.startswith("| `"):
+            cells = [c.strip() for c in line.strip("|").split("|")]
+            try:
+                by_rocprof[cells[0].strip("`")] = float(cells[col])
+            except ValueError:
+                pass
+    in_table = False
+    for line in names:
+        if line.startswith("## "):
+            in_table = "per bench.py kernel" in line
+            continue
+        if in_table and line.startswith("| `"):
+            cells = [c.strip() for c in line.strip("|").split("|")]
+            # a listed name matches the profiler's up to its template arguments ("gemm_nt_bf16_res<512, true>" as listed
+            # must not also match "...<512, false>"): compare the part the listing gives, from the start
+            wanted = []
+            for w in cells[1].split(", "):
+                if wanted and "<" in wanted[-1] and ">" not in wanted[-1]:
+                    wanted[-1] += ", " + w
+                else:
+                    wanted.append(w)
+            vals = [v for k, v in by_rocprof.items() if any(k.split("::")[-1].startswith(w) for w in wanted)]
+            if vals:
+                out[cells[0].strip("`")] = round(sum(vals) / len(vals), 3)
+    return out, commit
+
+
 def kernel_models(cfg, P, launched=()):
     """Algorithmic work per launch of each kernel: (bound, amount, unit-peak, unit).  `launched`: the kernel names the
     instrumented pass saw (which products a fused kernel took over depends on the plan)."""
@@ -247,6 +292,10 @@ def measure(binding, torch, name, cfg, steps, warmup, halves=False, valu_gemm=Fa
             entry.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit,
                           "frac": round(ach / peak, 4)})
         per_kernel[kname] = entry
+    issue, issue_commit = measured_issue_utilisation(name)
+    for kname, entry in per_kernel.items():
+        if entry.get("bound") == "alu" and kname in issue:
+            entry["valu_issue_utilisation"] = issue[kname]
     dominant = max(per_kernel, key=lambda k: per_kernel[k]["us_per_step"])
     d = per_kernel[dominant]
     traffic, commit = measured_traffic(name)
@@ -255,6 +304,11 @@ def measure(binding, torch, name, cfg, steps, warmup, halves=False, valu_gemm=Fa
                        "traffic": traffic.get(dominant), "traffic_unit": "MB per launch",
                        "traffic_source": (f"profiles/{name}_hbm_traffic.md" + (f" (measured at commit {commit})" if commit else "")) if dominant in traffic else None,
                        "avg_launch_us": d["avg_us"]}
+    if "valu_issue_utilisation" in d:
+        # a kernel bound by plain vector arithmetic: the flop fraction above counts only the network's multiply-adds
+        # (not Philox, exponentials, sampling, index arithmetic); the issue counters say how busy the vector units were
+        res["roofline"]["valu_issue_utilisation"] = d["valu_issue_utilisation"]
+        res["roofline"]["valu_issue_source"] = f"profiles/{name}_shader_counters.md" + (f" (measured at commit {issue_commit})" if issue_commit else "")
     res["kernels"] = per_kernel
     res["plan"] = g.plan()
     return g, res
@@ -411,6 +465,7 @@ def main():
                            "dominant_kernel": rr["roofline"]["kernel"], "bound": rr["roofline"]["bound"],
                            "frac": rr["roofline"]["frac"], "avg_launch_us": rr["roofline"]["avg_launch_us"],
                            "traffic": rr["roofline"]["traffic"],
+                           **({"valu_issue_utilisation": rr["roofline"]["valu_issue_utilisation"]} if "valu_issue_utilisation" in rr["roofline"] else {}),
                            "kernels_us_per_step": {kn: kv["us_per_step"] for kn, kv in rr["kernels"].items()}}
         out["workloads"] = sweep
     if not args.no_cpu_baseline:
