@@ -421,7 +421,7 @@ extern "C" int32_t anakin_create(anakin_t** out, const anakin_env_cfg* env, cons
     h->n_updates = 1; h->chunks_sequential = 0;
     h->TM = rollout_pick_tile(ns, B);
     h->TM_mfma = rollout_pick_tile_mfma(ns, B);
-    h->TM_res = rollout_resident_tile(ns, B);
+    h->TM_res = rollout_resident_tile(ns, ed.kind, B);
     h->bf16_path = rollout_bf16_ok(ns, ed, B) ? 1 : 0;
 
     auto fail = [&](int code) { g_create_error = h->err; delete h; return code; };

@@ -252,7 +252,7 @@ inline int first_fused_splits(const NetShape& n, int env_kind, int M, int tn_spl
 }
 int rollout_pick_tile(const NetShape& net, int B);
 int rollout_pick_tile_mfma(const NetShape& net, int B);
-int rollout_resident_tile(const NetShape& net, int B);
+int rollout_resident_tile(const NetShape& net, int env_kind, int B);
 size_t rollout_lds_bytes(const NetShape& net, const EnvDims& env, int TM, int* ldx);
 
 }  // namespace ank

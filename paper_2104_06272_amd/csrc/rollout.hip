@@ -1087,12 +1087,16 @@ int rollout_resident_width(const NetShape& net)
     const int w = net.dims[1];
     return (w == 64 || w == 128 || w == 256) ? w : 0;
 }
-int rollout_resident_tile(const NetShape& net, int B)
+int rollout_resident_tile(const NetShape& net, int env_kind, int B)
 {
     const int w = rollout_resident_width(net);
     if (!w) return 0;
-    if (w >= 128 && B % 32 == 0 && B / 32 >= 256) return 32;
-    return 16;
+    const int tm = (w >= 128 && B % 32 == 0 && B / 32 >= 256) ? 32 : 16;
+    // besides the tile's own buffers the kernel keeps both bias vectors and (Catch, pendulum) the whole first-layer
+    // matrix in LDS: a board too large for that runs on the streaming kernels instead
+    size_t lds = rollout_lds_bytes(net, EnvDims{}, tm, nullptr) + (size_t)2 * w * 4;
+    if (env_kind != ENV_MAZE) lds += (size_t)net.dims[0] * w * 4;
+    return lds <= 160 * 1024 ? tm : 0;
 }
 
 // can the hidden-to-hidden layers run on the matrix cores with TM envs per workgroup?
@@ -1108,7 +1112,8 @@ static bool mfma_tile_ok(const NetShape& net, int TM)
     }
     int hmax = 0;
     for (int l = 1; l <= net.L; ++l) hmax = net.dims[l] > hmax ? net.dims[l] : hmax;
-    return (size_t)2 * TM * (hmax + 4) * 4 <= 128 * 1024;           // two activation buffers in LDS
+    if ((size_t)2 * TM * (hmax + 4) * 4 > 128 * 1024) return false; // two activation buffers in LDS
+    return rollout_lds_bytes(net, EnvDims{}, TM, nullptr) <= 160 * 1024;   // ... and everything else the kernel keeps there
 }
 
 int rollout_pick_tile_mfma(const NetShape& net, int B)
@@ -1122,6 +1127,16 @@ int rollout_pick_tile_mfma(const NetShape& net, int B)
     return best;
 }
 
+size_t rollout_lds_bytes(const NetShape& net, const EnvDims&, int TM, int* ldx_out)
+{
+    int hmax = 0;
+    for (int l = 1; l <= net.L; ++l) hmax = net.dims[l] > hmax ? net.dims[l] : hmax;
+    const int ldx = hmax + 4;
+    if (ldx_out) *ldx_out = ldx;
+    size_t words = (size_t)2 * TM * ldx + (size_t)8 * (net.dims[net.L] + 4) + 8 + (size_t)TM * net.NHP + (size_t)TM * (OBS_WORDS + 4);
+    return words * 4;
+}
+
 int rollout_pick_tile(const NetShape& net, int B)
 {
     int lo = 16, hi = 256;
@@ -1132,27 +1147,20 @@ int rollout_pick_tile(const NetShape& net, int B)
         if (mn > lo) lo = mn;
         if (mx < hi) hi = mx;
     }
+    // a tile also has to fit LDS: two activation buffers of the widest layer plus the transposed head matrix (a
+    // 1024-wide last layer with 16 envs is 2 KB over; the caller then gets "no rollout tile fits" at create)
+    auto fits = [&](int tm) { return tm >= lo && tm <= hi && B % tm == 0 && rollout_lds_bytes(net, EnvDims{}, tm, nullptr) <= 160 * 1024; };   // what one workgroup can be given on gfx950
     int best = 0;
     for (int tm = 16; tm <= 256; tm *= 2) {
-        if (tm < lo || tm > hi || B % tm) continue;
+        if (!fits(tm)) continue;
         if (!best) best = tm;                            // smallest valid tile
         if (B / tm >= 2048) best = tm;                   // largest tile that still leaves eight workgroups per CU
     }
     if (best && B / best < 256) {                        // small batches: fill the chip first
         for (int tm = 16; tm <= 256; tm *= 2)
-            if (tm >= lo && tm <= hi && B % tm == 0 && B / tm >= 256) best = tm;
+            if (fits(tm) && B / tm >= 256) best = tm;
     }
     return best;
-}
-
-size_t rollout_lds_bytes(const NetShape& net, const EnvDims&, int TM, int* ldx_out)
-{
-    int hmax = 0;
-    for (int l = 1; l <= net.L; ++l) hmax = net.dims[l] > hmax ? net.dims[l] : hmax;
-    const int ldx = hmax + 4;
-    if (ldx_out) *ldx_out = ldx;
-    size_t words = (size_t)2 * TM * ldx + (size_t)8 * (net.dims[net.L] + 4) + 8 + (size_t)TM * net.NHP + (size_t)TM * (OBS_WORDS + 4);
-    return words * 4;
 }
 
 template <int ENV, bool BF, bool MF, bool REPLAY>

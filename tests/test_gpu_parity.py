@@ -227,6 +227,55 @@ def test_maze_goal_and_step_cap_inside_the_unroll(gpu, orc, dtype, hidden):
     g.close()
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_seeded_shape_sweep(gpu, orc, seed):
+    """A seeded sample of the shapes the library accepts -- one to four hidden layers of 32..1024 units in any order,
+    batch sizes that are not powers of two, one-step unrolls, boards of other sizes -- each two updates in lockstep
+    with the oracle.  Shapes without an acting tile (a 32-wide layer with B not a multiple of 32, a 1024-wide last
+    layer) are refused at create with ANAKIN_E_BAD_CONFIG and counted; nothing else may be refused."""
+    rng = np.random.default_rng(seed)
+    base = {"catch": "catch_small", "pendulum": "pendulum_8192", "maze": "maze_16384"}
+    ran = refused = 0
+    for c in range(16):
+        kind = ["catch", "pendulum", "maze"][c % 3]
+        L = int(rng.integers(1, 5))
+        widths = [int(rng.choice([32, 64, 128, 256, 512] if L > 2 else [32, 64, 128, 256, 512, 1024])) for _ in range(L)]
+        B = int(rng.choice([16, 48, 112, 272]))
+        T = int(rng.choice([1, 3, 6, 11]))
+        over = {}
+        if kind == "maze":
+            r, co = [(4, 4), (8, 8), (16, 16), (5, 7)][int(rng.integers(4))]
+            over = dict(rows=r, cols=co, max_steps=int(rng.integers(2, 12)))
+        elif kind == "pendulum":
+            over = dict(max_steps=int(rng.integers(2, 12)))
+        else:
+            r, co = [(10, 5), (4, 3), (6, 9)][int(rng.integers(3))]
+            over = dict(rows=r, cols=co)
+        cfg = variant(base[kind], hidden=widths, B=B, T=T, dtype="fp32", **over)
+        s = int(rng.integers(1000))
+        say(f"[shape sweep {seed}.{c}] {kind} {over} hidden={widths} B={B} T={T} seed={s}")
+        try:
+            g = gpu.Anakin(cfg, seed=s)
+        except gpu.AnakinError as e:
+            assert e.code == gpu.E_BAD_CONFIG and "no rollout tile" in str(e), str(e)
+            assert (32 in widths and (B % 32 or 1024 in widths)) or widths[-1] == 1024, "refused without a reason this test knows"
+            refused += 1
+            continue
+        o = orc.Oracle(cfg, seed=s)
+        PT.assert_same_init(g, o, kind)
+        for u in range(2):
+            PT.sync_oracle_from_gpu(g, o)
+            g.rollout(); o.rollout()
+            PT.assert_rollout_equal(g, o, kind)
+            PT.assert_final_state_equal(g, o, kind)
+            g.learn(); o.learn()
+            PT.assert_learn_close(g, o, TOL_F32)
+        g.close()
+        ran += 1
+    say(f"  {ran} shapes in lockstep, {refused} refused at create")
+    assert ran >= 8
+
+
 def test_catch_small_100_updates_lockstep(gpu, orc):
     """The small Catch workload for its full 100 updates, parameter-synchronised."""
     cfg = W.get("catch_small")
@@ -444,6 +493,55 @@ def test_bf16_matrix_core_goal_and_step_cap(gpu, orc):
     goals = int((o.tr_reward == 1.0).sum()); caps = int(o.tr_done.sum()) - goals
     say(f"  {goals} goals, {caps} step caps")
     assert goals >= 10 and caps >= 10, (goals, caps)
+
+
+def test_seeded_shape_sweep_bf16_and_boards(gpu, orc):
+    """More shapes off the benchmark's grid: Catch boards of other sizes (up to 32 x 32: the first-layer matrix no
+    longer fits LDS and the acting kernel that keeps it there has to step aside), and a seeded sample of bf16 nets
+    of one to three layers on all three envs -- on the matrix-core path where the plan takes it (logit-forced
+    protocol), on the canonical path elsewhere (bit-exact unrolls)."""
+    for (r, c, hid, B, T) in [(20, 20, [256, 256], 64, 4), (32, 32, [64, 64], 32, 3), (30, 7, [128, 128], 64, 5), (25, 25, [64], 64, 4)]:
+        cfg = variant("catch_small", hidden=hid, B=B, T=T, rows=r, cols=c)
+        say(f"[board] catch {r}x{c} hidden={hid} B={B} T={T}")
+        g = gpu.Anakin(cfg, seed=3); o = orc.Oracle(cfg, seed=3)
+        PT.assert_same_init(g, o, "catch")
+        for u in range(2):
+            PT.sync_oracle_from_gpu(g, o)
+            g.rollout(); o.rollout()
+            PT.assert_rollout_equal(g, o, "catch")
+            g.learn(); o.learn()
+            PT.assert_learn_close(g, o, TOL_F32)
+        g.close()
+    rng = np.random.default_rng(5)
+    base = {"catch": "catch_small", "pendulum": "pendulum_8192", "maze": "maze_16384"}
+    on_matrix_cores = 0
+    for i in range(12):
+        kind = ["maze", "catch", "pendulum"][i % 3]
+        widths = [int(rng.choice([64, 128, 256, 512])) for _ in range(int(rng.integers(1, 4)))]
+        B, T = int(rng.choice([64, 128, 192])), int(rng.choice([2, 5, 8]))
+        over = dict(max_steps=int(rng.integers(2, 9))) if kind != "catch" else {}
+        if kind == "maze":
+            r, co = [(8, 8), (16, 16), (4, 4)][int(rng.integers(3))]
+            over.update(rows=r, cols=co)
+        cfg = variant(base[kind], hidden=widths, B=B, T=T, dtype="bf16", **over)
+        s = int(rng.integers(100))
+        g = gpu.Anakin(cfg, seed=s)
+        matrix = g.plan()["bf16_matrix_path"]
+        g.close()
+        say(f"[bf16 shape {i}] {kind} {over} hidden={widths} B={B} T={T} seed={s} matrix cores: {matrix}")
+        if matrix:
+            on_matrix_cores += 1
+            _forced_lockstep(gpu, orc, cfg, s, 2)
+        else:
+            g = gpu.Anakin(cfg, seed=s); o = orc.Oracle(cfg, seed=s)
+            for u in range(2):
+                PT.sync_oracle_from_gpu(g, o)
+                g.rollout(); o.rollout()
+                PT.assert_rollout_equal(g, o, kind)
+                g.learn(); o.learn()
+                PT.assert_learn_close(g, o, TOL_BF16)
+            g.close()
+    assert 3 <= on_matrix_cores <= 10
 
 
 def _steady_state_update(gpu, orc, cfg, check_plan, n_head_envs):

@@ -50,6 +50,11 @@ def test_workspace_sizes(lib):
     lambda c: c["net"].update(lr=0.0),
     lambda c: c["env"].update(rows=1),
     lambda c: c.update(env=dict(kind="maze", rows=32, cols=32, max_steps=10, p_wall=0.2)),
+    # no acting tile fits: a 32-wide layer needs tiles of 32 envs (B = 48 is not a multiple), and a 1024-wide last
+    # layer with the only tile it allows (16 envs) is 2 KB over the LDS of a workgroup
+    lambda c: (c.update(B=48), c["net"].update(hidden=[32, 64])),
+    lambda c: (c.update(B=16), c["net"].update(hidden=[1024])),
+    lambda c: (c.update(B=16), c["net"].update(hidden=[1024, 1024])),
 ])
 def test_bad_configs_are_rejected_on_the_host(lib, mutate):
     cfg = W.get("catch_small")
