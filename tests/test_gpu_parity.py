@@ -972,6 +972,93 @@ def test_pathwise_rejections(gpu):
     p.close()
 
 
+def test_seeded_sweep_of_the_widened_calls(gpu, orc):
+    """The calls beyond the fused step on a seeded sample of shapes (fp32, one to three layers of 64..512 units, batch
+    sizes that are not powers of two, short unrolls): several updates per unroll in both readings, decoupled steps,
+    the pathwise gradient (on the shapes it takes), and the static-scratch update against the workspace one."""
+    rng = np.random.default_rng(0)
+    base = {"catch": "catch_small", "pendulum": "pendulum_8192", "maze": "maze_16384"}
+
+    def shape(kind):
+        widths = [int(rng.choice([64, 128, 256, 512])) for _ in range(int(rng.integers(1, 4)))]
+        B = int(rng.choice([16, 48, 112, 256]))
+        over = {}
+        if kind == "maze":
+            r, co = [(4, 4), (8, 8), (16, 16)][int(rng.integers(3))]
+            over = dict(rows=r, cols=co, max_steps=int(rng.integers(2, 12)))
+        elif kind == "pendulum":
+            over = dict(max_steps=int(rng.integers(2, 12)))
+        return widths, B, over
+
+    for i in range(6):
+        kind = ["catch", "pendulum", "maze"][i % 3]
+        widths, B, over = shape(kind)
+        N = int(rng.choice([2, 3, 4])); T = N * int(rng.integers(1, 4))
+        seq = bool(i % 2)
+        cfg = _fast_lr(variant(base[kind], hidden=widths, B=B, T=T, dtype="fp32", **over), 3e-3)
+        s = int(rng.integers(1000))
+        say(f"[sweep: n updates {i}] {kind} {over} hidden={widths} B={B} T={T} N={N} sequential={seq} seed={s}")
+        g = gpu.Anakin(cfg, seed=s); o = orc.Oracle(cfg, seed=s)
+        g.step()                  # Adam's first steps from zero moments are +-lr whatever the gradient's size: with only
+        g.step()                  # the last chunk's gradient visible, compare from moments that have settled
+        o.global_step = g.global_step
+        si, sf = g.get_env_state(); o.state_i[:] = si; o.state_f[:] = sf
+        g.set_updates_per_unroll(N, sequential=seq)
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout(); o.rollout()
+        PT.assert_rollout_equal(g, o, kind)
+        g.learn(); o.learn_n(N, sequential=seq)
+        PT.assert_learn_close(g, o, TOL_F32, n_updates=N)
+        g.close()
+    for i in range(6):
+        kind = ["catch", "pendulum", "maze"][i % 3]
+        widths, B, over = shape(kind)
+        T = int(rng.choice([2, 5, 9]))
+        cfg = _fast_lr(variant(base[kind], hidden=widths, B=B, T=T, dtype="fp32", **over), 3e-3)
+        s = int(rng.integers(1000))
+        say(f"[sweep: decoupled {i}] {kind} {over} hidden={widths} B={B} T={T} seed={s}")
+        g = gpu.Anakin(cfg, seed=s); o = orc.Oracle(cfg, seed=s)
+        for k in range(3):
+            PT.sync_oracle_from_gpu(g, o)
+            learned_on = (o.tr_reward.copy(), o.tr_done.copy())
+            g.step_decoupled(); o.step_decoupled()
+            tr = PT.assert_rollout_equal(g, o, kind)
+            PT.assert_final_state_equal(g, o, kind)
+            if k:
+                PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=learned_on)
+        g.close()
+    for i in range(4):
+        w = int(rng.choice([64, 128, 256]))
+        B, T = int(rng.choice([16, 48, 112, 256])), int(rng.choice([2, 5, 9]))
+        cfg = variant("pendulum_8192", hidden=[w, w], B=B, T=T, max_steps=int(rng.integers(2, 12)))
+        s = int(rng.integers(1000))
+        say(f"[sweep: pathwise {i}] hidden={[w, w]} B={B} T={T} max_steps={cfg['env']['max_steps']} seed={s}")
+        g = gpu.Anakin(cfg, seed=s); o = orc.Oracle(cfg, seed=s)
+        g.set_policy_gradient(gpu.PG_PATHWISE)
+        for u in range(2):
+            PT.sync_oracle_from_gpu(g, o)
+            g.rollout(); o.rollout()
+            PT.assert_rollout_equal(g, o, "pendulum")
+            rew, done = o.tr_reward.copy(), o.tr_done.copy()
+            g.learn(); o.learn_pathwise()
+            tr = g.trajectory(); tr["adv"] = np.zeros_like(o.adv)
+            PT.assert_learn_close(g, o, TOL_F32, tr_after=tr, learned_on=(rew, done))
+        g.close()
+    for i in range(6):
+        kind = ["catch", "pendulum", "maze"][i % 3]
+        widths, B, over = shape(kind)
+        T = int(rng.choice([2, 5, 9]))
+        dt = "bf16" if i % 2 else "fp32"
+        cfg = variant(base[kind], hidden=widths, B=max(B, 64) if dt == "bf16" else B, T=T, dtype=dt, **over)
+        s = int(rng.integers(1000))
+        say(f"[sweep: static scratch {i}] {kind} {over} hidden={widths} B={cfg['B']} T={T} {dt} seed={s}")
+        a = gpu.Anakin(cfg, seed=s); b = gpu.Anakin(cfg, seed=s)
+        for _ in range(2):
+            a.rollout(); a.learn(); b.rollout(); b.learn_static()
+            assert np.array_equal(a.get_grads(), b.get_grads()) and np.array_equal(a.get_params(), b.get_params())
+        a.close(); b.close()
+
+
 def test_determinism_and_resume(gpu):
     """Same seed twice gives the same bytes; a byte copy of the workspace plus the two host counters
     resumes bit-exactly (explicit, device-resident state; counter-based RNG)."""
