@@ -359,6 +359,39 @@ def test_full_size_rollout_sampled_envs(gpu, orc, name):
     g.close()
 
 
+@pytest.mark.parametrize("name,kw,forced", [
+    ("catch_262144", dict(B=1 << 20), False),          # four times the tiny-net workload: a million envs
+    ("catch_4096", dict(B=65536), False),              # sixteen times the headline batch
+    ("maze_16384", dict(B=32768), True),               # twice the maze batch (bf16 matrix-core path)
+])
+def test_batches_larger_than_the_benchmark(gpu, orc, name, kw, forced):
+    """Beyond the benchmark's sizes: two whole steps, a seeded sample of envs replayed by the oracle (bit-exact; the
+    bf16 matrix-core path logit-forced), returns and advantages of every sample against the oracle's routine, and a
+    finite update."""
+    cfg = W.get(name, **kw)
+    kind, B = cfg["env"]["kind"], cfg["B"]
+    say(f"[large batch] {name} B={B} T={cfg['T']} workspace {gpu.workspace_bytes(cfg) / 2 ** 30:.1f} GiB")
+    g = gpu.Anakin(cfg, seed=1); o = orc.Oracle(cfg, seed=1)
+    rng = np.random.default_rng(1)
+    sel = np.unique(np.concatenate([[0, 63, 64, B - 1, B - 64, B // 2], rng.integers(0, B, 10)])).astype(np.int32)
+    for u in range(2):
+        PT.sync_oracle_from_gpu(g, o)
+        g.rollout()
+        tr = g.trajectory()
+        o.rollout(forced_head=tr["head"] if forced else None, sel=sel)
+        PT.assert_rollout_equal(g, o, kind, sel=sel, forced=forced)
+        PT.assert_final_state_equal(g, o, kind, sel=sel)
+        g.learn()
+        m = g.metrics()
+        assert m["nonfinite"] == 0 and m["episodes"] == int(tr["done"].sum())
+        tr2 = g.trajectory()
+        ret_o, adv_o = orc.returns(tr["reward"], tr["done"], tr["value"], cfg["net"]["gamma"], cfg["net"]["lambda"])
+        assert np.abs(tr2["ret"] - ret_o).max() <= 1e-5 * max(1.0, np.abs(ret_o).max())
+        assert np.abs(tr2["adv"] - adv_o).max() <= 1e-5 * max(1.0, np.abs(ret_o).max())
+        del tr, tr2
+    g.close()
+
+
 def test_full_size_headline_update(gpu, orc):
     """The headline workload (Catch, B=4096, T=20, MLP 50-256-256) at full size, one whole step in lockstep:
     every env of the unroll bit-exact, then loss, gradient, parameters and Adam moments of the update in the
